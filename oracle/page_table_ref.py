@@ -1,0 +1,280 @@
+"""Reference model of the tree page table and of the per-launch plan -- TEST INFRASTRUCTURE.
+
+A dictionary-and-list model, written independently of the C++ library, of the
+integer side of the hot path: which physical pages hold which node's tokens,
+what pruning gives back, and how a set of requested nodes is flattened into
+root-to-node page lists, shared-prefix groups, private suffixes, split chunks
+and the partial-result slots the merge step reads.  Page lists, free lists and
+plans must match the library bit for bit, so the rules are written out here.
+
+Tree (paper Sec. 2.1: a node is the state reached by one step, i.e. a run of
+tokens; Alg. 2: children are added for primary and speculative expansions;
+Sec. 4.2: a mis-speculated BFS branch is terminated at once):
+  * node ids are dense, follow creation order and are never reused;
+  * a node's tokens fill pages of `page_size` slots in order; only its last page
+    may be partial; a child never continues its parent's last page, so a page
+    belongs to exactly one node;
+  * tokens may be appended only to a node without live children.
+
+Allocator: a stack.  Initially page free_order[0] is on top, then free_order[1]
+and so on (ascending ids if no order is given).  An append pops one page at a
+time in token order; an append that does not fit changes nothing.  Prune visits
+the subtree in pre-order (children in creation order) and pushes each visited
+node's pages in run order.
+
+Plan for requested nodes leaves[0..L) with q_lens (caller order):
+  * query tokens are numbered 0..NQ) leaf-major; query token (leaf, i) sees
+    limit = T - q_len + 1 + i path positions;
+  * live[u] = number of requested nodes in u's subtree (u included);
+  * a GROUP is a node on a requested path with live >= 2 and at least one token;
+    groups are listed by ascending node id; a group's rows are the query tokens
+    of all requested nodes below it, in caller order;
+  * the SUFFIX of requested node l is the maximal tail of its path with
+    live == 1, root side first, empty nodes skipped; it may be empty;
+  * a segment (group or suffix) of n pages is cut into c = ceil(n / chunk_pages)
+    chunks, chunk j covering pages [j*n // c, (j+1)*n // c);
+  * TASKS: one per chunk, all group chunks first (group order, chunk order), then
+    suffix chunks (caller order, chunk order).  A task owns
+    rows * Hkv partial slots starting at pbase (running sum in task order), where
+    rows = (number of query tokens of its segment) * (Hq / Hkv); the slot of
+    (kv head g, local query token r, head-in-group hh) is
+    pbase + g * rows + r * G + hh;
+  * a task is flagged MASKED (flag bit 0) if one of its pages is partial or if
+    some row's limit is smaller than the path position that follows its last token;
+  * the merge list of a query token holds, in task order, for every task that
+    has it as a row: base = pbase + r * G and hstride = rows.
+"""
+
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+NO_NODE = -1
+
+
+class OutOfPages(Exception):
+    pass
+
+
+class PageTableRef:
+    def __init__(self, num_pages: int, page_size: int = 16,
+                 free_order: Optional[Sequence[int]] = None):
+        self.P = page_size
+        self.num_pages = num_pages
+        order = list(range(num_pages)) if free_order is None else list(free_order)
+        assert sorted(order) == list(range(num_pages))
+        self.free: List[int] = order[::-1]            # stack: top is the END of the list
+        self.parent: List[int] = []
+        self.children: List[List[int]] = []
+        self.alive: List[bool] = []
+        self.tokens: List[int] = []
+        self.pages: List[List[int]] = []
+
+    # ---------------------------------------------------------------- mutation
+    def _check(self, u: int) -> None:
+        if not (0 <= u < len(self.parent)) or not self.alive[u]:
+            raise KeyError(u)
+
+    def fork(self, parent: int, n: int) -> List[int]:
+        if parent != NO_NODE:
+            self._check(parent)
+        ids = []
+        for _ in range(n):
+            u = len(self.parent)
+            self.parent.append(parent)
+            self.children.append([])
+            self.alive.append(True)
+            self.tokens.append(0)
+            self.pages.append([])
+            if parent != NO_NODE:
+                self.children[parent].append(u)
+            ids.append(u)
+        return ids
+
+    def has_live_children(self, u: int) -> bool:
+        return any(self.alive[c] for c in self.children[u])
+
+    def append(self, u: int, n_tokens: int) -> List[int]:
+        """Returns the pages newly started by this append."""
+        self._check(u)
+        if self.has_live_children(u):
+            raise ValueError("not a leaf")
+        need = -(-(self.tokens[u] + n_tokens) // self.P) - len(self.pages[u])
+        if need > len(self.free):
+            raise OutOfPages()
+        new = [self.free.pop() for _ in range(need)]
+        self.pages[u].extend(new)
+        self.tokens[u] += n_tokens
+        return new
+
+    def prune(self, u: int) -> None:
+        self._check(u)
+        stack = [u]
+        while stack:                                   # pre-order, children in creation order
+            w = stack.pop()
+            if not self.alive[w]:
+                continue
+            self.alive[w] = False
+            for p in self.pages[w]:
+                self.free.append(p)
+            self.pages[w] = []
+            stack.extend(reversed(self.children[w]))
+
+    # ---------------------------------------------------------------- queries
+    def stats(self):
+        live = sum(self.alive)
+        used = sum(len(p) for p in self.pages)
+        return live, used, len(self.free)
+
+    def free_list(self) -> List[int]:
+        """Free pages, next page to be handed out first."""
+        return self.free[::-1]
+
+    def path(self, u: int) -> List[int]:
+        self._check(u)
+        p = []
+        while u != NO_NODE:
+            p.append(u)
+            u = self.parent[u]
+        return p[::-1]
+
+    def node_page_valid(self, u: int):
+        n = self.tokens[u]
+        return [min(self.P, n - i * self.P) for i in range(len(self.pages[u]))]
+
+    def path_pages(self, u: int):
+        pages, valid = [], []
+        for w in self.path(u):
+            pages.extend(self.pages[w])
+            valid.extend(self.node_page_valid(w))
+        return pages, valid
+
+    # ---------------------------------------------------------------- the plan
+    def plan(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
+             num_q_heads: int, num_kv_heads: int,
+             prefix_chunk_pages: int, suffix_chunk_pages: int) -> Dict[str, list]:
+        L = len(leaves)
+        q_lens = [1] * L if q_lens is None else list(q_lens)
+        G = num_q_heads // num_kv_heads
+        P = self.P
+        paths = [self.path(u) for u in leaves]
+
+        # root-to-node CSR
+        leaf_indptr, leaf_pages, leaf_valid = [0], [], []
+        for u in leaves:
+            pg, va = self.path_pages(u)
+            leaf_pages += pg
+            leaf_valid += va
+            leaf_indptr.append(len(leaf_pages))
+
+        # query tokens and their visible lengths
+        qoff, qt_limit = [], []
+        for path, ql in zip(paths, q_lens):
+            T = sum(self.tokens[w] for w in path)
+            if ql < 1 or ql > T:
+                raise ValueError("empty path or q_len > path length")
+            qoff.append(len(qt_limit))
+            qt_limit += [T - ql + 1 + i for i in range(ql)]
+        NQ = len(qt_limit)
+
+        live: Dict[int, int] = {}
+        for path in paths:
+            for w in path:
+                live[w] = live.get(w, 0) + 1
+
+        # path position of each node's first token (same for every path through it)
+        pos0: Dict[int, int] = {}
+        for path in paths:
+            t = 0
+            for w in path:
+                pos0[w] = t
+                t += self.tokens[w]
+
+        group_nodes = sorted(w for w in live if live[w] >= 2 and self.tokens[w] > 0)
+        gindex = {w: i for i, w in enumerate(group_nodes)}
+        group_rows: List[List[int]] = [[] for _ in group_nodes]
+        for li, (path, ql) in enumerate(zip(paths, q_lens)):
+            for w in path:
+                if w in gindex:
+                    group_rows[gindex[w]] += list(range(qoff[li], qoff[li] + ql))
+
+        qt_list: List[int] = []
+        group_qt_begin = []
+        for rows in group_rows:
+            group_qt_begin.append(len(qt_list))
+            qt_list += rows
+        n_group_qt = len(qt_list)
+        qt_list += list(range(NQ))
+
+        def segment_entries(nodes):
+            ids, valid, pos = [], [], []
+            for w in nodes:
+                va = self.node_page_valid(w)
+                t = pos0[w]
+                for p, v in zip(self.pages[w], va):
+                    ids.append(p)
+                    valid.append(v)
+                    pos.append(t)
+                    t += v
+            return ids, valid, pos
+
+        def cut(n, chunk):
+            c = -(-n // chunk)
+            return [(j * n // c, (j + 1) * n // c) for j in range(c)]
+
+        tasks = dict(pg_begin=[], pg_count=[], qt_begin=[], qt_count=[], pbase=[], flags=[])
+        pg_id, pg_valid, pg_pos = [], [], []
+        parts: List[List[tuple]] = [[] for _ in range(NQ)]
+        pbase = 0
+
+        def emit(ids, valid, pos, chunk_pages, qt_begin, qt_count):
+            nonlocal pbase
+            rows = qt_count * G
+            min_limit = min(qt_limit[qt_list[qt_begin + r]] for r in range(qt_count))
+            for a, b in cut(len(ids), chunk_pages):
+                end_pos = pos[b - 1] + valid[b - 1]
+                masked = any(v != P for v in valid[a:b]) or min_limit < end_pos
+                tasks["pg_begin"].append(len(pg_id))
+                tasks["pg_count"].append(b - a)
+                tasks["qt_begin"].append(qt_begin)
+                tasks["qt_count"].append(qt_count)
+                tasks["pbase"].append(pbase)
+                tasks["flags"].append(1 if masked else 0)
+                pg_id.extend(ids[a:b])
+                pg_valid.extend(valid[a:b])
+                pg_pos.extend(pos[a:b])
+                for r in range(qt_count):
+                    parts[qt_list[qt_begin + r]].append((pbase + r * G, rows))
+                pbase += rows * num_kv_heads
+
+        for gi, w in enumerate(group_nodes):
+            ids, valid, pos = segment_entries([w])
+            emit(ids, valid, pos, prefix_chunk_pages, group_qt_begin[gi], len(group_rows[gi]))
+        n_prefix_tasks = len(tasks["pbase"])
+        for li, (path, ql) in enumerate(zip(paths, q_lens)):
+            tail = []
+            for w in reversed(path):
+                if live[w] != 1:
+                    break
+                tail.append(w)
+            ids, valid, pos = segment_entries(tail[::-1])
+            if ids:
+                emit(ids, valid, pos, suffix_chunk_pages, n_group_qt + qoff[li], ql)
+
+        part_indptr, part_base, part_hstride = [0], [], []
+        for lst in parts:
+            for b, h in lst:
+                part_base.append(b)
+                part_hstride.append(h)
+            part_indptr.append(len(part_base))
+
+        return dict(
+            leaf_indptr=leaf_indptr, leaf_pages=leaf_pages, leaf_valid=leaf_valid,
+            qt_limit=qt_limit, group_node=group_nodes,
+            n_prefix_tasks=n_prefix_tasks, n_partial_rows=pbase,
+            task_pg_begin=tasks["pg_begin"], task_pg_count=tasks["pg_count"],
+            task_qt_begin=tasks["qt_begin"], task_qt_count=tasks["qt_count"],
+            task_pbase=tasks["pbase"], task_flags=tasks["flags"],
+            pg_id=pg_id, pg_valid=pg_valid, pg_pos=pg_pos, qt_list=qt_list,
+            part_indptr=part_indptr, part_base=part_base, part_hstride=part_hstride,
+        )

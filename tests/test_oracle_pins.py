@@ -1,0 +1,332 @@
+"""Pins for the CPU oracle: brute force, a library routine, closed forms and invariants.
+
+None of these re-uses the oracle's own formula: the brute force is nested Python loops over an
+independently materialised branch, the library check is torch's fp64 scaled_dot_product_attention,
+and the rest are hand-derived values or properties.
+"""
+
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import spex_workloads as sw
+from oracle.adapters import OracleSink, queries_fp64
+from oracle.tree_attention import (OracleTree, decode_bf16, decode_e4m3, lse_merge,
+                                   partial_attention)
+from helpers import RecordingSink
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "closed_form_cases.txt")
+
+
+def run_oracle(wl):
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = queries_fp64(sw.gen_queries(wl))
+    return sink.tree, q, sink.tree.attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+
+
+def small_workloads():
+    return [
+        sw.random_trace(11, kv_dtype="f32", q_dtype="f32", value_scale=1.0, n_ops=25, max_tokens=9),
+        sw.random_trace(12, kv_dtype="bf16", q_dtype="bf16", n_ops=25, max_tokens=9, max_q_len=3),
+        sw.random_trace(13, heads=(6, 3, 8), kv_dtype="fp8_e4m3", q_dtype="bf16", n_ops=25,
+                        max_tokens=20, max_q_len=2),
+    ]
+
+
+# ------------------------------------------------------------------------- brute force
+@pytest.mark.parametrize("wl", small_workloads(), ids=lambda w: w.name + "_" + w.kv_dtype)
+def test_brute_force_loops(wl):
+    _, _, (out, lse) = run_oracle(wl)
+    rec = RecordingSink(wl)
+    sw.replay(wl, rec)
+    q = sw.gen_queries(wl).to(torch.float64)
+    G = wl.num_q_heads // wl.num_kv_heads
+    row = 0
+    for leaf, ql in zip(wl.leaves, wl.q_lens):
+        K, V = rec.branch(leaf)
+        K, V = K.tolist(), V.tolist()
+        T = len(K)
+        for i in range(ql):
+            visible = T - ql + i + 1
+            for h in range(wl.num_q_heads):
+                g = h // G
+                qv = q[row, h].tolist()
+                scores = []
+                for t in range(visible):
+                    dot = 0.0
+                    for d in range(wl.head_dim):
+                        dot += qv[d] * K[t][g][d]
+                    scores.append(dot * wl.sm_scale)
+                z = sum(math.exp(s) for s in scores)
+                for d in range(wl.head_dim):
+                    acc = 0.0
+                    for t in range(visible):
+                        acc += math.exp(scores[t]) / z * V[t][g][d]
+                    assert abs(acc - out[row, h, d]) < 1e-12
+                assert abs(math.log(z) - lse[row, h]) < 1e-12
+            row += 1
+    assert row == out.shape[0]
+
+
+# ------------------------------------------------------------------------- library routine
+def reduced_configs():
+    return [
+        sw.tiny_tree(),
+        sw.bfs_tot(n_queries=2, prompt=40, step=24),
+        sw.mcts_skewed(n_queries=3, prompt=(20, 60), step=(5, 40), max_leaves=12),
+        sw.spec_at_scale(n_queries=2, prompt=70, step=20, branches=6),
+        sw.tot_with_drafts(n_queries=2, prompt=50, step=16),
+    ]
+
+
+@pytest.mark.parametrize("wl", reduced_configs(), ids=lambda w: w.name)
+def test_against_torch_sdpa_fp64(wl):
+    _, _, (out, lse) = run_oracle(wl)
+    rec = RecordingSink(wl)
+    sw.replay(wl, rec)
+    q = sw.gen_queries(wl).to(torch.float64)
+    G = wl.num_q_heads // wl.num_kv_heads
+    row = 0
+    for leaf, ql in zip(wl.leaves, wl.q_lens):
+        K, V = rec.branch(leaf)                                   # [T, Hkv, D]
+        T = K.shape[0]
+        Kh = K.permute(1, 0, 2).repeat_interleave(G, dim=0)       # [Hq, T, D]
+        Vh = V.permute(1, 0, 2).repeat_interleave(G, dim=0)
+        qh = q[row:row + ql].permute(1, 0, 2)                     # [Hq, ql, D]
+        mask = torch.arange(T)[None, :] <= (T - ql + torch.arange(ql))[:, None]
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            qh[None], Kh[None], Vh[None], attn_mask=mask[None, None], scale=wl.sm_scale)[0]
+        got = torch.from_numpy(out[row:row + ql]).permute(1, 0, 2)
+        assert torch.max(torch.abs(ref - got)).item() < 1e-12
+        s = torch.einsum("hqd,htd->hqt", qh, Kh) * wl.sm_scale
+        s = s.masked_fill(~mask[None], float("-inf"))
+        ref_lse = torch.logsumexp(s, dim=-1)                      # [Hq, ql]
+        got_lse = torch.from_numpy(lse[row:row + ql]).T
+        assert torch.max(torch.abs(ref_lse - got_lse)).item() < 1e-12
+        row += ql
+
+
+def test_tiny_tree_matches_config_1():
+    wl = sw.tiny_tree()
+    tree, q, (out, lse) = run_oracle(wl)
+    assert out.shape == (4, 8, 64) and lse.shape == (4, 8)
+    assert [tree.path_tokens(u) for u in wl.leaves] == [320] * 4
+    assert wl.unique_kv_tokens() == 512 and wl.flat_kv_tokens() == 1280
+    assert abs(wl.sm_scale - 0.125) < 1e-15
+
+
+# ------------------------------------------------------------------------- closed forms
+def golden_cases():
+    cases = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, root, keys, vals, qlen, outs, zs = [c.strip() for c in line.split("|")]
+            cases.append((name, int(root), [float(x) for x in keys.split()],
+                          [float(x) for x in vals.split()], int(qlen),
+                          [float(x) for x in outs.split()], [float(x) for x in zs.split()]))
+    return cases
+
+
+@pytest.mark.parametrize("case", golden_cases(), ids=lambda c: c[0])
+def test_golden_closed_forms(case):
+    _, root, keys, vals, qlen, outs, zs = case
+    tree = OracleTree(1, 1, 1, "f32")
+    k = np.log(np.array(keys)).reshape(-1, 1, 1)
+    v = np.array(vals).reshape(-1, 1, 1)
+    (r,) = tree.fork(-1, 1)
+    tree.append(r, k[:root], v[:root])
+    (c,) = tree.fork(r, 1)
+    tree.append(c, k[root:], v[root:])
+    q = np.ones((qlen, 1, 1))
+    out, lse = tree.attention([c], [qlen], q, 1.0)
+    assert np.allclose(out[:, 0, 0], outs, rtol=0, atol=1e-12)
+    assert np.allclose(np.exp(lse[:, 0]), zs, rtol=1e-13, atol=0)
+
+
+def _chain_tree(K, V, cuts, Hq=None):
+    """Tree that is a single chain cut into nodes at `cuts`; returns (tree, leaf)."""
+    Hkv, D = K.shape[1], K.shape[2]
+    tree = OracleTree(Hq or Hkv, Hkv, D, "f32")
+    node = -1
+    edges = [0] + list(cuts) + [K.shape[0]]
+    for a, b in zip(edges[:-1], edges[1:]):
+        (node,) = tree.fork(node, 1)
+        tree.append(node, K[a:b], V[a:b])
+    return tree, node
+
+
+def test_special_cases():
+    rng = np.random.default_rng(0)
+    T, Hkv, G, D = 37, 2, 3, 5
+    V = rng.normal(size=(T, Hkv, D))
+    q = rng.normal(size=(1, Hkv * G, D))
+    # all keys equal -> uniform weights -> mean of V
+    K = np.tile(rng.normal(size=(1, Hkv, D)), (T, 1, 1))
+    tree, leaf = _chain_tree(K, V, [10, 11], Hq=Hkv * G)
+    out, lse = tree.attention([leaf], None, q, 0.3)
+    for h in range(Hkv * G):
+        assert np.allclose(out[0, h], V[:, h // G].mean(0), atol=1e-13)
+    # q = 0 -> uniform weights, lse = ln T
+    K = rng.normal(size=(T, Hkv, D))
+    tree, leaf = _chain_tree(K, V, [20], Hq=Hkv * G)
+    out, lse = tree.attention([leaf], None, np.zeros_like(q), 0.3)
+    assert np.allclose(out[0, 4], V[:, 1].mean(0), atol=1e-13)
+    assert np.allclose(lse, math.log(T), atol=1e-13)
+    # T = 1 -> V[0]
+    tree, leaf = _chain_tree(K[:1], V[:1], [], Hq=Hkv * G)
+    out, _ = tree.attention([leaf], None, q, 0.3)
+    assert np.allclose(out[0, 0], V[0, 0], atol=1e-15) and np.allclose(out[0, 5], V[0, 1], atol=1e-15)
+    # V constant -> that constant, whatever the weights
+    tree, leaf = _chain_tree(K, np.full_like(V, 2.5), [3, 30], Hq=Hkv * G)
+    out, _ = tree.attention([leaf], None, q, 0.3)
+    assert np.allclose(out, 2.5, atol=1e-13)
+    # one key far above the rest -> its value row
+    K2 = K.copy()
+    K2[17, 0] = q[0, 0] * 1e3
+    tree, leaf = _chain_tree(K2, V, [5], Hq=Hkv * G)
+    out, _ = tree.attention([leaf], None, q, 1.0)
+    assert np.allclose(out[0, 0], V[17, 0], atol=1e-9)
+
+
+def test_gqa_head_mapping_uses_consecutive_blocks():
+    # K of kv head 1 is huge at token 0, of kv head 0 at token 1: query heads 0..G-1 must pick
+    # token 1, heads G..2G-1 token 0.
+    G, D = 4, 3
+    K = np.zeros((2, 2, D))
+    K[1, 0, :] = 100.0
+    K[0, 1, :] = 100.0
+    V = np.zeros((2, 2, D))
+    V[0, :, :] = 1.0
+    V[1, :, :] = 2.0
+    tree, leaf = _chain_tree(K, V, [1], Hq=2 * G)
+    out, _ = tree.attention([leaf], None, np.ones((1, 2 * G, D)), 1.0)
+    assert np.allclose(out[0, :G], 2.0) and np.allclose(out[0, G:], 1.0)
+
+
+# ------------------------------------------------------------------------- invariants
+@pytest.mark.parametrize("wl", small_workloads() + reduced_configs()[1:3], ids=lambda w: w.name)
+def test_weights_sum_to_one_and_lse(wl):
+    tree, q, _ = run_oracle(wl)
+    out, lse, weights = tree.attention(wl.leaves, wl.q_lens, q, wl.sm_scale, return_weights=True)
+    G = wl.num_q_heads // wl.num_kv_heads
+    row = 0
+    for leaf, ql in zip(wl.leaves, wl.q_lens):
+        K, _ = tree.materialise(leaf)
+        for i in range(ql):
+            w = weights[row]
+            assert w.shape[1] == K.shape[0] - ql + 1 + i
+            assert np.all(w >= 0)
+            assert np.max(np.abs(w.sum(axis=1) - 1.0)) < 1e-14
+            for h in range(0, wl.num_q_heads, max(1, wl.num_q_heads // 3)):
+                s = wl.sm_scale * (K[:w.shape[1], h // G] @ q[row, h])
+                assert abs(math.log(np.sum(np.exp(s))) - lse[row, h]) < 1e-12
+            row += 1
+
+
+def test_identical_token_paths_give_identical_outputs():
+    wl = sw.Workload("twins", 8, 2, 16, 16, "bf16", "bf16", 0.5, 77)
+    b = sw.trees._Builder(wl)
+    (root,) = b.fork(-1, 1)
+    b.append(root, 21)
+    a1, a2 = b.fork(root, 2)
+    b.append(a1, 13, key=1234)
+    b.append(a2, 13, key=1234)                 # same logical tokens as a1
+    (c1,) = b.fork(a1, 1)
+    (c2,) = b.fork(a2, 1)
+    b.append(c1, 7, key=99)
+    b.append(c2, 7, key=99)
+    b.request(c1, 2, key=5)
+    b.request(c2, 2, key=5)
+    _, _, (out, lse) = run_oracle(wl)
+    assert np.array_equal(out[:2], out[2:]) and np.array_equal(lse[:2], lse[2:])
+
+
+def test_split_of_a_step_into_nodes_does_not_matter():
+    rng = np.random.default_rng(3)
+    K = rng.normal(size=(50, 2, 8))
+    V = rng.normal(size=(50, 2, 8))
+    q = rng.normal(size=(3, 4, 8))
+    t1, l1 = _chain_tree(K, V, [], Hq=4)
+    t2, l2 = _chain_tree(K, V, [1, 17, 18, 40], Hq=4)
+    o1, s1 = t1.attention([l1], [3], q, 0.4)
+    o2, s2 = t2.attention([l2], [3], q, 0.4)
+    assert np.array_equal(o1, o2) and np.array_equal(s1, s2)
+
+
+def test_causal_drafts_equal_truncated_single_queries():
+    rng = np.random.default_rng(4)
+    T, ql = 41, 6
+    K = rng.normal(size=(T, 2, 8))
+    V = rng.normal(size=(T, 2, 8))
+    q = rng.normal(size=(ql, 4, 8))
+    tree, leaf = _chain_tree(K, V, [30], Hq=4)
+    out, lse = tree.attention([leaf], [ql], q, 0.35)
+    for i in range(ql):
+        keep = T - ql + 1 + i
+        t_i, l_i = _chain_tree(K[:keep], V[:keep], [min(30, keep - 1)] if keep > 1 else [], Hq=4)
+        o, s = t_i.attention([l_i], [1], q[i:i + 1], 0.35)
+        assert np.allclose(o[0], out[i], atol=1e-14) and np.allclose(s[0], lse[i], atol=1e-14)
+
+
+def test_lse_merge_over_random_partitions():
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        T, D = int(rng.integers(1, 60)), 6
+        K = rng.normal(size=(T, 1, D)) * 3
+        V = rng.normal(size=(T, 1, D))
+        q = rng.normal(size=(1, 1, D))
+        tree, leaf = _chain_tree(K, V, [])
+        out, lse = tree.attention([leaf], None, q, 0.7)
+        ncut = int(rng.integers(0, 5))
+        cuts = sorted(rng.integers(0, T + 1, size=ncut).tolist())      # empty pieces allowed
+        edges = [0] + cuts + [T]
+        parts = [partial_attention(q[0, 0], K[a:b, 0], V[a:b, 0], 0.7)
+                 for a, b in zip(edges[:-1], edges[1:])]
+        o, l = lse_merge(parts)
+        assert np.allclose(o, out[0, 0], atol=1e-13) and abs(l - lse[0, 0]) < 1e-13
+        # merge is order independent, and merging one piece is the identity
+        o2, l2 = lse_merge(parts[::-1])
+        assert np.allclose(o2, o, atol=1e-13) and abs(l2 - l) < 1e-13
+    m, l, o = partial_attention(q[0, 0], K[:, 0], V[:, 0], 0.7)
+    o1, l1 = lse_merge([(m, l, o)])
+    assert np.allclose(o1, o / l, atol=1e-15) and abs(l1 - (m + math.log(l))) < 1e-15
+
+
+# ------------------------------------------------------------------------- bit decoders
+def test_bf16_and_e4m3_decoders_match_torch():
+    bits = np.arange(0, 65536, dtype=np.uint16)
+    ref = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float64).numpy()
+    got = decode_bf16(bits)
+    finite = np.isfinite(ref)
+    assert np.array_equal(got[finite], ref[finite]) and np.array_equal(np.isnan(got), np.isnan(ref))
+    codes = np.arange(256, dtype=np.uint8)
+    ref8 = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got8 = decode_e4m3(codes)
+    ok = ~np.isnan(ref8)
+    assert np.array_equal(got8[ok], ref8[ok]) and np.array_equal(np.isnan(got8), np.isnan(ref8))
+    assert got8[0x7E] == 448.0 and got8[0x08] == 2.0 ** -6 and got8[0x01] == 2.0 ** -9
+
+
+def test_pruned_and_interior_nodes():
+    tree = OracleTree(1, 1, 2, "f32")
+    (r,) = tree.fork(-1, 1)
+    tree.append(r, np.ones((3, 1, 2)), np.ones((3, 1, 2)))
+    a, b = tree.fork(r, 2)
+    tree.append(a, np.ones((2, 1, 2)), np.ones((2, 1, 2)))
+    with pytest.raises(ValueError):
+        tree.append(r, np.ones((1, 1, 2)), np.ones((1, 1, 2)))       # r has children
+    tree.prune(a)
+    with pytest.raises(KeyError):
+        tree.attention([a], None, np.ones((1, 1, 2)), 1.0)
+    tree.prune(b)
+    tree.append(r, np.ones((1, 1, 2)), np.ones((1, 1, 2)))           # childless again
+    assert tree.path_tokens(r) == 4
+    with pytest.raises(ValueError):
+        tree.attention([r], [5], np.ones((5, 1, 2)), 1.0)            # q_len > T
