@@ -1,0 +1,242 @@
+/*
+ * spex_tree.h -- C ABI of the tree decode-attention library for MI355X (gfx950).
+ *
+ * Problem served.  Tree-of-Thought search frames reasoning as a tree whose node is
+ * the state reached by one step, a coherent run of tokens (paper Sec. 2.1).  The
+ * consumer loop of Alg. 2 (Sec. 4.5) adds a child for every finished primary or
+ * speculative expansion, BFS mis-speculation terminates a branch at once
+ * (Sec. 4.2, "Mis-speculation Handling"), early termination ends a whole query
+ * (Sec. 4.4), and sibling branches reuse the KV cache of their shared prefix
+ * (Sec. 3.2; Sec. 4.1, insight 2; S_KV(q) of Eq. 1 in Sec. 4.3).  This library keeps
+ * that tree as a paged KV cache in which a node owns the pages of its own step and
+ * reaches its prefix through parent links, and computes, for many branches in one
+ * launch, decode attention over each branch's root-to-node KV while reading every
+ * shared page only once.
+ *
+ * All functions return a spex_status_t, never throw and never abort.  On error the
+ * out-parameters are untouched and the tree is unchanged.  A handle is not thread
+ * safe: one consumer loop owns it.  Device work is enqueued on the HIP stream given
+ * to the call and is asynchronous; the library synchronises only where stated.
+ * "HOST" / "DEVICE" below say where a pointer must point.
+ */
+#ifndef SPEX_TREE_H
+#define SPEX_TREE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spex_tree spex_tree_t; /* opaque: one forest over one page pool */
+typedef int32_t spex_node_t;          /* dense id in creation order, never reused */
+#define SPEX_NO_NODE (-1)
+
+typedef enum {
+  SPEX_OK = 0,
+  SPEX_ERR_INVALID_ARG = 1, /* NULL where data is needed, negative count, bad config */
+  SPEX_ERR_BAD_NODE = 2,    /* id unknown or pruned */
+  SPEX_ERR_NOT_LEAF = 3,    /* append to a node that has live children */
+  SPEX_ERR_OOM_PAGES = 4,   /* the pool has too few free pages; nothing was allocated */
+  SPEX_ERR_EMPTY_PATH = 5,  /* a requested node has fewer path tokens than queries (or none) */
+  SPEX_ERR_UNSUPPORTED = 6, /* dtype / shape combination without a kernel */
+  SPEX_ERR_DEVICE = 7,      /* a HIP call failed; see spex_last_device_error() */
+  SPEX_ERR_CAPACITY = 8     /* caller-provided output array too small */
+} spex_status_t;
+
+typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
+
+/*
+ * Pool layout.  k_pool and v_pool are caller-owned DEVICE buffers of
+ * num_pages * num_kv_heads * page_size * head_dim elements of kv_dtype each (see
+ * spex_pool_bytes).  The (page, kv head) tile at element offset
+ * (page * num_kv_heads + head) * page_size * head_dim holds page_size tokens; only
+ * the library reads and writes inside a tile, in one of two arrangements:
+ *
+ *  ROW-MAJOR  (kv_dtype F32, or page_size != 16, or head_dim not 64 / 128):
+ *     K and V element (token t, dim d) at t * head_dim + d.
+ *
+ *  MFMA-TILED (kv_dtype BF16 / FP8_E4M3 with page_size 16 and head_dim 64 or 128):
+ *     the order in which a 64-lane wavefront consumes MFMA 16x16x32 operands, so that
+ *     every 128-bit load instruction of the attention kernels reads contiguous memory
+ *     and lands directly in operand registers.
+ *     K, bf16:  ((t>>2)&1) * 8*head_dim + (d/32)*256 + ((d%32)/8)*64 + (4*(t>>3) + (t&3))*8 + d%8
+ *     V, bf16:  (d/16)*256 + (t/8)*128 + (d%16)*8 + t%8              (token-minor: V transposed)
+ *     K, fp8 :  ((t>>2)&1) * 8*head_dim + (d/64)*512 + ((d%32)/8)*128 + (4*(t>>3) + (t&3))*16 + ((d/32)&1)*8 + d%8
+ *     V, fp8 :  (d/32)*512 + (t/8)*256 + (d%16)*16 + ((d/16)&1)*8 + t%8
+ *  Use spex_tree_gather_kv to read tokens back in logical order.
+ *
+ * fp8 (OCP e4m3fn): value = code * scale, one fp32 scale per (page, kv head), separately
+ * for K and V, in the caller-owned DEVICE arrays k_scale / v_scale [num_pages][num_kv_heads].
+ */
+typedef struct {
+  int32_t num_q_heads;  /* multiple of num_kv_heads; query head h uses kv head h / (Hq/Hkv) */
+  int32_t num_kv_heads;
+  int32_t head_dim;     /* 1..256 */
+  int32_t page_size;    /* power of two, 1..64 */
+  int32_t q_dtype;      /* spex_dtype_t: (F32,F32) | (BF16,BF16) | (BF16,FP8_E4M3) as (q, kv) */
+  int32_t kv_dtype;
+  int64_t num_pages;
+  void *k_pool;         /* DEVICE; may be NULL for a host-only handle (no append data, no attention) */
+  void *v_pool;         /* DEVICE */
+  float *k_scale;       /* DEVICE, fp8 only, else NULL */
+  float *v_scale;       /* DEVICE, fp8 only, else NULL */
+  const int32_t *free_order; /* HOST, optional: permutation of 0..num_pages-1, the order in which
+                                pages are first handed out; NULL = ascending.  Copied by create. */
+  int32_t prefix_chunk_pages; /* split granularity of shared-prefix segments; 0 = automatic */
+  int32_t suffix_chunk_pages; /* split granularity of private suffixes;       0 = automatic */
+  int32_t kernel_mode;  /* 0 = fastest kernels available; 1 = force the generic (non-MFMA) kernels */
+  int32_t reserved;     /* must be 0 */
+} spex_config_t;
+
+/* Bytes each of k_pool and v_pool must hold for this config. */
+spex_status_t spex_pool_bytes(const spex_config_t *cfg, size_t *bytes_per_pool);
+
+const char *spex_status_string(spex_status_t s);
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char *spex_last_device_error(void);
+
+/* Create an empty forest over the caller's pool.  The config is copied. */
+spex_status_t spex_tree_create(const spex_config_t *cfg, spex_tree_t **out);
+/* Frees host state and the library's own device workspace (plan, partial results).
+ * Synchronises the device.  The pools stay the caller's. */
+void spex_tree_destroy(spex_tree_t *tree);
+
+/*
+ * Alg. 2 "add_node / add_spec_node": create n_children empty nodes under parent
+ * (SPEX_NO_NODE: new roots, i.e. new user queries).  Ids written to out_children[n_children]
+ * (HOST) are consecutive.  Children share the parent's pages through the parent link; nothing
+ * is copied, and a child's first token always starts a fresh page.  Primary and speculative
+ * children are the same kind of node.
+ */
+spex_status_t spex_tree_fork(spex_tree_t *tree, spex_node_t parent, int32_t n_children,
+                             spex_node_t *out_children);
+
+/*
+ * Append the K/V of n_tokens generated tokens (a step, or one decode token of it) to a node
+ * without live children.  k, v: DEVICE, [n_tokens][num_kv_heads][head_dim] in kv_dtype.
+ * fp8: k_scales / v_scales are DEVICE arrays [n_new_pages][num_kv_heads] with the scale of
+ * every page this append newly starts (see spex_tree_append_new_pages); tokens that continue a
+ * partially filled page use the scale that page already has.  Pages are taken from the
+ * allocator one at a time in token order; if too few are free the call fails with
+ * SPEX_ERR_OOM_PAGES and changes nothing.  Unused slots of a newly started page are zeroed.
+ * The scatter into the pool is enqueued on hip_stream (a hipStream_t, NULL = default stream);
+ * the source buffers must stay valid until that work has run.
+ * k == NULL and v == NULL: only the page table is updated (host-only handles, or callers that
+ * never read these tokens back).
+ */
+spex_status_t spex_tree_append_step(spex_tree_t *tree, spex_node_t node, int32_t n_tokens,
+                                    const void *k, const void *v, const float *k_scales,
+                                    const float *v_scales, void *hip_stream);
+/* Number of pages an append of n_tokens to node would newly start. */
+spex_status_t spex_tree_append_new_pages(const spex_tree_t *tree, spex_node_t node,
+                                         int32_t n_tokens, int32_t *n_new_pages);
+
+/*
+ * Sec. 4.2 mis-speculation / Sec. 4.4 early termination: remove node and its whole subtree and
+ * return their pages to the allocator (pre-order over the subtree, children in creation order,
+ * each node's pages in order; the page returned last is handed out first).  Pruning a root ends
+ * that query.  A parent left without children may be appended to again.
+ */
+spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
+
+/*
+ * Decode attention for n_leaves requested nodes (usually the live leaves; any live node is
+ * accepted, also twice).  q_lens[i] >= 1 queries belong to leaves[i] (NULL: all 1): the last
+ * q_lens[i] tokens of its path are the query tokens (already appended), and query j sees path
+ * positions 0 .. T_i - q_lens[i] + j, T_i being the number of tokens on the root-to-node path.
+ *   leaves, q_lens : HOST
+ *   q   : DEVICE [sum(q_lens)][num_q_heads][head_dim] in q_dtype, requested-node major
+ *   out : DEVICE fp32, same shape:  sum_t softmax_t(sm_scale * <q, K_t>) V_t  over visible t
+ *   lse : DEVICE fp32 [sum(q_lens)][num_q_heads] or NULL:  ln sum_t exp(sm_scale * <q, K_t>)
+ * The call flattens parent links into per-launch work lists (shared-prefix groups are read
+ * once for all nodes below them; private suffixes are split for parallelism), uploads them
+ * when the request or the tree changed since the previous call, and enqueues the
+ * shared-prefix, suffix and merge kernels on hip_stream.  It does not wait for them.
+ * Consecutive calls on one handle must use one stream or be separated by a synchronisation,
+ * because they share the handle's workspace.
+ */
+spex_status_t spex_tree_decode_attention(spex_tree_t *tree, const spex_node_t *leaves,
+                                         const int32_t *q_lens, int32_t n_leaves, const void *q,
+                                         float *out, float *lse, float sm_scale, void *hip_stream);
+
+/* ---- introspection (host only unless stated) -------------------------------------------- */
+
+typedef struct {
+  spex_node_t parent;
+  int32_t n_tokens;
+  int32_t n_pages;
+  int32_t n_live_children;
+} spex_node_info_t;
+spex_status_t spex_tree_node_info(const spex_tree_t *tree, spex_node_t node, spex_node_info_t *out);
+
+/* Pages of the root-to-node path in order and the number of valid tokens in each.  At most cap
+ * entries are written (SPEX_ERR_CAPACITY if more are needed; *n is set to the needed count). */
+spex_status_t spex_tree_path_pages(const spex_tree_t *tree, spex_node_t node, int32_t *pages,
+                                   int32_t *valid, int32_t cap, int32_t *n);
+/* Free pages, the one handed out next first. */
+spex_status_t spex_tree_free_pages(const spex_tree_t *tree, int32_t *pages, int32_t cap, int32_t *n);
+spex_status_t spex_tree_stats(const spex_tree_t *tree, int64_t *live_nodes, int64_t *used_pages,
+                              int64_t *free_pages);
+
+/*
+ * The work lists a decode_attention call with the same arguments would use.  All pointers are
+ * HOST arrays owned by the tree, valid until the next call that plans or mutates the tree.
+ *   leaf_indptr[n_leaves+1], leaf_pages[], leaf_valid[]: root-to-node page lists (CSR).
+ *   qt_limit[n_qtok]: visible path length of every query token.
+ *   group_node[n_groups]: nodes with >= 2 requested nodes below them and >= 1 token, ascending.
+ *   Tasks (one per chunk of a segment; the n_prefix_tasks group chunks first, then the suffix
+ *   chunks in request order): pages pg_id/pg_valid/pg_pos[task_pg_begin .. + task_pg_count)
+ *   (page id, valid tokens, path position of the page's first token), rows
+ *   qt_list[task_qt_begin .. + task_qt_count) (query-token indices), first partial slot
+ *   task_pbase, task_flags bit 0 = some page partial or some row's limit inside the chunk.
+ *   Merge lists: query token t combines entries part_indptr[t] .. part_indptr[t+1]; the slot of
+ *   (kv head g, head-in-group hh) in entry e is part_base[e] + g * part_hstride[e] + hh.
+ */
+typedef struct {
+  int32_t n_leaves, n_qtok, n_groups, n_tasks, n_prefix_tasks, n_pg, n_qt_list, n_parts;
+  int64_t n_partial_rows;
+  int32_t prefix_chunk_pages, suffix_chunk_pages; /* the values actually used */
+  const int32_t *leaf_indptr, *leaf_pages, *leaf_valid;
+  const int32_t *qt_limit;
+  const int32_t *group_node;
+  const int32_t *task_pg_begin, *task_pg_count, *task_qt_begin, *task_qt_count, *task_pbase,
+      *task_flags;
+  const int32_t *pg_id, *pg_valid, *pg_pos;
+  const int32_t *qt_list;
+  const int32_t *part_indptr, *part_base, *part_hstride;
+} spex_plan_view_t;
+spex_status_t spex_tree_plan_dump(spex_tree_t *tree, const spex_node_t *leaves,
+                                  const int32_t *q_lens, int32_t n_leaves, spex_plan_view_t *out);
+
+/* Copy a node's own tokens [first, first + n) out of the pool in logical order:
+ * k_out, v_out DEVICE [n][num_kv_heads][head_dim] in kv_dtype; fp8 codes are copied as stored and
+ * k_scale_out / v_scale_out (DEVICE [n][num_kv_heads] fp32, may be NULL) receive each token's
+ * page scale.  Enqueued on hip_stream. */
+spex_status_t spex_tree_gather_kv(spex_tree_t *tree, spex_node_t node, int32_t first, int32_t n,
+                                  void *k_out, void *v_out, float *k_scale_out, float *v_scale_out,
+                                  void *hip_stream);
+
+/* Change the split granularities (0 = automatic) and kernel_mode after creation. */
+spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages,
+                                   int32_t suffix_chunk_pages, int32_t kernel_mode);
+
+/*
+ * Per-kernel timing.  With profiling enabled, every decode_attention call brackets each of its
+ * kernels with HIP events on the call's stream.  spex_tree_last_kernel_ms waits for the last
+ * call's events and returns milliseconds for ms[0] = shared-prefix kernel, ms[1] = suffix
+ * kernel, ms[2] = merge kernel (0 for a kernel that was not launched).
+ */
+spex_status_t spex_tree_set_profiling(spex_tree_t *tree, int32_t enabled);
+spex_status_t spex_tree_last_kernel_ms(spex_tree_t *tree, float ms[3]);
+
+/* Counts of the last decode_attention call, for the throughput metric:
+ * info[0] distinct KV tokens read, [1] tokens in shared-prefix tasks, [2] tokens in suffix tasks,
+ * [3] prefix work items, [4] suffix work items, [5] partial rows, [6] 1 if the plan was rebuilt. */
+spex_status_t spex_tree_last_launch_info(const spex_tree_t *tree, int64_t info[8]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEX_TREE_H */

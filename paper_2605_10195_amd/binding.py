@@ -1,0 +1,354 @@
+"""ctypes binding of libspex_tree.so: argument marshalling only.
+
+Every step of the hot path (page table, planning, kernels) runs inside the
+library; this module turns torch tensors into device pointers and Python lists
+into int32 arrays.  There is no fallback: if the library has not been built the
+import fails.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from .build import LIB_PATH
+
+NO_NODE = -1
+F32, BF16, FP8_E4M3 = 0, 1, 2
+_DTYPES = {"f32": F32, "bf16": BF16, "fp8_e4m3": FP8_E4M3}
+_TORCH_KV = {F32: torch.float32, BF16: torch.bfloat16, FP8_E4M3: torch.uint8}
+
+STATUS_NAMES = ["OK", "INVALID_ARG", "BAD_NODE", "NOT_LEAF", "OOM_PAGES", "EMPTY_PATH",
+                "UNSUPPORTED", "DEVICE", "CAPACITY"]
+
+
+class SpexError(RuntimeError):
+    def __init__(self, status: int, detail: str = ""):
+        self.status = status
+        self.name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"SPEX_ERR_{self.name}" + (f": {detail}" if detail else ""))
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("page_size", C.c_int32), ("q_dtype", C.c_int32), ("kv_dtype", C.c_int32),
+        ("num_pages", C.c_int64),
+        ("k_pool", C.c_void_p), ("v_pool", C.c_void_p),
+        ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
+        ("free_order", C.POINTER(C.c_int32)),
+        ("prefix_chunk_pages", C.c_int32), ("suffix_chunk_pages", C.c_int32),
+        ("kernel_mode", C.c_int32), ("reserved", C.c_int32),
+    ]
+
+
+class NodeInfo(C.Structure):
+    _fields_ = [("parent", C.c_int32), ("n_tokens", C.c_int32), ("n_pages", C.c_int32),
+                ("n_live_children", C.c_int32)]
+
+
+_I32P = C.POINTER(C.c_int32)
+
+
+class PlanView(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_leaves", "n_qtok", "n_groups", "n_tasks",
+                                         "n_prefix_tasks", "n_pg", "n_qt_list", "n_parts")] + \
+               [("n_partial_rows", C.c_int64), ("prefix_chunk_pages", C.c_int32),
+                ("suffix_chunk_pages", C.c_int32)] + \
+               [(n, _I32P) for n in ("leaf_indptr", "leaf_pages", "leaf_valid", "qt_limit",
+                                     "group_node", "task_pg_begin", "task_pg_count",
+                                     "task_qt_begin", "task_qt_count", "task_pbase", "task_flags",
+                                     "pg_id", "pg_valid", "pg_pos", "qt_list", "part_indptr",
+                                     "part_base", "part_hstride")]
+
+
+EXPORTS = [
+    "spex_pool_bytes", "spex_status_string", "spex_last_device_error", "spex_tree_create",
+    "spex_tree_destroy", "spex_tree_fork", "spex_tree_append_step", "spex_tree_append_new_pages",
+    "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_node_info", "spex_tree_path_pages",
+    "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
+    "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_last_kernel_ms",
+    "spex_tree_last_launch_info",
+]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_10195_amd.build` "
+            "(there is no fallback implementation)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+    lib.spex_pool_bytes.argtypes = [C.POINTER(Config), C.POINTER(C.c_size_t)]
+    lib.spex_status_string.argtypes = [C.c_int]
+    lib.spex_status_string.restype = C.c_char_p
+    lib.spex_last_device_error.restype = C.c_char_p
+    lib.spex_tree_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+    lib.spex_tree_destroy.argtypes = [vp]
+    lib.spex_tree_destroy.restype = None
+    lib.spex_tree_fork.argtypes = [vp, i32, i32, _I32P]
+    lib.spex_tree_append_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.spex_tree_append_new_pages.argtypes = [vp, i32, i32, _I32P]
+    lib.spex_tree_prune.argtypes = [vp, i32]
+    lib.spex_tree_decode_attention.argtypes = [vp, _I32P, _I32P, i32, vp, vp, vp, f32, vp]
+    lib.spex_tree_node_info.argtypes = [vp, i32, C.POINTER(NodeInfo)]
+    lib.spex_tree_path_pages.argtypes = [vp, i32, _I32P, _I32P, i32, _I32P]
+    lib.spex_tree_free_pages.argtypes = [vp, _I32P, i32, _I32P]
+    lib.spex_tree_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.spex_tree_plan_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(PlanView)]
+    lib.spex_tree_gather_kv.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32]
+    lib.spex_tree_set_profiling.argtypes = [vp, i32]
+    lib.spex_tree_last_kernel_ms.argtypes = [vp, C.POINTER(f32)]
+    lib.spex_tree_last_launch_info.argtypes = [vp, C.POINTER(i64)]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("spex_status_string", "spex_last_device_error", "spex_tree_destroy"):
+            fn.restype = C.c_int
+    return lib
+
+
+lib = _load()
+
+
+def _check(status: int):
+    if status != 0:
+        detail = lib.spex_last_device_error().decode() if status == 7 else ""
+        raise SpexError(status, detail)
+
+
+def _i32(seq) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(seq, dtype=np.int32))
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_I32P)
+
+
+def _dev(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream) if torch.cuda.is_available() else None
+
+
+class SpexTree:
+    """One forest over one page pool (spex_tree_t).  Method names follow the C entry points."""
+
+    def __init__(self, num_q_heads: int, num_kv_heads: int, head_dim: int, page_size: int = 16,
+                 q_dtype: str = "bf16", kv_dtype: str = "bf16", num_pages: int = 0,
+                 device="cuda", free_order: Optional[Sequence[int]] = None,
+                 prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0,
+                 host_only: bool = False, pool_fill: Optional[int] = None):
+        self.Hq, self.Hkv, self.D, self.P = num_q_heads, num_kv_heads, head_dim, page_size
+        self.q_dtype, self.kv_dtype = _DTYPES[q_dtype], _DTYPES[kv_dtype]
+        self.num_pages = int(num_pages)
+        self.device = torch.device(device)
+        self.host_only = host_only
+        cfg = Config()
+        cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim = num_q_heads, num_kv_heads, head_dim
+        cfg.page_size, cfg.q_dtype, cfg.kv_dtype = page_size, self.q_dtype, self.kv_dtype
+        cfg.num_pages = self.num_pages
+        cfg.prefix_chunk_pages, cfg.suffix_chunk_pages = prefix_chunk_pages, suffix_chunk_pages
+        cfg.kernel_mode = kernel_mode
+        self.k_pool = self.v_pool = self.k_scale = self.v_scale = None
+        if not host_only:
+            nbytes = C.c_size_t()
+            _check(lib.spex_pool_bytes(C.byref(cfg), C.byref(nbytes)))
+            fill = 0 if pool_fill is None else pool_fill
+            self.k_pool = torch.full((max(nbytes.value, 16),), fill, dtype=torch.uint8, device=self.device)
+            self.v_pool = torch.full((max(nbytes.value, 16),), fill, dtype=torch.uint8, device=self.device)
+            cfg.k_pool, cfg.v_pool = self.k_pool.data_ptr(), self.v_pool.data_ptr()
+            if self.kv_dtype == FP8_E4M3:
+                n = max(self.num_pages * num_kv_heads, 1)
+                self.k_scale = torch.full((n,), float("nan"), dtype=torch.float32, device=self.device)
+                self.v_scale = torch.full((n,), float("nan"), dtype=torch.float32, device=self.device)
+                cfg.k_scale, cfg.v_scale = self.k_scale.data_ptr(), self.v_scale.data_ptr()
+        self._order = None
+        if free_order is not None:
+            self._order = _i32(free_order)
+            cfg.free_order = self._order.ctypes.data_as(_I32P)
+        self._h = C.c_void_p()
+        _check(lib.spex_tree_create(C.byref(cfg), C.byref(self._h)))
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib.spex_tree_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the five calls ------------------------------------------------------------------
+    def fork(self, parent: int, n_children: int) -> List[int]:
+        out = np.empty(max(n_children, 1), dtype=np.int32)
+        _check(lib.spex_tree_fork(self._h, parent, n_children, _ptr(out)))
+        return out[:n_children].tolist()
+
+    def append_step(self, node: int, k: Optional[torch.Tensor], v: Optional[torch.Tensor],
+                    k_scales: Optional[torch.Tensor] = None, v_scales: Optional[torch.Tensor] = None,
+                    n_tokens: Optional[int] = None) -> None:
+        if k is None:
+            _check(lib.spex_tree_append_step(self._h, node, int(n_tokens), None, None, None, None, None))
+            return
+        want = _TORCH_KV[self.kv_dtype]
+        assert k.dtype == want and v.dtype == want, (k.dtype, want)
+        assert k.is_contiguous() and v.is_contiguous() and k.device.type == self.device.type
+        n = k.shape[0]
+        assert tuple(k.shape) == (n, self.Hkv, self.D) and tuple(v.shape) == tuple(k.shape)
+        if k_scales is not None:
+            k_scales = k_scales.to(device=self.device, dtype=torch.float32).contiguous()
+            v_scales = v_scales.to(device=self.device, dtype=torch.float32).contiguous()
+        _check(lib.spex_tree_append_step(self._h, node, n, _dev(k), _dev(v), _dev(k_scales),
+                                         _dev(v_scales), _stream()))
+        # The scatter runs on torch's current stream, so the caching allocator cannot hand the
+        # source buffers to later work before the scatter has read them.
+
+    # name used by the trace replay
+    def append(self, node, k, v, k_scales=None, v_scales=None, n_tokens=None):
+        self.append_step(node, k, v, k_scales, v_scales, n_tokens)
+
+    def prune(self, node: int) -> None:
+        _check(lib.spex_tree_prune(self._h, node))
+
+    def decode_attention(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
+                         q: torch.Tensor, sm_scale: float, out: Optional[torch.Tensor] = None,
+                         lse: Optional[torch.Tensor] = None, want_lse: bool = True):
+        la = _i32(leaves)
+        qa = None if q_lens is None else _i32(q_lens)
+        nq = len(la) if qa is None else int(qa.sum())
+        assert q.is_contiguous() and tuple(q.shape) == (nq, self.Hq, self.D), q.shape
+        assert q.dtype == (torch.float32 if self.q_dtype == F32 else torch.bfloat16)
+        if out is None:
+            out = torch.empty((nq, self.Hq, self.D), dtype=torch.float32, device=q.device)
+        if lse is None and want_lse:
+            lse = torch.empty((nq, self.Hq), dtype=torch.float32, device=q.device)
+        _check(lib.spex_tree_decode_attention(self._h, _ptr(la), _ptr(qa), len(la), _dev(q),
+                                              _dev(out), _dev(lse), float(sm_scale), _stream()))
+        return out, lse
+
+    # ---- introspection -------------------------------------------------------------------
+    def append_new_pages(self, node: int, n_tokens: int) -> int:
+        n = C.c_int32()
+        _check(lib.spex_tree_append_new_pages(self._h, node, n_tokens, C.byref(n)))
+        return n.value
+
+    def node_info(self, node: int) -> dict:
+        info = NodeInfo()
+        _check(lib.spex_tree_node_info(self._h, node, C.byref(info)))
+        return dict(parent=info.parent, n_tokens=info.n_tokens, n_pages=info.n_pages,
+                    n_live_children=info.n_live_children)
+
+    def path_pages(self, node: int):
+        n = C.c_int32()
+        st = lib.spex_tree_path_pages(self._h, node, None, None, 0, C.byref(n))
+        if st not in (0, 8):
+            _check(st)
+        pages = np.empty(max(n.value, 1), dtype=np.int32)
+        valid = np.empty(max(n.value, 1), dtype=np.int32)
+        _check(lib.spex_tree_path_pages(self._h, node, _ptr(pages), _ptr(valid), n.value, C.byref(n)))
+        return pages[:n.value].tolist(), valid[:n.value].tolist()
+
+    def free_pages(self) -> List[int]:
+        n = C.c_int32()
+        st = lib.spex_tree_free_pages(self._h, None, 0, C.byref(n))
+        if st not in (0, 8):
+            _check(st)
+        pages = np.empty(max(n.value, 1), dtype=np.int32)
+        _check(lib.spex_tree_free_pages(self._h, _ptr(pages), n.value, C.byref(n)))
+        return pages[:n.value].tolist()
+
+    def stats(self):
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(lib.spex_tree_stats(self._h, C.byref(a), C.byref(b), C.byref(c)))
+        return a.value, b.value, c.value
+
+    def plan_dump(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]]) -> dict:
+        la = _i32(leaves)
+        qa = None if q_lens is None else _i32(q_lens)
+        v = PlanView()
+        _check(lib.spex_tree_plan_dump(self._h, _ptr(la), _ptr(qa), len(la), C.byref(v)))
+
+        def arr(name, n):
+            p = getattr(v, name)
+            return [] if n == 0 else np.ctypeslib.as_array(p, shape=(n,)).tolist()
+
+        return dict(
+            leaf_indptr=arr("leaf_indptr", v.n_leaves + 1),
+            leaf_pages=arr("leaf_pages", arr("leaf_indptr", v.n_leaves + 1)[-1]),
+            leaf_valid=arr("leaf_valid", arr("leaf_indptr", v.n_leaves + 1)[-1]),
+            qt_limit=arr("qt_limit", v.n_qtok), group_node=arr("group_node", v.n_groups),
+            n_prefix_tasks=v.n_prefix_tasks, n_partial_rows=v.n_partial_rows,
+            task_pg_begin=arr("task_pg_begin", v.n_tasks), task_pg_count=arr("task_pg_count", v.n_tasks),
+            task_qt_begin=arr("task_qt_begin", v.n_tasks), task_qt_count=arr("task_qt_count", v.n_tasks),
+            task_pbase=arr("task_pbase", v.n_tasks), task_flags=arr("task_flags", v.n_tasks),
+            pg_id=arr("pg_id", v.n_pg), pg_valid=arr("pg_valid", v.n_pg), pg_pos=arr("pg_pos", v.n_pg),
+            qt_list=arr("qt_list", v.n_qt_list),
+            part_indptr=arr("part_indptr", v.n_qtok + 1), part_base=arr("part_base", v.n_parts),
+            part_hstride=arr("part_hstride", v.n_parts),
+            prefix_chunk_pages=v.prefix_chunk_pages, suffix_chunk_pages=v.suffix_chunk_pages,
+        )
+
+    def gather_kv(self, node: int, first: int, n: int):
+        dt = _TORCH_KV[self.kv_dtype]
+        k = torch.empty((n, self.Hkv, self.D), dtype=dt, device=self.device)
+        v = torch.empty_like(k)
+        ks = vs = None
+        if self.kv_dtype == FP8_E4M3:
+            ks = torch.empty((n, self.Hkv), dtype=torch.float32, device=self.device)
+            vs = torch.empty_like(ks)
+        _check(lib.spex_tree_gather_kv(self._h, node, first, n, _dev(k), _dev(v), _dev(ks), _dev(vs),
+                                       _stream()))
+        return k, v, ks, vs
+
+    def set_tuning(self, prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0):
+        _check(lib.spex_tree_set_tuning(self._h, prefix_chunk_pages, suffix_chunk_pages, kernel_mode))
+
+    def set_profiling(self, enabled: bool):
+        _check(lib.spex_tree_set_profiling(self._h, int(enabled)))
+
+    def last_kernel_ms(self):
+        ms = (C.c_float * 3)()
+        _check(lib.spex_tree_last_kernel_ms(self._h, ms))
+        return dict(prefix=ms[0], suffix=ms[1], merge=ms[2])
+
+    def last_launch_info(self) -> dict:
+        info = (C.c_int64 * 8)()
+        _check(lib.spex_tree_last_launch_info(self._h, info))
+        names = ["kv_tokens", "prefix_tokens", "suffix_tokens", "prefix_items", "suffix_items",
+                 "partial_rows", "plan_rebuilt"]
+        return {n: info[i] for i, n in enumerate(names)}
+
+
+# ---- functions named like the C entry points ------------------------------------------------
+def spex_tree_create(**kwargs) -> SpexTree:
+    return SpexTree(**kwargs)
+
+
+def spex_tree_destroy(tree: SpexTree) -> None:
+    tree.close()
+
+
+def spex_tree_fork(tree: SpexTree, parent: int, n_children: int) -> List[int]:
+    return tree.fork(parent, n_children)
+
+
+def spex_tree_append_step(tree: SpexTree, node: int, k, v, k_scales=None, v_scales=None,
+                          n_tokens=None) -> None:
+    tree.append_step(node, k, v, k_scales, v_scales, n_tokens)
+
+
+def spex_tree_prune(tree: SpexTree, node: int) -> None:
+    tree.prune(node)
+
+
+def spex_tree_decode_attention(tree: SpexTree, leaves, q_lens, q, sm_scale, out=None, lse=None):
+    return tree.decode_attention(leaves, q_lens, q, sm_scale, out, lse)

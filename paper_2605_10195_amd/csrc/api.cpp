@@ -1,0 +1,635 @@
+// C ABI of the tree decode-attention library: argument checking, the host page table and
+// planner, device workspace management and kernel launches.  See include/spex_tree.h.
+#include "../../include/spex_tree.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+#include "page_table.hpp"
+#include "planner.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+bool hip_failed(hipError_t e, const char *what) {
+  if (e == hipSuccess) return false;
+  g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return true;
+}
+
+#define HIP_TRY(expr)                                      \
+  do {                                                     \
+    if (hip_failed((expr), #expr)) return SPEX_ERR_DEVICE; \
+  } while (0)
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// Device copy of a Plan: one blob, arrays at 256-byte aligned offsets.
+struct DevicePlan {
+  const int32_t *prefix_items = nullptr, *suffix_items = nullptr;
+  const int32_t *task_pg_begin = nullptr, *task_pg_count = nullptr, *task_qt_begin = nullptr,
+                *task_qt_count = nullptr, *task_pbase = nullptr, *task_flags = nullptr;
+  const int32_t *pg_id = nullptr, *pg_valid = nullptr, *pg_pos = nullptr, *qt_list = nullptr,
+                *qt_limit = nullptr;
+  const int32_t *part_indptr = nullptr, *part_base = nullptr, *part_hstride = nullptr;
+};
+
+}  // namespace
+
+struct spex_tree {
+  spex_config_t cfg{};
+  spex::Shape shape{};
+  spex::PageTable *pt = nullptr;
+  spex::Planner planner;
+  spex::Plan plan;
+  bool plan_on_device = false;
+  DevicePlan dplan;
+
+  void *d_plan = nullptr;
+  size_t d_plan_cap = 0;
+  void *h_stage = nullptr;  // pinned
+  size_t h_stage_cap = 0;
+  hipEvent_t stage_event = nullptr;
+  bool stage_pending = false;
+
+  float *d_part_o = nullptr, *d_part_ml = nullptr;
+  int64_t part_cap_rows = 0;
+
+  int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0;
+  bool profiling = false;
+  hipEvent_t prof_ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  bool prof_valid[3] = {false, false, false};
+  int64_t info[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+};
+
+namespace {
+
+spex_status_t check_config(const spex_config_t *c) {
+  if (!c) return SPEX_ERR_INVALID_ARG;
+  if (c->num_q_heads <= 0 || c->num_kv_heads <= 0 || c->num_kv_heads > 255 ||
+      c->num_q_heads % c->num_kv_heads != 0)
+    return SPEX_ERR_INVALID_ARG;
+  if (c->head_dim < 1 || c->head_dim > 256) return SPEX_ERR_INVALID_ARG;
+  if (!is_pow2(c->page_size) || c->page_size > 64) return SPEX_ERR_INVALID_ARG;
+  if (c->num_pages < 0 || c->num_pages > INT32_MAX) return SPEX_ERR_INVALID_ARG;
+  if (c->prefix_chunk_pages < 0 || c->suffix_chunk_pages < 0 || c->reserved != 0)
+    return SPEX_ERR_INVALID_ARG;
+  if (c->kernel_mode != 0 && c->kernel_mode != 1) return SPEX_ERR_INVALID_ARG;
+  const bool ok = (c->q_dtype == SPEX_F32 && c->kv_dtype == SPEX_F32) ||
+                  (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_BF16) ||
+                  (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_FP8_E4M3);
+  if (!ok) return SPEX_ERR_UNSUPPORTED;
+  if ((c->k_pool == nullptr) != (c->v_pool == nullptr)) return SPEX_ERR_INVALID_ARG;
+  if (c->kv_dtype == SPEX_FP8_E4M3 && c->k_pool && (!c->k_scale || !c->v_scale))
+    return SPEX_ERR_INVALID_ARG;
+  return SPEX_OK;
+}
+
+size_t elem_size(int32_t dt) { return dt == SPEX_F32 ? 4 : (dt == SPEX_BF16 ? 2 : 1); }
+
+spex::Shape make_shape(const spex_config_t &c) {
+  spex::Shape s{};
+  s.Hq = c.num_q_heads;
+  s.Hkv = c.num_kv_heads;
+  s.G = c.num_q_heads / c.num_kv_heads;
+  s.D = c.head_dim;
+  s.P = c.page_size;
+  s.q_dtype = c.q_dtype;
+  s.kv_dtype = c.kv_dtype;
+  const bool tiled = c.kv_dtype != SPEX_F32 && c.page_size == 16 && (c.head_dim == 64 || c.head_dim == 128);
+  s.layout = tiled ? spex::kMfmaTiled : spex::kRowMajor;
+  return s;
+}
+
+bool same_request(const spex::Plan &pl, const spex_tree *t, const int32_t *leaves,
+                  const int32_t *q_lens, int32_t n) {
+  if (!pl.valid || pl.table_version != t->pt->version()) return false;
+  if (pl.req_prefix_chunk != t->prefix_chunk || pl.req_suffix_chunk != t->suffix_chunk) return false;
+  if (static_cast<int32_t>(pl.req_leaves.size()) != n) return false;
+  if (n && std::memcmp(pl.req_leaves.data(), leaves, sizeof(int32_t) * n) != 0) return false;
+  if (q_lens) {
+    if (static_cast<int32_t>(pl.req_q_lens.size()) != n) return false;
+    if (n && std::memcmp(pl.req_q_lens.data(), q_lens, sizeof(int32_t) * n) != 0) return false;
+  } else if (!pl.req_q_lens.empty()) {
+    return false;
+  }
+  return true;
+}
+
+spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_lens, int32_t n,
+                        bool *rebuilt) {
+  *rebuilt = false;
+  if (same_request(t->plan, t, leaves, q_lens, n)) return SPEX_OK;
+  *rebuilt = true;
+  t->plan_on_device = false;
+  const spex::PlanError e = t->planner.build(*t->pt, leaves, q_lens, n, t->cfg.num_q_heads,
+                                             t->cfg.num_kv_heads, t->prefix_chunk, t->suffix_chunk,
+                                             &t->plan);
+  switch (e) {
+    case spex::PlanError::kOk: return SPEX_OK;
+    case spex::PlanError::kBadNode: t->plan.valid = false; return SPEX_ERR_BAD_NODE;
+    case spex::PlanError::kEmptyPath: t->plan.valid = false; return SPEX_ERR_EMPTY_PATH;
+    case spex::PlanError::kTooLarge: t->plan.valid = false; return SPEX_ERR_UNSUPPORTED;
+    default: t->plan.valid = false; return SPEX_ERR_INVALID_ARG;
+  }
+}
+
+spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
+  const spex::Plan &pl = t->plan;
+  const std::vector<int32_t> *arrays[] = {
+      &pl.prefix_items, &pl.suffix_items, &pl.task_pg_begin, &pl.task_pg_count, &pl.task_qt_begin,
+      &pl.task_qt_count, &pl.task_pbase, &pl.task_flags, &pl.pg_id, &pl.pg_valid, &pl.pg_pos,
+      &pl.qt_list, &pl.qt_limit, &pl.part_indptr, &pl.part_base, &pl.part_hstride};
+  constexpr int kN = sizeof(arrays) / sizeof(arrays[0]);
+  size_t off[kN], total = 0;
+  for (int i = 0; i < kN; ++i) {
+    off[i] = total;
+    total += align_up(arrays[i]->size() * sizeof(int32_t) + 16, 256);
+  }
+  if (t->stage_pending) {
+    HIP_TRY(hipEventSynchronize(t->stage_event));
+    t->stage_pending = false;
+  }
+  if (total > t->h_stage_cap) {
+    if (t->h_stage) HIP_TRY(hipHostFree(t->h_stage));
+    t->h_stage = nullptr;
+    t->h_stage_cap = 0;
+    const size_t cap = align_up(total + total / 2, 1 << 16);
+    HIP_TRY(hipHostMalloc(&t->h_stage, cap, hipHostMallocDefault));
+    t->h_stage_cap = cap;
+  }
+  if (total > t->d_plan_cap) {
+    if (t->d_plan) HIP_TRY(hipFree(t->d_plan));
+    t->d_plan = nullptr;
+    t->d_plan_cap = 0;
+    const size_t cap = align_up(total + total / 2, 1 << 16);
+    HIP_TRY(hipMalloc(&t->d_plan, cap));
+    t->d_plan_cap = cap;
+  }
+  char *h = static_cast<char *>(t->h_stage);
+  for (int i = 0; i < kN; ++i)
+    if (!arrays[i]->empty())
+      std::memcpy(h + off[i], arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
+  HIP_TRY(hipMemcpyAsync(t->d_plan, t->h_stage, total, hipMemcpyHostToDevice, stream));
+  if (!t->stage_event) HIP_TRY(hipEventCreateWithFlags(&t->stage_event, hipEventDisableTiming));
+  HIP_TRY(hipEventRecord(t->stage_event, stream));
+  t->stage_pending = true;
+  const char *d = static_cast<const char *>(t->d_plan);
+  auto at = [&](int i) { return reinterpret_cast<const int32_t *>(d + off[i]); };
+  DevicePlan &dp = t->dplan;
+  dp.prefix_items = at(0);
+  dp.suffix_items = at(1);
+  dp.task_pg_begin = at(2);
+  dp.task_pg_count = at(3);
+  dp.task_qt_begin = at(4);
+  dp.task_qt_count = at(5);
+  dp.task_pbase = at(6);
+  dp.task_flags = at(7);
+  dp.pg_id = at(8);
+  dp.pg_valid = at(9);
+  dp.pg_pos = at(10);
+  dp.qt_list = at(11);
+  dp.qt_limit = at(12);
+  dp.part_indptr = at(13);
+  dp.part_base = at(14);
+  dp.part_hstride = at(15);
+  t->plan_on_device = true;
+  return SPEX_OK;
+}
+
+spex_status_t ensure_partials(spex_tree *t, int64_t rows) {
+  if (rows <= t->part_cap_rows) return SPEX_OK;
+  if (t->d_part_o) HIP_TRY(hipFree(t->d_part_o));
+  if (t->d_part_ml) HIP_TRY(hipFree(t->d_part_ml));
+  t->d_part_o = t->d_part_ml = nullptr;
+  t->part_cap_rows = 0;
+  const int64_t cap = rows + rows / 4 + 1024;
+  HIP_TRY(hipMalloc(reinterpret_cast<void **>(&t->d_part_o),
+                    static_cast<size_t>(cap) * t->cfg.head_dim * sizeof(float)));
+  HIP_TRY(hipMalloc(reinterpret_cast<void **>(&t->d_part_ml), static_cast<size_t>(cap) * 2 * sizeof(float)));
+  t->part_cap_rows = cap;
+  return SPEX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *spex_status_string(spex_status_t s) {
+  switch (s) {
+    case SPEX_OK: return "ok";
+    case SPEX_ERR_INVALID_ARG: return "invalid argument";
+    case SPEX_ERR_BAD_NODE: return "unknown or pruned node";
+    case SPEX_ERR_NOT_LEAF: return "node has live children";
+    case SPEX_ERR_OOM_PAGES: return "page pool exhausted";
+    case SPEX_ERR_EMPTY_PATH: return "path shorter than the number of queries";
+    case SPEX_ERR_UNSUPPORTED: return "unsupported dtype or shape";
+    case SPEX_ERR_DEVICE: return "HIP error";
+    case SPEX_ERR_CAPACITY: return "output array too small";
+  }
+  return "unknown status";
+}
+
+const char *spex_last_device_error(void) { return g_last_error.c_str(); }
+
+spex_status_t spex_pool_bytes(const spex_config_t *cfg, size_t *bytes_per_pool) {
+  if (!cfg || !bytes_per_pool) return SPEX_ERR_INVALID_ARG;
+  if (cfg->num_pages < 0 || cfg->num_kv_heads <= 0 || cfg->page_size <= 0 || cfg->head_dim <= 0 ||
+      cfg->kv_dtype < 0 || cfg->kv_dtype > 2)
+    return SPEX_ERR_INVALID_ARG;
+  *bytes_per_pool = static_cast<size_t>(cfg->num_pages) * cfg->num_kv_heads * cfg->page_size *
+                    cfg->head_dim * elem_size(cfg->kv_dtype);
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_create(const spex_config_t *cfg, spex_tree_t **out) {
+  if (!out) return SPEX_ERR_INVALID_ARG;
+  const spex_status_t st = check_config(cfg);
+  if (st != SPEX_OK) return st;
+  if (cfg->free_order) {
+    std::vector<char> seen(static_cast<size_t>(cfg->num_pages), 0);
+    for (int64_t i = 0; i < cfg->num_pages; ++i) {
+      const int32_t p = cfg->free_order[i];
+      if (p < 0 || p >= cfg->num_pages || seen[p]) return SPEX_ERR_INVALID_ARG;
+      seen[p] = 1;
+    }
+  }
+  spex_tree *t = new (std::nothrow) spex_tree();
+  if (!t) return SPEX_ERR_INVALID_ARG;
+  t->cfg = *cfg;
+  t->shape = make_shape(*cfg);
+  t->pt = new (std::nothrow) spex::PageTable(cfg->num_pages, cfg->page_size, cfg->free_order);
+  if (!t->pt) {
+    delete t;
+    return SPEX_ERR_INVALID_ARG;
+  }
+  t->cfg.free_order = nullptr;
+  t->prefix_chunk = cfg->prefix_chunk_pages;
+  t->suffix_chunk = cfg->suffix_chunk_pages;
+  t->kernel_mode = cfg->kernel_mode;
+  *out = t;
+  return SPEX_OK;
+}
+
+void spex_tree_destroy(spex_tree_t *t) {
+  if (!t) return;
+  const bool used_device = t->d_plan || t->d_part_o || t->h_stage || t->stage_event || t->prof_ev[0];
+  if (used_device) (void)hipDeviceSynchronize();
+  if (t->d_plan) (void)hipFree(t->d_plan);
+  if (t->d_part_o) (void)hipFree(t->d_part_o);
+  if (t->d_part_ml) (void)hipFree(t->d_part_ml);
+  if (t->h_stage) (void)hipHostFree(t->h_stage);
+  if (t->stage_event) (void)hipEventDestroy(t->stage_event);
+  for (hipEvent_t e : t->prof_ev)
+    if (e) (void)hipEventDestroy(e);
+  delete t->pt;
+  delete t;
+}
+
+spex_status_t spex_tree_fork(spex_tree_t *t, spex_node_t parent, int32_t n_children,
+                             spex_node_t *out_children) {
+  if (!t || n_children < 0 || (n_children > 0 && !out_children)) return SPEX_ERR_INVALID_ARG;
+  if (parent != SPEX_NO_NODE && !t->pt->valid(parent)) return SPEX_ERR_BAD_NODE;
+  if (static_cast<int64_t>(t->pt->num_nodes()) + n_children > INT32_MAX) return SPEX_ERR_UNSUPPORTED;
+  if (n_children == 0) return SPEX_OK;
+  const int32_t first = t->pt->fork(parent, n_children);
+  for (int32_t i = 0; i < n_children; ++i) out_children[i] = first + i;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_append_new_pages(const spex_tree_t *t, spex_node_t node, int32_t n_tokens,
+                                         int32_t *n_new_pages) {
+  if (!t || !n_new_pages || n_tokens < 0) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  *n_new_pages = t->pt->new_pages_needed(node, n_tokens);
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_tokens,
+                                    const void *k, const void *v, const float *k_scales,
+                                    const float *v_scales, void *hip_stream) {
+  if (!t || n_tokens < 0 || ((k == nullptr) != (v == nullptr))) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  if (t->pt->node(node).n_live_children > 0) return SPEX_ERR_NOT_LEAF;
+  if (k && !t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
+  if (n_tokens == 0) return SPEX_OK;
+  const int32_t P = t->cfg.page_size;
+  const int32_t old_tokens = t->pt->node(node).n_tokens;
+  if (static_cast<int64_t>(old_tokens) + n_tokens > INT32_MAX / 2) return SPEX_ERR_UNSUPPORTED;
+  const int32_t need = t->pt->new_pages_needed(node, n_tokens);
+  if (k && t->cfg.kv_dtype == SPEX_FP8_E4M3 && need > 0 && (!k_scales || !v_scales))
+    return SPEX_ERR_INVALID_ARG;
+  int32_t first_new = 0;
+  if (!t->pt->append(node, n_tokens, &first_new)) return SPEX_ERR_OOM_PAGES;
+  if (!k) return SPEX_OK;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const spex::Node &nd = t->pt->node(node);
+  const int32_t new_total = old_tokens + n_tokens;
+  const int32_t page_lo = old_tokens / P;  // first page written (continuing or new)
+  const int32_t page_hi = (new_total + P - 1) / P;
+  const size_t tok_bytes = static_cast<size_t>(t->cfg.num_kv_heads) * t->cfg.head_dim *
+                           elem_size(t->cfg.kv_dtype);
+  for (int32_t pa = page_lo; pa < page_hi; pa += spex::kMaxPagesPerScatter) {
+    const int32_t pb = pa + spex::kMaxPagesPerScatter < page_hi ? pa + spex::kMaxPagesPerScatter : page_hi;
+    spex::ScatterArgs a{};
+    a.k_pool = t->cfg.k_pool;
+    a.v_pool = t->cfg.v_pool;
+    a.k_scale = t->cfg.k_scale;
+    a.v_scale = t->cfg.v_scale;
+    const int32_t tok_a = old_tokens > pa * P ? old_tokens : pa * P;
+    const int32_t tok_b = new_total < pb * P ? new_total : pb * P;
+    a.k_src = static_cast<const char *>(k) + static_cast<size_t>(tok_a - old_tokens) * tok_bytes;
+    a.v_src = static_cast<const char *>(v) + static_cast<size_t>(tok_a - old_tokens) * tok_bytes;
+    a.n_pages = pb - pa;
+    a.first_slot = tok_a - pa * P;
+    a.n_tokens = tok_b - tok_a;
+    a.first_page_is_new = pa >= first_new ? 1 : 0;
+    const int32_t first_new_in_launch = a.first_page_is_new ? pa : pa + 1;
+    if (k_scales) {
+      a.k_scale_src = k_scales + static_cast<size_t>(first_new_in_launch - first_new) * t->cfg.num_kv_heads;
+      a.v_scale_src = v_scales + static_cast<size_t>(first_new_in_launch - first_new) * t->cfg.num_kv_heads;
+    }
+    for (int32_t i = 0; i < a.n_pages; ++i) a.page_ids[i] = nd.pages[pa + i];
+    HIP_TRY(spex::launch_scatter(t->shape, a, stream));
+  }
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_prune(spex_tree_t *t, spex_node_t node) {
+  if (!t) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  t->pt->prune(node);
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leaves,
+                                         const int32_t *q_lens, int32_t n_leaves, const void *q,
+                                         float *out, float *lse, float sm_scale, void *hip_stream) {
+  if (!t || n_leaves < 0 || (n_leaves > 0 && (!leaves || !q || !out))) return SPEX_ERR_INVALID_ARG;
+  if (!t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
+  if (!(sm_scale == sm_scale) || std::isinf(sm_scale)) return SPEX_ERR_INVALID_ARG;
+  if (n_leaves == 0) return SPEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  bool rebuilt = false;
+  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &rebuilt);
+  if (st != SPEX_OK) return st;
+  if (!t->plan_on_device) {
+    const spex_status_t us = upload_plan(t, stream);
+    if (us != SPEX_OK) return us;
+  }
+  const spex::Plan &pl = t->plan;
+  const spex_status_t ps = ensure_partials(t, pl.n_partial_rows);
+  if (ps != SPEX_OK) return ps;
+
+  const DevicePlan &dp = t->dplan;
+  spex::AttnArgs a{};
+  a.k_pool = t->cfg.k_pool;
+  a.v_pool = t->cfg.v_pool;
+  a.k_scale = t->cfg.k_scale;
+  a.v_scale = t->cfg.v_scale;
+  a.q = q;
+  a.task_pg_begin = dp.task_pg_begin;
+  a.task_pg_count = dp.task_pg_count;
+  a.task_qt_begin = dp.task_qt_begin;
+  a.task_qt_count = dp.task_qt_count;
+  a.task_pbase = dp.task_pbase;
+  a.task_flags = dp.task_flags;
+  a.pg_id = dp.pg_id;
+  a.pg_valid = dp.pg_valid;
+  a.pg_pos = dp.pg_pos;
+  a.qt_list = dp.qt_list;
+  a.qt_limit = dp.qt_limit;
+  a.part_o = t->d_part_o;
+  a.part_ml = t->d_part_ml;
+  a.scale_log2 = sm_scale * 1.4426950408889634f;
+  const bool generic = t->kernel_mode == 1;
+
+  if (t->profiling) {
+    for (hipEvent_t &e : t->prof_ev)
+      if (!e) HIP_TRY(hipEventCreate(&e));
+    for (bool &b : t->prof_valid) b = false;
+  }
+  auto bracket = [&](int which, bool begin) -> hipError_t {
+    if (!t->profiling) return hipSuccess;
+    return hipEventRecord(t->prof_ev[2 * which + (begin ? 0 : 1)], stream);
+  };
+
+  const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / 2);
+  const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / 2);
+  if (n_prefix_items > 0) {
+    a.items = dp.prefix_items;
+    a.n_items = n_prefix_items;
+    HIP_TRY(bracket(0, true));
+    HIP_TRY(spex::launch_attention(t->shape, a, true, pl.prefix_row_tiles, generic, stream));
+    HIP_TRY(bracket(0, false));
+    t->prof_valid[0] = t->profiling;
+  }
+  if (n_suffix_items > 0) {
+    a.items = dp.suffix_items;
+    a.n_items = n_suffix_items;
+    HIP_TRY(bracket(1, true));
+    HIP_TRY(spex::launch_attention(t->shape, a, false, pl.suffix_row_tiles, generic, stream));
+    HIP_TRY(bracket(1, false));
+    t->prof_valid[1] = t->profiling;
+  }
+  spex::MergeArgs m{};
+  m.part_indptr = dp.part_indptr;
+  m.part_base = dp.part_base;
+  m.part_hstride = dp.part_hstride;
+  m.part_o = t->d_part_o;
+  m.part_ml = t->d_part_ml;
+  m.out = out;
+  m.lse = lse;
+  m.n_qtok = static_cast<int32_t>(pl.qt_limit.size());
+  HIP_TRY(bracket(2, true));
+  HIP_TRY(spex::launch_merge(t->shape, m, stream));
+  HIP_TRY(bracket(2, false));
+  t->prof_valid[2] = t->profiling;
+
+  t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
+  t->info[1] = pl.prefix_tokens;
+  t->info[2] = pl.suffix_tokens;
+  t->info[3] = n_prefix_items;
+  t->info[4] = n_suffix_items;
+  t->info[5] = pl.n_partial_rows;
+  t->info[6] = rebuilt ? 1 : 0;
+  t->info[7] = 0;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_node_info(const spex_tree_t *t, spex_node_t node, spex_node_info_t *out) {
+  if (!t || !out) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  const spex::Node &nd = t->pt->node(node);
+  out->parent = nd.parent;
+  out->n_tokens = nd.n_tokens;
+  out->n_pages = static_cast<int32_t>(nd.pages.size());
+  out->n_live_children = nd.n_live_children;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_path_pages(const spex_tree_t *t, spex_node_t node, int32_t *pages,
+                                   int32_t *valid, int32_t cap, int32_t *n) {
+  if (!t || !n || cap < 0 || (cap > 0 && (!pages || !valid))) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  std::vector<int32_t> chain;
+  int64_t total = 0;
+  for (int32_t u = node; u != spex::kNoNode; u = t->pt->node(u).parent) {
+    chain.push_back(u);
+    total += static_cast<int64_t>(t->pt->node(u).pages.size());
+  }
+  *n = static_cast<int32_t>(total);
+  if (total > cap) return SPEX_ERR_CAPACITY;
+  int32_t w = 0;
+  for (auto it = chain.rbegin(); it != chain.rend(); ++it) {
+    const spex::Node &nd = t->pt->node(*it);
+    for (size_t i = 0; i < nd.pages.size(); ++i) {
+      pages[w] = nd.pages[i];
+      valid[w] = t->pt->page_valid(*it, static_cast<int32_t>(i));
+      ++w;
+    }
+  }
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_free_pages(const spex_tree_t *t, int32_t *pages, int32_t cap, int32_t *n) {
+  if (!t || !n || cap < 0 || (cap > 0 && !pages)) return SPEX_ERR_INVALID_ARG;
+  const std::vector<int32_t> fl = t->pt->free_list();
+  *n = static_cast<int32_t>(fl.size());
+  if (static_cast<int64_t>(fl.size()) > cap) return SPEX_ERR_CAPACITY;
+  if (!fl.empty()) std::memcpy(pages, fl.data(), fl.size() * sizeof(int32_t));
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_stats(const spex_tree_t *t, int64_t *live_nodes, int64_t *used_pages,
+                              int64_t *free_pages) {
+  if (!t) return SPEX_ERR_INVALID_ARG;
+  if (live_nodes) *live_nodes = t->pt->live_nodes();
+  if (used_pages) *used_pages = t->pt->used_pages();
+  if (free_pages) *free_pages = t->pt->free_pages();
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_plan_dump(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
+                                  int32_t n_leaves, spex_plan_view_t *out) {
+  if (!t || !out || n_leaves < 0 || (n_leaves > 0 && !leaves)) return SPEX_ERR_INVALID_ARG;
+  bool rebuilt = false;
+  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &rebuilt);
+  if (st != SPEX_OK) return st;
+  const spex::Plan &pl = t->plan;
+  spex_plan_view_t v{};
+  v.n_leaves = n_leaves;
+  v.n_qtok = static_cast<int32_t>(pl.qt_limit.size());
+  v.n_groups = static_cast<int32_t>(pl.group_node.size());
+  v.n_tasks = static_cast<int32_t>(pl.task_pbase.size());
+  v.n_prefix_tasks = pl.n_prefix_tasks;
+  v.n_pg = static_cast<int32_t>(pl.pg_id.size());
+  v.n_qt_list = static_cast<int32_t>(pl.qt_list.size());
+  v.n_parts = static_cast<int32_t>(pl.part_base.size());
+  v.n_partial_rows = pl.n_partial_rows;
+  v.prefix_chunk_pages = pl.prefix_chunk_pages;
+  v.suffix_chunk_pages = pl.suffix_chunk_pages;
+  v.leaf_indptr = pl.leaf_indptr.data();
+  v.leaf_pages = pl.leaf_pages.data();
+  v.leaf_valid = pl.leaf_valid.data();
+  v.qt_limit = pl.qt_limit.data();
+  v.group_node = pl.group_node.data();
+  v.task_pg_begin = pl.task_pg_begin.data();
+  v.task_pg_count = pl.task_pg_count.data();
+  v.task_qt_begin = pl.task_qt_begin.data();
+  v.task_qt_count = pl.task_qt_count.data();
+  v.task_pbase = pl.task_pbase.data();
+  v.task_flags = pl.task_flags.data();
+  v.pg_id = pl.pg_id.data();
+  v.pg_valid = pl.pg_valid.data();
+  v.pg_pos = pl.pg_pos.data();
+  v.qt_list = pl.qt_list.data();
+  v.part_indptr = pl.part_indptr.data();
+  v.part_base = pl.part_base.data();
+  v.part_hstride = pl.part_hstride.data();
+  *out = v;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_gather_kv(spex_tree_t *t, spex_node_t node, int32_t first, int32_t n,
+                                  void *k_out, void *v_out, float *k_scale_out, float *v_scale_out,
+                                  void *hip_stream) {
+  if (!t || first < 0 || n < 0 || (n > 0 && (!k_out || !v_out))) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  if (!t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
+  const spex::Node &nd = t->pt->node(node);
+  if (static_cast<int64_t>(first) + n > nd.n_tokens) return SPEX_ERR_INVALID_ARG;
+  if (n == 0) return SPEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int32_t P = t->cfg.page_size;
+  const size_t tok_bytes = static_cast<size_t>(t->cfg.num_kv_heads) * t->cfg.head_dim *
+                           elem_size(t->cfg.kv_dtype);
+  const int32_t page_lo = first / P, page_hi = (first + n + P - 1) / P;
+  for (int32_t pa = page_lo; pa < page_hi; pa += spex::kMaxPagesPerScatter) {
+    const int32_t pb = pa + spex::kMaxPagesPerScatter < page_hi ? pa + spex::kMaxPagesPerScatter : page_hi;
+    spex::GatherArgs a{};
+    a.k_pool = t->cfg.k_pool;
+    a.v_pool = t->cfg.v_pool;
+    a.k_scale = t->cfg.k_scale;
+    a.v_scale = t->cfg.v_scale;
+    const int32_t tok_a = first > pa * P ? first : pa * P;
+    const int32_t tok_b = first + n < pb * P ? first + n : pb * P;
+    const size_t done = static_cast<size_t>(tok_a - first);
+    a.k_out = static_cast<char *>(k_out) + done * tok_bytes;
+    a.v_out = static_cast<char *>(v_out) + done * tok_bytes;
+    a.k_scale_out = k_scale_out ? k_scale_out + done * t->cfg.num_kv_heads : nullptr;
+    a.v_scale_out = v_scale_out ? v_scale_out + done * t->cfg.num_kv_heads : nullptr;
+    a.n_pages = pb - pa;
+    a.first_slot = tok_a - pa * P;
+    a.n_tokens = tok_b - tok_a;
+    for (int32_t i = 0; i < a.n_pages; ++i) a.page_ids[i] = nd.pages[pa + i];
+    HIP_TRY(spex::launch_gather(t->shape, a, stream));
+  }
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
+                                   int32_t suffix_chunk_pages, int32_t kernel_mode) {
+  if (!t || prefix_chunk_pages < 0 || suffix_chunk_pages < 0 || (kernel_mode != 0 && kernel_mode != 1))
+    return SPEX_ERR_INVALID_ARG;
+  t->prefix_chunk = prefix_chunk_pages;
+  t->suffix_chunk = suffix_chunk_pages;
+  t->kernel_mode = kernel_mode;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_set_profiling(spex_tree_t *t, int32_t enabled) {
+  if (!t) return SPEX_ERR_INVALID_ARG;
+  t->profiling = enabled != 0;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_last_kernel_ms(spex_tree_t *t, float ms[3]) {
+  if (!t || !ms) return SPEX_ERR_INVALID_ARG;
+  float r[3] = {0.f, 0.f, 0.f};
+  for (int i = 0; i < 3; ++i) {
+    if (!t->prof_valid[i]) continue;
+    HIP_TRY(hipEventSynchronize(t->prof_ev[2 * i + 1]));
+    HIP_TRY(hipEventElapsedTime(&r[i], t->prof_ev[2 * i], t->prof_ev[2 * i + 1]));
+  }
+  for (int i = 0; i < 3; ++i) ms[i] = r[i];
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_last_launch_info(const spex_tree_t *t, int64_t info[8]) {
+  if (!t || !info) return SPEX_ERR_INVALID_ARG;
+  for (int i = 0; i < 8; ++i) info[i] = t->info[i];
+  return SPEX_OK;
+}
+
+}  // extern "C"

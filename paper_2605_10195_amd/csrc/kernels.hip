@@ -1,0 +1,646 @@
+// HIP kernels for tree decode attention on gfx950 (CDNA4, 64-lane wavefronts).
+//
+//   spex_prefix_attn_kernel / spex_suffix_attn_kernel
+//       One wavefront per work item = (task, kv head, row tile).  A task is a run of KV pages
+//       (a chunk of a shared-prefix group or of a private suffix) and a set of query rows; the
+//       wavefront streams the pages once, contracts them against its rows on the matrix cores
+//       (S^T = K Q^T and O^T = V^T P^T with MFMA 16x16x32 bf16, fp32 accumulation), keeps an
+//       online softmax per row and emits the partial state (m, l, o).  The shared-prefix kernel
+//       stacks the rows of all branches below a node, so the node's pages are read once for all
+//       of them; the suffix kernel has the few rows of one branch and is bound by HBM bandwidth.
+//   spex_generic_attn_kernel
+//       Same contract without matrix cores, for fp32 KV and shapes the MFMA kernels do not cover.
+//   spex_lse_merge_kernel
+//       Combines the partial states of every query row (log-sum-exp rule) and normalises.
+//   spex_scatter_kv_kernel / spex_gather_kv_kernel
+//       Write appended tokens into / read tokens out of the paged pool.
+#include "kernels.hpp"
+
+#include <climits>
+
+namespace spex {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kNegInf = -__builtin_huge_valf();
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- element offsets inside a (page, kv head) tile ------------------------------------------
+template <int KV, int LAYOUT>
+__device__ __forceinline__ int k_offset(int t, int d, int D) {
+  if (LAYOUT == kRowMajor) return t * D + d;
+  const int tt = 4 * (t >> 3) + (t & 3);
+  if (KV == kFP8)
+    return ((t >> 2) & 1) * 8 * D + (d >> 6) * 512 + ((d & 31) >> 3) * 128 + tt * 16 +
+           ((d >> 5) & 1) * 8 + (d & 7);
+  return ((t >> 2) & 1) * 8 * D + (d >> 5) * 256 + ((d & 31) >> 3) * 64 + tt * 8 + (d & 7);
+}
+
+template <int KV, int LAYOUT>
+__device__ __forceinline__ int v_offset(int t, int d, int D) {
+  if (LAYOUT == kRowMajor) return t * D + d;
+  if (KV == kFP8)
+    return (d >> 5) * 512 + (t >> 3) * 256 + (d & 15) * 16 + ((d >> 4) & 1) * 8 + (t & 7);
+  return (d >> 4) * 256 + (t >> 3) * 128 + (d & 15) * 8 + (t & 7);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+  return __builtin_bit_cast(float, static_cast<uint32_t>(b) << 16);
+}
+
+// OCP e4m3fn code -> fp32 (exact).
+__device__ __forceinline__ float e4m3_to_float(uint8_t c) {
+  const f32x2 r = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(c), false);
+  return r[0];
+}
+
+template <int KV>
+__device__ __forceinline__ float load_elem(const void *base, int64_t idx) {
+  if (KV == kF32) return static_cast<const float *>(base)[idx];
+  if (KV == kBF16) return bf16_bits_to_float(static_cast<const uint16_t *>(base)[idx]);
+  return e4m3_to_float(static_cast<const uint8_t *>(base)[idx]);
+}
+
+template <int KV>
+__device__ __forceinline__ constexpr int elem_size() {
+  return KV == kF32 ? 4 : (KV == kBF16 ? 2 : 1);
+}
+
+// ---- MFMA attention ------------------------------------------------------------------------
+// Two fp32 -> one dword of two bf16 (truncation): low half from a, high half from b.
+__device__ __forceinline__ uint32_t pack_hi16(float a, float b) {
+  return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, a),
+                               0x07060302u);
+}
+
+// Eight e4m3 codes (two dwords) -> eight bf16 (exact: 3 mantissa bits fit in 7).
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w0), false);
+  const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w0), true);
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w1), false);
+  const f32x2 d = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w1), true);
+  u32x4 r;
+  r[0] = pack_hi16(a[0], a[1]);
+  r[1] = pack_hi16(b[0], b[1]);
+  r[2] = pack_hi16(c[0], c[1]);
+  r[3] = pack_hi16(d[0], d[1]);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Raw 128-bit pieces of one 32-token block (two pages) of one kv head, as loaded.
+template <int KV, int D>
+struct RawBlock {
+  static constexpr int NK = (KV == kFP8) ? D / 64 : D / 32;  // loads per K half-tile
+  static constexpr int NV = (KV == kFP8) ? D / 32 : D / 16;
+  u32x4 k[2][NK];
+  u32x4 v[NV];
+  int valid_a, valid_b, pos_a, pos_b;
+  float ks, vs;  // this lane's page scales (fp8), else 1
+};
+
+template <int KV, int D, int NT>
+__device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh, int item) {
+  constexpr int ESZ = (KV == kFP8) ? 1 : 2;
+  constexpr int TILE_BYTES = 16 * D * ESZ;
+  const int lane = threadIdx.x & 63;
+  const int m16 = lane & 15;
+  const int jj = lane >> 4;
+
+  const int task = uniform(p.items[2 * item]);
+  const int packed = uniform(p.items[2 * item + 1]);
+  const int g = packed & 0xff;
+  const int rt = packed >> 8;
+  const int pg_begin = uniform(p.task_pg_begin[task]);
+  const int pg_count = uniform(p.task_pg_count[task]);
+  const int qt_begin = uniform(p.task_qt_begin[task]);
+  const int qt_count = uniform(p.task_qt_count[task]);
+  const int pbase = uniform(p.task_pbase[task]);
+  const bool task_masked = (uniform(p.task_flags[task]) & 1) != 0;
+  const int G = sh.G;
+  const int rows = qt_count * G;
+  const int row0 = rt * 16 * NT;
+
+  // Query operand: lane (row n = lane%16, k-group j = lane/16) holds dims s*32 + 8j .. +7.
+  bf16x8 qf[NT][D / 32];
+  int limit[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int r = row0 + nt * 16 + m16;
+    limit[nt] = INT_MAX;
+    if (r < rows) {
+      const int qt = p.qt_list[qt_begin + r / G];
+      const int hh = r % G;
+      limit[nt] = p.qt_limit[qt];
+      const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
+                           (static_cast<int64_t>(qt) * sh.Hq + g * G + hh) * D + jj * 8;
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s)
+        qf[nt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + s * 32));
+    } else {
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s) qf[nt][s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    }
+  }
+
+  f32x4 o_acc[NT][D / 16];
+  float m_run[NT], l_run[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    m_run[nt] = kNegInf;
+    l_run[nt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const char *kpool = static_cast<const char *>(p.k_pool);
+  const char *vpool = static_cast<const char *>(p.v_pool);
+  // Byte offset of this lane inside a K half-tile / a V tile.
+  const int k_lane_off = jj * (64 * ESZ * (KV == kFP8 ? 2 : 1)) + (m16 & 7) * 16;
+  const int v_lane_off = (jj & 1) * 256 + m16 * 16;
+  const int nblk = (pg_count + 1) >> 1;
+
+  auto load_block = [&](RawBlock<KV, D> &rb, int b) {
+    const int ia = pg_begin + 2 * b;
+    const bool has_b = 2 * b + 1 < pg_count;
+    const int ib = has_b ? ia + 1 : ia;
+    const int pid_a = uniform(p.pg_id[ia]);
+    const int pid_b = uniform(p.pg_id[ib]);
+    rb.valid_a = uniform(p.pg_valid[ia]);
+    rb.valid_b = has_b ? uniform(p.pg_valid[ib]) : 0;
+    rb.pos_a = uniform(p.pg_pos[ia]);
+    rb.pos_b = uniform(p.pg_pos[ib]);
+    const int64_t tile_a = (static_cast<int64_t>(pid_a) * sh.Hkv + g);
+    const int64_t tile_b = (static_cast<int64_t>(pid_b) * sh.Hkv + g);
+    const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
+    const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < RawBlock<KV, D>::NK; ++s)
+        rb.k[t][s] = *reinterpret_cast<const u32x4 *>(kp + t * (TILE_BYTES / 2) + s * 512);
+#pragma unroll
+    for (int s = 0; s < RawBlock<KV, D>::NV; ++s)
+      rb.v[s] = *reinterpret_cast<const u32x4 *>(vp + s * 512);
+    if (KV == kFP8) {
+      rb.ks = p.k_scale[(jj < 2 ? tile_a : tile_b)];
+      rb.vs = p.v_scale[(jj < 2 ? tile_a : tile_b)];
+    } else {
+      rb.ks = 1.f;
+      rb.vs = 1.f;
+    }
+  };
+
+  auto compute_block = [&](const RawBlock<KV, D> &rb) {
+    bf16x8 kf[2][D / 32];
+    bf16x8 vf[D / 16];
+    if (KV == kFP8) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < D / 64; ++s) {
+          kf[t][2 * s] = fp8x8_to_bf16x8(rb.k[t][s][0], rb.k[t][s][1]);
+          kf[t][2 * s + 1] = fp8x8_to_bf16x8(rb.k[t][s][2], rb.k[t][s][3]);
+        }
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s) {
+        vf[2 * s] = fp8x8_to_bf16x8(rb.v[s][0], rb.v[s][1]);
+        vf[2 * s + 1] = fp8x8_to_bf16x8(rb.v[s][2], rb.v[s][3]);
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, rb.k[t][s]);
+#pragma unroll
+      for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
+    }
+    const bool masked = task_masked || rb.valid_b == 0;
+    // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
+    const int pg_valid_l = jj < 2 ? rb.valid_a : rb.valid_b;
+    const int pg_pos_l = jj < 2 ? rb.pos_a : rb.pos_b;
+    const float c = p.scale_log2 * rb.ks;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s) {
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt][s], sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt][s], sb, 0, 0, 0);
+      }
+      float x[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[i] = sa[i] * c;
+        x[4 + i] = sb[i] * c;
+      }
+      if (masked) {
+        int vis = limit[nt] - pg_pos_l;
+        vis = vis < pg_valid_l ? vis : pg_valid_l;
+        vis -= 8 * (jj & 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+      }
+      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                       fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[nt], mx);
+      const float m_safe = m_new == kNegInf ? 0.f : m_new;
+      const float alpha = fast_exp2(m_run[nt] - m_safe);
+      float pr[8];
+      float lsum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pr[i] = fast_exp2(x[i] - m_safe);
+        lsum += pr[i];
+      }
+      l_run[nt] = l_run[nt] * alpha + lsum;
+      m_run[nt] = m_new;
+      if (!__all(alpha == 1.0f)) {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] *= alpha;
+      }
+      // P as two bf16 pieces (hi + lo) so that the product keeps ~16 bits of each weight.
+      u32x4 phi, plo;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a0 = pr[2 * i] * rb.vs, a1 = pr[2 * i + 1] * rb.vs;
+        const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
+        const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
+        phi[i] = pack_hi16(h0, h1);
+        plo[i] = pack_hi16(a0 - h0, a1 - h1);
+      }
+      const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
+      const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) {
+        o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, o_acc[nt][dt], 0, 0, 0);
+        o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, o_acc[nt][dt], 0, 0, 0);
+      }
+    }
+  };
+
+  RawBlock<KV, D> r0, r1;
+  load_block(r0, 0);
+  for (int b = 0; b < nblk; b += 2) {
+    const bool more1 = b + 1 < nblk;
+    if (more1) load_block(r1, b + 1);
+    compute_block(r0);
+    if (more1) {
+      if (b + 2 < nblk) load_block(r0, b + 2);
+      compute_block(r1);
+    }
+  }
+
+  // Partial state: lanes of one row agree on m; l is summed over the four k-groups.
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float l = l_run[nt];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int r = row0 + nt * 16 + m16;
+    if (r < rows) {
+      const int64_t slot = static_cast<int64_t>(pbase) + static_cast<int64_t>(g) * rows + r;
+      if (jj == 0) {
+        p.part_ml[slot * 2] = m_run[nt];
+        p.part_ml[slot * 2 + 1] = l;
+      }
+      float *op = p.part_o + slot * D + jj * 4;
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(op + dt * 16) = o_acc[nt][dt];
+    }
+  }
+}
+
+template <int KV, int D, int NT>
+__global__ __launch_bounds__(256) void spex_prefix_attn_kernel(AttnArgs p, Shape sh) {
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item < p.n_items) attn_wave<KV, D, NT>(p, sh, item);
+}
+
+template <int KV, int D, int NT>
+__global__ __launch_bounds__(256) void spex_suffix_attn_kernel(AttnArgs p, Shape sh) {
+  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item < p.n_items) attn_wave<KV, D, NT>(p, sh, item);
+}
+
+// ---- generic attention (no matrix cores) ------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// One wavefront per work item; rows of the item one after the other.  Lane = token for the
+// scores, lane = dim (d, d+64, ..) for the weighted sum.
+template <int KV, int QT, int LAYOUT>
+__global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape sh, int rows_per_item) {
+  __shared__ float qs[256];
+  const int item = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int task = p.items[2 * item];
+  const int packed = p.items[2 * item + 1];
+  const int g = packed & 0xff;
+  const int rt = packed >> 8;
+  const int pg_begin = p.task_pg_begin[task];
+  const int pg_count = p.task_pg_count[task];
+  const int qt_begin = p.task_qt_begin[task];
+  const int qt_count = p.task_qt_count[task];
+  const int pbase = p.task_pbase[task];
+  const int D = sh.D, P = sh.P, G = sh.G;
+  const int rows = qt_count * G;
+  const int64_t tile_elems = static_cast<int64_t>(P) * D;
+  const int n_tok_slots = pg_count * P;
+  const int r_end = min(rows, (rt + 1) * rows_per_item);
+
+  for (int r = rt * rows_per_item; r < r_end; ++r) {
+    const int qt = p.qt_list[qt_begin + r / G];
+    const int hh = r % G;
+    const int limit = p.qt_limit[qt];
+    const int64_t qbase = (static_cast<int64_t>(qt) * sh.Hq + g * G + hh) * D;
+    __syncthreads();
+    for (int d = lane; d < D; d += 64) qs[d] = load_elem<QT>(p.q, qbase + d);
+    __syncthreads();
+
+    float m = kNegInf, l = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int t0 = 0; t0 < n_tok_slots; t0 += 64) {
+      const int ti = t0 + lane;
+      const int e = pg_begin + ti / P;
+      const int slot = ti % P;
+      bool ok = ti < n_tok_slots;
+      float s = kNegInf;
+      if (ok) ok = slot < p.pg_valid[e] && p.pg_pos[e] + slot < limit;
+      if (ok) {
+        const int64_t tile = (static_cast<int64_t>(p.pg_id[e]) * sh.Hkv + g);
+        float dot = 0.f;
+        for (int d = 0; d < D; ++d)
+          dot += qs[d] * load_elem<KV>(p.k_pool, tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D));
+        if (KV == kFP8) dot *= p.k_scale[tile];
+        s = dot * p.scale_log2;
+      }
+      const float m_new = fmaxf(m, wave_max(s));
+      if (m_new == kNegInf) continue;
+      const float alpha = fast_exp2(m - m_new);
+      const float pw = ok ? fast_exp2(s - m_new) : 0.f;
+      l = l * alpha + wave_sum(pw);
+      m = m_new;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[c] *= alpha;
+      const int n_here = min(64, n_tok_slots - t0);
+      for (int t = 0; t < n_here; ++t) {
+        const float pt = __shfl(pw, t);
+        if (pt == 0.f) continue;
+        const int e2 = pg_begin + (t0 + t) / P;
+        const int slot2 = (t0 + t) % P;
+        const int64_t tile = (static_cast<int64_t>(p.pg_id[e2]) * sh.Hkv + g);
+        const float w = (KV == kFP8) ? pt * p.v_scale[tile] : pt;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const int d = lane + 64 * c;
+          if (d < D)
+            acc[c] += w * load_elem<KV>(p.v_pool, tile * tile_elems + v_offset<KV, LAYOUT>(slot2, d, D));
+        }
+      }
+    }
+    const int64_t out_slot = static_cast<int64_t>(pbase) + static_cast<int64_t>(g) * rows + r;
+    if (lane == 0) {
+      p.part_ml[out_slot * 2] = m;
+      p.part_ml[out_slot * 2 + 1] = l;
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int d = lane + 64 * c;
+      if (d < D) p.part_o[out_slot * D + d] = acc[c];
+    }
+  }
+}
+
+// ---- merge -----------------------------------------------------------------------------------
+// Thread = (query token, query head, VEC consecutive dims).
+template <int VEC>
+__global__ __launch_bounds__(256) void spex_lse_merge_kernel(MergeArgs a, Shape sh) {
+  const int dv = sh.D / VEC;
+  const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t row = tid / dv;
+  const int c = static_cast<int>(tid % dv);
+  if (row >= static_cast<int64_t>(a.n_qtok) * sh.Hq) return;
+  const int qt = static_cast<int>(row / sh.Hq);
+  const int h = static_cast<int>(row % sh.Hq);
+  const int g = h / sh.G, hh = h % sh.G;
+  const int e0 = a.part_indptr[qt], e1 = a.part_indptr[qt + 1];
+  float m = kNegInf;
+  for (int e = e0; e < e1; ++e) {
+    const int64_t slot = static_cast<int64_t>(a.part_base[e]) + static_cast<int64_t>(g) * a.part_hstride[e] + hh;
+    m = fmaxf(m, a.part_ml[slot * 2]);
+  }
+  float l = 0.f;
+  float acc[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
+  for (int e = e0; e < e1; ++e) {
+    const int64_t slot = static_cast<int64_t>(a.part_base[e]) + static_cast<int64_t>(g) * a.part_hstride[e] + hh;
+    const float mj = a.part_ml[slot * 2];
+    const float lj = a.part_ml[slot * 2 + 1];
+    if (lj == 0.f) continue;
+    const float f = fast_exp2(mj - m);
+    l += lj * f;
+    const float *op = a.part_o + slot * sh.D + c * VEC;
+    if (VEC == 4) {
+      const f32x4 o = *reinterpret_cast<const f32x4 *>(op);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += o[i] * f;
+    } else {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] += op[i] * f;
+    }
+  }
+  const float inv = 1.0f / l;
+  float *out = a.out + row * sh.D + c * VEC;
+  if (VEC == 4) {
+    *reinterpret_cast<f32x4 *>(out) = f32x4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) out[i] = acc[i] * inv;
+  }
+  if (a.lse && c == 0) a.lse[row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+}
+
+// ---- append scatter / gather -----------------------------------------------------------------
+template <int KV, int LAYOUT>
+__global__ __launch_bounds__(256) void spex_scatter_kv_kernel(ScatterArgs a, Shape sh) {
+  typedef typename std::conditional<KV == kF32, float,
+                                    typename std::conditional<KV == kBF16, uint16_t, uint8_t>::type>::type T;
+  const int D = sh.D, P = sh.P, H = sh.Hkv;
+  const int64_t total = static_cast<int64_t>(a.n_pages) * H * P * D;
+  const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (tid >= total) return;
+  const int d = static_cast<int>(tid % D);
+  const int slot = static_cast<int>((tid / D) % P);
+  const int g = static_cast<int>((tid / (static_cast<int64_t>(D) * P)) % H);
+  const int pi = static_cast<int>(tid / (static_cast<int64_t>(D) * P * H));
+  const bool is_new = pi > 0 || a.first_page_is_new;
+  const int tok = pi * P + slot - a.first_slot;  // index among the tokens of this launch
+  const int64_t tile = (static_cast<int64_t>(a.page_ids[pi]) * H + g);
+  const int64_t tile_elems = static_cast<int64_t>(P) * D;
+  T *kp = static_cast<T *>(a.k_pool) + tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D);
+  T *vp = static_cast<T *>(a.v_pool) + tile * tile_elems + v_offset<KV, LAYOUT>(slot, d, D);
+  if (tok >= 0 && tok < a.n_tokens) {
+    const int64_t src = (static_cast<int64_t>(tok) * H + g) * D + d;
+    *kp = static_cast<const T *>(a.k_src)[src];
+    *vp = static_cast<const T *>(a.v_src)[src];
+  } else if (tok >= a.n_tokens && is_new) {
+    *kp = T(0);
+    *vp = T(0);
+  }
+  if (KV == kFP8 && is_new && d == 0 && slot == 0) {
+    const int idx_new = pi - (a.first_page_is_new ? 0 : 1);
+    a.k_scale[tile] = a.k_scale_src[idx_new * H + g];
+    a.v_scale[tile] = a.v_scale_src[idx_new * H + g];
+  }
+}
+
+template <int KV, int LAYOUT>
+__global__ __launch_bounds__(256) void spex_gather_kv_kernel(GatherArgs a, Shape sh) {
+  typedef typename std::conditional<KV == kF32, float,
+                                    typename std::conditional<KV == kBF16, uint16_t, uint8_t>::type>::type T;
+  const int D = sh.D, P = sh.P, H = sh.Hkv;
+  const int64_t total = static_cast<int64_t>(a.n_tokens) * H * D;
+  const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (tid >= total) return;
+  const int d = static_cast<int>(tid % D);
+  const int g = static_cast<int>((tid / D) % H);
+  const int tok = static_cast<int>(tid / (static_cast<int64_t>(D) * H));
+  const int pi = (tok + a.first_slot) / P;
+  const int slot = (tok + a.first_slot) % P;
+  const int64_t tile = (static_cast<int64_t>(a.page_ids[pi]) * H + g);
+  const int64_t tile_elems = static_cast<int64_t>(P) * D;
+  static_cast<T *>(a.k_out)[tid] =
+      static_cast<const T *>(a.k_pool)[tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D)];
+  static_cast<T *>(a.v_out)[tid] =
+      static_cast<const T *>(a.v_pool)[tile * tile_elems + v_offset<KV, LAYOUT>(slot, d, D)];
+  if (KV == kFP8 && d == 0) {
+    if (a.k_scale_out) a.k_scale_out[static_cast<int64_t>(tok) * H + g] = a.k_scale[tile];
+    if (a.v_scale_out) a.v_scale_out[static_cast<int64_t>(tok) * H + g] = a.v_scale[tile];
+  }
+}
+
+template <int KV, int D, int NT>
+hipError_t launch_mfma(const Shape &sh, const AttnArgs &a, bool prefix, hipStream_t stream) {
+  const dim3 grid((a.n_items + 3) / 4), block(256);
+  if (prefix)
+    hipLaunchKernelGGL((spex_prefix_attn_kernel<KV, D, NT>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_suffix_attn_kernel<KV, D, NT>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+template <int KV, int D>
+hipError_t launch_mfma_nt(const Shape &sh, const AttnArgs &a, bool prefix, int nt, hipStream_t s) {
+  return nt == 1 ? launch_mfma<KV, D, 1>(sh, a, prefix, s) : launch_mfma<KV, D, 2>(sh, a, prefix, s);
+}
+
+template <int KV, int QT>
+hipError_t launch_generic(const Shape &sh, const AttnArgs &a, int rows_per_item, hipStream_t stream) {
+  const dim3 grid(a.n_items), block(64);
+  if (sh.layout == kMfmaTiled)
+    hipLaunchKernelGGL((spex_generic_attn_kernel<KV, QT, kMfmaTiled>), grid, block, 0, stream, a, sh,
+                       rows_per_item);
+  else
+    hipLaunchKernelGGL((spex_generic_attn_kernel<KV, QT, kRowMajor>), grid, block, 0, stream, a, sh,
+                       rows_per_item);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool has_mfma_kernel(const Shape &sh) {
+  return sh.layout == kMfmaTiled && sh.q_dtype == kBF16 &&
+         (sh.kv_dtype == kBF16 || sh.kv_dtype == kFP8) && sh.P == 16 && (sh.D == 64 || sh.D == 128);
+}
+
+hipError_t launch_attention(const Shape &sh, const AttnArgs &a, bool prefix, int row_tiles,
+                            bool force_generic, hipStream_t stream) {
+  if (a.n_items <= 0) return hipSuccess;
+  if (!force_generic && has_mfma_kernel(sh)) {
+    if (sh.kv_dtype == kBF16)
+      return sh.D == 64 ? launch_mfma_nt<kBF16, 64>(sh, a, prefix, row_tiles, stream)
+                        : launch_mfma_nt<kBF16, 128>(sh, a, prefix, row_tiles, stream);
+    return sh.D == 64 ? launch_mfma_nt<kFP8, 64>(sh, a, prefix, row_tiles, stream)
+                      : launch_mfma_nt<kFP8, 128>(sh, a, prefix, row_tiles, stream);
+  }
+  const int rows_per_item = 16 * row_tiles;
+  if (sh.kv_dtype == kF32 && sh.q_dtype == kF32) return launch_generic<kF32, kF32>(sh, a, rows_per_item, stream);
+  if (sh.kv_dtype == kBF16 && sh.q_dtype == kBF16) return launch_generic<kBF16, kBF16>(sh, a, rows_per_item, stream);
+  if (sh.kv_dtype == kFP8 && sh.q_dtype == kBF16) return launch_generic<kFP8, kBF16>(sh, a, rows_per_item, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream) {
+  if (a.n_qtok <= 0) return hipSuccess;
+  const int vec = (sh.D % 4 == 0) ? 4 : 1;
+  const int64_t threads = static_cast<int64_t>(a.n_qtok) * sh.Hq * (sh.D / vec);
+  const dim3 grid(static_cast<unsigned>((threads + 255) / 256)), block(256);
+  if (vec == 4)
+    hipLaunchKernelGGL(spex_lse_merge_kernel<4>, grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL(spex_lse_merge_kernel<1>, grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+template <int KV>
+static hipError_t scatter_layout(const Shape &sh, const ScatterArgs &a, hipStream_t stream) {
+  const int64_t total = static_cast<int64_t>(a.n_pages) * sh.Hkv * sh.P * sh.D;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
+  if (sh.layout == kMfmaTiled)
+    hipLaunchKernelGGL((spex_scatter_kv_kernel<KV, kMfmaTiled>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_scatter_kv_kernel<KV, kRowMajor>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter(const Shape &sh, const ScatterArgs &a, hipStream_t stream) {
+  if (a.n_pages <= 0) return hipSuccess;
+  switch (sh.kv_dtype) {
+    case kF32: return scatter_layout<kF32>(sh, a, stream);
+    case kBF16: return scatter_layout<kBF16>(sh, a, stream);
+    case kFP8: return scatter_layout<kFP8>(sh, a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int KV>
+static hipError_t gather_layout(const Shape &sh, const GatherArgs &a, hipStream_t stream) {
+  const int64_t total = static_cast<int64_t>(a.n_tokens) * sh.Hkv * sh.D;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
+  if (sh.layout == kMfmaTiled)
+    hipLaunchKernelGGL((spex_gather_kv_kernel<KV, kMfmaTiled>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_gather_kv_kernel<KV, kRowMajor>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t stream) {
+  if (a.n_tokens <= 0) return hipSuccess;
+  switch (sh.kv_dtype) {
+    case kF32: return gather_layout<kF32>(sh, a, stream);
+    case kBF16: return gather_layout<kBF16>(sh, a, stream);
+    case kFP8: return gather_layout<kFP8>(sh, a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace spex

@@ -1,0 +1,73 @@
+// Launch interface between the C ABI layer and the HIP kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace spex {
+
+enum Dtype : int32_t { kF32 = 0, kBF16 = 1, kFP8 = 2 };
+
+// Element arrangement inside a (page, kv head) tile; see the pool layout in spex_tree.h.
+enum Layout : int32_t { kRowMajor = 0, kMfmaTiled = 1 };
+
+struct Shape {
+  int32_t Hq, Hkv, G, D, P;
+  int32_t q_dtype, kv_dtype, layout;
+};
+
+// Everything the attention kernels read; all pointers DEVICE.
+struct AttnArgs {
+  const void *k_pool, *v_pool;
+  const float *k_scale, *v_scale;
+  const void *q;
+  const int32_t *items;  // {task, kv_head | row_tile << 8} per work item
+  int32_t n_items;
+  const int32_t *task_pg_begin, *task_pg_count, *task_qt_begin, *task_qt_count, *task_pbase,
+      *task_flags;
+  const int32_t *pg_id, *pg_valid, *pg_pos, *qt_list, *qt_limit;
+  float *part_o;   // [partial rows][D] unnormalised sum of exp2(x - m) * V
+  float *part_ml;  // [partial rows][2] = {m, l}: running maximum of x = score * log2(e), sum of exp2
+  float scale_log2;
+};
+
+struct MergeArgs {
+  const int32_t *part_indptr, *part_base, *part_hstride;
+  const float *part_o, *part_ml;
+  float *out, *lse;
+  int32_t n_qtok;
+};
+
+constexpr int kMaxPagesPerScatter = 64;
+struct ScatterArgs {
+  void *k_pool, *v_pool;
+  float *k_scale, *v_scale;              // pool scale arrays (fp8) or null
+  const void *k_src, *v_src;             // [n_tokens][Hkv][D]
+  const float *k_scale_src, *v_scale_src;  // [new pages][Hkv], already offset to this launch
+  int32_t n_pages;                       // pages touched by this launch
+  int32_t first_slot;                    // first written slot of page 0 (0 if it is new)
+  int32_t n_tokens;                      // tokens written by this launch
+  int32_t first_page_is_new;
+  int32_t page_ids[kMaxPagesPerScatter];
+};
+
+struct GatherArgs {
+  const void *k_pool, *v_pool;
+  const float *k_scale, *v_scale;
+  void *k_out, *v_out;
+  float *k_scale_out, *v_scale_out;
+  int32_t n_pages, first_slot, n_tokens;
+  int32_t page_ids[kMaxPagesPerScatter];
+};
+
+// prefix == true launches the shared-prefix kernel, else the suffix kernel; row_tiles is the
+// number of 16-row MFMA tiles per wavefront the item list was built for.
+hipError_t launch_attention(const Shape &sh, const AttnArgs &a, bool prefix, int row_tiles,
+                            bool force_generic, hipStream_t stream);
+hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream);
+hipError_t launch_scatter(const Shape &sh, const ScatterArgs &a, hipStream_t stream);
+hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t stream);
+bool has_mfma_kernel(const Shape &sh);
+
+}  // namespace spex

@@ -1,0 +1,251 @@
+#include "planner.hpp"
+
+#include <algorithm>
+#include <limits>
+#include <numeric>
+
+namespace spex {
+namespace {
+
+constexpr int64_t kTargetItems = 4096;  // ~2 work items per wavefront slot of the chip
+
+int32_t clamp32(int64_t v, int32_t lo, int32_t hi) {
+  return static_cast<int32_t>(std::max<int64_t>(lo, std::min<int64_t>(hi, v)));
+}
+
+struct Segment {
+  std::vector<int32_t> ids, valid, pos;
+  int32_t qt_begin = 0, qt_count = 0;
+};
+
+}  // namespace
+
+PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
+                         int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
+                         int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, Plan *plan) {
+  if (n_leaves < 0 || (n_leaves > 0 && !leaves)) return PlanError::kInvalid;
+  const int32_t P = pt.page_size();
+  const int32_t G = num_q_heads / num_kv_heads;
+  const int32_t N = pt.num_nodes();
+  Plan &pl = *plan;
+  pl = Plan();
+  pl.req_leaves.assign(leaves, leaves + n_leaves);
+  if (q_lens) pl.req_q_lens.assign(q_lens, q_lens + n_leaves);
+  pl.table_version = pt.version();
+  pl.req_prefix_chunk = prefix_chunk_pages;
+  pl.req_suffix_chunk = suffix_chunk_pages;
+
+  if (static_cast<int32_t>(live_.size()) < N) {
+    live_.resize(N, 0);
+    pos0_.resize(N, 0);
+    gindex_.resize(N, -1);
+  }
+  auto reset = [&]() {
+    for (int32_t u : touched_) {
+      live_[u] = 0;
+      gindex_[u] = -1;
+    }
+    touched_.clear();
+  };
+
+  // ---- paths, CSR, limits, live counts
+  std::vector<int32_t> path_indptr(n_leaves + 1, 0), path_nodes, qoff(n_leaves, 0);
+  pl.leaf_indptr.assign(1, 0);
+  std::vector<int32_t> tmp;
+  for (int32_t i = 0; i < n_leaves; ++i) {
+    const int32_t leaf = leaves[i];
+    const int32_t ql = q_lens ? q_lens[i] : 1;
+    if (!pt.valid(leaf)) {
+      reset();
+      return PlanError::kBadNode;
+    }
+    tmp.clear();
+    for (int32_t u = leaf; u != kNoNode; u = pt.node(u).parent) tmp.push_back(u);
+    int64_t T = 0;
+    for (auto it = tmp.rbegin(); it != tmp.rend(); ++it) {
+      const int32_t u = *it;
+      path_nodes.push_back(u);
+      pos0_[u] = static_cast<int32_t>(T);
+      if (live_[u]++ == 0) touched_.push_back(u);
+      const Node &nd = pt.node(u);
+      for (size_t k = 0; k < nd.pages.size(); ++k) {
+        pl.leaf_pages.push_back(nd.pages[k]);
+        pl.leaf_valid.push_back(pt.page_valid(u, static_cast<int32_t>(k)));
+      }
+      T += nd.n_tokens;
+    }
+    path_indptr[i + 1] = static_cast<int32_t>(path_nodes.size());
+    pl.leaf_indptr.push_back(static_cast<int32_t>(pl.leaf_pages.size()));
+    if (ql < 1 || ql > T || T > std::numeric_limits<int32_t>::max() / 2) {
+      reset();
+      return ql < 1 ? PlanError::kInvalid : PlanError::kEmptyPath;
+    }
+    qoff[i] = static_cast<int32_t>(pl.qt_limit.size());
+    for (int32_t j = 0; j < ql; ++j) pl.qt_limit.push_back(static_cast<int32_t>(T) - ql + 1 + j);
+  }
+  const int32_t NQ = static_cast<int32_t>(pl.qt_limit.size());
+
+  // ---- groups
+  for (int32_t u : touched_)
+    if (live_[u] >= 2 && pt.node(u).n_tokens > 0) pl.group_node.push_back(u);
+  std::sort(pl.group_node.begin(), pl.group_node.end());
+  const int32_t NG = static_cast<int32_t>(pl.group_node.size());
+  for (int32_t gi = 0; gi < NG; ++gi) gindex_[pl.group_node[gi]] = gi;
+  std::vector<int32_t> group_count(NG, 0);
+  for (int32_t i = 0; i < n_leaves; ++i) {
+    const int32_t ql = q_lens ? q_lens[i] : 1;
+    for (int32_t k = path_indptr[i]; k < path_indptr[i + 1]; ++k) {
+      const int32_t gi = gindex_[path_nodes[k]];
+      if (gi >= 0) group_count[gi] += ql;
+    }
+  }
+  std::vector<int32_t> group_qt_begin(NG + 1, 0);
+  for (int32_t gi = 0; gi < NG; ++gi) group_qt_begin[gi + 1] = group_qt_begin[gi] + group_count[gi];
+  const int32_t n_group_qt = group_qt_begin[NG];
+  pl.qt_list.assign(static_cast<size_t>(n_group_qt) + NQ, 0);
+  std::vector<int32_t> fill(group_qt_begin.begin(), group_qt_begin.end() - 1);
+  for (int32_t i = 0; i < n_leaves; ++i) {
+    const int32_t ql = q_lens ? q_lens[i] : 1;
+    for (int32_t k = path_indptr[i]; k < path_indptr[i + 1]; ++k) {
+      const int32_t gi = gindex_[path_nodes[k]];
+      if (gi < 0) continue;
+      for (int32_t j = 0; j < ql; ++j) pl.qt_list[fill[gi]++] = qoff[i] + j;
+    }
+  }
+  std::iota(pl.qt_list.begin() + n_group_qt, pl.qt_list.end(), 0);
+
+  // ---- segments
+  auto add_node_pages = [&](Segment &s, int32_t u) {
+    const Node &nd = pt.node(u);
+    int32_t t = pos0_[u];
+    for (size_t k = 0; k < nd.pages.size(); ++k) {
+      const int32_t v = pt.page_valid(u, static_cast<int32_t>(k));
+      s.ids.push_back(nd.pages[k]);
+      s.valid.push_back(v);
+      s.pos.push_back(t);
+      t += v;
+    }
+  };
+  std::vector<Segment> groups(NG), suffixes;
+  int64_t prefix_pages_weighted = 0;
+  for (int32_t gi = 0; gi < NG; ++gi) {
+    add_node_pages(groups[gi], pl.group_node[gi]);
+    groups[gi].qt_begin = group_qt_begin[gi];
+    groups[gi].qt_count = group_count[gi];
+    pl.max_rows_prefix = std::max(pl.max_rows_prefix, group_count[gi] * G);
+  }
+  suffixes.reserve(n_leaves);
+  int64_t suffix_pages = 0;
+  for (int32_t i = 0; i < n_leaves; ++i) {
+    const int32_t ql = q_lens ? q_lens[i] : 1;
+    int32_t k0 = path_indptr[i + 1];
+    while (k0 > path_indptr[i] && live_[path_nodes[k0 - 1]] == 1) --k0;
+    Segment s;
+    for (int32_t k = k0; k < path_indptr[i + 1]; ++k) add_node_pages(s, path_nodes[k]);
+    if (s.ids.empty()) continue;
+    s.qt_begin = n_group_qt + qoff[i];
+    s.qt_count = ql;
+    suffix_pages += static_cast<int64_t>(s.ids.size());
+    pl.max_rows_suffix = std::max(pl.max_rows_suffix, ql * G);
+    suffixes.push_back(std::move(s));
+  }
+  pl.prefix_row_tiles = pl.max_rows_prefix <= 16 ? 1 : 2;
+  pl.suffix_row_tiles = pl.max_rows_suffix <= 16 ? 1 : 2;
+  const int32_t rw_prefix = 16 * pl.prefix_row_tiles, rw_suffix = 16 * pl.suffix_row_tiles;
+  for (const Segment &s : groups)
+    prefix_pages_weighted +=
+        static_cast<int64_t>(s.ids.size()) * ((s.qt_count * G + rw_prefix - 1) / rw_prefix);
+
+  // ---- split granularity
+  pl.prefix_chunk_pages = prefix_chunk_pages > 0
+                              ? prefix_chunk_pages
+                              : clamp32((prefix_pages_weighted * num_kv_heads + kTargetItems - 1) /
+                                            kTargetItems, 8, 64);
+  pl.suffix_chunk_pages = suffix_chunk_pages > 0
+                              ? suffix_chunk_pages
+                              : clamp32((suffix_pages * num_kv_heads + kTargetItems - 1) /
+                                            kTargetItems, 4, 64);
+
+  // ---- tasks
+  std::vector<std::vector<std::pair<int32_t, int32_t>>> parts(NQ);
+  int64_t pbase = 0;
+  bool overflow = false;
+  auto emit = [&](const Segment &s, int32_t chunk_pages, int64_t *tokens) {
+    const int32_t n = static_cast<int32_t>(s.ids.size());
+    const int32_t rows = s.qt_count * G;
+    int32_t min_limit = std::numeric_limits<int32_t>::max();
+    for (int32_t r = 0; r < s.qt_count; ++r)
+      min_limit = std::min(min_limit, pl.qt_limit[pl.qt_list[s.qt_begin + r]]);
+    const int32_t c = (n + chunk_pages - 1) / chunk_pages;
+    for (int32_t j = 0; j < c; ++j) {
+      const int32_t a = static_cast<int32_t>(static_cast<int64_t>(j) * n / c);
+      const int32_t b = static_cast<int32_t>(static_cast<int64_t>(j + 1) * n / c);
+      bool masked = min_limit < s.pos[b - 1] + s.valid[b - 1];
+      for (int32_t k = a; k < b; ++k) {
+        masked = masked || s.valid[k] != P;
+        *tokens += s.valid[k];
+      }
+      if (pbase > std::numeric_limits<int32_t>::max() - static_cast<int64_t>(rows) * num_kv_heads)
+        overflow = true;
+      pl.task_pg_begin.push_back(static_cast<int32_t>(pl.pg_id.size()));
+      pl.task_pg_count.push_back(b - a);
+      pl.task_qt_begin.push_back(s.qt_begin);
+      pl.task_qt_count.push_back(s.qt_count);
+      pl.task_pbase.push_back(static_cast<int32_t>(pbase));
+      pl.task_flags.push_back(masked ? 1 : 0);
+      pl.pg_id.insert(pl.pg_id.end(), s.ids.begin() + a, s.ids.begin() + b);
+      pl.pg_valid.insert(pl.pg_valid.end(), s.valid.begin() + a, s.valid.begin() + b);
+      pl.pg_pos.insert(pl.pg_pos.end(), s.pos.begin() + a, s.pos.begin() + b);
+      for (int32_t r = 0; r < s.qt_count; ++r)
+        parts[pl.qt_list[s.qt_begin + r]].emplace_back(static_cast<int32_t>(pbase) + r * G, rows);
+      pbase += static_cast<int64_t>(rows) * num_kv_heads;
+    }
+  };
+  for (const Segment &s : groups) emit(s, pl.prefix_chunk_pages, &pl.prefix_tokens);
+  pl.n_prefix_tasks = static_cast<int32_t>(pl.task_pbase.size());
+  for (const Segment &s : suffixes) emit(s, pl.suffix_chunk_pages, &pl.suffix_tokens);
+  pl.n_partial_rows = pbase;
+  reset();
+  if (overflow) return PlanError::kTooLarge;
+
+  pl.part_indptr.assign(1, 0);
+  for (const auto &lst : parts) {
+    for (const auto &e : lst) {
+      pl.part_base.push_back(e.first);
+      pl.part_hstride.push_back(e.second);
+    }
+    pl.part_indptr.push_back(static_cast<int32_t>(pl.part_base.size()));
+  }
+
+  // ---- launch lists, heaviest tasks first
+  const int32_t n_tasks = static_cast<int32_t>(pl.task_pbase.size());
+  auto order_of = [&](int32_t lo, int32_t hi) {
+    std::vector<int32_t> ord(hi - lo);
+    std::iota(ord.begin(), ord.end(), lo);
+    std::stable_sort(ord.begin(), ord.end(), [&](int32_t x, int32_t y) {
+      return static_cast<int64_t>(pl.task_pg_count[x]) * pl.task_qt_count[x] >
+             static_cast<int64_t>(pl.task_pg_count[y]) * pl.task_qt_count[y];
+    });
+    return ord;
+  };
+  for (int32_t t : order_of(0, pl.n_prefix_tasks)) {
+    const int32_t n_rt = (pl.task_qt_count[t] * G + rw_prefix - 1) / rw_prefix;
+    for (int32_t g = 0; g < num_kv_heads; ++g)
+      for (int32_t rt = 0; rt < n_rt; ++rt) {
+        pl.prefix_items.push_back(t);
+        pl.prefix_items.push_back(g | (rt << 8));
+      }
+  }
+  for (int32_t t : order_of(pl.n_prefix_tasks, n_tasks)) {
+    const int32_t n_rt = (pl.task_qt_count[t] * G + rw_suffix - 1) / rw_suffix;
+    for (int32_t rt = 0; rt < n_rt; ++rt)
+      for (int32_t g = 0; g < num_kv_heads; ++g) {
+        pl.suffix_items.push_back(t);
+        pl.suffix_items.push_back(g | (rt << 8));
+      }
+  }
+  pl.valid = true;
+  return PlanError::kOk;
+}
+
+}  // namespace spex

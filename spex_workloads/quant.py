@@ -28,6 +28,14 @@ def encode_e4m3(x: torch.Tensor) -> torch.Tensor:
     return (code | sign).to(torch.uint8)
 
 
+def _scale_and_inverse(amax: torch.Tensor):
+    """scale = max(amax / 448, tiny) and 1 / scale, both computed on the host: fp32 division
+    is not rounded the same way on every device, multiplication is."""
+    a = amax.detach().to("cpu", torch.float32)
+    s = (a / E4M3_MAX).clamp_min(_MIN_SCALE)
+    return s.to(amax.device), (1.0 / s).to(amax.device)
+
+
 def quantise_pages(x: torch.Tensor, first_slot: int, page_size: int, prev_scale=None):
     """Quantise an append of n tokens, x = [n, H, D] fp32, that starts at slot `first_slot`
     of the node's current last page.
@@ -35,7 +43,7 @@ def quantise_pages(x: torch.Tensor, first_slot: int, page_size: int, prev_scale=
     Tokens that continue a partially filled page reuse that page's scale
     (`prev_scale`, [H]) and saturate; every newly started page gets
     scale = max(amax / 448, tiny) with amax taken over the tokens this append puts
-    into that page, separately per KV head.
+    into that page, separately per KV head.  code = round_to_e4m3(x * (1 / scale)).
 
     Returns (codes uint8 [n, H, D], new_page_scales fp32 [n_new_pages, H]).
     """
@@ -46,7 +54,8 @@ def quantise_pages(x: torch.Tensor, first_slot: int, page_size: int, prev_scale=
         head = min(n, page_size - first_slot % page_size)
         if prev_scale is None:
             raise ValueError("continuing a partial page needs that page's scale")
-        codes[:head] = encode_e4m3(x[:head] / prev_scale.to(x.device).reshape(1, H, 1))
+        inv = (1.0 / prev_scale.detach().to("cpu", torch.float32)).to(x.device)
+        codes[:head] = encode_e4m3(x[:head] * inv.reshape(1, H, 1))
     rest = n - head
     n_new = (rest + page_size - 1) // page_size
     scales = torch.empty((n_new, H), dtype=torch.float32, device=x.device)
@@ -54,13 +63,13 @@ def quantise_pages(x: torch.Tensor, first_slot: int, page_size: int, prev_scale=
         full = rest // page_size
         if full:
             blk = x[head:head + full * page_size].reshape(full, page_size, H, D)
-            s = (blk.abs().amax(dim=(1, 3)) / E4M3_MAX).clamp_min(_MIN_SCALE)
+            s, inv = _scale_and_inverse(blk.abs().amax(dim=(1, 3)))
             scales[:full] = s
             codes[head:head + full * page_size] = encode_e4m3(
-                blk / s.reshape(full, 1, H, 1)).reshape(full * page_size, H, D)
+                blk * inv.reshape(full, 1, H, 1)).reshape(full * page_size, H, D)
         if rest % page_size:
             tail = x[head + full * page_size:]
-            s = (tail.abs().amax(dim=(0, 2)) / E4M3_MAX).clamp_min(_MIN_SCALE)
+            s, inv = _scale_and_inverse(tail.abs().amax(dim=(0, 2)))
             scales[full] = s
-            codes[head + full * page_size:] = encode_e4m3(tail / s.reshape(1, H, 1))
+            codes[head + full * page_size:] = encode_e4m3(tail * inv.reshape(1, H, 1))
     return codes, scales

@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element."""
+
+import numpy as np
+import pytest
+import torch
+
+import spex_workloads as sw
+from gpu_common import assert_close, build_gpu_tree, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def test_generators_agree_between_cpu_and_gpu():
+    for tag, scale in ((1, 0.5), (2, 1.0)):
+        a = sw.normal_values(9, tag, 1234567, torch.arange(300), 4, 128, scale, "cpu")
+        b = sw.normal_values(9, tag, 1234567, torch.arange(300), 4, 128, scale, "cuda").cpu()
+        assert torch.equal(a, b)
+    x = sw.normal_values(9, 1, 5, torch.arange(100), 4, 128, 0.5, "cpu")
+    ca, sa = sw.quantise_pages(x, 0, 16, None)
+    cb, sb = sw.quantise_pages(x.cuda(), 0, 16, None)
+    assert torch.equal(ca, cb.cpu()) and torch.equal(sa, sb.cpu())
+    assert torch.equal(x.to(torch.bfloat16), x.cuda().to(torch.bfloat16).cpu())
+
+
+@pytest.mark.parametrize("kv_dtype,heads", [("f32", (4, 2, 64)), ("f32", (2, 1, 40)),
+                                            ("bf16", (8, 2, 64)), ("bf16", (4, 4, 128)),
+                                            ("bf16", (2, 2, 96)), ("fp8_e4m3", (10, 2, 128)),
+                                            ("fp8_e4m3", (4, 2, 64))])
+def test_append_then_gather_is_bit_exact(kv_dtype, heads):
+    wl = sw.random_trace(31, heads=heads, kv_dtype=kv_dtype,
+                         q_dtype="f32" if kv_dtype == "f32" else "bf16", n_ops=40, max_tokens=45)
+    rng = np.random.default_rng(1)
+    order = rng.permutation(wl.peak_pages() + 3).tolist()
+    tree = build_gpu_tree(wl, free_order=order, extra_pages=3, pool_fill=0xFF)
+
+    class Rec:
+        def __init__(self):
+            self.k, self.v, self.ks, self.vs, self.n = {}, {}, {}, {}, []
+
+        def fork(self, parent, n):
+            ids = list(range(len(self.n), len(self.n) + n))
+            self.n += [0] * n
+            return ids
+
+        def prune(self, node):
+            pass
+
+        def append(self, node, k, v, ks, vs, n_tokens=None):
+            self.k.setdefault(node, []).append(k)
+            self.v.setdefault(node, []).append(v)
+            if ks is not None:
+                self.ks.setdefault(node, []).append(ks)
+                self.vs.setdefault(node, []).append(vs)
+
+    rec = Rec()
+    sw.replay(wl, rec, device="cpu")
+    _, _, alive = wl.node_tokens()
+    checked = 0
+    for u, pieces in rec.k.items():
+        if not alive[u]:
+            continue
+        k_ref, v_ref = torch.cat(pieces, 0), torch.cat(rec.v[u], 0)
+        n = k_ref.shape[0]
+        k, v, ks, vs = tree.gather_kv(u, 0, n)
+        assert torch.equal(k.cpu(), k_ref) and torch.equal(v.cpu(), v_ref)
+        if n > 3:
+            k2, v2, _, _ = tree.gather_kv(u, 2, n - 3)
+            assert torch.equal(k2.cpu(), k_ref[2:n - 1]) and torch.equal(v2.cpu(), v_ref[2:n - 1])
+        if kv_dtype == "fp8_e4m3":
+            ks_ref = torch.cat(rec.ks[u], 0).repeat_interleave(16, 0)[:n]
+            vs_ref = torch.cat(rec.vs[u], 0).repeat_interleave(16, 0)[:n]
+            assert torch.equal(ks.cpu(), ks_ref) and torch.equal(vs.cpu(), vs_ref)
+        checked += 1
+    assert checked > 5
+    tree.close()
+
+
+def test_config_1_tiny_tree_fp32():
+    wl = sw.tiny_tree()
+    assert_close(run_gpu(wl), run_oracle(wl), "f32", "tiny_tree")
+
+
+RANDOM_CASES = [
+    dict(seed=41, heads=(8, 2, 64), kv_dtype="bf16", max_q_len=1),
+    dict(seed=42, heads=(8, 2, 128), kv_dtype="bf16", max_q_len=4),
+    dict(seed=43, heads=(28, 4, 128), kv_dtype="bf16", max_q_len=3),
+    dict(seed=44, heads=(16, 2, 64), kv_dtype="bf16", max_q_len=6),
+    dict(seed=45, heads=(10, 2, 128), kv_dtype="fp8_e4m3", max_q_len=6),
+    dict(seed=46, heads=(8, 8, 64), kv_dtype="fp8_e4m3", max_q_len=2),
+    dict(seed=47, heads=(4, 2, 64), kv_dtype="f32", max_q_len=3),
+    dict(seed=48, heads=(6, 3, 40), kv_dtype="bf16", max_q_len=2),      # no MFMA kernel: generic
+    dict(seed=49, heads=(4, 1, 128), kv_dtype="bf16", max_q_len=9),     # 36 rows: two row tiles
+]
+
+
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")
+@pytest.mark.parametrize("chunks", [(0, 0), (1, 1), (3, 2)])
+def test_random_trees_match_oracle(case, chunks):
+    wl = sw.random_trace(case["seed"], heads=case["heads"], kv_dtype=case["kv_dtype"],
+                         q_dtype="f32" if case["kv_dtype"] == "f32" else "bf16",
+                         n_ops=70, max_tokens=90, max_q_len=case["max_q_len"])
+    ref = run_oracle(wl)
+    got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1])
+    assert_close(got, ref, case["kv_dtype"], wl.name)
+
+
+@pytest.mark.parametrize("case", RANDOM_CASES[:6], ids=lambda c: f"{c['kv_dtype']}-{c['heads']}")
+def test_generic_kernels_match_oracle_and_mfma(case):
+    wl = sw.random_trace(case["seed"] + 100, heads=case["heads"], kv_dtype=case["kv_dtype"],
+                         n_ops=60, max_tokens=70, max_q_len=case["max_q_len"])
+    ref = run_oracle(wl)
+    slow = run_gpu(wl, kernel_mode=1)
+    fast = run_gpu(wl, kernel_mode=0)
+    assert_close(slow, ref, case["kv_dtype"], "generic")
+    assert_close(fast, ref, case["kv_dtype"], "mfma")
+    assert np.max(np.abs(slow[0] - fast[0])) < 1e-3
+
+
+REDUCED = [
+    sw.bfs_tot(n_queries=3, prompt=200, step=72),
+    sw.mcts_skewed(n_queries=5, prompt=(100, 300), step=(10, 90), max_leaves=24),
+    sw.spec_at_scale(n_queries=3, prompt=300, step=100, branches=12),
+    sw.tot_with_drafts(n_queries=3, prompt=250, step=56),
+    sw.bfs_tot(n_queries=2, prompt=64, step=32, kv_dtype="fp8_e4m3", heads=(16, 2, 64)),
+]
+
+
+@pytest.mark.parametrize("wl", REDUCED, ids=lambda w: w.name + "_" + w.kv_dtype)
+def test_reduced_config_shapes_match_oracle(wl):
+    assert_close(run_gpu(wl), run_oracle(wl), wl.kv_dtype, wl.name)
+
+
+def test_nan_poisoned_pool_and_ragged_pages():
+    # 0xFF bytes are NaN in bf16 and in e4m3: unused slots of partial pages must never contribute.
+    for kv in ("bf16", "fp8_e4m3"):
+        wl = sw.random_trace(51, heads=(8, 2, 128), kv_dtype=kv, n_ops=60, max_tokens=37, max_q_len=3)
+        got = run_gpu(wl, pool_fill=0xFF, extra_pages=7)
+        assert_close(got, run_oracle(wl), kv, "poisoned " + kv)
+
+
+def test_page_placement_does_not_change_the_result():
+    wl = sw.random_trace(52, heads=(8, 2, 128), kv_dtype="bf16", n_ops=60, max_tokens=80, max_q_len=2)
+    base = run_gpu(wl)
+    n = wl.peak_pages() + 11
+    for s in range(3):
+        order = np.random.default_rng(s).permutation(n).tolist()
+        other = run_gpu(wl, free_order=order, extra_pages=11)
+        assert np.array_equal(base[0], other[0]) and np.array_equal(base[1], other[1])
+
+
+def test_identical_token_paths_give_identical_outputs():
+    wl = sw.Workload("twins", 8, 2, 128, 16, "bf16", "bf16", 0.5, 78)
+    b = sw.trees._Builder(wl)
+    (root,) = b.fork(-1, 1)
+    b.append(root, 100)
+    a1, a2 = b.fork(root, 2)
+    b.append(a1, 45, key=1234)
+    b.append(a2, 45, key=1234)
+    (c1,) = b.fork(a1, 1)
+    (c2,) = b.fork(a2, 1)
+    b.append(c1, 30, key=99)
+    b.append(c2, 30, key=99)
+    b.request(c1, 3, key=5)
+    b.request(c2, 3, key=5)
+    out, lse = run_gpu(wl)
+    assert np.array_equal(out[:3], out[3:]) and np.array_equal(lse[:3], lse[3:])
+    assert_close((out, lse), run_oracle(wl), "bf16", "twins")
+
+
+def test_duplicate_interior_and_empty_requests():
+    wl = sw.Workload("odd_requests", 8, 2, 64, 16, "bf16", "bf16", 0.5, 79)
+    b = sw.trees._Builder(wl)
+    (root,) = b.fork(-1, 1)
+    b.append(root, 37)
+    a, e = b.fork(root, 2)
+    b.append(a, 5)
+    b.request(a, 1)
+    b.request(a, 7)          # same node again; 7 queries reach 2 tokens into the shared root
+    b.request(root, 2)       # interior node
+    b.request(e, 1)          # empty child: sees exactly the root
+    assert_close(run_gpu(wl), run_oracle(wl), "bf16", wl.name)
+
+
+def test_decode_loop_replans_after_every_append():
+    wl = sw.bfs_tot(n_queries=2, prompt=48, step=20)
+    tree = build_gpu_tree(wl, extra_pages=64)
+    from oracle.adapters import OracleSink, queries_fp64
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = sw.gen_queries(wl, device="cuda")
+    qd = queries_fp64(q)
+    for step in range(20):                                   # crosses a page boundary
+        k = sw.normal_values(5, 1, 777 + step, torch.arange(len(wl.leaves)), 8, 128, 0.5, "cuda")
+        v = sw.normal_values(5, 2, 777 + step, torch.arange(len(wl.leaves)), 8, 128, 0.5, "cuda")
+        k, v = k.to(torch.bfloat16), v.to(torch.bfloat16)
+        for i, leaf in enumerate(wl.leaves):
+            tree.append_step(leaf, k[i:i + 1].contiguous(), v[i:i + 1].contiguous())
+            sink.append(leaf, k[i:i + 1], v[i:i + 1])
+        out, lse = tree.decode_attention(wl.leaves, None, q, wl.sm_scale)
+        rebuilt = tree.last_launch_info()["plan_rebuilt"]
+        out2, _ = tree.decode_attention(wl.leaves, None, q, wl.sm_scale)
+        assert rebuilt == 1 and tree.last_launch_info()["plan_rebuilt"] == 0
+        if step % 6 == 5:
+            ref = sink.tree.attention(wl.leaves, None, qd, wl.sm_scale)
+            got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+            assert_close(got, ref, "bf16", f"decode step {step}")
+            assert torch.equal(out, out2)
+    tree.close()
+
+
+def test_device_errors_are_reported_not_raised_from_kernels():
+    import paper_2605_10195_amd as spex
+    t = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=4, device="cuda")
+    (r,) = t.fork(-1, 1)
+    q = torch.zeros((1, 8, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(spex.SpexError) as e:
+        t.decode_attention([r], None, q, 0.125)              # no tokens yet
+    assert e.value.name == "EMPTY_PATH"
+    k = torch.zeros((70, 2, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(spex.SpexError) as e:
+        t.append_step(r, k, k)                                # 5 pages > 4
+    assert e.value.name == "OOM_PAGES"
+    t.append_step(r, k[:64].contiguous(), k[:64].contiguous())
+    out, lse = t.decode_attention([r], None, q, 0.125)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and abs(lse[0, 0].item() - np.log(64)) < 1e-5
+    t.close()

@@ -1,0 +1,186 @@
+"""Host side of the library through the C ABI, on CPU: exported symbols, page table, allocator,
+prune and the per-launch plan, all bit-exact against the reference model."""
+
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import spex_workloads as sw
+from oracle.page_table_ref import OutOfPages, PageTableRef
+import paper_2605_10195_amd as spex
+from paper_2605_10195_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "spex_tree.h")).read()
+    declared = set(re.findall(r"\b(spex_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert binding.lib.spex_status_string(4) == b"page pool exhausted"
+
+
+def host_tree(wl, num_pages, free_order=None, **kw):
+    return spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
+                         wl.kv_dtype, num_pages=num_pages, free_order=free_order, host_only=True, **kw)
+
+
+def replay_both(wl, tree, ref, check_every_op=False):
+    for op in wl.ops:
+        if op.kind == "fork":
+            assert tree.fork(op.node, op.n) == ref.fork(op.node, op.n)
+        elif op.kind == "append":
+            assert tree.append_new_pages(op.node, op.n) == \
+                -(-(ref.tokens[op.node] + op.n) // ref.P) - len(ref.pages[op.node])
+            tree.append_step(op.node, None, None, n_tokens=op.n)
+            ref.append(op.node, op.n)
+        else:
+            tree.prune(op.node)
+            ref.prune(op.node)
+        if check_every_op:
+            assert tree.free_pages() == ref.free_list()
+            assert tree.stats() == ref.stats()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_page_lists_and_free_list_bit_exact(seed):
+    wl = sw.random_trace(300 + seed, n_ops=90, max_tokens=50, max_q_len=3)
+    rng = np.random.default_rng(seed)
+    n_pages = wl.peak_pages() + 5
+    order = rng.permutation(n_pages).tolist() if seed % 2 else None
+    tree, ref = host_tree(wl, n_pages, order), PageTableRef(n_pages, 16, order)
+    replay_both(wl, tree, ref, check_every_op=True)
+    for u in range(len(ref.parent)):
+        if ref.alive[u]:
+            assert tree.path_pages(u) == ref.path_pages(u)
+            info = tree.node_info(u)
+            assert info["parent"] == ref.parent[u] and info["n_tokens"] == ref.tokens[u]
+            assert info["n_pages"] == len(ref.pages[u])
+            assert info["n_live_children"] == sum(ref.alive[c] for c in ref.children[u])
+        else:
+            with pytest.raises(spex.SpexError) as e:
+                tree.path_pages(u)
+            assert e.value.name == "BAD_NODE"
+
+
+PLAN_KEYS = ["leaf_indptr", "leaf_pages", "leaf_valid", "qt_limit", "group_node", "n_prefix_tasks",
+             "n_partial_rows", "task_pg_begin", "task_pg_count", "task_qt_begin", "task_qt_count",
+             "task_pbase", "task_flags", "pg_id", "pg_valid", "pg_pos", "qt_list", "part_indptr",
+             "part_base", "part_hstride"]
+
+
+def assert_same_plan(tree, ref, wl, pc, sc):
+    tree.set_tuning(pc, sc, 0)
+    got = tree.plan_dump(wl.leaves, wl.q_lens)
+    want = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
+                    got["prefix_chunk_pages"], got["suffix_chunk_pages"])
+    if pc:
+        assert got["prefix_chunk_pages"] == pc
+    if sc:
+        assert got["suffix_chunk_pages"] == sc
+    for k in PLAN_KEYS:
+        assert got[k] == want[k], k
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_plan_bit_exact_random_traces(seed):
+    wl = sw.random_trace(400 + seed, n_ops=80, max_tokens=70, max_q_len=4,
+                         heads=[(8, 2, 64), (6, 6, 32), (28, 4, 128)][seed % 3])
+    n_pages = wl.peak_pages()
+    order = np.random.default_rng(seed).permutation(n_pages).tolist()
+    tree, ref = host_tree(wl, n_pages, order), PageTableRef(n_pages, 16, order)
+    replay_both(wl, tree, ref)
+    for pc, sc in ((0, 0), (1, 1), (2, 3), (1000, 1000)):
+        assert_same_plan(tree, ref, wl, pc, sc)
+
+
+@pytest.mark.parametrize("wl", [
+    sw.tiny_tree(), sw.bfs_tot(n_queries=3), sw.mcts_skewed(n_queries=6),
+    sw.spec_at_scale(n_queries=4), sw.tot_with_drafts(n_queries=3)], ids=lambda w: w.name)
+def test_plan_bit_exact_config_shapes(wl):
+    n_pages = wl.peak_pages()
+    tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
+    replay_both(wl, tree, ref)
+    assert tree.stats() == ref.stats()
+    for pc, sc in ((0, 0), (16, 8)):
+        assert_same_plan(tree, ref, wl, pc, sc)
+
+
+def test_full_size_config_4_plan_counts():
+    wl = sw.spec_at_scale()
+    tree = host_tree(wl, wl.peak_pages())
+    ref = PageTableRef(wl.peak_pages(), 16)
+    replay_both(wl, tree, ref)
+    assert tree.stats() == (256 * 36, 176128, 0)
+    pl = tree.plan_dump(wl.leaves, wl.q_lens)
+    assert len(pl["pg_id"]) == wl.unique_kv_tokens() // 16 and len(set(pl["pg_id"])) == len(pl["pg_id"])
+    assert pl["leaf_indptr"][-1] == wl.flat_kv_tokens() // 16
+    want = ref.plan(wl.leaves, wl.q_lens, 64, 8, pl["prefix_chunk_pages"], pl["suffix_chunk_pages"])
+    for k in PLAN_KEYS:
+        assert pl[k] == want[k], k
+
+
+def test_error_paths_leave_the_tree_unchanged():
+    t = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=4, host_only=True)
+    (r,) = t.fork(-1, 1)
+    t.append_step(r, None, None, n_tokens=20)                 # 2 pages
+    a, b = t.fork(r, 2)
+    before = (t.free_pages(), t.stats(), t.path_pages(a))
+    with pytest.raises(spex.SpexError) as e:
+        t.append_step(r, None, None, n_tokens=1)              # r has children
+    assert e.value.name == "NOT_LEAF"
+    with pytest.raises(spex.SpexError) as e:
+        t.append_step(a, None, None, n_tokens=33)             # needs 3 pages, 2 free
+    assert e.value.name == "OOM_PAGES"
+    with pytest.raises(spex.SpexError) as e:
+        t.fork(99, 1)
+    assert e.value.name == "BAD_NODE"
+    with pytest.raises(spex.SpexError) as e:
+        t.plan_dump([a], [1 + 20 + 1])                         # more queries than path tokens
+    assert e.value.name == "EMPTY_PATH"
+    with pytest.raises(spex.SpexError) as e:
+        t.plan_dump([a], [0])
+    assert e.value.name == "INVALID_ARG"
+    assert before == (t.free_pages(), t.stats(), t.path_pages(a))
+    t.append_step(a, None, None, n_tokens=32)                 # exactly fits
+    assert t.stats() == (3, 4, 0)
+    t.prune(a)
+    with pytest.raises(spex.SpexError) as e:
+        t.prune(a)
+    assert e.value.name == "BAD_NODE"
+    t.prune(b)
+    t.append_step(r, None, None, n_tokens=12)                 # childless again: fills page 2 of r
+    assert t.node_info(r)["n_tokens"] == 32 and t.stats() == (1, 2, 2)
+    t.prune(r)
+    assert t.stats() == (0, 0, 4)
+    with pytest.raises(spex.SpexError):
+        spex.SpexTree(8, 3, 64, 16, "bf16", "bf16", num_pages=4, host_only=True)     # 8 % 3
+    with pytest.raises(spex.SpexError):
+        spex.SpexTree(8, 2, 64, 24, "bf16", "bf16", num_pages=4, host_only=True)     # page size
+    with pytest.raises(spex.SpexError) as e:
+        spex.SpexTree(8, 2, 64, 16, "f32", "bf16", num_pages=4, host_only=True)      # dtype pair
+    assert e.value.name == "UNSUPPORTED"
+    with pytest.raises(spex.SpexError):
+        spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=4, host_only=True, free_order=[0, 1, 1, 3])
+
+
+def test_plan_is_cached_until_the_tree_changes():
+    wl = sw.bfs_tot(n_queries=1, prompt=32, step=16)
+    t = host_tree(wl, wl.peak_pages() + 2)
+    ref = PageTableRef(wl.peak_pages() + 2, 16)
+    replay_both(wl, t, ref)
+    p1 = t.plan_dump(wl.leaves, wl.q_lens)
+    t.append_step(wl.leaves[0], None, None, n_tokens=1)
+    ref.append(wl.leaves[0], 1)
+    p2 = t.plan_dump(wl.leaves, wl.q_lens)
+    assert p1["qt_limit"][0] + 1 == p2["qt_limit"][0]
+    want = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
+                    p2["prefix_chunk_pages"], p2["suffix_chunk_pages"])
+    for k in PLAN_KEYS:
+        assert p2[k] == want[k], k

@@ -51,7 +51,7 @@ def test_quantise_pages_scales_and_continuation():
     # continuing a partial page keeps that page's scale and adds scales only for new pages
     c2, s2 = sw.quantise_pages(x[:30], 8, 16, scales[0])
     assert s2.shape == (2, 2)
-    assert torch.equal(c2[:8], sw.encode_e4m3(x[:8] / scales[0].reshape(1, 2, 1)))
+    assert torch.equal(c2[:8], sw.encode_e4m3(x[:8] * (1.0 / scales[0]).reshape(1, 2, 1)))
 
 
 def test_config_shapes():
