@@ -223,13 +223,16 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages
                                    int32_t suffix_chunk_pages, int32_t kernel_mode);
 
 /*
- * Per-kernel timing.  With profiling enabled, every decode_attention call brackets each of its
- * kernels with HIP events on the call's stream.  spex_tree_last_kernel_ms waits for the last
- * call's events and returns milliseconds for ms[0] = shared-prefix kernel, ms[1] = suffix
- * kernel, ms[2] = merge kernel (0 for a kernel that was not launched).
+ * Per-kernel timing.  While profiling is enabled, every decode_attention call brackets each of
+ * its kernels with HIP events on the call's stream (the last 256 calls are kept).
+ * spex_tree_read_profile waits for those events and writes, for each recorded call in order,
+ * milliseconds for ms[3*c+0] = shared-prefix kernel, ms[3*c+1] = suffix kernel, ms[3*c+2] = merge
+ * kernel (0 for a kernel that was not launched); *n = number of calls; the record is then
+ * cleared.  SPEX_ERR_CAPACITY (with *n set) if cap calls are too few.  Enabling or disabling
+ * profiling also clears the record.
  */
 spex_status_t spex_tree_set_profiling(spex_tree_t *tree, int32_t enabled);
-spex_status_t spex_tree_last_kernel_ms(spex_tree_t *tree, float ms[3]);
+spex_status_t spex_tree_read_profile(spex_tree_t *tree, float *ms, int32_t cap, int32_t *n);
 
 /* Counts of the last decode_attention call, for the throughput metric:
  * info[0] distinct KV tokens read, [1] tokens in shared-prefix tasks, [2] tokens in suffix tasks,

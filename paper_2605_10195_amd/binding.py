@@ -71,7 +71,7 @@ EXPORTS = [
     "spex_tree_destroy", "spex_tree_fork", "spex_tree_append_step", "spex_tree_append_new_pages",
     "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
-    "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_last_kernel_ms",
+    "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
     "spex_tree_last_launch_info",
 ]
 
@@ -103,7 +103,7 @@ def _load():
     lib.spex_tree_gather_kv.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.spex_tree_set_profiling.argtypes = [vp, i32]
-    lib.spex_tree_last_kernel_ms.argtypes = [vp, C.POINTER(f32)]
+    lib.spex_tree_read_profile.argtypes = [vp, C.POINTER(f32), i32, _I32P]
     lib.spex_tree_last_launch_info.argtypes = [vp, C.POINTER(i64)]
     for name in EXPORTS:
         fn = getattr(lib, name)
@@ -315,10 +315,13 @@ class SpexTree:
     def set_profiling(self, enabled: bool):
         _check(lib.spex_tree_set_profiling(self._h, int(enabled)))
 
-    def last_kernel_ms(self):
-        ms = (C.c_float * 3)()
-        _check(lib.spex_tree_last_kernel_ms(self._h, ms))
-        return dict(prefix=ms[0], suffix=ms[1], merge=ms[2])
+    def read_profile(self) -> np.ndarray:
+        """[n_calls, 3] milliseconds (prefix, suffix, merge) of the calls recorded so far."""
+        ms = np.zeros((256, 3), dtype=np.float32)
+        n = C.c_int32()
+        _check(lib.spex_tree_read_profile(self._h, ms.ctypes.data_as(C.POINTER(C.c_float)), 256,
+                                          C.byref(n)))
+        return ms[:n.value].copy()
 
     def last_launch_info(self) -> dict:
         info = (C.c_int64 * 8)()

@@ -65,9 +65,15 @@ struct spex_tree {
   int64_t part_cap_rows = 0;
 
   int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0;
+  // Profiling: a ring of event sets, one per decode_attention call since it was enabled.
+  static constexpr int kProfSlots = 256;
+  struct ProfSlot {
+    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    bool valid[3] = {false, false, false};
+  };
   bool profiling = false;
-  hipEvent_t prof_ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-  bool prof_valid[3] = {false, false, false};
+  std::vector<ProfSlot> prof;
+  int64_t prof_calls = 0;  // calls recorded since profiling was enabled / last read
   int64_t info[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 };
 
@@ -282,15 +288,16 @@ spex_status_t spex_tree_create(const spex_config_t *cfg, spex_tree_t **out) {
 
 void spex_tree_destroy(spex_tree_t *t) {
   if (!t) return;
-  const bool used_device = t->d_plan || t->d_part_o || t->h_stage || t->stage_event || t->prof_ev[0];
+  const bool used_device = t->d_plan || t->d_part_o || t->h_stage || t->stage_event || !t->prof.empty();
   if (used_device) (void)hipDeviceSynchronize();
   if (t->d_plan) (void)hipFree(t->d_plan);
   if (t->d_part_o) (void)hipFree(t->d_part_o);
   if (t->d_part_ml) (void)hipFree(t->d_part_ml);
   if (t->h_stage) (void)hipHostFree(t->h_stage);
   if (t->stage_event) (void)hipEventDestroy(t->stage_event);
-  for (hipEvent_t e : t->prof_ev)
-    if (e) (void)hipEventDestroy(e);
+  for (auto &slot : t->prof)
+    for (hipEvent_t e : slot.ev)
+      if (e) (void)hipEventDestroy(e);
   delete t->pt;
   delete t;
 }
@@ -414,14 +421,19 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   const bool generic = t->kernel_mode == 1;
 
+  spex_tree::ProfSlot *slot = nullptr;
   if (t->profiling) {
-    for (hipEvent_t &e : t->prof_ev)
+    if (t->prof.empty()) t->prof.resize(spex_tree::kProfSlots);
+    slot = &t->prof[t->prof_calls % spex_tree::kProfSlots];
+    ++t->prof_calls;
+    for (hipEvent_t &e : slot->ev)
       if (!e) HIP_TRY(hipEventCreate(&e));
-    for (bool &b : t->prof_valid) b = false;
+    for (bool &b : slot->valid) b = false;
   }
   auto bracket = [&](int which, bool begin) -> hipError_t {
-    if (!t->profiling) return hipSuccess;
-    return hipEventRecord(t->prof_ev[2 * which + (begin ? 0 : 1)], stream);
+    if (!slot) return hipSuccess;
+    if (!begin) slot->valid[which] = true;
+    return hipEventRecord(slot->ev[2 * which + (begin ? 0 : 1)], stream);
   };
 
   const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / 2);
@@ -432,7 +444,6 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     HIP_TRY(bracket(0, true));
     HIP_TRY(spex::launch_attention(t->shape, a, true, pl.prefix_row_tiles, generic, stream));
     HIP_TRY(bracket(0, false));
-    t->prof_valid[0] = t->profiling;
   }
   if (n_suffix_items > 0) {
     a.items = dp.suffix_items;
@@ -440,7 +451,6 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     HIP_TRY(bracket(1, true));
     HIP_TRY(spex::launch_attention(t->shape, a, false, pl.suffix_row_tiles, generic, stream));
     HIP_TRY(bracket(1, false));
-    t->prof_valid[1] = t->profiling;
   }
   spex::MergeArgs m{};
   m.part_indptr = dp.part_indptr;
@@ -454,7 +464,6 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   HIP_TRY(bracket(2, true));
   HIP_TRY(spex::launch_merge(t->shape, m, stream));
   HIP_TRY(bracket(2, false));
-  t->prof_valid[2] = t->profiling;
 
   t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
   t->info[1] = pl.prefix_tokens;
@@ -611,18 +620,28 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
 spex_status_t spex_tree_set_profiling(spex_tree_t *t, int32_t enabled) {
   if (!t) return SPEX_ERR_INVALID_ARG;
   t->profiling = enabled != 0;
+  t->prof_calls = 0;
   return SPEX_OK;
 }
 
-spex_status_t spex_tree_last_kernel_ms(spex_tree_t *t, float ms[3]) {
-  if (!t || !ms) return SPEX_ERR_INVALID_ARG;
-  float r[3] = {0.f, 0.f, 0.f};
-  for (int i = 0; i < 3; ++i) {
-    if (!t->prof_valid[i]) continue;
-    HIP_TRY(hipEventSynchronize(t->prof_ev[2 * i + 1]));
-    HIP_TRY(hipEventElapsedTime(&r[i], t->prof_ev[2 * i], t->prof_ev[2 * i + 1]));
+spex_status_t spex_tree_read_profile(spex_tree_t *t, float *ms, int32_t cap, int32_t *n) {
+  if (!t || !n || cap < 0 || (cap > 0 && !ms)) return SPEX_ERR_INVALID_ARG;
+  const int64_t have = t->prof_calls < spex_tree::kProfSlots ? t->prof_calls : spex_tree::kProfSlots;
+  *n = static_cast<int32_t>(have);
+  if (have > cap) return SPEX_ERR_CAPACITY;
+  const int64_t first = t->prof_calls - have;
+  for (int64_t c = 0; c < have; ++c) {
+    spex_tree::ProfSlot &slot = t->prof[(first + c) % spex_tree::kProfSlots];
+    for (int i = 0; i < 3; ++i) {
+      float r = 0.f;
+      if (slot.valid[i]) {
+        HIP_TRY(hipEventSynchronize(slot.ev[2 * i + 1]));
+        HIP_TRY(hipEventElapsedTime(&r, slot.ev[2 * i], slot.ev[2 * i + 1]));
+      }
+      ms[c * 3 + i] = r;
+    }
   }
-  for (int i = 0; i < 3; ++i) ms[i] = r[i];
+  t->prof_calls = 0;
   return SPEX_OK;
 }
 

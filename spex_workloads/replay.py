@@ -77,8 +77,6 @@ def replay(wl: Workload, sink, device="cpu", batch_tokens: Optional[int] = None,
         else:
             skip = only_nodes is not None and op.node not in only_nodes
             if skip:
-                if wl.kv_dtype == "fp8_e4m3":
-                    raise ValueError("only_nodes is not supported for fp8 traces")
                 sink.append(op.node, None, None, None, None, n_tokens=op.n)
                 n_tokens[op.node] += op.n
                 continue
