@@ -33,11 +33,14 @@ def parse():
                     choices=["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts"])
     ap.add_argument("--copies", type=int, default=0, help="rotating tree copies (0 = automatic)")
     ap.add_argument("--placement", default="random", choices=["random", "ascending"])
+    ap.add_argument("--kv-pools", default="interleaved", choices=["interleaved", "separate"])
     ap.add_argument("--prefix-chunk", type=int, default=0)
     ap.add_argument("--suffix-chunk", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
-    ap.add_argument("--check", action="store_true", help="compare a sample of outputs with the oracle")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one elementwise kernel that reads 1 GiB and writes 1 GiB, as the "
+                         "known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     return ap.parse_args()
 
 
@@ -102,7 +105,8 @@ def main():
             order = np.random.default_rng(1000 + c).permutation(n_pages).tolist()
         tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
                              wl.kv_dtype, num_pages=n_pages, device=dev, free_order=order,
-                             prefix_chunk_pages=args.prefix_chunk, suffix_chunk_pages=args.suffix_chunk)
+                             prefix_chunk_pages=args.prefix_chunk, suffix_chunk_pages=args.suffix_chunk,
+                             interleave_kv=args.kv_pools == "interleaved")
         sw.replay(wl, tree, device=dev)
         trees.append(tree)
     q = sw.gen_queries(wl, device=dev)
@@ -181,7 +185,7 @@ def main():
             "query_tokens": nq, "heads": [wl.num_q_heads, wl.num_kv_heads, wl.head_dim],
             "page_size": wl.page_size, "unique_kv_tokens": unique_tokens,
             "unique_kv_bytes": unique_bytes, "flat_kv_bytes": wl.flat_kv_tokens() * b_tok,
-            "tree_copies_rotated": copies, "page_placement": args.placement,
+            "tree_copies_rotated": copies, "page_placement": args.placement, "kv_pools": args.kv_pools,
             "prefix_chunk_pages": args.prefix_chunk, "suffix_chunk_pages": args.suffix_chunk,
         },
         "hbm_gbps_unique_kv": unique_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -199,6 +203,14 @@ def main():
         "build_seconds": t_build,
         "paper_context": PAPER_CONTEXT,
     }
+
+    if args.calibrate:
+        ref_in = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        ref_out = torch.empty_like(ref_in)
+        torch.cuda.synchronize()
+        torch.add(ref_in, 1.0, out=ref_out)
+        torch.cuda.synchronize()
+        del ref_in, ref_out
 
     if not args.no_cpu_baseline:
         n_cpu = args.cpu_sample_leaves or {"tiny_tree": 4, "bfs_tot": 512, "mcts_skewed": 1105,

@@ -48,10 +48,10 @@ typedef enum {
 typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
 
 /*
- * Pool layout.  k_pool and v_pool are caller-owned DEVICE buffers of
- * num_pages * num_kv_heads * page_size * head_dim elements of kv_dtype each (see
- * spex_pool_bytes).  The (page, kv head) tile at element offset
- * (page * num_kv_heads + head) * page_size * head_dim holds page_size tokens; only
+ * Pool layout.  k_pool and v_pool are caller-owned DEVICE buffers of (page, kv head) tiles of
+ * page_size * head_dim elements of kv_dtype; with the dense stride each holds
+ * num_pages * num_kv_heads tiles (see spex_pool_bytes and page_stride_tiles).  The tile at element
+ * offset (page * page_stride_tiles + head) * page_size * head_dim holds page_size tokens; only
  * the library reads and writes inside a tile, in one of two arrangements:
  *
  *  ROW-MAJOR  (kv_dtype F32, or page_size != 16, or head_dim not 64 / 128):
@@ -87,7 +87,10 @@ typedef struct {
   int32_t prefix_chunk_pages; /* split granularity of shared-prefix segments; 0 = automatic */
   int32_t suffix_chunk_pages; /* split granularity of private suffixes;       0 = automatic */
   int32_t kernel_mode;  /* 0 = fastest kernels available; 1 = force the generic (non-MFMA) kernels */
-  int32_t reserved;     /* must be 0 */
+  int32_t page_stride_tiles; /* distance between consecutive pages of a pool, in (page, head) tiles;
+                                0 = num_kv_heads (dense).  2 * num_kv_heads with
+                                v_pool = k_pool + num_kv_heads tiles interleaves K and V of a page
+                                in one buffer, so that a page's K and V share a 64 KiB region. */
 } spex_config_t;
 
 /* Bytes each of k_pool and v_pool must hold for this config. */

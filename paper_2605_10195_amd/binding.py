@@ -42,7 +42,7 @@ class Config(C.Structure):
         ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
         ("free_order", C.POINTER(C.c_int32)),
         ("prefix_chunk_pages", C.c_int32), ("suffix_chunk_pages", C.c_int32),
-        ("kernel_mode", C.c_int32), ("reserved", C.c_int32),
+        ("kernel_mode", C.c_int32), ("page_stride_tiles", C.c_int32),
     ]
 
 
@@ -144,7 +144,8 @@ class SpexTree:
                  q_dtype: str = "bf16", kv_dtype: str = "bf16", num_pages: int = 0,
                  device="cuda", free_order: Optional[Sequence[int]] = None,
                  prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0,
-                 host_only: bool = False, pool_fill: Optional[int] = None):
+                 host_only: bool = False, pool_fill: Optional[int] = None,
+                 interleave_kv: bool = False):
         self.Hq, self.Hkv, self.D, self.P = num_q_heads, num_kv_heads, head_dim, page_size
         self.q_dtype, self.kv_dtype = _DTYPES[q_dtype], _DTYPES[kv_dtype]
         self.num_pages = int(num_pages)
@@ -161,8 +162,17 @@ class SpexTree:
             nbytes = C.c_size_t()
             _check(lib.spex_pool_bytes(C.byref(cfg), C.byref(nbytes)))
             fill = 0 if pool_fill is None else pool_fill
-            self.k_pool = torch.full((max(nbytes.value, 16),), fill, dtype=torch.uint8, device=self.device)
-            self.v_pool = torch.full((max(nbytes.value, 16),), fill, dtype=torch.uint8, device=self.device)
+            if interleave_kv:
+                # one buffer, [page][K tiles of all heads | V tiles of all heads]
+                esz = {F32: 4, BF16: 2, FP8_E4M3: 1}[self.kv_dtype]
+                half = num_kv_heads * page_size * head_dim * esz
+                self.k_pool = torch.full((max(2 * half * self.num_pages, 16),), fill, dtype=torch.uint8,
+                                         device=self.device)
+                self.v_pool = self.k_pool[half:]
+                cfg.page_stride_tiles = 2 * num_kv_heads
+            else:
+                self.k_pool = torch.full((max(nbytes.value, 16),), fill, dtype=torch.uint8, device=self.device)
+                self.v_pool = torch.full((max(nbytes.value, 16),), fill, dtype=torch.uint8, device=self.device)
             cfg.k_pool, cfg.v_pool = self.k_pool.data_ptr(), self.v_pool.data_ptr()
             if self.kv_dtype == FP8_E4M3:
                 n = max(self.num_pages * num_kv_heads, 1)

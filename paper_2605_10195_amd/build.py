@@ -23,8 +23,7 @@ def build_library(verbose: bool = False) -> str:
     """Always recompiles; returns the path of the shared library."""
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wall", "-Wno-unused-function",
-           "-x", "hip"]
+           "-Wall", "-Wno-unused-function", "-x", "hip"]
     cmd += [os.path.join(CSRC, s) for s in SOURCES]
     cmd += ["-o", LIB_PATH]
     if verbose:

@@ -35,11 +35,7 @@ bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 
 // Device copy of a Plan: one blob, arrays at 256-byte aligned offsets.
 struct DevicePlan {
-  const int32_t *prefix_items = nullptr, *suffix_items = nullptr;
-  const int32_t *task_pg_begin = nullptr, *task_pg_count = nullptr, *task_qt_begin = nullptr,
-                *task_qt_count = nullptr, *task_pbase = nullptr, *task_flags = nullptr;
-  const int32_t *pg_id = nullptr, *pg_valid = nullptr, *pg_pos = nullptr, *qt_list = nullptr,
-                *qt_limit = nullptr;
+  const int32_t *prefix_items = nullptr, *suffix_items = nullptr, *pg_rec = nullptr, *qt_rec = nullptr;
   const int32_t *part_indptr = nullptr, *part_base = nullptr, *part_hstride = nullptr;
 };
 
@@ -87,8 +83,8 @@ spex_status_t check_config(const spex_config_t *c) {
   if (c->head_dim < 1 || c->head_dim > 256) return SPEX_ERR_INVALID_ARG;
   if (!is_pow2(c->page_size) || c->page_size > 64) return SPEX_ERR_INVALID_ARG;
   if (c->num_pages < 0 || c->num_pages > INT32_MAX) return SPEX_ERR_INVALID_ARG;
-  if (c->prefix_chunk_pages < 0 || c->suffix_chunk_pages < 0 || c->reserved != 0)
-    return SPEX_ERR_INVALID_ARG;
+  if (c->prefix_chunk_pages < 0 || c->suffix_chunk_pages < 0) return SPEX_ERR_INVALID_ARG;
+  if (c->page_stride_tiles != 0 && c->page_stride_tiles < c->num_kv_heads) return SPEX_ERR_INVALID_ARG;
   if (c->kernel_mode != 0 && c->kernel_mode != 1) return SPEX_ERR_INVALID_ARG;
   const bool ok = (c->q_dtype == SPEX_F32 && c->kv_dtype == SPEX_F32) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_BF16) ||
@@ -113,6 +109,7 @@ spex::Shape make_shape(const spex_config_t &c) {
   s.kv_dtype = c.kv_dtype;
   const bool tiled = c.kv_dtype != SPEX_F32 && c.page_size == 16 && (c.head_dim == 64 || c.head_dim == 128);
   s.layout = tiled ? spex::kMfmaTiled : spex::kRowMajor;
+  s.page_tiles = c.page_stride_tiles ? c.page_stride_tiles : c.num_kv_heads;
   return s;
 }
 
@@ -152,9 +149,8 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
 spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   const spex::Plan &pl = t->plan;
   const std::vector<int32_t> *arrays[] = {
-      &pl.prefix_items, &pl.suffix_items, &pl.task_pg_begin, &pl.task_pg_count, &pl.task_qt_begin,
-      &pl.task_qt_count, &pl.task_pbase, &pl.task_flags, &pl.pg_id, &pl.pg_valid, &pl.pg_pos,
-      &pl.qt_list, &pl.qt_limit, &pl.part_indptr, &pl.part_base, &pl.part_hstride};
+      &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
+      &pl.part_indptr, &pl.part_base,    &pl.part_hstride};
   constexpr int kN = sizeof(arrays) / sizeof(arrays[0]);
   size_t off[kN], total = 0;
   for (int i = 0; i < kN; ++i) {
@@ -194,20 +190,11 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   DevicePlan &dp = t->dplan;
   dp.prefix_items = at(0);
   dp.suffix_items = at(1);
-  dp.task_pg_begin = at(2);
-  dp.task_pg_count = at(3);
-  dp.task_qt_begin = at(4);
-  dp.task_qt_count = at(5);
-  dp.task_pbase = at(6);
-  dp.task_flags = at(7);
-  dp.pg_id = at(8);
-  dp.pg_valid = at(9);
-  dp.pg_pos = at(10);
-  dp.qt_list = at(11);
-  dp.qt_limit = at(12);
-  dp.part_indptr = at(13);
-  dp.part_base = at(14);
-  dp.part_hstride = at(15);
+  dp.pg_rec = at(2);
+  dp.qt_rec = at(3);
+  dp.part_indptr = at(4);
+  dp.part_base = at(5);
+  dp.part_hstride = at(6);
   t->plan_on_device = true;
   return SPEX_OK;
 }
@@ -252,8 +239,12 @@ spex_status_t spex_pool_bytes(const spex_config_t *cfg, size_t *bytes_per_pool) 
   if (cfg->num_pages < 0 || cfg->num_kv_heads <= 0 || cfg->page_size <= 0 || cfg->head_dim <= 0 ||
       cfg->kv_dtype < 0 || cfg->kv_dtype > 2)
     return SPEX_ERR_INVALID_ARG;
-  *bytes_per_pool = static_cast<size_t>(cfg->num_pages) * cfg->num_kv_heads * cfg->page_size *
-                    cfg->head_dim * elem_size(cfg->kv_dtype);
+  const size_t tiles = cfg->page_stride_tiles ? cfg->page_stride_tiles : cfg->num_kv_heads;
+  const size_t tile_bytes = static_cast<size_t>(cfg->page_size) * cfg->head_dim * elem_size(cfg->kv_dtype);
+  // A strided pool ends with the last page's own tiles, not with a full stride.
+  *bytes_per_pool = cfg->num_pages == 0 ? 0
+                                        : (static_cast<size_t>(cfg->num_pages - 1) * tiles +
+                                           cfg->num_kv_heads) * tile_bytes;
   return SPEX_OK;
 }
 
@@ -405,17 +396,8 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   a.k_scale = t->cfg.k_scale;
   a.v_scale = t->cfg.v_scale;
   a.q = q;
-  a.task_pg_begin = dp.task_pg_begin;
-  a.task_pg_count = dp.task_pg_count;
-  a.task_qt_begin = dp.task_qt_begin;
-  a.task_qt_count = dp.task_qt_count;
-  a.task_pbase = dp.task_pbase;
-  a.task_flags = dp.task_flags;
-  a.pg_id = dp.pg_id;
-  a.pg_valid = dp.pg_valid;
-  a.pg_pos = dp.pg_pos;
-  a.qt_list = dp.qt_list;
-  a.qt_limit = dp.qt_limit;
+  a.pg_rec = dp.pg_rec;
+  a.qt_rec = dp.qt_rec;
   a.part_o = t->d_part_o;
   a.part_ml = t->d_part_ml;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
@@ -436,8 +418,8 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     return hipEventRecord(slot->ev[2 * which + (begin ? 0 : 1)], stream);
   };
 
-  const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / 2);
-  const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / 2);
+  const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / spex::Plan::kItemInts);
+  const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / spex::Plan::kItemInts);
   if (n_prefix_items > 0) {
     a.items = dp.prefix_items;
     a.n_items = n_prefix_items;

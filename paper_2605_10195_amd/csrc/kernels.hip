@@ -31,6 +31,15 @@ constexpr float kNegInf = -__builtin_huge_valf();
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// Wave-uniform read of plan data through the scalar (constant) path.  The plan arrays are
+// written by the host before the launch and never by a kernel.  Going through scalar loads keeps
+// these small reads out of the vector-memory queue, whose in-order completion counter would
+// otherwise make every page-record lookup wait for all K/V loads in flight.
+typedef const int32_t __attribute__((address_space(4))) const_i32;
+__device__ __forceinline__ int sload(const int32_t *base, int64_t idx) {
+  return ((const_i32 *)(uintptr_t)base)[idx];
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // ---- element offsets inside a (page, kv head) tile ------------------------------------------
@@ -106,79 +115,73 @@ struct RawBlock {
   float ks, vs;  // this lane's page scales (fp8), else 1
 };
 
+// Wave-uniform description of one work item.
+struct Item {
+  int pg_begin, pg_count, qt_begin, qt_count, pbase, flags, g, row0;
+};
+
+__device__ __forceinline__ Item load_item(const int32_t *items, int idx) {
+  const int64_t r = static_cast<int64_t>(uniform(idx)) * 8;
+  Item it;
+  it.pg_begin = sload(items, r + 0);
+  it.pg_count = sload(items, r + 1);
+  it.qt_begin = sload(items, r + 2);
+  it.qt_count = sload(items, r + 3);
+  it.pbase = sload(items, r + 4);
+  it.flags = sload(items, r + 5);
+  it.g = sload(items, r + 6);
+  it.row0 = sload(items, r + 7);
+  return it;
+}
+
+// Page ids / valid counts / positions of one 32-token block, wave-uniform.
+struct BlockMeta {
+  int pid_a, pid_b, vp_a, vp_b;  // vp = position << 7 | valid; vp_b = 0 when the block has one page
+};
+
+__device__ __forceinline__ BlockMeta load_block_meta(const int32_t *pg_rec, const Item &it, int b) {
+  const int ia = it.pg_begin + 2 * b;
+  const bool has_b = 2 * b + 1 < it.pg_count;
+  const int ib = has_b ? ia + 1 : ia;
+  BlockMeta bm;
+  bm.pid_a = sload(pg_rec, 2 * ia);
+  bm.vp_a = sload(pg_rec, 2 * ia + 1);
+  bm.pid_b = sload(pg_rec, 2 * ib);
+  bm.vp_b = has_b ? sload(pg_rec, 2 * ib + 1) : 0;
+  return bm;
+}
+
+// One wavefront per work item.  The K/V loads of block b+1 are in flight while block b is
+// computed.  The steady-state loop is free of conditional loads on purpose: the vector-memory
+// completion counter is in-order, and a load that is issued on one path only would force the
+// compiler to wait for everything outstanding at the join.
 template <int KV, int D, int NT>
-__device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh, int item) {
+__device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   constexpr int ESZ = (KV == kFP8) ? 1 : 2;
   constexpr int TILE_BYTES = 16 * D * ESZ;
   const int lane = threadIdx.x & 63;
   const int m16 = lane & 15;
   const int jj = lane >> 4;
-
-  const int task = uniform(p.items[2 * item]);
-  const int packed = uniform(p.items[2 * item + 1]);
-  const int g = packed & 0xff;
-  const int rt = packed >> 8;
-  const int pg_begin = uniform(p.task_pg_begin[task]);
-  const int pg_count = uniform(p.task_pg_count[task]);
-  const int qt_begin = uniform(p.task_qt_begin[task]);
-  const int qt_count = uniform(p.task_qt_count[task]);
-  const int pbase = uniform(p.task_pbase[task]);
-  const bool task_masked = (uniform(p.task_flags[task]) & 1) != 0;
+  const int item_idx = uniform(blockIdx.x * 4 + (threadIdx.x >> 6));
+  if (item_idx >= p.n_items) return;
   const int G = sh.G;
-  const int rows = qt_count * G;
-  const int row0 = rt * 16 * NT;
-
-  // Query operand: lane (row n = lane%16, k-group j = lane/16) holds dims s*32 + 8j .. +7.
-  bf16x8 qf[NT][D / 32];
-  int limit[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int r = row0 + nt * 16 + m16;
-    limit[nt] = INT_MAX;
-    if (r < rows) {
-      const int qt = p.qt_list[qt_begin + r / G];
-      const int hh = r % G;
-      limit[nt] = p.qt_limit[qt];
-      const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
-                           (static_cast<int64_t>(qt) * sh.Hq + g * G + hh) * D + jj * 8;
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s)
-        qf[nt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + s * 32));
-    } else {
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s) qf[nt][s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
-    }
-  }
-
-  f32x4 o_acc[NT][D / 16];
-  float m_run[NT], l_run[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    m_run[nt] = kNegInf;
-    l_run[nt] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
   const char *kpool = static_cast<const char *>(p.k_pool);
   const char *vpool = static_cast<const char *>(p.v_pool);
   // Byte offset of this lane inside a K half-tile / a V tile.
-  const int k_lane_off = jj * (64 * ESZ * (KV == kFP8 ? 2 : 1)) + (m16 & 7) * 16;
+  const int k_lane_off = jj * 128 + (m16 & 7) * 16;
   const int v_lane_off = (jj & 1) * 256 + m16 * 16;
-  const int nblk = (pg_count + 1) >> 1;
 
-  auto load_block = [&](RawBlock<KV, D> &rb, int b) {
-    const int ia = pg_begin + 2 * b;
-    const bool has_b = 2 * b + 1 < pg_count;
-    const int ib = has_b ? ia + 1 : ia;
-    const int pid_a = uniform(p.pg_id[ia]);
-    const int pid_b = uniform(p.pg_id[ib]);
-    rb.valid_a = uniform(p.pg_valid[ia]);
-    rb.valid_b = has_b ? uniform(p.pg_valid[ib]) : 0;
-    rb.pos_a = uniform(p.pg_pos[ia]);
-    rb.pos_b = uniform(p.pg_pos[ib]);
-    const int64_t tile_a = (static_cast<int64_t>(pid_a) * sh.Hkv + g);
-    const int64_t tile_b = (static_cast<int64_t>(pid_b) * sh.Hkv + g);
+  const Item cur = load_item(p.items, item_idx);
+  const int g = cur.g;
+  const int nblk = (cur.pg_count + 1) >> 1;
+
+  auto issue_loads = [&](RawBlock<KV, D> &rb, const BlockMeta &bm) {
+    rb.valid_a = bm.vp_a & 127;
+    rb.valid_b = bm.vp_b & 127;
+    rb.pos_a = bm.vp_a >> 7;
+    rb.pos_b = bm.vp_b >> 7;
+    const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
+    const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
     const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
     const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
 #pragma unroll
@@ -190,146 +193,208 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh, in
     for (int s = 0; s < RawBlock<KV, D>::NV; ++s)
       rb.v[s] = *reinterpret_cast<const u32x4 *>(vp + s * 512);
     if (KV == kFP8) {
-      rb.ks = p.k_scale[(jj < 2 ? tile_a : tile_b)];
-      rb.vs = p.v_scale[(jj < 2 ? tile_a : tile_b)];
+      const int sidx = (jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g;
+      rb.ks = p.k_scale[sidx];
+      rb.vs = p.v_scale[sidx];
     } else {
       rb.ks = 1.f;
       rb.vs = 1.f;
     }
   };
+  // page records of block min(b, nblk - 1)
+  auto meta = [&](int b) { return load_block_meta(p.pg_rec, cur, b < nblk ? b : nblk - 1); };
 
-  auto compute_block = [&](const RawBlock<KV, D> &rb) {
-    bf16x8 kf[2][D / 32];
-    bf16x8 vf[D / 16];
-    if (KV == kFP8) {
+  const bool task_masked = (cur.flags & 1) != 0;
+  const int rows = cur.qt_count * G;
+
+  // Query operand: lane (row n = lane%16, k-group j = lane/16) holds dims s*32 + 8j .. +7.
+  bf16x8 qf[NT][D / 32];
+  int limit[NT];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+  for (int nt = 0; nt < NT; ++nt) {
+    const int r = cur.row0 + nt * 16 + m16;
+    limit[nt] = INT_MAX;
+    if (r < rows) {
+      const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (cur.qt_begin + r / G));
+      const int hh = r % G;
+      limit[nt] = qr.y;
+      const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
+                           (static_cast<int64_t>(qr.x) * sh.Hq + g * G + hh) * D + jj * 8;
 #pragma unroll
-        for (int s = 0; s < D / 64; ++s) {
-          kf[t][2 * s] = fp8x8_to_bf16x8(rb.k[t][s][0], rb.k[t][s][1]);
-          kf[t][2 * s + 1] = fp8x8_to_bf16x8(rb.k[t][s][2], rb.k[t][s][3]);
-        }
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s) {
-        vf[2 * s] = fp8x8_to_bf16x8(rb.v[s][0], rb.v[s][1]);
-        vf[2 * s + 1] = fp8x8_to_bf16x8(rb.v[s][2], rb.v[s][3]);
-      }
+      for (int s = 0; s < D / 32; ++s)
+        qf[nt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + s * 32));
     } else {
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, rb.k[t][s]);
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
-    }
-    const bool masked = task_masked || rb.valid_b == 0;
-    // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
-    const int pg_valid_l = jj < 2 ? rb.valid_a : rb.valid_b;
-    const int pg_pos_l = jj < 2 ? rb.pos_a : rb.pos_b;
-    const float c = p.scale_log2 * rb.ks;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s) {
-        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt][s], sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt][s], sb, 0, 0, 0);
-      }
-      float x[8];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        x[i] = sa[i] * c;
-        x[4 + i] = sb[i] * c;
-      }
-      if (masked) {
-        int vis = limit[nt] - pg_pos_l;
-        vis = vis < pg_valid_l ? vis : pg_valid_l;
-        vis -= 8 * (jj & 1);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
-      }
-      float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                       fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[nt], mx);
-      const float m_safe = m_new == kNegInf ? 0.f : m_new;
-      const float alpha = fast_exp2(m_run[nt] - m_safe);
-      float pr[8];
-      float lsum = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        pr[i] = fast_exp2(x[i] - m_safe);
-        lsum += pr[i];
-      }
-      l_run[nt] = l_run[nt] * alpha + lsum;
-      m_run[nt] = m_new;
-      if (!__all(alpha == 1.0f)) {
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] *= alpha;
-      }
-      // P as two bf16 pieces (hi + lo) so that the product keeps ~16 bits of each weight.
-      u32x4 phi, plo;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float a0 = pr[2 * i] * rb.vs, a1 = pr[2 * i + 1] * rb.vs;
-        const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
-        const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
-        phi[i] = pack_hi16(h0, h1);
-        plo[i] = pack_hi16(a0 - h0, a1 - h1);
-      }
-      const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
-      const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
-#pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) {
-        o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, o_acc[nt][dt], 0, 0, 0);
-        o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, o_acc[nt][dt], 0, 0, 0);
-      }
-    }
-  };
-
-  RawBlock<KV, D> r0, r1;
-  load_block(r0, 0);
-  for (int b = 0; b < nblk; b += 2) {
-    const bool more1 = b + 1 < nblk;
-    if (more1) load_block(r1, b + 1);
-    compute_block(r0);
-    if (more1) {
-      if (b + 2 < nblk) load_block(r0, b + 2);
-      compute_block(r1);
+      for (int s = 0; s < D / 32; ++s) qf[nt][s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
     }
   }
 
+  RawBlock<KV, D> r0, r1;
+  issue_loads(r0, meta(0));
+
+  f32x4 o_acc[NT][D / 16];
+  float m_run[NT], l_run[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    m_run[nt] = kNegInf;
+    l_run[nt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+    auto compute_block = [&](const RawBlock<KV, D> &rb) {
+      bf16x8 kf[2][D / 32];
+      bf16x8 vf[D / 16];
+      if (KV == kFP8) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int s = 0; s < D / 64; ++s) {
+            kf[t][2 * s] = fp8x8_to_bf16x8(rb.k[t][s][0], rb.k[t][s][1]);
+            kf[t][2 * s + 1] = fp8x8_to_bf16x8(rb.k[t][s][2], rb.k[t][s][3]);
+          }
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+          vf[2 * s] = fp8x8_to_bf16x8(rb.v[s][0], rb.v[s][1]);
+          vf[2 * s + 1] = fp8x8_to_bf16x8(rb.v[s][2], rb.v[s][3]);
+        }
+      } else {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int s = 0; s < D / 32; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, rb.k[t][s]);
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
+      }
+      const bool masked = task_masked || rb.valid_b == 0;
+      // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
+      const int pg_valid_l = jj < 2 ? rb.valid_a : rb.valid_b;
+      const int pg_pos_l = jj < 2 ? rb.pos_a : rb.pos_b;
+      const float c = p.scale_log2 * rb.ks;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt][s], sa, 0, 0, 0);
+          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt][s], sb, 0, 0, 0);
+        }
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          x[i] = sa[i] * c;
+          x[4 + i] = sb[i] * c;
+        }
+        if (masked) {
+          int vis = limit[nt] - pg_pos_l;
+          vis = vis < pg_valid_l ? vis : pg_valid_l;
+          vis -= 8 * (jj & 1);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+        }
+        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                         fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[nt], mx);
+        const float m_safe = m_new == kNegInf ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run[nt] - m_safe);
+        float pr[8];
+        float lsum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          pr[i] = fast_exp2(x[i] - m_safe);
+          lsum += pr[i];
+        }
+        l_run[nt] = l_run[nt] * alpha + lsum;
+        m_run[nt] = m_new;
+        if (!__all(alpha == 1.0f)) {
+#pragma unroll
+          for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] *= alpha;
+        }
+        // P as two bf16 pieces (hi + lo) so that the product keeps ~16 bits of each weight.
+        u32x4 phi, plo;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float a0 = pr[2 * i] * rb.vs, a1 = pr[2 * i + 1] * rb.vs;
+          const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
+          const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
+          phi[i] = pack_hi16(h0, h1);
+          plo[i] = pack_hi16(a0 - h0, a1 - h1);
+        }
+        const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
+        const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+          o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, o_acc[nt][dt], 0, 0, 0);
+          o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, o_acc[nt][dt], 0, 0, 0);
+        }
+      }
+    };
+
+  BlockMeta bm1 = meta(1);
+  int b = 0;
+  for (; b + 2 < nblk; b += 2) {  // blocks b, b+1, b+2 all exist
+    const BlockMeta bm2 = meta(b + 2);
+    issue_loads(r1, bm1);
+    compute_block(r0);
+    bm1 = meta(b + 3);
+    issue_loads(r0, bm2);
+    compute_block(r1);
+  }
+  if (b + 1 < nblk) {
+    issue_loads(r1, bm1);
+    compute_block(r0);
+    compute_block(r1);
+  } else {
+    compute_block(r0);
+  }
+
   // Partial state: lanes of one row agree on m; l is summed over the four k-groups.
+  // The accumulators hold 4 consecutive dims of one row per lane (64 B runs at a 512 B stride);
+  // stored like that they reach HBM as half-filled cache lines, which costs far more than their
+  // 3 % share of the traffic.  They are transposed through a wave-private LDS tile so that every
+  // store instruction writes two whole rows (1 KiB contiguous).
+  constexpr int kRowPad = D + 4;  // floats per staged row; the pad spreads rows over LDS banks
+  __shared__ float stage[4][16 * kRowPad];
+  float *my = stage[threadIdx.x >> 6];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     float l = l_run[nt];
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
-    const int r = row0 + nt * 16 + m16;
-    if (r < rows) {
-      const int64_t slot = static_cast<int64_t>(pbase) + static_cast<int64_t>(g) * rows + r;
-      if (jj == 0) {
-        p.part_ml[slot * 2] = m_run[nt];
-        p.part_ml[slot * 2 + 1] = l;
-      }
-      float *op = p.part_o + slot * D + jj * 4;
+    const int r0w = cur.row0 + nt * 16;  // first row of this tile
+    const int64_t slot0 = static_cast<int64_t>(cur.pbase) + static_cast<int64_t>(g) * rows + r0w;
+    if (r0w + m16 < rows && jj == 0)
+      *reinterpret_cast<f32x2 *>(p.part_ml + (slot0 + m16) * 2) = f32x2{m_run[nt], l};
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) *reinterpret_cast<f32x4 *>(op + dt * 16) = o_acc[nt][dt];
+    for (int dt = 0; dt < D / 16; ++dt)
+      *reinterpret_cast<f32x4 *>(my + m16 * kRowPad + dt * 16 + jj * 4) = o_acc[nt][dt];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    constexpr int kLanesPerRow = D / 4;            // 16-byte pieces per row
+    constexpr int kRowsPerInst = 64 / kLanesPerRow;
+    const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
+#pragma unroll
+    for (int i = 0; i < 16 / kRowsPerInst; ++i) {
+      const int row = i * kRowsPerInst + sub;
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(my + row * kRowPad + piece * 4);
+      if (r0w + row < rows)
+        *reinterpret_cast<f32x4 *>(p.part_o + (slot0 + row) * D + piece * 4) = v;
     }
   }
 }
 
 template <int KV, int D, int NT>
-__global__ __launch_bounds__(256) void spex_prefix_attn_kernel(AttnArgs p, Shape sh) {
-  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (item < p.n_items) attn_wave<KV, D, NT>(p, sh, item);
+__global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_prefix_attn_kernel(AttnArgs p, Shape sh) {
+  attn_wave<KV, D, NT>(p, sh);
 }
 
 template <int KV, int D, int NT>
-__global__ __launch_bounds__(256) void spex_suffix_attn_kernel(AttnArgs p, Shape sh) {
-  const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (item < p.n_items) attn_wave<KV, D, NT>(p, sh, item);
+__global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_suffix_attn_kernel(AttnArgs p, Shape sh) {
+  attn_wave<KV, D, NT>(p, sh);
 }
 
 // ---- generic attention (no matrix cores) ------------------------------------------------------
@@ -349,27 +414,25 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <int KV, int QT, int LAYOUT>
 __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape sh, int rows_per_item) {
   __shared__ float qs[256];
-  const int item = blockIdx.x;
   const int lane = threadIdx.x;
-  const int task = p.items[2 * item];
-  const int packed = p.items[2 * item + 1];
-  const int g = packed & 0xff;
-  const int rt = packed >> 8;
-  const int pg_begin = p.task_pg_begin[task];
-  const int pg_count = p.task_pg_count[task];
-  const int qt_begin = p.task_qt_begin[task];
-  const int qt_count = p.task_qt_count[task];
-  const int pbase = p.task_pbase[task];
+  const int32_t *rec = p.items + static_cast<int64_t>(blockIdx.x) * 8;
+  const int pg_begin = rec[0];
+  const int pg_count = rec[1];
+  const int qt_begin = rec[2];
+  const int qt_count = rec[3];
+  const int pbase = rec[4];
+  const int g = rec[6];
+  const int row0 = rec[7];
   const int D = sh.D, P = sh.P, G = sh.G;
   const int rows = qt_count * G;
   const int64_t tile_elems = static_cast<int64_t>(P) * D;
   const int n_tok_slots = pg_count * P;
-  const int r_end = min(rows, (rt + 1) * rows_per_item);
+  const int r_end = min(rows, row0 + rows_per_item);
 
-  for (int r = rt * rows_per_item; r < r_end; ++r) {
-    const int qt = p.qt_list[qt_begin + r / G];
+  for (int r = row0; r < r_end; ++r) {
+    const int qt = p.qt_rec[2 * (qt_begin + r / G)];
     const int hh = r % G;
-    const int limit = p.qt_limit[qt];
+    const int limit = p.qt_rec[2 * (qt_begin + r / G) + 1];
     const int64_t qbase = (static_cast<int64_t>(qt) * sh.Hq + g * G + hh) * D;
     __syncthreads();
     for (int d = lane; d < D; d += 64) qs[d] = load_elem<QT>(p.q, qbase + d);
@@ -383,13 +446,16 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
       const int slot = ti % P;
       bool ok = ti < n_tok_slots;
       float s = kNegInf;
-      if (ok) ok = slot < p.pg_valid[e] && p.pg_pos[e] + slot < limit;
       if (ok) {
-        const int64_t tile = (static_cast<int64_t>(p.pg_id[e]) * sh.Hkv + g);
+        const int vp = p.pg_rec[2 * e + 1];
+        ok = slot < (vp & 127) && (vp >> 7) + slot < limit;
+      }
+      if (ok) {
+        const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e]) * sh.page_tiles + g);
         float dot = 0.f;
         for (int d = 0; d < D; ++d)
           dot += qs[d] * load_elem<KV>(p.k_pool, tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D));
-        if (KV == kFP8) dot *= p.k_scale[tile];
+        if (KV == kFP8) dot *= p.k_scale[p.pg_rec[2 * e] * sh.Hkv + g];
         s = dot * p.scale_log2;
       }
       const float m_new = fmaxf(m, wave_max(s));
@@ -406,8 +472,8 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
         if (pt == 0.f) continue;
         const int e2 = pg_begin + (t0 + t) / P;
         const int slot2 = (t0 + t) % P;
-        const int64_t tile = (static_cast<int64_t>(p.pg_id[e2]) * sh.Hkv + g);
-        const float w = (KV == kFP8) ? pt * p.v_scale[tile] : pt;
+        const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e2]) * sh.page_tiles + g);
+        const float w = (KV == kFP8) ? pt * p.v_scale[p.pg_rec[2 * e2] * sh.Hkv + g] : pt;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           const int d = lane + 64 * c;
@@ -494,7 +560,8 @@ __global__ __launch_bounds__(256) void spex_scatter_kv_kernel(ScatterArgs a, Sha
   const int pi = static_cast<int>(tid / (static_cast<int64_t>(D) * P * H));
   const bool is_new = pi > 0 || a.first_page_is_new;
   const int tok = pi * P + slot - a.first_slot;  // index among the tokens of this launch
-  const int64_t tile = (static_cast<int64_t>(a.page_ids[pi]) * H + g);
+  const int64_t tile = (static_cast<int64_t>(a.page_ids[pi]) * sh.page_tiles + g);
+  const int sidx = a.page_ids[pi] * H + g;
   const int64_t tile_elems = static_cast<int64_t>(P) * D;
   T *kp = static_cast<T *>(a.k_pool) + tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D);
   T *vp = static_cast<T *>(a.v_pool) + tile * tile_elems + v_offset<KV, LAYOUT>(slot, d, D);
@@ -508,8 +575,8 @@ __global__ __launch_bounds__(256) void spex_scatter_kv_kernel(ScatterArgs a, Sha
   }
   if (KV == kFP8 && is_new && d == 0 && slot == 0) {
     const int idx_new = pi - (a.first_page_is_new ? 0 : 1);
-    a.k_scale[tile] = a.k_scale_src[idx_new * H + g];
-    a.v_scale[tile] = a.v_scale_src[idx_new * H + g];
+    a.k_scale[sidx] = a.k_scale_src[idx_new * H + g];
+    a.v_scale[sidx] = a.v_scale_src[idx_new * H + g];
   }
 }
 
@@ -526,15 +593,16 @@ __global__ __launch_bounds__(256) void spex_gather_kv_kernel(GatherArgs a, Shape
   const int tok = static_cast<int>(tid / (static_cast<int64_t>(D) * H));
   const int pi = (tok + a.first_slot) / P;
   const int slot = (tok + a.first_slot) % P;
-  const int64_t tile = (static_cast<int64_t>(a.page_ids[pi]) * H + g);
+  const int64_t tile = (static_cast<int64_t>(a.page_ids[pi]) * sh.page_tiles + g);
+  const int sidx = a.page_ids[pi] * H + g;
   const int64_t tile_elems = static_cast<int64_t>(P) * D;
   static_cast<T *>(a.k_out)[tid] =
       static_cast<const T *>(a.k_pool)[tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D)];
   static_cast<T *>(a.v_out)[tid] =
       static_cast<const T *>(a.v_pool)[tile * tile_elems + v_offset<KV, LAYOUT>(slot, d, D)];
   if (KV == kFP8 && d == 0) {
-    if (a.k_scale_out) a.k_scale_out[static_cast<int64_t>(tok) * H + g] = a.k_scale[tile];
-    if (a.v_scale_out) a.v_scale_out[static_cast<int64_t>(tok) * H + g] = a.v_scale[tile];
+    if (a.k_scale_out) a.k_scale_out[static_cast<int64_t>(tok) * H + g] = a.k_scale[sidx];
+    if (a.v_scale_out) a.v_scale_out[static_cast<int64_t>(tok) * H + g] = a.v_scale[sidx];
   }
 }
 

@@ -15,6 +15,7 @@ enum Layout : int32_t { kRowMajor = 0, kMfmaTiled = 1 };
 struct Shape {
   int32_t Hq, Hkv, G, D, P;
   int32_t q_dtype, kv_dtype, layout;
+  int32_t page_tiles;  // tiles between the starts of consecutive pages inside a pool (>= Hkv)
 };
 
 // Everything the attention kernels read; all pointers DEVICE.
@@ -22,11 +23,11 @@ struct AttnArgs {
   const void *k_pool, *v_pool;
   const float *k_scale, *v_scale;
   const void *q;
-  const int32_t *items;  // {task, kv_head | row_tile << 8} per work item
+  const int32_t *items;   // 8 ints per work item: {pg_begin, pg_count, qt_begin, qt_count, pbase,
+                          //                       flags, kv_head, first_row}
   int32_t n_items;
-  const int32_t *task_pg_begin, *task_pg_count, *task_qt_begin, *task_qt_count, *task_pbase,
-      *task_flags;
-  const int32_t *pg_id, *pg_valid, *pg_pos, *qt_list, *qt_limit;
+  const int32_t *pg_rec;  // 2 ints per page entry: {page id, path position << 7 | valid tokens}
+  const int32_t *qt_rec;  // 2 ints per row-set entry: {query token, visible path length}
   float *part_o;   // [partial rows][D] unnormalised sum of exp2(x - m) * V
   float *part_ml;  // [partial rows][2] = {m, l}: running maximum of x = score * log2(e), sum of exp2
   float scale_log2;

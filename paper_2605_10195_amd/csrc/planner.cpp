@@ -76,9 +76,10 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     }
     path_indptr[i + 1] = static_cast<int32_t>(path_nodes.size());
     pl.leaf_indptr.push_back(static_cast<int32_t>(pl.leaf_pages.size()));
-    if (ql < 1 || ql > T || T > std::numeric_limits<int32_t>::max() / 2) {
+    if (ql < 1 || ql > T || T >= (1 << 24)) {
       reset();
-      return ql < 1 ? PlanError::kInvalid : PlanError::kEmptyPath;
+      if (ql < 1) return PlanError::kInvalid;
+      return ql > T ? PlanError::kEmptyPath : PlanError::kTooLarge;  // positions are packed in 24 bits
     }
     qoff[i] = static_cast<int32_t>(pl.qt_limit.size());
     for (int32_t j = 0; j < ql; ++j) pl.qt_limit.push_back(static_cast<int32_t>(T) - ql + 1 + j);
@@ -228,21 +229,31 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     });
     return ord;
   };
+  auto push_item = [&](std::vector<int32_t> &items, int32_t t, int32_t g, int32_t row0) {
+    const int32_t rec[Plan::kItemInts] = {pl.task_pg_begin[t], pl.task_pg_count[t],
+                                          pl.task_qt_begin[t], pl.task_qt_count[t],
+                                          pl.task_pbase[t],    pl.task_flags[t], g, row0};
+    items.insert(items.end(), rec, rec + Plan::kItemInts);
+  };
   for (int32_t t : order_of(0, pl.n_prefix_tasks)) {
     const int32_t n_rt = (pl.task_qt_count[t] * G + rw_prefix - 1) / rw_prefix;
     for (int32_t g = 0; g < num_kv_heads; ++g)
-      for (int32_t rt = 0; rt < n_rt; ++rt) {
-        pl.prefix_items.push_back(t);
-        pl.prefix_items.push_back(g | (rt << 8));
-      }
+      for (int32_t rt = 0; rt < n_rt; ++rt) push_item(pl.prefix_items, t, g, rt * rw_prefix);
   }
   for (int32_t t : order_of(pl.n_prefix_tasks, n_tasks)) {
     const int32_t n_rt = (pl.task_qt_count[t] * G + rw_suffix - 1) / rw_suffix;
     for (int32_t rt = 0; rt < n_rt; ++rt)
-      for (int32_t g = 0; g < num_kv_heads; ++g) {
-        pl.suffix_items.push_back(t);
-        pl.suffix_items.push_back(g | (rt << 8));
-      }
+      for (int32_t g = 0; g < num_kv_heads; ++g) push_item(pl.suffix_items, t, g, rt * rw_suffix);
+  }
+  pl.pg_rec.resize(pl.pg_id.size() * 2);
+  for (size_t i = 0; i < pl.pg_id.size(); ++i) {
+    pl.pg_rec[2 * i] = pl.pg_id[i];
+    pl.pg_rec[2 * i + 1] = (pl.pg_pos[i] << 7) | pl.pg_valid[i];
+  }
+  pl.qt_rec.resize(pl.qt_list.size() * 2);
+  for (size_t i = 0; i < pl.qt_list.size(); ++i) {
+    pl.qt_rec[2 * i] = pl.qt_list[i];
+    pl.qt_rec[2 * i + 1] = pl.qt_limit[pl.qt_list[i]];
   }
   pl.valid = true;
   return PlanError::kOk;

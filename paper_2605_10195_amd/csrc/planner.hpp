@@ -42,8 +42,12 @@ struct Plan {
   int64_t n_partial_rows = 0;
   int32_t prefix_chunk_pages = 0, suffix_chunk_pages = 0;  // values used
 
-  // ---- launch lists: 2 ints per work item = {task, kv_head | row_tile << 8}
-  std::vector<int32_t> prefix_items, suffix_items;
+  // ---- launch lists (device side).  A work item is kItemInts ints:
+  //   {pg_begin, pg_count, qt_begin, qt_count, pbase, flags, kv_head, first_row}
+  // pg_rec: per page entry {page id, path position << 7 | valid tokens};
+  // qt_rec: per qt_list entry {query token, its limit}.
+  static constexpr int kItemInts = 8;
+  std::vector<int32_t> prefix_items, suffix_items, pg_rec, qt_rec;
   int32_t prefix_row_tiles = 1, suffix_row_tiles = 1;  // 16-row MFMA tiles per wavefront
   int32_t max_rows_prefix = 0, max_rows_suffix = 0;
   int64_t prefix_tokens = 0, suffix_tokens = 0;        // distinct KV tokens per kind
