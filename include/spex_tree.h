@@ -193,12 +193,15 @@ spex_status_t spex_tree_stats(const spex_tree_t *tree, int64_t *live_nodes, int6
  *   chunks in request order): pages pg_id/pg_valid/pg_pos[task_pg_begin .. + task_pg_count)
  *   (page id, valid tokens, path position of the page's first token), rows
  *   qt_list[task_qt_begin .. + task_qt_count) (query-token indices), first partial slot
- *   task_pbase, task_flags bit 0 = some page partial or some row's limit inside the chunk.
+ *   task_pbase, task_flags bit 0 = some page partial or some row's limit inside the chunk,
+ *   bit 1 = suffix task that is the only chunk of its suffix (the suffix kernel then folds the
+ *   rows' other pieces in and writes the output rows itself).
  *   Merge lists: query token t combines entries part_indptr[t] .. part_indptr[t+1]; the slot of
  *   (kv head g, head-in-group hh) in entry e is part_base[e] + g * part_hstride[e] + hh.
+ *   merge_qt[n_merge_qt]: the query tokens that still need the separate merge kernel.
  */
 typedef struct {
-  int32_t n_leaves, n_qtok, n_groups, n_tasks, n_prefix_tasks, n_pg, n_qt_list, n_parts;
+  int32_t n_leaves, n_qtok, n_groups, n_tasks, n_prefix_tasks, n_pg, n_qt_list, n_parts, n_merge_qt;
   int64_t n_partial_rows;
   int32_t prefix_chunk_pages, suffix_chunk_pages; /* the values actually used */
   const int32_t *leaf_indptr, *leaf_pages, *leaf_valid;
@@ -209,6 +212,7 @@ typedef struct {
   const int32_t *pg_id, *pg_valid, *pg_pos;
   const int32_t *qt_list;
   const int32_t *part_indptr, *part_base, *part_hstride;
+  const int32_t *merge_qt;
 } spex_plan_view_t;
 spex_status_t spex_tree_plan_dump(spex_tree_t *tree, const spex_node_t *leaves,
                                   const int32_t *q_lens, int32_t n_leaves, spex_plan_view_t *out);

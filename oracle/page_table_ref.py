@@ -41,6 +41,11 @@ Plan for requested nodes leaves[0..L) with q_lens (caller order):
     pbase + g * rows + r * G + hh;
   * a task is flagged MASKED (flag bit 0) if one of its pages is partial or if
     some row's limit is smaller than the path position that follows its last token;
+    a suffix task that is the only chunk of its suffix is flagged FINAL (flag bit 1):
+    it is the last piece of its rows, so the kernel that computes it can combine it
+    with the rows' other pieces and write the output itself;
+  * merge_qt lists, ascending, the query tokens that still need the separate merge
+    step: those of requested nodes whose suffix is empty or cut into several chunks;
   * the merge list of a query token holds, in task order, for every task that
     has it as a row: base = pbase + r * G and hstride = rows.
 """
@@ -227,11 +232,13 @@ class PageTableRef:
         parts: List[List[tuple]] = [[] for _ in range(NQ)]
         pbase = 0
 
-        def emit(ids, valid, pos, chunk_pages, qt_begin, qt_count):
+        def emit(ids, valid, pos, chunk_pages, qt_begin, qt_count, suffix=False):
             nonlocal pbase
             rows = qt_count * G
             min_limit = min(qt_limit[qt_list[qt_begin + r]] for r in range(qt_count))
-            for a, b in cut(len(ids), chunk_pages):
+            pieces = cut(len(ids), chunk_pages)
+            final = suffix and len(pieces) == 1
+            for a, b in pieces:
                 end_pos = pos[b - 1] + valid[b - 1]
                 masked = any(v != P for v in valid[a:b]) or min_limit < end_pos
                 tasks["pg_begin"].append(len(pg_id))
@@ -239,18 +246,20 @@ class PageTableRef:
                 tasks["qt_begin"].append(qt_begin)
                 tasks["qt_count"].append(qt_count)
                 tasks["pbase"].append(pbase)
-                tasks["flags"].append(1 if masked else 0)
+                tasks["flags"].append((1 if masked else 0) | (2 if final else 0))
                 pg_id.extend(ids[a:b])
                 pg_valid.extend(valid[a:b])
                 pg_pos.extend(pos[a:b])
                 for r in range(qt_count):
                     parts[qt_list[qt_begin + r]].append((pbase + r * G, rows))
                 pbase += rows * num_kv_heads
+            return final
 
         for gi, w in enumerate(group_nodes):
             ids, valid, pos = segment_entries([w])
             emit(ids, valid, pos, prefix_chunk_pages, group_qt_begin[gi], len(group_rows[gi]))
         n_prefix_tasks = len(tasks["pbase"])
+        merge_qt: List[int] = []
         for li, (path, ql) in enumerate(zip(paths, q_lens)):
             tail = []
             for w in reversed(path):
@@ -259,7 +268,11 @@ class PageTableRef:
                 tail.append(w)
             ids, valid, pos = segment_entries(tail[::-1])
             if ids:
-                emit(ids, valid, pos, suffix_chunk_pages, n_group_qt + qoff[li], ql)
+                final = emit(ids, valid, pos, suffix_chunk_pages, n_group_qt + qoff[li], ql, True)
+            else:
+                final = False
+            if not final:
+                merge_qt += list(range(qoff[li], qoff[li] + ql))
 
         part_indptr, part_base, part_hstride = [0], [], []
         for lst in parts:
@@ -277,4 +290,5 @@ class PageTableRef:
             task_pbase=tasks["pbase"], task_flags=tasks["flags"],
             pg_id=pg_id, pg_valid=pg_valid, pg_pos=pg_pos, qt_list=qt_list,
             part_indptr=part_indptr, part_base=part_base, part_hstride=part_hstride,
+            merge_qt=merge_qt,
         )

@@ -56,14 +56,15 @@ _I32P = C.POINTER(C.c_int32)
 
 class PlanView(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_leaves", "n_qtok", "n_groups", "n_tasks",
-                                         "n_prefix_tasks", "n_pg", "n_qt_list", "n_parts")] + \
+                                         "n_prefix_tasks", "n_pg", "n_qt_list", "n_parts",
+                                         "n_merge_qt")] + \
                [("n_partial_rows", C.c_int64), ("prefix_chunk_pages", C.c_int32),
                 ("suffix_chunk_pages", C.c_int32)] + \
                [(n, _I32P) for n in ("leaf_indptr", "leaf_pages", "leaf_valid", "qt_limit",
                                      "group_node", "task_pg_begin", "task_pg_count",
                                      "task_qt_begin", "task_qt_count", "task_pbase", "task_flags",
                                      "pg_id", "pg_valid", "pg_pos", "qt_list", "part_indptr",
-                                     "part_base", "part_hstride")]
+                                     "part_base", "part_hstride", "merge_qt")]
 
 
 EXPORTS = [
@@ -303,7 +304,7 @@ class SpexTree:
             pg_id=arr("pg_id", v.n_pg), pg_valid=arr("pg_valid", v.n_pg), pg_pos=arr("pg_pos", v.n_pg),
             qt_list=arr("qt_list", v.n_qt_list),
             part_indptr=arr("part_indptr", v.n_qtok + 1), part_base=arr("part_base", v.n_parts),
-            part_hstride=arr("part_hstride", v.n_parts),
+            part_hstride=arr("part_hstride", v.n_parts), merge_qt=arr("merge_qt", v.n_merge_qt),
             prefix_chunk_pages=v.prefix_chunk_pages, suffix_chunk_pages=v.suffix_chunk_pages,
         )
 

@@ -37,6 +37,7 @@ bool is_pow2(int32_t x) { return x > 0 && (x & (x - 1)) == 0; }
 struct DevicePlan {
   const int32_t *prefix_items = nullptr, *suffix_items = nullptr, *pg_rec = nullptr, *qt_rec = nullptr;
   const int32_t *part_indptr = nullptr, *part_base = nullptr, *part_hstride = nullptr;
+  const int32_t *merge_qt = nullptr;
 };
 
 }  // namespace
@@ -150,7 +151,7 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   const spex::Plan &pl = t->plan;
   const std::vector<int32_t> *arrays[] = {
       &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
-      &pl.part_indptr, &pl.part_base,    &pl.part_hstride};
+      &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt};
   constexpr int kN = sizeof(arrays) / sizeof(arrays[0]);
   size_t off[kN], total = 0;
   for (int i = 0; i < kN; ++i) {
@@ -195,6 +196,7 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   dp.part_indptr = at(4);
   dp.part_base = at(5);
   dp.part_hstride = at(6);
+  dp.merge_qt = at(7);
   t->plan_on_device = true;
   return SPEX_OK;
 }
@@ -400,6 +402,11 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   a.qt_rec = dp.qt_rec;
   a.part_o = t->d_part_o;
   a.part_ml = t->d_part_ml;
+  a.part_indptr = dp.part_indptr;
+  a.part_base = dp.part_base;
+  a.part_hstride = dp.part_hstride;
+  a.out = out;
+  a.lse = lse;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   const bool generic = t->kernel_mode == 1;
 
@@ -442,7 +449,12 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   m.part_ml = t->d_part_ml;
   m.out = out;
   m.lse = lse;
-  m.n_qtok = static_cast<int32_t>(pl.qt_limit.size());
+  // The MFMA suffix kernel finishes the rows of single-chunk suffixes itself; the generic kernels
+  // leave every row to the merge kernel.
+  const bool fused = !generic && spex::has_mfma_kernel(t->shape);
+  m.qt_ids = fused ? dp.merge_qt : nullptr;
+  m.n_qtok = fused ? static_cast<int32_t>(pl.merge_qt.size())
+                   : static_cast<int32_t>(pl.qt_limit.size());
   HIP_TRY(bracket(2, true));
   HIP_TRY(spex::launch_merge(t->shape, m, stream));
   HIP_TRY(bracket(2, false));
@@ -548,6 +560,8 @@ spex_status_t spex_tree_plan_dump(spex_tree_t *t, const spex_node_t *leaves, con
   v.part_indptr = pl.part_indptr.data();
   v.part_base = pl.part_base.data();
   v.part_hstride = pl.part_hstride.data();
+  v.n_merge_qt = static_cast<int32_t>(pl.merge_qt.size());
+  v.merge_qt = pl.merge_qt.data();
   *out = v;
   return SPEX_OK;
 }

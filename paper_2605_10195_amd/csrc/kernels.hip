@@ -209,15 +209,17 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
 
   // Query operand: lane (row n = lane%16, k-group j = lane/16) holds dims s*32 + 8j .. +7.
   bf16x8 qf[NT][D / 32];
-  int limit[NT];
+  int limit[NT], qtok[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     const int r = cur.row0 + nt * 16 + m16;
     limit[nt] = INT_MAX;
+    qtok[nt] = 0;
     if (r < rows) {
       const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (cur.qt_begin + r / G));
       const int hh = r % G;
       limit[nt] = qr.y;
+      qtok[nt] = qr.x;
       const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
                            (static_cast<int64_t>(qr.x) * sh.Hq + g * G + hh) * D + jj * 8;
 #pragma unroll
@@ -352,21 +354,61 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
 
   // Partial state: lanes of one row agree on m; l is summed over the four k-groups.
   // The accumulators hold 4 consecutive dims of one row per lane (64 B runs at a 512 B stride);
-  // stored like that they reach HBM as half-filled cache lines, which costs far more than their
-  // 3 % share of the traffic.  They are transposed through a wave-private LDS tile so that every
-  // store instruction writes two whole rows (1 KiB contiguous).
+  // they are transposed through a wave-private LDS tile so that every store instruction writes
+  // whole rows (1 KiB contiguous) instead of half-filled cache lines.
   constexpr int kRowPad = D + 4;  // floats per staged row; the pad spreads rows over LDS banks
   __shared__ float stage[4][16 * kRowPad];
   float *my = stage[threadIdx.x >> 6];
+  const bool final_task = (cur.flags & 2) != 0;
+  constexpr int kLanesPerRow = D / 4;  // 16-byte pieces per row
+  constexpr int kRowsPerInst = 64 / kLanesPerRow;
+  const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     float l = l_run[nt];
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
+    float m = m_run[nt];
     const int r0w = cur.row0 + nt * 16;  // first row of this tile
-    const int64_t slot0 = static_cast<int64_t>(cur.pbase) + static_cast<int64_t>(g) * rows + r0w;
-    if (r0w + m16 < rows && jj == 0)
-      *reinterpret_cast<f32x2 *>(p.part_ml + (slot0 + m16) * 2) = f32x2{m_run[nt], l};
+    const bool row_ok = r0w + m16 < rows;
+    const int hh = (r0w + m16) % G;
+    int64_t dst_row;  // row index in part_o, or in out for a final task
+    if (final_task) {
+      // Fold in the other pieces of this row (written by the shared-prefix kernel, which ran
+      // before on the same stream) and normalise.  All rows of a suffix belong to one requested
+      // node, so they have the same number of pieces.
+      int e0 = 0, n_other = 0;
+      if (row_ok) {
+        e0 = p.part_indptr[qtok[nt]];
+        n_other = p.part_indptr[qtok[nt] + 1] - 1 - e0;
+      }
+      const int n_max = uniform(__builtin_amdgcn_readfirstlane(n_other));
+      for (int j = 0; j < n_max; ++j) {
+        if (j < n_other) {
+          const int64_t slot = static_cast<int64_t>(p.part_base[e0 + j]) +
+                               static_cast<int64_t>(g) * p.part_hstride[e0 + j] + hh;
+          const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.part_ml + slot * 2);
+          const float m_new = fmaxf(m, ml[0]);
+          const float m_safe = m_new == kNegInf ? 0.f : m_new;
+          const float fa = fast_exp2(m - m_safe), fb = fast_exp2(ml[0] - m_safe);
+          l = l * fa + ml[1] * fb;
+          m = m_new;
+          const float *src = p.part_o + slot * D + jj * 4;
+#pragma unroll
+          for (int dt = 0; dt < D / 16; ++dt)
+            o_acc[nt][dt] = o_acc[nt][dt] * fa + *reinterpret_cast<const f32x4 *>(src + dt * 16) * fb;
+        }
+      }
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] *= inv;
+      dst_row = static_cast<int64_t>(qtok[nt]) * sh.Hq + g * G + hh;
+      if (row_ok && jj == 0 && p.lse) p.lse[dst_row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+    } else {
+      dst_row = static_cast<int64_t>(cur.pbase) + static_cast<int64_t>(g) * rows + r0w + m16;
+      if (row_ok && jj == 0) *reinterpret_cast<f32x2 *>(p.part_ml + dst_row * 2) = f32x2{m, l};
+    }
+    float *dst = final_task ? p.out : p.part_o;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -374,15 +416,15 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
       *reinterpret_cast<f32x4 *>(my + m16 * kRowPad + dt * 16 + jj * 4) = o_acc[nt][dt];
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    constexpr int kLanesPerRow = D / 4;            // 16-byte pieces per row
-    constexpr int kRowsPerInst = 64 / kLanesPerRow;
-    const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
 #pragma unroll
     for (int i = 0; i < 16 / kRowsPerInst; ++i) {
       const int row = i * kRowsPerInst + sub;
       const f32x4 v = *reinterpret_cast<const f32x4 *>(my + row * kRowPad + piece * 4);
-      if (r0w + row < rows)
-        *reinterpret_cast<f32x4 *>(p.part_o + (slot0 + row) * D + piece * 4) = v;
+      // destination row index of tile row `row`, held by lane `row` (k-group 0)
+      const int lo = __shfl(static_cast<int>(dst_row & 0xffffffff), row);
+      const int hi = __shfl(static_cast<int>(dst_row >> 32), row);
+      const int64_t drow = (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+      if (r0w + row < rows) *reinterpret_cast<f32x4 *>(dst + drow * D + piece * 4) = v;
     }
   }
 }
@@ -504,7 +546,7 @@ __global__ __launch_bounds__(256) void spex_lse_merge_kernel(MergeArgs a, Shape 
   const int64_t row = tid / dv;
   const int c = static_cast<int>(tid % dv);
   if (row >= static_cast<int64_t>(a.n_qtok) * sh.Hq) return;
-  const int qt = static_cast<int>(row / sh.Hq);
+  const int qt = a.qt_ids ? a.qt_ids[row / sh.Hq] : static_cast<int>(row / sh.Hq);
   const int h = static_cast<int>(row % sh.Hq);
   const int g = h / sh.G, hh = h % sh.G;
   const int e0 = a.part_indptr[qt], e1 = a.part_indptr[qt + 1];
@@ -535,14 +577,15 @@ __global__ __launch_bounds__(256) void spex_lse_merge_kernel(MergeArgs a, Shape 
     }
   }
   const float inv = 1.0f / l;
-  float *out = a.out + row * sh.D + c * VEC;
+  const int64_t orow = static_cast<int64_t>(qt) * sh.Hq + h;
+  float *out = a.out + orow * sh.D + c * VEC;
   if (VEC == 4) {
     *reinterpret_cast<f32x4 *>(out) = f32x4{acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
   } else {
 #pragma unroll
     for (int i = 0; i < VEC; ++i) out[i] = acc[i] * inv;
   }
-  if (a.lse && c == 0) a.lse[row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+  if (a.lse && c == 0) a.lse[orow] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
 }
 
 // ---- append scatter / gather -----------------------------------------------------------------

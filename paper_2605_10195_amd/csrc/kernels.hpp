@@ -30,6 +30,10 @@ struct AttnArgs {
   const int32_t *qt_rec;  // 2 ints per row-set entry: {query token, visible path length}
   float *part_o;   // [partial rows][D] unnormalised sum of exp2(x - m) * V
   float *part_ml;  // [partial rows][2] = {m, l}: running maximum of x = score * log2(e), sum of exp2
+  // Rows of tasks flagged final are finished in place: the other pieces of a row are read through
+  // its merge list (all entries but the last, which is the task itself) and out / lse are written.
+  const int32_t *part_indptr, *part_base, *part_hstride;
+  float *out, *lse;  // lse may be null
   float scale_log2;
 };
 
@@ -37,7 +41,8 @@ struct MergeArgs {
   const int32_t *part_indptr, *part_base, *part_hstride;
   const float *part_o, *part_ml;
   float *out, *lse;
-  int32_t n_qtok;
+  const int32_t *qt_ids;  // query tokens to merge, or null for 0 .. n_qtok-1
+  int32_t n_qtok;         // number of query tokens handled by the launch
 };
 
 constexpr int kMaxPagesPerScatter = 64;

@@ -171,13 +171,14 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
   std::vector<std::vector<std::pair<int32_t, int32_t>>> parts(NQ);
   int64_t pbase = 0;
   bool overflow = false;
-  auto emit = [&](const Segment &s, int32_t chunk_pages, int64_t *tokens) {
+  auto emit = [&](const Segment &s, int32_t chunk_pages, int64_t *tokens, bool suffix) -> bool {
     const int32_t n = static_cast<int32_t>(s.ids.size());
     const int32_t rows = s.qt_count * G;
     int32_t min_limit = std::numeric_limits<int32_t>::max();
     for (int32_t r = 0; r < s.qt_count; ++r)
       min_limit = std::min(min_limit, pl.qt_limit[pl.qt_list[s.qt_begin + r]]);
     const int32_t c = (n + chunk_pages - 1) / chunk_pages;
+    const bool final = suffix && c == 1;
     for (int32_t j = 0; j < c; ++j) {
       const int32_t a = static_cast<int32_t>(static_cast<int64_t>(j) * n / c);
       const int32_t b = static_cast<int32_t>(static_cast<int64_t>(j + 1) * n / c);
@@ -193,7 +194,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
       pl.task_qt_begin.push_back(s.qt_begin);
       pl.task_qt_count.push_back(s.qt_count);
       pl.task_pbase.push_back(static_cast<int32_t>(pbase));
-      pl.task_flags.push_back(masked ? 1 : 0);
+      pl.task_flags.push_back((masked ? 1 : 0) | (final ? 2 : 0));
       pl.pg_id.insert(pl.pg_id.end(), s.ids.begin() + a, s.ids.begin() + b);
       pl.pg_valid.insert(pl.pg_valid.end(), s.valid.begin() + a, s.valid.begin() + b);
       pl.pg_pos.insert(pl.pg_pos.end(), s.pos.begin() + a, s.pos.begin() + b);
@@ -201,10 +202,18 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
         parts[pl.qt_list[s.qt_begin + r]].emplace_back(static_cast<int32_t>(pbase) + r * G, rows);
       pbase += static_cast<int64_t>(rows) * num_kv_heads;
     }
+    return final;
   };
-  for (const Segment &s : groups) emit(s, pl.prefix_chunk_pages, &pl.prefix_tokens);
+  for (const Segment &s : groups) emit(s, pl.prefix_chunk_pages, &pl.prefix_tokens, false);
   pl.n_prefix_tasks = static_cast<int32_t>(pl.task_pbase.size());
-  for (const Segment &s : suffixes) emit(s, pl.suffix_chunk_pages, &pl.suffix_tokens);
+  {
+    std::vector<char> is_final(NQ, 0);
+    for (const Segment &s : suffixes)
+      if (emit(s, pl.suffix_chunk_pages, &pl.suffix_tokens, true))
+        for (int32_t r = 0; r < s.qt_count; ++r) is_final[pl.qt_list[s.qt_begin + r]] = 1;
+    for (int32_t t = 0; t < NQ; ++t)
+      if (!is_final[t]) pl.merge_qt.push_back(t);
+  }
   pl.n_partial_rows = pbase;
   reset();
   if (overflow) return PlanError::kTooLarge;

@@ -15,7 +15,11 @@
 //    chunk order); a task owns rows*Hkv partial slots from pbase (running sum), slot of
 //    (kv head g, local query token r, head-in-group hh) = pbase + g*rows + r*G + hh;
 //  * flag bit 0 (masked): a page of the task is partial, or a row's limit is smaller than the
-//    path position following the task's last token.
+//    path position following the task's last token;
+//  * flag bit 1 (final): suffix task that is the only chunk of its suffix; the suffix kernel
+//    folds the other pieces of its rows into it and writes the output rows itself;
+//  * merge_qt: ascending query tokens that still go through the merge kernel (requested nodes
+//    whose suffix is empty or has several chunks).
 #pragma once
 
 #include <cstdint>
@@ -37,7 +41,7 @@ struct Plan {
   std::vector<int32_t> task_pg_begin, task_pg_count, task_qt_begin, task_qt_count, task_pbase,
       task_flags;
   std::vector<int32_t> pg_id, pg_valid, pg_pos, qt_list;
-  std::vector<int32_t> part_indptr, part_base, part_hstride;
+  std::vector<int32_t> part_indptr, part_base, part_hstride, merge_qt;
   int32_t n_prefix_tasks = 0;
   int64_t n_partial_rows = 0;
   int32_t prefix_chunk_pages = 0, suffix_chunk_pages = 0;  // values used

@@ -72,7 +72,7 @@ def test_page_lists_and_free_list_bit_exact(seed):
 PLAN_KEYS = ["leaf_indptr", "leaf_pages", "leaf_valid", "qt_limit", "group_node", "n_prefix_tasks",
              "n_partial_rows", "task_pg_begin", "task_pg_count", "task_qt_begin", "task_qt_count",
              "task_pbase", "task_flags", "pg_id", "pg_valid", "pg_pos", "qt_list", "part_indptr",
-             "part_base", "part_hstride"]
+             "part_base", "part_hstride", "merge_qt"]
 
 
 def assert_same_plan(tree, ref, wl, pc, sc):

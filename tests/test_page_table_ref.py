@@ -127,7 +127,7 @@ def test_plan_properties(seed, pc, sc):
         end_pos = pl["pg_pos"][a + n - 1] + pl["pg_valid"][a + n - 1]
         masked = any(v != 16 for v in pl["pg_valid"][a:a + n]) or \
             min(pl["qt_limit"][r] for r in rows) < end_pos
-        assert pl["task_flags"][t] == int(masked)
+        assert pl["task_flags"][t] & 1 == int(masked)
         for r in rows:
             per_qt[r].append(t)
     assert pb == pl["n_partial_rows"]
@@ -158,6 +158,23 @@ def test_plan_properties(seed, pc, sc):
                         slots.add(s)
             qt += 1
     assert len(slots) == pl["n_partial_rows"]
+    # final flag: exactly the suffix tasks that are their suffix's only chunk; merge_qt = the rest
+    finals = set()
+    for t in range(n_tasks):
+        qa, qn = pl["task_qt_begin"][t], pl["task_qt_count"][t]
+        rows = tuple(pl["qt_list"][qa:qa + qn])
+        if t < pl["n_prefix_tasks"]:
+            assert pl["task_flags"][t] & 2 == 0
+            continue
+        same = [u for u in range(pl["n_prefix_tasks"], n_tasks)
+                if tuple(pl["qt_list"][pl["task_qt_begin"][u]:pl["task_qt_begin"][u] + pl["task_qt_count"][u]]) == rows]
+        assert bool(pl["task_flags"][t] & 2) == (len(same) == 1)
+        if len(same) == 1:
+            finals.update(rows)
+            # a final task is the last entry of each of its rows' merge lists
+            for r in rows:
+                assert per_qt[r][-1] == t
+    assert pl["merge_qt"] == [q for q in range(NQ) if q not in finals]
     # groups: ascending ids, live >= 2, and their rows are the requests underneath
     assert pl["group_node"] == sorted(pl["group_node"])
     for w in pl["group_node"]:
@@ -182,7 +199,7 @@ def test_sharing_counts_for_config_shapes():
     # depth-3 leaves are private: suffix = leaf step + the 6 drafts (one full + one partial page)
     suffix = range(pl5["n_prefix_tasks"], len(pl5["task_pbase"]))
     assert all(pl5["task_pg_count"][t] == 2 and pl5["task_qt_count"][t] == 6 for t in suffix)
-    assert all(pl5["task_flags"][t] == 1 for t in suffix)
+    assert all(pl5["task_flags"][t] == 3 for t in suffix)        # masked and final
     assert all(pl5["task_flags"][t] == 0 for t in range(pl5["n_prefix_tasks"]))
 
 
