@@ -153,6 +153,7 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *   q   : DEVICE [sum(q_lens)][num_q_heads][head_dim] in q_dtype, requested-node major
  *   out : DEVICE fp32, same shape:  sum_t softmax_t(sm_scale * <q, K_t>) V_t  over visible t
  *   lse : DEVICE fp32 [sum(q_lens)][num_q_heads] or NULL:  ln sum_t exp(sm_scale * <q, K_t>)
+ *   sm_scale must be positive and finite.
  * The call flattens parent links into per-launch work lists (shared-prefix groups are read
  * once for all nodes below them; private suffixes are split for parallelism), uploads them
  * when the request or the tree changed since the previous call, and enqueues the

@@ -38,6 +38,7 @@ struct DevicePlan {
   const int32_t *prefix_items = nullptr, *suffix_items = nullptr, *pg_rec = nullptr, *qt_rec = nullptr;
   const int32_t *part_indptr = nullptr, *part_base = nullptr, *part_hstride = nullptr;
   const int32_t *merge_qt = nullptr;
+  const int32_t *coop_items[3] = {nullptr, nullptr, nullptr};
 };
 
 }  // namespace
@@ -151,7 +152,8 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   const spex::Plan &pl = t->plan;
   const std::vector<int32_t> *arrays[] = {
       &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
-      &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt};
+      &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt,
+      &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2]};
   constexpr int kN = sizeof(arrays) / sizeof(arrays[0]);
   size_t off[kN], total = 0;
   for (int i = 0; i < kN; ++i) {
@@ -197,6 +199,7 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   dp.part_base = at(5);
   dp.part_hstride = at(6);
   dp.merge_qt = at(7);
+  for (int c = 0; c < 3; ++c) dp.coop_items[c] = at(8 + c);
   t->plan_on_device = true;
   return SPEX_OK;
 }
@@ -377,7 +380,7 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
                                          float *out, float *lse, float sm_scale, void *hip_stream) {
   if (!t || n_leaves < 0 || (n_leaves > 0 && (!leaves || !q || !out))) return SPEX_ERR_INVALID_ARG;
   if (!t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
-  if (!(sm_scale == sm_scale) || std::isinf(sm_scale)) return SPEX_ERR_INVALID_ARG;
+  if (!(sm_scale > 0.f) || std::isinf(sm_scale)) return SPEX_ERR_INVALID_ARG;
   if (n_leaves == 0) return SPEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   bool rebuilt = false;
@@ -427,11 +430,25 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
 
   const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / spex::Plan::kItemInts);
   const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / spex::Plan::kItemInts);
-  if (n_prefix_items > 0) {
-    a.items = dp.prefix_items;
-    a.n_items = n_prefix_items;
+  int32_t n_coop_items = 0;
+  for (int c = 0; c < 3; ++c)
+    n_coop_items += static_cast<int32_t>(pl.coop_items[c].size() / spex::Plan::kItemInts);
+  if (n_prefix_items + n_coop_items > 0) {
     HIP_TRY(bracket(0, true));
-    HIP_TRY(spex::launch_attention(t->shape, a, true, pl.prefix_row_tiles, generic, stream));
+    if (n_prefix_items > 0) {
+      a.items = dp.prefix_items;
+      a.n_items = n_prefix_items;
+      HIP_TRY(spex::launch_attention(t->shape, a, true, pl.prefix_row_tiles, generic, stream));
+    }
+    for (int c = 0; c < 3; ++c) {
+      a.items = dp.coop_items[c];
+      a.n_items = static_cast<int32_t>(pl.coop_items[c].size() / spex::Plan::kItemInts);
+      if (a.n_items == 0) continue;
+      if (generic || !spex::has_mfma_kernel(t->shape))  // generic kernels take any row count
+        HIP_TRY(spex::launch_attention(t->shape, a, true, 4 << c, true, stream));
+      else
+        HIP_TRY(spex::launch_prefix_coop(t->shape, a, 1 << c, stream));
+    }
     HIP_TRY(bracket(0, false));
   }
   if (n_suffix_items > 0) {
@@ -462,7 +479,7 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
   t->info[1] = pl.prefix_tokens;
   t->info[2] = pl.suffix_tokens;
-  t->info[3] = n_prefix_items;
+  t->info[3] = n_prefix_items + n_coop_items;
   t->info[4] = n_suffix_items;
   t->info[5] = pl.n_partial_rows;
   t->info[6] = rebuilt ? 1 : 0;

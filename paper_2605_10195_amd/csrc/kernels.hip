@@ -22,6 +22,8 @@ namespace spex {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -104,17 +106,6 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint32_t w0, uint32_t w1) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// Raw 128-bit pieces of one 32-token block (two pages) of one kv head, as loaded.
-template <int KV, int D>
-struct RawBlock {
-  static constexpr int NK = (KV == kFP8) ? D / 64 : D / 32;  // loads per K half-tile
-  static constexpr int NV = (KV == kFP8) ? D / 32 : D / 16;
-  u32x4 k[2][NK];
-  u32x4 v[NV];
-  int valid_a, valid_b, pos_a, pos_b;
-  float ks, vs;  // this lane's page scales (fp8), else 1
-};
-
 // Wave-uniform description of one work item.
 struct Item {
   int pg_begin, pg_count, qt_begin, qt_count, pbase, flags, g, row0;
@@ -151,10 +142,219 @@ __device__ __forceinline__ BlockMeta load_block_meta(const int32_t *pg_rec, cons
   return bm;
 }
 
-// One wavefront per work item.  The K/V loads of block b+1 are in flight while block b is
-// computed.  The steady-state loop is free of conditional loads on purpose: the vector-memory
-// completion counter is in-order, and a load that is issued on one path only would force the
-// compiler to wait for everything outstanding at the join.
+// Per-wavefront state of NT tiles of 16 query rows.  Lane (n = lane % 16, jj = lane / 16) works
+// on row n of every tile; its accumulators hold dims dt*16 + 4*jj .. +3.
+template <int D, int NT>
+struct RowState {
+  bf16x8 qf[NT][D / 32];  // query operand: dims s*32 + 8*jj .. +7
+  int limit[NT], qtok[NT];
+  f32x4 o[NT][D / 16];
+  float m[NT], l[NT];     // l is this lane's share; summed over the four jj at the end
+};
+
+template <int D, int NT>
+__device__ __forceinline__ void load_rows(const AttnArgs &p, const Shape &sh, const Item &cur,
+                                          int row_base, RowState<D, NT> &st) {
+  const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
+  const int G = sh.G, rows = cur.qt_count * G;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int r = row_base + nt * 16 + m16;
+    st.limit[nt] = INT_MAX;
+    st.qtok[nt] = 0;
+    st.m[nt] = kNegInf;
+    st.l[nt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) st.o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (r < rows) {
+      const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (cur.qt_begin + r / G));
+      st.limit[nt] = qr.y;
+      st.qtok[nt] = qr.x;
+      const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
+                           (static_cast<int64_t>(qr.x) * sh.Hq + cur.g * G + r % G) * D + jj * 8;
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s)
+        st.qf[nt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + s * 32));
+    } else {
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s) st.qf[nt][s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    }
+  }
+}
+
+// One 32-token block (pages A and B of one kv head) against the wavefront's rows.
+// kf[t][s]: K half-tile t (tokens {0-3, 8-11} + 4t of each page), dims s*32..; rows 0-7 of the MFMA
+// tile come from page A, rows 8-15 from page B.  vf[dt]: V^T, dims dt*16.., tokens 8*(jj&1)..+7 of
+// page jj/2.  After the two score tiles this lane holds the scores of exactly those 8 tokens, i.e.
+// the operand layout of the PV product, so P never leaves the registers.
+template <int D, int NT>
+__device__ __forceinline__ void block_math(RowState<D, NT> &st, const bf16x8 (&kf)[2][D / 32],
+                                           const bf16x8 (&vf)[D / 16], bool masked, int valid_l,
+                                           int pos_l, float c, float vs) {
+  const int jj = (threadIdx.x & 63) >> 4;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], st.qf[nt][s], sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], st.qf[nt][s], sb, 0, 0, 0);
+    }
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[i] = sa[i] * c;
+      x[4 + i] = sb[i] * c;
+    }
+    if (masked) {
+      int vis = st.limit[nt] - pos_l;
+      vis = vis < valid_l ? vis : valid_l;
+      vis -= 8 * (jj & 1);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(st.m[nt], mx);
+    const float m_safe = m_new == kNegInf ? 0.f : m_new;
+    const float alpha = fast_exp2(st.m[nt] - m_safe);
+    float pr[8];
+    float lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      pr[i] = fast_exp2(x[i] - m_safe);
+      lsum += pr[i];
+    }
+    st.l[nt] = st.l[nt] * alpha + lsum;
+    st.m[nt] = m_new;
+    if (!__all(alpha == 1.0f)) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) st.o[nt][dt] *= alpha;
+    }
+    // P as two bf16 pieces (hi + lo) so that the product keeps ~16 bits of each weight.
+    u32x4 phi, plo;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float a0 = pr[2 * i] * vs, a1 = pr[2 * i + 1] * vs;
+      const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
+      const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
+      phi[i] = pack_hi16(h0, h1);
+      plo[i] = pack_hi16(a0 - h0, a1 - h1);
+    }
+    const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
+    const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, st.o[nt][dt], 0, 0, 0);
+      st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, st.o[nt][dt], 0, 0, 0);
+    }
+  }
+}
+
+// Floats of LDS one wavefront needs to transpose a 16-row tile.
+template <int D>
+constexpr int stage_floats() { return 16 * (D + 4); }
+
+// Emit the rows of a wavefront: partial state (m, l, o) for the merge step, or -- for a task
+// flagged final -- the finished output rows after folding in the rows' other pieces.  The
+// accumulators hold 4 consecutive dims of one row per lane (64 B runs at a 512 B stride); they are
+// transposed through the wave-private LDS tile `my` so that every store instruction writes whole
+// rows (1 KiB contiguous) instead of half-filled cache lines.
+template <int D, int NT>
+__device__ __forceinline__ void finish_rows(const AttnArgs &p, const Shape &sh, const Item &cur,
+                                            int row_base, f32x4 (&o)[NT][D / 16],
+                                            const float (&m_in)[NT], const float (&l_in)[NT],
+                                            const int (&qtok)[NT], float *my) {
+  constexpr int kRowPad = D + 4;  // the pad spreads rows over LDS banks
+  const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
+  const int G = sh.G, rows = cur.qt_count * G, g = cur.g;
+  const bool final_task = (cur.flags & 2) != 0;
+  constexpr int kLanesPerRow = D / 4;  // 16-byte pieces per row
+  constexpr int kRowsPerInst = 64 / kLanesPerRow;
+  const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float l = l_in[nt];
+    float m = m_in[nt];
+    const int r0w = row_base + nt * 16;  // first row of this tile
+    if (r0w >= rows) break;              // wave-uniform
+    const bool row_ok = r0w + m16 < rows;
+    const int hh = (r0w + m16) % G;
+    int64_t dst_row;  // row index in part_o, or in out for a final task
+    if (final_task) {
+      // Fold in the other pieces of this row (written by the shared-prefix kernels, which ran
+      // before on the same stream) and normalise.  All rows of a suffix belong to one requested
+      // node, so they have the same number of pieces.
+      int e0 = 0, n_other = 0;
+      if (row_ok) {
+        e0 = p.part_indptr[qtok[nt]];
+        n_other = p.part_indptr[qtok[nt] + 1] - 1 - e0;
+      }
+      const int n_max = uniform(n_other);
+      for (int j = 0; j < n_max; ++j) {
+        if (j < n_other) {
+          const int64_t slot = static_cast<int64_t>(p.part_base[e0 + j]) +
+                               static_cast<int64_t>(g) * p.part_hstride[e0 + j] + hh;
+          const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.part_ml + slot * 2);
+          const float m_new = fmaxf(m, ml[0]);
+          const float m_safe = m_new == kNegInf ? 0.f : m_new;
+          const float fa = fast_exp2(m - m_safe), fb = fast_exp2(ml[0] - m_safe);
+          l = l * fa + ml[1] * fb;
+          m = m_new;
+          const float *src = p.part_o + slot * D + jj * 4;
+#pragma unroll
+          for (int dt = 0; dt < D / 16; ++dt)
+            o[nt][dt] = o[nt][dt] * fa + *reinterpret_cast<const f32x4 *>(src + dt * 16) * fb;
+        }
+      }
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] *= inv;
+      dst_row = static_cast<int64_t>(qtok[nt]) * sh.Hq + g * G + hh;
+      if (row_ok && jj == 0 && p.lse) p.lse[dst_row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+    } else {
+      dst_row = static_cast<int64_t>(cur.pbase) + static_cast<int64_t>(g) * rows + r0w + m16;
+      if (row_ok && jj == 0) *reinterpret_cast<f32x2 *>(p.part_ml + dst_row * 2) = f32x2{m, l};
+    }
+    float *dst = final_task ? p.out : p.part_o;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+      *reinterpret_cast<f32x4 *>(my + m16 * kRowPad + dt * 16 + jj * 4) = o[nt][dt];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 16 / kRowsPerInst; ++i) {
+      const int row = i * kRowsPerInst + sub;
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(my + row * kRowPad + piece * 4);
+      // destination row index of tile row `row`, held by lane `row` (k-group 0)
+      const int lo = __shfl(static_cast<int>(dst_row & 0xffffffff), row);
+      const int hi = __shfl(static_cast<int>(dst_row >> 32), row);
+      const int64_t drow = (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
+      if (r0w + row < rows) *reinterpret_cast<f32x4 *>(dst + drow * D + piece * 4) = v;
+    }
+  }
+}
+
+// Raw 128-bit pieces of one 32-token block (two pages) of one kv head, as loaded.
+template <int KV, int D>
+struct RawBlock {
+  static constexpr int NK = (KV == kFP8) ? D / 64 : D / 32;  // loads per K half-tile
+  static constexpr int NV = (KV == kFP8) ? D / 32 : D / 16;
+  u32x4 k[2][NK];
+  u32x4 v[NV];
+  int valid_a, valid_b, pos_a, pos_b;
+  float ks, vs;  // this lane's page scales (fp8), else 1
+};
+
+// ---- wavefront kernel: one wavefront per work item ---------------------------------------------
+// The K/V loads of block b+1 are in flight while block b is computed.  The steady-state loop is
+// free of conditional loads on purpose: the vector-memory completion counter is in-order, and a
+// load that is issued on one path only would force the compiler to wait for everything
+// outstanding at the join.
 template <int KV, int D, int NT>
 __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   constexpr int ESZ = (KV == kFP8) ? 1 : 2;
@@ -164,7 +364,6 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   const int jj = lane >> 4;
   const int item_idx = uniform(blockIdx.x * 4 + (threadIdx.x >> 6));
   if (item_idx >= p.n_items) return;
-  const int G = sh.G;
   const char *kpool = static_cast<const char *>(p.k_pool);
   const char *vpool = static_cast<const char *>(p.v_pool);
   // Byte offset of this lane inside a K half-tile / a V tile.
@@ -172,6 +371,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   const int v_lane_off = (jj & 1) * 256 + m16 * 16;
 
   const Item cur = load_item(p.items, item_idx);
+  if (cur.pg_count == 0) return;  // padding item
   const int g = cur.g;
   const int nblk = (cur.pg_count + 1) >> 1;
 
@@ -205,134 +405,40 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   auto meta = [&](int b) { return load_block_meta(p.pg_rec, cur, b < nblk ? b : nblk - 1); };
 
   const bool task_masked = (cur.flags & 1) != 0;
-  const int rows = cur.qt_count * G;
-
-  // Query operand: lane (row n = lane%16, k-group j = lane/16) holds dims s*32 + 8j .. +7.
-  bf16x8 qf[NT][D / 32];
-  int limit[NT], qtok[NT];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int r = cur.row0 + nt * 16 + m16;
-    limit[nt] = INT_MAX;
-    qtok[nt] = 0;
-    if (r < rows) {
-      const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (cur.qt_begin + r / G));
-      const int hh = r % G;
-      limit[nt] = qr.y;
-      qtok[nt] = qr.x;
-      const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
-                           (static_cast<int64_t>(qr.x) * sh.Hq + g * G + hh) * D + jj * 8;
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s)
-        qf[nt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + s * 32));
-    } else {
-#pragma unroll
-      for (int s = 0; s < D / 32; ++s) qf[nt][s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
-    }
-  }
+  RowState<D, NT> st;
+  load_rows<D, NT>(p, sh, cur, cur.row0, st);
 
   RawBlock<KV, D> r0, r1;
   issue_loads(r0, meta(0));
 
-  f32x4 o_acc[NT][D / 16];
-  float m_run[NT], l_run[NT];
+  auto compute_block = [&](const RawBlock<KV, D> &rb) {
+    bf16x8 kf[2][D / 32];
+    bf16x8 vf[D / 16];
+    if (KV == kFP8) {
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    m_run[nt] = kNegInf;
-    l_run[nt] = 0.f;
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-    auto compute_block = [&](const RawBlock<KV, D> &rb) {
-      bf16x8 kf[2][D / 32];
-      bf16x8 vf[D / 16];
-      if (KV == kFP8) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int s = 0; s < D / 64; ++s) {
-            kf[t][2 * s] = fp8x8_to_bf16x8(rb.k[t][s][0], rb.k[t][s][1]);
-            kf[t][2 * s + 1] = fp8x8_to_bf16x8(rb.k[t][s][2], rb.k[t][s][3]);
-          }
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s) {
-          vf[2 * s] = fp8x8_to_bf16x8(rb.v[s][0], rb.v[s][1]);
-          vf[2 * s + 1] = fp8x8_to_bf16x8(rb.v[s][2], rb.v[s][3]);
+        for (int s = 0; s < D / 64; ++s) {
+          kf[t][2 * s] = fp8x8_to_bf16x8(rb.k[t][s][0], rb.k[t][s][1]);
+          kf[t][2 * s + 1] = fp8x8_to_bf16x8(rb.k[t][s][2], rb.k[t][s][3]);
         }
-      } else {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int s = 0; s < D / 32; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, rb.k[t][s]);
-#pragma unroll
-        for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
+      for (int s = 0; s < D / 32; ++s) {
+        vf[2 * s] = fp8x8_to_bf16x8(rb.v[s][0], rb.v[s][1]);
+        vf[2 * s + 1] = fp8x8_to_bf16x8(rb.v[s][2], rb.v[s][3]);
       }
-      const bool masked = task_masked || rb.valid_b == 0;
-      // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
-      const int pg_valid_l = jj < 2 ? rb.valid_a : rb.valid_b;
-      const int pg_pos_l = jj < 2 ? rb.pos_a : rb.pos_b;
-      const float c = p.scale_log2 * rb.ks;
+    } else {
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int s = 0; s < D / 32; ++s) {
-          sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt][s], sa, 0, 0, 0);
-          sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt][s], sb, 0, 0, 0);
-        }
-        float x[8];
+        for (int s = 0; s < D / 32; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, rb.k[t][s]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          x[i] = sa[i] * c;
-          x[4 + i] = sb[i] * c;
-        }
-        if (masked) {
-          int vis = limit[nt] - pg_pos_l;
-          vis = vis < pg_valid_l ? vis : pg_valid_l;
-          vis -= 8 * (jj & 1);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
-        }
-        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                         fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[nt], mx);
-        const float m_safe = m_new == kNegInf ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run[nt] - m_safe);
-        float pr[8];
-        float lsum = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          pr[i] = fast_exp2(x[i] - m_safe);
-          lsum += pr[i];
-        }
-        l_run[nt] = l_run[nt] * alpha + lsum;
-        m_run[nt] = m_new;
-        if (!__all(alpha == 1.0f)) {
-#pragma unroll
-          for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] *= alpha;
-        }
-        // P as two bf16 pieces (hi + lo) so that the product keeps ~16 bits of each weight.
-        u32x4 phi, plo;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const float a0 = pr[2 * i] * rb.vs, a1 = pr[2 * i + 1] * rb.vs;
-          const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
-          const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
-          phi[i] = pack_hi16(h0, h1);
-          plo[i] = pack_hi16(a0 - h0, a1 - h1);
-        }
-        const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
-        const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-          o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, o_acc[nt][dt], 0, 0, 0);
-          o_acc[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, o_acc[nt][dt], 0, 0, 0);
-        }
-      }
-    };
+      for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
+    }
+    // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
+    block_math<D, NT>(st, kf, vf, task_masked || rb.valid_b == 0, jj < 2 ? rb.valid_a : rb.valid_b,
+                      jj < 2 ? rb.pos_a : rb.pos_b, p.scale_log2 * rb.ks, rb.vs);
+  };
 
   BlockMeta bm1 = meta(1);
   int b = 0;
@@ -352,81 +458,16 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
     compute_block(r0);
   }
 
-  // Partial state: lanes of one row agree on m; l is summed over the four k-groups.
-  // The accumulators hold 4 consecutive dims of one row per lane (64 B runs at a 512 B stride);
-  // they are transposed through a wave-private LDS tile so that every store instruction writes
-  // whole rows (1 KiB contiguous) instead of half-filled cache lines.
-  constexpr int kRowPad = D + 4;  // floats per staged row; the pad spreads rows over LDS banks
-  __shared__ float stage[4][16 * kRowPad];
-  float *my = stage[threadIdx.x >> 6];
-  const bool final_task = (cur.flags & 2) != 0;
-  constexpr int kLanesPerRow = D / 4;  // 16-byte pieces per row
-  constexpr int kRowsPerInst = 64 / kLanesPerRow;
-  const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
+  __shared__ float stage[4][stage_floats<D>()];
+  float l_tot[NT];
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    float l = l_run[nt];
+  for (int nt = 0; nt < NT; ++nt) {  // the row sum is spread over the four lane groups
+    float l = st.l[nt];
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
-    float m = m_run[nt];
-    const int r0w = cur.row0 + nt * 16;  // first row of this tile
-    const bool row_ok = r0w + m16 < rows;
-    const int hh = (r0w + m16) % G;
-    int64_t dst_row;  // row index in part_o, or in out for a final task
-    if (final_task) {
-      // Fold in the other pieces of this row (written by the shared-prefix kernel, which ran
-      // before on the same stream) and normalise.  All rows of a suffix belong to one requested
-      // node, so they have the same number of pieces.
-      int e0 = 0, n_other = 0;
-      if (row_ok) {
-        e0 = p.part_indptr[qtok[nt]];
-        n_other = p.part_indptr[qtok[nt] + 1] - 1 - e0;
-      }
-      const int n_max = uniform(__builtin_amdgcn_readfirstlane(n_other));
-      for (int j = 0; j < n_max; ++j) {
-        if (j < n_other) {
-          const int64_t slot = static_cast<int64_t>(p.part_base[e0 + j]) +
-                               static_cast<int64_t>(g) * p.part_hstride[e0 + j] + hh;
-          const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.part_ml + slot * 2);
-          const float m_new = fmaxf(m, ml[0]);
-          const float m_safe = m_new == kNegInf ? 0.f : m_new;
-          const float fa = fast_exp2(m - m_safe), fb = fast_exp2(ml[0] - m_safe);
-          l = l * fa + ml[1] * fb;
-          m = m_new;
-          const float *src = p.part_o + slot * D + jj * 4;
-#pragma unroll
-          for (int dt = 0; dt < D / 16; ++dt)
-            o_acc[nt][dt] = o_acc[nt][dt] * fa + *reinterpret_cast<const f32x4 *>(src + dt * 16) * fb;
-        }
-      }
-      const float inv = 1.0f / l;
-#pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) o_acc[nt][dt] *= inv;
-      dst_row = static_cast<int64_t>(qtok[nt]) * sh.Hq + g * G + hh;
-      if (row_ok && jj == 0 && p.lse) p.lse[dst_row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
-    } else {
-      dst_row = static_cast<int64_t>(cur.pbase) + static_cast<int64_t>(g) * rows + r0w + m16;
-      if (row_ok && jj == 0) *reinterpret_cast<f32x2 *>(p.part_ml + dst_row * 2) = f32x2{m, l};
-    }
-    float *dst = final_task ? p.out : p.part_o;
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt)
-      *reinterpret_cast<f32x4 *>(my + m16 * kRowPad + dt * 16 + jj * 4) = o_acc[nt][dt];
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int i = 0; i < 16 / kRowsPerInst; ++i) {
-      const int row = i * kRowsPerInst + sub;
-      const f32x4 v = *reinterpret_cast<const f32x4 *>(my + row * kRowPad + piece * 4);
-      // destination row index of tile row `row`, held by lane `row` (k-group 0)
-      const int lo = __shfl(static_cast<int>(dst_row & 0xffffffff), row);
-      const int hi = __shfl(static_cast<int>(dst_row >> 32), row);
-      const int64_t drow = (static_cast<int64_t>(hi) << 32) | static_cast<uint32_t>(lo);
-      if (r0w + row < rows) *reinterpret_cast<f32x4 *>(dst + drow * D + piece * 4) = v;
-    }
+    l_tot[nt] = l;
   }
+  finish_rows<D, NT>(p, sh, cur, cur.row0, st.o, st.m, l_tot, st.qtok, stage[threadIdx.x >> 6]);
 }
 
 template <int KV, int D, int NT>
@@ -437,6 +478,238 @@ __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_prefix_attn_kernel(
 template <int KV, int D, int NT>
 __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_suffix_attn_kernel(AttnArgs p, Shape sh) {
   attn_wave<KV, D, NT>(p, sh);
+}
+
+// Block step of the cooperative kernel.  Same contraction as block_math, tuned for many row
+// tiles per wavefront, where the vector ALU work of the softmax -- not the matrix cores -- sets
+// the pace:
+//  * P is rounded once to fp16 (11 significant bits; round to nearest) and V^T arrives as fp16
+//    operand images, so PV is one MFMA per tile instead of a hi and a lo one;
+//  * the row sums come from one more MFMA against a tile of ones, which also adds up the four
+//    lane groups and uses the same rounded weights as the numerator;
+//  * with a page-independent scale (bf16 KV) the running maximum is kept on the raw scores and
+//    scale and subtraction fuse into one FMA per score.
+// m is in units of raw score for bf16 KV and of scaled score for fp8 KV (c differs per page).
+template <bool FP8, int D, int NT>
+__device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], const int (&limit)[NT],
+                                               f32x4 (&o)[NT][D / 16], float (&m)[NT],
+                                               f32x4 (&lacc)[NT], const bf16x8 (&kf)[2][D / 32],
+                                               const f16x8 (&vh)[D / 16], bool masked, int valid_l,
+                                               int pos_l, float c) {
+  const int jj = (threadIdx.x & 63) >> 4;
+  const _Float16 one = static_cast<_Float16>(1.0f);
+  const f16x8 ones = {one, one, one, one, one, one, one, one};
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt][s], sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt][s], sb, 0, 0, 0);
+    }
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[i] = FP8 ? sa[i] * c : sa[i];
+      x[4 + i] = FP8 ? sb[i] * c : sb[i];
+    }
+    if (masked) {
+      int vis = limit[nt] - pos_l;
+      vis = vis < valid_l ? vis : valid_l;
+      vis -= 8 * (jj & 1);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m[nt], mx);
+    const float m_safe = m_new == kNegInf ? 0.f : m_new;
+    float alpha, pr[8];
+    if (FP8) {
+      alpha = fast_exp2(m[nt] - m_safe);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
+    } else {
+      const float mc = m_safe * c;
+      alpha = fast_exp2(m[nt] * c - mc);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, -mc));
+    }
+    m[nt] = m_new;
+    if (!__all(alpha == 1.0f)) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] *= alpha;
+      lacc[nt] *= alpha;
+    }
+    u32x4 pw;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pr[2 * i], pr[2 * i + 1]}, f16x2));
+    const f16x8 ph = __builtin_bit_cast(f16x8, pw);
+    lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, ph, lacc[nt], 0, 0, 0);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+      o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh[dt], ph, o[nt][dt], 0, 0, 0);
+  }
+}
+
+// Eight bf16 -> eight fp16 (exact for magnitudes in [2^-14, 65504]; smaller ones lose low bits).
+__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = __builtin_bit_cast(float, w[i] << 16);
+    const float hi = __builtin_bit_cast(float, w[i] & 0xffff0000u);
+    r[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
+  }
+  return r;
+}
+
+// Eight e4m3 codes times a page scale -> eight fp16.
+__device__ __forceinline__ u32x4 fp8x8_to_f16x8(uint32_t w0, uint32_t w1, float scale) {
+  const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w0), false) * scale;
+  const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w0), true) * scale;
+  const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w1), false) * scale;
+  const f32x2 d = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(w1), true) * scale;
+  u32x4 r;
+  r[0] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, f16x2));
+  r[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, f16x2));
+  r[2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(c, f16x2));
+  r[3] = __builtin_bit_cast(uint32_t, __builtin_convertvector(d, f16x2));
+  return r;
+}
+
+// ---- cooperative shared-prefix kernel: one workgroup (4 wavefronts) per work item --------------
+// For groups with many stacked rows.  The workgroup covers up to 64 * NTW rows of one (task, kv
+// head); wavefront w owns rows row0 + w*16*NTW .. .  Each 32-token block is fetched from global
+// memory once per workgroup -- every wavefront loads a quarter of it -- and is placed in LDS as
+// ready-made MFMA operand images (K as bf16, V^T as fp16, fp8 widened on the way and V multiplied
+// by its page scale) that all four wavefronts read (lane * 16 B, conflict free).  Two LDS buffers
+// and one barrier per block.
+template <int KV, int D, int NTW>
+__global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel(AttnArgs p, Shape sh) {
+  constexpr bool FP8 = KV == kFP8;
+  constexpr int ESZ = FP8 ? 1 : 2;
+  constexpr int TILE_BYTES = 16 * D * ESZ;
+  constexpr int NKI = 2 * (D / 32);        // K operand images per block
+  constexpr int NI = NKI + D / 16;         // all operand images per block (1 KiB each)
+  constexpr int RAW = FP8 ? NI / 2 : NI;   // 1 KiB global loads per block
+  constexpr int RK = FP8 ? NKI / 2 : NKI;  // of which K
+  constexpr int PER = RAW / 4;             // global loads per wavefront and block
+  static_assert(RAW % 4 == 0, "block must split evenly over four wavefronts");
+  constexpr int kImgFloats = NI * 64 * 4;  // one buffer, in 4-byte units
+  constexpr int kLdsFloats =
+      2 * kImgFloats > 4 * stage_floats<D>() ? 2 * kImgFloats : 4 * stage_floats<D>();
+  __shared__ __attribute__((aligned(16))) float lds[kLdsFloats];
+  u32x4 *img = reinterpret_cast<u32x4 *>(lds);  // [buf][image][lane]
+
+  const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
+  const int w = uniform(threadIdx.x >> 6);
+  const Item cur = load_item(p.items, blockIdx.x);
+  if (cur.pg_count == 0) return;  // padding item (whole workgroup)
+  const int g = cur.g;
+  const int nblk = (cur.pg_count + 1) >> 1;
+  const int rows = cur.qt_count * sh.G;
+  const int row_base = cur.row0 + w * 16 * NTW;
+  const bool has_rows = row_base < rows;
+  const bool task_masked = (cur.flags & 1) != 0;
+  const char *kpool = static_cast<const char *>(p.k_pool);
+  const char *vpool = static_cast<const char *>(p.v_pool);
+  const int k_lane_off = jj * 128 + (m16 & 7) * 16;
+  const int v_lane_off = (jj & 1) * 256 + m16 * 16;
+
+  RowState<D, NTW> st;
+  load_rows<D, NTW>(p, sh, cur, row_base, st);
+  f32x4 lacc[NTW];
+#pragma unroll
+  for (int nt = 0; nt < NTW; ++nt) lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Wavefront w fetches raw pieces w, w + 4, ... of the block (K pieces first, then V).
+  struct Raw {
+    u32x4 r[PER];
+    float vs;
+  };
+  auto stage_load = [&](Raw &rw, const BlockMeta &bm) {
+    const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
+    const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
+    const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
+    const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int idx = k * 4 + w;  // wave-uniform
+      const char *src = idx < RK ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
+                                 : vp + (idx - RK) * 512;
+      rw.r[k] = *reinterpret_cast<const u32x4 *>(src);
+    }
+    rw.vs = FP8 ? p.v_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g] : 1.f;
+  };
+  auto stage_store = [&](const Raw &rw, int buf) {
+    u32x4 *dst = img + buf * (NI * 64) + lane;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int idx = k * 4 + w;
+      if (FP8) {
+        if (idx < RK) {
+          dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][0], rw.r[k][1]));
+          dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][2], rw.r[k][3]));
+        } else {
+          dst[(2 * idx) * 64] = fp8x8_to_f16x8(rw.r[k][0], rw.r[k][1], rw.vs);
+          dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(rw.r[k][2], rw.r[k][3], rw.vs);
+        }
+      } else {
+        dst[idx * 64] = idx < RK ? rw.r[k] : bf16x8_to_f16x8(rw.r[k]);
+      }
+    }
+  };
+  auto compute = [&](int b, const BlockMeta &bm) {
+    if (!has_rows) return;
+    const u32x4 *src = img + (b & 1) * (NI * 64) + lane;
+    bf16x8 kf[2][D / 32];
+    f16x8 vh[D / 16];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s)
+        kf[t][s] = __builtin_bit_cast(bf16x8, src[(t * (D / 32) + s) * 64]);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
+    const int valid_a = bm.vp_a & 127, valid_b = bm.vp_b & 127;
+    float c = p.scale_log2;
+    if (FP8) c *= p.k_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g];
+    block_math_f16<FP8, D, NTW>(st.qf, st.limit, st.o, st.m, lacc, kf, vh,
+                                task_masked || valid_b == 0, jj < 2 ? valid_a : valid_b,
+                                jj < 2 ? (bm.vp_a >> 7) : (bm.vp_b >> 7), c);
+  };
+  auto meta = [&](int b) { return load_block_meta(p.pg_rec, cur, b < nblk ? b : nblk - 1); };
+
+  // LDS holds block b while it is computed; the pieces of block b+1 are requested before the
+  // computation and moved to the other LDS buffer after it.
+  Raw x;
+  BlockMeta bm = meta(0);
+  stage_load(x, bm);
+  stage_store(x, 0);
+  __syncthreads();
+  for (int b = 0; b < nblk; ++b) {
+    const bool more = b + 1 < nblk;  // uniform over the workgroup
+    const BlockMeta nbm = meta(b + 1);
+    if (more) stage_load(x, nbm);
+    compute(b, bm);
+    if (more) stage_store(x, (b + 1) & 1);
+    bm = nbm;
+    __syncthreads();
+  }
+  // The operand images are dead after the last barrier; the same LDS now serves the transposes.
+  if (has_rows) {
+    float m_out[NTW], l_out[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+      m_out[nt] = FP8 ? st.m[nt] : st.m[nt] * p.scale_log2;
+      l_out[nt] = lacc[nt][0];
+    }
+    finish_rows<D, NTW>(p, sh, cur, row_base, st.o, m_out, l_out, st.qtok, lds + w * stage_floats<D>());
+  }
 }
 
 // ---- generic attention (no matrix cores) ------------------------------------------------------
@@ -465,6 +738,7 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
   const int pbase = rec[4];
   const int g = rec[6];
   const int row0 = rec[7];
+  if (pg_count == 0) return;  // padding item
   const int D = sh.D, P = sh.P, G = sh.G;
   const int rows = qt_count * G;
   const int64_t tile_elems = static_cast<int64_t>(P) * D;
@@ -698,6 +972,28 @@ hipError_t launch_attention(const Shape &sh, const AttnArgs &a, bool prefix, int
   if (sh.kv_dtype == kBF16 && sh.q_dtype == kBF16) return launch_generic<kBF16, kBF16>(sh, a, rows_per_item, stream);
   if (sh.kv_dtype == kFP8 && sh.q_dtype == kBF16) return launch_generic<kFP8, kBF16>(sh, a, rows_per_item, stream);
   return hipErrorInvalidValue;
+}
+
+template <int KV, int D>
+static hipError_t launch_coop_ntw(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream) {
+  const dim3 grid(a.n_items), block(256);
+  if (ntw == 1)
+    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 1>), grid, block, 0, stream, a, sh);
+  else if (ntw == 2)
+    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 2>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 4>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream) {
+  if (a.n_items <= 0) return hipSuccess;
+  if (!has_mfma_kernel(sh) || (ntw != 1 && ntw != 2 && ntw != 4)) return hipErrorInvalidValue;
+  if (sh.kv_dtype == kBF16)
+    return sh.D == 64 ? launch_coop_ntw<kBF16, 64>(sh, a, ntw, stream)
+                      : launch_coop_ntw<kBF16, 128>(sh, a, ntw, stream);
+  return sh.D == 64 ? launch_coop_ntw<kFP8, 64>(sh, a, ntw, stream)
+                    : launch_coop_ntw<kFP8, 128>(sh, a, ntw, stream);
 }
 
 hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream) {

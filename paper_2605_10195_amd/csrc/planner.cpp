@@ -8,6 +8,9 @@ namespace spex {
 namespace {
 
 constexpr int64_t kTargetItems = 4096;  // ~2 work items per wavefront slot of the chip
+constexpr int32_t kWaveRowsMax = 32;    // largest group the wavefront kernel takes
+constexpr int kWideClass = 1;           // cooperative launch class of groups above 64 rows
+constexpr int32_t kWideSpan = 64 << kWideClass;  // rows per workgroup in that class
 
 int32_t clamp32(int64_t v, int32_t lo, int32_t hi) {
   return static_cast<int32_t>(std::max<int64_t>(lo, std::min<int64_t>(hi, v)));
@@ -129,11 +132,13 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
   };
   std::vector<Segment> groups(NG), suffixes;
   int64_t prefix_pages_weighted = 0;
+  int32_t max_rows_small = 0;
   for (int32_t gi = 0; gi < NG; ++gi) {
     add_node_pages(groups[gi], pl.group_node[gi]);
     groups[gi].qt_begin = group_qt_begin[gi];
     groups[gi].qt_count = group_count[gi];
     pl.max_rows_prefix = std::max(pl.max_rows_prefix, group_count[gi] * G);
+    if (group_count[gi] * G <= kWaveRowsMax) max_rows_small = std::max(max_rows_small, group_count[gi] * G);
   }
   suffixes.reserve(n_leaves);
   int64_t suffix_pages = 0;
@@ -150,18 +155,18 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     pl.max_rows_suffix = std::max(pl.max_rows_suffix, ql * G);
     suffixes.push_back(std::move(s));
   }
-  pl.prefix_row_tiles = pl.max_rows_prefix <= 16 ? 1 : 2;
+  pl.prefix_row_tiles = max_rows_small <= 16 ? 1 : 2;
   pl.suffix_row_tiles = pl.max_rows_suffix <= 16 ? 1 : 2;
-  const int32_t rw_prefix = 16 * pl.prefix_row_tiles, rw_suffix = 16 * pl.suffix_row_tiles;
-  for (const Segment &s : groups)
+  const int32_t rw_suffix = 16 * pl.suffix_row_tiles;
+  for (const Segment &s : groups)  // work items per page if nothing were split
     prefix_pages_weighted +=
-        static_cast<int64_t>(s.ids.size()) * ((s.qt_count * G + rw_prefix - 1) / rw_prefix);
+        static_cast<int64_t>(s.ids.size()) * (s.qt_count * G <= 64 ? 1 : (s.qt_count * G + kWideSpan - 1) / kWideSpan);
 
   // ---- split granularity
   pl.prefix_chunk_pages = prefix_chunk_pages > 0
                               ? prefix_chunk_pages
                               : clamp32((prefix_pages_weighted * num_kv_heads + kTargetItems - 1) /
-                                            kTargetItems, 8, 64);
+                                            kTargetItems, 8, 256);
   pl.suffix_chunk_pages = suffix_chunk_pages > 0
                               ? suffix_chunk_pages
                               : clamp32((suffix_pages * num_kv_heads + kTargetItems - 1) /
@@ -244,10 +249,39 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
                                           pl.task_pbase[t],    pl.task_flags[t], g, row0};
     items.insert(items.end(), rec, rec + Plan::kItemInts);
   };
-  for (int32_t t : order_of(0, pl.n_prefix_tasks)) {
-    const int32_t n_rt = (pl.task_qt_count[t] * G + rw_prefix - 1) / rw_prefix;
-    for (int32_t g = 0; g < num_kv_heads; ++g)
-      for (int32_t rt = 0; rt < n_rt; ++rt) push_item(pl.prefix_items, t, g, rt * rw_prefix);
+  // Shared-prefix items.  Groups of up to 32 rows go to the wavefront kernel (one item per task
+  // and kv head).  Larger groups go to the cooperative kernel, one workgroup per (task, kv head,
+  // span of 64 * NTW rows): NTW = 1 for up to 64 rows, else NTW = 2 (spans of 128 rows).
+  // The spans of one (task, kv head) read the same pages; workgroup b of a launch runs on XCD
+  // b % 8 and every XCD has its own L2, so units are laid out in batches of 8 with span s of unit
+  // u at position s * 8 + u of the batch: all spans of a unit land on one XCD, next to each other
+  // in dispatch order.  Holes are padding items (pg_count = 0).
+  {
+    constexpr int kXcds = 8;
+    const int32_t empty_rec[Plan::kItemInts] = {0, 0, 0, 0, 0, 0, 0, 0};
+    struct Unit { int32_t t, g, spans; };
+    std::vector<Unit> wide;
+    for (int32_t t : order_of(0, pl.n_prefix_tasks)) {
+      const int32_t rows = pl.task_qt_count[t] * G;
+      for (int32_t g = 0; g < num_kv_heads; ++g) {
+        if (rows <= kWaveRowsMax) push_item(pl.prefix_items, t, g, 0);
+        else if (rows <= 64) push_item(pl.coop_items[0], t, g, 0);
+        else wide.push_back({t, g, (rows + kWideSpan - 1) / kWideSpan});
+      }
+    }
+    for (size_t u0 = 0; u0 < wide.size(); u0 += kXcds) {
+      const size_t n = std::min<size_t>(kXcds, wide.size() - u0);
+      int32_t max_spans = 0;
+      for (size_t k = 0; k < n; ++k) max_spans = std::max(max_spans, wide[u0 + k].spans);
+      for (int32_t sidx = 0; sidx < max_spans; ++sidx)
+        for (size_t k = 0; k < kXcds; ++k) {
+          if (k < n && sidx < wide[u0 + k].spans)
+            push_item(pl.coop_items[kWideClass], wide[u0 + k].t, wide[u0 + k].g, sidx * kWideSpan);
+          else if (max_spans > 1)  // keep the XCD alignment inside the batch
+            pl.coop_items[kWideClass].insert(pl.coop_items[kWideClass].end(), empty_rec,
+                                             empty_rec + Plan::kItemInts);
+        }
+    }
   }
   for (int32_t t : order_of(pl.n_prefix_tasks, n_tasks)) {
     const int32_t n_rt = (pl.task_qt_count[t] * G + rw_suffix - 1) / rw_suffix;

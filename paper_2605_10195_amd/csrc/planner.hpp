@@ -52,6 +52,7 @@ struct Plan {
   // qt_rec: per qt_list entry {query token, its limit}.
   static constexpr int kItemInts = 8;
   std::vector<int32_t> prefix_items, suffix_items, pg_rec, qt_rec;
+  std::vector<int32_t> coop_items[3];  // cooperative shared-prefix kernel, 64 / 128 / 256 rows per workgroup
   int32_t prefix_row_tiles = 1, suffix_row_tiles = 1;  // 16-row MFMA tiles per wavefront
   int32_t max_rows_prefix = 0, max_rows_suffix = 0;
   int64_t prefix_tokens = 0, suffix_tokens = 0;        // distinct KV tokens per kind
