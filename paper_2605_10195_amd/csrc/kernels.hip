@@ -262,7 +262,7 @@ constexpr int stage_floats() { return 16 * (D + 4); }
 // accumulators hold 4 consecutive dims of one row per lane (64 B runs at a 512 B stride); they are
 // transposed through the wave-private LDS tile `my` so that every store instruction writes whole
 // rows (1 KiB contiguous) instead of half-filled cache lines.
-template <int D, int NT>
+template <int D, int NT, bool ALLOW_FINAL>
 __device__ __forceinline__ void finish_rows(const AttnArgs &p, const Shape &sh, const Item &cur,
                                             int row_base, f32x4 (&o)[NT][D / 16],
                                             const float (&m_in)[NT], const float (&l_in)[NT],
@@ -270,7 +270,7 @@ __device__ __forceinline__ void finish_rows(const AttnArgs &p, const Shape &sh, 
   constexpr int kRowPad = D + 4;  // the pad spreads rows over LDS banks
   const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
   const int G = sh.G, rows = cur.qt_count * G, g = cur.g;
-  const bool final_task = (cur.flags & 2) != 0;
+  const bool final_task = ALLOW_FINAL && (cur.flags & 2) != 0;
   constexpr int kLanesPerRow = D / 4;  // 16-byte pieces per row
   constexpr int kRowsPerInst = 64 / kLanesPerRow;
   const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
@@ -283,7 +283,7 @@ __device__ __forceinline__ void finish_rows(const AttnArgs &p, const Shape &sh, 
     const bool row_ok = r0w + m16 < rows;
     const int hh = (r0w + m16) % G;
     int64_t dst_row;  // row index in part_o, or in out for a final task
-    if (final_task) {
+    if (ALLOW_FINAL && final_task) {
       // Fold in the other pieces of this row (written by the shared-prefix kernels, which ran
       // before on the same stream) and normalise.  All rows of a suffix belong to one requested
       // node, so they have the same number of pieces.
@@ -293,20 +293,54 @@ __device__ __forceinline__ void finish_rows(const AttnArgs &p, const Shape &sh, 
         n_other = p.part_indptr[qtok[nt] + 1] - 1 - e0;
       }
       const int n_max = uniform(n_other);
-      for (int j = 0; j < n_max; ++j) {
-        if (j < n_other) {
-          const int64_t slot = static_cast<int64_t>(p.part_base[e0 + j]) +
-                               static_cast<int64_t>(g) * p.part_hstride[e0 + j] + hh;
-          const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.part_ml + slot * 2);
-          const float m_new = fmaxf(m, ml[0]);
-          const float m_safe = m_new == kNegInf ? 0.f : m_new;
-          const float fa = fast_exp2(m - m_safe), fb = fast_exp2(ml[0] - m_safe);
-          l = l * fa + ml[1] * fb;
-          m = m_new;
-          const float *src = p.part_o + slot * D + jj * 4;
+      auto fold = [&](const f32x2 ml, const f32x4 (&oj)[D / 16], bool use) {
+        const float mj = use ? ml[0] : kNegInf;
+        const float m_new = fmaxf(m, mj);
+        const float m_safe = m_new == kNegInf ? 0.f : m_new;
+        const float fa = fast_exp2(m - m_safe), fb = fast_exp2(mj - m_safe);
+        l = l * fa + ml[1] * fb;
+        m = m_new;
 #pragma unroll
-          for (int dt = 0; dt < D / 16; ++dt)
-            o[nt][dt] = o[nt][dt] * fa + *reinterpret_cast<const f32x4 *>(src + dt * 16) * fb;
+        for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] = o[nt][dt] * fa + oj[dt] * fb;
+      };
+      if (n_max > 0) {
+        // The first 8 pieces are fetched four at a time with all loads of a batch in flight
+        // together.  Indices past a row's last piece are clamped to it (a repeated, finite read
+        // that is weighted with zero), which keeps the batches free of per-piece branches.
+        constexpr int kBatch = 4;
+        int64_t slot[2 * kBatch];
+#pragma unroll
+        for (int j = 0; j < 2 * kBatch; ++j) {
+          const int last = n_other - 1;
+          const int e = e0 + max(0, j < last ? j : last);
+          slot[j] = static_cast<int64_t>(p.part_base[e]) + static_cast<int64_t>(g) * p.part_hstride[e] + hh;
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          if (q * kBatch < n_max) {
+            f32x2 ml[kBatch];
+            f32x4 oj[kBatch][D / 16];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+              ml[k] = *reinterpret_cast<const f32x2 *>(p.part_ml + slot[q * kBatch + k] * 2);
+              const float *src = p.part_o + slot[q * kBatch + k] * D + jj * 4;
+#pragma unroll
+              for (int dt = 0; dt < D / 16; ++dt) oj[k][dt] = *reinterpret_cast<const f32x4 *>(src + dt * 16);
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) fold(ml[k], oj[k], q * kBatch + k < n_other);
+          }
+        }
+        for (int j = 2 * kBatch; j < n_max; ++j) {  // deeper paths: one piece at a time
+          const int last = n_other - 1;
+          const int e = e0 + max(0, j < last ? j : last);
+          const int64_t sl = static_cast<int64_t>(p.part_base[e]) + static_cast<int64_t>(g) * p.part_hstride[e] + hh;
+          const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.part_ml + sl * 2);
+          f32x4 oj[D / 16];
+          const float *src = p.part_o + sl * D + jj * 4;
+#pragma unroll
+          for (int dt = 0; dt < D / 16; ++dt) oj[dt] = *reinterpret_cast<const f32x4 *>(src + dt * 16);
+          fold(ml, oj, j < n_other);
         }
       }
       const float inv = 1.0f / l;
@@ -355,7 +389,7 @@ struct RawBlock {
 // free of conditional loads on purpose: the vector-memory completion counter is in-order, and a
 // load that is issued on one path only would force the compiler to wait for everything
 // outstanding at the join.
-template <int KV, int D, int NT>
+template <int KV, int D, int NT, bool SUFFIX>
 __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   constexpr int ESZ = (KV == kFP8) ? 1 : 2;
   constexpr int TILE_BYTES = 16 * D * ESZ;
@@ -467,17 +501,17 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
     l += __shfl_xor(l, 32);
     l_tot[nt] = l;
   }
-  finish_rows<D, NT>(p, sh, cur, cur.row0, st.o, st.m, l_tot, st.qtok, stage[threadIdx.x >> 6]);
+  finish_rows<D, NT, SUFFIX>(p, sh, cur, cur.row0, st.o, st.m, l_tot, st.qtok, stage[threadIdx.x >> 6]);
 }
 
 template <int KV, int D, int NT>
 __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_prefix_attn_kernel(AttnArgs p, Shape sh) {
-  attn_wave<KV, D, NT>(p, sh);
+  attn_wave<KV, D, NT, false>(p, sh);
 }
 
 template <int KV, int D, int NT>
 __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_suffix_attn_kernel(AttnArgs p, Shape sh) {
-  attn_wave<KV, D, NT>(p, sh);
+  attn_wave<KV, D, NT, true>(p, sh);
 }
 
 // Block step of the cooperative kernel.  Same contraction as block_math, tuned for many row
@@ -708,7 +742,8 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
       m_out[nt] = FP8 ? st.m[nt] : st.m[nt] * p.scale_log2;
       l_out[nt] = lacc[nt][0];
     }
-    finish_rows<D, NTW>(p, sh, cur, row_base, st.o, m_out, l_out, st.qtok, lds + w * stage_floats<D>());
+    finish_rows<D, NTW, false>(p, sh, cur, row_base, st.o, m_out, l_out, st.qtok,
+                               lds + w * stage_floats<D>());
   }
 }
 
