@@ -7,7 +7,6 @@
 namespace spex {
 namespace {
 
-constexpr int64_t kTargetItems = 4096;  // ~2 work items per wavefront slot of the chip
 constexpr int32_t kWaveRowsMax = 32;    // largest group the wavefront kernel takes
 constexpr int kWideClass = 1;           // cooperative launch class of groups above 64 rows
 constexpr int32_t kWideSpan = 64 << kWideClass;  // rows per workgroup in that class
@@ -162,15 +161,15 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     prefix_pages_weighted +=
         static_cast<int64_t>(s.ids.size()) * (s.qt_count * G <= 64 ? 1 : (s.qt_count * G + kWideSpan - 1) / kWideSpan);
 
-  // ---- split granularity
+  // ---- split granularity.  Every extra chunk costs a partial result per row that is written and
+  // read back, so segments are cut only as far as needed to keep the longest work item near
+  // 1/1024 (shared prefix) or 1/2048 (suffix) of the launch, i.e. a few items per wavefront slot.
   pl.prefix_chunk_pages = prefix_chunk_pages > 0
                               ? prefix_chunk_pages
-                              : clamp32((prefix_pages_weighted * num_kv_heads + kTargetItems - 1) /
-                                            kTargetItems, 8, 256);
+                              : clamp32((prefix_pages_weighted * num_kv_heads + 1023) / 1024, 16, 256);
   pl.suffix_chunk_pages = suffix_chunk_pages > 0
                               ? suffix_chunk_pages
-                              : clamp32((suffix_pages * num_kv_heads + kTargetItems - 1) /
-                                            kTargetItems, 4, 64);
+                              : clamp32((suffix_pages * num_kv_heads + 2047) / 2048, 8, 64);
 
   // ---- tasks
   std::vector<std::vector<std::pair<int32_t, int32_t>>> parts(NQ);
