@@ -225,3 +225,50 @@ def test_device_errors_are_reported_not_raised_from_kernels():
     torch.cuda.synchronize()
     assert torch.all(out == 0) and abs(lse[0, 0].item() - np.log(64)) < 1e-5
     t.close()
+
+
+# ------------------------------------------------------------------ wide groups / pool layouts
+WIDE = [
+    # 40 branches x G=8 -> 320 stacked rows at the root: three 128-row spans of the cooperative kernel
+    sw.spec_at_scale(n_queries=2, prompt=150, step=40, branches=40, heads=(32, 4, 128)),
+    # 24 branches x 6 drafts x G=5 -> 720 rows, fp8, causal drafts reach into partial pages
+    sw.tot_with_drafts(n_queries=1, prompt=90, step=24, depth=3, drafts=6, heads=(20, 4, 128)),
+    sw.spec_at_scale(n_queries=2, prompt=100, step=30, branches=20, heads=(16, 2, 64), kv_dtype="fp8_e4m3"),
+    sw.bfs_tot(n_queries=2, prompt=100, step=40, width=64, keep=16, depth=3, heads=(16, 4, 64)),
+]
+
+
+@pytest.mark.parametrize("wl", WIDE, ids=lambda w: f"{w.name}_{w.kv_dtype}_{w.num_q_heads}")
+@pytest.mark.parametrize("mode", [0, 1])
+def test_wide_groups_match_oracle(wl, mode):
+    ref = run_oracle(wl)
+    for chunks in ((0, 0), (3, 2)):
+        got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1], kernel_mode=mode)
+        assert_close(got, ref, wl.kv_dtype, f"{wl.name} mode {mode} chunks {chunks}")
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3", "f32"])
+def test_interleaved_kv_pool(kv_dtype):
+    wl = sw.random_trace(61, heads=(8, 2, 128) if kv_dtype != "f32" else (4, 2, 64), kv_dtype=kv_dtype,
+                         q_dtype="f32" if kv_dtype == "f32" else "bf16", n_ops=60, max_tokens=70,
+                         max_q_len=3)
+    ref = run_oracle(wl)
+    order = np.random.default_rng(3).permutation(wl.peak_pages() + 5).tolist()
+    got = run_gpu(wl, interleave_kv=True, free_order=order, extra_pages=5, pool_fill=0xFF)
+    assert_close(got, ref, kv_dtype, "interleaved " + kv_dtype)
+    sep = run_gpu(wl, free_order=order, extra_pages=5)
+    assert np.array_equal(got[0], sep[0])
+
+
+def test_softmax_scale_must_be_positive():
+    import paper_2605_10195_amd as spex
+    t = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=4, device="cuda")
+    (r,) = t.fork(-1, 1)
+    k = torch.zeros((5, 2, 64), dtype=torch.bfloat16, device="cuda")
+    t.append_step(r, k, k)
+    q = torch.zeros((1, 8, 64), dtype=torch.bfloat16, device="cuda")
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(spex.SpexError) as e:
+            t.decode_attention([r], None, q, bad)
+        assert e.value.name == "INVALID_ARG"
+    t.close()
