@@ -7,7 +7,7 @@
 namespace spex {
 namespace {
 
-constexpr int32_t kWaveRowsMax = 32;    // largest group the wavefront kernel takes
+constexpr int32_t kWaveRowsMax = 16;    // largest group the wavefront kernel takes
 constexpr int kWideClass = 1;           // cooperative launch class of groups above 64 rows
 constexpr int32_t kWideSpan = 64 << kWideClass;  // rows per workgroup in that class
 
@@ -248,7 +248,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
                                           pl.task_pbase[t],    pl.task_flags[t], g, row0};
     items.insert(items.end(), rec, rec + Plan::kItemInts);
   };
-  // Shared-prefix items.  Groups of up to 32 rows go to the wavefront kernel (one item per task
+  // Shared-prefix items.  Groups of up to 16 rows go to the wavefront kernel (one item per task
   // and kv head).  Larger groups go to the cooperative kernel, one workgroup per (task, kv head,
   // span of 64 * NTW rows): NTW = 1 for up to 64 rows, else NTW = 2 (spans of 128 rows).
   // The spans of one (task, kv head) read the same pages; workgroup b of a launch runs on XCD
