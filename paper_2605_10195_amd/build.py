@@ -38,5 +38,21 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+PROBE_PATH = os.path.join(HERE, "hbm_probe")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Compile the stand-alone HBM bandwidth probe (measurement aid, not part of the library)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", os.path.join(CSRC, "hbm_probe.hip"), "-o", PROBE_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    return PROBE_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probe(verbose=True))
