@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--kv-pools", default="interleaved", choices=["interleaved", "separate"])
     ap.add_argument("--prefix-chunk", type=int, default=0)
     ap.add_argument("--suffix-chunk", type=int, default=0)
+    ap.add_argument("--kernel-mode", type=int, default=0,
+                    help="0 automatic, 2 shared-prefix + suffix + merge kernels, 3 tree-walk kernel")
+    ap.add_argument("--walk-row-tiles", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true",
@@ -106,7 +109,8 @@ def main():
         tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
                              wl.kv_dtype, num_pages=n_pages, device=dev, free_order=order,
                              prefix_chunk_pages=args.prefix_chunk, suffix_chunk_pages=args.suffix_chunk,
-                             interleave_kv=args.kv_pools == "interleaved")
+                             interleave_kv=args.kv_pools == "interleaved", kernel_mode=args.kernel_mode,
+                             walk_row_tiles=args.walk_row_tiles)
         sw.replay(wl, tree, device=dev)
         trees.append(tree)
     q = sw.gen_queries(wl, device=dev)
@@ -152,20 +156,24 @@ def main():
     prof = np.concatenate([t.read_profile() for t in trees], axis=0)
     for t in trees:
         t.set_profiling(False)
-    k_ms = [float(x) for x in prof.mean(axis=0)]          # prefix, suffix, merge
+    k_ms = [float(x) for x in prof.mean(axis=0)]          # prefix, suffix, merge, tree-walk
     b_tok = wl.kv_bytes_per_token()
     kernels = {}
-    for name, ms, toks in (("prefix", k_ms[0], info["prefix_tokens"]),
-                           ("suffix", k_ms[1], info["suffix_tokens"])):
+    walked = info["walk_row_tiles"] > 0
+    for name, ms, toks in (("prefix", k_ms[0], 0 if walked else info["prefix_tokens"]),
+                           ("suffix", k_ms[1], 0 if walked else info["suffix_tokens"]),
+                           ("walk", k_ms[3], info["kv_tokens"] if walked else 0)):
         gbps = toks * b_tok / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         kernels[name] = dict(ms=float(ms), kv_tokens=int(toks), kv_bytes=float(toks * b_tok),
                              gbps=gbps, frac_hbm=gbps / HBM_PEAK_GBPS)
-    part_bytes = info["partial_rows"] * (wl.head_dim + 2) * 4 + nq * wl.num_q_heads * (wl.head_dim + 1) * 4
+    part_bytes = 0 if walked else (info["partial_rows"] * (wl.head_dim + 2) * 4 +
+                                   nq * wl.num_q_heads * (wl.head_dim + 1) * 4)
     kernels["merge"] = dict(ms=float(k_ms[2]), bytes=float(part_bytes),
                             gbps=part_bytes / (k_ms[2] * 1e-3) / 1e9 if k_ms[2] > 0 else 0.0)
-    dominant = "suffix" if k_ms[1] >= k_ms[0] else "prefix"
+    dominant = "walk" if walked else ("suffix" if k_ms[1] >= k_ms[0] else "prefix")
     dom = kernels[dominant]
-    kernel_name = {"suffix": "spex_suffix_attn_kernel", "prefix": "spex_prefix_attn_kernel"}[dominant]
+    kernel_name = {"suffix": "spex_suffix_attn_kernel", "prefix": "spex_prefix_attn_kernel",
+                   "walk": "spex_tree_walk_kernel"}[dominant]
 
     result = {
         "metric": "tree decode-attn query-tokens/s + achieved HBM GB/s (unique KV bytes), 1 GPU",
@@ -187,6 +195,8 @@ def main():
             "unique_kv_bytes": unique_bytes, "flat_kv_bytes": wl.flat_kv_tokens() * b_tok,
             "tree_copies_rotated": copies, "page_placement": args.placement, "kv_pools": args.kv_pools,
             "prefix_chunk_pages": args.prefix_chunk, "suffix_chunk_pages": args.suffix_chunk,
+            "kernels": "tree-walk" if walked else "shared-prefix + suffix + merge",
+            "walk_row_tiles": int(info["walk_row_tiles"]),
         },
         "hbm_gbps_unique_kv": unique_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac_unique_kv": unique_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

@@ -86,11 +86,14 @@ typedef struct {
                                 pages are first handed out; NULL = ascending.  Copied by create. */
   int32_t prefix_chunk_pages; /* split granularity of shared-prefix segments; 0 = automatic */
   int32_t suffix_chunk_pages; /* split granularity of private suffixes;       0 = automatic */
-  int32_t kernel_mode;  /* 0 = fastest kernels available; 1 = force the generic (non-MFMA) kernels */
+  int32_t kernel_mode;  /* 0 = automatic; 1 = generic (non-MFMA) kernels; 2 = shared-prefix + suffix +
+                           merge kernels; 3 = tree-walk kernel (decode_attention fails with
+                           SPEX_ERR_UNSUPPORTED where it does not apply) */
   int32_t page_stride_tiles; /* distance between consecutive pages of a pool, in (page, head) tiles;
                                 0 = num_kv_heads (dense).  2 * num_kv_heads with
                                 v_pool = k_pool + num_kv_heads tiles interleaves K and V of a page
                                 in one buffer, so that a page's K and V share a 64 KiB region. */
+  int32_t walk_row_tiles; /* tree-walk kernel: 16-row tiles per wavefront, 1 / 2 / 4; 0 = automatic */
 } spex_config_t;
 
 /* Bytes each of k_pool and v_pool must hold for this config. */
@@ -154,10 +157,17 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *   out : DEVICE fp32, same shape:  sum_t softmax_t(sm_scale * <q, K_t>) V_t  over visible t
  *   lse : DEVICE fp32 [sum(q_lens)][num_q_heads] or NULL:  ln sum_t exp(sm_scale * <q, K_t>)
  *   sm_scale must be positive and finite.
- * The call flattens parent links into per-launch work lists (shared-prefix groups are read
- * once for all nodes below them; private suffixes are split for parallelism), uploads them
- * when the request or the tree changed since the previous call, and enqueues the
- * shared-prefix, suffix and merge kernels on hip_stream.  It does not wait for them.
+ * The call flattens parent links into per-launch work lists, uploads them when the request or
+ * the tree changed since the previous call, and enqueues the kernels on hip_stream without
+ * waiting for them.  Two kernel sets compute the same result:
+ *   tree-walk: one workgroup carries a block of up to 64 * walk_row_tiles query rows (requested
+ *     nodes that are neighbours in the tree) from the root to the requested nodes; pages shared
+ *     by rows of several wavefronts are fetched once per workgroup, the softmax state stays in
+ *     registers, only the output is written.  Needs MFMA-tiled pools and q_len * Hq / Hkv <= 64
+ *     for every requested node.  Chosen automatically when it yields >= 128 workgroups or when
+ *     every workgroup has at most 64 two-page blocks;
+ *   shared-prefix + suffix + merge: every shared node is read once for all rows below it, private
+ *     suffixes are split for parallelism, partial softmax states go through memory.  Any shape.
  * Consecutive calls on one handle must use one stream or be separated by a synchronisation,
  * because they share the handle's workspace.
  */
@@ -226,16 +236,47 @@ spex_status_t spex_tree_gather_kv(spex_tree_t *tree, spex_node_t node, int32_t f
                                   void *k_out, void *v_out, float *k_scale_out, float *v_scale_out,
                                   void *hip_stream);
 
-/* Change the split granularities (0 = automatic) and kernel_mode after creation. */
+/* Change the split granularities (0 = automatic), kernel_mode and walk_row_tiles after creation. */
 spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages,
-                                   int32_t suffix_chunk_pages, int32_t kernel_mode);
+                                   int32_t suffix_chunk_pages, int32_t kernel_mode,
+                                   int32_t walk_row_tiles);
+
+/*
+ * The tree-walk kernel's lists for a request (HOST arrays owned by the tree, valid until the next
+ * call that plans or mutates it).  available = 0: some requested node has more rows than one
+ * wavefront takes; the arrays are then empty.  With G = Hq / Hkv and C = 16 * row_tiles:
+ *   qt[2 * n_qt]: {query token, visible path length} of the requested nodes, grouped by root
+ *     (roots in order of first appearance) and sorted by path below a root, so that the requests
+ *     below any node are consecutive.
+ *   row_blocks[15 * n_row_blocks]: {root node, first block, shared blocks, private blocks of
+ *     wavefronts 0..3, first qt entry of wavefronts 0..3, qt entries of wavefronts 0..3}.  Requests
+ *     fill a wavefront while their q_len * G rows fit into C; a fifth wavefront or a new root
+ *     starts a new row block.  Row of a request: wavefront * C + rows before it in the wavefront.
+ *   blocks[8 * n_blocks]: {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b (0 = no page
+ *     b), first row | (last row + 1) << 16, flags, 0, 0}: two consecutive pages of one node on the
+ *     row block's paths, the path position and valid tokens of each, and the rows whose path
+ *     holds the node.  A row block's blocks: first the nodes whose rows touch several
+ *     wavefronts, then those of wavefront 0, 1, 2, 3 alone; every page of every row's path
+ *     appears exactly once per row block.  Flag bit 0: a page is partial or missing, or some
+ *     row in the range sees fewer positions than the block ends at.
+ *   items[16 * n_items]: launch order, one workgroup each: {kv head, copy of row block fields
+ *     1..14, row block index}; index -1 = padding that keeps the row blocks of one root on one
+ *     XCD when fewer than 8 kv heads exist.
+ */
+typedef struct {
+  int32_t available, row_tiles, n_row_blocks, n_blocks, n_qt, n_items;
+  const int32_t *row_blocks, *blocks, *qt, *items;
+} spex_walk_view_t;
+spex_status_t spex_tree_walk_dump(spex_tree_t *tree, const spex_node_t *leaves,
+                                  const int32_t *q_lens, int32_t n_leaves, spex_walk_view_t *out);
 
 /*
  * Per-kernel timing.  While profiling is enabled, every decode_attention call brackets each of
  * its kernels with HIP events on the call's stream (the last 256 calls are kept).
  * spex_tree_read_profile waits for those events and writes, for each recorded call in order,
- * milliseconds for ms[3*c+0] = shared-prefix kernel, ms[3*c+1] = suffix kernel, ms[3*c+2] = merge
- * kernel (0 for a kernel that was not launched); *n = number of calls; the record is then
+ * milliseconds for ms[4*c+0] = shared-prefix kernel, ms[4*c+1] = suffix kernel, ms[4*c+2] = merge
+ * kernel, ms[4*c+3] = tree-walk kernel (0 for a kernel that was not launched; cap counts calls,
+ * ms holds 4 * cap floats); *n = number of calls; the record is then
  * cleared.  SPEX_ERR_CAPACITY (with *n set) if cap calls are too few.  Enabling or disabling
  * profiling also clears the record.
  */
@@ -243,8 +284,11 @@ spex_status_t spex_tree_set_profiling(spex_tree_t *tree, int32_t enabled);
 spex_status_t spex_tree_read_profile(spex_tree_t *tree, float *ms, int32_t cap, int32_t *n);
 
 /* Counts of the last decode_attention call, for the throughput metric:
- * info[0] distinct KV tokens read, [1] tokens in shared-prefix tasks, [2] tokens in suffix tasks,
- * [3] prefix work items, [4] suffix work items, [5] partial rows, [6] 1 if the plan was rebuilt. */
+ * info[0] distinct KV tokens on the requested paths, [1] of which on nodes shared by >= 2 requested
+ * nodes, [2] of which private, [6] 1 if the plan was rebuilt, [7] 0 = shared-prefix + suffix + merge
+ * kernels ran ([3] prefix work items, [4] suffix work items, [5] partial rows), else the tree-walk
+ * kernel ran with [7] row tiles per wavefront ([3] workgroups with work, [4] two-page blocks
+ * summed over workgroups of one kv head, [5] 0). */
 spex_status_t spex_tree_last_launch_info(const spex_tree_t *tree, int64_t info[8]);
 
 #ifdef __cplusplus

@@ -48,6 +48,33 @@ Plan for requested nodes leaves[0..L) with q_lens (caller order):
     step: those of requested nodes whose suffix is empty or cut into several chunks;
   * the merge list of a query token holds, in task order, for every task that
     has it as a row: base = pbase + r * G and hstride = rows.
+
+Tree-walk lists (second kernel set: one workgroup carries a block of query rows
+from the root to the requested nodes).  With G = Hq / Hkv, request i has
+q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
+  * row_tiles is the value asked for (1, 2, 4) or, if 0, the smallest of them
+    with max rows <= 16 * row_tiles, raised to 2 when it is 1 and some root has
+    more than 64 rows below it; no lists if a request has more rows than C;
+  * roots in order of first appearance; a root's requests sorted by path (node
+    ids root first, lexicographic, a proper prefix first; ties in request
+    order), so the requests below any node are consecutive;
+  * a request joins the current wavefront while its rows fit, else starts the
+    next; a fifth wavefront or a new root starts a new row block; `qt` lists
+    (query token, limit) of the requests in this order; the row of a request in
+    its row block is wavefront * C + rows before it in the wavefront;
+  * the nodes of a row block are the nodes with tokens on its requests' paths in
+    order of first encounter, with row range [first row of the first request
+    through it, last row + 1 of the last one) and minlim = min T - q_len + 1 over
+    those requests; a node whose range touches two wavefronts is shared, else
+    private to wavefront lo // C;
+  * blocks of a row block: shared nodes first, then the private nodes of
+    wavefront 0..3, a node's pages two at a time; record (page a, pos_a << 7 |
+    valid_a, page b or a again, pos_b << 7 | valid_b or 0, lo | hi << 16, flag, 0,
+    0); flag = a page partial or missing, or minlim < position after the block;
+  * launch order: roots by descending block count (stable); lanes = 8 // Hkv for
+    Hkv in (1, 2, 4) else 1; each root goes to the lane with the fewest blocks so
+    far; round r emits for every lane its r-th row block (padding if it ran out
+    and lanes > 1), each for kv head 0..Hkv-1.
 """
 
 from __future__ import annotations
@@ -292,3 +319,139 @@ class PageTableRef:
             part_indptr=part_indptr, part_base=part_base, part_hstride=part_hstride,
             merge_qt=merge_qt,
         )
+
+    # ---------------------------------------------------------------- tree-walk lists
+    def walk_plan(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
+                  num_q_heads: int, num_kv_heads: int, row_tiles: int = 0) -> Dict[str, object]:
+        L = len(leaves)
+        q_lens = [1] * L if q_lens is None else list(q_lens)
+        G = num_q_heads // num_kv_heads
+        P = self.P
+        paths = [self.path(u) for u in leaves]
+        rows = [ql * G for ql in q_lens]
+        none = dict(available=0, row_tiles=0, row_blocks=[], blocks=[], qt=[], items=[])
+        if L == 0:
+            return none
+        qoff, limits = [], []
+        for path, ql in zip(paths, q_lens):
+            T = sum(self.tokens[w] for w in path)
+            qoff.append(len(limits))
+            limits += [T - ql + 1 + i for i in range(ql)]
+        roots: List[int] = []
+        for path in paths:
+            if path[0] not in roots:
+                roots.append(path[0])
+        root_rows = {r: 0 for r in roots}
+        for path, n in zip(paths, rows):
+            root_rows[path[0]] += n
+        if row_tiles == 0:
+            if max(rows) > 64:
+                return none
+            row_tiles = 1 if max(rows) <= 16 else (2 if max(rows) <= 32 else 4)
+            if row_tiles == 1 and max(root_rows.values()) > 64:
+                row_tiles = 2
+        elif max(rows) > 16 * row_tiles:
+            return dict(none, row_tiles=0)
+        C = 16 * row_tiles
+        pos0: Dict[int, int] = {}
+        for path in paths:
+            t = 0
+            for w in path:
+                pos0[w] = t
+                t += self.tokens[w]
+
+        order = sorted(range(L), key=lambda i: (roots.index(paths[i][0]), paths[i], i))
+        qt: List[int] = []
+        row_blocks: List[List[int]] = []
+        blocks: List[List[int]] = []
+        rb_total: List[int] = []
+        rbs_of_root: Dict[int, List[int]] = {r: [] for r in roots}
+
+        def node_blocks(u, lo, hi, minlim):
+            out = []
+            pages, valid = self.pages[u], self.node_page_valid(u)
+            for k in range(0, len(pages), 2):
+                has_b = k + 1 < len(pages)
+                va, vb = valid[k], (valid[k + 1] if has_b else 0)
+                pos_a = pos0[u] + k * P
+                pos_b = pos_a + P
+                end = pos_b + vb if has_b else pos_a + va
+                masked = va != P or not has_b or vb != P or minlim < end
+                out.append([pages[k], (pos_a << 7) | va, pages[k + 1] if has_b else pages[k],
+                            ((pos_b << 7) | vb) if has_b else 0, lo | (hi << 16), int(masked), 0, 0])
+            return out
+
+        def flush(root, placed, qt_first, qt_count):
+            if not placed:
+                return
+            nodes: Dict[int, List[int]] = {}          # insertion order = encounter order
+            for i, row0 in placed:
+                for w in paths[i]:
+                    if self.tokens[w] == 0:
+                        continue
+                    if w not in nodes:
+                        nodes[w] = [row0, row0 + rows[i], limits[qoff[i]]]
+                    else:
+                        nodes[w][1] = row0 + rows[i]
+                        nodes[w][2] = min(nodes[w][2], limits[qoff[i]])
+            first = len(blocks)
+            shared = [b for w, (lo, hi, ml) in nodes.items() if lo // C != (hi - 1) // C
+                      for b in node_blocks(w, lo, hi, ml)]
+            blocks.extend(shared)
+            n_priv = []
+            for wv in range(4):
+                mine = [b for w, (lo, hi, ml) in nodes.items()
+                        if lo // C == (hi - 1) // C and lo // C == wv for b in node_blocks(w, lo, hi, ml)]
+                blocks.extend(mine)
+                n_priv.append(len(mine))
+            rbs_of_root[root].append(len(row_blocks))
+            row_blocks.append([root, first, len(shared)] + n_priv + qt_first + qt_count)
+            rb_total.append(len(shared) + sum(n_priv))
+
+        cur_root, wave, used = None, 0, 0
+        placed, qt_first, qt_count = [], [0] * 4, [0] * 4
+        for i in order:
+            root = paths[i][0]
+            if root != cur_root:
+                flush(cur_root, placed, qt_first, qt_count)
+                cur_root, wave, used = root, 0, 0
+                placed, qt_first, qt_count = [], [0] * 4, [0] * 4
+            elif used + rows[i] > C:
+                wave, used = wave + 1, 0
+                if wave == 4:
+                    flush(cur_root, placed, qt_first, qt_count)
+                    wave = 0
+                    placed, qt_first, qt_count = [], [0] * 4, [0] * 4
+            if qt_count[wave] == 0:
+                qt_first[wave] = len(qt) // 2
+            for j in range(q_lens[i]):
+                qt += [qoff[i] + j, limits[qoff[i] + j]]
+            qt_count[wave] += q_lens[i]
+            placed.append((i, wave * C + used))
+            used += rows[i]
+        flush(cur_root, placed, qt_first, qt_count)
+
+        root_blocks = {r: sum(rb_total[b] for b in rbs_of_root[r]) for r in roots}
+        root_order = sorted(roots, key=lambda r: -root_blocks[r])      # stable
+        lanes = 8 // num_kv_heads if num_kv_heads in (1, 2, 4) else 1
+        lane_rbs: List[List[int]] = [[] for _ in range(lanes)]
+        load = [0] * lanes
+        for r in root_order:
+            best = min(range(lanes), key=lambda l: (load[l], l))
+            lane_rbs[best] += rbs_of_root[r]
+            load[best] += root_blocks[r]
+        items: List[int] = []
+        for r in range(max(len(v) for v in lane_rbs)):
+            for l in range(lanes):
+                real = r < len(lane_rbs[l])
+                if not real and lanes == 1:
+                    continue
+                for g in range(num_kv_heads):
+                    if real:
+                        rb = lane_rbs[l][r]
+                        items += [g] + row_blocks[rb][1:] + [rb]
+                    else:
+                        items += [g] + [0] * 14 + [-1]
+        return dict(available=1, row_tiles=row_tiles,
+                    row_blocks=[x for rb in row_blocks for x in rb],
+                    blocks=[x for b in blocks for x in b], qt=qt, items=items)

@@ -43,6 +43,7 @@ class Config(C.Structure):
         ("free_order", C.POINTER(C.c_int32)),
         ("prefix_chunk_pages", C.c_int32), ("suffix_chunk_pages", C.c_int32),
         ("kernel_mode", C.c_int32), ("page_stride_tiles", C.c_int32),
+        ("walk_row_tiles", C.c_int32),
     ]
 
 
@@ -67,13 +68,19 @@ class PlanView(C.Structure):
                                      "part_base", "part_hstride", "merge_qt")]
 
 
+class WalkView(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("available", "row_tiles", "n_row_blocks", "n_blocks", "n_qt",
+                                         "n_items")] + \
+               [(n, _I32P) for n in ("row_blocks", "blocks", "qt", "items")]
+
+
 EXPORTS = [
     "spex_pool_bytes", "spex_status_string", "spex_last_device_error", "spex_tree_create",
     "spex_tree_destroy", "spex_tree_fork", "spex_tree_append_step", "spex_tree_append_new_pages",
     "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
-    "spex_tree_last_launch_info",
+    "spex_tree_last_launch_info", "spex_tree_walk_dump",
 ]
 
 
@@ -102,7 +109,8 @@ def _load():
     lib.spex_tree_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.spex_tree_plan_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(PlanView)]
     lib.spex_tree_gather_kv.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
-    lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32]
+    lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32, i32]
+    lib.spex_tree_walk_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(WalkView)]
     lib.spex_tree_set_profiling.argtypes = [vp, i32]
     lib.spex_tree_read_profile.argtypes = [vp, C.POINTER(f32), i32, _I32P]
     lib.spex_tree_last_launch_info.argtypes = [vp, C.POINTER(i64)]
@@ -145,7 +153,7 @@ class SpexTree:
                  q_dtype: str = "bf16", kv_dtype: str = "bf16", num_pages: int = 0,
                  device="cuda", free_order: Optional[Sequence[int]] = None,
                  prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0,
-                 host_only: bool = False, pool_fill: Optional[int] = None,
+                 walk_row_tiles: int = 0, host_only: bool = False, pool_fill: Optional[int] = None,
                  interleave_kv: bool = False):
         self.Hq, self.Hkv, self.D, self.P = num_q_heads, num_kv_heads, head_dim, page_size
         self.q_dtype, self.kv_dtype = _DTYPES[q_dtype], _DTYPES[kv_dtype]
@@ -158,6 +166,7 @@ class SpexTree:
         cfg.num_pages = self.num_pages
         cfg.prefix_chunk_pages, cfg.suffix_chunk_pages = prefix_chunk_pages, suffix_chunk_pages
         cfg.kernel_mode = kernel_mode
+        cfg.walk_row_tiles = walk_row_tiles
         self.k_pool = self.v_pool = self.k_scale = self.v_scale = None
         if not host_only:
             nbytes = C.c_size_t()
@@ -320,15 +329,31 @@ class SpexTree:
                                        _stream()))
         return k, v, ks, vs
 
-    def set_tuning(self, prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0):
-        _check(lib.spex_tree_set_tuning(self._h, prefix_chunk_pages, suffix_chunk_pages, kernel_mode))
+    def set_tuning(self, prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0,
+                   walk_row_tiles: int = 0):
+        _check(lib.spex_tree_set_tuning(self._h, prefix_chunk_pages, suffix_chunk_pages, kernel_mode,
+                                        walk_row_tiles))
+
+    def walk_dump(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]]) -> dict:
+        la = _i32(leaves)
+        qa = None if q_lens is None else _i32(q_lens)
+        v = WalkView()
+        _check(lib.spex_tree_walk_dump(self._h, _ptr(la), _ptr(qa), len(la), C.byref(v)))
+
+        def arr(name, n):
+            p = getattr(v, name)
+            return [] if n == 0 else np.ctypeslib.as_array(p, shape=(n,)).tolist()
+
+        return dict(available=v.available, row_tiles=v.row_tiles,
+                    row_blocks=arr("row_blocks", 15 * v.n_row_blocks), blocks=arr("blocks", 8 * v.n_blocks),
+                    qt=arr("qt", 2 * v.n_qt), items=arr("items", 16 * v.n_items))
 
     def set_profiling(self, enabled: bool):
         _check(lib.spex_tree_set_profiling(self._h, int(enabled)))
 
     def read_profile(self) -> np.ndarray:
-        """[n_calls, 3] milliseconds (prefix, suffix, merge) of the calls recorded so far."""
-        ms = np.zeros((256, 3), dtype=np.float32)
+        """[n_calls, 4] milliseconds (prefix, suffix, merge, tree-walk) of the calls recorded so far."""
+        ms = np.zeros((256, 4), dtype=np.float32)
         n = C.c_int32()
         _check(lib.spex_tree_read_profile(self._h, ms.ctypes.data_as(C.POINTER(C.c_float)), 256,
                                           C.byref(n)))
@@ -338,7 +363,7 @@ class SpexTree:
         info = (C.c_int64 * 8)()
         _check(lib.spex_tree_last_launch_info(self._h, info))
         names = ["kv_tokens", "prefix_tokens", "suffix_tokens", "prefix_items", "suffix_items",
-                 "partial_rows", "plan_rebuilt"]
+                 "partial_rows", "plan_rebuilt", "walk_row_tiles"]
         return {n: info[i] for i, n in enumerate(names)}
 
 

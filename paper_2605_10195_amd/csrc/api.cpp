@@ -39,6 +39,7 @@ struct DevicePlan {
   const int32_t *part_indptr = nullptr, *part_base = nullptr, *part_hstride = nullptr;
   const int32_t *merge_qt = nullptr;
   const int32_t *coop_items[3] = {nullptr, nullptr, nullptr};
+  const int32_t *walk_items = nullptr, *walk_blocks = nullptr, *walk_qt = nullptr;
 };
 
 }  // namespace
@@ -62,12 +63,12 @@ struct spex_tree {
   float *d_part_o = nullptr, *d_part_ml = nullptr;
   int64_t part_cap_rows = 0;
 
-  int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0;
+  int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0, walk_row_tiles = 0;
   // Profiling: a ring of event sets, one per decode_attention call since it was enabled.
   static constexpr int kProfSlots = 256;
   struct ProfSlot {
-    hipEvent_t ev[6] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-    bool valid[3] = {false, false, false};
+    hipEvent_t ev[8] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    bool valid[4] = {false, false, false, false};
   };
   bool profiling = false;
   std::vector<ProfSlot> prof;
@@ -87,7 +88,9 @@ spex_status_t check_config(const spex_config_t *c) {
   if (c->num_pages < 0 || c->num_pages > INT32_MAX) return SPEX_ERR_INVALID_ARG;
   if (c->prefix_chunk_pages < 0 || c->suffix_chunk_pages < 0) return SPEX_ERR_INVALID_ARG;
   if (c->page_stride_tiles != 0 && c->page_stride_tiles < c->num_kv_heads) return SPEX_ERR_INVALID_ARG;
-  if (c->kernel_mode != 0 && c->kernel_mode != 1) return SPEX_ERR_INVALID_ARG;
+  if (c->kernel_mode < 0 || c->kernel_mode > 3) return SPEX_ERR_INVALID_ARG;
+  if (c->walk_row_tiles != 0 && c->walk_row_tiles != 1 && c->walk_row_tiles != 2 && c->walk_row_tiles != 4)
+    return SPEX_ERR_INVALID_ARG;
   const bool ok = (c->q_dtype == SPEX_F32 && c->kv_dtype == SPEX_F32) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_BF16) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_FP8_E4M3);
@@ -118,7 +121,9 @@ spex::Shape make_shape(const spex_config_t &c) {
 bool same_request(const spex::Plan &pl, const spex_tree *t, const int32_t *leaves,
                   const int32_t *q_lens, int32_t n) {
   if (!pl.valid || pl.table_version != t->pt->version()) return false;
-  if (pl.req_prefix_chunk != t->prefix_chunk || pl.req_suffix_chunk != t->suffix_chunk) return false;
+  if (pl.req_prefix_chunk != t->prefix_chunk || pl.req_suffix_chunk != t->suffix_chunk ||
+      pl.req_walk_row_tiles != t->walk_row_tiles)
+    return false;
   if (static_cast<int32_t>(pl.req_leaves.size()) != n) return false;
   if (n && std::memcmp(pl.req_leaves.data(), leaves, sizeof(int32_t) * n) != 0) return false;
   if (q_lens) {
@@ -138,7 +143,7 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
   t->plan_on_device = false;
   const spex::PlanError e = t->planner.build(*t->pt, leaves, q_lens, n, t->cfg.num_q_heads,
                                              t->cfg.num_kv_heads, t->prefix_chunk, t->suffix_chunk,
-                                             &t->plan);
+                                             t->walk_row_tiles, &t->plan);
   switch (e) {
     case spex::PlanError::kOk: return SPEX_OK;
     case spex::PlanError::kBadNode: t->plan.valid = false; return SPEX_ERR_BAD_NODE;
@@ -153,7 +158,8 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   const std::vector<int32_t> *arrays[] = {
       &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
       &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt,
-      &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2]};
+      &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2],
+      &pl.walk_items, &pl.walk_blocks, &pl.walk_qt};
   constexpr int kN = sizeof(arrays) / sizeof(arrays[0]);
   size_t off[kN], total = 0;
   for (int i = 0; i < kN; ++i) {
@@ -200,6 +206,9 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   dp.part_hstride = at(6);
   dp.merge_qt = at(7);
   for (int c = 0; c < 3; ++c) dp.coop_items[c] = at(8 + c);
+  dp.walk_items = at(11);
+  dp.walk_blocks = at(12);
+  dp.walk_qt = at(13);
   t->plan_on_device = true;
   return SPEX_OK;
 }
@@ -278,6 +287,7 @@ spex_status_t spex_tree_create(const spex_config_t *cfg, spex_tree_t **out) {
   t->prefix_chunk = cfg->prefix_chunk_pages;
   t->suffix_chunk = cfg->suffix_chunk_pages;
   t->kernel_mode = cfg->kernel_mode;
+  t->walk_row_tiles = cfg->walk_row_tiles;
   *out = t;
   return SPEX_OK;
 }
@@ -391,10 +401,61 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     if (us != SPEX_OK) return us;
   }
   const spex::Plan &pl = t->plan;
+  // Which kernels: the tree-walk kernel when its lists exist and fill the chip (or every work item
+  // is short anyway); else shared-prefix + suffix + merge, which can split long paths.
+  const bool walk_possible = pl.walk_ok && spex::has_mfma_kernel(t->shape);
+  if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
+  const bool use_walk =
+      walk_possible && (t->kernel_mode == 3 ||
+                        (t->kernel_mode == 0 && (pl.walk_real_items >= 128 || pl.walk_max_item_blocks <= 64)));
+  const DevicePlan &dp = t->dplan;
+
+  spex_tree::ProfSlot *slot = nullptr;
+  if (t->profiling) {
+    if (t->prof.empty()) t->prof.resize(spex_tree::kProfSlots);
+    slot = &t->prof[t->prof_calls % spex_tree::kProfSlots];
+    ++t->prof_calls;
+    for (hipEvent_t &e : slot->ev)
+      if (!e) HIP_TRY(hipEventCreate(&e));
+    for (bool &b : slot->valid) b = false;
+  }
+  auto bracket = [&](int which, bool begin) -> hipError_t {
+    if (!slot) return hipSuccess;
+    if (!begin) slot->valid[which] = true;
+    return hipEventRecord(slot->ev[2 * which + (begin ? 0 : 1)], stream);
+  };
+
+  if (use_walk) {
+    spex::WalkArgs wa{};
+    wa.k_pool = t->cfg.k_pool;
+    wa.v_pool = t->cfg.v_pool;
+    wa.k_scale = t->cfg.k_scale;
+    wa.v_scale = t->cfg.v_scale;
+    wa.q = q;
+    wa.items = dp.walk_items;
+    wa.n_items = static_cast<int32_t>(pl.walk_items.size() / spex::Plan::kWalkItemInts);
+    wa.blocks = dp.walk_blocks;
+    wa.qt_rec = dp.walk_qt;
+    wa.out = out;
+    wa.lse = lse;
+    wa.scale_log2 = sm_scale * 1.4426950408889634f;
+    HIP_TRY(bracket(3, true));
+    HIP_TRY(spex::launch_tree_walk(t->shape, wa, pl.walk_row_tiles, stream));
+    HIP_TRY(bracket(3, false));
+    t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
+    t->info[1] = pl.prefix_tokens;
+    t->info[2] = pl.suffix_tokens;
+    t->info[3] = pl.walk_real_items;
+    t->info[4] = pl.walk_block_visits;
+    t->info[5] = 0;
+    t->info[6] = rebuilt ? 1 : 0;
+    t->info[7] = pl.walk_row_tiles;
+    return SPEX_OK;
+  }
+
   const spex_status_t ps = ensure_partials(t, pl.n_partial_rows);
   if (ps != SPEX_OK) return ps;
 
-  const DevicePlan &dp = t->dplan;
   spex::AttnArgs a{};
   a.k_pool = t->cfg.k_pool;
   a.v_pool = t->cfg.v_pool;
@@ -412,21 +473,6 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   a.lse = lse;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   const bool generic = t->kernel_mode == 1;
-
-  spex_tree::ProfSlot *slot = nullptr;
-  if (t->profiling) {
-    if (t->prof.empty()) t->prof.resize(spex_tree::kProfSlots);
-    slot = &t->prof[t->prof_calls % spex_tree::kProfSlots];
-    ++t->prof_calls;
-    for (hipEvent_t &e : slot->ev)
-      if (!e) HIP_TRY(hipEventCreate(&e));
-    for (bool &b : slot->valid) b = false;
-  }
-  auto bracket = [&](int which, bool begin) -> hipError_t {
-    if (!slot) return hipSuccess;
-    if (!begin) slot->valid[which] = true;
-    return hipEventRecord(slot->ev[2 * which + (begin ? 0 : 1)], stream);
-  };
 
   const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / spex::Plan::kItemInts);
   const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / spex::Plan::kItemInts);
@@ -621,12 +667,37 @@ spex_status_t spex_tree_gather_kv(spex_tree_t *t, spex_node_t node, int32_t firs
 }
 
 spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
-                                   int32_t suffix_chunk_pages, int32_t kernel_mode) {
-  if (!t || prefix_chunk_pages < 0 || suffix_chunk_pages < 0 || (kernel_mode != 0 && kernel_mode != 1))
+                                   int32_t suffix_chunk_pages, int32_t kernel_mode,
+                                   int32_t walk_row_tiles) {
+  if (!t || prefix_chunk_pages < 0 || suffix_chunk_pages < 0 || kernel_mode < 0 || kernel_mode > 3 ||
+      (walk_row_tiles != 0 && walk_row_tiles != 1 && walk_row_tiles != 2 && walk_row_tiles != 4))
     return SPEX_ERR_INVALID_ARG;
   t->prefix_chunk = prefix_chunk_pages;
   t->suffix_chunk = suffix_chunk_pages;
   t->kernel_mode = kernel_mode;
+  t->walk_row_tiles = walk_row_tiles;
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_walk_dump(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
+                                  int32_t n_leaves, spex_walk_view_t *out) {
+  if (!t || !out || n_leaves < 0 || (n_leaves > 0 && !leaves)) return SPEX_ERR_INVALID_ARG;
+  bool rebuilt = false;
+  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &rebuilt);
+  if (st != SPEX_OK) return st;
+  const spex::Plan &pl = t->plan;
+  spex_walk_view_t v{};
+  v.available = pl.walk_ok ? 1 : 0;
+  v.row_tiles = pl.walk_row_tiles;
+  v.n_row_blocks = static_cast<int32_t>(pl.walk_rb.size() / spex::Plan::kRbInts);
+  v.n_blocks = static_cast<int32_t>(pl.walk_blocks.size() / spex::Plan::kBlockInts);
+  v.n_qt = static_cast<int32_t>(pl.walk_qt.size() / 2);
+  v.n_items = static_cast<int32_t>(pl.walk_items.size() / spex::Plan::kWalkItemInts);
+  v.row_blocks = pl.walk_rb.data();
+  v.blocks = pl.walk_blocks.data();
+  v.qt = pl.walk_qt.data();
+  v.items = pl.walk_items.data();
+  *out = v;
   return SPEX_OK;
 }
 
@@ -645,13 +716,13 @@ spex_status_t spex_tree_read_profile(spex_tree_t *t, float *ms, int32_t cap, int
   const int64_t first = t->prof_calls - have;
   for (int64_t c = 0; c < have; ++c) {
     spex_tree::ProfSlot &slot = t->prof[(first + c) % spex_tree::kProfSlots];
-    for (int i = 0; i < 3; ++i) {
+    for (int i = 0; i < 4; ++i) {
       float r = 0.f;
       if (slot.valid[i]) {
         HIP_TRY(hipEventSynchronize(slot.ev[2 * i + 1]));
         HIP_TRY(hipEventElapsedTime(&r, slot.ev[2 * i], slot.ev[2 * i + 1]));
       }
-      ms[c * 3 + i] = r;
+      ms[c * 4 + i] = r;
     }
   }
   t->prof_calls = 0;

@@ -754,6 +754,402 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
   }
 }
 
+// ---- tree-walk kernel: one workgroup carries a block of query rows from the root to the leaves --
+// A work item is a row block (up to 4 wavefronts x 16 * NTW rows of the requested nodes below one
+// root, neighbours in the tree next to each other) and a kv head.  Its block list covers every
+// page on the rows' paths exactly once, each block with the range of rows whose path contains it.
+// Phase 1 walks the blocks whose rows span several wavefronts: the workgroup fetches each block
+// once into LDS operand images (as the cooperative kernel does) and every wavefront contracts it
+// with the row tiles inside the range.  Phase 2: every wavefront streams the blocks that only its
+// own rows need straight into registers.  The softmax state (m, l, o) of a row stays in registers
+// from the first block to the last, so the only global writes are the finished output rows.
+struct WalkBlock {
+  int pid_a, vp_a, pid_b, vp_b, rows, flags;
+};
+
+__device__ __forceinline__ WalkBlock load_walk_block(const int32_t *blocks, int idx) {
+  const int64_t r = static_cast<int64_t>(uniform(idx)) * 8;
+  WalkBlock b;
+  b.pid_a = sload(blocks, r + 0);
+  b.vp_a = sload(blocks, r + 1);
+  b.pid_b = sload(blocks, r + 2);
+  b.vp_b = sload(blocks, r + 3);
+  b.rows = sload(blocks, r + 4);
+  b.flags = sload(blocks, r + 5);
+  return b;
+}
+
+__device__ __forceinline__ float sload_f(const float *base, int64_t idx) {
+  typedef const float __attribute__((address_space(4))) const_f32;
+  return ((const_f32 *)(uintptr_t)base)[idx];
+}
+
+// Scores of one 32-token block for the row tiles that intersect the wave-relative row range
+// [lo, hi): S^T = K Q^T (see block_math for the operand layout).
+template <int D, int NT>
+__device__ __forceinline__ void walk_scores(const bf16x8 (&qf)[NT][D / 32], const bf16x8 (&kf)[2][D / 32],
+                                            int lo, int hi, f32x4 (&sa)[NT], f32x4 (&sb)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    if (nt * 16 >= hi || nt * 16 + 16 <= lo) continue;  // wave-uniform
+    f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+      a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][s], qf[nt][s], a, 0, 0, 0);
+      b = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][s], qf[nt][s], b, 0, 0, 0);
+    }
+    sa[nt] = a;
+    sb[nt] = b;
+  }
+}
+
+// Online softmax and O^T += V^T P^T for the same tiles; P rounded to fp16, row sums by MFMA
+// against ones (see block_math_f16).  Rows of a tile outside [lo, hi) see nothing of the block.
+template <bool FP8, int D, int NT>
+__device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&o)[NT][D / 16],
+                                                float (&m)[NT], f32x4 (&lacc)[NT],
+                                                const f32x4 (&sa)[NT], const f32x4 (&sb)[NT],
+                                                const f16x8 (&vh)[D / 16], bool tok_masked,
+                                                int valid_l, int pos_l, float c, int lo, int hi) {
+  const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
+  const _Float16 one = static_cast<_Float16>(1.0f);
+  const f16x8 ones = {one, one, one, one, one, one, one, one};
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    if (nt * 16 >= hi || nt * 16 + 16 <= lo) continue;  // wave-uniform
+    const bool partial_tile = lo > nt * 16 || hi < nt * 16 + 16;
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[i] = FP8 ? sa[nt][i] * c : sa[nt][i];
+      x[4 + i] = FP8 ? sb[nt][i] * c : sb[nt][i];
+    }
+    if (tok_masked || partial_tile) {
+      int vis = limit[nt] - pos_l;
+      vis = vis < valid_l ? vis : valid_l;
+      vis -= 8 * (jj & 1);
+      const int row = nt * 16 + m16;
+      vis = (row >= lo && row < hi) ? vis : 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m[nt], mx);
+    const float m_safe = m_new == kNegInf ? 0.f : m_new;
+    float alpha, pr[8];
+    if (FP8) {
+      alpha = fast_exp2(m[nt] - m_safe);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
+    } else {
+      const float mc = m_safe * c;
+      alpha = fast_exp2(m[nt] * c - mc);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, -mc));
+    }
+    m[nt] = m_new;
+    if (!__all(alpha == 1.0f)) {
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] *= alpha;
+      lacc[nt] *= alpha;
+    }
+    u32x4 pw;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pr[2 * i], pr[2 * i + 1]}, f16x2));
+    const f16x8 ph = __builtin_bit_cast(f16x8, pw);
+    lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, ph, lacc[nt], 0, 0, 0);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+      o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh[dt], ph, o[nt][dt], 0, 0, 0);
+  }
+}
+
+// Normalise and store the finished rows of one wavefront.  As in finish_rows the tile goes through
+// a wave-private LDS area so that every store instruction writes whole 4 * D byte rows.
+template <int D, int NT>
+__device__ __forceinline__ void walk_write_rows(float *out, float *lse, const Shape &sh, int g, int rows,
+                                                f32x4 (&o)[NT][D / 16], const float (&m_log2)[NT],
+                                                const f32x4 (&lacc)[NT], const int (&qtok)[NT], float *my) {
+  constexpr int kRowPad = D + 4;
+  constexpr int kLanesPerRow = D / 4;
+  constexpr int kRowsPerInst = 64 / kLanesPerRow;
+  const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
+  const int sub = lane / kLanesPerRow, piece = lane % kLanesPerRow;
+  const int G = sh.G;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int r0w = nt * 16;
+    if (r0w >= rows) break;  // wave-uniform
+    const bool row_ok = r0w + m16 < rows;
+    const float l = lacc[nt][0];
+    const float inv = 1.0f / l;
+    const int64_t dst_row = static_cast<int64_t>(qtok[nt]) * sh.Hq + g * G + (r0w + m16) % G;
+    if (row_ok && jj == 0 && lse) lse[dst_row] = (m_log2[nt] + __builtin_log2f(l)) * 0.6931471805599453f;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+      *reinterpret_cast<f32x4 *>(my + m16 * kRowPad + dt * 16 + jj * 4) = o[nt][dt] * inv;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 16 / kRowsPerInst; ++i) {
+      const int row = i * kRowsPerInst + sub;
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(my + row * kRowPad + piece * 4);
+      const int lo32 = __shfl(static_cast<int>(dst_row & 0xffffffff), row);
+      const int hi32 = __shfl(static_cast<int>(dst_row >> 32), row);
+      const int64_t drow = (static_cast<int64_t>(hi32) << 32) | static_cast<uint32_t>(lo32);
+      if (r0w + row < rows) *reinterpret_cast<f32x4 *>(out + drow * D + piece * 4) = v;
+    }
+  }
+}
+
+template <int KV, int D, int NTW>
+__global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(WalkArgs p, Shape sh) {
+  constexpr bool FP8 = KV == kFP8;
+  constexpr int ESZ = FP8 ? 1 : 2;
+  constexpr int TILE_BYTES = 16 * D * ESZ;
+  constexpr int C = 16 * NTW;              // rows per wavefront
+  constexpr int NKI = 2 * (D / 32);        // K operand images per block
+  constexpr int NI = NKI + D / 16;         // all operand images per block (1 KiB each)
+  constexpr int RAW = FP8 ? NI / 2 : NI;   // 1 KiB global loads per block
+  constexpr int RK = FP8 ? NKI / 2 : NKI;  // of which K
+  constexpr int PER = RAW / 4;             // global loads per wavefront and block in phase 1
+  static_assert(RAW % 4 == 0, "block must split evenly over four wavefronts");
+  constexpr int kImgFloats = NI * 64 * 4;
+  constexpr int kLdsFloats =
+      2 * kImgFloats > 4 * stage_floats<D>() ? 2 * kImgFloats : 4 * stage_floats<D>();
+  __shared__ __attribute__((aligned(16))) float lds[kLdsFloats];
+  u32x4 *img = reinterpret_cast<u32x4 *>(lds);  // [buf][image][lane]
+
+  const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
+  const int w = uniform(threadIdx.x >> 6);
+  const int64_t ir = static_cast<int64_t>(blockIdx.x) * 16;
+  const int g = sload(p.items, ir + 0);
+  const int blk_begin = sload(p.items, ir + 1);
+  const int n_shared = sload(p.items, ir + 2);
+  const int np0 = sload(p.items, ir + 3), np1 = sload(p.items, ir + 4), np2 = sload(p.items, ir + 5),
+            np3 = sload(p.items, ir + 6);
+  if (n_shared + np0 + np1 + np2 + np3 == 0) return;  // padding item (whole workgroup)
+  const int n_priv = w == 0 ? np0 : (w == 1 ? np1 : (w == 2 ? np2 : np3));
+  const int priv_begin =
+      blk_begin + n_shared + (w > 0 ? np0 : 0) + (w > 1 ? np1 : 0) + (w > 2 ? np2 : 0);
+  const int qt_begin = sload(p.items, ir + 7 + w);
+  const int qt_count = sload(p.items, ir + 11 + w);
+  const int rows = qt_count * sh.G;
+  const bool has_rows = rows > 0;
+  const char *kpool = static_cast<const char *>(p.k_pool);
+  const char *vpool = static_cast<const char *>(p.v_pool);
+  const int k_lane_off = jj * 128 + (m16 & 7) * 16;
+  const int v_lane_off = (jj & 1) * 256 + m16 * 16;
+
+  // ---- rows of this wavefront
+  bf16x8 qf[NTW][D / 32];
+  int limit[NTW], qtok[NTW];
+  f32x4 o[NTW][D / 16], lacc[NTW];
+  float m[NTW];
+#pragma unroll
+  for (int nt = 0; nt < NTW; ++nt) {
+    const int r = nt * 16 + m16;
+    limit[nt] = INT_MAX;
+    qtok[nt] = 0;
+    m[nt] = kNegInf;
+    lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (r < rows) {
+      const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (qt_begin + r / sh.G));
+      qtok[nt] = qr.x;
+      limit[nt] = qr.y;
+      const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
+                           (static_cast<int64_t>(qr.x) * sh.Hq + g * sh.G + r % sh.G) * D + jj * 8;
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s)
+        qf[nt][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(qp + s * 32));
+    } else {
+#pragma unroll
+      for (int s = 0; s < D / 32; ++s) qf[nt][s] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    }
+  }
+
+  // ---- phase 1: blocks shared by several wavefronts, through LDS
+  if (n_shared > 0) {
+    struct Raw {
+      u32x4 r[PER];
+      float vs;
+    };
+    auto stage_load = [&](Raw &rw, const WalkBlock &bm) {
+      const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
+      const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
+      const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
+      const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int idx = k * 4 + w;  // wave-uniform
+        const char *src = idx < RK ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
+                                   : vp + (idx - RK) * 512;
+        rw.r[k] = load_kv(src);
+      }
+      if (FP8) {
+        const float va = sload_f(p.v_scale, static_cast<int64_t>(bm.pid_a) * sh.Hkv + g);
+        const float vb = sload_f(p.v_scale, static_cast<int64_t>(bm.pid_b) * sh.Hkv + g);
+        rw.vs = jj < 2 ? va : vb;
+      } else {
+        rw.vs = 1.f;
+      }
+    };
+    auto stage_store = [&](const Raw &rw, int buf) {
+      u32x4 *dst = img + buf * (NI * 64) + lane;
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int idx = k * 4 + w;
+        if (FP8) {
+          if (idx < RK) {
+            dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][0], rw.r[k][1]));
+            dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][2], rw.r[k][3]));
+          } else {
+            dst[(2 * idx) * 64] = fp8x8_to_f16x8(rw.r[k][0], rw.r[k][1], rw.vs);
+            dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(rw.r[k][2], rw.r[k][3], rw.vs);
+          }
+        } else {
+          dst[idx * 64] = idx < RK ? rw.r[k] : bf16x8_to_f16x8(rw.r[k]);
+        }
+      }
+    };
+    auto compute = [&](int b, const WalkBlock &bm) {
+      const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
+      if (!has_rows || hi <= 0 || lo >= C) return;  // wave-uniform: none of this wavefront's rows
+      const u32x4 *src = img + (b & 1) * (NI * 64) + lane;
+      bf16x8 kf[2][D / 32];
+      f16x8 vh[D / 16];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s)
+          kf[t][s] = __builtin_bit_cast(bf16x8, src[(t * (D / 32) + s) * 64]);
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
+      float c = p.scale_log2;
+      if (FP8) {
+        const float ka = sload_f(p.k_scale, static_cast<int64_t>(bm.pid_a) * sh.Hkv + g);
+        const float kb = sload_f(p.k_scale, static_cast<int64_t>(bm.pid_b) * sh.Hkv + g);
+        c *= jj < 2 ? ka : kb;
+      }
+      f32x4 sa[NTW], sb[NTW];
+      walk_scores<D, NTW>(qf, kf, lo, hi, sa, sb);
+      walk_softmax_pv<FP8, D, NTW>(limit, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
+                                   (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
+                                   c, lo, hi);
+    };
+    auto meta = [&](int b) { return load_walk_block(p.blocks, blk_begin + (b < n_shared ? b : n_shared - 1)); };
+
+    Raw x;
+    WalkBlock bm = meta(0);
+    stage_load(x, bm);
+    stage_store(x, 0);
+    __syncthreads();
+    for (int b = 0; b < n_shared; ++b) {
+      const bool more = b + 1 < n_shared;  // uniform over the workgroup
+      const WalkBlock nbm = meta(b + 1);
+      if (more) stage_load(x, nbm);
+      compute(b, bm);
+      if (more) stage_store(x, (b + 1) & 1);
+      bm = nbm;
+      __syncthreads();
+    }
+  }
+
+  // ---- phase 2: blocks of this wavefront alone, straight into registers
+  if (has_rows && n_priv > 0) {
+    constexpr int NK = FP8 ? D / 64 : D / 32;  // 128-bit loads per K half-tile
+    constexpr int NV = FP8 ? D / 32 : D / 16;
+    u32x4 kr[2][NK], vr[NV];
+    auto issue_k = [&](const WalkBlock &bm) {
+      const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
+      const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
+      const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < NK; ++s) kr[t][s] = load_kv(kp + t * (TILE_BYTES / 2) + s * 512);
+    };
+    auto issue_v = [&](const WalkBlock &bm) {
+      const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
+      const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
+      const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
+#pragma unroll
+      for (int s = 0; s < NV; ++s) vr[s] = load_kv(vp + s * 512);
+    };
+    // One block: scores from the K registers, which are then refilled with the next block's K
+    // while the softmax runs; the V registers are refilled after the PV product.
+    auto step = [&](const WalkBlock &bm, const WalkBlock &nxt, bool more) {
+      const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
+      float c = p.scale_log2, vs = 1.f;
+      if (FP8) {
+        const int64_t sa_i = static_cast<int64_t>(bm.pid_a) * sh.Hkv + g, sb_i = static_cast<int64_t>(bm.pid_b) * sh.Hkv + g;
+        const float ka = sload_f(p.k_scale, sa_i), kb = sload_f(p.k_scale, sb_i);
+        const float va = sload_f(p.v_scale, sa_i), vb = sload_f(p.v_scale, sb_i);
+        c *= jj < 2 ? ka : kb;
+        vs = jj < 2 ? va : vb;
+      }
+      bf16x8 kf[2][D / 32];
+      if (FP8) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int s = 0; s < D / 64; ++s) {
+            kf[t][2 * s] = fp8x8_to_bf16x8(kr[t][s][0], kr[t][s][1]);
+            kf[t][2 * s + 1] = fp8x8_to_bf16x8(kr[t][s][2], kr[t][s][3]);
+          }
+      } else {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int s = 0; s < D / 32; ++s) kf[t][s] = __builtin_bit_cast(bf16x8, kr[t][s]);
+      }
+      f32x4 sa[NTW], sb[NTW];
+      walk_scores<D, NTW>(qf, kf, lo, hi, sa, sb);
+      if (more) issue_k(nxt);
+      f16x8 vh[D / 16];
+      if (FP8) {
+#pragma unroll
+        for (int s = 0; s < D / 32; ++s) {
+          vh[2 * s] = __builtin_bit_cast(f16x8, fp8x8_to_f16x8(vr[s][0], vr[s][1], vs));
+          vh[2 * s + 1] = __builtin_bit_cast(f16x8, fp8x8_to_f16x8(vr[s][2], vr[s][3], vs));
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) vh[s] = __builtin_bit_cast(f16x8, bf16x8_to_f16x8(vr[s]));
+      }
+      if (more) issue_v(nxt);
+      walk_softmax_pv<FP8, D, NTW>(limit, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
+                                   (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
+                                   c, lo, hi);
+    };
+    WalkBlock cur = load_walk_block(p.blocks, priv_begin);
+    issue_k(cur);
+    issue_v(cur);
+    for (int i = 0; i + 1 < n_priv; ++i) {
+      const WalkBlock nxt = load_walk_block(p.blocks, priv_begin + i + 1);
+      step(cur, nxt, true);
+      cur = nxt;
+    }
+    step(cur, cur, false);
+  }
+
+  // ---- output.  The LDS images are dead after the last barrier of phase 1.
+  if (has_rows) {
+    float m_log2[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) m_log2[nt] = FP8 ? m[nt] : m[nt] * p.scale_log2;
+    walk_write_rows<D, NTW>(p.out, p.lse, sh, g, rows, o, m_log2, lacc, qtok, lds + w * stage_floats<D>());
+  }
+}
+
 // ---- generic attention (no matrix cores) ------------------------------------------------------
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
@@ -1036,6 +1432,28 @@ hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipSt
                       : launch_coop_ntw<kBF16, 128>(sh, a, ntw, stream);
   return sh.D == 64 ? launch_coop_ntw<kFP8, 64>(sh, a, ntw, stream)
                     : launch_coop_ntw<kFP8, 128>(sh, a, ntw, stream);
+}
+
+template <int KV, int D>
+static hipError_t launch_walk_ntw(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream) {
+  const dim3 grid(a.n_items), block(256);
+  if (ntw == 1)
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 1>), grid, block, 0, stream, a, sh);
+  else if (ntw == 2)
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 2>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 4>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream) {
+  if (a.n_items <= 0) return hipSuccess;
+  if (!has_mfma_kernel(sh) || (ntw != 1 && ntw != 2 && ntw != 4)) return hipErrorInvalidValue;
+  if (sh.kv_dtype == kBF16)
+    return sh.D == 64 ? launch_walk_ntw<kBF16, 64>(sh, a, ntw, stream)
+                      : launch_walk_ntw<kBF16, 128>(sh, a, ntw, stream);
+  return sh.D == 64 ? launch_walk_ntw<kFP8, 64>(sh, a, ntw, stream)
+                    : launch_walk_ntw<kFP8, 128>(sh, a, ntw, stream);
 }
 
 hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream) {

@@ -37,6 +37,23 @@ struct AttnArgs {
   float scale_log2;
 };
 
+// Tree-walk kernel: one workgroup per work item.
+struct WalkArgs {
+  const void *k_pool, *v_pool;
+  const float *k_scale, *v_scale;
+  const void *q;
+  const int32_t *items;   // 16 ints per workgroup: {kv head, first block, shared blocks, private
+                          //   blocks of wavefronts 0..3, first qt_rec entry of wavefronts 0..3,
+                          //   qt_rec entries of wavefronts 0..3, row block}; no blocks = padding
+  int32_t n_items;
+  const int32_t *blocks;  // 8 ints per 32-token block: {page a, pos_a << 7 | valid_a, page b,
+                          //   pos_b << 7 | valid_b (0: no page b), first row | (last row + 1) << 16
+                          //   within the row block, flags (bit 0: token mask needed), 0, 0}
+  const int32_t *qt_rec;  // 2 ints per row-set entry: {query token, visible path length}
+  float *out, *lse;       // lse may be null
+  float scale_log2;
+};
+
 struct MergeArgs {
   const int32_t *part_indptr, *part_base, *part_hstride;
   const float *part_o, *part_ml;
@@ -78,5 +95,7 @@ bool has_mfma_kernel(const Shape &sh);
 // Cooperative shared-prefix kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront (64 * ntw rows
 // per workgroup).  One work item per workgroup.  Only for shapes with has_mfma_kernel().
 hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream);
+// Tree-walk kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront the lists were built for.
+hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream);
 
 }  // namespace spex

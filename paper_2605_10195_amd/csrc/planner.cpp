@@ -24,7 +24,8 @@ struct Segment {
 
 PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
                          int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
-                         int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, Plan *plan) {
+                         int32_t prefix_chunk_pages, int32_t suffix_chunk_pages,
+                         int32_t walk_row_tiles, Plan *plan) {
   if (n_leaves < 0 || (n_leaves > 0 && !leaves)) return PlanError::kInvalid;
   const int32_t P = pt.page_size();
   const int32_t G = num_q_heads / num_kv_heads;
@@ -36,6 +37,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
   pl.table_version = pt.version();
   pl.req_prefix_chunk = prefix_chunk_pages;
   pl.req_suffix_chunk = suffix_chunk_pages;
+  pl.req_walk_row_tiles = walk_row_tiles;
 
   if (static_cast<int32_t>(live_.size()) < N) {
     live_.resize(N, 0);
@@ -297,8 +299,242 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     pl.qt_rec[2 * i] = pl.qt_list[i];
     pl.qt_rec[2 * i + 1] = pl.qt_limit[pl.qt_list[i]];
   }
+  build_walk(pt, q_lens, n_leaves, G, num_kv_heads, walk_row_tiles, path_indptr, path_nodes, qoff, plan);
   pl.valid = true;
   return PlanError::kOk;
+}
+
+// Tree-walk lists: the whole path of a set of query rows is handled by one workgroup, which keeps
+// the rows' softmax state in registers from the root to the requested nodes, so nothing is
+// written but the output.  Rules (they fix the result uniquely):
+//  * request i has q_len_i * G rows; C = 16 * NTW rows fit one wavefront.  NTW is the value asked
+//    for (1, 2 or 4) or, if 0, the smallest of {1, 2, 4} with max rows <= 16 * NTW, raised to 2 when
+//    that is 1 and some root has more than 64 rows below it.  No lists (walk_ok = false) if some
+//    request has more rows than 16 * NTW.
+//  * roots in order of first appearance in the request list; the requests of a root sorted by
+//    path (node ids root first, lexicographic, a proper prefix first), ties in request order;
+//    so the requests below any node are consecutive.
+//  * packing: a request joins the current wavefront if its rows still fit, else it starts the
+//    next one; a fifth wavefront, or a new root, starts a new row block.  walk_qt lists
+//    {query token, limit} of the requests in this order.  Wavefronts without requests have
+//    first entry 0 and count 0.  Row of a request in its row block: wavefront * C + rows before
+//    it in the wavefront.
+//  * nodes of a row block: the nodes with >= 1 token on its requests' paths, in order of first
+//    encounter (requests in order, each path root first), each with the row range
+//    [first row of the first request through it, last row + 1 of the last request through it)
+//    and minlim = min over those requests of T - q_len + 1.  A node whose range touches two
+//    wavefronts is shared, else it is private to wavefront lo / C.
+//  * blocks of a row block: its shared nodes in encounter order, then the private nodes of
+//    wavefront 0, 1, 2, 3; a node's pages two at a time (the last block of an odd run has no
+//    page b).  Flag bit 0: page a or b partial, or no page b, or minlim smaller than the path
+//    position after the block's last token.
+//  * launch order: roots by descending number of blocks in their row blocks (stable).  With
+//    lanes = 8 / Hkv for Hkv in {1, 2, 4}, else 1, every root in that order goes to the lane with the
+//    fewest blocks so far (lowest index on ties) and appends its row blocks to it; round r emits,
+//    for lane 0, 1, ..: the lane's r-th row block, or padding if the lane has run out and more
+//    than one lane exists; each for kv head 0 .. Hkv-1.  Workgroup b runs on XCD b % 8, so the row
+//    blocks of one root and kv head follow each other on one XCD and share its L2.
+void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_leaves, int32_t G,
+                         int32_t num_kv_heads, int32_t walk_row_tiles,
+                         const std::vector<int32_t> &path_indptr,
+                         const std::vector<int32_t> &path_nodes, const std::vector<int32_t> &qoff,
+                         Plan *plan) {
+  Plan &pl = *plan;
+  pl.walk_ok = false;
+  pl.walk_row_tiles = 0;
+  if (n_leaves == 0) return;
+  const int32_t P = pt.page_size();
+  const int32_t N = pt.num_nodes();
+  if (static_cast<int32_t>(stamp_.size()) < N) {
+    stamp_.resize(N, 0);
+    slot_.resize(N, 0);
+  }
+  auto fresh = [&]() {
+    if (stamp_next_ == std::numeric_limits<int32_t>::max()) {
+      std::fill(stamp_.begin(), stamp_.end(), 0);
+      stamp_next_ = 1;
+    }
+    return stamp_next_++;
+  };
+  auto rows_of = [&](int32_t i) { return (q_lens ? q_lens[i] : 1) * G; };
+
+  int32_t max_rows = 0;
+  std::vector<int32_t> root_of(n_leaves), root_ids;
+  std::vector<int64_t> root_rows;
+  {
+    const int32_t st = fresh();
+    for (int32_t i = 0; i < n_leaves; ++i) {
+      max_rows = std::max(max_rows, rows_of(i));
+      const int32_t r = path_nodes[path_indptr[i]];
+      if (stamp_[r] != st) {
+        stamp_[r] = st;
+        slot_[r] = static_cast<int32_t>(root_ids.size());
+        root_ids.push_back(r);
+        root_rows.push_back(0);
+      }
+      root_of[i] = slot_[r];
+      root_rows[slot_[r]] += rows_of(i);
+    }
+  }
+  int32_t ntw = walk_row_tiles;
+  if (ntw == 0) {
+    if (max_rows > 64) return;
+    ntw = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
+    if (ntw == 1 && *std::max_element(root_rows.begin(), root_rows.end()) > 64) ntw = 2;
+  } else if (max_rows > 16 * ntw) {
+    return;
+  }
+  pl.walk_row_tiles = ntw;
+  const int32_t C = 16 * ntw;
+
+  std::vector<int32_t> order(n_leaves);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+    if (root_of[a] != root_of[b]) return root_of[a] < root_of[b];
+    const int32_t la = path_indptr[a + 1] - path_indptr[a], lb = path_indptr[b + 1] - path_indptr[b];
+    const int32_t *pa = path_nodes.data() + path_indptr[a], *pb = path_nodes.data() + path_indptr[b];
+    for (int32_t k = 0; k < la && k < lb; ++k)
+      if (pa[k] != pb[k]) return pa[k] < pb[k];
+    return la < lb;
+  });
+
+  struct Placed { int32_t req, row0; };
+  struct NodeRange { int32_t node, lo, hi, minlim; };
+  std::vector<Placed> cur;
+  std::vector<NodeRange> nodes;
+  std::vector<int64_t> rb_blocks;           // blocks per row block
+  std::vector<std::vector<int32_t>> rbs_of_root(root_ids.size());
+  int32_t rb_rec[Plan::kRbInts];
+  auto start_rb = [&](int32_t root_slot) {
+    for (int &x : rb_rec) x = 0;
+    rb_rec[0] = root_ids[root_slot];
+    cur.clear();
+  };
+  auto emit_node = [&](const NodeRange &nr) -> int32_t {
+    const Node &nd = pt.node(nr.node);
+    const int32_t n = static_cast<int32_t>(nd.pages.size());
+    int32_t made = 0;
+    for (int32_t k = 0; k < n; k += 2, ++made) {
+      const bool has_b = k + 1 < n;
+      const int32_t va = pt.page_valid(nr.node, k);
+      const int32_t vb = has_b ? pt.page_valid(nr.node, k + 1) : 0;
+      const int32_t pos_a = pos0_[nr.node] + k * P, pos_b = pos_a + P;
+      const int32_t end = has_b ? pos_b + vb : pos_a + va;
+      const bool masked = va != P || !has_b || vb != P || nr.minlim < end;
+      const int32_t rec[Plan::kBlockInts] = {nd.pages[k],
+                                             (pos_a << 7) | va,
+                                             has_b ? nd.pages[k + 1] : nd.pages[k],
+                                             has_b ? ((pos_b << 7) | vb) : 0,
+                                             nr.lo | (nr.hi << 16),
+                                             masked ? 1 : 0,
+                                             0,
+                                             0};
+      pl.walk_blocks.insert(pl.walk_blocks.end(), rec, rec + Plan::kBlockInts);
+    }
+    return made;
+  };
+  auto flush = [&](int32_t root_slot) {
+    if (cur.empty()) return;
+    const int32_t st = fresh();
+    nodes.clear();
+    for (const Placed &pc : cur) {
+      const int32_t i = pc.req, rows = rows_of(i), minlim = pl.qt_limit[qoff[i]];
+      for (int32_t k = path_indptr[i]; k < path_indptr[i + 1]; ++k) {
+        const int32_t u = path_nodes[k];
+        if (pt.node(u).n_tokens == 0) continue;
+        if (stamp_[u] != st) {
+          stamp_[u] = st;
+          slot_[u] = static_cast<int32_t>(nodes.size());
+          nodes.push_back({u, pc.row0, pc.row0 + rows, minlim});
+        } else {
+          NodeRange &nr = nodes[slot_[u]];
+          nr.hi = pc.row0 + rows;
+          nr.minlim = std::min(nr.minlim, minlim);
+        }
+      }
+    }
+    rb_rec[1] = static_cast<int32_t>(pl.walk_blocks.size() / Plan::kBlockInts);
+    int64_t total = 0;
+    for (const NodeRange &nr : nodes)
+      if (nr.lo / C != (nr.hi - 1) / C) rb_rec[2] += emit_node(nr);
+    total += rb_rec[2];
+    for (int32_t w = 0; w < 4; ++w) {
+      for (const NodeRange &nr : nodes)
+        if (nr.lo / C == (nr.hi - 1) / C && nr.lo / C == w) rb_rec[3 + w] += emit_node(nr);
+      total += rb_rec[3 + w];
+    }
+    rbs_of_root[root_slot].push_back(static_cast<int32_t>(pl.walk_rb.size() / Plan::kRbInts));
+    pl.walk_rb.insert(pl.walk_rb.end(), rb_rec, rb_rec + Plan::kRbInts);
+    rb_blocks.push_back(total);
+    pl.walk_block_visits += total;
+    pl.walk_max_item_blocks = std::max<int32_t>(pl.walk_max_item_blocks, static_cast<int32_t>(total));
+  };
+
+  int32_t wave = 0, used = 0, cur_root = -1;
+  for (int32_t idx : order) {
+    const int32_t rows = rows_of(idx), ql = q_lens ? q_lens[idx] : 1;
+    if (root_of[idx] != cur_root) {
+      if (cur_root >= 0) flush(cur_root);
+      cur_root = root_of[idx];
+      start_rb(cur_root);
+      wave = used = 0;
+    } else if (used + rows > C) {
+      ++wave;
+      used = 0;
+      if (wave == 4) {
+        flush(cur_root);
+        start_rb(cur_root);
+        wave = 0;
+      }
+    }
+    if (rb_rec[11 + wave] == 0) rb_rec[7 + wave] = static_cast<int32_t>(pl.walk_qt.size() / 2);
+    for (int32_t j = 0; j < ql; ++j) {
+      pl.walk_qt.push_back(qoff[idx] + j);
+      pl.walk_qt.push_back(pl.qt_limit[qoff[idx] + j]);
+    }
+    rb_rec[11 + wave] += ql;
+    cur.push_back({idx, wave * C + used});
+    used += rows;
+  }
+  flush(cur_root);
+
+  // ---- launch order
+  const int32_t n_roots = static_cast<int32_t>(root_ids.size());
+  std::vector<int64_t> root_blocks(n_roots, 0);
+  for (int32_t r = 0; r < n_roots; ++r)
+    for (int32_t rb : rbs_of_root[r]) root_blocks[r] += rb_blocks[rb];
+  std::vector<int32_t> root_order(n_roots);
+  std::iota(root_order.begin(), root_order.end(), 0);
+  std::stable_sort(root_order.begin(), root_order.end(),
+                   [&](int32_t a, int32_t b) { return root_blocks[a] > root_blocks[b]; });
+  const int32_t lanes = (num_kv_heads == 1 || num_kv_heads == 2 || num_kv_heads == 4) ? 8 / num_kv_heads : 1;
+  std::vector<std::vector<int32_t>> lane_rbs(lanes);
+  std::vector<int64_t> lane_load(lanes, 0);
+  for (int32_t r : root_order) {
+    int32_t best = 0;
+    for (int32_t l = 1; l < lanes; ++l)
+      if (lane_load[l] < lane_load[best]) best = l;
+    lane_rbs[best].insert(lane_rbs[best].end(), rbs_of_root[r].begin(), rbs_of_root[r].end());
+    lane_load[best] += root_blocks[r];
+  }
+  size_t rounds = 0;
+  for (const auto &v : lane_rbs) rounds = std::max(rounds, v.size());
+  for (size_t r = 0; r < rounds; ++r)
+    for (int32_t l = 0; l < lanes; ++l) {
+      const bool real = r < lane_rbs[l].size();
+      if (!real && lanes == 1) continue;
+      for (int32_t g = 0; g < num_kv_heads; ++g) {
+        int32_t rec[Plan::kWalkItemInts] = {g, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, -1};
+        if (real) {
+          const int32_t rb = lane_rbs[l][r];
+          for (int k = 1; k < Plan::kRbInts; ++k) rec[k] = pl.walk_rb[static_cast<size_t>(rb) * Plan::kRbInts + k];
+          rec[15] = rb;
+          ++pl.walk_real_items;
+        }
+        pl.walk_items.insert(pl.walk_items.end(), rec, rec + Plan::kWalkItemInts);
+      }
+    }
+  pl.walk_ok = true;
 }
 
 }  // namespace spex

@@ -56,6 +56,28 @@ struct Plan {
   int32_t prefix_row_tiles = 1, suffix_row_tiles = 1;  // 16-row MFMA tiles per wavefront
   int32_t max_rows_prefix = 0, max_rows_suffix = 0;
   int64_t prefix_tokens = 0, suffix_tokens = 0;        // distinct KV tokens per kind
+
+  // ---- tree-walk lists (see the rules above build_walk in planner.cpp)
+  bool walk_ok = false;         // every requested node's rows fit one wavefront
+  int32_t walk_row_tiles = 0;   // 16-row tiles per wavefront (1, 2 or 4)
+  int32_t req_walk_row_tiles = -1;
+  // row blocks: kRbInts ints each
+  //   {root node, first block, shared blocks, private blocks of wavefronts 0..3,
+  //    first walk_qt entry of wavefronts 0..3, walk_qt entries of wavefronts 0..3}
+  static constexpr int kRbInts = 15;
+  std::vector<int32_t> walk_rb;
+  // blocks: kBlockInts ints each {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b
+  //   (0: no page b), first row | (last row + 1) << 16, flags (bit 0: token mask needed), 0, 0}
+  static constexpr int kBlockInts = 8;
+  std::vector<int32_t> walk_blocks;
+  std::vector<int32_t> walk_qt;     // {query token, limit} in row order
+  // launch order: kWalkItemInts ints per workgroup {kv head, first block, shared blocks,
+  //   private blocks[4], walk_qt first[4], walk_qt count[4], row block index}; a padding item has
+  //   row block index -1 and no blocks
+  static constexpr int kWalkItemInts = 16;
+  std::vector<int32_t> walk_items;
+  int32_t walk_real_items = 0, walk_max_item_blocks = 0;
+  int64_t walk_block_visits = 0;  // blocks over all row blocks (a block shared by two row blocks counts twice)
 };
 
 enum class PlanError { kOk, kBadNode, kEmptyPath, kInvalid, kTooLarge };
@@ -64,9 +86,16 @@ class Planner {
  public:
   PlanError build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
                   int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
-                  int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, Plan *plan);
+                  int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, int32_t walk_row_tiles,
+                  Plan *plan);
 
  private:
+  void build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_leaves, int32_t G,
+                  int32_t num_kv_heads, int32_t walk_row_tiles,
+                  const std::vector<int32_t> &path_indptr, const std::vector<int32_t> &path_nodes,
+                  const std::vector<int32_t> &qoff, Plan *plan);
+  std::vector<int32_t> stamp_, slot_;  // per-node scratch of build_walk, valid where stamp_ == current stamp
+  int32_t stamp_next_ = 1;
   // dense per-node scratch, reset through touched_
   std::vector<int32_t> live_, pos0_, gindex_, touched_;
 };

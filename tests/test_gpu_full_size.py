@@ -14,13 +14,13 @@ from gpu_common import assert_close, run_oracle
 pytestmark = pytest.mark.gpu
 
 
-def run_full(wl):
+def run_full(wl, mode):
     import paper_2605_10195_amd as spex
     n_pages = wl.peak_pages()
     order = np.random.default_rng(1000).permutation(n_pages).tolist()
     tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
                          wl.kv_dtype, num_pages=n_pages, device="cuda", free_order=order,
-                         interleave_kv=True)
+                         interleave_kv=True, kernel_mode=mode)
     sw.replay(wl, tree, device="cuda")
     q = sw.gen_queries(wl, device="cuda")
     out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
@@ -37,26 +37,33 @@ def sample_rows(wl, picks):
     return [wl.leaves[i] for i in picks], [wl.q_lens[i] for i in picks], rows
 
 
+MODES = [0, 2]      # automatic (the tree-walk kernel at these sizes) and shared-prefix + suffix + merge
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name", ["bfs_tot", "mcts_skewed"])
-def test_full_config_every_output(name):
+def test_full_config_every_output(name, mode):
     wl = sw.WORKLOADS[name]()
-    (out, lse), info = run_full(wl)
+    (out, lse), info = run_full(wl, mode)
+    assert (info["walk_row_tiles"] > 0) == (mode == 0)
     assert info["kv_tokens"] == wl.unique_kv_tokens()          # every shared page planned once
     max_abs, rel = assert_close((out, lse), run_oracle(wl), wl.kv_dtype, name)
-    print(f"{name}: max_abs={max_abs:.2e} rel_l2={rel:.2e}")
+    print(f"{name} mode {mode}: max_abs={max_abs:.2e} rel_l2={rel:.2e}")
 
 
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("name,n_sample", [("spec_at_scale", 96), ("tot_with_drafts", 48)])
-def test_full_config_sampled_outputs(name, n_sample):
+def test_full_config_sampled_outputs(name, n_sample, mode):
     wl = sw.WORKLOADS[name]()
-    (out, lse), info = run_full(wl)
+    (out, lse), info = run_full(wl, mode)
+    assert (info["walk_row_tiles"] > 0) == (mode == 0)
     assert info["kv_tokens"] == wl.unique_kv_tokens()
     assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
     picks = np.sort(np.random.default_rng(7).choice(len(wl.leaves), size=n_sample, replace=False)).tolist()
     leaves, q_lens, rows = sample_rows(wl, picks)
     ref = run_oracle(wl, leaves, q_lens, rows)
     max_abs, rel = assert_close((out[rows], lse[rows]), ref, wl.kv_dtype, name)
-    print(f"{name}: {n_sample} branches sampled, max_abs={max_abs:.2e} rel_l2={rel:.2e}")
+    print(f"{name} mode {mode}: {n_sample} branches sampled, max_abs={max_abs:.2e} rel_l2={rel:.2e}")
     # a property that holds at any size: rows of one requested node differ only through their
     # queries, so identical query vectors would give identical rows; here: outputs stay inside the
     # value range of the inputs (a convex combination of V rows with |v| <= 0.5 * 4.9)

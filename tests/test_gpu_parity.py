@@ -100,8 +100,48 @@ def test_random_trees_match_oracle(case, chunks):
                          q_dtype="f32" if case["kv_dtype"] == "f32" else "bf16",
                          n_ops=70, max_tokens=90, max_q_len=case["max_q_len"])
     ref = run_oracle(wl)
-    got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1])
+    got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1], kernel_mode=2)
     assert_close(got, ref, case["kv_dtype"], wl.name)
+
+
+def walk_applies(wl, row_tiles=0):
+    rows = max(wl.q_lens) * (wl.num_q_heads // wl.num_kv_heads)
+    mfma = wl.kv_dtype != "f32" and wl.head_dim in (64, 128)
+    return mfma and rows <= (16 * row_tiles if row_tiles else 64)
+
+
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")
+@pytest.mark.parametrize("row_tiles", [0, 1, 2, 4])
+def test_random_trees_tree_walk_kernel(case, row_tiles):
+    import paper_2605_10195_amd as spex
+    wl = sw.random_trace(case["seed"], heads=case["heads"], kv_dtype=case["kv_dtype"],
+                         q_dtype="f32" if case["kv_dtype"] == "f32" else "bf16",
+                         n_ops=70, max_tokens=90, max_q_len=case["max_q_len"])
+    if not walk_applies(wl, row_tiles):
+        with pytest.raises(spex.SpexError) as e:
+            run_gpu(wl, kernel_mode=3, walk_row_tiles=row_tiles)
+        assert e.value.name == "UNSUPPORTED"
+        return
+    tree = build_gpu_tree(wl, kernel_mode=3, walk_row_tiles=row_tiles)
+    got = run_gpu(wl, tree=tree)
+    info = tree.last_launch_info()
+    tree.close()
+    assert info["walk_row_tiles"] == (row_tiles or info["walk_row_tiles"]) and info["walk_row_tiles"] > 0
+    assert_close(got, run_oracle(wl), case["kv_dtype"], wl.name)
+
+
+def test_automatic_mode_picks_the_tree_walk_kernel_for_short_paths():
+    wl = sw.random_trace(42, heads=(8, 2, 128), kv_dtype="bf16", n_ops=70, max_tokens=90, max_q_len=4)
+    tree = build_gpu_tree(wl)
+    got = run_gpu(wl, tree=tree)
+    assert tree.last_launch_info()["walk_row_tiles"] > 0
+    tree.set_tuning(0, 0, 2, 0)
+    split = run_gpu(wl, tree=tree)
+    assert tree.last_launch_info()["walk_row_tiles"] == 0
+    tree.close()
+    ref = run_oracle(wl)
+    assert_close(got, ref, "bf16", "walk")
+    assert_close(split, ref, "bf16", "split")
 
 
 @pytest.mark.parametrize("case", RANDOM_CASES[:6], ids=lambda c: f"{c['kv_dtype']}-{c['heads']}")
@@ -110,10 +150,11 @@ def test_generic_kernels_match_oracle_and_mfma(case):
                          n_ops=60, max_tokens=70, max_q_len=case["max_q_len"])
     ref = run_oracle(wl)
     slow = run_gpu(wl, kernel_mode=1)
-    fast = run_gpu(wl, kernel_mode=0)
     assert_close(slow, ref, case["kv_dtype"], "generic")
-    assert_close(fast, ref, case["kv_dtype"], "mfma")
-    assert np.max(np.abs(slow[0] - fast[0])) < 1e-3
+    for mode in (2, 3):
+        fast = run_gpu(wl, kernel_mode=mode)
+        assert_close(fast, ref, case["kv_dtype"], f"mfma mode {mode}")
+        assert np.max(np.abs(slow[0] - fast[0])) < 1e-3
 
 
 REDUCED = [
@@ -126,26 +167,30 @@ REDUCED = [
 
 
 @pytest.mark.parametrize("wl", REDUCED, ids=lambda w: w.name + "_" + w.kv_dtype)
-def test_reduced_config_shapes_match_oracle(wl):
-    assert_close(run_gpu(wl), run_oracle(wl), wl.kv_dtype, wl.name)
+@pytest.mark.parametrize("mode", [2, 3])
+def test_reduced_config_shapes_match_oracle(wl, mode):
+    assert_close(run_gpu(wl, kernel_mode=mode), run_oracle(wl), wl.kv_dtype, f"{wl.name} mode {mode}")
 
 
 def test_nan_poisoned_pool_and_ragged_pages():
     # 0xFF bytes are NaN in bf16 and in e4m3: unused slots of partial pages must never contribute.
     for kv in ("bf16", "fp8_e4m3"):
         wl = sw.random_trace(51, heads=(8, 2, 128), kv_dtype=kv, n_ops=60, max_tokens=37, max_q_len=3)
-        got = run_gpu(wl, pool_fill=0xFF, extra_pages=7)
-        assert_close(got, run_oracle(wl), kv, "poisoned " + kv)
+        ref = run_oracle(wl)
+        for mode in (2, 3):
+            got = run_gpu(wl, pool_fill=0xFF, extra_pages=7, kernel_mode=mode)
+            assert_close(got, ref, kv, f"poisoned {kv} mode {mode}")
 
 
 def test_page_placement_does_not_change_the_result():
     wl = sw.random_trace(52, heads=(8, 2, 128), kv_dtype="bf16", n_ops=60, max_tokens=80, max_q_len=2)
-    base = run_gpu(wl)
     n = wl.peak_pages() + 11
-    for s in range(3):
-        order = np.random.default_rng(s).permutation(n).tolist()
-        other = run_gpu(wl, free_order=order, extra_pages=11)
-        assert np.array_equal(base[0], other[0]) and np.array_equal(base[1], other[1])
+    for mode in (2, 3):
+        base = run_gpu(wl, kernel_mode=mode)
+        for s in range(3):
+            order = np.random.default_rng(s).permutation(n).tolist()
+            other = run_gpu(wl, free_order=order, extra_pages=11, kernel_mode=mode)
+            assert np.array_equal(base[0], other[0]) and np.array_equal(base[1], other[1])
 
 
 def test_identical_token_paths_give_identical_outputs():
@@ -162,9 +207,10 @@ def test_identical_token_paths_give_identical_outputs():
     b.append(c2, 30, key=99)
     b.request(c1, 3, key=5)
     b.request(c2, 3, key=5)
-    out, lse = run_gpu(wl)
-    assert np.array_equal(out[:3], out[3:]) and np.array_equal(lse[:3], lse[3:])
-    assert_close((out, lse), run_oracle(wl), "bf16", "twins")
+    for mode in (2, 3):
+        out, lse = run_gpu(wl, kernel_mode=mode)
+        assert np.array_equal(out[:3], out[3:]) and np.array_equal(lse[:3], lse[3:])
+        assert_close((out, lse), run_oracle(wl), "bf16", "twins")
 
 
 def test_duplicate_interior_and_empty_requests():
@@ -178,7 +224,8 @@ def test_duplicate_interior_and_empty_requests():
     b.request(a, 7)          # same node again; 7 queries reach 2 tokens into the shared root
     b.request(root, 2)       # interior node
     b.request(e, 1)          # empty child: sees exactly the root
-    assert_close(run_gpu(wl), run_oracle(wl), "bf16", wl.name)
+    for mode in (2, 3):
+        assert_close(run_gpu(wl, kernel_mode=mode), run_oracle(wl), "bf16", f"{wl.name} mode {mode}")
 
 
 def test_decode_loop_replans_after_every_append():
@@ -239,10 +286,10 @@ WIDE = [
 
 
 @pytest.mark.parametrize("wl", WIDE, ids=lambda w: f"{w.name}_{w.kv_dtype}_{w.num_q_heads}")
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [2, 1, 3])
 def test_wide_groups_match_oracle(wl, mode):
     ref = run_oracle(wl)
-    for chunks in ((0, 0), (3, 2)):
+    for chunks in ((0, 0), (3, 2)) if mode != 3 else ((0, 0),):
         got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1], kernel_mode=mode)
         assert_close(got, ref, wl.kv_dtype, f"{wl.name} mode {mode} chunks {chunks}")
 

@@ -76,7 +76,7 @@ PLAN_KEYS = ["leaf_indptr", "leaf_pages", "leaf_valid", "qt_limit", "group_node"
 
 
 def assert_same_plan(tree, ref, wl, pc, sc):
-    tree.set_tuning(pc, sc, 0)
+    tree.set_tuning(pc, sc, 0, 0)
     got = tree.plan_dump(wl.leaves, wl.q_lens)
     want = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
                     got["prefix_chunk_pages"], got["suffix_chunk_pages"])
@@ -184,3 +184,123 @@ def test_plan_is_cached_until_the_tree_changes():
                     p2["prefix_chunk_pages"], p2["suffix_chunk_pages"])
     for k in PLAN_KEYS:
         assert p2[k] == want[k], k
+
+
+# ------------------------------------------------------------------ tree-walk lists
+WALK_KEYS = ["available", "row_tiles", "row_blocks", "blocks", "qt", "items"]
+
+
+def check_walk_lists(tree, ref, wl, row_tiles):
+    """Bit-exact against the reference model, and -- independently of both -- every row of every
+    row block meets every page of its path exactly once, with the right positions and masks."""
+    tree.set_tuning(0, 0, 0, row_tiles)
+    got = tree.walk_dump(wl.leaves, wl.q_lens)
+    want = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, row_tiles)
+    for k in WALK_KEYS:
+        assert got[k] == want[k], k
+    G = wl.num_q_heads // wl.num_kv_heads
+    q_lens = wl.q_lens if wl.q_lens is not None else [1] * len(wl.leaves)
+    if not got["available"]:
+        assert max(q * G for q in q_lens) > (16 * row_tiles if row_tiles else 64)
+        return got
+    C = 16 * got["row_tiles"]
+    rbs = np.array(got["row_blocks"]).reshape(-1, 15)
+    blocks = np.array(got["blocks"]).reshape(-1, 8)
+    qt = np.array(got["qt"]).reshape(-1, 2)
+    qoff = np.concatenate([[0], np.cumsum(q_lens)])
+    tok_owner = np.repeat(np.arange(len(wl.leaves)), q_lens)        # query token -> request
+    seen_tokens = []
+    used_blocks = np.zeros(len(blocks), dtype=bool)
+    for rb in rbs:
+        first, n_sh, n_pr = rb[1], rb[2], rb[3:7]
+        spans = [(first, first + n_sh, None)]
+        b0 = first + n_sh
+        for w in range(4):
+            spans.append((b0, b0 + n_pr[w], w))
+            b0 += n_pr[w]
+        # rows of the row block: row -> (query token, limit)
+        row_tok = {}
+        for w in range(4):
+            for e in range(rb[11 + w]):
+                t, lim = qt[rb[7 + w] + e]
+                assert lim == ref_limit(ref, wl, tok_owner[t], t - qoff[tok_owner[t]], q_lens)
+                for hh in range(G):
+                    row_tok[w * C + e * G + hh] = (t, lim)
+                seen_tokens.append(t)
+            assert rb[11 + w] * G <= C
+        pages_of_row = {r: [] for r in row_tok}
+        for a, b, wave in spans:
+            for blk in blocks[a:b]:
+                lo, hi = blk[4] & 0xffff, blk[4] >> 16
+                assert lo < hi
+                if wave is None:
+                    assert lo // C != (hi - 1) // C                 # really shared by >= 2 wavefronts
+                else:
+                    assert lo // C == wave and (hi - 1) // C == wave
+                entries = [(blk[0], blk[1] >> 7, blk[1] & 127)]
+                if blk[3]:
+                    entries.append((blk[2], blk[3] >> 7, blk[3] & 127))
+                    assert (blk[1] & 127) == 16
+                end = entries[-1][1] + entries[-1][2]
+                need_mask = len(entries) == 1 or any(v != 16 for _, _, v in entries)
+                for r, (t, lim) in row_tok.items():
+                    if lo <= r < hi:
+                        pages_of_row[r] += entries
+                        need_mask = need_mask or lim < end
+                assert (blk[5] & 1) or not need_mask               # a needed mask is never dropped
+            used_blocks[a:b] = True
+        for r, (t, lim) in row_tok.items():
+            pages, valid = ref.path_pages(wl.leaves[tok_owner[t]])
+            pos = np.concatenate([[0], np.cumsum(valid)])[:-1]
+            want_entries = sorted((p, int(s), v) for p, s, v in zip(pages, pos, valid) if v > 0)
+            assert sorted(pages_of_row[r]) == want_entries, (r, t)
+    assert sorted(seen_tokens) == list(range(qoff[-1]))            # every query token in one row block
+    assert used_blocks.all()
+    items = np.array(got["items"]).reshape(-1, 16)
+    real = items[items[:, 15] >= 0]
+    assert len(real) == len(rbs) * wl.num_kv_heads
+    for g in range(wl.num_kv_heads):
+        assert sorted(real[real[:, 0] == g][:, 15].tolist()) == list(range(len(rbs)))
+    for it in real:
+        assert it[1:15].tolist() == rbs[it[15]][1:15].tolist()
+    assert (items[items[:, 15] < 0][:, 1:15] == 0).all()
+    return got
+
+
+def ref_limit(ref, wl, req, j, q_lens):
+    T = sum(ref.tokens[w] for w in ref.path(wl.leaves[req]))
+    return T - q_lens[req] + 1 + j
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_walk_lists_random_traces(seed):
+    wl = sw.random_trace(500 + seed, n_ops=80, max_tokens=70, max_q_len=[1, 4, 9][seed % 3],
+                         heads=[(8, 2, 64), (6, 6, 32), (28, 4, 128), (8, 1, 128)][seed % 4])
+    n_pages = wl.peak_pages()
+    order = np.random.default_rng(seed).permutation(n_pages).tolist()
+    tree, ref = host_tree(wl, n_pages, order), PageTableRef(n_pages, 16, order)
+    replay_both(wl, tree, ref)
+    for rt in (0, 1, 2, 4):
+        check_walk_lists(tree, ref, wl, rt)
+
+
+@pytest.mark.parametrize("wl", [
+    sw.bfs_tot(n_queries=3), sw.mcts_skewed(n_queries=6), sw.spec_at_scale(n_queries=4),
+    sw.tot_with_drafts(n_queries=3)], ids=lambda w: w.name)
+def test_walk_lists_config_shapes(wl):
+    n_pages = wl.peak_pages()
+    tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
+    replay_both(wl, tree, ref)
+    got = check_walk_lists(tree, ref, wl, 0)
+    assert got["available"] == 1
+    for rt in (1, 2, 4):
+        check_walk_lists(tree, ref, wl, rt)
+
+
+def test_walk_lists_not_available_for_wide_requests():
+    wl = sw.random_trace(77, n_ops=30, max_tokens=90, max_q_len=9, heads=(16, 2, 64))   # up to 72 rows
+    tree, ref = host_tree(wl, wl.peak_pages()), PageTableRef(wl.peak_pages(), 16)
+    replay_both(wl, tree, ref)
+    assert max(wl.q_lens) * 8 > 64
+    got = tree.walk_dump(wl.leaves, wl.q_lens)
+    assert got["available"] == 0 and got["items"] == []
