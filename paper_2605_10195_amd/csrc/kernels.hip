@@ -44,6 +44,27 @@ __device__ __forceinline__ int sload(const int32_t *base, int64_t idx) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Maximum over lanes l, l^16, l^32, l^48 (the four lane groups that hold one query row), by the
+// gfx950 row-swap instructions: v_permlane16_swap exchanges the odd 16-lane rows of its first
+// operand with the even rows of its second, v_permlane32_swap the upper half of the first with
+// the lower half of the second; with both operands equal, the pair afterwards holds the value of
+// the lane and of its partner.  Two wait states separate a vector write from a swap that reads it.
+// The compiler does not track hazards of instructions inside inline assembly, so the argument must
+// be the result of an ordinary vector ALU instruction -- never of an MFMA, whose results need many
+// more wait states before they can be read.
+__device__ __forceinline__ float row_group_max(float v) {
+  float a = v, b = v;
+  asm("s_nop 1\n\t"
+      "v_permlane16_swap_b32 %0, %1\n\t"
+      "v_max_f32 %0, %0, %1\n\t"
+      "v_mov_b32 %1, %0\n\t"
+      "s_nop 1\n\t"
+      "v_permlane32_swap_b32 %0, %1\n\t"
+      "v_max_f32 %0, %0, %1"
+      : "+v"(a), "+v"(b));
+  return a;
+}
+
 // 128-bit K/V load.  Every K/V byte is used once per launch, so the loads carry the non-temporal
 // hint: measured on MI355X, a streaming read of the pool reaches 7.0 TB/s with it against
 // 6.2 TB/s without (the lines do not displace each other in the last-level caches).
@@ -818,11 +839,12 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&
   for (int nt = 0; nt < NT; ++nt) {
     if (nt * 16 >= hi || nt * 16 + 16 <= lo) continue;  // wave-uniform
     const bool partial_tile = lo > nt * 16 || hi < nt * 16 + 16;
-    float x[8];
+    float x[8];  // scores in units of log2(e): the products are also what makes the maxima below
+                 // plain vector ALU results (see row_group_max)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      x[i] = FP8 ? sa[nt][i] * c : sa[nt][i];
-      x[4 + i] = FP8 ? sb[nt][i] * c : sb[nt][i];
+      x[i] = sa[nt][i] * c;
+      x[4 + i] = sb[nt][i] * c;
     }
     if (tok_masked || partial_tile) {
       int vis = limit[nt] - pos_l;
@@ -833,23 +855,15 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&
 #pragma unroll
       for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
     }
-    float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                     fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m[nt], mx);
+    const float mx8 = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                            fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    const float mx = row_group_max(fmaxf(mx8, m[nt]));
+    const float m_new = mx;  // includes the running maximum
     const float m_safe = m_new == kNegInf ? 0.f : m_new;
-    float alpha, pr[8];
-    if (FP8) {
-      alpha = fast_exp2(m[nt] - m_safe);
+    float pr[8];
+    const float alpha = fast_exp2(m[nt] - m_safe);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
-    } else {
-      const float mc = m_safe * c;
-      alpha = fast_exp2(m[nt] * c - mc);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, -mc));
-    }
+    for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
     m[nt] = m_new;
     if (!__all(alpha == 1.0f)) {
 #pragma unroll
@@ -1024,15 +1038,6 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
       const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
       if (!has_rows || hi <= 0 || lo >= C) return;  // wave-uniform: none of this wavefront's rows
       const u32x4 *src = img + (b & 1) * (NI * 64) + lane;
-      bf16x8 kf[2][D / 32];
-      f16x8 vh[D / 16];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int s = 0; s < D / 32; ++s)
-          kf[t][s] = __builtin_bit_cast(bf16x8, src[(t * (D / 32) + s) * 64]);
-#pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
       float c = p.scale_log2;
       if (FP8) {
         const float ka = sload_f(p.k_scale, static_cast<int64_t>(bm.pid_a) * sh.Hkv + g);
@@ -1040,26 +1045,51 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
         c *= jj < 2 ? ka : kb;
       }
       f32x4 sa[NTW], sb[NTW];
-      walk_scores<D, NTW>(qf, kf, lo, hi, sa, sb);
+      {
+        bf16x8 kf[2][D / 32];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int s = 0; s < D / 32; ++s)
+            kf[t][s] = __builtin_bit_cast(bf16x8, src[(t * (D / 32) + s) * 64]);
+        walk_scores<D, NTW>(qf, kf, lo, hi, sa, sb);
+      }
+      // The V images are fetched only now, into the registers the K images have left, and their
+      // LDS latency passes under the softmax arithmetic.
+      __builtin_amdgcn_sched_barrier(0);
+      f16x8 vh[D / 16];
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
       walk_softmax_pv<FP8, D, NTW>(limit, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
                                    c, lo, hi);
     };
     auto meta = [&](int b) { return load_walk_block(p.blocks, blk_begin + (b < n_shared ? b : n_shared - 1)); };
 
-    Raw x;
-    WalkBlock bm = meta(0);
-    stage_load(x, bm);
-    stage_store(x, 0);
+    // Software pipeline, two blocks deep: while block b is computed from one LDS buffer, block
+    // b+1 is already in registers (requested an iteration earlier) and moves to the other LDS
+    // buffer after the computation, and the global loads of block b+2 are in flight.  The loads
+    // are unconditional (indices past the end repeat the last block) because a load issued on
+    // one path only would make every later wait a wait for all outstanding loads.
+    Raw x0, x1;
+    WalkBlock bm0 = meta(0), bm1 = meta(1);
+    stage_load(x0, bm0);
+    stage_load(x1, bm1);
+    stage_store(x0, 0);
     __syncthreads();
-    for (int b = 0; b < n_shared; ++b) {
-      const bool more = b + 1 < n_shared;  // uniform over the workgroup
-      const WalkBlock nbm = meta(b + 1);
-      if (more) stage_load(x, nbm);
-      compute(b, bm);
-      if (more) stage_store(x, (b + 1) & 1);
-      bm = nbm;
+    for (int b = 0; b < n_shared; b += 2) {
+      const WalkBlock bm2 = meta(b + 2), bm3 = meta(b + 3);
+      stage_load(x0, bm2);
+      compute(b, bm0);
+      if (b + 1 < n_shared) stage_store(x1, 1);
       __syncthreads();
+      if (b + 1 >= n_shared) break;
+      stage_load(x1, bm3);
+      compute(b + 1, bm1);
+      if (b + 2 < n_shared) stage_store(x0, 0);
+      __syncthreads();
+      bm0 = bm2;
+      bm1 = bm3;
     }
   }
 
@@ -1145,7 +1175,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
   if (has_rows) {
     float m_log2[NTW];
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) m_log2[nt] = FP8 ? m[nt] : m[nt] * p.scale_log2;
+    for (int nt = 0; nt < NTW; ++nt) m_log2[nt] = m[nt];
     walk_write_rows<D, NTW>(p.out, p.lse, sh, g, rows, o, m_log2, lacc, qtok, lds + w * stage_floats<D>());
   }
 }
