@@ -258,7 +258,8 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages
  *     holds the node.  A row block's blocks: first the nodes whose rows touch several
  *     wavefronts, then those of wavefront 0, 1, 2, 3 alone; every page of every row's path
  *     appears exactly once per row block.  Flag bit 0: a page is partial or missing, or some
- *     row in the range sees fewer positions than the block ends at.
+ *     row in the range sees fewer positions than the block ends at.  Flag bit 1: the node is
+ *     also on the paths of another row block.
  *   items[16 * n_items]: launch order, one workgroup each: {kv head, copy of row block fields
  *     1..14, row block index}; index -1 = padding that keeps the row blocks of one root on one
  *     XCD when fewer than 8 kv heads exist.

@@ -70,7 +70,8 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
   * blocks of a row block: shared nodes first, then the private nodes of
     wavefront 0..3, a node's pages two at a time; record (page a, pos_a << 7 |
     valid_a, page b or a again, pos_b << 7 | valid_b or 0, lo | hi << 16, flag, 0,
-    0); flag = a page partial or missing, or minlim < position after the block;
+    0); flag bit 0 = a page partial or missing, or minlim < position after the
+    block; flag bit 1 = the node lies on paths of more than one row block;
   * launch order: roots by descending block count (stable); lanes = 8 // Hkv for
     Hkv in (1, 2, 4) else 1; each root goes to the lane with the fewest blocks so
     far; round r emits for every lane its r-th row block (padding if it ran out
@@ -367,8 +368,25 @@ class PageTableRef:
         rb_total: List[int] = []
         rbs_of_root: Dict[int, List[int]] = {r: [] for r in roots}
 
+        # row block of every request (same packing as below), then the nodes met by several
+        rb_of, rb, cur_root, wave, used = {}, -1, None, 0, 0
+        for i in order:
+            if paths[i][0] != cur_root:
+                cur_root, rb, wave, used = paths[i][0], rb + 1, 0, 0
+            elif used + rows[i] > C:
+                wave, used = wave + 1, 0
+                if wave == 4:
+                    rb, wave = rb + 1, 0
+            used += rows[i]
+            rb_of[i] = rb
+        rbs_through: Dict[int, set] = {}
+        for i in order:
+            for w in paths[i]:
+                rbs_through.setdefault(w, set()).add(rb_of[i])
+
         def node_blocks(u, lo, hi, minlim):
             out = []
+            multi = 2 if len(rbs_through[u]) > 1 else 0
             pages, valid = self.pages[u], self.node_page_valid(u)
             for k in range(0, len(pages), 2):
                 has_b = k + 1 < len(pages)
@@ -378,7 +396,7 @@ class PageTableRef:
                 end = pos_b + vb if has_b else pos_a + va
                 masked = va != P or not has_b or vb != P or minlim < end
                 out.append([pages[k], (pos_a << 7) | va, pages[k + 1] if has_b else pages[k],
-                            ((pos_b << 7) | vb) if has_b else 0, lo | (hi << 16), int(masked), 0, 0])
+                            ((pos_b << 7) | vb) if has_b else 0, lo | (hi << 16), int(masked) | multi, 0, 0])
             return out
 
         def flush(root, placed, qt_first, qt_count):

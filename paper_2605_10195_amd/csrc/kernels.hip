@@ -996,6 +996,9 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
       u32x4 r[PER];
       float vs;
     };
+    // A block that another row block reads too (flag bit 1) is loaded with the ordinary cache
+    // policy, so that the second reader finds it in the L2 of the XCD both run on; everything
+    // else is streamed.
     auto stage_load = [&](Raw &rw, const WalkBlock &bm) {
       const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
       const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
@@ -1006,7 +1009,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
         const int idx = k * 4 + w;  // wave-uniform
         const char *src = idx < RK ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
                                    : vp + (idx - RK) * 512;
-        rw.r[k] = load_kv(src);
+        rw.r[k] = (bm.flags & 2) ? *reinterpret_cast<const u32x4 *>(src) : load_kv(src);
       }
       if (FP8) {
         const float va = sload_f(p.v_scale, static_cast<int64_t>(bm.pid_a) * sh.Hkv + g);

@@ -327,7 +327,8 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
 //  * blocks of a row block: its shared nodes in encounter order, then the private nodes of
 //    wavefront 0, 1, 2, 3; a node's pages two at a time (the last block of an odd run has no
 //    page b).  Flag bit 0: page a or b partial, or no page b, or minlim smaller than the path
-//    position after the block's last token.
+//    position after the block's last token.  Flag bit 1: the node lies on paths of more than one
+//    row block (its pages are fetched again by another workgroup and are worth keeping cached).
 //  * launch order: roots by descending number of blocks in their row blocks (stable).  With
 //    lanes = 8 / Hkv for Hkv in {1, 2, 4}, else 1, every root in that order goes to the lane with the
 //    fewest blocks so far (lowest index on ties) and appends its row blocks to it; round r emits,
@@ -398,6 +399,39 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
     return la < lb;
   });
 
+  // Nodes that lie on paths of more than one row block (same packing as below, counted first).
+  if (static_cast<int32_t>(multi_.size()) < N) multi_.resize(N, 0);
+  const int32_t st_multi = fresh();
+  {
+    const int32_t st_seen = fresh();
+    int32_t wave = 0, used = 0, cur_root = -1, rb = -1;
+    for (int32_t idx : order) {
+      const int32_t rows = rows_of(idx);
+      if (root_of[idx] != cur_root) {
+        cur_root = root_of[idx];
+        ++rb;
+        wave = used = 0;
+      } else if (used + rows > C) {
+        ++wave;
+        used = 0;
+        if (wave == 4) {
+          ++rb;
+          wave = 0;
+        }
+      }
+      used += rows;
+      for (int32_t k = path_indptr[idx]; k < path_indptr[idx + 1]; ++k) {
+        const int32_t u = path_nodes[k];
+        if (stamp_[u] != st_seen) {
+          stamp_[u] = st_seen;
+          slot_[u] = rb;
+        } else if (slot_[u] != rb) {
+          multi_[u] = st_multi;
+        }
+      }
+    }
+  }
+
   struct Placed { int32_t req, row0; };
   struct NodeRange { int32_t node, lo, hi, minlim; };
   std::vector<Placed> cur;
@@ -426,7 +460,7 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
                                              has_b ? nd.pages[k + 1] : nd.pages[k],
                                              has_b ? ((pos_b << 7) | vb) : 0,
                                              nr.lo | (nr.hi << 16),
-                                             masked ? 1 : 0,
+                                             (masked ? 1 : 0) | (multi_[nr.node] == st_multi ? 2 : 0),
                                              0,
                                              0};
       pl.walk_blocks.insert(pl.walk_blocks.end(), rec, rec + Plan::kBlockInts);

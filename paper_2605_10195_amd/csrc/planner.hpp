@@ -67,7 +67,8 @@ struct Plan {
   static constexpr int kRbInts = 15;
   std::vector<int32_t> walk_rb;
   // blocks: kBlockInts ints each {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b
-  //   (0: no page b), first row | (last row + 1) << 16, flags (bit 0: token mask needed), 0, 0}
+  //   (0: no page b), first row | (last row + 1) << 16, flags (bit 0: token mask needed, bit 1:
+  //   node shared with another row block), 0, 0}
   static constexpr int kBlockInts = 8;
   std::vector<int32_t> walk_blocks;
   std::vector<int32_t> walk_qt;     // {query token, limit} in row order
@@ -94,6 +95,7 @@ class Planner {
                   int32_t num_kv_heads, int32_t walk_row_tiles,
                   const std::vector<int32_t> &path_indptr, const std::vector<int32_t> &path_nodes,
                   const std::vector<int32_t> &qoff, Plan *plan);
+  std::vector<int32_t> multi_;
   std::vector<int32_t> stamp_, slot_;  // per-node scratch of build_walk, valid where stamp_ == current stamp
   int32_t stamp_next_ = 1;
   // dense per-node scratch, reset through touched_

@@ -211,6 +211,13 @@ def check_walk_lists(tree, ref, wl, row_tiles):
     tok_owner = np.repeat(np.arange(len(wl.leaves)), q_lens)        # query token -> request
     seen_tokens = []
     used_blocks = np.zeros(len(blocks), dtype=bool)
+    rbs_of_page = {}                                              # page -> row blocks that list it
+    for bi, rb in enumerate(rbs):
+        for blk in blocks[rb[1]:rb[1] + rb[2] + rb[3:7].sum()]:
+            for pg in {int(blk[0]), int(blk[2])}:
+                rbs_of_page.setdefault(pg, set()).add(bi)
+    for blk in blocks:                                            # flag bit 1: shared between row blocks
+        assert bool(blk[5] & 2) == (len(rbs_of_page[int(blk[0])]) > 1)
     for rb in rbs:
         first, n_sh, n_pr = rb[1], rb[2], rb[3:7]
         spans = [(first, first + n_sh, None)]
