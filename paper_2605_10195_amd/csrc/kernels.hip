@@ -786,23 +786,37 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
 // from the first block to the last, so the only global writes are the finished output rows.
 struct WalkBlock {
   int pid_a, vp_a, pid_b, vp_b, rows, flags;
+  float ka, kb, va, vb;  // fp8: K and V scales of pages a and b for the item's kv head; else unused
 };
-
-__device__ __forceinline__ WalkBlock load_walk_block(const int32_t *blocks, int idx) {
-  const int64_t r = static_cast<int64_t>(uniform(idx)) * 8;
-  WalkBlock b;
-  b.pid_a = sload(blocks, r + 0);
-  b.vp_a = sload(blocks, r + 1);
-  b.pid_b = sload(blocks, r + 2);
-  b.vp_b = sload(blocks, r + 3);
-  b.rows = sload(blocks, r + 4);
-  b.flags = sload(blocks, r + 5);
-  return b;
-}
 
 __device__ __forceinline__ float sload_f(const float *base, int64_t idx) {
   typedef const float __attribute__((address_space(4))) const_f32;
   return ((const_f32 *)(uintptr_t)base)[idx];
+}
+
+// The record of a block and, for fp8, the page scales it will need.  All of it goes through the
+// scalar path and is requested one or two blocks before its use, so its latency (a miss in the
+// scalar cache goes to memory) stays off the critical path.
+template <bool FP8>
+__device__ __forceinline__ WalkBlock load_walk_block(const WalkArgs &p, int idx, int g, int Hkv) {
+  const int64_t r = static_cast<int64_t>(uniform(idx)) * 8;
+  WalkBlock b;
+  b.pid_a = sload(p.blocks, r + 0);
+  b.vp_a = sload(p.blocks, r + 1);
+  b.pid_b = sload(p.blocks, r + 2);
+  b.vp_b = sload(p.blocks, r + 3);
+  b.rows = sload(p.blocks, r + 4);
+  b.flags = sload(p.blocks, r + 5);
+  if (FP8) {
+    const int64_t ia = static_cast<int64_t>(b.pid_a) * Hkv + g, ib = static_cast<int64_t>(b.pid_b) * Hkv + g;
+    b.ka = sload_f(p.k_scale, ia);
+    b.kb = sload_f(p.k_scale, ib);
+    b.va = sload_f(p.v_scale, ia);
+    b.vb = sload_f(p.v_scale, ib);
+  } else {
+    b.ka = b.kb = b.va = b.vb = 1.f;
+  }
+  return b;
 }
 
 // Scores of one 32-token block for the row tiles that intersect the wave-relative row range
@@ -1011,13 +1025,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
                                    : vp + (idx - RK) * 512;
         rw.r[k] = (bm.flags & 2) ? *reinterpret_cast<const u32x4 *>(src) : load_kv(src);
       }
-      if (FP8) {
-        const float va = sload_f(p.v_scale, static_cast<int64_t>(bm.pid_a) * sh.Hkv + g);
-        const float vb = sload_f(p.v_scale, static_cast<int64_t>(bm.pid_b) * sh.Hkv + g);
-        rw.vs = jj < 2 ? va : vb;
-      } else {
-        rw.vs = 1.f;
-      }
+      rw.vs = jj < 2 ? bm.va : bm.vb;
     };
     auto stage_store = [&](const Raw &rw, int buf) {
       u32x4 *dst = img + buf * (NI * 64) + lane;
@@ -1041,12 +1049,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
       const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
       if (!has_rows || hi <= 0 || lo >= C) return;  // wave-uniform: none of this wavefront's rows
       const u32x4 *src = img + (b & 1) * (NI * 64) + lane;
-      float c = p.scale_log2;
-      if (FP8) {
-        const float ka = sload_f(p.k_scale, static_cast<int64_t>(bm.pid_a) * sh.Hkv + g);
-        const float kb = sload_f(p.k_scale, static_cast<int64_t>(bm.pid_b) * sh.Hkv + g);
-        c *= jj < 2 ? ka : kb;
-      }
+      const float c = p.scale_log2 * (jj < 2 ? bm.ka : bm.kb);
       f32x4 sa[NTW], sb[NTW];
       {
         bf16x8 kf[2][D / 32];
@@ -1067,7 +1070,9 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
                                    c, lo, hi);
     };
-    auto meta = [&](int b) { return load_walk_block(p.blocks, blk_begin + (b < n_shared ? b : n_shared - 1)); };
+    auto meta = [&](int b) {
+      return load_walk_block<FP8>(p, blk_begin + (b < n_shared ? b : n_shared - 1), g, sh.Hkv);
+    };
 
     // Software pipeline, two blocks deep: while block b is computed from one LDS buffer, block
     // b+1 is already in registers (requested an iteration earlier) and moves to the other LDS
@@ -1121,14 +1126,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
     // while the softmax runs; the V registers are refilled after the PV product.
     auto step = [&](const WalkBlock &bm, const WalkBlock &nxt, bool more) {
       const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
-      float c = p.scale_log2, vs = 1.f;
-      if (FP8) {
-        const int64_t sa_i = static_cast<int64_t>(bm.pid_a) * sh.Hkv + g, sb_i = static_cast<int64_t>(bm.pid_b) * sh.Hkv + g;
-        const float ka = sload_f(p.k_scale, sa_i), kb = sload_f(p.k_scale, sb_i);
-        const float va = sload_f(p.v_scale, sa_i), vb = sload_f(p.v_scale, sb_i);
-        c *= jj < 2 ? ka : kb;
-        vs = jj < 2 ? va : vb;
-      }
+      const float c = p.scale_log2 * (jj < 2 ? bm.ka : bm.kb), vs = jj < 2 ? bm.va : bm.vb;
       bf16x8 kf[2][D / 32];
       if (FP8) {
 #pragma unroll
@@ -1163,13 +1161,17 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
                                    c, lo, hi);
     };
-    WalkBlock cur = load_walk_block(p.blocks, priv_begin);
+    const int priv_last = priv_begin + n_priv - 1;
+    WalkBlock cur = load_walk_block<FP8>(p, priv_begin, g, sh.Hkv);
+    WalkBlock nxt = load_walk_block<FP8>(p, priv_begin + 1 < priv_last ? priv_begin + 1 : priv_last, g, sh.Hkv);
     issue_k(cur);
     issue_v(cur);
     for (int i = 0; i + 1 < n_priv; ++i) {
-      const WalkBlock nxt = load_walk_block(p.blocks, priv_begin + i + 1);
+      const int i2 = priv_begin + i + 2;
+      const WalkBlock nxt2 = load_walk_block<FP8>(p, i2 < priv_last ? i2 : priv_last, g, sh.Hkv);
       step(cur, nxt, true);
       cur = nxt;
+      nxt = nxt2;
     }
     step(cur, cur, false);
   }
