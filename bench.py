@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--kernel-mode", type=int, default=0,
                     help="0 automatic, 2 shared-prefix + suffix + merge kernels, 3 tree-walk kernel")
     ap.add_argument("--walk-row-tiles", type=int, default=0)
+    ap.add_argument("--walk-waves", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true",
@@ -110,7 +111,7 @@ def main():
                              wl.kv_dtype, num_pages=n_pages, device=dev, free_order=order,
                              prefix_chunk_pages=args.prefix_chunk, suffix_chunk_pages=args.suffix_chunk,
                              interleave_kv=args.kv_pools == "interleaved", kernel_mode=args.kernel_mode,
-                             walk_row_tiles=args.walk_row_tiles)
+                             walk_row_tiles=args.walk_row_tiles, walk_waves=args.walk_waves)
         sw.replay(wl, tree, device=dev)
         trees.append(tree)
     q = sw.gen_queries(wl, device=dev)
@@ -196,7 +197,7 @@ def main():
             "tree_copies_rotated": copies, "page_placement": args.placement, "kv_pools": args.kv_pools,
             "prefix_chunk_pages": args.prefix_chunk, "suffix_chunk_pages": args.suffix_chunk,
             "kernels": "tree-walk" if walked else "shared-prefix + suffix + merge",
-            "walk_row_tiles": int(info["walk_row_tiles"]),
+            "walk_row_tiles": int(info["walk_row_tiles"]), "walk_waves": int(info["walk_waves"]),
         },
         "hbm_gbps_unique_kv": unique_bytes / (ms_per_step * 1e-3) / 1e9,
         "hbm_frac_unique_kv": unique_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,

@@ -94,6 +94,7 @@ typedef struct {
                                 v_pool = k_pool + num_kv_heads tiles interleaves K and V of a page
                                 in one buffer, so that a page's K and V share a 64 KiB region. */
   int32_t walk_row_tiles; /* tree-walk kernel: 16-row tiles per wavefront, 1 / 2 / 4; 0 = automatic */
+  int32_t walk_waves;     /* tree-walk kernel: wavefronts per workgroup, 4 / 8; 0 = 4 */
 } spex_config_t;
 
 /* Bytes each of k_pool and v_pool must hold for this config. */
@@ -160,12 +161,12 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  * The call flattens parent links into per-launch work lists, uploads them when the request or
  * the tree changed since the previous call, and enqueues the kernels on hip_stream without
  * waiting for them.  Two kernel sets compute the same result:
- *   tree-walk: one workgroup carries a block of up to 64 * walk_row_tiles query rows (requested
+ *   tree-walk: one workgroup carries a block of up to 16 * walk_row_tiles * walk_waves query rows (requested
  *     nodes that are neighbours in the tree) from the root to the requested nodes; pages shared
  *     by rows of several wavefronts are fetched once per workgroup, the softmax state stays in
  *     registers, only the output is written.  Needs MFMA-tiled pools and q_len * Hq / Hkv <= 64
  *     for every requested node.  Chosen automatically when it yields >= 128 workgroups or when
- *     every workgroup has at most 64 two-page blocks;
+ *     no wavefront has more than 64 two-page blocks to walk;
  *   shared-prefix + suffix + merge: every shared node is read once for all rows below it, private
  *     suffixes are split for parallelism, partial softmax states go through memory.  Any shape.
  * Consecutive calls on one handle must use one stream or be separated by a synchronisation,
@@ -236,36 +237,38 @@ spex_status_t spex_tree_gather_kv(spex_tree_t *tree, spex_node_t node, int32_t f
                                   void *k_out, void *v_out, float *k_scale_out, float *v_scale_out,
                                   void *hip_stream);
 
-/* Change the split granularities (0 = automatic), kernel_mode and walk_row_tiles after creation. */
+/* Change the split granularities (0 = automatic), kernel_mode, walk_row_tiles and walk_waves
+ * after creation. */
 spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages,
                                    int32_t suffix_chunk_pages, int32_t kernel_mode,
-                                   int32_t walk_row_tiles);
+                                   int32_t walk_row_tiles, int32_t walk_waves);
 
 /*
  * The tree-walk kernel's lists for a request (HOST arrays owned by the tree, valid until the next
  * call that plans or mutates it).  available = 0: some requested node has more rows than one
- * wavefront takes; the arrays are then empty.  With G = Hq / Hkv and C = 16 * row_tiles:
+ * wavefront takes; the arrays are then empty.  With G = Hq / Hkv, C = 16 * row_tiles rows per
+ * wavefront and NW = waves wavefronts per row block:
  *   qt[2 * n_qt]: {query token, visible path length} of the requested nodes, grouped by root
  *     (roots in order of first appearance) and sorted by path below a root, so that the requests
  *     below any node are consecutive.
- *   row_blocks[15 * n_row_blocks]: {root node, first block, shared blocks, private blocks of
- *     wavefronts 0..3, first qt entry of wavefronts 0..3, qt entries of wavefronts 0..3}.  Requests
- *     fill a wavefront while their q_len * G rows fit into C; a fifth wavefront or a new root
- *     starts a new row block.  Row of a request: wavefront * C + rows before it in the wavefront.
+ *   row_blocks[(3 + 3 * NW) * n_row_blocks]: {root node, first block, shared blocks, private
+ *     blocks of wavefronts 0..NW-1, first qt entry of each wavefront, qt entries of each
+ *     wavefront}.  Requests fill a wavefront while their q_len * G rows fit into C; wavefront NW
+ *     or a new root starts a new row block.  Row of a request: wavefront * C + rows before it in the wavefront.
  *   blocks[8 * n_blocks]: {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b (0 = no page
  *     b), first row | (last row + 1) << 16, flags, 0, 0}: two consecutive pages of one node on the
  *     row block's paths, the path position and valid tokens of each, and the rows whose path
  *     holds the node.  A row block's blocks: first the nodes whose rows touch several
- *     wavefronts, then those of wavefront 0, 1, 2, 3 alone; every page of every row's path
+ *     wavefronts, then those of wavefront 0, 1, .. alone; every page of every row's path
  *     appears exactly once per row block.  Flag bit 0: a page is partial or missing, or some
  *     row in the range sees fewer positions than the block ends at.  Flag bit 1: the node is
  *     also on the paths of another row block.
- *   items[16 * n_items]: launch order, one workgroup each: {kv head, copy of row block fields
- *     1..14, row block index}; index -1 = padding that keeps the row blocks of one root on one
- *     XCD when fewer than 8 kv heads exist.
+ *   items[S * n_items], S = 16 for NW = 4 and 32 for NW = 8: launch order, one workgroup each:
+ *     {kv head, copy of row block fields 1.., zeros, row block index in the last int}; index -1 =
+ *     padding that keeps the row blocks of one root on one XCD when fewer than 8 kv heads exist.
  */
 typedef struct {
-  int32_t available, row_tiles, n_row_blocks, n_blocks, n_qt, n_items;
+  int32_t available, row_tiles, waves, n_row_blocks, n_blocks, n_qt, n_items;
   const int32_t *row_blocks, *blocks, *qt, *items;
 } spex_walk_view_t;
 spex_status_t spex_tree_walk_dump(spex_tree_t *tree, const spex_node_t *leaves,
@@ -288,8 +291,8 @@ spex_status_t spex_tree_read_profile(spex_tree_t *tree, float *ms, int32_t cap, 
  * info[0] distinct KV tokens on the requested paths, [1] of which on nodes shared by >= 2 requested
  * nodes, [2] of which private, [6] 1 if the plan was rebuilt, [7] 0 = shared-prefix + suffix + merge
  * kernels ran ([3] prefix work items, [4] suffix work items, [5] partial rows), else the tree-walk
- * kernel ran with [7] row tiles per wavefront ([3] workgroups with work, [4] two-page blocks
- * summed over workgroups of one kv head, [5] 0). */
+ * kernel ran with [7] = row tiles per wavefront + 256 * wavefronts per workgroup ([3] workgroups
+ * with work, [4] two-page blocks summed over workgroups of one kv head, [5] 0). */
 spex_status_t spex_tree_last_launch_info(const spex_tree_t *tree, int64_t info[8]);
 
 #ifdef __cplusplus

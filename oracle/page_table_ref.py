@@ -58,8 +58,9 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
   * roots in order of first appearance; a root's requests sorted by path (node
     ids root first, lexicographic, a proper prefix first; ties in request
     order), so the requests below any node are consecutive;
+  * a row block has NW wavefronts: the value asked for (4, 8), 4 if 0;
   * a request joins the current wavefront while its rows fit, else starts the
-    next; a fifth wavefront or a new root starts a new row block; `qt` lists
+    next; wavefront NW or a new root starts a new row block; `qt` lists
     (query token, limit) of the requests in this order; the row of a request in
     its row block is wavefront * C + rows before it in the wavefront;
   * the nodes of a row block are the nodes with tokens on its requests' paths in
@@ -68,7 +69,7 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
     those requests; a node whose range touches two wavefronts is shared, else
     private to wavefront lo // C;
   * blocks of a row block: shared nodes first, then the private nodes of
-    wavefront 0..3, a node's pages two at a time; record (page a, pos_a << 7 |
+    wavefront 0..NW-1, a node's pages two at a time; record (page a, pos_a << 7 |
     valid_a, page b or a again, pos_b << 7 | valid_b or 0, lo | hi << 16, flag, 0,
     0); flag bit 0 = a page partial or missing, or minlim < position after the
     block; flag bit 1 = the node lies on paths of more than one row block;
@@ -323,14 +324,15 @@ class PageTableRef:
 
     # ---------------------------------------------------------------- tree-walk lists
     def walk_plan(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
-                  num_q_heads: int, num_kv_heads: int, row_tiles: int = 0) -> Dict[str, object]:
+                  num_q_heads: int, num_kv_heads: int, row_tiles: int = 0,
+                  waves: int = 0) -> Dict[str, object]:
         L = len(leaves)
         q_lens = [1] * L if q_lens is None else list(q_lens)
         G = num_q_heads // num_kv_heads
         P = self.P
         paths = [self.path(u) for u in leaves]
         rows = [ql * G for ql in q_lens]
-        none = dict(available=0, row_tiles=0, row_blocks=[], blocks=[], qt=[], items=[])
+        none = dict(available=0, row_tiles=0, waves=0, row_blocks=[], blocks=[], qt=[], items=[])
         if L == 0:
             return none
         qoff, limits = [], []
@@ -354,6 +356,7 @@ class PageTableRef:
         elif max(rows) > 16 * row_tiles:
             return dict(none, row_tiles=0)
         C = 16 * row_tiles
+        NW = waves if waves else 4
         pos0: Dict[int, int] = {}
         for path in paths:
             t = 0
@@ -375,7 +378,7 @@ class PageTableRef:
                 cur_root, rb, wave, used = paths[i][0], rb + 1, 0, 0
             elif used + rows[i] > C:
                 wave, used = wave + 1, 0
-                if wave == 4:
+                if wave == NW:
                     rb, wave = rb + 1, 0
             used += rows[i]
             rb_of[i] = rb
@@ -417,7 +420,7 @@ class PageTableRef:
                       for b in node_blocks(w, lo, hi, ml)]
             blocks.extend(shared)
             n_priv = []
-            for wv in range(4):
+            for wv in range(NW):
                 mine = [b for w, (lo, hi, ml) in nodes.items()
                         if lo // C == (hi - 1) // C and lo // C == wv for b in node_blocks(w, lo, hi, ml)]
                 blocks.extend(mine)
@@ -427,19 +430,19 @@ class PageTableRef:
             rb_total.append(len(shared) + sum(n_priv))
 
         cur_root, wave, used = None, 0, 0
-        placed, qt_first, qt_count = [], [0] * 4, [0] * 4
+        placed, qt_first, qt_count = [], [0] * NW, [0] * NW
         for i in order:
             root = paths[i][0]
             if root != cur_root:
                 flush(cur_root, placed, qt_first, qt_count)
                 cur_root, wave, used = root, 0, 0
-                placed, qt_first, qt_count = [], [0] * 4, [0] * 4
+                placed, qt_first, qt_count = [], [0] * NW, [0] * NW
             elif used + rows[i] > C:
                 wave, used = wave + 1, 0
-                if wave == 4:
+                if wave == NW:
                     flush(cur_root, placed, qt_first, qt_count)
                     wave = 0
-                    placed, qt_first, qt_count = [], [0] * 4, [0] * 4
+                    placed, qt_first, qt_count = [], [0] * NW, [0] * NW
             if qt_count[wave] == 0:
                 qt_first[wave] = len(qt) // 2
             for j in range(q_lens[i]):
@@ -465,11 +468,13 @@ class PageTableRef:
                 if not real and lanes == 1:
                     continue
                 for g in range(num_kv_heads):
+                    stride = 16 if NW == 4 else 32
                     if real:
                         rb = lane_rbs[l][r]
-                        items += [g] + row_blocks[rb][1:] + [rb]
+                        body = [g] + row_blocks[rb][1:]
+                        items += body + [0] * (stride - 1 - len(body)) + [rb]
                     else:
-                        items += [g] + [0] * 14 + [-1]
-        return dict(available=1, row_tiles=row_tiles,
+                        items += [g] + [0] * (stride - 2) + [-1]
+        return dict(available=1, row_tiles=row_tiles, waves=NW,
                     row_blocks=[x for rb in row_blocks for x in rb],
                     blocks=[x for b in blocks for x in b], qt=qt, items=items)

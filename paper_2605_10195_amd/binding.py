@@ -43,7 +43,7 @@ class Config(C.Structure):
         ("free_order", C.POINTER(C.c_int32)),
         ("prefix_chunk_pages", C.c_int32), ("suffix_chunk_pages", C.c_int32),
         ("kernel_mode", C.c_int32), ("page_stride_tiles", C.c_int32),
-        ("walk_row_tiles", C.c_int32),
+        ("walk_row_tiles", C.c_int32), ("walk_waves", C.c_int32),
     ]
 
 
@@ -69,7 +69,7 @@ class PlanView(C.Structure):
 
 
 class WalkView(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("available", "row_tiles", "n_row_blocks", "n_blocks", "n_qt",
+    _fields_ = [(n, C.c_int32) for n in ("available", "row_tiles", "waves", "n_row_blocks", "n_blocks", "n_qt",
                                          "n_items")] + \
                [(n, _I32P) for n in ("row_blocks", "blocks", "qt", "items")]
 
@@ -109,7 +109,7 @@ def _load():
     lib.spex_tree_stats.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.spex_tree_plan_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(PlanView)]
     lib.spex_tree_gather_kv.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
-    lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32, i32]
+    lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.spex_tree_walk_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(WalkView)]
     lib.spex_tree_set_profiling.argtypes = [vp, i32]
     lib.spex_tree_read_profile.argtypes = [vp, C.POINTER(f32), i32, _I32P]
@@ -153,7 +153,7 @@ class SpexTree:
                  q_dtype: str = "bf16", kv_dtype: str = "bf16", num_pages: int = 0,
                  device="cuda", free_order: Optional[Sequence[int]] = None,
                  prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0,
-                 walk_row_tiles: int = 0, host_only: bool = False, pool_fill: Optional[int] = None,
+                 walk_row_tiles: int = 0, walk_waves: int = 0, host_only: bool = False, pool_fill: Optional[int] = None,
                  interleave_kv: bool = False):
         self.Hq, self.Hkv, self.D, self.P = num_q_heads, num_kv_heads, head_dim, page_size
         self.q_dtype, self.kv_dtype = _DTYPES[q_dtype], _DTYPES[kv_dtype]
@@ -167,6 +167,7 @@ class SpexTree:
         cfg.prefix_chunk_pages, cfg.suffix_chunk_pages = prefix_chunk_pages, suffix_chunk_pages
         cfg.kernel_mode = kernel_mode
         cfg.walk_row_tiles = walk_row_tiles
+        cfg.walk_waves = walk_waves
         self.k_pool = self.v_pool = self.k_scale = self.v_scale = None
         if not host_only:
             nbytes = C.c_size_t()
@@ -330,9 +331,9 @@ class SpexTree:
         return k, v, ks, vs
 
     def set_tuning(self, prefix_chunk_pages: int = 0, suffix_chunk_pages: int = 0, kernel_mode: int = 0,
-                   walk_row_tiles: int = 0):
+                   walk_row_tiles: int = 0, walk_waves: int = 0):
         _check(lib.spex_tree_set_tuning(self._h, prefix_chunk_pages, suffix_chunk_pages, kernel_mode,
-                                        walk_row_tiles))
+                                        walk_row_tiles, walk_waves))
 
     def walk_dump(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]]) -> dict:
         la = _i32(leaves)
@@ -344,9 +345,11 @@ class SpexTree:
             p = getattr(v, name)
             return [] if n == 0 else np.ctypeslib.as_array(p, shape=(n,)).tolist()
 
-        return dict(available=v.available, row_tiles=v.row_tiles,
-                    row_blocks=arr("row_blocks", 15 * v.n_row_blocks), blocks=arr("blocks", 8 * v.n_blocks),
-                    qt=arr("qt", 2 * v.n_qt), items=arr("items", 16 * v.n_items))
+        nw = v.waves
+        return dict(available=v.available, row_tiles=v.row_tiles, waves=nw,
+                    row_blocks=arr("row_blocks", (3 + 3 * nw) * v.n_row_blocks),
+                    blocks=arr("blocks", 8 * v.n_blocks), qt=arr("qt", 2 * v.n_qt),
+                    items=arr("items", (16 if nw == 4 else 32) * v.n_items))
 
     def set_profiling(self, enabled: bool):
         _check(lib.spex_tree_set_profiling(self._h, int(enabled)))
@@ -364,7 +367,10 @@ class SpexTree:
         _check(lib.spex_tree_last_launch_info(self._h, info))
         names = ["kv_tokens", "prefix_tokens", "suffix_tokens", "prefix_items", "suffix_items",
                  "partial_rows", "plan_rebuilt", "walk_row_tiles"]
-        return {n: info[i] for i, n in enumerate(names)}
+        d = {n: info[i] for i, n in enumerate(names)}
+        d["walk_waves"] = d["walk_row_tiles"] // 256
+        d["walk_row_tiles"] %= 256
+        return d
 
 
 # ---- functions named like the C entry points ------------------------------------------------

@@ -63,7 +63,7 @@ struct spex_tree {
   float *d_part_o = nullptr, *d_part_ml = nullptr;
   int64_t part_cap_rows = 0;
 
-  int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0, walk_row_tiles = 0;
+  int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0, walk_row_tiles = 0, walk_waves = 0;
   // Profiling: a ring of event sets, one per decode_attention call since it was enabled.
   static constexpr int kProfSlots = 256;
   struct ProfSlot {
@@ -91,6 +91,7 @@ spex_status_t check_config(const spex_config_t *c) {
   if (c->kernel_mode < 0 || c->kernel_mode > 3) return SPEX_ERR_INVALID_ARG;
   if (c->walk_row_tiles != 0 && c->walk_row_tiles != 1 && c->walk_row_tiles != 2 && c->walk_row_tiles != 4)
     return SPEX_ERR_INVALID_ARG;
+  if (c->walk_waves != 0 && c->walk_waves != 4 && c->walk_waves != 8) return SPEX_ERR_INVALID_ARG;
   const bool ok = (c->q_dtype == SPEX_F32 && c->kv_dtype == SPEX_F32) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_BF16) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_FP8_E4M3);
@@ -122,7 +123,7 @@ bool same_request(const spex::Plan &pl, const spex_tree *t, const int32_t *leave
                   const int32_t *q_lens, int32_t n) {
   if (!pl.valid || pl.table_version != t->pt->version()) return false;
   if (pl.req_prefix_chunk != t->prefix_chunk || pl.req_suffix_chunk != t->suffix_chunk ||
-      pl.req_walk_row_tiles != t->walk_row_tiles)
+      pl.req_walk_row_tiles != t->walk_row_tiles || pl.req_walk_waves != t->walk_waves)
     return false;
   if (static_cast<int32_t>(pl.req_leaves.size()) != n) return false;
   if (n && std::memcmp(pl.req_leaves.data(), leaves, sizeof(int32_t) * n) != 0) return false;
@@ -143,7 +144,7 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
   t->plan_on_device = false;
   const spex::PlanError e = t->planner.build(*t->pt, leaves, q_lens, n, t->cfg.num_q_heads,
                                              t->cfg.num_kv_heads, t->prefix_chunk, t->suffix_chunk,
-                                             t->walk_row_tiles, &t->plan);
+                                             t->walk_row_tiles, t->walk_waves, &t->plan);
   switch (e) {
     case spex::PlanError::kOk: return SPEX_OK;
     case spex::PlanError::kBadNode: t->plan.valid = false; return SPEX_ERR_BAD_NODE;
@@ -288,6 +289,7 @@ spex_status_t spex_tree_create(const spex_config_t *cfg, spex_tree_t **out) {
   t->suffix_chunk = cfg->suffix_chunk_pages;
   t->kernel_mode = cfg->kernel_mode;
   t->walk_row_tiles = cfg->walk_row_tiles;
+  t->walk_waves = cfg->walk_waves;
   *out = t;
   return SPEX_OK;
 }
@@ -433,14 +435,14 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     wa.v_scale = t->cfg.v_scale;
     wa.q = q;
     wa.items = dp.walk_items;
-    wa.n_items = static_cast<int32_t>(pl.walk_items.size() / spex::Plan::kWalkItemInts);
+    wa.n_items = static_cast<int32_t>(pl.walk_items.size() / pl.item_ints());
     wa.blocks = dp.walk_blocks;
     wa.qt_rec = dp.walk_qt;
     wa.out = out;
     wa.lse = lse;
     wa.scale_log2 = sm_scale * 1.4426950408889634f;
     HIP_TRY(bracket(3, true));
-    HIP_TRY(spex::launch_tree_walk(t->shape, wa, pl.walk_row_tiles, stream));
+    HIP_TRY(spex::launch_tree_walk(t->shape, wa, pl.walk_row_tiles, pl.walk_waves, stream));
     HIP_TRY(bracket(3, false));
     t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
     t->info[1] = pl.prefix_tokens;
@@ -449,7 +451,7 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     t->info[4] = pl.walk_block_visits;
     t->info[5] = 0;
     t->info[6] = rebuilt ? 1 : 0;
-    t->info[7] = pl.walk_row_tiles;
+    t->info[7] = pl.walk_row_tiles + 256 * pl.walk_waves;
     return SPEX_OK;
   }
 
@@ -668,14 +670,16 @@ spex_status_t spex_tree_gather_kv(spex_tree_t *t, spex_node_t node, int32_t firs
 
 spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
                                    int32_t suffix_chunk_pages, int32_t kernel_mode,
-                                   int32_t walk_row_tiles) {
+                                   int32_t walk_row_tiles, int32_t walk_waves) {
   if (!t || prefix_chunk_pages < 0 || suffix_chunk_pages < 0 || kernel_mode < 0 || kernel_mode > 3 ||
-      (walk_row_tiles != 0 && walk_row_tiles != 1 && walk_row_tiles != 2 && walk_row_tiles != 4))
+      (walk_row_tiles != 0 && walk_row_tiles != 1 && walk_row_tiles != 2 && walk_row_tiles != 4) ||
+      (walk_waves != 0 && walk_waves != 4 && walk_waves != 8))
     return SPEX_ERR_INVALID_ARG;
   t->prefix_chunk = prefix_chunk_pages;
   t->suffix_chunk = suffix_chunk_pages;
   t->kernel_mode = kernel_mode;
   t->walk_row_tiles = walk_row_tiles;
+  t->walk_waves = walk_waves;
   return SPEX_OK;
 }
 
@@ -689,10 +693,11 @@ spex_status_t spex_tree_walk_dump(spex_tree_t *t, const spex_node_t *leaves, con
   spex_walk_view_t v{};
   v.available = pl.walk_ok ? 1 : 0;
   v.row_tiles = pl.walk_row_tiles;
-  v.n_row_blocks = static_cast<int32_t>(pl.walk_rb.size() / spex::Plan::kRbInts);
+  v.waves = pl.walk_waves;
+  v.n_row_blocks = pl.walk_ok ? static_cast<int32_t>(pl.walk_rb.size() / pl.rb_ints()) : 0;
   v.n_blocks = static_cast<int32_t>(pl.walk_blocks.size() / spex::Plan::kBlockInts);
   v.n_qt = static_cast<int32_t>(pl.walk_qt.size() / 2);
-  v.n_items = static_cast<int32_t>(pl.walk_items.size() / spex::Plan::kWalkItemInts);
+  v.n_items = pl.walk_ok ? static_cast<int32_t>(pl.walk_items.size() / pl.item_ints()) : 0;
   v.row_blocks = pl.walk_rb.data();
   v.blocks = pl.walk_blocks.data();
   v.qt = pl.walk_qt.data();

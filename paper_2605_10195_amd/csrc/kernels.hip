@@ -776,7 +776,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
 }
 
 // ---- tree-walk kernel: one workgroup carries a block of query rows from the root to the leaves --
-// A work item is a row block (up to 4 wavefronts x 16 * NTW rows of the requested nodes below one
+// A work item is a row block (up to NW = 4 or 8 wavefronts x 16 * NTW rows of the requested nodes below one
 // root, neighbours in the tree next to each other) and a kv head.  Its block list covers every
 // page on the rows' paths exactly once, each block with the range of rows whose path contains it.
 // Phase 1 walks the blocks whose rows span several wavefronts: the workgroup fetches each block
@@ -936,8 +936,8 @@ __device__ __forceinline__ void walk_write_rows(float *out, float *lse, const Sh
   }
 }
 
-template <int KV, int D, int NTW>
-__global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(WalkArgs p, Shape sh) {
+template <int KV, int D, int NTW, int NW>
+__global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_tree_walk_kernel(WalkArgs p, Shape sh) {
   constexpr bool FP8 = KV == kFP8;
   constexpr int ESZ = FP8 ? 1 : 2;
   constexpr int TILE_BYTES = 16 * D * ESZ;
@@ -946,28 +946,32 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
   constexpr int NI = NKI + D / 16;         // all operand images per block (1 KiB each)
   constexpr int RAW = FP8 ? NI / 2 : NI;   // 1 KiB global loads per block
   constexpr int RK = FP8 ? NKI / 2 : NKI;  // of which K
-  constexpr int PER = RAW / 4;             // global loads per wavefront and block in phase 1
-  static_assert(RAW % 4 == 0, "block must split evenly over four wavefronts");
+  constexpr int PER = (RAW + NW - 1) / NW;  // global loads per wavefront and block in the shared phase
+  constexpr bool kEven = RAW % NW == 0;     // else the last wavefronts have no piece to fetch
+  constexpr int kItemInts = NW == 4 ? 16 : 32;
   constexpr int kImgFloats = NI * 64 * 4;
   constexpr int kLdsFloats =
-      2 * kImgFloats > 4 * stage_floats<D>() ? 2 * kImgFloats : 4 * stage_floats<D>();
+      2 * kImgFloats > NW * stage_floats<D>() ? 2 * kImgFloats : NW * stage_floats<D>();
   __shared__ __attribute__((aligned(16))) float lds[kLdsFloats];
   u32x4 *img = reinterpret_cast<u32x4 *>(lds);  // [buf][image][lane]
 
   const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
   const int w = uniform(threadIdx.x >> 6);
-  const int64_t ir = static_cast<int64_t>(blockIdx.x) * 16;
+  const int64_t ir = static_cast<int64_t>(blockIdx.x) * kItemInts;
   const int g = sload(p.items, ir + 0);
   const int blk_begin = sload(p.items, ir + 1);
   const int n_shared = sload(p.items, ir + 2);
-  const int np0 = sload(p.items, ir + 3), np1 = sload(p.items, ir + 4), np2 = sload(p.items, ir + 5),
-            np3 = sload(p.items, ir + 6);
-  if (n_shared + np0 + np1 + np2 + np3 == 0) return;  // padding item (whole workgroup)
-  const int n_priv = w == 0 ? np0 : (w == 1 ? np1 : (w == 2 ? np2 : np3));
-  const int priv_begin =
-      blk_begin + n_shared + (w > 0 ? np0 : 0) + (w > 1 ? np1 : 0) + (w > 2 ? np2 : 0);
-  const int qt_begin = sload(p.items, ir + 7 + w);
-  const int qt_count = sload(p.items, ir + 11 + w);
+  int n_all = n_shared, n_priv = 0, priv_begin = blk_begin + n_shared;
+#pragma unroll
+  for (int v = 0; v < NW; ++v) {
+    const int npv = sload(p.items, ir + 3 + v);
+    n_all += npv;
+    n_priv = v == w ? npv : n_priv;
+    priv_begin += v < w ? npv : 0;
+  }
+  if (n_all == 0) return;  // padding item (whole workgroup)
+  const int qt_begin = sload(p.items, ir + 3 + NW + w);
+  const int qt_count = sload(p.items, ir + 3 + 2 * NW + w);
   const int rows = qt_count * sh.G;
   const bool has_rows = rows > 0;
   const char *kpool = static_cast<const char *>(p.k_pool);
@@ -1020,7 +1024,8 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
       const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        const int idx = k * 4 + w;  // wave-uniform
+        const int idx = k * NW + w;  // wave-uniform
+        if (!kEven && idx >= RAW) continue;
         const char *src = idx < RK ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
                                    : vp + (idx - RK) * 512;
         rw.r[k] = (bm.flags & 2) ? *reinterpret_cast<const u32x4 *>(src) : load_kv(src);
@@ -1031,7 +1036,8 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_tree_walk_kernel(W
       u32x4 *dst = img + buf * (NI * 64) + lane;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        const int idx = k * 4 + w;
+        const int idx = k * NW + w;
+        if (!kEven && idx >= RAW) continue;
         if (FP8) {
           if (idx < RK) {
             dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][0], rw.r[k][1]));
@@ -1469,26 +1475,32 @@ hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipSt
                     : launch_coop_ntw<kFP8, 128>(sh, a, ntw, stream);
 }
 
-template <int KV, int D>
+template <int KV, int D, int NW>
 static hipError_t launch_walk_ntw(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream) {
-  const dim3 grid(a.n_items), block(256);
+  const dim3 grid(a.n_items), block(64 * NW);
   if (ntw == 1)
-    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 1>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 1, NW>), grid, block, 0, stream, a, sh);
   else if (ntw == 2)
-    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 2>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 2, NW>), grid, block, 0, stream, a, sh);
   else
-    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 4>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 4, NW>), grid, block, 0, stream, a, sh);
   return hipGetLastError();
 }
 
-hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream) {
+template <int KV, int D>
+static hipError_t launch_walk_nw(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {
+  return waves == 4 ? launch_walk_ntw<KV, D, 4>(sh, a, ntw, stream) : launch_walk_ntw<KV, D, 8>(sh, a, ntw, stream);
+}
+
+hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {
   if (a.n_items <= 0) return hipSuccess;
-  if (!has_mfma_kernel(sh) || (ntw != 1 && ntw != 2 && ntw != 4)) return hipErrorInvalidValue;
+  if (!has_mfma_kernel(sh) || (ntw != 1 && ntw != 2 && ntw != 4) || (waves != 4 && waves != 8))
+    return hipErrorInvalidValue;
   if (sh.kv_dtype == kBF16)
-    return sh.D == 64 ? launch_walk_ntw<kBF16, 64>(sh, a, ntw, stream)
-                      : launch_walk_ntw<kBF16, 128>(sh, a, ntw, stream);
-  return sh.D == 64 ? launch_walk_ntw<kFP8, 64>(sh, a, ntw, stream)
-                    : launch_walk_ntw<kFP8, 128>(sh, a, ntw, stream);
+    return sh.D == 64 ? launch_walk_nw<kBF16, 64>(sh, a, ntw, waves, stream)
+                      : launch_walk_nw<kBF16, 128>(sh, a, ntw, waves, stream);
+  return sh.D == 64 ? launch_walk_nw<kFP8, 64>(sh, a, ntw, waves, stream)
+                    : launch_walk_nw<kFP8, 128>(sh, a, ntw, waves, stream);
 }
 
 hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream) {

@@ -42,9 +42,10 @@ struct WalkArgs {
   const void *k_pool, *v_pool;
   const float *k_scale, *v_scale;
   const void *q;
-  const int32_t *items;   // 16 ints per workgroup: {kv head, first block, shared blocks, private
-                          //   blocks of wavefronts 0..3, first qt_rec entry of wavefronts 0..3,
-                          //   qt_rec entries of wavefronts 0..3, row block}; no blocks = padding
+  const int32_t *items;   // 16 (4 wavefronts per workgroup) or 32 (8) ints per workgroup: {kv head,
+                          //   first block, shared blocks, private blocks of wavefronts 0..NW-1,
+                          //   first qt_rec entry of each wavefront, qt_rec entries of each
+                          //   wavefront, zeros.., row block}; no blocks = padding
   int32_t n_items;
   const int32_t *blocks;  // 8 ints per 32-token block: {page a, pos_a << 7 | valid_a, page b,
                           //   pos_b << 7 | valid_b (0: no page b), first row | (last row + 1) << 16
@@ -95,7 +96,8 @@ bool has_mfma_kernel(const Shape &sh);
 // Cooperative shared-prefix kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront (64 * ntw rows
 // per workgroup).  One work item per workgroup.  Only for shapes with has_mfma_kernel().
 hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream);
-// Tree-walk kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront the lists were built for.
-hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream);
+// Tree-walk kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront and waves in {4, 8} = wavefronts
+// per workgroup the lists were built for.
+hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream);
 
 }  // namespace spex

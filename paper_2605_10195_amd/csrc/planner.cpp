@@ -25,7 +25,7 @@ struct Segment {
 PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
                          int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
                          int32_t prefix_chunk_pages, int32_t suffix_chunk_pages,
-                         int32_t walk_row_tiles, Plan *plan) {
+                         int32_t walk_row_tiles, int32_t walk_waves, Plan *plan) {
   if (n_leaves < 0 || (n_leaves > 0 && !leaves)) return PlanError::kInvalid;
   const int32_t P = pt.page_size();
   const int32_t G = num_q_heads / num_kv_heads;
@@ -38,6 +38,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
   pl.req_prefix_chunk = prefix_chunk_pages;
   pl.req_suffix_chunk = suffix_chunk_pages;
   pl.req_walk_row_tiles = walk_row_tiles;
+  pl.req_walk_waves = walk_waves;
 
   if (static_cast<int32_t>(live_.size()) < N) {
     live_.resize(N, 0);
@@ -299,7 +300,8 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     pl.qt_rec[2 * i] = pl.qt_list[i];
     pl.qt_rec[2 * i + 1] = pl.qt_limit[pl.qt_list[i]];
   }
-  build_walk(pt, q_lens, n_leaves, G, num_kv_heads, walk_row_tiles, path_indptr, path_nodes, qoff, plan);
+  build_walk(pt, q_lens, n_leaves, G, num_kv_heads, walk_row_tiles, walk_waves, path_indptr, path_nodes, qoff,
+             plan);
   pl.valid = true;
   return PlanError::kOk;
 }
@@ -314,8 +316,9 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
 //  * roots in order of first appearance in the request list; the requests of a root sorted by
 //    path (node ids root first, lexicographic, a proper prefix first), ties in request order;
 //    so the requests below any node are consecutive.
+//  * a row block has NW wavefronts: the value asked for (4 or 8), 4 if 0.
 //  * packing: a request joins the current wavefront if its rows still fit, else it starts the
-//    next one; a fifth wavefront, or a new root, starts a new row block.  walk_qt lists
+//    next one; wavefront NW, or a new root, starts a new row block.  walk_qt lists
 //    {query token, limit} of the requests in this order.  Wavefronts without requests have
 //    first entry 0 and count 0.  Row of a request in its row block: wavefront * C + rows before
 //    it in the wavefront.
@@ -325,7 +328,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
 //    and minlim = min over those requests of T - q_len + 1.  A node whose range touches two
 //    wavefronts is shared, else it is private to wavefront lo / C.
 //  * blocks of a row block: its shared nodes in encounter order, then the private nodes of
-//    wavefront 0, 1, 2, 3; a node's pages two at a time (the last block of an odd run has no
+//    wavefront 0, 1, ..; a node's pages two at a time (the last block of an odd run has no
 //    page b).  Flag bit 0: page a or b partial, or no page b, or minlim smaller than the path
 //    position after the block's last token.  Flag bit 1: the node lies on paths of more than one
 //    row block (its pages are fetched again by another workgroup and are worth keeping cached).
@@ -336,13 +339,14 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
 //    than one lane exists; each for kv head 0 .. Hkv-1.  Workgroup b runs on XCD b % 8, so the row
 //    blocks of one root and kv head follow each other on one XCD and share its L2.
 void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_leaves, int32_t G,
-                         int32_t num_kv_heads, int32_t walk_row_tiles,
+                         int32_t num_kv_heads, int32_t walk_row_tiles, int32_t walk_waves,
                          const std::vector<int32_t> &path_indptr,
                          const std::vector<int32_t> &path_nodes, const std::vector<int32_t> &qoff,
                          Plan *plan) {
   Plan &pl = *plan;
   pl.walk_ok = false;
   pl.walk_row_tiles = 0;
+  pl.walk_waves = 0;
   if (n_leaves == 0) return;
   const int32_t P = pt.page_size();
   const int32_t N = pt.num_nodes();
@@ -387,6 +391,12 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
   }
   pl.walk_row_tiles = ntw;
   const int32_t C = 16 * ntw;
+  // Measured on MI355X, two workgroups of 4 wavefronts per compute unit beat one of 8 on every
+  // workload tried (the barrier of the shared phase then stalls only half of the unit), so 4 is
+  // the default even for roots with more rows than one 4-wavefront row block takes.
+  const int32_t NW = walk_waves == 0 ? 4 : walk_waves;
+  pl.walk_waves = NW;
+  const int32_t rb_ints = 3 + 3 * NW, item_ints = NW == 4 ? 16 : 32;
 
   std::vector<int32_t> order(n_leaves);
   std::iota(order.begin(), order.end(), 0);
@@ -414,7 +424,7 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
       } else if (used + rows > C) {
         ++wave;
         used = 0;
-        if (wave == 4) {
+        if (wave == NW) {
           ++rb;
           wave = 0;
         }
@@ -438,9 +448,9 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
   std::vector<NodeRange> nodes;
   std::vector<int64_t> rb_blocks;           // blocks per row block
   std::vector<std::vector<int32_t>> rbs_of_root(root_ids.size());
-  int32_t rb_rec[Plan::kRbInts];
+  std::vector<int32_t> rb_rec(rb_ints);
   auto start_rb = [&](int32_t root_slot) {
-    for (int &x : rb_rec) x = 0;
+    for (int32_t &x : rb_rec) x = 0;
     rb_rec[0] = root_ids[root_slot];
     cur.clear();
   };
@@ -492,16 +502,18 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
     for (const NodeRange &nr : nodes)
       if (nr.lo / C != (nr.hi - 1) / C) rb_rec[2] += emit_node(nr);
     total += rb_rec[2];
-    for (int32_t w = 0; w < 4; ++w) {
+    int32_t longest_private = 0;
+    for (int32_t w = 0; w < NW; ++w) {
       for (const NodeRange &nr : nodes)
         if (nr.lo / C == (nr.hi - 1) / C && nr.lo / C == w) rb_rec[3 + w] += emit_node(nr);
       total += rb_rec[3 + w];
+      longest_private = std::max(longest_private, rb_rec[3 + w]);
     }
-    rbs_of_root[root_slot].push_back(static_cast<int32_t>(pl.walk_rb.size() / Plan::kRbInts));
-    pl.walk_rb.insert(pl.walk_rb.end(), rb_rec, rb_rec + Plan::kRbInts);
+    rbs_of_root[root_slot].push_back(static_cast<int32_t>(pl.walk_rb.size() / rb_ints));
+    pl.walk_rb.insert(pl.walk_rb.end(), rb_rec.begin(), rb_rec.end());
     rb_blocks.push_back(total);
     pl.walk_block_visits += total;
-    pl.walk_max_item_blocks = std::max<int32_t>(pl.walk_max_item_blocks, static_cast<int32_t>(total));
+    pl.walk_max_item_blocks = std::max(pl.walk_max_item_blocks, rb_rec[2] + longest_private);
   };
 
   int32_t wave = 0, used = 0, cur_root = -1;
@@ -515,18 +527,18 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
     } else if (used + rows > C) {
       ++wave;
       used = 0;
-      if (wave == 4) {
+      if (wave == NW) {
         flush(cur_root);
         start_rb(cur_root);
         wave = 0;
       }
     }
-    if (rb_rec[11 + wave] == 0) rb_rec[7 + wave] = static_cast<int32_t>(pl.walk_qt.size() / 2);
+    if (rb_rec[3 + 2 * NW + wave] == 0) rb_rec[3 + NW + wave] = static_cast<int32_t>(pl.walk_qt.size() / 2);
     for (int32_t j = 0; j < ql; ++j) {
       pl.walk_qt.push_back(qoff[idx] + j);
       pl.walk_qt.push_back(pl.qt_limit[qoff[idx] + j]);
     }
-    rb_rec[11 + wave] += ql;
+    rb_rec[3 + 2 * NW + wave] += ql;
     cur.push_back({idx, wave * C + used});
     used += rows;
   }
@@ -558,14 +570,16 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
       const bool real = r < lane_rbs[l].size();
       if (!real && lanes == 1) continue;
       for (int32_t g = 0; g < num_kv_heads; ++g) {
-        int32_t rec[Plan::kWalkItemInts] = {g, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, -1};
+        std::vector<int32_t> rec(item_ints, 0);
+        rec[0] = g;
+        rec[item_ints - 1] = -1;
         if (real) {
           const int32_t rb = lane_rbs[l][r];
-          for (int k = 1; k < Plan::kRbInts; ++k) rec[k] = pl.walk_rb[static_cast<size_t>(rb) * Plan::kRbInts + k];
-          rec[15] = rb;
+          for (int k = 1; k < rb_ints; ++k) rec[k] = pl.walk_rb[static_cast<size_t>(rb) * rb_ints + k];
+          rec[item_ints - 1] = rb;
           ++pl.walk_real_items;
         }
-        pl.walk_items.insert(pl.walk_items.end(), rec, rec + Plan::kWalkItemInts);
+        pl.walk_items.insert(pl.walk_items.end(), rec.begin(), rec.end());
       }
     }
   pl.walk_ok = true;

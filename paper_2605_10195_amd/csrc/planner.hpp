@@ -60,11 +60,12 @@ struct Plan {
   // ---- tree-walk lists (see the rules above build_walk in planner.cpp)
   bool walk_ok = false;         // every requested node's rows fit one wavefront
   int32_t walk_row_tiles = 0;   // 16-row tiles per wavefront (1, 2 or 4)
-  int32_t req_walk_row_tiles = -1;
-  // row blocks: kRbInts ints each
-  //   {root node, first block, shared blocks, private blocks of wavefronts 0..3,
-  //    first walk_qt entry of wavefronts 0..3, walk_qt entries of wavefronts 0..3}
-  static constexpr int kRbInts = 15;
+  int32_t walk_waves = 0;       // NW: wavefronts per row block = per workgroup (4 or 8)
+  int32_t req_walk_row_tiles = -1, req_walk_waves = -1;
+  // row blocks: 3 + 3 * NW ints each
+  //   {root node, first block, shared blocks, private blocks of wavefronts 0..NW-1,
+  //    first walk_qt entry of wavefronts 0..NW-1, walk_qt entries of wavefronts 0..NW-1}
+  int rb_ints() const { return 3 + 3 * walk_waves; }
   std::vector<int32_t> walk_rb;
   // blocks: kBlockInts ints each {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b
   //   (0: no page b), first row | (last row + 1) << 16, flags (bit 0: token mask needed, bit 1:
@@ -72,12 +73,13 @@ struct Plan {
   static constexpr int kBlockInts = 8;
   std::vector<int32_t> walk_blocks;
   std::vector<int32_t> walk_qt;     // {query token, limit} in row order
-  // launch order: kWalkItemInts ints per workgroup {kv head, first block, shared blocks,
-  //   private blocks[4], walk_qt first[4], walk_qt count[4], row block index}; a padding item has
-  //   row block index -1 and no blocks
-  static constexpr int kWalkItemInts = 16;
+  // launch order: item_ints() = 16 (NW = 4) or 32 (NW = 8) ints per workgroup {kv head, first
+  //   block, shared blocks, private blocks[NW], walk_qt first[NW], walk_qt count[NW], zeros..,
+  //   row block index in the last int}; a padding item has row block index -1 and no blocks
+  int item_ints() const { return walk_waves == 4 ? 16 : 32; }
   std::vector<int32_t> walk_items;
-  int32_t walk_real_items = 0, walk_max_item_blocks = 0;
+  int32_t walk_real_items = 0;       // workgroups with work
+  int32_t walk_max_item_blocks = 0;  // longest workgroup: shared blocks + most private blocks of a wavefront
   int64_t walk_block_visits = 0;  // blocks over all row blocks (a block shared by two row blocks counts twice)
 };
 
@@ -88,11 +90,11 @@ class Planner {
   PlanError build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
                   int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
                   int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, int32_t walk_row_tiles,
-                  Plan *plan);
+                  int32_t walk_waves, Plan *plan);
 
  private:
   void build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_leaves, int32_t G,
-                  int32_t num_kv_heads, int32_t walk_row_tiles,
+                  int32_t num_kv_heads, int32_t walk_row_tiles, int32_t walk_waves,
                   const std::vector<int32_t> &path_indptr, const std::vector<int32_t> &path_nodes,
                   const std::vector<int32_t> &qoff, Plan *plan);
   std::vector<int32_t> multi_;

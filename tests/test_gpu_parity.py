@@ -111,22 +111,23 @@ def walk_applies(wl, row_tiles=0):
 
 
 @pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")
-@pytest.mark.parametrize("row_tiles", [0, 1, 2, 4])
-def test_random_trees_tree_walk_kernel(case, row_tiles):
+@pytest.mark.parametrize("row_tiles,waves", [(0, 0), (1, 4), (2, 4), (4, 4), (1, 8), (2, 8), (4, 8)])
+def test_random_trees_tree_walk_kernel(case, row_tiles, waves):
     import paper_2605_10195_amd as spex
     wl = sw.random_trace(case["seed"], heads=case["heads"], kv_dtype=case["kv_dtype"],
                          q_dtype="f32" if case["kv_dtype"] == "f32" else "bf16",
                          n_ops=70, max_tokens=90, max_q_len=case["max_q_len"])
     if not walk_applies(wl, row_tiles):
         with pytest.raises(spex.SpexError) as e:
-            run_gpu(wl, kernel_mode=3, walk_row_tiles=row_tiles)
+            run_gpu(wl, kernel_mode=3, walk_row_tiles=row_tiles, walk_waves=waves)
         assert e.value.name == "UNSUPPORTED"
         return
-    tree = build_gpu_tree(wl, kernel_mode=3, walk_row_tiles=row_tiles)
+    tree = build_gpu_tree(wl, kernel_mode=3, walk_row_tiles=row_tiles, walk_waves=waves)
     got = run_gpu(wl, tree=tree)
     info = tree.last_launch_info()
     tree.close()
     assert info["walk_row_tiles"] == (row_tiles or info["walk_row_tiles"]) and info["walk_row_tiles"] > 0
+    assert info["walk_waves"] == (waves or info["walk_waves"]) and info["walk_waves"] in (4, 8)
     assert_close(got, run_oracle(wl), case["kv_dtype"], wl.name)
 
 
@@ -135,7 +136,7 @@ def test_automatic_mode_picks_the_tree_walk_kernel_for_short_paths():
     tree = build_gpu_tree(wl)
     got = run_gpu(wl, tree=tree)
     assert tree.last_launch_info()["walk_row_tiles"] > 0
-    tree.set_tuning(0, 0, 2, 0)
+    tree.set_tuning(0, 0, 2, 0, 0)
     split = run_gpu(wl, tree=tree)
     assert tree.last_launch_info()["walk_row_tiles"] == 0
     tree.close()
@@ -167,9 +168,10 @@ REDUCED = [
 
 
 @pytest.mark.parametrize("wl", REDUCED, ids=lambda w: w.name + "_" + w.kv_dtype)
-@pytest.mark.parametrize("mode", [2, 3])
-def test_reduced_config_shapes_match_oracle(wl, mode):
-    assert_close(run_gpu(wl, kernel_mode=mode), run_oracle(wl), wl.kv_dtype, f"{wl.name} mode {mode}")
+@pytest.mark.parametrize("mode,waves", [(2, 0), (3, 4), (3, 8)])
+def test_reduced_config_shapes_match_oracle(wl, mode, waves):
+    assert_close(run_gpu(wl, kernel_mode=mode, walk_waves=waves), run_oracle(wl), wl.kv_dtype,
+                 f"{wl.name} mode {mode} waves {waves}")
 
 
 def test_nan_poisoned_pool_and_ragged_pages():
@@ -177,9 +179,9 @@ def test_nan_poisoned_pool_and_ragged_pages():
     for kv in ("bf16", "fp8_e4m3"):
         wl = sw.random_trace(51, heads=(8, 2, 128), kv_dtype=kv, n_ops=60, max_tokens=37, max_q_len=3)
         ref = run_oracle(wl)
-        for mode in (2, 3):
-            got = run_gpu(wl, pool_fill=0xFF, extra_pages=7, kernel_mode=mode)
-            assert_close(got, ref, kv, f"poisoned {kv} mode {mode}")
+        for mode, waves in ((2, 0), (3, 4), (3, 8)):
+            got = run_gpu(wl, pool_fill=0xFF, extra_pages=7, kernel_mode=mode, walk_waves=waves)
+            assert_close(got, ref, kv, f"poisoned {kv} mode {mode} waves {waves}")
 
 
 def test_page_placement_does_not_change_the_result():
@@ -286,11 +288,13 @@ WIDE = [
 
 
 @pytest.mark.parametrize("wl", WIDE, ids=lambda w: f"{w.name}_{w.kv_dtype}_{w.num_q_heads}")
-@pytest.mark.parametrize("mode", [2, 1, 3])
+@pytest.mark.parametrize("mode", [2, 1, 3, 38])
 def test_wide_groups_match_oracle(wl, mode):
     ref = run_oracle(wl)
+    waves, mode = (8, 3) if mode == 38 else (0, mode)          # 38: tree-walk with 8 wavefronts
     for chunks in ((0, 0), (3, 2)) if mode != 3 else ((0, 0),):
-        got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1], kernel_mode=mode)
+        got = run_gpu(wl, prefix_chunk_pages=chunks[0], suffix_chunk_pages=chunks[1], kernel_mode=mode,
+                      walk_waves=waves)
         assert_close(got, ref, wl.kv_dtype, f"{wl.name} mode {mode} chunks {chunks}")
 
 

@@ -76,7 +76,7 @@ PLAN_KEYS = ["leaf_indptr", "leaf_pages", "leaf_valid", "qt_limit", "group_node"
 
 
 def assert_same_plan(tree, ref, wl, pc, sc):
-    tree.set_tuning(pc, sc, 0, 0)
+    tree.set_tuning(pc, sc, 0, 0, 0)
     got = tree.plan_dump(wl.leaves, wl.q_lens)
     want = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
                     got["prefix_chunk_pages"], got["suffix_chunk_pages"])
@@ -187,15 +187,15 @@ def test_plan_is_cached_until_the_tree_changes():
 
 
 # ------------------------------------------------------------------ tree-walk lists
-WALK_KEYS = ["available", "row_tiles", "row_blocks", "blocks", "qt", "items"]
+WALK_KEYS = ["available", "row_tiles", "waves", "row_blocks", "blocks", "qt", "items"]
 
 
-def check_walk_lists(tree, ref, wl, row_tiles):
+def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
     """Bit-exact against the reference model, and -- independently of both -- every row of every
     row block meets every page of its path exactly once, with the right positions and masks."""
-    tree.set_tuning(0, 0, 0, row_tiles)
+    tree.set_tuning(0, 0, 0, row_tiles, waves)
     got = tree.walk_dump(wl.leaves, wl.q_lens)
-    want = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, row_tiles)
+    want = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, row_tiles, waves)
     for k in WALK_KEYS:
         assert got[k] == want[k], k
     G = wl.num_q_heads // wl.num_kv_heads
@@ -204,7 +204,9 @@ def check_walk_lists(tree, ref, wl, row_tiles):
         assert max(q * G for q in q_lens) > (16 * row_tiles if row_tiles else 64)
         return got
     C = 16 * got["row_tiles"]
-    rbs = np.array(got["row_blocks"]).reshape(-1, 15)
+    NW = got["waves"]
+    assert NW in (4, 8) and (waves == 0 or NW == waves)
+    rbs = np.array(got["row_blocks"]).reshape(-1, 3 + 3 * NW)
     blocks = np.array(got["blocks"]).reshape(-1, 8)
     qt = np.array(got["qt"]).reshape(-1, 2)
     qoff = np.concatenate([[0], np.cumsum(q_lens)])
@@ -213,28 +215,29 @@ def check_walk_lists(tree, ref, wl, row_tiles):
     used_blocks = np.zeros(len(blocks), dtype=bool)
     rbs_of_page = {}                                              # page -> row blocks that list it
     for bi, rb in enumerate(rbs):
-        for blk in blocks[rb[1]:rb[1] + rb[2] + rb[3:7].sum()]:
+        for blk in blocks[rb[1]:rb[1] + rb[2] + rb[3:3 + NW].sum()]:
             for pg in {int(blk[0]), int(blk[2])}:
                 rbs_of_page.setdefault(pg, set()).add(bi)
     for blk in blocks:                                            # flag bit 1: shared between row blocks
         assert bool(blk[5] & 2) == (len(rbs_of_page[int(blk[0])]) > 1)
     for rb in rbs:
-        first, n_sh, n_pr = rb[1], rb[2], rb[3:7]
+        first, n_sh, n_pr = rb[1], rb[2], rb[3:3 + NW]
+        qt_first, qt_count = rb[3 + NW:3 + 2 * NW], rb[3 + 2 * NW:3 + 3 * NW]
         spans = [(first, first + n_sh, None)]
         b0 = first + n_sh
-        for w in range(4):
+        for w in range(NW):
             spans.append((b0, b0 + n_pr[w], w))
             b0 += n_pr[w]
         # rows of the row block: row -> (query token, limit)
         row_tok = {}
-        for w in range(4):
-            for e in range(rb[11 + w]):
-                t, lim = qt[rb[7 + w] + e]
+        for w in range(NW):
+            for e in range(qt_count[w]):
+                t, lim = qt[qt_first[w] + e]
                 assert lim == ref_limit(ref, wl, tok_owner[t], t - qoff[tok_owner[t]], q_lens)
                 for hh in range(G):
                     row_tok[w * C + e * G + hh] = (t, lim)
                 seen_tokens.append(t)
-            assert rb[11 + w] * G <= C
+            assert qt_count[w] * G <= C
         pages_of_row = {r: [] for r in row_tok}
         for a, b, wave in spans:
             for blk in blocks[a:b]:
@@ -263,14 +266,16 @@ def check_walk_lists(tree, ref, wl, row_tiles):
             assert sorted(pages_of_row[r]) == want_entries, (r, t)
     assert sorted(seen_tokens) == list(range(qoff[-1]))            # every query token in one row block
     assert used_blocks.all()
-    items = np.array(got["items"]).reshape(-1, 16)
-    real = items[items[:, 15] >= 0]
+    S = 16 if NW == 4 else 32
+    items = np.array(got["items"]).reshape(-1, S)
+    real = items[items[:, S - 1] >= 0]
     assert len(real) == len(rbs) * wl.num_kv_heads
     for g in range(wl.num_kv_heads):
-        assert sorted(real[real[:, 0] == g][:, 15].tolist()) == list(range(len(rbs)))
+        assert sorted(real[real[:, 0] == g][:, S - 1].tolist()) == list(range(len(rbs)))
     for it in real:
-        assert it[1:15].tolist() == rbs[it[15]][1:15].tolist()
-    assert (items[items[:, 15] < 0][:, 1:15] == 0).all()
+        assert it[1:3 + 3 * NW].tolist() == rbs[it[S - 1]][1:].tolist()
+        assert (it[3 + 3 * NW:S - 1] == 0).all()
+    assert (items[items[:, S - 1] < 0][:, 1:S - 1] == 0).all()
     return got
 
 
@@ -288,7 +293,8 @@ def test_walk_lists_random_traces(seed):
     tree, ref = host_tree(wl, n_pages, order), PageTableRef(n_pages, 16, order)
     replay_both(wl, tree, ref)
     for rt in (0, 1, 2, 4):
-        check_walk_lists(tree, ref, wl, rt)
+        for nw in (0, 4, 8):
+            check_walk_lists(tree, ref, wl, rt, nw)
 
 
 @pytest.mark.parametrize("wl", [
@@ -300,8 +306,10 @@ def test_walk_lists_config_shapes(wl):
     replay_both(wl, tree, ref)
     got = check_walk_lists(tree, ref, wl, 0)
     assert got["available"] == 1
+    assert got["waves"] == 4
     for rt in (1, 2, 4):
-        check_walk_lists(tree, ref, wl, rt)
+        for nw in (4, 8):
+            check_walk_lists(tree, ref, wl, rt, nw)
 
 
 def test_walk_lists_not_available_for_wide_requests():
