@@ -2,9 +2,9 @@
 """Benchmark: tree decode attention over a prefix-shared paged KV cache on one MI355X.
 
 A step is one spex_tree_decode_attention call on a fully built synthetic tree (page table ->
-cached plan -> shared-prefix kernel -> suffix kernel -> merge kernel) with all inputs resident in
-HBM.  Steps rotate over several identical trees in separate pools so that no step finds its KV in
-the 256 MB last-level cache.  Prints one JSON line.
+cached plan -> tree-walk kernel, or shared-prefix + suffix + merge kernels with --kernel-mode 2)
+with all inputs resident in HBM.  Steps rotate over several identical trees in separate pools so
+that no step finds its KV in the 256 MB last-level cache.  Prints one JSON line.
 """
 
 from __future__ import annotations
@@ -20,6 +20,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (counters need runs of their own); scaled by the factors the same counters show for
+# a plain 1 GiB-in / 1 GiB-out kernel (--calibrate): FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB.  The
+# summaries are in profiles/<workload>_tree_walk.md.  Key: (workload, kernel).
+MEASURED_TRAFFIC_BYTES = {
+    ("bfs_tot", "spex_tree_walk_kernel"): 536158433,           # profiles/bfs_tot_tree_walk.md
+    ("mcts_skewed", "spex_tree_walk_kernel"): 604621588,       # profiles/mcts_skewed_tree_walk.md
+    ("spec_at_scale", "spex_tree_walk_kernel"): 13068627066,   # profiles/spec_at_scale_tree_walk.md
+    ("tot_with_drafts", "spex_tree_walk_kernel"): 507995033,   # profiles/tot_with_drafts_tree_walk.md
+}
 PAPER_CONTEXT = ("paper reports only end-to-end serving speedups (1.2-3x, up to 4.1x with MTP) on "
                  "NVIDIA A6000/A100; no attention-kernel number exists for this metric")
 
@@ -203,7 +213,8 @@ def main():
         "hbm_frac_unique_kv": unique_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "roofline": {
             "bound": "hbm", "kernel": kernel_name, "achieved": dom["gbps"], "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s", "frac": dom["frac_hbm"], "traffic": None,
+            "unit": "GB/s", "frac": dom["frac_hbm"],
+            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name)),
             "bytes_per_launch": dom["kv_bytes"], "ms_per_launch": dom["ms"],
         },
         "kernels": kernels,
