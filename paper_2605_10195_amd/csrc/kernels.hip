@@ -50,8 +50,9 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // the lower half of the second; with both operands equal, the pair afterwards holds the value of
 // the lane and of its partner.  Two wait states separate a vector write from a swap that reads it.
 // The compiler does not track hazards of instructions inside inline assembly, so the argument must
-// be the result of an ordinary vector ALU instruction -- never of an MFMA, whose results need many
-// more wait states before they can be read.
+// be the result of an ordinary vector ALU instruction (here: the v_max that folds in the running
+// maximum) -- never directly of an MFMA, whose results need many more wait states before they can
+// be read.
 __device__ __forceinline__ float row_group_max(float v) {
   float a = v, b = v;
   asm("s_nop 1\n\t"
@@ -853,12 +854,14 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&
   for (int nt = 0; nt < NT; ++nt) {
     if (nt * 16 >= hi || nt * 16 + 16 <= lo) continue;  // wave-uniform
     const bool partial_tile = lo > nt * 16 || hi < nt * 16 + 16;
-    float x[8];  // scores in units of log2(e): the products are also what makes the maxima below
-                 // plain vector ALU results (see row_group_max)
+    // Scores: with one scale for the whole path (bf16 KV) they stay raw, the running maximum is
+    // kept on raw scores and scale and subtraction fuse into one FMA per score; with a scale per
+    // page (fp8 KV) they are scaled here.  m is in units of raw score / of log2(e) accordingly.
+    float x[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      x[i] = sa[nt][i] * c;
-      x[4 + i] = sb[nt][i] * c;
+      x[i] = FP8 ? sa[nt][i] * c : sa[nt][i];
+      x[4 + i] = FP8 ? sb[nt][i] * c : sb[nt][i];
     }
     if (tok_masked || partial_tile) {
       int vis = limit[nt] - pos_l;
@@ -874,10 +877,17 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&
     const float mx = row_group_max(fmaxf(mx8, m[nt]));
     const float m_new = mx;  // includes the running maximum
     const float m_safe = m_new == kNegInf ? 0.f : m_new;
-    float pr[8];
-    const float alpha = fast_exp2(m[nt] - m_safe);
+    float alpha, pr[8];
+    if (FP8) {
+      alpha = fast_exp2(m[nt] - m_safe);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
+    } else {
+      const float mc = m_safe * c;
+      alpha = fast_exp2(__builtin_fmaf(m[nt], c, -mc));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, -mc));
+    }
     m[nt] = m_new;
     if (!__all(alpha == 1.0f)) {
 #pragma unroll
@@ -1186,7 +1196,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   if (has_rows) {
     float m_log2[NTW];
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) m_log2[nt] = m[nt];
+    for (int nt = 0; nt < NTW; ++nt) m_log2[nt] = FP8 ? m[nt] : m[nt] * p.scale_log2;
     walk_write_rows<D, NTW>(p.out, p.lse, sh, g, rows, o, m_log2, lacc, qtok, lds + w * stage_floats<D>());
   }
 }
