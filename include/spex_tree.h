@@ -160,7 +160,10 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *   sm_scale must be positive and finite.
  * The call flattens parent links into per-launch work lists, uploads them when the request or
  * the tree changed since the previous call, and enqueues the kernels on hip_stream without
- * waiting for them.  Two kernel sets compute the same result:
+ * waiting for them.  If the only change is that tokens were appended without starting a new page
+ * (the usual decode iteration), the cached lists are patched instead: the valid count of each
+ * grown page and the limits of its queries, on the host and -- with one small kernel -- in the
+ * device copy.  Two kernel sets compute the same result:
  *   tree-walk: one workgroup carries a block of up to 16 * walk_row_tiles * walk_waves query rows (requested
  *     nodes that are neighbours in the tree) from the root to the requested nodes; pages shared
  *     by rows of several wavefronts are fetched once per workgroup, the softmax state stays in
@@ -269,6 +272,7 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages
  */
 typedef struct {
   int32_t available, row_tiles, waves, n_row_blocks, n_blocks, n_qt, n_items;
+  int32_t plan_state; /* how this call got its plan: 0 cached, 1 planned afresh, 2 cached plan patched */
   const int32_t *row_blocks, *blocks, *qt, *items;
 } spex_walk_view_t;
 spex_status_t spex_tree_walk_dump(spex_tree_t *tree, const spex_node_t *leaves,
@@ -288,9 +292,10 @@ spex_status_t spex_tree_set_profiling(spex_tree_t *tree, int32_t enabled);
 spex_status_t spex_tree_read_profile(spex_tree_t *tree, float *ms, int32_t cap, int32_t *n);
 
 /* Counts of the last decode_attention call, for the throughput metric:
- * info[0] distinct KV tokens on the requested paths, [1] of which on nodes shared by >= 2 requested
- * nodes, [2] of which private, [6] 1 if the plan was rebuilt, [7] 0 = shared-prefix + suffix + merge
- * kernels ran ([3] prefix work items, [4] suffix work items, [5] partial rows), else the tree-walk
+ * info[0] distinct KV tokens on the requested paths, [6] 0 = the cached plan was used, 1 = planned
+ * afresh, 2 = the cached plan was patched (tokens had been appended without starting a page),
+ * [7] 0 = shared-prefix + suffix + merge kernels ran ([1] tokens in shared-prefix tasks, [2] tokens in
+ * suffix tasks, [3] prefix work items, [4] suffix work items, [5] partial rows), else the tree-walk
  * kernel ran with [7] = row tiles per wavefront + 256 * wavefronts per workgroup ([3] workgroups
  * with work, [4] two-page blocks summed over workgroups of one kv head, [5] 0). */
 spex_status_t spex_tree_last_launch_info(const spex_tree_t *tree, int64_t info[8]);

@@ -70,7 +70,7 @@ class PlanView(C.Structure):
 
 class WalkView(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("available", "row_tiles", "waves", "n_row_blocks", "n_blocks", "n_qt",
-                                         "n_items")] + \
+                                         "n_items", "plan_state")] + \
                [(n, _I32P) for n in ("row_blocks", "blocks", "qt", "items")]
 
 
@@ -346,7 +346,7 @@ class SpexTree:
             return [] if n == 0 else np.ctypeslib.as_array(p, shape=(n,)).tolist()
 
         nw = v.waves
-        return dict(available=v.available, row_tiles=v.row_tiles, waves=nw,
+        return dict(available=v.available, row_tiles=v.row_tiles, waves=nw, plan_state=v.plan_state,
                     row_blocks=arr("row_blocks", (3 + 3 * nw) * v.n_row_blocks),
                     blocks=arr("blocks", 8 * v.n_blocks), qt=arr("qt", 2 * v.n_qt),
                     items=arr("items", (16 if nw == 4 else 32) * v.n_items))

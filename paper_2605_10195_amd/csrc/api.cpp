@@ -50,8 +50,12 @@ struct spex_tree {
   spex::PageTable *pt = nullptr;
   spex::Planner planner;
   spex::Plan plan;
-  bool plan_on_device = false;
+  bool plan_on_device = false, device_has_split = false, device_has_walk = false;
   DevicePlan dplan;
+  size_t blob_off[14] = {}, blob_ints[14] = {};  // byte offset and length of each list in the blob
+  std::vector<int32_t> pending_patches;          // {array, index, value} not yet on the device
+  void *d_patch = nullptr;
+  size_t d_patch_cap = 0;
 
   void *d_plan = nullptr;
   size_t d_plan_cap = 0;
@@ -119,9 +123,9 @@ spex::Shape make_shape(const spex_config_t &c) {
   return s;
 }
 
-bool same_request(const spex::Plan &pl, const spex_tree *t, const int32_t *leaves,
-                  const int32_t *q_lens, int32_t n) {
-  if (!pl.valid || pl.table_version != t->pt->version()) return false;
+bool request_matches(const spex::Plan &pl, const spex_tree *t, const int32_t *leaves,
+                     const int32_t *q_lens, int32_t n) {
+  if (!pl.valid) return false;
   if (pl.req_prefix_chunk != t->prefix_chunk || pl.req_suffix_chunk != t->suffix_chunk ||
       pl.req_walk_row_tiles != t->walk_row_tiles || pl.req_walk_waves != t->walk_waves)
     return false;
@@ -136,15 +140,7 @@ bool same_request(const spex::Plan &pl, const spex_tree *t, const int32_t *leave
   return true;
 }
 
-spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_lens, int32_t n,
-                        bool *rebuilt) {
-  *rebuilt = false;
-  if (same_request(t->plan, t, leaves, q_lens, n)) return SPEX_OK;
-  *rebuilt = true;
-  t->plan_on_device = false;
-  const spex::PlanError e = t->planner.build(*t->pt, leaves, q_lens, n, t->cfg.num_q_heads,
-                                             t->cfg.num_kv_heads, t->prefix_chunk, t->suffix_chunk,
-                                             t->walk_row_tiles, t->walk_waves, &t->plan);
+spex_status_t plan_status(spex_tree *t, spex::PlanError e) {
   switch (e) {
     case spex::PlanError::kOk: return SPEX_OK;
     case spex::PlanError::kBadNode: t->plan.valid = false; return SPEX_ERR_BAD_NODE;
@@ -154,31 +150,71 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
   }
 }
 
-spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
-  const spex::Plan &pl = t->plan;
-  const std::vector<int32_t> *arrays[] = {
-      &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
-      &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt,
-      &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2],
-      &pl.walk_items, &pl.walk_blocks, &pl.walk_qt};
-  constexpr int kN = sizeof(arrays) / sizeof(arrays[0]);
-  size_t off[kN], total = 0;
-  for (int i = 0; i < kN; ++i) {
-    off[i] = total;
-    total += align_up(arrays[i]->size() * sizeof(int32_t) + 16, 256);
+// Brings t->plan up to date for the request.  *state: 0 = the cached plan still holds, 1 = planned
+// afresh, 2 = the cached plan was patched (tokens were appended to requested nodes without starting
+// a page; the changed entries wait in t->pending_patches for the device copy).
+spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_lens, int32_t n,
+                        int *state) {
+  *state = 0;
+  if (request_matches(t->plan, t, leaves, q_lens, n)) {
+    if (t->plan.table_version == t->pt->version()) return SPEX_OK;
+    if (t->planner.patch_lengths(*t->pt, &t->plan, &t->pending_patches)) {
+      *state = 2;
+      return SPEX_OK;
+    }
   }
+  *state = 1;
+  t->plan_on_device = false;
+  t->pending_patches.clear();
+  return plan_status(t, t->planner.begin(*t->pt, leaves, q_lens, n, t->cfg.num_q_heads,
+                                         t->cfg.num_kv_heads, t->prefix_chunk, t->suffix_chunk,
+                                         t->walk_row_tiles, t->walk_waves, &t->plan));
+}
+
+constexpr int kPlanArrays = 14;
+// Index, in the device blob's array list, of the arrays a length patch can touch.
+constexpr int kPatchTarget[4] = {2 /*pg_rec*/, 3 /*qt_rec*/, 12 /*walk_blocks*/, 13 /*walk_qt*/};
+
+spex_status_t stage_reserve(spex_tree *t, size_t bytes) {
   if (t->stage_pending) {
     HIP_TRY(hipEventSynchronize(t->stage_event));
     t->stage_pending = false;
   }
-  if (total > t->h_stage_cap) {
+  if (bytes > t->h_stage_cap) {
     if (t->h_stage) HIP_TRY(hipHostFree(t->h_stage));
     t->h_stage = nullptr;
     t->h_stage_cap = 0;
-    const size_t cap = align_up(total + total / 2, 1 << 16);
+    const size_t cap = align_up(bytes + bytes / 2, 1 << 16);
     HIP_TRY(hipHostMalloc(&t->h_stage, cap, hipHostMallocDefault));
     t->h_stage_cap = cap;
   }
+  return SPEX_OK;
+}
+
+spex_status_t stage_send(spex_tree *t, void *dst, size_t bytes, hipStream_t stream) {
+  HIP_TRY(hipMemcpyAsync(dst, t->h_stage, bytes, hipMemcpyHostToDevice, stream));
+  if (!t->stage_event) HIP_TRY(hipEventCreateWithFlags(&t->stage_event, hipEventDisableTiming));
+  HIP_TRY(hipEventRecord(t->stage_event, stream));
+  t->stage_pending = true;
+  return SPEX_OK;
+}
+
+// Copies every list that has been built to the device (one blob, arrays at 256-byte offsets).
+spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
+  const spex::Plan &pl = t->plan;
+  const std::vector<int32_t> *arrays[kPlanArrays] = {
+      &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
+      &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt,
+      &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2],
+      &pl.walk_items, &pl.walk_blocks, &pl.walk_qt};
+  size_t total = 0;
+  for (int i = 0; i < kPlanArrays; ++i) {
+    t->blob_off[i] = total;
+    t->blob_ints[i] = arrays[i]->size();
+    total += align_up(arrays[i]->size() * sizeof(int32_t) + 16, 256);
+  }
+  const spex_status_t rs = stage_reserve(t, total);
+  if (rs != SPEX_OK) return rs;
   if (total > t->d_plan_cap) {
     if (t->d_plan) HIP_TRY(hipFree(t->d_plan));
     t->d_plan = nullptr;
@@ -188,15 +224,13 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
     t->d_plan_cap = cap;
   }
   char *h = static_cast<char *>(t->h_stage);
-  for (int i = 0; i < kN; ++i)
+  for (int i = 0; i < kPlanArrays; ++i)
     if (!arrays[i]->empty())
-      std::memcpy(h + off[i], arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
-  HIP_TRY(hipMemcpyAsync(t->d_plan, t->h_stage, total, hipMemcpyHostToDevice, stream));
-  if (!t->stage_event) HIP_TRY(hipEventCreateWithFlags(&t->stage_event, hipEventDisableTiming));
-  HIP_TRY(hipEventRecord(t->stage_event, stream));
-  t->stage_pending = true;
+      std::memcpy(h + t->blob_off[i], arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
+  const spex_status_t ss = stage_send(t, t->d_plan, total, stream);
+  if (ss != SPEX_OK) return ss;
   const char *d = static_cast<const char *>(t->d_plan);
-  auto at = [&](int i) { return reinterpret_cast<const int32_t *>(d + off[i]); };
+  auto at = [&](int i) { return reinterpret_cast<const int32_t *>(d + t->blob_off[i]); };
   DevicePlan &dp = t->dplan;
   dp.prefix_items = at(0);
   dp.suffix_items = at(1);
@@ -211,6 +245,43 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   dp.walk_blocks = at(12);
   dp.walk_qt = at(13);
   t->plan_on_device = true;
+  t->device_has_split = pl.has_split;
+  t->device_has_walk = pl.has_walk;
+  t->pending_patches.clear();
+  return SPEX_OK;
+}
+
+// Applies the pending length patches to the device copy of the plan with one small kernel.
+spex_status_t send_patches(spex_tree *t, hipStream_t stream) {
+  std::vector<int32_t> &pp = t->pending_patches;
+  const size_t n_in = pp.size() / 3;
+  const spex_status_t rs = stage_reserve(t, n_in * 2 * sizeof(int32_t));
+  if (rs != SPEX_OK) return rs;
+  int32_t *h = static_cast<int32_t *>(t->h_stage);
+  size_t n = 0;
+  for (size_t i = 0; i < n_in; ++i) {
+    const int arr = kPatchTarget[pp[3 * i]];
+    const size_t idx = static_cast<size_t>(pp[3 * i + 1]);
+    if (idx >= t->blob_ints[arr]) continue;  // that list is not on the device
+    h[2 * n] = static_cast<int32_t>(t->blob_off[arr] / sizeof(int32_t) + idx);
+    h[2 * n + 1] = pp[3 * i + 2];
+    ++n;
+  }
+  pp.clear();
+  if (n == 0) return SPEX_OK;
+  const size_t bytes = n * 2 * sizeof(int32_t);
+  if (bytes > t->d_patch_cap) {
+    if (t->d_patch) HIP_TRY(hipFree(t->d_patch));
+    t->d_patch = nullptr;
+    t->d_patch_cap = 0;
+    const size_t cap = align_up(bytes + bytes / 2, 1 << 16);
+    HIP_TRY(hipMalloc(&t->d_patch, cap));
+    t->d_patch_cap = cap;
+  }
+  const spex_status_t ss = stage_send(t, t->d_patch, bytes, stream);
+  if (ss != SPEX_OK) return ss;
+  HIP_TRY(spex::launch_patch(static_cast<int32_t *>(t->d_plan), static_cast<const int32_t *>(t->d_patch),
+                             static_cast<int32_t>(n), stream));
   return SPEX_OK;
 }
 
@@ -299,6 +370,7 @@ void spex_tree_destroy(spex_tree_t *t) {
   const bool used_device = t->d_plan || t->d_part_o || t->h_stage || t->stage_event || !t->prof.empty();
   if (used_device) (void)hipDeviceSynchronize();
   if (t->d_plan) (void)hipFree(t->d_plan);
+  if (t->d_patch) (void)hipFree(t->d_patch);
   if (t->d_part_o) (void)hipFree(t->d_part_o);
   if (t->d_part_ml) (void)hipFree(t->d_part_ml);
   if (t->h_stage) (void)hipHostFree(t->h_stage);
@@ -395,21 +467,30 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   if (!(sm_scale > 0.f) || std::isinf(sm_scale)) return SPEX_ERR_INVALID_ARG;
   if (n_leaves == 0) return SPEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  bool rebuilt = false;
-  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &rebuilt);
+  int plan_state = 0;
+  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
-  if (!t->plan_on_device) {
+  spex::Plan &pl = t->plan;
+  // Which kernels: the tree-walk kernel when its lists exist and fill the chip (or every work item
+  // is short anyway); else shared-prefix + suffix + merge, which can split long paths.  Only the
+  // lists of the chosen kernels are built.
+  const bool want_walk = (t->kernel_mode == 0 || t->kernel_mode == 3) && spex::has_mfma_kernel(t->shape);
+  if (want_walk) t->planner.ensure_walk(*t->pt, &pl);
+  const bool walk_possible = want_walk && pl.walk_ok;
+  if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
+  const bool use_walk = walk_possible && (t->kernel_mode == 3 || pl.walk_real_items >= 128 ||
+                                          pl.walk_max_item_blocks <= 64);
+  if (!use_walk) {
+    const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &pl));
+    if (ss != SPEX_OK) return ss;
+  }
+  if (!t->plan_on_device || (use_walk ? !t->device_has_walk : !t->device_has_split)) {
     const spex_status_t us = upload_plan(t, stream);
     if (us != SPEX_OK) return us;
+  } else if (!t->pending_patches.empty()) {
+    const spex_status_t us = send_patches(t, stream);
+    if (us != SPEX_OK) return us;
   }
-  const spex::Plan &pl = t->plan;
-  // Which kernels: the tree-walk kernel when its lists exist and fill the chip (or every work item
-  // is short anyway); else shared-prefix + suffix + merge, which can split long paths.
-  const bool walk_possible = pl.walk_ok && spex::has_mfma_kernel(t->shape);
-  if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
-  const bool use_walk =
-      walk_possible && (t->kernel_mode == 3 ||
-                        (t->kernel_mode == 0 && (pl.walk_real_items >= 128 || pl.walk_max_item_blocks <= 64)));
   const DevicePlan &dp = t->dplan;
 
   spex_tree::ProfSlot *slot = nullptr;
@@ -444,13 +525,13 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     HIP_TRY(bracket(3, true));
     HIP_TRY(spex::launch_tree_walk(t->shape, wa, pl.walk_row_tiles, pl.walk_waves, stream));
     HIP_TRY(bracket(3, false));
-    t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
+    t->info[0] = pl.unique_tokens;
     t->info[1] = pl.prefix_tokens;
     t->info[2] = pl.suffix_tokens;
     t->info[3] = pl.walk_real_items;
     t->info[4] = pl.walk_block_visits;
     t->info[5] = 0;
-    t->info[6] = rebuilt ? 1 : 0;
+    t->info[6] = plan_state;
     t->info[7] = pl.walk_row_tiles + 256 * pl.walk_waves;
     return SPEX_OK;
   }
@@ -524,13 +605,13 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   HIP_TRY(spex::launch_merge(t->shape, m, stream));
   HIP_TRY(bracket(2, false));
 
-  t->info[0] = pl.prefix_tokens + pl.suffix_tokens;
+  t->info[0] = pl.unique_tokens;
   t->info[1] = pl.prefix_tokens;
   t->info[2] = pl.suffix_tokens;
   t->info[3] = n_prefix_items + n_coop_items;
   t->info[4] = n_suffix_items;
   t->info[5] = pl.n_partial_rows;
-  t->info[6] = rebuilt ? 1 : 0;
+  t->info[6] = plan_state;
   t->info[7] = 0;
   return SPEX_OK;
 }
@@ -591,9 +672,12 @@ spex_status_t spex_tree_stats(const spex_tree_t *t, int64_t *live_nodes, int64_t
 spex_status_t spex_tree_plan_dump(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
                                   int32_t n_leaves, spex_plan_view_t *out) {
   if (!t || !out || n_leaves < 0 || (n_leaves > 0 && !leaves)) return SPEX_ERR_INVALID_ARG;
-  bool rebuilt = false;
-  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &rebuilt);
+  int plan_state = 0;
+  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
+  t->planner.ensure_csr(*t->pt, &t->plan);
+  const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &t->plan));
+  if (ss != SPEX_OK) return ss;
   const spex::Plan &pl = t->plan;
   spex_plan_view_t v{};
   v.n_leaves = n_leaves;
@@ -686,14 +770,16 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
 spex_status_t spex_tree_walk_dump(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
                                   int32_t n_leaves, spex_walk_view_t *out) {
   if (!t || !out || n_leaves < 0 || (n_leaves > 0 && !leaves)) return SPEX_ERR_INVALID_ARG;
-  bool rebuilt = false;
-  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &rebuilt);
+  int plan_state = 0;
+  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
+  t->planner.ensure_walk(*t->pt, &t->plan);
   const spex::Plan &pl = t->plan;
   spex_walk_view_t v{};
   v.available = pl.walk_ok ? 1 : 0;
   v.row_tiles = pl.walk_row_tiles;
   v.waves = pl.walk_waves;
+  v.plan_state = plan_state;
   v.n_row_blocks = pl.walk_ok ? static_cast<int32_t>(pl.walk_rb.size() / pl.rb_ints()) : 0;
   v.n_blocks = static_cast<int32_t>(pl.walk_blocks.size() / spex::Plan::kBlockInts);
   v.n_qt = static_cast<int32_t>(pl.walk_qt.size() / 2);

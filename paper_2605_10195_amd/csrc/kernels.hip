@@ -1513,6 +1513,20 @@ hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, int wav
                     : launch_walk_nw<kFP8, 128>(sh, a, ntw, waves, stream);
 }
 
+namespace {
+// blob[pairs[2i]] = pairs[2i + 1]: brings the device copy of a plan up to date after appends.
+__global__ __launch_bounds__(256) void spex_patch_plan_kernel(int32_t *blob, const int32_t *pairs, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) blob[pairs[2 * i]] = pairs[2 * i + 1];
+}
+}  // namespace
+
+hipError_t launch_patch(int32_t *blob, const int32_t *pairs, int32_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(spex_patch_plan_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, blob, pairs, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream) {
   if (a.n_qtok <= 0) return hipSuccess;
   const int vec = (sh.D % 4 == 0) ? 4 : 1;

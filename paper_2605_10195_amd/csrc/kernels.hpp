@@ -93,6 +93,8 @@ hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream)
 hipError_t launch_scatter(const Shape &sh, const ScatterArgs &a, hipStream_t stream);
 hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t stream);
 bool has_mfma_kernel(const Shape &sh);
+// blob[pairs[2i]] = pairs[2i+1] for i < n (all DEVICE): patches the device copy of a plan.
+hipError_t launch_patch(int32_t *blob, const int32_t *pairs, int32_t n, hipStream_t stream);
 // Cooperative shared-prefix kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront (64 * ntw rows
 // per workgroup).  One work item per workgroup.  Only for shapes with has_mfma_kernel().
 hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream);

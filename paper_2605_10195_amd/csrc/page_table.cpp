@@ -22,6 +22,7 @@ int32_t PageTable::fork(int32_t parent, int32_t n) {
   if (parent != kNoNode) nodes_[parent].n_live_children += n;
   live_nodes_ += n;
   ++version_;
+  ++structure_version_;
   return first;
 }
 
@@ -43,6 +44,7 @@ bool PageTable::append(int32_t u, int32_t n_tokens, int32_t *first_new) {
   }
   nd.n_tokens += n_tokens;
   ++version_;
+  if (need > 0) ++structure_version_;
   return true;
 }
 
@@ -64,6 +66,7 @@ void PageTable::prune(int32_t u) {
     for (auto it = nd.children.rbegin(); it != nd.children.rend(); ++it) stack.push_back(*it);
   }
   ++version_;
+  ++structure_version_;
 }
 
 }  // namespace spex

@@ -33,6 +33,9 @@ class PageTable {
   bool valid(int32_t u) const { return u >= 0 && u < num_nodes() && nodes_[u].alive; }
   const Node &node(int32_t u) const { return nodes_[u]; }
   uint64_t version() const { return version_; }
+  // Bumped by fork, prune and every append that starts a new page; appends that only fill up a
+  // node's last page leave it unchanged.
+  uint64_t structure_version() const { return structure_version_; }
 
   // Creates n children under parent (kNoNode: roots); returns the first new id.
   int32_t fork(int32_t parent, int32_t n);
@@ -64,6 +67,7 @@ class PageTable {
   std::vector<int32_t> free_;  // stack, top = back()
   int64_t live_nodes_ = 0;
   uint64_t version_ = 1;       // bumped by every mutation; the planner's cache key
+  uint64_t structure_version_ = 1;
 };
 
 }  // namespace spex

@@ -17,78 +17,123 @@ int32_t clamp32(int64_t v, int32_t lo, int32_t hi) {
 
 struct Segment {
   std::vector<int32_t> ids, valid, pos;
+  std::vector<int32_t> last_of;  // node whose last page the entry is, else -1
   int32_t qt_begin = 0, qt_count = 0;
 };
 
 }  // namespace
 
-PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
+PlanError Planner::begin(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
                          int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
                          int32_t prefix_chunk_pages, int32_t suffix_chunk_pages,
                          int32_t walk_row_tiles, int32_t walk_waves, Plan *plan) {
   if (n_leaves < 0 || (n_leaves > 0 && !leaves)) return PlanError::kInvalid;
-  const int32_t P = pt.page_size();
-  const int32_t G = num_q_heads / num_kv_heads;
   const int32_t N = pt.num_nodes();
   Plan &pl = *plan;
   pl = Plan();
   pl.req_leaves.assign(leaves, leaves + n_leaves);
   if (q_lens) pl.req_q_lens.assign(q_lens, q_lens + n_leaves);
   pl.table_version = pt.version();
+  pl.structure_version = pt.structure_version();
   pl.req_prefix_chunk = prefix_chunk_pages;
   pl.req_suffix_chunk = suffix_chunk_pages;
   pl.req_walk_row_tiles = walk_row_tiles;
   pl.req_walk_waves = walk_waves;
+  pl.num_q_heads = num_q_heads;
+  pl.num_kv_heads = num_kv_heads;
 
   if (static_cast<int32_t>(live_.size()) < N) {
     live_.resize(N, 0);
     pos0_.resize(N, 0);
     gindex_.resize(N, -1);
+    last_pg_.resize(N, -1);
   }
-  auto reset = [&]() {
-    for (int32_t u : touched_) {
-      live_[u] = 0;
-      gindex_[u] = -1;
-    }
-    touched_.clear();
-  };
 
-  // ---- paths, CSR, limits, live counts
-  std::vector<int32_t> path_indptr(n_leaves + 1, 0), path_nodes, qoff(n_leaves, 0);
-  pl.leaf_indptr.assign(1, 0);
+  // ---- paths and limits
+  if (static_cast<int32_t>(stamp_.size()) < N) {
+    stamp_.resize(N, 0);
+    slot_.resize(N, 0);
+  }
+  if (stamp_next_ == std::numeric_limits<int32_t>::max()) {
+    std::fill(stamp_.begin(), stamp_.end(), 0);
+    stamp_next_ = 1;
+  }
+  const int32_t st_seen = stamp_next_++;
+  pl.path_indptr.assign(n_leaves + 1, 0);
+  pl.qoff.assign(n_leaves, 0);
+  pl.req_tokens.assign(n_leaves, 0);
   std::vector<int32_t> tmp;
   for (int32_t i = 0; i < n_leaves; ++i) {
     const int32_t leaf = leaves[i];
     const int32_t ql = q_lens ? q_lens[i] : 1;
-    if (!pt.valid(leaf)) {
-      reset();
-      return PlanError::kBadNode;
-    }
+    if (!pt.valid(leaf)) return PlanError::kBadNode;
     tmp.clear();
     for (int32_t u = leaf; u != kNoNode; u = pt.node(u).parent) tmp.push_back(u);
     int64_t T = 0;
     for (auto it = tmp.rbegin(); it != tmp.rend(); ++it) {
       const int32_t u = *it;
-      path_nodes.push_back(u);
+      pl.path_nodes.push_back(u);
       pos0_[u] = static_cast<int32_t>(T);
-      if (live_[u]++ == 0) touched_.push_back(u);
-      const Node &nd = pt.node(u);
-      for (size_t k = 0; k < nd.pages.size(); ++k) {
-        pl.leaf_pages.push_back(nd.pages[k]);
-        pl.leaf_valid.push_back(pt.page_valid(u, static_cast<int32_t>(k)));
+      T += pt.node(u).n_tokens;
+      if (stamp_[u] != st_seen) {
+        stamp_[u] = st_seen;
+        pl.unique_tokens += pt.node(u).n_tokens;
       }
-      T += nd.n_tokens;
     }
-    path_indptr[i + 1] = static_cast<int32_t>(path_nodes.size());
-    pl.leaf_indptr.push_back(static_cast<int32_t>(pl.leaf_pages.size()));
-    if (ql < 1 || ql > T || T >= (1 << 24)) {
-      reset();
-      if (ql < 1) return PlanError::kInvalid;
-      return ql > T ? PlanError::kEmptyPath : PlanError::kTooLarge;  // positions are packed in 24 bits
-    }
-    qoff[i] = static_cast<int32_t>(pl.qt_limit.size());
+    pl.path_indptr[i + 1] = static_cast<int32_t>(pl.path_nodes.size());
+    pl.req_tokens[i] = pt.node(leaf).n_tokens;
+    if (ql < 1) return PlanError::kInvalid;
+    if (ql > T) return PlanError::kEmptyPath;
+    if (T >= (1 << 24)) return PlanError::kTooLarge;  // positions are packed in 24 bits
+    pl.qoff[i] = static_cast<int32_t>(pl.qt_limit.size());
     for (int32_t j = 0; j < ql; ++j) pl.qt_limit.push_back(static_cast<int32_t>(T) - ql + 1 + j);
   }
+  pl.valid = true;
+  return PlanError::kOk;
+}
+
+// Root-to-node page lists of the requested nodes (CSR); only the dump and the tests read them.
+void Planner::ensure_csr(const PageTable &pt, Plan *plan) {
+  Plan &pl = *plan;
+  if (pl.has_csr) return;
+  const int32_t n_leaves = static_cast<int32_t>(pl.req_leaves.size());
+  pl.leaf_indptr.assign(1, 0);
+  for (int32_t i = 0; i < n_leaves; ++i) {
+    for (int32_t k = pl.path_indptr[i]; k < pl.path_indptr[i + 1]; ++k) {
+      const int32_t u = pl.path_nodes[k];
+      const Node &nd = pt.node(u);
+      for (size_t pg = 0; pg < nd.pages.size(); ++pg) {
+        pl.leaf_pages.push_back(nd.pages[pg]);
+        pl.leaf_valid.push_back(pt.page_valid(u, static_cast<int32_t>(pg)));
+      }
+    }
+    pl.leaf_indptr.push_back(static_cast<int32_t>(pl.leaf_pages.size()));
+  }
+  pl.has_csr = true;
+}
+
+// Shared-prefix groups, suffixes, chunks, partial slots, merge lists and the work items of the
+// shared-prefix / suffix / merge kernels.
+PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
+  Plan &pl = *plan;
+  if (pl.has_split) return PlanError::kOk;
+  const int32_t P = pt.page_size();
+  const int32_t num_kv_heads = pl.num_kv_heads;
+  const int32_t G = pl.num_q_heads / pl.num_kv_heads;
+  const int32_t n_leaves = static_cast<int32_t>(pl.req_leaves.size());
+  const int32_t *q_lens = pl.req_q_lens.empty() ? nullptr : pl.req_q_lens.data();
+  const std::vector<int32_t> &path_indptr = pl.path_indptr, &path_nodes = pl.path_nodes, &qoff = pl.qoff;
+  const int32_t prefix_chunk_pages = pl.req_prefix_chunk, suffix_chunk_pages = pl.req_suffix_chunk;
+  auto reset = [&]() {
+    for (int32_t u : touched_) {
+      live_[u] = 0;
+      gindex_[u] = -1;
+      last_pg_[u] = -1;
+    }
+    touched_.clear();
+  };
+  for (int32_t k : path_nodes)
+    if (live_[k]++ == 0) touched_.push_back(k);
   const int32_t NQ = static_cast<int32_t>(pl.qt_limit.size());
 
   // ---- groups
@@ -129,6 +174,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
       s.ids.push_back(nd.pages[k]);
       s.valid.push_back(v);
       s.pos.push_back(t);
+      s.last_of.push_back(k + 1 == nd.pages.size() ? u : -1);
       t += v;
     }
   };
@@ -205,6 +251,8 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
       pl.pg_id.insert(pl.pg_id.end(), s.ids.begin() + a, s.ids.begin() + b);
       pl.pg_valid.insert(pl.pg_valid.end(), s.valid.begin() + a, s.valid.begin() + b);
       pl.pg_pos.insert(pl.pg_pos.end(), s.pos.begin() + a, s.pos.begin() + b);
+      for (int32_t k = a; k < b; ++k)
+        if (s.last_of[k] >= 0) last_pg_[s.last_of[k]] = static_cast<int32_t>(pl.pg_id.size()) - (b - k);
       for (int32_t r = 0; r < s.qt_count; ++r)
         parts[pl.qt_list[s.qt_begin + r]].emplace_back(static_cast<int32_t>(pbase) + r * G, rows);
       pbase += static_cast<int64_t>(rows) * num_kv_heads;
@@ -222,8 +270,33 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
       if (!is_final[t]) pl.merge_qt.push_back(t);
   }
   pl.n_partial_rows = pbase;
+  // Where an append to a requested node shows up: the page entry of its last page, whether that
+  // entry belongs to a group, and the positions of its query tokens in qt_list.
+  pl.req_split_pg.assign(n_leaves, -1);
+  pl.req_in_group.assign(n_leaves, 0);
+  pl.req_qtpos_indptr.assign(1, 0);
+  {
+    std::vector<int32_t> fill2(group_qt_begin.begin(), group_qt_begin.end() - 1);
+    for (int32_t i = 0; i < n_leaves; ++i) {
+      const int32_t ql = q_lens ? q_lens[i] : 1;
+      const int32_t u = pl.req_leaves[i];
+      pl.req_split_pg[i] = last_pg_[u];
+      pl.req_in_group[i] = gindex_[u] >= 0 ? 1 : 0;
+      for (int32_t k = path_indptr[i]; k < path_indptr[i + 1]; ++k) {
+        const int32_t gi = gindex_[path_nodes[k]];
+        if (gi < 0) continue;
+        pl.req_qtpos.push_back(fill2[gi]);
+        fill2[gi] += ql;
+      }
+      pl.req_qtpos.push_back(n_group_qt + qoff[i]);
+      pl.req_qtpos_indptr.push_back(static_cast<int32_t>(pl.req_qtpos.size()));
+    }
+  }
   reset();
-  if (overflow) return PlanError::kTooLarge;
+  if (overflow) {
+    pl.valid = false;
+    return PlanError::kTooLarge;
+  }
 
   pl.part_indptr.assign(1, 0);
   for (const auto &lst : parts) {
@@ -300,9 +373,7 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
     pl.qt_rec[2 * i] = pl.qt_list[i];
     pl.qt_rec[2 * i + 1] = pl.qt_limit[pl.qt_list[i]];
   }
-  build_walk(pt, q_lens, n_leaves, G, num_kv_heads, walk_row_tiles, walk_waves, path_indptr, path_nodes, qoff,
-             plan);
-  pl.valid = true;
+  pl.has_split = true;
   return PlanError::kOk;
 }
 
@@ -338,11 +409,15 @@ PlanError Planner::build(const PageTable &pt, const int32_t *leaves, const int32
 //    for lane 0, 1, ..: the lane's r-th row block, or padding if the lane has run out and more
 //    than one lane exists; each for kv head 0 .. Hkv-1.  Workgroup b runs on XCD b % 8, so the row
 //    blocks of one root and kv head follow each other on one XCD and share its L2.
-void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_leaves, int32_t G,
-                         int32_t num_kv_heads, int32_t walk_row_tiles, int32_t walk_waves,
-                         const std::vector<int32_t> &path_indptr,
-                         const std::vector<int32_t> &path_nodes, const std::vector<int32_t> &qoff,
-                         Plan *plan) {
+void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
+  if (plan->has_walk) return;
+  plan->has_walk = true;
+  const int32_t n_leaves = static_cast<int32_t>(plan->req_leaves.size());
+  const int32_t *q_lens = plan->req_q_lens.empty() ? nullptr : plan->req_q_lens.data();
+  const int32_t num_kv_heads = plan->num_kv_heads, G = plan->num_q_heads / plan->num_kv_heads;
+  const int32_t walk_row_tiles = plan->req_walk_row_tiles, walk_waves = plan->req_walk_waves;
+  const std::vector<int32_t> &path_indptr = plan->path_indptr, &path_nodes = plan->path_nodes,
+                             &qoff = plan->qoff;
   Plan &pl = *plan;
   pl.walk_ok = false;
   pl.walk_row_tiles = 0;
@@ -390,6 +465,8 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
     return;
   }
   pl.walk_row_tiles = ntw;
+  pl.req_walk_blk.assign(n_leaves, -1);
+  pl.req_walk_qt.assign(n_leaves, -1);
   const int32_t C = 16 * ntw;
   // Measured on MI355X, two workgroups of 4 wavefronts per compute unit beat one of 8 on every
   // workload tried (the barrier of the shared phase then stalls only half of the unit), so 4 is
@@ -454,8 +531,10 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
     rb_rec[0] = root_ids[root_slot];
     cur.clear();
   };
+  int32_t last_blk_of_node = -1;  // set by emit_node: block that holds the node's last page
   auto emit_node = [&](const NodeRange &nr) -> int32_t {
     const Node &nd = pt.node(nr.node);
+    last_blk_of_node = -1;
     const int32_t n = static_cast<int32_t>(nd.pages.size());
     int32_t made = 0;
     for (int32_t k = 0; k < n; k += 2, ++made) {
@@ -465,6 +544,7 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
       const int32_t pos_a = pos0_[nr.node] + k * P, pos_b = pos_a + P;
       const int32_t end = has_b ? pos_b + vb : pos_a + va;
       const bool masked = va != P || !has_b || vb != P || nr.minlim < end;
+      if (k + 2 >= n) last_blk_of_node = static_cast<int32_t>(pl.walk_blocks.size() / Plan::kBlockInts);
       const int32_t rec[Plan::kBlockInts] = {nd.pages[k],
                                              (pos_a << 7) | va,
                                              has_b ? nd.pages[k + 1] : nd.pages[k],
@@ -499,13 +579,23 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
     }
     rb_rec[1] = static_cast<int32_t>(pl.walk_blocks.size() / Plan::kBlockInts);
     int64_t total = 0;
+    auto note_last = [&](const NodeRange &nr) {  // requests of this row block that asked for nr.node
+      for (const Placed &pc : cur)
+        if (pl.req_leaves[pc.req] == nr.node) pl.req_walk_blk[pc.req] = last_blk_of_node;
+    };
     for (const NodeRange &nr : nodes)
-      if (nr.lo / C != (nr.hi - 1) / C) rb_rec[2] += emit_node(nr);
+      if (nr.lo / C != (nr.hi - 1) / C) {
+        rb_rec[2] += emit_node(nr);
+        note_last(nr);
+      }
     total += rb_rec[2];
     int32_t longest_private = 0;
     for (int32_t w = 0; w < NW; ++w) {
       for (const NodeRange &nr : nodes)
-        if (nr.lo / C == (nr.hi - 1) / C && nr.lo / C == w) rb_rec[3 + w] += emit_node(nr);
+        if (nr.lo / C == (nr.hi - 1) / C && nr.lo / C == w) {
+          rb_rec[3 + w] += emit_node(nr);
+          note_last(nr);
+        }
       total += rb_rec[3 + w];
       longest_private = std::max(longest_private, rb_rec[3 + w]);
     }
@@ -534,6 +624,7 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
       }
     }
     if (rb_rec[3 + 2 * NW + wave] == 0) rb_rec[3 + NW + wave] = static_cast<int32_t>(pl.walk_qt.size() / 2);
+    pl.req_walk_qt[idx] = static_cast<int32_t>(pl.walk_qt.size() / 2);
     for (int32_t j = 0; j < ql; ++j) {
       pl.walk_qt.push_back(qoff[idx] + j);
       pl.walk_qt.push_back(pl.qt_limit[qoff[idx] + j]);
@@ -583,6 +674,80 @@ void Planner::build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_l
       }
     }
   pl.walk_ok = true;
+}
+
+// Appends that only filled up last pages (same structure version): the lists stay as they are
+// except for the valid count of each grown node's last page and the limits of its query tokens.
+// Mask flags are left alone: a flag that a fresh plan would no longer set only costs the masked
+// code path, never correctness.
+bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t> *dev_patches) {
+  Plan &pl = *plan;
+  if (!pl.valid || pl.structure_version != pt.structure_version()) return false;
+  const int32_t n_leaves = static_cast<int32_t>(pl.req_leaves.size());
+  const int32_t N = pt.num_nodes();
+  if (static_cast<int32_t>(stamp_.size()) < N) {
+    stamp_.resize(N, 0);
+    slot_.resize(N, 0);
+  }
+  if (stamp_next_ == std::numeric_limits<int32_t>::max()) {
+    std::fill(stamp_.begin(), stamp_.end(), 0);
+    stamp_next_ = 1;
+  }
+  const int32_t st = stamp_next_++;
+  auto patch = [&](int32_t array, int64_t index, int32_t value) {
+    dev_patches->push_back(array);
+    dev_patches->push_back(static_cast<int32_t>(index));
+    dev_patches->push_back(value);
+  };
+  const bool walk = pl.has_walk && pl.walk_ok;
+  for (int32_t i = 0; i < n_leaves; ++i) {
+    const int32_t u = pl.req_leaves[i];
+    const Node &nd = pt.node(u);
+    const int32_t delta = nd.n_tokens - pl.req_tokens[i];
+    if (delta == 0) continue;
+    if (delta < 0 || nd.pages.empty()) return false;
+    const int32_t ql = pl.req_q_lens.empty() ? 1 : pl.req_q_lens[i];
+    const int32_t new_valid = pt.page_valid(u, static_cast<int32_t>(nd.pages.size()) - 1);
+    const int32_t q0 = pl.qoff[i];
+    if (pl.qt_limit[q0 + ql - 1] + delta >= (1 << 24)) return false;
+    for (int32_t j = 0; j < ql; ++j) pl.qt_limit[q0 + j] += delta;
+    const bool first_visit = stamp_[u] != st;
+    stamp_[u] = st;
+    if (first_visit) pl.unique_tokens += delta;
+    if (pl.has_csr) pl.leaf_valid[pl.leaf_indptr[i + 1] - 1] = new_valid;
+    if (pl.has_split) {
+      const int32_t pg = pl.req_split_pg[i];
+      if (pg < 0) return false;
+      pl.pg_valid[pg] = new_valid;
+      pl.pg_rec[2 * pg + 1] = (pl.pg_pos[pg] << 7) | new_valid;
+      if (first_visit) {
+        patch(kPatchPgRec, 2 * static_cast<int64_t>(pg) + 1, pl.pg_rec[2 * pg + 1]);
+        (pl.req_in_group[i] ? pl.prefix_tokens : pl.suffix_tokens) += delta;
+      }
+      for (int32_t e = pl.req_qtpos_indptr[i]; e < pl.req_qtpos_indptr[i + 1]; ++e)
+        for (int32_t j = 0; j < ql; ++j) {
+          const int64_t at = 2 * static_cast<int64_t>(pl.req_qtpos[e] + j) + 1;
+          pl.qt_rec[at] = pl.qt_limit[q0 + j];
+          patch(kPatchQtRec, at, pl.qt_rec[at]);
+        }
+    }
+    if (walk) {
+      const int32_t blk = pl.req_walk_blk[i];
+      if (blk < 0) return false;
+      int32_t *rec = &pl.walk_blocks[static_cast<size_t>(blk) * Plan::kBlockInts];
+      const int slot = rec[3] != 0 ? 3 : 1;  // the last page is page b if the block has one
+      rec[slot] = (rec[slot] & ~127) | new_valid;
+      patch(kPatchWalkBlocks, static_cast<int64_t>(blk) * Plan::kBlockInts + slot, rec[slot]);
+      for (int32_t j = 0; j < ql; ++j) {
+        const int64_t at = 2 * static_cast<int64_t>(pl.req_walk_qt[i] + j) + 1;
+        pl.walk_qt[at] = pl.qt_limit[q0 + j];
+        patch(kPatchWalkQt, at, pl.walk_qt[at]);
+      }
+    }
+    pl.req_tokens[i] = nd.n_tokens;
+  }
+  pl.table_version = pt.version();
+  return true;
 }
 
 }  // namespace spex

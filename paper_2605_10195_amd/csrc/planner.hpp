@@ -32,9 +32,22 @@ namespace spex {
 struct Plan {
   // ---- cache key
   std::vector<int32_t> req_leaves, req_q_lens;
-  uint64_t table_version = 0;
+  uint64_t table_version = 0, structure_version = 0;
   int32_t req_prefix_chunk = -1, req_suffix_chunk = -1;
+  int32_t num_q_heads = 0, num_kv_heads = 0;
   bool valid = false;
+  // The lists are built in stages, each on first use: the page CSR (dump and tests only), the
+  // split lists (shared-prefix / suffix / merge kernels) and the tree-walk lists.
+  bool has_csr = false, has_split = false, has_walk = false;
+
+  // ---- common to all stages
+  std::vector<int32_t> path_indptr, path_nodes;  // root-to-node paths of the requests
+  std::vector<int32_t> qoff;                     // first query token of each request
+  std::vector<int32_t> req_tokens;               // tokens of each requested node when planned / patched
+  int64_t unique_tokens = 0;                     // KV tokens on the requested paths, each node once
+  // ---- where an append to a requested node shows up (see Planner::patch_lengths)
+  std::vector<int32_t> req_split_pg, req_in_group, req_qtpos_indptr, req_qtpos;
+  std::vector<int32_t> req_walk_blk, req_walk_qt;
 
   // ---- canonical arrays (see spex_plan_view_t)
   std::vector<int32_t> leaf_indptr, leaf_pages, leaf_valid, qt_limit, group_node;
@@ -85,19 +98,25 @@ struct Plan {
 
 enum class PlanError { kOk, kBadNode, kEmptyPath, kInvalid, kTooLarge };
 
+// Device arrays a length patch can touch; a patch is the triple {array, int index, new value}.
+enum PatchArray : int32_t { kPatchPgRec = 0, kPatchQtRec = 1, kPatchWalkBlocks = 2, kPatchWalkQt = 3 };
+
 class Planner {
  public:
-  PlanError build(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
+  // Validates the request, walks the paths and computes the limits; the lists follow on demand.
+  PlanError begin(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
                   int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
                   int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, int32_t walk_row_tiles,
                   int32_t walk_waves, Plan *plan);
+  void ensure_csr(const PageTable &pt, Plan *plan);
+  PlanError ensure_split(const PageTable &pt, Plan *plan);
+  void ensure_walk(const PageTable &pt, Plan *plan);
+  // Brings a plan up to date after appends that started no new page (same structure version).
+  // Returns false if that is not possible (the caller then plans afresh).
+  bool patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t> *dev_patches);
 
  private:
-  void build_walk(const PageTable &pt, const int32_t *q_lens, int32_t n_leaves, int32_t G,
-                  int32_t num_kv_heads, int32_t walk_row_tiles, int32_t walk_waves,
-                  const std::vector<int32_t> &path_indptr, const std::vector<int32_t> &path_nodes,
-                  const std::vector<int32_t> &qoff, Plan *plan);
-  std::vector<int32_t> multi_;
+  std::vector<int32_t> multi_, last_pg_;
   std::vector<int32_t> stamp_, slot_;  // per-node scratch of build_walk, valid where stamp_ == current stamp
   int32_t stamp_next_ = 1;
   // dense per-node scratch, reset through touched_

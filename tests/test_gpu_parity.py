@@ -230,9 +230,11 @@ def test_duplicate_interior_and_empty_requests():
         assert_close(run_gpu(wl, kernel_mode=mode), run_oracle(wl), "bf16", f"{wl.name} mode {mode}")
 
 
-def test_decode_loop_replans_after_every_append():
+@pytest.mark.parametrize("mode", [2, 3])
+def test_decode_loop_patches_or_replans_after_every_append(mode):
     wl = sw.bfs_tot(n_queries=2, prompt=48, step=20)
-    tree = build_gpu_tree(wl, extra_pages=64)
+    tree = build_gpu_tree(wl, extra_pages=64, kernel_mode=mode)
+    states = set()
     from oracle.adapters import OracleSink, queries_fp64
     sink = OracleSink.for_workload(wl)
     sw.replay(wl, sink)
@@ -245,15 +247,19 @@ def test_decode_loop_replans_after_every_append():
         for i, leaf in enumerate(wl.leaves):
             tree.append_step(leaf, k[i:i + 1].contiguous(), v[i:i + 1].contiguous())
             sink.append(leaf, k[i:i + 1], v[i:i + 1])
+        # the first call plans afresh; later ones only when an append has started a page
+        new_page = step == 0 or tree.node_info(wl.leaves[0])["n_tokens"] % 16 == 1
         out, lse = tree.decode_attention(wl.leaves, None, q, wl.sm_scale)
-        rebuilt = tree.last_launch_info()["plan_rebuilt"]
+        state = tree.last_launch_info()["plan_rebuilt"]          # 1 planned afresh, 2 patched
+        states.add(state)
         out2, _ = tree.decode_attention(wl.leaves, None, q, wl.sm_scale)
-        assert rebuilt == 1 and tree.last_launch_info()["plan_rebuilt"] == 0
-        if step % 6 == 5:
+        assert state == (1 if new_page else 2) and tree.last_launch_info()["plan_rebuilt"] == 0
+        if step % 3 == 2 or new_page:
             ref = sink.tree.attention(wl.leaves, None, qd, wl.sm_scale)
             got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
             assert_close(got, ref, "bf16", f"decode step {step}")
             assert torch.equal(out, out2)
+    assert states == {1, 2}
     tree.close()
 
 

@@ -319,3 +319,59 @@ def test_walk_lists_not_available_for_wide_requests():
     assert max(wl.q_lens) * 8 > 64
     got = tree.walk_dump(wl.leaves, wl.q_lens)
     assert got["available"] == 0 and got["items"] == []
+
+
+# ------------------------------------------------------------------ length patches
+def grow_and_compare(wl, n_steps, seed):
+    """Append tokens to requested leaves step by step.  The library patches its cached lists when no
+    page is started; a second tree that replays everything and plans afresh must give the same
+    lists, except that a patched plan may keep mask flags a fresh plan no longer needs."""
+    n_pages = wl.peak_pages() + 2 * len(wl.leaves) + 8
+    tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
+    replay_both(wl, tree, ref)
+    rng = np.random.default_rng(seed)
+    childless = [u for u in sorted(set(wl.leaves)) if not ref.has_live_children(u)]
+    tree.plan_dump(wl.leaves, wl.q_lens)
+    tree.walk_dump(wl.leaves, wl.q_lens)
+    patched_seen = fresh_seen = 0
+    for step in range(n_steps):
+        grow = [u for u in childless if rng.random() < 0.7]
+        started_page = False
+        for u in grow:
+            n = int(rng.integers(1, 4))
+            started_page |= tree.append_new_pages(u, n) > 0
+            tree.append_step(u, None, None, n_tokens=n)
+            ref.append(u, n)
+        got_walk = tree.walk_dump(wl.leaves, wl.q_lens)
+        got_split = tree.plan_dump(wl.leaves, wl.q_lens)
+        if grow:
+            assert got_walk["plan_state"] == (1 if started_page else 2), step
+        want_split = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
+                              got_split["prefix_chunk_pages"], got_split["suffix_chunk_pages"])
+        want_walk = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads)
+        for k in PLAN_KEYS:
+            if k == "task_flags":
+                for a, b in zip(got_split[k], want_split[k]):
+                    assert a & 2 == b & 2 and (a & 1) >= (b & 1)
+            else:
+                assert got_split[k] == want_split[k], (step, k)
+        for k in WALK_KEYS:
+            if k == "blocks":
+                a, b = np.array(got_walk[k]).reshape(-1, 8), np.array(want_walk[k]).reshape(-1, 8)
+                assert np.array_equal(a[:, :5], b[:, :5]) and np.array_equal(a[:, 5] & 2, b[:, 5] & 2)
+                assert np.all((a[:, 5] & 1) >= (b[:, 5] & 1))
+            else:
+                assert got_walk[k] == want_walk[k], (step, k)
+        if grow:
+            patched_seen += not started_page
+            fresh_seen += started_page
+    return patched_seen, fresh_seen
+
+
+@pytest.mark.parametrize("wl", [
+    sw.bfs_tot(n_queries=2, prompt=40, step=19), sw.tot_with_drafts(n_queries=2, prompt=50, step=21),
+    sw.mcts_skewed(n_queries=4, prompt=(30, 90), step=(5, 40), max_leaves=12),
+    sw.random_trace(640, n_ops=60, max_tokens=40, max_q_len=3, heads=(8, 2, 64))], ids=lambda w: w.name)
+def test_length_patches_match_a_fresh_plan(wl):
+    patched, fresh = grow_and_compare(wl, 24, 5)
+    assert patched > 3 and fresh > 3          # both the patch path and the replan path were taken
