@@ -136,6 +136,22 @@ spex_status_t spex_tree_fork(spex_tree_t *tree, spex_node_t parent, int32_t n_ch
 spex_status_t spex_tree_append_step(spex_tree_t *tree, spex_node_t node, int32_t n_tokens,
                                     const void *k, const void *v, const float *k_scales,
                                     const float *v_scales, void *hip_stream);
+/*
+ * The decode iteration between two steps (Sec. 3.1: a step is tens to hundreds of tokens, generated
+ * one at a time; Alg. 2: all live branches are generated concurrently): append ONE token to each
+ * of n_nodes distinct nodes without live children, with one kernel launch.
+ *   nodes : HOST [n_nodes]
+ *   k, v  : DEVICE [n_nodes][num_kv_heads][head_dim] in kv_dtype (both NULL: page table only)
+ *   k_scales, v_scales : DEVICE fp32 [n_nodes][num_kv_heads], fp8 only: row i is used if node i's
+ *           token starts a new page and ignored otherwise
+ * All or nothing: if a node is unknown, repeated (SPEX_ERR_INVALID_ARG), has live children, or
+ * the pool has too few free pages for all of them, nothing is changed.  Pages are taken in the
+ * order of `nodes`.  Tokens that start no page leave the structure version of the tree unchanged,
+ * so the next decode_attention patches its cached lists instead of planning afresh.
+ */
+spex_status_t spex_tree_append_tokens(spex_tree_t *tree, const spex_node_t *nodes, int32_t n_nodes,
+                                      const void *k, const void *v, const float *k_scales,
+                                      const float *v_scales, void *hip_stream);
 /* Number of pages an append of n_tokens to node would newly start. */
 spex_status_t spex_tree_append_new_pages(const spex_tree_t *tree, spex_node_t node,
                                          int32_t n_tokens, int32_t *n_new_pages);

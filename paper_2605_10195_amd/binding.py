@@ -80,7 +80,7 @@ EXPORTS = [
     "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
-    "spex_tree_last_launch_info", "spex_tree_walk_dump",
+    "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens",
 ]
 
 
@@ -101,6 +101,7 @@ def _load():
     lib.spex_tree_fork.argtypes = [vp, i32, i32, _I32P]
     lib.spex_tree_append_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_append_new_pages.argtypes = [vp, i32, i32, _I32P]
+    lib.spex_tree_append_tokens.argtypes = [vp, _I32P, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_prune.argtypes = [vp, i32]
     lib.spex_tree_decode_attention.argtypes = [vp, _I32P, _I32P, i32, vp, vp, vp, f32, vp]
     lib.spex_tree_node_info.argtypes = [vp, i32, C.POINTER(NodeInfo)]
@@ -236,6 +237,15 @@ class SpexTree:
     # name used by the trace replay
     def append(self, node, k, v, k_scales=None, v_scales=None, n_tokens=None):
         self.append_step(node, k, v, k_scales, v_scales, n_tokens)
+
+    def append_tokens(self, nodes: Sequence[int], k: Optional[torch.Tensor], v: Optional[torch.Tensor],
+                      k_scales: Optional[torch.Tensor] = None, v_scales: Optional[torch.Tensor] = None):
+        """One token per node, one launch.  k, v: [len(nodes), Hkv, D] on the tree's device."""
+        na = _i32(nodes)
+        if k is not None:
+            assert k.is_contiguous() and v.is_contiguous() and k.shape == (len(na), self.Hkv, self.D)
+        _check(lib.spex_tree_append_tokens(self._h, _ptr(na), len(na), _dev(k), _dev(v), _dev(k_scales),
+                                           _dev(v_scales), _stream()))
 
     def prune(self, node: int) -> None:
         _check(lib.spex_tree_prune(self._h, node))

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -449,6 +450,75 @@ spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_
     for (int32_t i = 0; i < a.n_pages; ++i) a.page_ids[i] = nd.pages[pa + i];
     HIP_TRY(spex::launch_scatter(t->shape, a, stream));
   }
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_append_tokens(spex_tree_t *t, const spex_node_t *nodes, int32_t n_nodes,
+                                      const void *k, const void *v, const float *k_scales,
+                                      const float *v_scales, void *hip_stream) {
+  if (!t || n_nodes < 0 || (n_nodes > 0 && !nodes) || ((k == nullptr) != (v == nullptr)))
+    return SPEX_ERR_INVALID_ARG;
+  if (k && !t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
+  if (n_nodes == 0) return SPEX_OK;
+  // Check everything before touching the table: the call is all or nothing.
+  const int32_t P = t->cfg.page_size;
+  int64_t need = 0;
+  std::vector<int32_t> sorted(nodes, nodes + n_nodes);
+  std::sort(sorted.begin(), sorted.end());
+  for (int32_t i = 0; i < n_nodes; ++i) {
+    const int32_t u = sorted[i];
+    if (!t->pt->valid(u)) return SPEX_ERR_BAD_NODE;
+    if (i > 0 && sorted[i - 1] == u) return SPEX_ERR_INVALID_ARG;
+    if (t->pt->node(u).n_live_children > 0) return SPEX_ERR_NOT_LEAF;
+    if (t->pt->node(u).n_tokens >= INT32_MAX / 2) return SPEX_ERR_UNSUPPORTED;
+    need += t->pt->new_pages_needed(u, 1);
+  }
+  if (need > t->pt->free_pages()) return SPEX_ERR_OOM_PAGES;
+  if (k && t->cfg.kv_dtype == SPEX_FP8_E4M3 && need > 0 && (!k_scales || !v_scales))
+    return SPEX_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const size_t bytes = static_cast<size_t>(n_nodes) * 2 * sizeof(int32_t);
+  int32_t *h = nullptr;
+  if (k) {
+    const spex_status_t rs = stage_reserve(t, bytes);
+    if (rs != SPEX_OK) return rs;
+    if (bytes > t->d_patch_cap) {
+      if (t->d_patch) HIP_TRY(hipFree(t->d_patch));
+      t->d_patch = nullptr;
+      t->d_patch_cap = 0;
+      const size_t cap = align_up(bytes + bytes / 2, 1 << 16);
+      HIP_TRY(hipMalloc(&t->d_patch, cap));
+      t->d_patch_cap = cap;
+    }
+    h = static_cast<int32_t *>(t->h_stage);
+  }
+  for (int32_t i = 0; i < n_nodes; ++i) {
+    const int32_t u = nodes[i];
+    const int32_t old_tokens = t->pt->node(u).n_tokens;
+    int32_t first_new = 0;
+    t->pt->append(u, 1, &first_new);  // cannot fail: the pages were counted above
+    if (h) {
+      const spex::Node &nd = t->pt->node(u);
+      const int32_t pi = old_tokens / P;
+      h[2 * i] = nd.pages[pi];
+      h[2 * i + 1] = (old_tokens % P) | ((pi >= first_new ? 1 : 0) << 8);
+    }
+  }
+  if (!k) return SPEX_OK;
+  const spex_status_t ss = stage_send(t, t->d_patch, bytes, stream);
+  if (ss != SPEX_OK) return ss;
+  spex::AppendTokensArgs a{};
+  a.k_pool = t->cfg.k_pool;
+  a.v_pool = t->cfg.v_pool;
+  a.k_scale = t->cfg.k_scale;
+  a.v_scale = t->cfg.v_scale;
+  a.k_src = k;
+  a.v_src = v;
+  a.k_scale_src = k_scales;
+  a.v_scale_src = v_scales;
+  a.dst = static_cast<const int32_t *>(t->d_patch);
+  a.n_nodes = n_nodes;
+  HIP_TRY(spex::launch_append_tokens(t->shape, a, stream));
   return SPEX_OK;
 }
 

@@ -1386,6 +1386,40 @@ __global__ __launch_bounds__(256) void spex_scatter_kv_kernel(ScatterArgs a, Sha
   }
 }
 
+// One appended token per node: thread = (node, kv head, dim).  Writes the token's K and V element
+// into its slot; where the token starts a page it also zeroes the page's other slots (so that
+// nothing stale can be read from a partial page) and stores the page's fp8 scales.
+template <int KV, int LAYOUT>
+__global__ __launch_bounds__(256) void spex_append_tokens_kernel(AppendTokensArgs a, Shape sh) {
+  typedef typename std::conditional<KV == kF32, float,
+                                    typename std::conditional<KV == kBF16, uint16_t, uint8_t>::type>::type T;
+  const int D = sh.D, P = sh.P, H = sh.Hkv;
+  const int64_t total = static_cast<int64_t>(a.n_nodes) * H * D;
+  const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (tid >= total) return;
+  const int d = static_cast<int>(tid % D);
+  const int g = static_cast<int>((tid / D) % H);
+  const int node = static_cast<int>(tid / (static_cast<int64_t>(D) * H));
+  const int page = a.dst[2 * node], code = a.dst[2 * node + 1];
+  const int slot = code & 0xff;
+  const bool is_new = (code >> 8) != 0;
+  const int64_t tile = (static_cast<int64_t>(page) * sh.page_tiles + g) * (static_cast<int64_t>(P) * D);
+  T *kp = static_cast<T *>(a.k_pool) + tile, *vp = static_cast<T *>(a.v_pool) + tile;
+  kp[k_offset<KV, LAYOUT>(slot, d, D)] = static_cast<const T *>(a.k_src)[tid];
+  vp[v_offset<KV, LAYOUT>(slot, d, D)] = static_cast<const T *>(a.v_src)[tid];
+  if (is_new) {
+    for (int s2 = 0; s2 < P; ++s2)
+      if (s2 != slot) {
+        kp[k_offset<KV, LAYOUT>(s2, d, D)] = T(0);
+        vp[v_offset<KV, LAYOUT>(s2, d, D)] = T(0);
+      }
+    if (KV == kFP8 && d == 0) {
+      a.k_scale[page * H + g] = a.k_scale_src[node * H + g];
+      a.v_scale[page * H + g] = a.v_scale_src[node * H + g];
+    }
+  }
+}
+
 template <int KV, int LAYOUT>
 __global__ __launch_bounds__(256) void spex_gather_kv_kernel(GatherArgs a, Shape sh) {
   typedef typename std::conditional<KV == kF32, float,
@@ -1577,6 +1611,27 @@ hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t strea
     case kF32: return gather_layout<kF32>(sh, a, stream);
     case kBF16: return gather_layout<kBF16>(sh, a, stream);
     case kFP8: return gather_layout<kFP8>(sh, a, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int KV>
+static hipError_t append_tokens_layout(const Shape &sh, const AppendTokensArgs &a, hipStream_t stream) {
+  const int64_t total = static_cast<int64_t>(a.n_nodes) * sh.Hkv * sh.D;
+  const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
+  if (sh.layout == kMfmaTiled)
+    hipLaunchKernelGGL((spex_append_tokens_kernel<KV, kMfmaTiled>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_append_tokens_kernel<KV, kRowMajor>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+hipError_t launch_append_tokens(const Shape &sh, const AppendTokensArgs &a, hipStream_t stream) {
+  if (a.n_nodes <= 0) return hipSuccess;
+  switch (sh.kv_dtype) {
+    case kF32: return append_tokens_layout<kF32>(sh, a, stream);
+    case kBF16: return append_tokens_layout<kBF16>(sh, a, stream);
+    case kFP8: return append_tokens_layout<kFP8>(sh, a, stream);
   }
   return hipErrorInvalidValue;
 }

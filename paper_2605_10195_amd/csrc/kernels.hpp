@@ -76,6 +76,16 @@ struct ScatterArgs {
   int32_t page_ids[kMaxPagesPerScatter];
 };
 
+// One token for each of n_nodes nodes in one launch.
+struct AppendTokensArgs {
+  void *k_pool, *v_pool;
+  float *k_scale, *v_scale;                // pool scale arrays (fp8) or null
+  const void *k_src, *v_src;               // [n_nodes][Hkv][D]
+  const float *k_scale_src, *v_scale_src;  // [n_nodes][Hkv] (fp8; read only for nodes that start a page)
+  const int32_t *dst;                      // 2 ints per node: {page id, slot | (page is new) << 8}
+  int32_t n_nodes;
+};
+
 struct GatherArgs {
   const void *k_pool, *v_pool;
   const float *k_scale, *v_scale;
@@ -92,6 +102,7 @@ hipError_t launch_attention(const Shape &sh, const AttnArgs &a, bool prefix, int
 hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream);
 hipError_t launch_scatter(const Shape &sh, const ScatterArgs &a, hipStream_t stream);
 hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t stream);
+hipError_t launch_append_tokens(const Shape &sh, const AppendTokensArgs &a, hipStream_t stream);
 bool has_mfma_kernel(const Shape &sh);
 // blob[pairs[2i]] = pairs[2i+1] for i < n (all DEVICE): patches the device copy of a plan.
 hipError_t launch_patch(int32_t *blob, const int32_t *pairs, int32_t n, hipStream_t stream);

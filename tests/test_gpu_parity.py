@@ -329,3 +329,69 @@ def test_softmax_scale_must_be_positive():
             t.decode_attention([r], None, q, bad)
         assert e.value.name == "INVALID_ARG"
     t.close()
+
+
+# ------------------------------------------------------------------ decode loop, one launch per append
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3", "f32"])
+def test_decode_loop_with_append_tokens(kv_dtype):
+    """Every iteration appends one token to every leaf with one call, then attends.  Checked
+    against the oracle (same tokens appended to its own tree) and against gather_kv bit for bit."""
+    from oracle.adapters import OracleSink, queries_fp64
+    heads = (8, 2, 128) if kv_dtype != "f32" else (4, 2, 64)
+    wl = sw.bfs_tot(n_queries=2, prompt=40, step=13, heads=heads, kv_dtype=kv_dtype,
+                    q_dtype="f32" if kv_dtype == "f32" else "bf16")
+    tree = build_gpu_tree(wl, extra_pages=2 * len(wl.leaves) + 4, pool_fill=0xFF)
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = sw.gen_queries(wl, device="cuda")
+    qd = queries_fp64(q)
+    H, D = heads[1], heads[2]
+    L = len(wl.leaves)
+    grown = {u: [] for u in wl.leaves}
+    states = set()
+    for step in range(22):
+        x_k = sw.normal_values(6, 1, 900 + step, torch.arange(L), H, D, 0.5, "cuda")
+        x_v = sw.normal_values(6, 2, 900 + step, torch.arange(L), H, D, 0.5, "cuda")
+        ks = vs = None
+        if kv_dtype == "fp8_e4m3":
+            # a token that starts a page brings its own scale; others use the page's scale
+            k = torch.empty((L, H, D), dtype=torch.uint8, device="cuda")
+            v = torch.empty_like(k)
+            ks = torch.ones((L, H), dtype=torch.float32, device="cuda")
+            vs = torch.ones((L, H), dtype=torch.float32, device="cuda")
+            for i, u in enumerate(wl.leaves):
+                n_old = tree.node_info(u)["n_tokens"]
+                prev = None
+                if n_old % 16:
+                    _, _, pk, pv = tree.gather_kv(u, n_old - 1, 1)
+                    prev = (pk[0], pv[0])
+                ck, sk = sw.quantise_pages(x_k[i:i + 1], n_old % 16, 16, None if prev is None else prev[0])
+                cv, sv = sw.quantise_pages(x_v[i:i + 1], n_old % 16, 16, None if prev is None else prev[1])
+                k[i], v[i] = ck[0], cv[0]
+                if sk.shape[0]:
+                    ks[i], vs[i] = sk[0], sv[0]
+                sink.append(u, ck.cpu(), cv.cpu(), sk.cpu() if sk.shape[0] else None,
+                            sv.cpu() if sv.shape[0] else None)
+                grown[u].append((ck.cpu(), cv.cpu()))
+            k, v = k.view(torch.float8_e4m3fn), v.view(torch.float8_e4m3fn)
+        else:
+            dt = torch.bfloat16 if kv_dtype == "bf16" else torch.float32
+            k, v = x_k.to(dt).contiguous(), x_v.to(dt).contiguous()
+            for i, u in enumerate(wl.leaves):
+                sink.append(u, k[i:i + 1].cpu(), v[i:i + 1].cpu())
+                grown[u].append((k[i:i + 1].cpu(), v[i:i + 1].cpu()))
+        tree.append_tokens(wl.leaves, k, v, ks, vs)
+        out, lse = tree.decode_attention(wl.leaves, None, q, wl.sm_scale)
+        states.add(tree.last_launch_info()["plan_rebuilt"])
+        if step % 4 == 3 or step < 2:
+            ref = sink.tree.attention(wl.leaves, None, qd, wl.sm_scale)
+            got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+            assert_close(got, ref, kv_dtype, f"{kv_dtype} decode step {step}")
+    assert states == {1, 2}
+    for u in wl.leaves[:6]:                                    # what was appended is what is stored
+        n = tree.node_info(u)["n_tokens"]
+        gk, gv, _, _ = tree.gather_kv(u, n - 22, 22)
+        want_k = torch.cat([a for a, _ in grown[u]], 0)
+        want_v = torch.cat([b for _, b in grown[u]], 0)
+        assert torch.equal(gk.cpu().view(want_k.dtype), want_k) and torch.equal(gv.cpu().view(want_v.dtype), want_v)
+    tree.close()

@@ -375,3 +375,39 @@ def grow_and_compare(wl, n_steps, seed):
 def test_length_patches_match_a_fresh_plan(wl):
     patched, fresh = grow_and_compare(wl, 24, 5)
     assert patched > 3 and fresh > 3          # both the patch path and the replan path were taken
+
+
+# ------------------------------------------------------------------ one token per node
+def test_append_tokens_matches_single_appends_and_is_all_or_nothing():
+    wl = sw.bfs_tot(n_queries=2, prompt=40, step=15)
+    n_pages = wl.peak_pages() + 3 * len(wl.leaves)
+    order = np.random.default_rng(4).permutation(n_pages).tolist()
+    tree, ref = host_tree(wl, n_pages, order), PageTableRef(n_pages, 16, order)
+    replay_both(wl, tree, ref)
+    leaves = list(wl.leaves)
+    for it in range(20):                                      # crosses page boundaries
+        nodes = leaves[::2] if it % 3 == 0 else leaves
+        tree.append_tokens(nodes, None, None)
+        for u in nodes:
+            ref.append(u, 1)                                   # same page order as one call per node
+        assert tree.free_pages() == ref.free_list() and tree.stats() == ref.stats()
+        for u in leaves[:5]:
+            assert tree.path_pages(u) == ref.path_pages(u)
+    before = (tree.free_pages(), tree.stats(), [tree.node_info(u)["n_tokens"] for u in leaves])
+    root = ref.path(leaves[0])[0]
+    for bad, name in (([leaves[0], 10 ** 6], "BAD_NODE"), ([leaves[0], leaves[1], leaves[0]], "INVALID_ARG"),
+                      ([leaves[1], root], "NOT_LEAF")):
+        with pytest.raises(spex.SpexError) as e:
+            tree.append_tokens(bad, None, None)
+        assert e.value.name == name
+        assert before == (tree.free_pages(), tree.stats(), [tree.node_info(u)["n_tokens"] for u in leaves])
+    # too few pages for all: nothing happens to any of them
+    small = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=3, host_only=True)
+    (r,) = small.fork(-1, 1)
+    small.append_step(r, None, None, n_tokens=16)
+    kids = small.fork(r, 3)
+    with pytest.raises(spex.SpexError) as e:
+        small.append_tokens(kids, None, None)                 # needs 3 pages, 2 free
+    assert e.value.name == "OOM_PAGES" and small.stats() == (4, 1, 2)
+    small.append_tokens(kids[:2], None, None)
+    assert small.stats() == (4, 3, 0)
