@@ -50,6 +50,10 @@ def parse():
                     help="0 automatic, 2 shared-prefix + suffix + merge kernels, 3 tree-walk kernel")
     ap.add_argument("--walk-row-tiles", type=int, default=0)
     ap.add_argument("--walk-waves", type=int, default=0)
+    ap.add_argument("--decode-iters", type=int, default=32,
+                    help="after the timed steps: this many decode iterations (one token appended to "
+                         "every branch with spex_tree_append_tokens, then attention) on one tree, "
+                         "reported as decode_loop; 0 = skip")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true",
@@ -87,6 +91,42 @@ def cpu_baseline(wl, n_leaves):
                 seconds=dt), out, leaves, q_lens
 
 
+def decode_loop(tree, wl, q, out, lse, iters, dev):
+    """The per-token loop of a step: every iteration appends one token to every requested branch
+    (one spex_tree_append_tokens launch) and attends.  The new K/V are drawn before the timed
+    region.  Reports wall time per iteration and how often the cached plan was patched / redone."""
+    import torch
+
+    import spex_workloads as sw
+    nodes = sorted(set(wl.leaves))
+    n = len(nodes)
+    kv_torch = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.uint8}[wl.kv_dtype]
+    ks = vs = None
+    if wl.kv_dtype == "fp8_e4m3":
+        k = torch.randint(0, 120, (n, wl.num_kv_heads, wl.head_dim), dtype=torch.uint8, device=dev)
+        v = torch.randint(0, 120, (n, wl.num_kv_heads, wl.head_dim), dtype=torch.uint8, device=dev)
+        k, v = k.view(torch.float8_e4m3fn), v.view(torch.float8_e4m3fn)
+        ks = torch.full((n, wl.num_kv_heads), 2.0 ** -7, dtype=torch.float32, device=dev)
+        vs = ks.clone()
+    else:
+        gen = torch.Generator(device=dev).manual_seed(7)
+        k = (0.5 * torch.randn((n, wl.num_kv_heads, wl.head_dim), generator=gen, device=dev)).to(kv_torch)
+        v = (0.5 * torch.randn((n, wl.num_kv_heads, wl.head_dim), generator=gen, device=dev)).to(kv_torch)
+    counts = {0: 0, 1: 0, 2: 0}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        tree.append_tokens(nodes, k, v, ks, vs)
+        tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse)
+        counts[tree.last_launch_info()["plan_rebuilt"]] += 1
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / iters
+    return dict(iterations=iters, ms_per_iteration=dt * 1e3, query_tokens_per_s=q.shape[0] / dt,
+                plans_patched=counts[2], plans_redone=counts[1],
+                note="append_tokens + decode_attention per iteration, one tree, KV of earlier "
+                     "iterations may sit in the last-level cache")
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -117,8 +157,11 @@ def main():
         order = None
         if args.placement == "random":
             order = np.random.default_rng(1000 + c).permutation(n_pages).tolist()
+        extra = len(set(wl.leaves)) * (args.decode_iters // wl.page_size + 2) if c == 0 else 0
+        if order is not None and extra:
+            order = order + list(range(n_pages, n_pages + extra))
         tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
-                             wl.kv_dtype, num_pages=n_pages, device=dev, free_order=order,
+                             wl.kv_dtype, num_pages=n_pages + extra, device=dev, free_order=order,
                              prefix_chunk_pages=args.prefix_chunk, suffix_chunk_pages=args.suffix_chunk,
                              interleave_kv=args.kv_pools == "interleaved", kernel_mode=args.kernel_mode,
                              walk_row_tiles=args.walk_row_tiles, walk_waves=args.walk_waves)
@@ -225,6 +268,9 @@ def main():
         "build_seconds": t_build,
         "paper_context": PAPER_CONTEXT,
     }
+
+    if args.decode_iters > 0:
+        result["decode_loop"] = decode_loop(trees[0], wl, q, outs[0], lses[0], args.decode_iters, dev)
 
     if args.calibrate:
         ref_in = torch.ones(1 << 28, dtype=torch.float32, device=dev)
