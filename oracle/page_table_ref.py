@@ -53,8 +53,9 @@ Tree-walk lists (second kernel set: one workgroup carries a block of query rows
 from the root to the requested nodes).  With G = Hq / Hkv, request i has
 q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
   * row_tiles is the value asked for (1, 2, 4) or, if 0, the smallest of them
-    with max rows <= 16 * row_tiles, raised to 2 when it is 1 and some root has
-    more than 64 rows below it; no lists if a request has more rows than C;
+    with max rows <= 16 * row_tiles, raised to 2 when it is 1, some root has
+    more than 64 rows below it and sum over roots of ceil(rows / 128), times Hkv,
+    is at least 512; no lists if a request has more rows than C;
   * roots in order of first appearance; a root's requests sorted by path (node
     ids root first, lexicographic, a proper prefix first; ties in request
     order), so the requests below any node are consecutive;
@@ -351,7 +352,8 @@ class PageTableRef:
             if max(rows) > 64:
                 return none
             row_tiles = 1 if max(rows) <= 16 else (2 if max(rows) <= 32 else 4)
-            if row_tiles == 1 and max(root_rows.values()) > 64:
+            if row_tiles == 1 and max(root_rows.values()) > 64 and \
+                    sum(-(-r // 128) for r in root_rows.values()) * num_kv_heads >= 512:
                 row_tiles = 2
         elif max(rows) > 16 * row_tiles:
             return dict(none, row_tiles=0)

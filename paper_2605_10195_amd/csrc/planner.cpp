@@ -382,7 +382,8 @@ PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
 // written but the output.  Rules (they fix the result uniquely):
 //  * request i has q_len_i * G rows; C = 16 * NTW rows fit one wavefront.  NTW is the value asked
 //    for (1, 2 or 4) or, if 0, the smallest of {1, 2, 4} with max rows <= 16 * NTW, raised to 2 when
-//    that is 1 and some root has more than 64 rows below it.  No lists (walk_ok = false) if some
+//    that is 1, some root has more than 64 rows below it and sum over roots of ceil(rows / 128),
+//    times Hkv, is at least 512.  No lists (walk_ok = false) if some
 //    request has more rows than 16 * NTW.
 //  * roots in order of first appearance in the request list; the requests of a root sorted by
 //    path (node ids root first, lexicographic, a proper prefix first), ties in request order;
@@ -460,7 +461,14 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   if (ntw == 0) {
     if (max_rows > 64) return;
     ntw = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
-    if (ntw == 1 && *std::max_element(root_rows.begin(), root_rows.end()) > 64) ntw = 2;
+    if (ntw == 1 && *std::max_element(root_rows.begin(), root_rows.end()) > 64) {
+      // Two tiles per wavefront halve the number of row blocks that walk a wide root's shared
+      // pages -- worth it only if the launch still has at least two workgroups per compute unit
+      // (512); below that, more and shorter workgroups balance better.
+      int64_t wide_items = 0;
+      for (int64_t r : root_rows) wide_items += (r + 127) / 128;
+      if (wide_items * num_kv_heads >= 512) ntw = 2;
+    }
   } else if (max_rows > 16 * ntw) {
     return;
   }
