@@ -1090,30 +1090,34 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       return load_walk_block<FP8>(p, blk_begin + (b < n_shared ? b : n_shared - 1), g, sh.Hkv);
     };
 
-    // Software pipeline, two blocks deep: while block b is computed from one LDS buffer, block
-    // b+1 is already in registers (requested an iteration earlier) and moves to the other LDS
-    // buffer after the computation, and the global loads of block b+2 are in flight.  The loads
+    // Software pipeline, PF blocks deep: while block c is computed from one LDS buffer, blocks
+    // c+1 .. c+PF-1 are already in (or on their way to) registers, block c+1 moves to the other
+    // LDS buffer after the computation, and the global loads of block c+PF are issued.  The loads
     // are unconditional (indices past the end repeat the last block) because a load issued on
-    // one path only would make every later wait a wait for all outstanding loads.
-    Raw x0, x1;
-    WalkBlock bm0 = meta(0), bm1 = meta(1);
-    stage_load(x0, bm0);
-    stage_load(x1, bm1);
-    stage_store(x0, 0);
+    // one path only would make every later wait a wait for all outstanding loads.  (PF = 4 was
+    // measured for one row tile per wavefront, where the registers allow it: no gain.)
+    constexpr int PF = 2;
+    Raw x[PF];
+    WalkBlock bmq[PF];
+#pragma unroll
+    for (int k = 0; k < PF; ++k) {
+      bmq[k] = meta(k);
+      stage_load(x[k], bmq[k]);
+    }
+    stage_store(x[0], 0);
     __syncthreads();
-    for (int b = 0; b < n_shared; b += 2) {
-      const WalkBlock bm2 = meta(b + 2), bm3 = meta(b + 3);
-      stage_load(x0, bm2);
-      compute(b, bm0);
-      if (b + 1 < n_shared) stage_store(x1, 1);
-      __syncthreads();
-      if (b + 1 >= n_shared) break;
-      stage_load(x1, bm3);
-      compute(b + 1, bm1);
-      if (b + 2 < n_shared) stage_store(x0, 0);
-      __syncthreads();
-      bm0 = bm2;
-      bm1 = bm3;
+    for (int b = 0; b < n_shared; b += PF) {
+#pragma unroll
+      for (int k = 0; k < PF; ++k) {
+        const int c = b + k;             // block computed in this step; x[k] is free again
+        if (c >= n_shared) break;        // uniform over the workgroup
+        const WalkBlock cur = bmq[k];
+        bmq[k] = meta(c + PF);
+        stage_load(x[k], bmq[k]);
+        compute(c, cur);
+        if (c + 1 < n_shared) stage_store(x[(k + 1) % PF], (c + 1) & 1);
+        __syncthreads();
+      }
     }
   }
 
