@@ -131,6 +131,21 @@ def test_random_trees_tree_walk_kernel(case, row_tiles, waves):
     assert_close(got, run_oracle(wl), case["kv_dtype"], wl.name)
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3"])
+def test_tree_walk_kernel_with_more_blocks_than_its_lds_copy_holds(kv_dtype):
+    # 9 000-token prompt + 1 100-token steps: > 256 two-page blocks per row block, so the kernel
+    # reads its block records through the scalar path instead of from LDS
+    wl = sw.bfs_tot(n_queries=1, prompt=9000, step=1100, width=4, keep=2, depth=2, heads=(8, 2, 128),
+                    kv_dtype=kv_dtype)
+    tree = build_gpu_tree(wl, kernel_mode=3)
+    got = run_gpu(wl, tree=tree)
+    dump = tree.walk_dump(wl.leaves, wl.q_lens)
+    tree.close()
+    rbs = np.array(dump["row_blocks"]).reshape(-1, 3 + 3 * dump["waves"])
+    assert (rbs[:, 2] + rbs[:, 3:3 + dump["waves"]].sum(1)).max() > 256
+    assert_close(got, run_oracle(wl), kv_dtype, wl.name)
+
+
 def test_automatic_mode_picks_the_tree_walk_kernel_for_short_paths():
     wl = sw.random_trace(42, heads=(8, 2, 128), kv_dtype="bf16", n_ops=70, max_tokens=90, max_q_len=4)
     tree = build_gpu_tree(wl)
