@@ -25,10 +25,10 @@ HBM_PEAK_GBPS = 8000.0
 # a plain 1 GiB-in / 1 GiB-out kernel (--calibrate): FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB.  The
 # summaries are in profiles/<workload>_tree_walk.md.  Key: (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("bfs_tot", "spex_tree_walk_kernel"): 536158433,           # profiles/bfs_tot_tree_walk.md
-    ("mcts_skewed", "spex_tree_walk_kernel"): 604621588,       # profiles/mcts_skewed_tree_walk.md
-    ("spec_at_scale", "spex_tree_walk_kernel"): 13068627066,   # profiles/spec_at_scale_tree_walk.md
-    ("tot_with_drafts", "spex_tree_walk_kernel"): 507995033,   # profiles/tot_with_drafts_tree_walk.md
+    ("bfs_tot", "spex_tree_walk_kernel"): 535151677,           # profiles/bfs_tot_tree_walk.md
+    ("mcts_skewed", "spex_tree_walk_kernel"): 609996247,       # profiles/mcts_skewed_tree_walk.md
+    ("spec_at_scale", "spex_tree_walk_kernel"): 13166198681,   # profiles/spec_at_scale_tree_walk.md
+    ("tot_with_drafts", "spex_tree_walk_kernel"): 497297500,   # profiles/tot_with_drafts_tree_walk.md
 }
 PAPER_CONTEXT = ("paper reports only end-to-end serving speedups (1.2-3x, up to 4.1x with MTP) on "
                  "NVIDIA A6000/A100; no attention-kernel number exists for this metric")
