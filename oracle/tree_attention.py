@@ -13,6 +13,10 @@ and evaluate scaled-dot-product attention with grouped-query heads in fp64.
 
     T      = tokens on the path,  q_len queries attached to the node
     query i sees path positions 0 .. T - q_len + i          (causal among the q_len)
+    or, with draft masks (token-level speculative decoding verifies a TREE of draft tokens,
+    Sec. 6.5: token trees of 16 / 8 / 4 drafts): the q_len last tokens of the path are the
+    drafts, query i sees every earlier position and draft j iff bit j of its mask is set
+    (its ancestors in the draft tree and itself)
     kv head of query head h:  g = h // (Hq // Hkv)
     s_t = sm_scale * <q, K[t, g]>,  p = softmax(s),  out = sum_t p_t V[t, g],  lse = log sum_t e^{s_t}
 
@@ -184,9 +188,12 @@ class OracleTree:
 
     # -- attention -------------------------------------------------------------------
     def attention(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]], q: np.ndarray,
-                  sm_scale: float, return_weights: bool = False):
+                  sm_scale: float, return_weights: bool = False,
+                  draft_masks: Optional[Sequence[int]] = None):
         """q: [sum(q_lens), Hq, D] fp64 (already decoded).  Returns out [.., Hq, D], lse [.., Hq]
-        (and, on request, the list of per-query weight matrices [Hq, T_i])."""
+        (and, on request, the list of per-query weight matrices [Hq, T_i]).
+        draft_masks: one integer per query (request-major), bit j = the query sees draft token
+        j of its request (path position T - q_len + j); None = the causal chain."""
         if q_lens is None:
             q_lens = [1] * len(leaves)
         q = np.asarray(q, dtype=np.float64)
@@ -203,16 +210,26 @@ class OracleTree:
             if ql < 1 or ql > T:
                 raise ValueError("every query needs at least one visible token")
             for i in range(ql):
-                Ti = T - ql + 1 + i
+                if draft_masks is None:
+                    vis = np.arange(T - ql + 1 + i)
+                else:
+                    mask = int(draft_masks[row])
+                    if mask >> ql:
+                        raise ValueError("mask bit beyond the request's drafts")
+                    vis = np.array(list(range(T - ql)) + [T - ql + j for j in range(ql) if mask >> j & 1],
+                                   dtype=np.int64)
+                    if vis.size == 0:
+                        raise ValueError("every query needs at least one visible token")
+                Ti = vis.size
                 w_all = np.zeros((self.Hq, Ti))
                 for g in range(self.Hkv):
                     qg = q[row, g * G:(g + 1) * G, :]                 # [G, D]
-                    s = sm_scale * (qg @ K[:Ti, g, :].T)              # [G, Ti]
+                    s = sm_scale * (qg @ K[vis, g, :].T)              # [G, Ti]
                     m = s.max(axis=1, keepdims=True)
                     w = np.exp(s - m)
                     Z = w.sum(axis=1, keepdims=True)
                     p = w / Z
-                    out[row, g * G:(g + 1) * G, :] = p @ V[:Ti, g, :]
+                    out[row, g * G:(g + 1) * G, :] = p @ V[vis, g, :]
                     lse[row, g * G:(g + 1) * G] = (m + np.log(Z))[:, 0]
                     w_all[g * G:(g + 1) * G] = p
                 if return_weights:

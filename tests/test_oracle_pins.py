@@ -330,3 +330,98 @@ def test_pruned_and_interior_nodes():
     assert tree.path_tokens(r) == 4
     with pytest.raises(ValueError):
         tree.attention([r], [5], np.ones((5, 1, 2)), 1.0)            # q_len > T
+
+
+# ------------------------------------------------------------------------- draft token trees
+def _random_draft_tree(rng, n):
+    """Parents of a seeded token tree (draft 0 is the root) and each draft's ancestor-or-self mask."""
+    parent = [-1] + [int(rng.integers(0, j)) for j in range(1, n)]
+    masks = []
+    for j in range(n):
+        m, u = 0, j
+        while u >= 0:
+            m |= 1 << u
+            u = parent[u]
+        masks.append(m)
+    return parent, masks
+
+
+def test_draft_masks_brute_force_and_library():
+    """Nested loops over an explicit visibility table, and torch's fp64 attention with a boolean
+    mask, on a branch whose last q_len tokens form a draft token tree."""
+    rng = np.random.default_rng(21)
+    T, ql, Hkv, G, D = 29, 7, 2, 3, 8
+    K = rng.normal(size=(T, Hkv, D))
+    V = rng.normal(size=(T, Hkv, D))
+    q = rng.normal(size=(ql, Hkv * G, D))
+    _, masks = _random_draft_tree(rng, ql)
+    tree, leaf = _chain_tree(K, V, [9, 20], Hq=Hkv * G)
+    out, lse = tree.attention([leaf], [ql], q, 0.31, draft_masks=masks)
+    base = T - ql
+    for i in range(ql):
+        for h in range(Hkv * G):
+            g = h // G
+            num, den, seen = np.zeros(D), 0.0, 0
+            for t in range(T):
+                if t >= base and not (masks[i] >> (t - base)) & 1:
+                    continue
+                w = math.exp(0.31 * sum(q[i, h, d] * K[t, g, d] for d in range(D)))
+                den += w
+                seen += 1
+                for d in range(D):
+                    num[d] += w * V[t, g, d]
+            assert seen == base + bin(masks[i]).count("1")
+            assert np.allclose(out[i, h], num / den, atol=1e-12) and abs(lse[i, h] - math.log(den)) < 1e-12
+    allowed = torch.ones((ql, T), dtype=torch.bool)
+    for i in range(ql):
+        for j in range(ql):
+            allowed[i, base + j] = bool((masks[i] >> j) & 1)
+    qt = torch.from_numpy(q).permute(1, 0, 2)[None]                                  # [1, Hq, ql, D]
+    kt = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    vt = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, attn_mask=allowed, scale=0.31)
+    assert np.allclose(ref[0].permute(1, 0, 2).numpy(), out, atol=1e-12)
+
+
+def test_draft_masks_equal_a_branch_holding_only_the_ancestors():
+    """Query i of a draft tree must give what a plain single query gives on a branch that holds
+    the prefix followed by i's ancestors and i itself, in order."""
+    rng = np.random.default_rng(22)
+    T, ql, Hkv, D = 33, 9, 2, 6
+    K = rng.normal(size=(T, Hkv, D))
+    V = rng.normal(size=(T, Hkv, D))
+    q = rng.normal(size=(ql, 4, D))
+    _, masks = _random_draft_tree(rng, ql)
+    tree, leaf = _chain_tree(K, V, [5, 26], Hq=4)
+    out, lse = tree.attention([leaf], [ql], q, 0.4, draft_masks=masks)
+    base = T - ql
+    for i in range(ql):
+        keep = list(range(base)) + [base + j for j in range(ql) if (masks[i] >> j) & 1]
+        t_i, l_i = _chain_tree(K[keep], V[keep], [3], Hq=4)
+        o, s = t_i.attention([l_i], [1], q[i:i + 1], 0.4)
+        assert np.allclose(o[0], out[i], atol=1e-13) and np.allclose(s[0], lse[i], atol=1e-13)
+
+
+def test_chain_masks_equal_the_causal_default_and_hand_values():
+    rng = np.random.default_rng(23)
+    T, ql = 20, 5
+    K = rng.normal(size=(T, 1, 4))
+    V = rng.normal(size=(T, 1, 4))
+    q = rng.normal(size=(ql, 2, 4))
+    tree, leaf = _chain_tree(K, V, [7])
+    tree.Hq = 2
+    a = tree.attention([leaf], [ql], q, 0.5)
+    b = tree.attention([leaf], [ql], q, 0.5, draft_masks=[(2 << i) - 1 for i in range(ql)])
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # hand case: keys ln 1, ln 2, ln 3, ln 6, values 6 12 18 36, q = 1, head_dim 1; the last
+    # three tokens are drafts 0 <- 1 and 0 <- 2 (two children of draft 0)
+    Kh = np.log(np.array([1.0, 2.0, 3.0, 6.0])).reshape(4, 1, 1)
+    Vh = np.array([6.0, 12.0, 18.0, 36.0]).reshape(4, 1, 1)
+    th, lh = _chain_tree(Kh, Vh, [1])
+    o, s = th.attention([lh], [3], np.ones((3, 1, 1)), 1.0, draft_masks=[0b001, 0b011, 0b101])
+    # weights 1 2 3 6: query 0 sees {1,2} -> (6 + 24) / 3; query 1 sees {1,2,3} -> (6 + 24 + 54) / 6;
+    # query 2 sees {1,2,6} -> (6 + 24 + 216) / 9
+    assert np.allclose(o[:, 0, 0], [10.0, 14.0, 246.0 / 9.0], atol=1e-13)
+    assert np.allclose(np.exp(s[:, 0]), [3.0, 6.0, 9.0], atol=1e-12)
+    with pytest.raises(ValueError):
+        th.attention([lh], [3], np.ones((3, 1, 1)), 1.0, draft_masks=[0b001, 0b011, 0b1101])
