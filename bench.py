@@ -54,6 +54,10 @@ def parse():
                     help="after the timed steps: this many decode iterations (one token appended to "
                          "every branch with spex_tree_append_tokens, then attention) on one tree, "
                          "reported as decode_loop; 0 = skip")
+    ap.add_argument("--token-trees", type=int, default=0,
+                    help="verify a seeded draft token tree of this many tokens per branch (4-16, "
+                         "tot_with_drafts only; visibility masks through "
+                         "spex_tree_decode_attention_masked); 0 = the workload's causal drafts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true",
@@ -81,9 +85,10 @@ def cpu_baseline(wl, n_leaves):
     sink = OracleSink.for_workload(wl)
     sw.replay(wl, sink, device="cpu", only_nodes=only)
     q = queries_fp64(sw.gen_queries(wl, device="cpu"))[:sum(q_lens)]
+    masks = None if wl.draft_masks is None else [int(m) for m in wl.draft_masks[:sum(q_lens)]]
     with threadpool_limits(limits=1):
         t0 = time.perf_counter()
-        out, _ = sink.tree.attention(leaves, q_lens, q, wl.sm_scale)
+        out, _ = sink.tree.attention(leaves, q_lens, q, wl.sm_scale, draft_masks=masks)
         dt = time.perf_counter() - t0
     return dict(value=sum(q_lens) / dt, unit="query-tokens/s", cores=1, kind="oracle",
                 sample=f"first {len(leaves)} of {len(wl.leaves)} requested branches "
@@ -117,7 +122,7 @@ def decode_loop(tree, wl, q, out, lse, iters, dev):
     t0 = time.perf_counter()
     for _ in range(iters):
         tree.append_tokens(nodes, k, v, ks, vs)
-        tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse)
+        tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse, draft_masks=wl.draft_masks)
         counts[tree.last_launch_info()["plan_rebuilt"]] += 1
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / iters
@@ -143,7 +148,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
-    wl = sw.WORKLOADS[args.workload]()
+    if args.token_trees:
+        assert args.workload == "tot_with_drafts" and 1 <= args.token_trees <= 32
+        wl = sw.tot_with_drafts(drafts=args.token_trees, token_trees=True)
+    else:
+        wl = sw.WORKLOADS[args.workload]()
+    if wl.draft_masks is not None:
+        wl.draft_masks = np.asarray(wl.draft_masks, dtype=np.uint32)   # marshalled once, not per step
     n_pages = wl.peak_pages()
     unique_tokens = wl.unique_kv_tokens()
     unique_bytes = unique_tokens * wl.kv_bytes_per_token()
@@ -177,7 +188,8 @@ def main():
 
     def step(i):
         c = i % copies
-        trees[c].decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, outs[c], lses[c])
+        trees[c].decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, outs[c], lses[c],
+                                  draft_masks=wl.draft_masks)
 
     # cold call: plan build + upload + kernels
     t0 = time.perf_counter()
@@ -243,7 +255,9 @@ def main():
         "dtype": {"f32": "f32", "bf16": "bf16", "fp8_e4m3": "fp8_e4m3 kv / bf16 q"}[wl.kv_dtype],
         "data": "synthetic",
         "config": {
-            "workload": wl.name, "queries": wl.n_trees, "branches": len(wl.leaves),
+            "workload": wl.name, "drafts_per_branch": max(wl.q_lens),
+            "draft_visibility": "causal chain" if wl.draft_masks is None else "seeded token tree (masks)",
+            "queries": wl.n_trees, "branches": len(wl.leaves),
             "query_tokens": nq, "heads": [wl.num_q_heads, wl.num_kv_heads, wl.head_dim],
             "page_size": wl.page_size, "unique_kv_tokens": unique_tokens,
             "unique_kv_bytes": unique_bytes, "flat_kv_bytes": wl.flat_kv_tokens() * b_tok,
@@ -282,7 +296,8 @@ def main():
 
     if not args.no_cpu_baseline:
         n_cpu = args.cpu_sample_leaves or {"tiny_tree": 4, "bfs_tot": 512, "mcts_skewed": 1105,
-                                           "spec_at_scale": 512, "tot_with_drafts": 128}[wl.name]
+                                           "spec_at_scale": 512, "tot_with_drafts": 128,
+                                           "tot_with_drafts_token_trees": 128}[wl.name]
         base, ref_out, leaves, q_lens = cpu_baseline(wl, n_cpu)
         got = outs[0][:ref_out.shape[0]].cpu().numpy().astype(np.float64)
         base["gpu_vs_oracle_max_abs"] = float(np.max(np.abs(got - ref_out)))

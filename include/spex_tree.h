@@ -195,6 +195,28 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *tree, const spex_node_t *l
                                          const int32_t *q_lens, int32_t n_leaves, const void *q,
                                          float *out, float *lse, float sm_scale, void *hip_stream);
 
+/*
+ * Sec. 6.5 (composition with token-level speculative decoding): the draft tokens a branch
+ * verifies in one step form a small token TREE rather than a chain.  Same as decode_attention,
+ * except that the last q_lens[i] tokens of leaves[i]'s path are drafts whose mutual visibility
+ * the caller states:
+ *   draft_masks : HOST [sum(q_lens)], requested-node major like q.  With B_i = T_i - q_lens[i],
+ *     query j of request i sees path positions 0 .. B_i - 1 (everything before the drafts) and
+ *     position B_i + k iff bit k of its mask is set.  For a draft tree the mask holds the bits of
+ *     the draft's ancestors and of itself; the chain is mask_j = 2^(j+1) - 1, which gives
+ *     decode_attention's result.  NULL = that chain.
+ * With masks, q_lens must be given and q_lens[i] <= 32; bits at or above q_lens[i] must be clear
+ * (SPEX_ERR_INVALID_ARG); a query that sees no position at all is SPEX_ERR_EMPTY_PATH.  Nothing is
+ * launched when an error is returned.  The tree-walk kernel (4 wavefronts per workgroup) and the
+ * generic kernels evaluate masks; kernel_mode 2 with MFMA-tiled pools, or kernel_mode 3 where the
+ * tree-walk kernel cannot take the request or walk_waves is 8, is SPEX_ERR_UNSUPPORTED.
+ * Length patches work as for decode_attention: the masks are part of the cached request.
+ */
+spex_status_t spex_tree_decode_attention_masked(spex_tree_t *tree, const spex_node_t *leaves,
+                                                const int32_t *q_lens, const uint32_t *draft_masks,
+                                                int32_t n_leaves, const void *q, float *out,
+                                                float *lse, float sm_scale, void *hip_stream);
+
 /* ---- introspection (host only unless stated) -------------------------------------------- */
 
 typedef struct {
@@ -280,8 +302,11 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages
  *     holds the node.  A row block's blocks: first the nodes whose rows touch several
  *     wavefronts, then those of wavefront 0, 1, .. alone; every page of every row's path
  *     appears exactly once per row block.  Flag bit 0: a page is partial or missing, or some
- *     row in the range sees fewer positions than the block ends at.  Flag bit 1: the node is
- *     also on the paths of another row block.
+ *     row in the range may not see every position the block holds (the block ends beyond the
+ *     first position that some query of a request in the range does not see: T - q_len + 1 for
+ *     the chain, T - q_len + the number of leading drafts all its queries see with draft_masks,
+ *     which may be NULL as in decode_attention_masked).  Flag bit 1: the node is also on the
+ *     paths of another row block.
  *   items[S * n_items], S = 16 for NW = 4 and 32 for NW = 8: launch order, one workgroup each:
  *     {kv head, copy of row block fields 1.., zeros, row block index in the last int}; index -1 =
  *     padding that keeps the row blocks of one root on one XCD when fewer than 8 kv heads exist.
@@ -292,7 +317,8 @@ typedef struct {
   const int32_t *row_blocks, *blocks, *qt, *items;
 } spex_walk_view_t;
 spex_status_t spex_tree_walk_dump(spex_tree_t *tree, const spex_node_t *leaves,
-                                  const int32_t *q_lens, int32_t n_leaves, spex_walk_view_t *out);
+                                  const int32_t *q_lens, const uint32_t *draft_masks,
+                                  int32_t n_leaves, spex_walk_view_t *out);
 
 /*
  * Per-kernel timing.  While profiling is enabled, every decode_attention call brackets each of

@@ -66,9 +66,12 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
     its row block is wavefront * C + rows before it in the wavefront;
   * the nodes of a row block are the nodes with tokens on its requests' paths in
     order of first encounter, with row range [first row of the first request
-    through it, last row + 1 of the last one) and minlim = min T - q_len + 1 over
-    those requests; a node whose range touches two wavefronts is shared, else
-    private to wavefront lo // C;
+    through it, last row + 1 of the last one) and minlim = min over those requests
+    of the first path position some query of the request does not see: T - q_len
+    + 1 for the causal chain; with draft masks (query j sees everything before
+    the q_len drafts and draft k iff bit k of mask j is set) T - q_len + the
+    number of leading drafts that all of the request's queries see; a node whose
+    range touches two wavefronts is shared, else private to wavefront lo // C;
   * blocks of a row block: shared nodes first, then the private nodes of
     wavefront 0..NW-1, a node's pages two at a time; record (page a, pos_a << 7 |
     valid_a, page b or a again, pos_b << 7 | valid_b or 0, lo | hi << 16, flag, 0,
@@ -326,7 +329,7 @@ class PageTableRef:
     # ---------------------------------------------------------------- tree-walk lists
     def walk_plan(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
                   num_q_heads: int, num_kv_heads: int, row_tiles: int = 0,
-                  waves: int = 0) -> Dict[str, object]:
+                  waves: int = 0, draft_masks: Optional[Sequence[int]] = None) -> Dict[str, object]:
         L = len(leaves)
         q_lens = [1] * L if q_lens is None else list(q_lens)
         G = num_q_heads // num_kv_heads
@@ -336,10 +339,17 @@ class PageTableRef:
         none = dict(available=0, row_tiles=0, waves=0, row_blocks=[], blocks=[], qt=[], items=[])
         if L == 0:
             return none
-        qoff, limits = [], []
+        qoff, limits, first_unseen = [], [], []
         for path, ql in zip(paths, q_lens):
             T = sum(self.tokens[w] for w in path)
             qoff.append(len(limits))
+            lead = 1
+            if draft_masks is not None:
+                mk = [int(x) for x in draft_masks[len(limits):len(limits) + ql]]
+                lead = 0
+                while lead < ql and all((x >> lead) & 1 for x in mk):
+                    lead += 1
+            first_unseen.append(T - ql + lead)
             limits += [T - ql + 1 + i for i in range(ql)]
         roots: List[int] = []
         for path in paths:
@@ -413,10 +423,10 @@ class PageTableRef:
                     if self.tokens[w] == 0:
                         continue
                     if w not in nodes:
-                        nodes[w] = [row0, row0 + rows[i], limits[qoff[i]]]
+                        nodes[w] = [row0, row0 + rows[i], first_unseen[i]]
                     else:
                         nodes[w][1] = row0 + rows[i]
-                        nodes[w][2] = min(nodes[w][2], limits[qoff[i]])
+                        nodes[w][2] = min(nodes[w][2], first_unseen[i])
             first = len(blocks)
             shared = [b for w, (lo, hi, ml) in nodes.items() if lo // C != (hi - 1) // C
                       for b in node_blocks(w, lo, hi, ml)]

@@ -53,6 +53,7 @@ class NodeInfo(C.Structure):
 
 
 _I32P = C.POINTER(C.c_int32)
+_U32P = C.POINTER(C.c_uint32)
 
 
 class PlanView(C.Structure):
@@ -77,7 +78,7 @@ class WalkView(C.Structure):
 EXPORTS = [
     "spex_pool_bytes", "spex_status_string", "spex_last_device_error", "spex_tree_create",
     "spex_tree_destroy", "spex_tree_fork", "spex_tree_append_step", "spex_tree_append_new_pages",
-    "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_node_info", "spex_tree_path_pages",
+    "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_decode_attention_masked", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
     "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens",
@@ -104,6 +105,7 @@ def _load():
     lib.spex_tree_append_tokens.argtypes = [vp, _I32P, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_prune.argtypes = [vp, i32]
     lib.spex_tree_decode_attention.argtypes = [vp, _I32P, _I32P, i32, vp, vp, vp, f32, vp]
+    lib.spex_tree_decode_attention_masked.argtypes = [vp, _I32P, _I32P, _U32P, i32, vp, vp, vp, f32, vp]
     lib.spex_tree_node_info.argtypes = [vp, i32, C.POINTER(NodeInfo)]
     lib.spex_tree_path_pages.argtypes = [vp, i32, _I32P, _I32P, i32, _I32P]
     lib.spex_tree_free_pages.argtypes = [vp, _I32P, i32, _I32P]
@@ -111,7 +113,7 @@ def _load():
     lib.spex_tree_plan_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(PlanView)]
     lib.spex_tree_gather_kv.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_set_tuning.argtypes = [vp, i32, i32, i32, i32, i32]
-    lib.spex_tree_walk_dump.argtypes = [vp, _I32P, _I32P, i32, C.POINTER(WalkView)]
+    lib.spex_tree_walk_dump.argtypes = [vp, _I32P, _I32P, _U32P, i32, C.POINTER(WalkView)]
     lib.spex_tree_set_profiling.argtypes = [vp, i32]
     lib.spex_tree_read_profile.argtypes = [vp, C.POINTER(f32), i32, _I32P]
     lib.spex_tree_last_launch_info.argtypes = [vp, C.POINTER(i64)]
@@ -137,6 +139,14 @@ def _i32(seq) -> np.ndarray:
 
 def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data_as(_I32P)
+
+
+def _u32(seq) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(seq, dtype=np.uint32))
+
+
+def _uptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(_U32P)
 
 
 def _dev(t: Optional[torch.Tensor]):
@@ -252,18 +262,26 @@ class SpexTree:
 
     def decode_attention(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
                          q: torch.Tensor, sm_scale: float, out: Optional[torch.Tensor] = None,
-                         lse: Optional[torch.Tensor] = None, want_lse: bool = True):
+                         lse: Optional[torch.Tensor] = None, want_lse: bool = True,
+                         draft_masks: Optional[Sequence[int]] = None):
         la = _i32(leaves)
         qa = None if q_lens is None else _i32(q_lens)
         nq = len(la) if qa is None else int(qa.sum())
+        ma = None if draft_masks is None else _u32(draft_masks)
+        assert ma is None or len(ma) == nq
         assert q.is_contiguous() and tuple(q.shape) == (nq, self.Hq, self.D), q.shape
         assert q.dtype == (torch.float32 if self.q_dtype == F32 else torch.bfloat16)
         if out is None:
             out = torch.empty((nq, self.Hq, self.D), dtype=torch.float32, device=q.device)
         if lse is None and want_lse:
             lse = torch.empty((nq, self.Hq), dtype=torch.float32, device=q.device)
-        _check(lib.spex_tree_decode_attention(self._h, _ptr(la), _ptr(qa), len(la), _dev(q),
-                                              _dev(out), _dev(lse), float(sm_scale), _stream()))
+        if ma is None:
+            _check(lib.spex_tree_decode_attention(self._h, _ptr(la), _ptr(qa), len(la), _dev(q),
+                                                  _dev(out), _dev(lse), float(sm_scale), _stream()))
+        else:
+            _check(lib.spex_tree_decode_attention_masked(self._h, _ptr(la), _ptr(qa), _uptr(ma), len(la),
+                                                         _dev(q), _dev(out), _dev(lse), float(sm_scale),
+                                                         _stream()))
         return out, lse
 
     # ---- introspection -------------------------------------------------------------------
@@ -345,11 +363,13 @@ class SpexTree:
         _check(lib.spex_tree_set_tuning(self._h, prefix_chunk_pages, suffix_chunk_pages, kernel_mode,
                                         walk_row_tiles, walk_waves))
 
-    def walk_dump(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]]) -> dict:
+    def walk_dump(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
+                  draft_masks: Optional[Sequence[int]] = None) -> dict:
         la = _i32(leaves)
         qa = None if q_lens is None else _i32(q_lens)
+        ma = None if draft_masks is None else _u32(draft_masks)
         v = WalkView()
-        _check(lib.spex_tree_walk_dump(self._h, _ptr(la), _ptr(qa), len(la), C.byref(v)))
+        _check(lib.spex_tree_walk_dump(self._h, _ptr(la), _ptr(qa), _uptr(ma), len(la), C.byref(v)))
 
         def arr(name, n):
             p = getattr(v, name)
@@ -407,3 +427,8 @@ def spex_tree_prune(tree: SpexTree, node: int) -> None:
 
 def spex_tree_decode_attention(tree: SpexTree, leaves, q_lens, q, sm_scale, out=None, lse=None):
     return tree.decode_attention(leaves, q_lens, q, sm_scale, out, lse)
+
+
+def spex_tree_decode_attention_masked(tree: SpexTree, leaves, q_lens, draft_masks, q, sm_scale, out=None,
+                                      lse=None):
+    return tree.decode_attention(leaves, q_lens, q, sm_scale, out, lse, draft_masks=draft_masks)

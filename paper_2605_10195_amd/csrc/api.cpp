@@ -40,7 +40,7 @@ struct DevicePlan {
   const int32_t *part_indptr = nullptr, *part_base = nullptr, *part_hstride = nullptr;
   const int32_t *merge_qt = nullptr;
   const int32_t *coop_items[3] = {nullptr, nullptr, nullptr};
-  const int32_t *walk_items = nullptr, *walk_blocks = nullptr, *walk_qt = nullptr;
+  const int32_t *walk_items = nullptr, *walk_blocks = nullptr, *walk_qt = nullptr, *qt_mask = nullptr;
 };
 
 }  // namespace
@@ -53,7 +53,7 @@ struct spex_tree {
   spex::Plan plan;
   bool plan_on_device = false, device_has_split = false, device_has_walk = false;
   DevicePlan dplan;
-  size_t blob_off[14] = {}, blob_ints[14] = {};  // byte offset and length of each list in the blob
+  size_t blob_off[15] = {}, blob_ints[15] = {};  // byte offset and length of each list in the blob
   std::vector<int32_t> pending_patches;          // {array, index, value} not yet on the device
   void *d_patch = nullptr;
   size_t d_patch_cap = 0;
@@ -125,7 +125,7 @@ spex::Shape make_shape(const spex_config_t &c) {
 }
 
 bool request_matches(const spex::Plan &pl, const spex_tree *t, const int32_t *leaves,
-                     const int32_t *q_lens, int32_t n) {
+                     const int32_t *q_lens, const uint32_t *masks, int32_t n) {
   if (!pl.valid) return false;
   if (pl.req_prefix_chunk != t->prefix_chunk || pl.req_suffix_chunk != t->suffix_chunk ||
       pl.req_walk_row_tiles != t->walk_row_tiles || pl.req_walk_waves != t->walk_waves)
@@ -138,6 +138,10 @@ bool request_matches(const spex::Plan &pl, const spex_tree *t, const int32_t *le
   } else if (!pl.req_q_lens.empty()) {
     return false;
   }
+  // same leaves and q_lens, hence the same number of query tokens and of masks
+  if ((masks != nullptr) != !pl.req_masks.empty()) return false;
+  if (masks && std::memcmp(pl.req_masks.data(), masks, sizeof(uint32_t) * pl.req_masks.size()) != 0)
+    return false;
   return true;
 }
 
@@ -154,10 +158,10 @@ spex_status_t plan_status(spex_tree *t, spex::PlanError e) {
 // Brings t->plan up to date for the request.  *state: 0 = the cached plan still holds, 1 = planned
 // afresh, 2 = the cached plan was patched (tokens were appended to requested nodes without starting
 // a page; the changed entries wait in t->pending_patches for the device copy).
-spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_lens, int32_t n,
-                        int *state) {
+spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_lens,
+                        const uint32_t *masks, int32_t n, int *state) {
   *state = 0;
-  if (request_matches(t->plan, t, leaves, q_lens, n)) {
+  if (request_matches(t->plan, t, leaves, q_lens, masks, n)) {
     if (t->plan.table_version == t->pt->version()) return SPEX_OK;
     if (t->planner.patch_lengths(*t->pt, &t->plan, &t->pending_patches)) {
       *state = 2;
@@ -167,12 +171,12 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
   *state = 1;
   t->plan_on_device = false;
   t->pending_patches.clear();
-  return plan_status(t, t->planner.begin(*t->pt, leaves, q_lens, n, t->cfg.num_q_heads,
+  return plan_status(t, t->planner.begin(*t->pt, leaves, q_lens, masks, n, t->cfg.num_q_heads,
                                          t->cfg.num_kv_heads, t->prefix_chunk, t->suffix_chunk,
                                          t->walk_row_tiles, t->walk_waves, &t->plan));
 }
 
-constexpr int kPlanArrays = 14;
+constexpr int kPlanArrays = 15;
 // Index, in the device blob's array list, of the arrays a length patch can touch.
 constexpr int kPatchTarget[4] = {2 /*pg_rec*/, 3 /*qt_rec*/, 12 /*walk_blocks*/, 13 /*walk_qt*/};
 
@@ -207,7 +211,7 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
       &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
       &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt,
       &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2],
-      &pl.walk_items, &pl.walk_blocks, &pl.walk_qt};
+      &pl.walk_items, &pl.walk_blocks, &pl.walk_qt, &pl.qt_mask};
   size_t total = 0;
   for (int i = 0; i < kPlanArrays; ++i) {
     t->blob_off[i] = total;
@@ -245,6 +249,7 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
   dp.walk_items = at(11);
   dp.walk_blocks = at(12);
   dp.walk_qt = at(13);
+  dp.qt_mask = pl.qt_mask.empty() ? nullptr : at(14);
   t->plan_on_device = true;
   t->device_has_split = pl.has_split;
   t->device_has_walk = pl.has_walk;
@@ -532,13 +537,22 @@ spex_status_t spex_tree_prune(spex_tree_t *t, spex_node_t node) {
 spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leaves,
                                          const int32_t *q_lens, int32_t n_leaves, const void *q,
                                          float *out, float *lse, float sm_scale, void *hip_stream) {
+  return spex_tree_decode_attention_masked(t, leaves, q_lens, nullptr, n_leaves, q, out, lse, sm_scale,
+                                           hip_stream);
+}
+
+spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_t *leaves,
+                                                const int32_t *q_lens, const uint32_t *draft_masks,
+                                                int32_t n_leaves, const void *q, float *out, float *lse,
+                                                float sm_scale, void *hip_stream) {
   if (!t || n_leaves < 0 || (n_leaves > 0 && (!leaves || !q || !out))) return SPEX_ERR_INVALID_ARG;
   if (!t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
   if (!(sm_scale > 0.f) || std::isinf(sm_scale)) return SPEX_ERR_INVALID_ARG;
   if (n_leaves == 0) return SPEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int plan_state = 0;
-  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &plan_state);
+  if (draft_masks && !q_lens) return SPEX_ERR_INVALID_ARG;
+  const spex_status_t st = make_plan(t, leaves, q_lens, draft_masks, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
   spex::Plan &pl = t->plan;
   // Which kernels: the tree-walk kernel when its lists exist and fill the chip (or every work item
@@ -546,9 +560,13 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   // lists of the chosen kernels are built.
   const bool want_walk = (t->kernel_mode == 0 || t->kernel_mode == 3) && spex::has_mfma_kernel(t->shape);
   if (want_walk) t->planner.ensure_walk(*t->pt, &pl);
-  const bool walk_possible = want_walk && pl.walk_ok;
+  const bool tree_masks = draft_masks != nullptr;
+  // Draft-tree masks are understood by the tree-walk kernel (4 wavefronts per workgroup) and by
+  // the generic kernels.
+  const bool walk_possible = want_walk && pl.walk_ok && (!tree_masks || pl.walk_waves == 4);
   if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
-  const bool use_walk = walk_possible && (t->kernel_mode == 3 || pl.walk_real_items >= 128 ||
+  if (t->kernel_mode == 2 && tree_masks && spex::has_mfma_kernel(t->shape)) return SPEX_ERR_UNSUPPORTED;
+  const bool use_walk = walk_possible && (t->kernel_mode == 3 || tree_masks || pl.walk_real_items >= 128 ||
                                           pl.walk_max_item_blocks <= 64);
   if (!use_walk) {
     const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &pl));
@@ -592,6 +610,7 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
     wa.out = out;
     wa.lse = lse;
     wa.scale_log2 = sm_scale * 1.4426950408889634f;
+    wa.qt_mask = dp.qt_mask;
     HIP_TRY(bracket(3, true));
     HIP_TRY(spex::launch_tree_walk(t->shape, wa, pl.walk_row_tiles, pl.walk_waves, stream));
     HIP_TRY(bracket(3, false));
@@ -625,7 +644,8 @@ spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leav
   a.out = out;
   a.lse = lse;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
-  const bool generic = t->kernel_mode == 1;
+  a.qt_mask = dp.qt_mask;
+  const bool generic = t->kernel_mode == 1 || tree_masks;
 
   const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / spex::Plan::kItemInts);
   const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / spex::Plan::kItemInts);
@@ -743,7 +763,7 @@ spex_status_t spex_tree_plan_dump(spex_tree_t *t, const spex_node_t *leaves, con
                                   int32_t n_leaves, spex_plan_view_t *out) {
   if (!t || !out || n_leaves < 0 || (n_leaves > 0 && !leaves)) return SPEX_ERR_INVALID_ARG;
   int plan_state = 0;
-  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &plan_state);
+  const spex_status_t st = make_plan(t, leaves, q_lens, nullptr, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
   t->planner.ensure_csr(*t->pt, &t->plan);
   const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &t->plan));
@@ -838,10 +858,11 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
 }
 
 spex_status_t spex_tree_walk_dump(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
-                                  int32_t n_leaves, spex_walk_view_t *out) {
+                                  const uint32_t *draft_masks, int32_t n_leaves, spex_walk_view_t *out) {
   if (!t || !out || n_leaves < 0 || (n_leaves > 0 && !leaves)) return SPEX_ERR_INVALID_ARG;
+  if (draft_masks && !q_lens) return SPEX_ERR_INVALID_ARG;
   int plan_state = 0;
-  const spex_status_t st = make_plan(t, leaves, q_lens, n_leaves, &plan_state);
+  const spex_status_t st = make_plan(t, leaves, q_lens, draft_masks, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
   t->planner.ensure_walk(*t->pt, &t->plan);
   const spex::Plan &pl = t->plan;

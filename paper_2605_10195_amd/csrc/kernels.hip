@@ -869,8 +869,9 @@ __device__ __forceinline__ void walk_scores(const bf16x8 (&qf)[NT][D / 32], cons
 
 // Online softmax and O^T += V^T P^T for the same tiles; P rounded to fp16, row sums by MFMA
 // against ones (see block_math_f16).  Rows of a tile outside [lo, hi) see nothing of the block.
-template <bool FP8, int D, int NT>
-__device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&o)[NT][D / 16],
+template <bool FP8, bool TREE, int D, int NT>
+__device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const int (&qidx)[NT],
+                                                const uint32_t (&dmask)[NT], f32x4 (&o)[NT][D / 16],
                                                 float (&m)[NT], f32x4 (&lacc)[NT],
                                                 const f32x4 (&sa)[NT], const f32x4 (&sb)[NT],
                                                 const f16x8 (&vh)[D / 16], bool tok_masked,
@@ -892,13 +893,29 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], f32x4 (&
       x[4 + i] = FP8 ? sb[nt][i] * c : sb[nt][i];
     }
     if (tok_masked || partial_tile) {
-      int vis = limit[nt] - pos_l;
-      vis = vis < valid_l ? vis : valid_l;
-      vis -= 8 * (jj & 1);
       const int row = nt * 16 + m16;
-      vis = (row >= lo && row < hi) ? vis : 0;
+      const bool row_in = row >= lo && row < hi;
+      if (TREE) {
+        // Draft tree: positions below base = T - q_len are visible, position base + k iff bit k of
+        // the row's mask is set.  The lane's 8 tokens start at relative position rel; shifting
+        // {mask, 32 ones} right by rel + 32 puts their visibility into the low 8 bits.
+        const int base = limit[nt] - 1 - qidx[nt];
+        const int first = 8 * (jj & 1);
+        const int sh = pos_l + first - base + 32;
+        const uint64_t bits = (static_cast<uint64_t>(dmask[nt]) << 32) | 0xffffffffull;
+        uint32_t vm = sh <= 0 ? 0xffu : (sh >= 64 ? 0u : static_cast<uint32_t>(bits >> sh) & 0xffu);
+        const int have = valid_l - first;  // tokens of the lane's 8 that exist
+        vm = row_in ? vm : 0u;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+        for (int i = 0; i < 8; ++i) x[i] = (i < have && ((vm >> i) & 1u)) ? x[i] : kNegInf;
+      } else {
+        int vis = limit[nt] - pos_l;
+        vis = vis < valid_l ? vis : valid_l;
+        vis -= 8 * (jj & 1);
+        vis = row_in ? vis : 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+      }
     }
     const float mx8 = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
@@ -974,7 +991,7 @@ __device__ __forceinline__ void walk_write_rows(float *out, float *lse, const Sh
   }
 }
 
-template <int KV, int D, int NTW, int NW>
+template <int KV, int D, int NTW, int NW, bool TREE>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_tree_walk_kernel(WalkArgs p, Shape sh) {
   constexpr bool FP8 = KV == kFP8;
   constexpr int ESZ = FP8 ? 1 : 2;
@@ -1034,7 +1051,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
 
   // ---- rows of this wavefront
   bf16x8 qf[NTW][D / 32];
-  int limit[NTW], qtok[NTW];
+  int limit[NTW], qtok[NTW], qidx[NTW];
+  uint32_t dmask[NTW];
   f32x4 o[NTW][D / 16], lacc[NTW];
   float m[NTW];
 #pragma unroll
@@ -1042,6 +1060,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     const int r = nt * 16 + m16;
     limit[nt] = INT_MAX;
     qtok[nt] = 0;
+    qidx[nt] = 0;
+    dmask[nt] = 0;
     m[nt] = kNegInf;
     lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -1050,6 +1070,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (qt_begin + r / sh.G));
       qtok[nt] = qr.x;
       limit[nt] = qr.y;
+      if (TREE) {
+        const int2 dm = *reinterpret_cast<const int2 *>(p.qt_mask + 2 * qr.x);
+        qidx[nt] = dm.x;
+        dmask[nt] = static_cast<uint32_t>(dm.y);
+      }
       const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
                            (static_cast<int64_t>(qr.x) * sh.Hq + g * sh.G + r % sh.G) * D + jj * 8;
 #pragma unroll
@@ -1125,7 +1150,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       f16x8 vh[D / 16];
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
-      walk_softmax_pv<FP8, D, NTW>(limit, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
+      walk_softmax_pv<FP8, TREE, D, NTW>(limit, qidx, dmask, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
                                    c, lo, hi);
     };
@@ -1221,7 +1246,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
         for (int s = 0; s < D / 16; ++s) vh[s] = __builtin_bit_cast(f16x8, bf16x8_to_f16x8(vr[s]));
       }
       if (more) issue_v(nxt);
-      walk_softmax_pv<FP8, D, NTW>(limit, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
+      walk_softmax_pv<FP8, TREE, D, NTW>(limit, qidx, dmask, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
                                    c, lo, hi);
     };
@@ -1289,6 +1314,8 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
     const int qt = p.qt_rec[2 * (qt_begin + r / G)];
     const int hh = r % G;
     const int limit = p.qt_rec[2 * (qt_begin + r / G) + 1];
+    const int d_base = p.qt_mask ? limit - 1 - p.qt_mask[2 * qt] : 0;
+    const uint32_t d_mask = p.qt_mask ? static_cast<uint32_t>(p.qt_mask[2 * qt + 1]) : 0u;
     const int64_t qbase = (static_cast<int64_t>(qt) * sh.Hq + g * G + hh) * D;
     __syncthreads();
     for (int d = lane; d < D; d += 64) qs[d] = load_elem<QT>(p.q, qbase + d);
@@ -1304,7 +1331,13 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
       float s = kNegInf;
       if (ok) {
         const int vp = p.pg_rec[2 * e + 1];
-        ok = slot < (vp & 127) && (vp >> 7) + slot < limit;
+        const int pos = (vp >> 7) + slot;
+        bool seen = pos < limit;
+        if (p.qt_mask) {  // draft tree: everything before the drafts, then the mask's bits
+          const int rel = pos - d_base;
+          seen = rel < 0 || (rel < 32 && ((d_mask >> rel) & 1u));
+        }
+        ok = slot < (vp & 127) && seen;
       }
       if (ok) {
         const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e]) * sh.page_tiles + g);
@@ -1570,21 +1603,24 @@ hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipSt
                     : launch_coop_ntw<kFP8, 128>(sh, a, ntw, stream);
 }
 
-template <int KV, int D, int NW>
+template <int KV, int D, int NW, bool TREE>
 static hipError_t launch_walk_ntw(const Shape &sh, const WalkArgs &a, int ntw, hipStream_t stream) {
   const dim3 grid(a.n_items), block(64 * NW);
   if (ntw == 1)
-    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 1, NW>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 1, NW, TREE>), grid, block, 0, stream, a, sh);
   else if (ntw == 2)
-    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 2, NW>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 2, NW, TREE>), grid, block, 0, stream, a, sh);
   else
-    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 4, NW>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 4, NW, TREE>), grid, block, 0, stream, a, sh);
   return hipGetLastError();
 }
 
 template <int KV, int D>
 static hipError_t launch_walk_nw(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {
-  return waves == 4 ? launch_walk_ntw<KV, D, 4>(sh, a, ntw, stream) : launch_walk_ntw<KV, D, 8>(sh, a, ntw, stream);
+  if (a.qt_mask)  // draft-tree masks: 4 wavefronts per workgroup only
+    return waves == 4 ? launch_walk_ntw<KV, D, 4, true>(sh, a, ntw, stream) : hipErrorInvalidValue;
+  return waves == 4 ? launch_walk_ntw<KV, D, 4, false>(sh, a, ntw, stream)
+                    : launch_walk_ntw<KV, D, 8, false>(sh, a, ntw, stream);
 }
 
 hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {

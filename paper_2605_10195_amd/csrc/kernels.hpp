@@ -35,6 +35,10 @@ struct AttnArgs {
   const int32_t *part_indptr, *part_base, *part_hstride;
   float *out, *lse;  // lse may be null
   float scale_log2;
+  // Draft-tree visibility, or null for the causal chain: 2 ints per query token {index i of the
+  // query in its request, mask}; with base = limit - 1 - i the query sees path positions below base
+  // and position base + k iff bit k of the mask is set.  Only the generic kernel reads it.
+  const int32_t *qt_mask;
 };
 
 // Tree-walk kernel: one workgroup per work item.
@@ -53,6 +57,7 @@ struct WalkArgs {
   const int32_t *qt_rec;  // 2 ints per row-set entry: {query token, visible path length}
   float *out, *lse;       // lse may be null
   float scale_log2;
+  const int32_t *qt_mask; // as in AttnArgs; null for the causal chain
 };
 
 struct MergeArgs {

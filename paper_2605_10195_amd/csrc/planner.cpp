@@ -24,7 +24,8 @@ struct Segment {
 }  // namespace
 
 PlanError Planner::begin(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
-                         int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
+                         const uint32_t *draft_masks, int32_t n_leaves, int32_t num_q_heads,
+                         int32_t num_kv_heads,
                          int32_t prefix_chunk_pages, int32_t suffix_chunk_pages,
                          int32_t walk_row_tiles, int32_t walk_waves, Plan *plan) {
   if (n_leaves < 0 || (n_leaves > 0 && !leaves)) return PlanError::kInvalid;
@@ -62,6 +63,7 @@ PlanError Planner::begin(const PageTable &pt, const int32_t *leaves, const int32
   pl.path_indptr.assign(n_leaves + 1, 0);
   pl.qoff.assign(n_leaves, 0);
   pl.req_tokens.assign(n_leaves, 0);
+  pl.req_minlim.assign(n_leaves, 0);
   std::vector<int32_t> tmp;
   for (int32_t i = 0; i < n_leaves; ++i) {
     const int32_t leaf = leaves[i];
@@ -87,7 +89,26 @@ PlanError Planner::begin(const PageTable &pt, const int32_t *leaves, const int32
     if (T >= (1 << 24)) return PlanError::kTooLarge;  // positions are packed in 24 bits
     pl.qoff[i] = static_cast<int32_t>(pl.qt_limit.size());
     for (int32_t j = 0; j < ql; ++j) pl.qt_limit.push_back(static_cast<int32_t>(T) - ql + 1 + j);
+    int32_t lead = 1;
+    if (draft_masks) {
+      // Query j of the request sees every position before the q_len drafts and draft k iff bit k
+      // of its mask is set.
+      if (ql > 32) return PlanError::kInvalid;
+      const uint32_t *mk = draft_masks + pl.qoff[i];
+      uint32_t all = 0xffffffffu;
+      for (int32_t j = 0; j < ql; ++j) {
+        if (ql < 32 && (mk[j] >> ql) != 0) return PlanError::kInvalid;
+        if (mk[j] == 0 && T == ql) return PlanError::kEmptyPath;
+        all &= mk[j];
+        pl.qt_mask.push_back(j);
+        pl.qt_mask.push_back(static_cast<int32_t>(mk[j]));
+      }
+      lead = 0;
+      while (lead < ql && ((all >> lead) & 1)) ++lead;
+    }
+    pl.req_minlim[i] = static_cast<int32_t>(T) - ql + lead;
   }
+  if (draft_masks) pl.req_masks.assign(draft_masks, draft_masks + pl.qt_limit.size());
   pl.valid = true;
   return PlanError::kOk;
 }
@@ -397,7 +418,8 @@ PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
 //  * nodes of a row block: the nodes with >= 1 token on its requests' paths, in order of first
 //    encounter (requests in order, each path root first), each with the row range
 //    [first row of the first request through it, last row + 1 of the last request through it)
-//    and minlim = min over those requests of T - q_len + 1.  A node whose range touches two
+//    and minlim = min over those requests of the first path position some query of the request
+//    does not see (T - q_len + 1 for the causal chain).  A node whose range touches two
 //    wavefronts is shared, else it is private to wavefront lo / C.
 //  * blocks of a row block: its shared nodes in encounter order, then the private nodes of
 //    wavefront 0, 1, ..; a node's pages two at a time (the last block of an odd run has no
@@ -570,7 +592,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     const int32_t st = fresh();
     nodes.clear();
     for (const Placed &pc : cur) {
-      const int32_t i = pc.req, rows = rows_of(i), minlim = pl.qt_limit[qoff[i]];
+      const int32_t i = pc.req, rows = rows_of(i), minlim = pl.req_minlim[i];
       for (int32_t k = path_indptr[i]; k < path_indptr[i + 1]; ++k) {
         const int32_t u = path_nodes[k];
         if (pt.node(u).n_tokens == 0) continue;
@@ -719,6 +741,7 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
     const int32_t q0 = pl.qoff[i];
     if (pl.qt_limit[q0 + ql - 1] + delta >= (1 << 24)) return false;
     for (int32_t j = 0; j < ql; ++j) pl.qt_limit[q0 + j] += delta;
+    pl.req_minlim[i] += delta;
     const bool first_visit = stamp_[u] != st;
     stamp_[u] = st;
     if (first_visit) pl.unique_tokens += delta;

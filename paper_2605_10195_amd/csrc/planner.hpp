@@ -32,6 +32,7 @@ namespace spex {
 struct Plan {
   // ---- cache key
   std::vector<int32_t> req_leaves, req_q_lens;
+  std::vector<uint32_t> req_masks;  // draft visibility masks per query token, or empty (causal chain)
   uint64_t table_version = 0, structure_version = 0;
   int32_t req_prefix_chunk = -1, req_suffix_chunk = -1;
   int32_t num_q_heads = 0, num_kv_heads = 0;
@@ -45,6 +46,10 @@ struct Plan {
   std::vector<int32_t> qoff;                     // first query token of each request
   std::vector<int32_t> req_tokens;               // tokens of each requested node when planned / patched
   int64_t unique_tokens = 0;                     // KV tokens on the requested paths, each node once
+  // first path position that some query of the request does not see: T - q_len + (number of
+  // leading drafts all its queries see); T - q_len + 1 for the causal chain
+  std::vector<int32_t> req_minlim;
+  std::vector<int32_t> qt_mask;                  // {index of the query in its request, mask} per query token; empty without masks
   // ---- where an append to a requested node shows up (see Planner::patch_lengths)
   std::vector<int32_t> req_split_pg, req_in_group, req_qtpos_indptr, req_qtpos;
   std::vector<int32_t> req_walk_blk, req_walk_qt;
@@ -105,7 +110,7 @@ class Planner {
  public:
   // Validates the request, walks the paths and computes the limits; the lists follow on demand.
   PlanError begin(const PageTable &pt, const int32_t *leaves, const int32_t *q_lens,
-                  int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
+                  const uint32_t *draft_masks, int32_t n_leaves, int32_t num_q_heads, int32_t num_kv_heads,
                   int32_t prefix_chunk_pages, int32_t suffix_chunk_pages, int32_t walk_row_tiles,
                   int32_t walk_waves, Plan *plan);
   void ensure_csr(const PageTable &pt, Plan *plan);

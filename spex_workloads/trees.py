@@ -51,6 +51,9 @@ class Workload:
     q_keys: List[int] = field(default_factory=list)     # random-stream key of each node's queries
     sm_scale: float = 0.0
     n_trees: int = 0
+    # visibility mask of every query token among its request's q_len drafts (bit k = draft k is
+    # seen), or None for the causal chain
+    draft_masks: Optional[List[int]] = None
 
     def __post_init__(self):
         if self.sm_scale == 0.0:
@@ -321,9 +324,11 @@ def spec_at_scale(seed: int = 4, n_queries: int = 256, prompt: int = 2048, step:
 
 def tot_with_drafts(seed: int = 5, n_queries: int = 64, prompt: int = 1024, step: int = 128,
                     depth: int = 3, drafts: int = 6,
-                    heads=(40, 8, 128), kv_dtype: str = "fp8_e4m3", q_dtype: str = "bf16") -> Workload:
+                    heads=(40, 8, 128), kv_dtype: str = "fp8_e4m3", q_dtype: str = "bf16",
+                    token_trees: bool = False) -> Workload:
     """Config 5: per query a binary tree prompt -> 2 -> 4 -> 8 with one step per node; every
-    leaf then receives `drafts` draft tokens that are verified by `drafts` causal queries."""
+    leaf then receives `drafts` draft tokens that are verified by `drafts` causal queries, or,
+    with token_trees, by queries that see the drafts along a seeded token tree."""
     wl = Workload("tot_with_drafts", heads[0], heads[1], heads[2], 16, q_dtype, kv_dtype, 0.5, seed,
                   n_trees=n_queries)
     b = _Builder(wl)
@@ -342,6 +347,27 @@ def tot_with_drafts(seed: int = 5, n_queries: int = 64, prompt: int = 1024, step
         for leaf in level:
             b.append(leaf, drafts)
             b.request(leaf, drafts)
+    return with_draft_trees(wl) if token_trees else wl
+
+
+def draft_tree_masks(seed: int, key: int, n: int) -> List[int]:
+    """A seeded draft token tree of n tokens (Sec. 6.5 verifies token trees of 4-16 drafts): draft
+    0 is the root, the parent of draft j > 0 is drawn from the drafts before it; the mask of a
+    draft has the bits of its ancestors and its own."""
+    rng = np.random.default_rng([seed & 0xFFFFFFFF, key & 0xFFFFFFFF, (key >> 32) & 0xFFFFFFFF, n])
+    masks = [1]
+    for j in range(1, n):
+        masks.append(masks[int(rng.integers(0, j))] | (1 << j))
+    return masks
+
+
+def with_draft_trees(wl: Workload) -> Workload:
+    """The same workload with every request's q_len queries arranged as a seeded token tree."""
+    assert all(ql <= 32 for ql in wl.q_lens)
+    wl.draft_masks = []
+    for key, ql in zip(wl.q_keys, wl.q_lens):
+        wl.draft_masks += draft_tree_masks(wl.seed, key, ql)
+    wl.name += "_token_trees"
     return wl
 
 

@@ -27,7 +27,7 @@ def run_gpu(wl, tree=None, **kw):
     if own:
         tree = build_gpu_tree(wl, **kw)
     q = sw.gen_queries(wl, device="cuda")
-    out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+    out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
     torch.cuda.synchronize()
     res = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
     if own:
@@ -35,9 +35,9 @@ def run_gpu(wl, tree=None, **kw):
     return res
 
 
-def run_oracle(wl, leaves=None, q_lens=None, q_rows=None):
+def run_oracle(wl, leaves=None, q_lens=None, q_rows=None, draft_masks=None):
     """Oracle output for all requested nodes, or for a subset (then only the nodes on those
-    paths hold values)."""
+    paths hold values; draft_masks are then the subset's)."""
     sink = OracleSink.for_workload(wl)
     only = None
     if leaves is not None:
@@ -50,8 +50,8 @@ def run_oracle(wl, leaves=None, q_lens=None, q_rows=None):
     sw.replay(wl, sink, device="cpu", only_nodes=only)
     q = queries_fp64(sw.gen_queries(wl, device="cpu"))
     if leaves is None:
-        return sink.tree.attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
-    return sink.tree.attention(leaves, q_lens, q[q_rows], wl.sm_scale)
+        return sink.tree.attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
+    return sink.tree.attention(leaves, q_lens, q[q_rows], wl.sm_scale, draft_masks=draft_masks)
 
 
 def assert_close(got, ref, kv_dtype, what=""):

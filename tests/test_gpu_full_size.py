@@ -68,3 +68,29 @@ def test_full_config_sampled_outputs(name, n_sample, mode):
     # queries, so identical query vectors would give identical rows; here: outputs stay inside the
     # value range of the inputs (a convex combination of V rows with |v| <= 0.5 * 4.9)
     assert np.max(np.abs(out)) <= 0.5 * 4.9 + 1e-3
+
+
+@pytest.mark.parametrize("drafts", [6, 16])
+def test_full_config_5_with_draft_token_trees(drafts):
+    """Config 5 with the drafts of every branch arranged as a token tree (Sec. 6.5: 4-16 drafts),
+    through spex_tree_decode_attention_masked, on sampled branches."""
+    import paper_2605_10195_amd as spex
+    wl = sw.tot_with_drafts(drafts=drafts, token_trees=True, **({} if drafts == 6 else {"heads": (32, 8, 128)}))
+    n_pages = wl.peak_pages()
+    order = np.random.default_rng(1000).permutation(n_pages).tolist()
+    tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
+                         wl.kv_dtype, num_pages=n_pages, device="cuda", free_order=order, interleave_kv=True)
+    sw.replay(wl, tree, device="cuda")
+    q = sw.gen_queries(wl, device="cuda")
+    out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
+    torch.cuda.synchronize()
+    info = tree.last_launch_info()
+    tree.close()
+    assert info["walk_row_tiles"] > 0 and info["kv_tokens"] == wl.unique_kv_tokens()
+    out, lse = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+    picks = np.sort(np.random.default_rng(8).choice(len(wl.leaves), size=40, replace=False)).tolist()
+    leaves, q_lens, rows = sample_rows(wl, picks)
+    ref = run_oracle(wl, leaves, q_lens, rows, draft_masks=[wl.draft_masks[r] for r in rows])
+    max_abs, rel = assert_close((out[rows], lse[rows]), ref, wl.kv_dtype, wl.name)
+    print(f"{wl.name} {drafts} drafts: max_abs={max_abs:.2e} rel_l2={rel:.2e}")

@@ -410,3 +410,140 @@ def test_decode_loop_with_append_tokens(kv_dtype):
         want_v = torch.cat([b for _, b in grown[u]], 0)
         assert torch.equal(gk.cpu().view(want_k.dtype), want_k) and torch.equal(gv.cpu().view(want_v.dtype), want_v)
     tree.close()
+
+
+# ------------------------------------------------------------------ draft token trees (Sec. 6.5)
+TOKEN_TREE_CASES = [
+    dict(seed=71, heads=(8, 2, 64), kv_dtype="bf16", max_q_len=16),      # up to 64 rows per request
+    dict(seed=72, heads=(4, 4, 128), kv_dtype="bf16", max_q_len=32),     # the widest mask
+    dict(seed=73, heads=(28, 4, 128), kv_dtype="bf16", max_q_len=8),
+    dict(seed=74, heads=(10, 2, 128), kv_dtype="fp8_e4m3", max_q_len=12),
+    dict(seed=75, heads=(8, 8, 64), kv_dtype="fp8_e4m3", max_q_len=16),
+    dict(seed=76, heads=(4, 2, 64), kv_dtype="f32", max_q_len=8),        # generic kernels only
+    dict(seed=77, heads=(6, 3, 40), kv_dtype="bf16", max_q_len=8),       # no MFMA kernel: generic
+]
+
+
+def token_tree_workload(case, arbitrary=False):
+    wl = sw.random_trace(case["seed"], heads=case["heads"], kv_dtype=case["kv_dtype"],
+                         q_dtype="f32" if case["kv_dtype"] == "f32" else "bf16",
+                         n_ops=60, max_tokens=90, max_q_len=case["max_q_len"])
+    wl = sw.with_draft_trees(wl)
+    if arbitrary:
+        # any bit pattern is a valid request as long as every query sees something: also queries
+        # that see no draft at all (not even themselves) or a later draft
+        rng = np.random.default_rng(case["seed"])
+        masks, o = [], 0
+        for leaf, ql in zip(wl.leaves, wl.q_lens):
+            prefix = wl.path_tokens(leaf) - ql
+            for j in range(ql):
+                m = int(rng.integers(0, 1 << ql)) if rng.random() < 0.8 else 0
+                masks.append(m if (m or prefix) else 1 << j)
+            o += ql
+        wl.draft_masks = masks
+    return wl
+
+
+@pytest.mark.parametrize("case", TOKEN_TREE_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")
+@pytest.mark.parametrize("mode,row_tiles", [(0, 0), (1, 0), (3, 0), (3, 2), (3, 4)])
+@pytest.mark.parametrize("arbitrary", [False, True], ids=["ancestors", "any_bits"])
+def test_draft_token_trees_match_oracle(case, mode, row_tiles, arbitrary):
+    import paper_2605_10195_amd as spex
+    wl = token_tree_workload(case, arbitrary)
+    assert max(wl.q_lens) > 4
+    if mode == 3 and not walk_applies(wl, row_tiles):
+        with pytest.raises(spex.SpexError) as e:
+            run_gpu(wl, kernel_mode=3, walk_row_tiles=row_tiles)
+        assert e.value.name == "UNSUPPORTED"
+        return
+    tree = build_gpu_tree(wl, kernel_mode=mode, walk_row_tiles=row_tiles)
+    got = run_gpu(wl, tree=tree)
+    info = tree.last_launch_info()
+    tree.close()
+    if mode == 3 or (mode == 0 and walk_applies(wl)):
+        assert info["walk_row_tiles"] > 0 and info["walk_waves"] == 4
+    else:
+        assert info["walk_row_tiles"] == 0
+    assert_close(got, run_oracle(wl), case["kv_dtype"], wl.name)
+
+
+@pytest.mark.parametrize("case", TOKEN_TREE_CASES[:5], ids=lambda c: f"{c['kv_dtype']}-{c['heads']}")
+def test_chain_masks_give_the_bits_of_the_call_without_masks(case):
+    wl = token_tree_workload(case)
+    chain = [(2 << j) - 1 for ql in wl.q_lens for j in range(ql)]
+    q = sw.gen_queries(wl, device="cuda")
+    for mode in (3, 1):
+        tree = build_gpu_tree(wl, kernel_mode=mode)
+        a, la = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        b, lb = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=chain)
+        assert tree.last_launch_info()["plan_rebuilt"] == 1       # the masks are part of the request
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and torch.equal(la, lb)
+        tree.close()
+
+
+def test_draft_masks_where_no_kernel_takes_them():
+    import paper_2605_10195_amd as spex
+    wl = token_tree_workload(TOKEN_TREE_CASES[0])
+    q = sw.gen_queries(wl, device="cuda")
+    for kw in (dict(kernel_mode=2), dict(kernel_mode=3, walk_waves=8)):
+        tree = build_gpu_tree(wl, **kw)
+        with pytest.raises(spex.SpexError) as e:
+            tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
+        assert e.value.name == "UNSUPPORTED"
+        tree.close()
+    # automatic mode with 8 wavefronts asked for: the generic kernels take the request
+    tree = build_gpu_tree(wl, kernel_mode=0, walk_waves=8)
+    got = run_gpu(wl, tree=tree)
+    assert tree.last_launch_info()["walk_row_tiles"] == 0
+    tree.close()
+    assert_close(got, run_oracle(wl), "bf16", wl.name)
+
+
+TOKEN_TREE_SHAPES = [
+    sw.tot_with_drafts(n_queries=3, prompt=250, step=56, token_trees=True),                       # 6 drafts, G = 5
+    sw.tot_with_drafts(n_queries=2, prompt=130, step=40, drafts=16, heads=(16, 4, 128), token_trees=True),
+    sw.tot_with_drafts(n_queries=2, prompt=200, step=30, drafts=8, heads=(32, 4, 128), kv_dtype="bf16",
+                       token_trees=True),
+    sw.tot_with_drafts(n_queries=2, prompt=90, step=24, drafts=4, heads=(16, 2, 64), kv_dtype="bf16",
+                       token_trees=True),
+]
+
+
+@pytest.mark.parametrize("wl", TOKEN_TREE_SHAPES, ids=lambda w: f"{w.name}_{w.kv_dtype}_{w.num_q_heads}_{w.q_lens[0]}")
+@pytest.mark.parametrize("mode", [0, 1])
+def test_token_tree_sizes_of_the_paper_match_oracle(wl, mode):
+    # Sec. 6.5 verifies token trees of 16, 8 and 4 drafts per branch
+    tree = build_gpu_tree(wl, kernel_mode=mode)
+    got = run_gpu(wl, tree=tree)
+    assert (tree.last_launch_info()["walk_row_tiles"] > 0) == (mode == 0)
+    tree.close()
+    assert_close(got, run_oracle(wl), wl.kv_dtype, wl.name)
+
+
+def test_decode_loop_with_draft_masks_patches_lengths():
+    """Tokens appended in place shift the window of drafts; the cached lists (with their masks) are
+    patched and every call matches the oracle on the grown tree."""
+    wl = sw.bfs_tot(n_queries=2, prompt=48, step=20)
+    wl.q_lens = [5] * len(wl.leaves)
+    wl = sw.with_draft_trees(wl)
+    tree = build_gpu_tree(wl, extra_pages=64, kernel_mode=3)
+    from oracle.adapters import OracleSink, queries_fp64
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = sw.gen_queries(wl, device="cuda")
+    qd = queries_fp64(q)
+    states = set()
+    for step in range(12):
+        k = sw.normal_values(6, 1, 900 + step, torch.arange(len(wl.leaves)), 8, 128, 0.5, "cuda").to(torch.bfloat16)
+        v = sw.normal_values(6, 2, 900 + step, torch.arange(len(wl.leaves)), 8, 128, 0.5, "cuda").to(torch.bfloat16)
+        tree.append_tokens(wl.leaves, k, v)
+        for i, leaf in enumerate(wl.leaves):
+            sink.append(leaf, k[i:i + 1], v[i:i + 1])
+        out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
+        states.add(tree.last_launch_info()["plan_rebuilt"])
+        ref = sink.tree.attention(wl.leaves, wl.q_lens, qd, wl.sm_scale, draft_masks=wl.draft_masks)
+        got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+        assert_close(got, ref, "bf16", f"masked decode step {step}")
+    assert states == {1, 2}
+    tree.close()

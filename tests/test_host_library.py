@@ -194,12 +194,16 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
     """Bit-exact against the reference model, and -- independently of both -- every row of every
     row block meets every page of its path exactly once, with the right positions and masks."""
     tree.set_tuning(0, 0, 0, row_tiles, waves)
-    got = tree.walk_dump(wl.leaves, wl.q_lens)
-    want = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, row_tiles, waves)
+    got = tree.walk_dump(wl.leaves, wl.q_lens, wl.draft_masks)
+    want = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, row_tiles, waves,
+                         draft_masks=wl.draft_masks)
     for k in WALK_KEYS:
         assert got[k] == want[k], k
     G = wl.num_q_heads // wl.num_kv_heads
     q_lens = wl.q_lens if wl.q_lens is not None else [1] * len(wl.leaves)
+    masks = wl.draft_masks                                       # the chain if none are given
+    if masks is None:
+        masks = [(2 << j) - 1 for ql in q_lens for j in range(ql)]
     if not got["available"]:
         assert max(q * G for q in q_lens) > (16 * row_tiles if row_tiles else 64)
         return got
@@ -234,8 +238,10 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
             for e in range(qt_count[w]):
                 t, lim = qt[qt_first[w] + e]
                 assert lim == ref_limit(ref, wl, tok_owner[t], t - qoff[tok_owner[t]], q_lens)
+                j = t - qoff[tok_owner[t]]
+                hidden = [lim - 1 - j + k for k in range(q_lens[tok_owner[t]]) if not (masks[t] >> k) & 1]
                 for hh in range(G):
-                    row_tok[w * C + e * G + hh] = (t, lim)
+                    row_tok[w * C + e * G + hh] = (t, hidden)
                 seen_tokens.append(t)
             assert qt_count[w] * G <= C
         pages_of_row = {r: [] for r in row_tok}
@@ -251,15 +257,15 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
                 if blk[3]:
                     entries.append((blk[2], blk[3] >> 7, blk[3] & 127))
                     assert (blk[1] & 127) == 16
-                end = entries[-1][1] + entries[-1][2]
+                start, end = entries[0][1], entries[-1][1] + entries[-1][2]
                 need_mask = len(entries) == 1 or any(v != 16 for _, _, v in entries)
-                for r, (t, lim) in row_tok.items():
+                for r, (t, hidden) in row_tok.items():
                     if lo <= r < hi:
                         pages_of_row[r] += entries
-                        need_mask = need_mask or lim < end
+                        need_mask = need_mask or any(start <= h < end for h in hidden)
                 assert (blk[5] & 1) or not need_mask               # a needed mask is never dropped
             used_blocks[a:b] = True
-        for r, (t, lim) in row_tok.items():
+        for r, (t, _) in row_tok.items():
             pages, valid = ref.path_pages(wl.leaves[tok_owner[t]])
             pos = np.concatenate([[0], np.cumsum(valid)])[:-1]
             want_entries = sorted((p, int(s), v) for p, s, v in zip(pages, pos, valid) if v > 0)
@@ -312,6 +318,59 @@ def test_walk_lists_config_shapes(wl):
             check_walk_lists(tree, ref, wl, rt, nw)
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_walk_lists_with_draft_token_trees(seed):
+    """Sec. 6.5 token trees: the mask flag of a block follows the first draft some query does not
+    see; everything else is as for the chain."""
+    if seed < 3:
+        wl = sw.with_draft_trees(sw.random_trace(520 + seed, n_ops=70, max_tokens=60, max_q_len=[4, 8, 16][seed],
+                                                 heads=[(8, 2, 64), (4, 4, 128), (4, 2, 64)][seed]))
+    else:
+        wl = sw.tot_with_drafts(n_queries=2, prompt=70, step=33, drafts=6, token_trees=True)
+    assert any(m != (2 << j) - 1 for ql, o in zip(wl.q_lens, np.cumsum([0] + wl.q_lens[:-1]))
+               for j, m in enumerate(wl.draft_masks[o:o + ql]))
+    n_pages = wl.peak_pages()
+    tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
+    replay_both(wl, tree, ref)
+    for rt in (0, 1, 2):
+        check_walk_lists(tree, ref, wl, rt, 4)
+    # the chain written as masks gives the lists of the call without masks
+    chain = [(2 << j) - 1 for ql in wl.q_lens for j in range(ql)]
+    tree.set_tuning(0, 0, 0, 0, 0)
+    a = tree.walk_dump(wl.leaves, wl.q_lens, chain)
+    b = tree.walk_dump(wl.leaves, wl.q_lens)
+    assert b["plan_state"] == 1                                  # masks are part of the cached request
+    for k in WALK_KEYS:
+        assert a[k] == b[k], k
+    assert tree.walk_dump(wl.leaves, wl.q_lens)["plan_state"] == 0
+
+
+def test_draft_mask_errors():
+    t = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=8, host_only=True)
+    (r,) = t.fork(-1, 1)
+    t.append_step(r, None, None, n_tokens=40)
+    with pytest.raises(spex.SpexError) as e:
+        t.walk_dump([r], [3], [1, 3, 8])                          # bit 3 with 3 drafts
+    assert e.value.name == "INVALID_ARG"
+    with pytest.raises(spex.SpexError) as e:
+        t.walk_dump([r], [33], [1] * 33)                          # more than 32 drafts
+    assert e.value.name == "INVALID_ARG"
+    with pytest.raises(spex.SpexError) as e:
+        t.walk_dump([r], None, [1])                               # masks need q_lens
+    assert e.value.name == "INVALID_ARG"
+    with pytest.raises(spex.SpexError) as e:
+        t.walk_dump([r], [40], None)                              # chain of 40 is fine without masks ..
+        t.walk_dump([r], [41], None)                              # .. 41 queries on 40 tokens are not
+    assert e.value.name == "EMPTY_PATH"
+    (s,) = t.fork(-1, 1)
+    t.append_step(s, None, None, n_tokens=3)
+    with pytest.raises(spex.SpexError) as e:
+        t.walk_dump([s], [3], [1, 0, 5])                          # query 1 sees nothing at all
+    assert e.value.name == "EMPTY_PATH"
+    assert t.walk_dump([s], [3], [1, 2, 5])["available"] == 1
+    assert t.walk_dump([r, s], [2, 3], [0, 0, 1, 2, 5])["available"] == 1   # r's drafts still see its prefix
+
+
 def test_walk_lists_not_available_for_wide_requests():
     wl = sw.random_trace(77, n_ops=30, max_tokens=90, max_q_len=9, heads=(16, 2, 64))   # up to 72 rows
     tree, ref = host_tree(wl, wl.peak_pages()), PageTableRef(wl.peak_pages(), 16)
@@ -331,8 +390,10 @@ def grow_and_compare(wl, n_steps, seed):
     replay_both(wl, tree, ref)
     rng = np.random.default_rng(seed)
     childless = [u for u in sorted(set(wl.leaves)) if not ref.has_live_children(u)]
-    tree.plan_dump(wl.leaves, wl.q_lens)
-    tree.walk_dump(wl.leaves, wl.q_lens)
+    masks = wl.draft_masks          # with masks only the tree-walk lists are compared: the
+    if masks is None:               # split lists' dump takes no masks and would plan afresh
+        tree.plan_dump(wl.leaves, wl.q_lens)
+    tree.walk_dump(wl.leaves, wl.q_lens, masks)
     patched_seen = fresh_seen = 0
     for step in range(n_steps):
         grow = [u for u in childless if rng.random() < 0.7]
@@ -342,14 +403,16 @@ def grow_and_compare(wl, n_steps, seed):
             started_page |= tree.append_new_pages(u, n) > 0
             tree.append_step(u, None, None, n_tokens=n)
             ref.append(u, n)
-        got_walk = tree.walk_dump(wl.leaves, wl.q_lens)
-        got_split = tree.plan_dump(wl.leaves, wl.q_lens)
+        got_walk = tree.walk_dump(wl.leaves, wl.q_lens, masks)
         if grow:
             assert got_walk["plan_state"] == (1 if started_page else 2), step
-        want_split = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
-                              got_split["prefix_chunk_pages"], got_split["suffix_chunk_pages"])
-        want_walk = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads)
-        for k in PLAN_KEYS:
+        want_walk = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, draft_masks=masks)
+        got_split = want_split = {}
+        if masks is None:
+            got_split = tree.plan_dump(wl.leaves, wl.q_lens)
+            want_split = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
+                                  got_split["prefix_chunk_pages"], got_split["suffix_chunk_pages"])
+        for k in (PLAN_KEYS if masks is None else []):
             if k == "task_flags":
                 for a, b in zip(got_split[k], want_split[k]):
                     assert a & 2 == b & 2 and (a & 1) >= (b & 1)
@@ -371,7 +434,9 @@ def grow_and_compare(wl, n_steps, seed):
 @pytest.mark.parametrize("wl", [
     sw.bfs_tot(n_queries=2, prompt=40, step=19), sw.tot_with_drafts(n_queries=2, prompt=50, step=21),
     sw.mcts_skewed(n_queries=4, prompt=(30, 90), step=(5, 40), max_leaves=12),
-    sw.random_trace(640, n_ops=60, max_tokens=40, max_q_len=3, heads=(8, 2, 64))], ids=lambda w: w.name)
+    sw.random_trace(640, n_ops=60, max_tokens=40, max_q_len=3, heads=(8, 2, 64)),
+    sw.with_draft_trees(sw.random_trace(641, n_ops=14, max_tokens=40, max_q_len=5, heads=(8, 2, 64)))],
+    ids=lambda w: w.name)
 def test_length_patches_match_a_fresh_plan(wl):
     patched, fresh = grow_and_compare(wl, 24, 5)
     assert patched > 3 and fresh > 3          # both the patch path and the replan path were taken
