@@ -283,6 +283,7 @@ def main():
         "paper_context": PAPER_CONTEXT,
     }
 
+    sample_out = outs[0].clone()          # the decode loop below reuses outs[0] on a grown tree
     if args.decode_iters > 0:
         result["decode_loop"] = decode_loop(trees[0], wl, q, outs[0], lses[0], args.decode_iters, dev)
 
@@ -299,7 +300,7 @@ def main():
                                            "spec_at_scale": 512, "tot_with_drafts": 128,
                                            "tot_with_drafts_token_trees": 128}[wl.name]
         base, ref_out, leaves, q_lens = cpu_baseline(wl, n_cpu)
-        got = outs[0][:ref_out.shape[0]].cpu().numpy().astype(np.float64)
+        got = sample_out[:ref_out.shape[0]].cpu().numpy().astype(np.float64)
         base["gpu_vs_oracle_max_abs"] = float(np.max(np.abs(got - ref_out)))
         base["gpu_vs_oracle_rel_l2"] = float(np.linalg.norm(got - ref_out) / np.linalg.norm(ref_out))
         result["cpu_baseline"] = base

@@ -183,9 +183,10 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *   tree-walk: one workgroup carries a block of up to 16 * walk_row_tiles * walk_waves query rows (requested
  *     nodes that are neighbours in the tree) from the root to the requested nodes; pages shared
  *     by rows of several wavefronts are fetched once per workgroup, the softmax state stays in
- *     registers, only the output is written.  Needs MFMA-tiled pools and q_len * Hq / Hkv <= 64
- *     for every requested node.  Chosen automatically when it yields >= 128 workgroups or when
- *     no wavefront has more than 64 two-page blocks to walk;
+ *     registers, only the output is written.  Needs MFMA-tiled pools and Hq / Hkv <= 64 (one
+ *     query token's rows fit a wavefront; a requested node with more rows than a wavefront takes
+ *     is cut into pieces of whole query tokens).  Chosen automatically when it yields >= 128
+ *     workgroups or when no wavefront has more than 64 two-page blocks to walk;
  *   shared-prefix + suffix + merge: every shared node is read once for all rows below it, private
  *     suffixes are split for parallelism, partial softmax states go through memory.  Any shape.
  * Consecutive calls on one handle must use one stream or be separated by a synchronisation,
@@ -286,9 +287,11 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages
 
 /*
  * The tree-walk kernel's lists for a request (HOST arrays owned by the tree, valid until the next
- * call that plans or mutates it).  available = 0: some requested node has more rows than one
- * wavefront takes; the arrays are then empty.  With G = Hq / Hkv, C = 16 * row_tiles rows per
- * wavefront and NW = waves wavefronts per row block:
+ * call that plans or mutates it).  available = 0: one query token has more rows (Hq / Hkv) than
+ * one wavefront takes; the arrays are then empty.  With G = Hq / Hkv, C = 16 * row_tiles rows per
+ * wavefront and NW = waves wavefronts per row block (a requested node with more than C / G
+ * queries counts as ceil(q_len / (C / G)) requests of consecutive queries, sizes differing by
+ * at most one, the longer ones first):
  *   qt[2 * n_qt]: {query token, visible path length} of the requested nodes, grouped by root
  *     (roots in order of first appearance) and sorted by path below a root, so that the requests
  *     below any node are consecutive.

@@ -52,13 +52,17 @@ Plan for requested nodes leaves[0..L) with q_lens (caller order):
 Tree-walk lists (second kernel set: one workgroup carries a block of query rows
 from the root to the requested nodes).  With G = Hq / Hkv, request i has
 q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
-  * row_tiles is the value asked for (1, 2, 4) or, if 0, the smallest of them
-    with max rows <= 16 * row_tiles, raised to 2 when it is 1, some root has
-    more than 64 rows below it and sum over roots of ceil(rows / 128), times Hkv,
-    is at least 512; no lists if a request has more rows than C;
+  * row_tiles is the value asked for (1, 2, 4) or, if 0: 1 if no request has
+    more than 16 rows (raised to 2 when some root has more than 64 rows below
+    it and sum over roots of ceil(rows / 128), times Hkv, is at least 512), 2 if
+    none has more than 32, else 2 (4 if G > 32); no lists if G > C;
   * roots in order of first appearance; a root's requests sorted by path (node
     ids root first, lexicographic, a proper prefix first; ties in request
     order), so the requests below any node are consecutive;
+  * a request with more than cap = C // G query tokens is cut into
+    ceil(q_len / cap) pieces of consecutive query tokens, the first
+    q_len mod pieces of them one token longer than the rest; "request" below
+    means such a piece;
   * a row block has NW wavefronts: the value asked for (4, 8), 4 if 0;
   * a request joins the current wavefront while its rows fit, else starts the
     next; wavefront NW or a new root starts a new row block; `qt` lists
@@ -85,7 +89,7 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
 
 from __future__ import annotations
 
-from typing import Dict, List, Optional, Sequence
+from typing import Dict, List, Optional, Sequence, Tuple
 
 NO_NODE = -1
 
@@ -359,13 +363,18 @@ class PageTableRef:
         for path, n in zip(paths, rows):
             root_rows[path[0]] += n
         if row_tiles == 0:
-            if max(rows) > 64:
+            if G > 64:
                 return none
-            row_tiles = 1 if max(rows) <= 16 else (2 if max(rows) <= 32 else 4)
-            if row_tiles == 1 and max(root_rows.values()) > 64 and \
-                    sum(-(-r // 128) for r in root_rows.values()) * num_kv_heads >= 512:
+            if max(rows) <= 16:
+                row_tiles = 1
+                if max(root_rows.values()) > 64 and \
+                        sum(-(-r // 128) for r in root_rows.values()) * num_kv_heads >= 512:
+                    row_tiles = 2
+            elif max(rows) <= 32:
                 row_tiles = 2
-        elif max(rows) > 16 * row_tiles:
+            else:                      # wider requests are cut into pieces of whole query tokens
+                row_tiles = 4 if G > 32 else 2
+        elif G > 16 * row_tiles:
             return dict(none, row_tiles=0)
         C = 16 * row_tiles
         NW = waves if waves else 4
@@ -377,6 +386,16 @@ class PageTableRef:
                 t += self.tokens[w]
 
         order = sorted(range(L), key=lambda i: (roots.index(paths[i][0]), paths[i], i))
+        cap = C // G                   # query tokens a wavefront holds
+        pieces: List[Tuple[int, int, int]] = []     # (request, first query token, tokens)
+        for i in order:
+            n_p = -(-q_lens[i] // cap)
+            base, rem = divmod(q_lens[i], n_p)
+            j0 = 0
+            for k in range(n_p):
+                n = base + (1 if k < rem else 0)
+                pieces.append((i, j0, n))
+                j0 += n
         qt: List[int] = []
         row_blocks: List[List[int]] = []
         blocks: List[List[int]] = []
@@ -384,20 +403,18 @@ class PageTableRef:
         rbs_of_root: Dict[int, List[int]] = {r: [] for r in roots}
 
         # row block of every request (same packing as below), then the nodes met by several
-        rb_of, rb, cur_root, wave, used = {}, -1, None, 0, 0
-        for i in order:
+        rbs_through: Dict[int, set] = {}
+        rb, cur_root, wave, used = -1, None, 0, 0
+        for i, _, n in pieces:
             if paths[i][0] != cur_root:
                 cur_root, rb, wave, used = paths[i][0], rb + 1, 0, 0
-            elif used + rows[i] > C:
+            elif used + n * G > C:
                 wave, used = wave + 1, 0
                 if wave == NW:
                     rb, wave = rb + 1, 0
-            used += rows[i]
-            rb_of[i] = rb
-        rbs_through: Dict[int, set] = {}
-        for i in order:
+            used += n * G
             for w in paths[i]:
-                rbs_through.setdefault(w, set()).add(rb_of[i])
+                rbs_through.setdefault(w, set()).add(rb)
 
         def node_blocks(u, lo, hi, minlim):
             out = []
@@ -418,14 +435,14 @@ class PageTableRef:
             if not placed:
                 return
             nodes: Dict[int, List[int]] = {}          # insertion order = encounter order
-            for i, row0 in placed:
+            for i, row0, nrows in placed:
                 for w in paths[i]:
                     if self.tokens[w] == 0:
                         continue
                     if w not in nodes:
-                        nodes[w] = [row0, row0 + rows[i], first_unseen[i]]
+                        nodes[w] = [row0, row0 + nrows, first_unseen[i]]
                     else:
-                        nodes[w][1] = row0 + rows[i]
+                        nodes[w][1] = row0 + nrows
                         nodes[w][2] = min(nodes[w][2], first_unseen[i])
             first = len(blocks)
             shared = [b for w, (lo, hi, ml) in nodes.items() if lo // C != (hi - 1) // C
@@ -443,13 +460,13 @@ class PageTableRef:
 
         cur_root, wave, used = None, 0, 0
         placed, qt_first, qt_count = [], [0] * NW, [0] * NW
-        for i in order:
+        for i, j0, n in pieces:
             root = paths[i][0]
             if root != cur_root:
                 flush(cur_root, placed, qt_first, qt_count)
                 cur_root, wave, used = root, 0, 0
                 placed, qt_first, qt_count = [], [0] * NW, [0] * NW
-            elif used + rows[i] > C:
+            elif used + n * G > C:
                 wave, used = wave + 1, 0
                 if wave == NW:
                     flush(cur_root, placed, qt_first, qt_count)
@@ -457,11 +474,11 @@ class PageTableRef:
                     placed, qt_first, qt_count = [], [0] * NW, [0] * NW
             if qt_count[wave] == 0:
                 qt_first[wave] = len(qt) // 2
-            for j in range(q_lens[i]):
+            for j in range(j0, j0 + n):
                 qt += [qoff[i] + j, limits[qoff[i] + j]]
-            qt_count[wave] += q_lens[i]
-            placed.append((i, wave * C + used))
-            used += rows[i]
+            qt_count[wave] += n
+            placed.append((i, wave * C + used, n * G))
+            used += n * G
         flush(cur_root, placed, qt_first, qt_count)
 
         root_blocks = {r: sum(rb_total[b] for b in rbs_of_root[r]) for r in roots}

@@ -30,6 +30,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kNegInf = -__builtin_huge_valf();
+// Start value of the tree-walk kernel's softmax reference: finite, so that (-inf) - m stays -inf,
+// and so far below any score that the first visible score replaces it.
+constexpr float kWalkMInit = -1.0e30f;
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -875,7 +878,8 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const in
                                                 float (&m)[NT], f32x4 (&lacc)[NT],
                                                 const f32x4 (&sa)[NT], const f32x4 (&sb)[NT],
                                                 const f16x8 (&vh)[D / 16], bool tok_masked,
-                                                int valid_l, int pos_l, float c, int lo, int hi) {
+                                                int valid_l, int pos_l, float c, float slack, int lo,
+                                                int hi) {
   const int lane = threadIdx.x & 63, m16 = lane & 15, jj = lane >> 4;
   const _Float16 one = static_cast<_Float16>(1.0f);
   const f16x8 ones = {one, one, one, one, one, one, one, one};
@@ -919,25 +923,29 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const in
     }
     const float mx8 = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    const float mx = row_group_max(fmaxf(mx8, m[nt]));
-    const float m_new = mx;  // includes the running maximum
-    const float m_safe = m_new == kNegInf ? 0.f : m_new;
-    float alpha, pr[8];
-    if (FP8) {
-      alpha = fast_exp2(m[nt] - m_safe);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m_safe);
-    } else {
-      const float mc = m_safe * c;
-      alpha = fast_exp2(__builtin_fmaf(m[nt], c, -mc));
-#pragma unroll
-      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, -mc));
-    }
-    m[nt] = m_new;
-    if (!__all(alpha == 1.0f)) {
+    // Lazy reference: m is the value the row's weights are taken relative to, not its exact
+    // running maximum.  It moves (and o and l are rescaled) only when a score of the row exceeds it
+    // by more than `slack` (2^8 in weight); until then weights are at most 2^8, which fp16 and
+    // the fp32 sums hold.  The decision is taken per row from the row's own scores, so a row's
+    // result does not depend on its neighbours in the tile; most blocks skip the cross-lane
+    // maximum and the rescaling altogether.  m starts at kWalkMInit (finite, far below any score).
+    if (__any(mx8 > m[nt] + slack)) {
+      const float rmax = row_group_max(mx8);
+      const float m_new = rmax > m[nt] + slack ? rmax : m[nt];
+      const float alpha = fast_exp2(FP8 ? m[nt] - m_new : (m[nt] - m_new) * c);
+      m[nt] = m_new;
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] *= alpha;
       lacc[nt] *= alpha;
+    }
+    float pr[8];
+    if (FP8) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m[nt]);
+    } else {
+      const float mc = m[nt] * c;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, -mc));
     }
     u32x4 pw;
 #pragma unroll
@@ -1049,6 +1057,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   const int k_lane_off = jj * 128 + (m16 & 7) * 16;
   const int v_lane_off = (jj & 1) * 256 + m16 * 16;
 
+  // how far a score may exceed a row's softmax reference before the reference moves (log2 units: 8)
+  const float slack = FP8 ? 8.f : 8.f / p.scale_log2;
   // ---- rows of this wavefront
   bf16x8 qf[NTW][D / 32];
   int limit[NTW], qtok[NTW], qidx[NTW];
@@ -1062,7 +1072,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     qtok[nt] = 0;
     qidx[nt] = 0;
     dmask[nt] = 0;
-    m[nt] = kNegInf;
+    m[nt] = kWalkMInit;
     lacc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -1152,7 +1162,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
       walk_softmax_pv<FP8, TREE, D, NTW>(limit, qidx, dmask, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
-                                   c, lo, hi);
+                                   c, slack, lo, hi);
     };
     auto meta = [&](int b) {
       return load_walk_block<FP8>(p, blk_begin + (b < n_shared ? b : n_shared - 1), g, sh.Hkv, rec_in_lds,
@@ -1248,7 +1258,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       if (more) issue_v(nxt);
       walk_softmax_pv<FP8, TREE, D, NTW>(limit, qidx, dmask, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
-                                   c, lo, hi);
+                                   c, slack, lo, hi);
     };
     const int priv_last = priv_begin + n_priv - 1;
     auto rec_at = [&](int idx) {

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <limits>
 #include <numeric>
+#include <utility>
 
 namespace spex {
 namespace {
@@ -402,13 +403,16 @@ PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
 // the rows' softmax state in registers from the root to the requested nodes, so nothing is
 // written but the output.  Rules (they fix the result uniquely):
 //  * request i has q_len_i * G rows; C = 16 * NTW rows fit one wavefront.  NTW is the value asked
-//    for (1, 2 or 4) or, if 0, the smallest of {1, 2, 4} with max rows <= 16 * NTW, raised to 2 when
-//    that is 1, some root has more than 64 rows below it and sum over roots of ceil(rows / 128),
-//    times Hkv, is at least 512.  No lists (walk_ok = false) if some
-//    request has more rows than 16 * NTW.
+//    for (1, 2 or 4) or, if 0: 1 if no request has more than 16 rows (raised to 2 when some root
+//    has more than 64 rows below it and sum over roots of ceil(rows / 128), times Hkv, is at least
+//    512), 2 if none has more than 32, else 2 (4 if G > 32).  No lists (walk_ok = false) if
+//    G > 16 * NTW, i.e. if one query token does not fit a wavefront.
 //  * roots in order of first appearance in the request list; the requests of a root sorted by
 //    path (node ids root first, lexicographic, a proper prefix first), ties in request order;
 //    so the requests below any node are consecutive.
+//  * a request with more than cap = C / G query tokens is cut into ceil(q_len / cap) pieces of
+//    consecutive query tokens, the first (q_len mod pieces) of them one token longer than the
+//    others; "request" in the rules below means such a piece.
 //  * a row block has NW wavefronts: the value asked for (4 or 8), 4 if 0.
 //  * packing: a request joins the current wavefront if its rows still fit, else it starts the
 //    next one; wavefront NW, or a new root, starts a new row block.  walk_qt lists
@@ -481,21 +485,29 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   }
   int32_t ntw = walk_row_tiles;
   if (ntw == 0) {
-    if (max_rows > 64) return;
-    ntw = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
-    if (ntw == 1 && *std::max_element(root_rows.begin(), root_rows.end()) > 64) {
-      // Two tiles per wavefront halve the number of row blocks that walk a wide root's shared
-      // pages -- worth it only if the launch still has at least two workgroups per compute unit
-      // (512); below that, more and shorter workgroups balance better.
-      int64_t wide_items = 0;
-      for (int64_t r : root_rows) wide_items += (r + 127) / 128;
-      if (wide_items * num_kv_heads >= 512) ntw = 2;
+    if (G > 64) return;
+    if (max_rows <= 16) {
+      ntw = 1;
+      if (*std::max_element(root_rows.begin(), root_rows.end()) > 64) {
+        // Two tiles per wavefront halve the number of row blocks that walk a wide root's shared
+        // pages -- worth it only if the launch still has at least two workgroups per compute unit
+        // (512); below that, more and shorter workgroups balance better.
+        int64_t wide_items = 0;
+        for (int64_t r : root_rows) wide_items += (r + 127) / 128;
+        if (wide_items * num_kv_heads >= 512) ntw = 2;
+      }
+    } else if (max_rows <= 32) {
+      ntw = 2;
+    } else {
+      // Wider requests are cut into pieces (below).  Four tiles per wavefront leave one wavefront
+      // per SIMD and were the slowest choice measured, so they are taken only when one query
+      // token alone needs them.
+      ntw = G > 32 ? 4 : 2;
     }
-  } else if (max_rows > 16 * ntw) {
+  } else if (G > 16 * ntw) {
     return;
   }
   pl.walk_row_tiles = ntw;
-  pl.req_walk_blk.assign(n_leaves, -1);
   pl.req_walk_qt.assign(n_leaves, -1);
   const int32_t C = 16 * ntw;
   // Measured on MI355X, two workgroups of 4 wavefronts per compute unit beat one of 8 on every
@@ -516,14 +528,32 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     return la < lb;
   });
 
+  // A request with more query tokens than a wavefront holds is cut into pieces of consecutive
+  // query tokens of (almost) equal size; the packing below places pieces.
+  struct Piece { int32_t req, j0, n; };
+  std::vector<Piece> pieces;
+  pieces.reserve(n_leaves);
+  {
+    const int32_t cap = C / G;
+    for (int32_t idx : order) {
+      const int32_t ql = q_lens ? q_lens[idx] : 1;
+      const int32_t n_p = (ql + cap - 1) / cap, base = ql / n_p, rem = ql % n_p;
+      for (int32_t k = 0, j0 = 0; k < n_p; ++k) {
+        const int32_t n = base + (k < rem ? 1 : 0);
+        pieces.push_back({idx, j0, n});
+        j0 += n;
+      }
+    }
+  }
+
   // Nodes that lie on paths of more than one row block (same packing as below, counted first).
   if (static_cast<int32_t>(multi_.size()) < N) multi_.resize(N, 0);
   const int32_t st_multi = fresh();
   {
     const int32_t st_seen = fresh();
     int32_t wave = 0, used = 0, cur_root = -1, rb = -1;
-    for (int32_t idx : order) {
-      const int32_t rows = rows_of(idx);
+    for (const Piece &pc : pieces) {
+      const int32_t idx = pc.req, rows = pc.n * G;
       if (root_of[idx] != cur_root) {
         cur_root = root_of[idx];
         ++rb;
@@ -549,7 +579,8 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     }
   }
 
-  struct Placed { int32_t req, row0; };
+  struct Placed { int32_t req, row0, rows; };
+  std::vector<std::pair<int32_t, int32_t>> last_blks;  // (request, block with its node's last page)
   struct NodeRange { int32_t node, lo, hi, minlim; };
   std::vector<Placed> cur;
   std::vector<NodeRange> nodes;
@@ -592,7 +623,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     const int32_t st = fresh();
     nodes.clear();
     for (const Placed &pc : cur) {
-      const int32_t i = pc.req, rows = rows_of(i), minlim = pl.req_minlim[i];
+      const int32_t i = pc.req, rows = pc.rows, minlim = pl.req_minlim[i];
       for (int32_t k = path_indptr[i]; k < path_indptr[i + 1]; ++k) {
         const int32_t u = path_nodes[k];
         if (pt.node(u).n_tokens == 0) continue;
@@ -611,7 +642,9 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     int64_t total = 0;
     auto note_last = [&](const NodeRange &nr) {  // requests of this row block that asked for nr.node
       for (const Placed &pc : cur)
-        if (pl.req_leaves[pc.req] == nr.node) pl.req_walk_blk[pc.req] = last_blk_of_node;
+        if (pl.req_leaves[pc.req] == nr.node &&
+            (last_blks.empty() || last_blks.back() != std::make_pair(pc.req, last_blk_of_node)))
+          last_blks.emplace_back(pc.req, last_blk_of_node);
     };
     for (const NodeRange &nr : nodes)
       if (nr.lo / C != (nr.hi - 1) / C) {
@@ -637,8 +670,8 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   };
 
   int32_t wave = 0, used = 0, cur_root = -1;
-  for (int32_t idx : order) {
-    const int32_t rows = rows_of(idx), ql = q_lens ? q_lens[idx] : 1;
+  for (const Piece &piece : pieces) {
+    const int32_t idx = piece.req, rows = piece.n * G;
     if (root_of[idx] != cur_root) {
       if (cur_root >= 0) flush(cur_root);
       cur_root = root_of[idx];
@@ -654,16 +687,26 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
       }
     }
     if (rb_rec[3 + 2 * NW + wave] == 0) rb_rec[3 + NW + wave] = static_cast<int32_t>(pl.walk_qt.size() / 2);
-    pl.req_walk_qt[idx] = static_cast<int32_t>(pl.walk_qt.size() / 2);
-    for (int32_t j = 0; j < ql; ++j) {
+    // the pieces of a request follow each other, so its entries in walk_qt are consecutive
+    if (piece.j0 == 0) pl.req_walk_qt[idx] = static_cast<int32_t>(pl.walk_qt.size() / 2);
+    for (int32_t j = piece.j0; j < piece.j0 + piece.n; ++j) {
       pl.walk_qt.push_back(qoff[idx] + j);
       pl.walk_qt.push_back(pl.qt_limit[qoff[idx] + j]);
     }
-    rb_rec[3 + 2 * NW + wave] += ql;
-    cur.push_back({idx, wave * C + used});
+    rb_rec[3 + 2 * NW + wave] += piece.n;
+    cur.push_back({idx, wave * C + used, rows});
     used += rows;
   }
   flush(cur_root);
+  // blocks to patch when a requested node grows: one per row block that holds a piece of the request
+  pl.req_walk_blk_indptr.assign(n_leaves + 1, 0);
+  for (const auto &rb : last_blks) ++pl.req_walk_blk_indptr[rb.first + 1];
+  for (int32_t i = 0; i < n_leaves; ++i) pl.req_walk_blk_indptr[i + 1] += pl.req_walk_blk_indptr[i];
+  pl.req_walk_blk.assign(last_blks.size(), -1);
+  {
+    std::vector<int32_t> fill(pl.req_walk_blk_indptr.begin(), pl.req_walk_blk_indptr.end() - 1);
+    for (const auto &rb : last_blks) pl.req_walk_blk[fill[rb.first]++] = rb.second;
+  }
 
   // ---- launch order
   const int32_t n_roots = static_cast<int32_t>(root_ids.size());
@@ -763,12 +806,14 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
         }
     }
     if (walk) {
-      const int32_t blk = pl.req_walk_blk[i];
-      if (blk < 0) return false;
-      int32_t *rec = &pl.walk_blocks[static_cast<size_t>(blk) * Plan::kBlockInts];
-      const int slot = rec[3] != 0 ? 3 : 1;  // the last page is page b if the block has one
-      rec[slot] = (rec[slot] & ~127) | new_valid;
-      patch(kPatchWalkBlocks, static_cast<int64_t>(blk) * Plan::kBlockInts + slot, rec[slot]);
+      if (pl.req_walk_blk_indptr[i] == pl.req_walk_blk_indptr[i + 1]) return false;
+      for (int32_t e = pl.req_walk_blk_indptr[i]; e < pl.req_walk_blk_indptr[i + 1]; ++e) {
+        const int32_t blk = pl.req_walk_blk[e];
+        int32_t *rec = &pl.walk_blocks[static_cast<size_t>(blk) * Plan::kBlockInts];
+        const int slot = rec[3] != 0 ? 3 : 1;  // the last page is page b if the block has one
+        rec[slot] = (rec[slot] & ~127) | new_valid;
+        patch(kPatchWalkBlocks, static_cast<int64_t>(blk) * Plan::kBlockInts + slot, rec[slot]);
+      }
       for (int32_t j = 0; j < ql; ++j) {
         const int64_t at = 2 * static_cast<int64_t>(pl.req_walk_qt[i] + j) + 1;
         pl.walk_qt[at] = pl.qt_limit[q0 + j];

@@ -52,7 +52,7 @@ struct Plan {
   std::vector<int32_t> qt_mask;                  // {index of the query in its request, mask} per query token; empty without masks
   // ---- where an append to a requested node shows up (see Planner::patch_lengths)
   std::vector<int32_t> req_split_pg, req_in_group, req_qtpos_indptr, req_qtpos;
-  std::vector<int32_t> req_walk_blk, req_walk_qt;
+  std::vector<int32_t> req_walk_blk_indptr, req_walk_blk, req_walk_qt;
 
   // ---- canonical arrays (see spex_plan_view_t)
   std::vector<int32_t> leaf_indptr, leaf_pages, leaf_valid, qt_limit, group_node;

@@ -75,7 +75,7 @@ def test_full_config_5_with_draft_token_trees(drafts):
     """Config 5 with the drafts of every branch arranged as a token tree (Sec. 6.5: 4-16 drafts),
     through spex_tree_decode_attention_masked, on sampled branches."""
     import paper_2605_10195_amd as spex
-    wl = sw.tot_with_drafts(drafts=drafts, token_trees=True, **({} if drafts == 6 else {"heads": (32, 8, 128)}))
+    wl = sw.tot_with_drafts(drafts=drafts, token_trees=True)     # 16 drafts x G = 5: 80 rows, three pieces
     n_pages = wl.peak_pages()
     order = np.random.default_rng(1000).permutation(n_pages).tolist()
     tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,

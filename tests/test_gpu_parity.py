@@ -89,7 +89,9 @@ RANDOM_CASES = [
     dict(seed=46, heads=(8, 8, 64), kv_dtype="fp8_e4m3", max_q_len=2),
     dict(seed=47, heads=(4, 2, 64), kv_dtype="f32", max_q_len=3),
     dict(seed=48, heads=(6, 3, 40), kv_dtype="bf16", max_q_len=2),      # no MFMA kernel: generic
-    dict(seed=49, heads=(4, 1, 128), kv_dtype="bf16", max_q_len=9),     # 36 rows: two row tiles
+    dict(seed=49, heads=(4, 1, 128), kv_dtype="bf16", max_q_len=9),     # 36 rows: cut into pieces
+    dict(seed=50, heads=(16, 2, 64), kv_dtype="bf16", max_q_len=20),    # up to 160 rows per request
+    dict(seed=53, heads=(40, 2, 128), kv_dtype="fp8_e4m3", max_q_len=5),  # G = 20: two row tiles at least
 ]
 
 
@@ -105,9 +107,10 @@ def test_random_trees_match_oracle(case, chunks):
 
 
 def walk_applies(wl, row_tiles=0):
-    rows = max(wl.q_lens) * (wl.num_q_heads // wl.num_kv_heads)
+    # wider requests are cut into pieces of query tokens; one query token must fit a wavefront
+    G = wl.num_q_heads // wl.num_kv_heads
     mfma = wl.kv_dtype != "f32" and wl.head_dim in (64, 128)
-    return mfma and rows <= (16 * row_tiles if row_tiles else 64)
+    return mfma and G <= (16 * row_tiles if row_tiles else 64)
 
 
 @pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")

@@ -205,7 +205,7 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
     if masks is None:
         masks = [(2 << j) - 1 for ql in q_lens for j in range(ql)]
     if not got["available"]:
-        assert max(q * G for q in q_lens) > (16 * row_tiles if row_tiles else 64)
+        assert G > (16 * row_tiles if row_tiles else 64)            # one query token does not fit a wavefront
         return got
     C = 16 * got["row_tiles"]
     NW = got["waves"]
@@ -371,13 +371,35 @@ def test_draft_mask_errors():
     assert t.walk_dump([r, s], [2, 3], [0, 0, 1, 2, 5])["available"] == 1   # r's drafts still see its prefix
 
 
-def test_walk_lists_not_available_for_wide_requests():
+def test_wide_requests_are_cut_into_pieces_of_query_tokens():
     wl = sw.random_trace(77, n_ops=30, max_tokens=90, max_q_len=9, heads=(16, 2, 64))   # up to 72 rows
     tree, ref = host_tree(wl, wl.peak_pages()), PageTableRef(wl.peak_pages(), 16)
     replay_both(wl, tree, ref)
     assert max(wl.q_lens) * 8 > 64
-    got = tree.walk_dump(wl.leaves, wl.q_lens)
-    assert got["available"] == 0 and got["items"] == []
+    got = check_walk_lists(tree, ref, wl, 0)
+    assert got["available"] == 1 and got["row_tiles"] == 2       # 4 query tokens of 8 rows per wavefront
+    for rt in (1, 2, 4):
+        for nw in (4, 8):
+            assert check_walk_lists(tree, ref, wl, rt, nw)["available"] == 1
+    # 9 queries: three pieces of three; the pieces' entries follow each other in qt
+    qt = np.array(got["qt"]).reshape(-1, 2)[:, 0]
+    qoff = np.concatenate([[0], np.cumsum(wl.q_lens)])
+    for i, ql in enumerate(wl.q_lens):
+        at = int(np.flatnonzero(qt == qoff[i])[0])
+        assert qt[at:at + ql].tolist() == list(range(qoff[i], qoff[i] + ql))
+
+
+def test_walk_lists_not_available_when_one_query_token_is_wider_than_a_wavefront():
+    wl = sw.random_trace(78, n_ops=20, max_tokens=50, max_q_len=2, heads=(40, 1, 64))   # G = 40
+    tree, ref = host_tree(wl, wl.peak_pages()), PageTableRef(wl.peak_pages(), 16)
+    replay_both(wl, tree, ref)
+    for rt, avail in ((0, 1), (4, 1), (2, 0), (1, 0)):
+        got = check_walk_lists(tree, ref, wl, rt)
+        assert got["available"] == avail and (avail or got["items"] == [])
+    wl = sw.random_trace(79, n_ops=20, max_tokens=50, heads=(80, 1, 64))                # G = 80
+    tree, ref = host_tree(wl, wl.peak_pages()), PageTableRef(wl.peak_pages(), 16)
+    replay_both(wl, tree, ref)
+    assert check_walk_lists(tree, ref, wl, 0)["available"] == 0
 
 
 # ------------------------------------------------------------------ length patches
@@ -435,7 +457,8 @@ def grow_and_compare(wl, n_steps, seed):
     sw.bfs_tot(n_queries=2, prompt=40, step=19), sw.tot_with_drafts(n_queries=2, prompt=50, step=21),
     sw.mcts_skewed(n_queries=4, prompt=(30, 90), step=(5, 40), max_leaves=12),
     sw.random_trace(640, n_ops=60, max_tokens=40, max_q_len=3, heads=(8, 2, 64)),
-    sw.with_draft_trees(sw.random_trace(641, n_ops=14, max_tokens=40, max_q_len=5, heads=(8, 2, 64)))],
+    sw.with_draft_trees(sw.random_trace(641, n_ops=14, max_tokens=40, max_q_len=5, heads=(8, 2, 64))),
+    sw.random_trace(642, n_ops=16, max_tokens=40, max_q_len=9, heads=(16, 2, 64))],      # requests cut into pieces
     ids=lambda w: w.name)
 def test_length_patches_match_a_fresh_plan(wl):
     patched, fresh = grow_and_compare(wl, 24, 5)
