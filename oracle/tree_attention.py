@@ -26,9 +26,16 @@ Inputs are decoded to fp64 from the exact bits the GPU receives: bf16 and fp8
 definitions below; an fp8 value is code * scale with one scale per block of
 `scale_block` consecutive tokens of a node and per KV head, separately for K and V.
 
+A cache that is quantised while tokens are appended (append_quantised) encodes
+bf16 tokens with encode_e4m3 and the scale of the block they fall in; a block's
+scale is fixed by the append that starts it.
+
 Pins (tests/test_oracle_pins.py): brute-force loops, fp64 library attention on a
 materialised branch, closed forms, softmax weights summing to one, identical
-token paths, and the log-sum-exp merge identity over arbitrary partitions.
+token paths, and the log-sum-exp merge identity over arbitrary partitions; for the
+encoder: every code survives decode -> encode, midpoints go to the even code and
+their fp32 neighbours to the nearer value, saturation, torch's own fp32 -> e4m3fn
+cast on random values, exact rational arithmetic on a sample.
 """
 
 from __future__ import annotations
@@ -68,6 +75,25 @@ _E4M3 = e4m3_table()
 
 def decode_e4m3(codes: np.ndarray) -> np.ndarray:
     return _E4M3[np.ascontiguousarray(codes).astype(np.uint8)]
+
+
+def encode_e4m3(y: np.ndarray) -> np.ndarray:
+    """Values -> e4m3fn codes for a cache that is quantised when tokens are appended: the
+    representable value nearest to y, of two equally near ones the one with the even code (round
+    to nearest even), magnitudes above 448 saturate to +-448, NaN stays NaN (0x7F | sign).
+    Written as a search over the 127 finite non-negative values of the decode table, not as bit
+    arithmetic."""
+    y = np.asarray(y, dtype=np.float64)
+    grid = _E4M3[:0x7F]                                   # codes 0x00 .. 0x7E, ascending
+    a = np.minimum(np.abs(y), grid[-1])
+    a = np.where(np.isnan(a), 0.0, a)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 0, len(grid) - 1)    # first value >= a
+    lo = np.maximum(hi - 1, 0)
+    d_lo, d_hi = a - grid[lo], grid[hi] - a
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+    code = np.where(take_hi, hi, lo).astype(np.uint8)
+    code = np.where(np.isnan(y), np.uint8(0x7F), code)
+    return (code | np.where(np.signbit(y), np.uint8(0x80), np.uint8(0))).astype(np.uint8)
 
 
 # ----------------------------------------------------------------------------- the tree
@@ -133,6 +159,28 @@ class OracleTree:
         self.K[node].append(kd)
         self.V[node].append(vd)
         self.n_tokens[node] += n
+
+    def append_quantised(self, node: int, k_bits, v_bits, k_scales=None, v_scales=None) -> None:
+        """fp8 cache filled from bf16 tokens (uint16 bit patterns [n, Hkv, D]): token j is encoded
+        with the scale of the block of scale_block tokens it falls in -- the next row of k_scales /
+        v_scales ([blocks this append starts, Hkv]) for a block it starts, else the scale the block
+        already has; a block is never requantised.  code = encode_e4m3(x * (1 / scale)) with the
+        reciprocal and the product rounded to fp32, the precision in which the cache is written."""
+        assert self.kv_dtype == "fp8_e4m3"
+        self._check(node)
+        codes = []
+        for which, bits, new in ((0, k_bits, k_scales), (1, v_bits, v_scales)):
+            x = decode_bf16(np.asarray(bits)).astype(np.float32)
+            have = [r.astype(np.float32) for r in self._scales.get(node, ([], []))[which]]
+            if new is not None:
+                have += list(np.asarray(new, dtype=np.float32).reshape(-1, self.Hkv))
+            blk = (self.n_tokens[node] + np.arange(x.shape[0])) // self.scale_block
+            assert blk.max() < len(have), "a started block needs a scale"
+            sc = np.stack(have)[blk][:, :, None]                       # [n, Hkv, 1] fp32
+            inv = (np.float32(1.0) / sc).astype(np.float32)
+            codes.append(encode_e4m3((x * inv).astype(np.float32)))
+        self.append(node, codes[0], codes[1], k_scales, v_scales)
+        self.last_codes = codes                                        # for byte-level comparison
 
     def _dequant(self, node, x, new_scales, which):
         """Multiply codes by the scale of the block (of scale_block tokens of this node)

@@ -425,3 +425,78 @@ def test_chain_masks_equal_the_causal_default_and_hand_values():
     assert np.allclose(np.exp(s[:, 0]), [3.0, 6.0, 9.0], atol=1e-12)
     with pytest.raises(ValueError):
         th.attention([lh], [3], np.ones((3, 1, 1)), 1.0, draft_masks=[0b001, 0b011, 0b1101])
+
+
+# ------------------------------------------------------------------ e4m3 encoder / quantising append
+def test_e4m3_encoder_round_trips_ties_and_saturation():
+    from oracle.tree_attention import decode_e4m3, encode_e4m3
+    codes = np.array([c for c in range(256) if c & 0x7F != 0x7F], dtype=np.uint8)
+    vals = decode_e4m3(codes)
+    assert np.array_equal(encode_e4m3(vals), codes)                       # -0.0 -> 0x80 included
+    grid = decode_e4m3(np.arange(0x7F, dtype=np.uint8))
+    assert np.all(np.diff(grid) > 0) and grid[0] == 0 and grid[8] == 2.0 ** -6 and grid[-1] == 448
+    mid = (grid[:-1] + grid[1:]) / 2                                      # exact in fp64 and in fp32
+    assert np.array_equal(mid.astype(np.float32).astype(np.float64), mid)
+    want_even = np.where(np.arange(0x7E) % 2 == 0, np.arange(0x7E), np.arange(1, 0x7F))
+    assert np.array_equal(encode_e4m3(mid), want_even)
+    assert np.array_equal(encode_e4m3(-mid), want_even | 0x80)
+    below = np.nextafter(mid.astype(np.float32), np.float32(0))
+    above = np.nextafter(mid.astype(np.float32), np.float32(1e9))
+    assert np.array_equal(encode_e4m3(below), np.arange(0x7E))
+    assert np.array_equal(encode_e4m3(above), np.arange(1, 0x7F))
+    big = np.array([448.0, 449.0, 464.0, 480.0, 1e6, np.inf, -500.0, -np.inf])
+    assert encode_e4m3(big).tolist() == [0x7E] * 6 + [0xFE] * 2
+    assert encode_e4m3(np.array([np.nan]))[0] & 0x7F == 0x7F
+    tiny = np.array([2.0 ** -10, 2.0 ** -10 * 1.0001, 2.0 ** -9 * 1.5, 1e-30, 0.0])
+    assert encode_e4m3(tiny).tolist() == [0, 1, 2, 0, 0]                  # 2^-10 ties to the even code 0
+
+
+def test_e4m3_encoder_matches_torch_cast_and_exact_rationals():
+    from fractions import Fraction
+    from oracle.tree_attention import decode_e4m3, encode_e4m3
+    rng = np.random.default_rng(31)
+    y = np.concatenate([rng.normal(size=20000) * s for s in (1e-3, 0.05, 1.0, 30.0, 150.0)]).astype(np.float32)
+    y = y[np.abs(y) <= 448]
+    want = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(encode_e4m3(y), want)
+    grid = [Fraction(float(g)) for g in decode_e4m3(np.arange(0x7F, dtype=np.uint8))]
+    for v in y[:400]:
+        a = abs(Fraction(float(v)))
+        best = min(range(0x7F), key=lambda c: (abs(grid[c] - a), c % 2))  # nearest, then the even code
+        assert encode_e4m3(np.array([v]))[0] == best | (0x80 if v < 0 else 0)
+
+
+def test_quantising_append_uses_the_scale_of_the_block_a_token_falls_in():
+    from oracle.tree_attention import OracleTree, decode_e4m3
+
+    def bf16_bits(x):
+        return (np.asarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+    t = OracleTree(2, 1, 4, "fp8_e4m3", scale_block=4)
+    (r,) = t.fork(-1, 1)
+    # block 0, scale 2^-3: values scale * grid point are encoded exactly; block never requantised
+    k0 = np.array([[[0.25, -0.5, 2.0 ** -3 * 448, 2.0 ** -3 * 2.0 ** -9]]])
+    t.append_quantised(r, bf16_bits(k0), bf16_bits(k0), np.array([[2.0 ** -3]]), np.array([[2.0 ** -3]]))
+    assert t.last_codes[0].ravel().tolist() == [0x40, 0xC8, 0x7E, 0x01]   # 2, -4, 448, 2^-9 in units of the scale
+    # second token of the same block: 100 > 448 * 2^-3 saturates, no new scale is taken
+    k1 = np.array([[[100.0, -100.0, 3.0, 0.0]]])
+    t.append_quantised(r, bf16_bits(k1), bf16_bits(k1))
+    assert t.last_codes[0].ravel().tolist() == [0x7E, 0xFE, 0x5C, 0x00]   # 3 / 2^-3 = 24 = 1.5 * 2^4: exponent field 11, mantissa 100
+    # tokens 2..4 of the path: the third starts block 1 and takes the scale passed with it
+    k2 = np.array([[[1.0, 1.0, 1.0, 1.0]]] * 3)
+    t.append_quantised(r, bf16_bits(k2), bf16_bits(k2), np.array([[2.0 ** -1]]), np.array([[1.0]]))
+    assert t.last_codes[0][:, 0, 0].tolist() == [0x50, 0x50, 0x40]        # 8, 8 | 2
+    assert t.last_codes[1][:, 0, 0].tolist() == [0x50, 0x50, 0x38]        # V scale of block 1 is 1
+    K, V = t.materialise(r)
+    assert np.array_equal(K[:, 0, 0], [0.25, 56.0, 1.0, 1.0, 1.0]) and V[4, 0, 0] == 1.0
+    # any scale: the stored value is within half a grid step of x (fp32 rounding of x / scale aside)
+    rng = np.random.default_rng(5)
+    t2 = OracleTree(2, 1, 64, "fp8_e4m3", scale_block=16)
+    (r2,) = t2.fork(-1, 1)
+    x = bf16_bits(rng.normal(size=(1, 1, 64)))
+    xv = (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    s = np.float32(np.abs(xv).max() / 448 * 1.37)
+    t2.append_quantised(r2, x, x, np.array([[s]]), np.array([[s]]))
+    got = decode_e4m3(t2.last_codes[0]) * float(s)
+    step = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(xv) / float(s), 2.0 ** -6))) - 3), 2.0 ** -9) * float(s)
+    assert np.all(np.abs(got - xv) <= step / 2 * (1 + 1e-6))
