@@ -107,28 +107,27 @@ def decode_loop(tree, wl, q, out, lse, iters, dev):
     n = len(nodes)
     kv_torch = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.uint8}[wl.kv_dtype]
     ks = vs = None
-    if wl.kv_dtype == "fp8_e4m3":
-        k = torch.randint(0, 120, (n, wl.num_kv_heads, wl.head_dim), dtype=torch.uint8, device=dev)
-        v = torch.randint(0, 120, (n, wl.num_kv_heads, wl.head_dim), dtype=torch.uint8, device=dev)
-        k, v = k.view(torch.float8_e4m3fn), v.view(torch.float8_e4m3fn)
+    gen = torch.Generator(device=dev).manual_seed(7)
+    src = torch.bfloat16 if wl.kv_dtype == "fp8_e4m3" else kv_torch
+    k = (0.5 * torch.randn((n, wl.num_kv_heads, wl.head_dim), generator=gen, device=dev)).to(src)
+    v = (0.5 * torch.randn((n, wl.num_kv_heads, wl.head_dim), generator=gen, device=dev)).to(src)
+    quantize = wl.kv_dtype == "fp8_e4m3"        # bf16 tokens in, encoded by the append kernel
+    if quantize:
         ks = torch.full((n, wl.num_kv_heads), 2.0 ** -7, dtype=torch.float32, device=dev)
         vs = ks.clone()
-    else:
-        gen = torch.Generator(device=dev).manual_seed(7)
-        k = (0.5 * torch.randn((n, wl.num_kv_heads, wl.head_dim), generator=gen, device=dev)).to(kv_torch)
-        v = (0.5 * torch.randn((n, wl.num_kv_heads, wl.head_dim), generator=gen, device=dev)).to(kv_torch)
     counts = {0: 0, 1: 0, 2: 0}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(iters):
-        tree.append_tokens(nodes, k, v, ks, vs)
+        tree.append_tokens(nodes, k, v, ks, vs, quantize=quantize)
         tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse, draft_masks=wl.draft_masks)
         counts[tree.last_launch_info()["plan_rebuilt"]] += 1
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / iters
     return dict(iterations=iters, ms_per_iteration=dt * 1e3, query_tokens_per_s=q.shape[0] / dt,
                 plans_patched=counts[2], plans_redone=counts[1],
-                note="append_tokens + decode_attention per iteration, one tree, KV of earlier "
+                note="append_tokens (fp8 pools: append_tokens_quantize, bf16 tokens encoded by the "
+                     "append kernel) + decode_attention per iteration, one tree, KV of earlier "
                      "iterations may sit in the last-level cache")
 
 

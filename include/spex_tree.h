@@ -152,6 +152,20 @@ spex_status_t spex_tree_append_step(spex_tree_t *tree, spex_node_t node, int32_t
 spex_status_t spex_tree_append_tokens(spex_tree_t *tree, const spex_node_t *nodes, int32_t n_nodes,
                                       const void *k, const void *v, const float *k_scales,
                                       const float *v_scales, void *hip_stream);
+/*
+ * The same step with the cache quantised on the fly (fp8 pools only, else SPEX_ERR_UNSUPPORTED):
+ * k, v are DEVICE [n_nodes][num_kv_heads][head_dim] in bf16, as the model produces them, and the
+ * kernel that scatters them also encodes them: code = e4m3fn(x * (1 / scale)), product and
+ * reciprocal in fp32, round to nearest even, saturating at +-448, NaN kept.  scale is row i of
+ * k_scales / v_scales if node i's token starts a page (the row becomes that page's scale) and the
+ * scale the page already has otherwise -- a page is never requantised, later tokens saturate.
+ * Everything else (argument checks, all or nothing, page order, structure version) as
+ * spex_tree_append_tokens.
+ */
+spex_status_t spex_tree_append_tokens_quantize(spex_tree_t *tree, const spex_node_t *nodes,
+                                               int32_t n_nodes, const void *k, const void *v,
+                                               const float *k_scales, const float *v_scales,
+                                               void *hip_stream);
 /* Number of pages an append of n_tokens to node would newly start. */
 spex_status_t spex_tree_append_new_pages(const spex_tree_t *tree, spex_node_t node,
                                          int32_t n_tokens, int32_t *n_new_pages);

@@ -81,7 +81,7 @@ EXPORTS = [
     "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_decode_attention_masked", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
-    "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens",
+    "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens", "spex_tree_append_tokens_quantize",
 ]
 
 
@@ -103,6 +103,7 @@ def _load():
     lib.spex_tree_append_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_append_new_pages.argtypes = [vp, i32, i32, _I32P]
     lib.spex_tree_append_tokens.argtypes = [vp, _I32P, i32, vp, vp, vp, vp, vp]
+    lib.spex_tree_append_tokens_quantize.argtypes = [vp, _I32P, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_prune.argtypes = [vp, i32]
     lib.spex_tree_decode_attention.argtypes = [vp, _I32P, _I32P, i32, vp, vp, vp, f32, vp]
     lib.spex_tree_decode_attention_masked.argtypes = [vp, _I32P, _I32P, _U32P, i32, vp, vp, vp, f32, vp]
@@ -249,13 +250,16 @@ class SpexTree:
         self.append_step(node, k, v, k_scales, v_scales, n_tokens)
 
     def append_tokens(self, nodes: Sequence[int], k: Optional[torch.Tensor], v: Optional[torch.Tensor],
-                      k_scales: Optional[torch.Tensor] = None, v_scales: Optional[torch.Tensor] = None):
-        """One token per node, one launch.  k, v: [len(nodes), Hkv, D] on the tree's device."""
+                      k_scales: Optional[torch.Tensor] = None, v_scales: Optional[torch.Tensor] = None,
+                      quantize: bool = False):
+        """One token per node, one launch.  k, v: [len(nodes), Hkv, D] on the tree's device, in the
+        pool's dtype, or -- quantize=True, fp8 pools -- in bf16, encoded by the library."""
         na = _i32(nodes)
         if k is not None:
             assert k.is_contiguous() and v.is_contiguous() and k.shape == (len(na), self.Hkv, self.D)
-        _check(lib.spex_tree_append_tokens(self._h, _ptr(na), len(na), _dev(k), _dev(v), _dev(k_scales),
-                                           _dev(v_scales), _stream()))
+            assert not quantize or (k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16)
+        fn = lib.spex_tree_append_tokens_quantize if quantize else lib.spex_tree_append_tokens
+        _check(fn(self._h, _ptr(na), len(na), _dev(k), _dev(v), _dev(k_scales), _dev(v_scales), _stream()))
 
     def prune(self, node: int) -> None:
         _check(lib.spex_tree_prune(self._h, node))
@@ -432,3 +436,7 @@ def spex_tree_decode_attention(tree: SpexTree, leaves, q_lens, q, sm_scale, out=
 def spex_tree_decode_attention_masked(tree: SpexTree, leaves, q_lens, draft_masks, q, sm_scale, out=None,
                                       lse=None):
     return tree.decode_attention(leaves, q_lens, q, sm_scale, out, lse, draft_masks=draft_masks)
+
+
+def spex_tree_append_tokens_quantize(tree: SpexTree, nodes, k, v, k_scales, v_scales) -> None:
+    tree.append_tokens(nodes, k, v, k_scales, v_scales, quantize=True)

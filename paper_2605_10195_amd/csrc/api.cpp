@@ -458,11 +458,12 @@ spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_
   return SPEX_OK;
 }
 
-spex_status_t spex_tree_append_tokens(spex_tree_t *t, const spex_node_t *nodes, int32_t n_nodes,
-                                      const void *k, const void *v, const float *k_scales,
-                                      const float *v_scales, void *hip_stream) {
+static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes, int32_t n_nodes,
+                                        const void *k, const void *v, const float *k_scales,
+                                        const float *v_scales, void *hip_stream, bool quantise) {
   if (!t || n_nodes < 0 || (n_nodes > 0 && !nodes) || ((k == nullptr) != (v == nullptr)))
     return SPEX_ERR_INVALID_ARG;
+  if (quantise && t->cfg.kv_dtype != SPEX_FP8_E4M3) return SPEX_ERR_UNSUPPORTED;
   if (k && !t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
   if (n_nodes == 0) return SPEX_OK;
   // Check everything before touching the table: the call is all or nothing.
@@ -523,8 +524,21 @@ spex_status_t spex_tree_append_tokens(spex_tree_t *t, const spex_node_t *nodes, 
   a.v_scale_src = v_scales;
   a.dst = static_cast<const int32_t *>(t->d_patch);
   a.n_nodes = n_nodes;
+  a.quantise = quantise;
   HIP_TRY(spex::launch_append_tokens(t->shape, a, stream));
   return SPEX_OK;
+}
+
+spex_status_t spex_tree_append_tokens(spex_tree_t *t, const spex_node_t *nodes, int32_t n_nodes,
+                                      const void *k, const void *v, const float *k_scales,
+                                      const float *v_scales, void *hip_stream) {
+  return append_tokens_impl(t, nodes, n_nodes, k, v, k_scales, v_scales, hip_stream, false);
+}
+
+spex_status_t spex_tree_append_tokens_quantize(spex_tree_t *t, const spex_node_t *nodes, int32_t n_nodes,
+                                               const void *k, const void *v, const float *k_scales,
+                                               const float *v_scales, void *hip_stream) {
+  return append_tokens_impl(t, nodes, n_nodes, k, v, k_scales, v_scales, hip_stream, true);
 }
 
 spex_status_t spex_tree_prune(spex_tree_t *t, spex_node_t node) {

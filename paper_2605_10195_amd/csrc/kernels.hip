@@ -1480,10 +1480,34 @@ __global__ __launch_bounds__(256) void spex_scatter_kv_kernel(ScatterArgs a, Sha
   }
 }
 
+// fp32 -> OCP e4m3fn code, round to nearest even, saturating at +-448 (0x7E / 0xFE); NaN -> 0x7F
+// with the sign.  Integer arithmetic on the bit pattern, so the result does not depend on
+// floating-point compile flags.  Normal range (|y| >= 2^-6): the fp32 mantissa is rounded to 3
+// bits with the usual add-half-and-LSB trick, a carry moves into the exponent by itself.  Below
+// that the grid is the multiples of 2^-9, and 8 * 2^-9 is the smallest normal (code 0x08).
+__device__ __forceinline__ uint32_t encode_e4m3(float y) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, y);
+  const uint32_t sign = (u >> 24) & 0x80u, a = u & 0x7fffffffu;
+  uint32_t code;
+  if (a > 0x7f800000u) {
+    code = 0x7fu;
+  } else if (a >= 0x43e00000u) {  // 448.0f and above (infinity included)
+    code = 0x7eu;
+  } else if (a >= 0x3c800000u) {  // 2^-6
+    const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);
+    code = (((r >> 23) - 120u) << 3) | ((r >> 20) & 7u);
+  } else {
+    code = static_cast<uint32_t>(__builtin_rintf(__builtin_bit_cast(float, a) * 512.0f));
+  }
+  return code | sign;
+}
+
 // One appended token per node: thread = (node, kv head, dim).  Writes the token's K and V element
 // into its slot; where the token starts a page it also zeroes the page's other slots (so that
-// nothing stale can be read from a partial page) and stores the page's fp8 scales.
-template <int KV, int LAYOUT>
+// nothing stale can be read from a partial page) and stores the page's fp8 scales.  QUANT (fp8
+// pools): the source holds bf16 values and the code is encode_e4m3(x * (1 / scale)), scale being
+// the one given for a page the token starts, else the one the page already has.
+template <int KV, int LAYOUT, bool QUANT>
 __global__ __launch_bounds__(256) void spex_append_tokens_kernel(AppendTokensArgs a, Shape sh) {
   typedef typename std::conditional<KV == kF32, float,
                                     typename std::conditional<KV == kBF16, uint16_t, uint8_t>::type>::type T;
@@ -1499,8 +1523,20 @@ __global__ __launch_bounds__(256) void spex_append_tokens_kernel(AppendTokensArg
   const bool is_new = (code >> 8) != 0;
   const int64_t tile = (static_cast<int64_t>(page) * sh.page_tiles + g) * (static_cast<int64_t>(P) * D);
   T *kp = static_cast<T *>(a.k_pool) + tile, *vp = static_cast<T *>(a.v_pool) + tile;
-  kp[k_offset<KV, LAYOUT>(slot, d, D)] = static_cast<const T *>(a.k_src)[tid];
-  vp[v_offset<KV, LAYOUT>(slot, d, D)] = static_cast<const T *>(a.v_src)[tid];
+  T kx, vx;
+  if (QUANT) {
+    const float ks = is_new ? a.k_scale_src[node * H + g] : a.k_scale[page * H + g];
+    const float vs = is_new ? a.v_scale_src[node * H + g] : a.v_scale[page * H + g];
+    const float kf = __builtin_bit_cast(float, static_cast<uint32_t>(static_cast<const uint16_t *>(a.k_src)[tid]) << 16);
+    const float vf = __builtin_bit_cast(float, static_cast<uint32_t>(static_cast<const uint16_t *>(a.v_src)[tid]) << 16);
+    kx = static_cast<T>(encode_e4m3(kf * (1.0f / ks)));
+    vx = static_cast<T>(encode_e4m3(vf * (1.0f / vs)));
+  } else {
+    kx = static_cast<const T *>(a.k_src)[tid];
+    vx = static_cast<const T *>(a.v_src)[tid];
+  }
+  kp[k_offset<KV, LAYOUT>(slot, d, D)] = kx;
+  vp[v_offset<KV, LAYOUT>(slot, d, D)] = vx;
   if (is_new) {
     for (int s2 = 0; s2 < P; ++s2)
       if (s2 != slot) {
@@ -1712,23 +1748,25 @@ hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t strea
   return hipErrorInvalidValue;
 }
 
-template <int KV>
+template <int KV, bool QUANT>
 static hipError_t append_tokens_layout(const Shape &sh, const AppendTokensArgs &a, hipStream_t stream) {
   const int64_t total = static_cast<int64_t>(a.n_nodes) * sh.Hkv * sh.D;
   const dim3 grid(static_cast<unsigned>((total + 255) / 256)), block(256);
   if (sh.layout == kMfmaTiled)
-    hipLaunchKernelGGL((spex_append_tokens_kernel<KV, kMfmaTiled>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_append_tokens_kernel<KV, kMfmaTiled, QUANT>), grid, block, 0, stream, a, sh);
   else
-    hipLaunchKernelGGL((spex_append_tokens_kernel<KV, kRowMajor>), grid, block, 0, stream, a, sh);
+    hipLaunchKernelGGL((spex_append_tokens_kernel<KV, kRowMajor, QUANT>), grid, block, 0, stream, a, sh);
   return hipGetLastError();
 }
 
 hipError_t launch_append_tokens(const Shape &sh, const AppendTokensArgs &a, hipStream_t stream) {
   if (a.n_nodes <= 0) return hipSuccess;
+  if (a.quantise)
+    return sh.kv_dtype == kFP8 ? append_tokens_layout<kFP8, true>(sh, a, stream) : hipErrorInvalidValue;
   switch (sh.kv_dtype) {
-    case kF32: return append_tokens_layout<kF32>(sh, a, stream);
-    case kBF16: return append_tokens_layout<kBF16>(sh, a, stream);
-    case kFP8: return append_tokens_layout<kFP8>(sh, a, stream);
+    case kF32: return append_tokens_layout<kF32, false>(sh, a, stream);
+    case kBF16: return append_tokens_layout<kBF16, false>(sh, a, stream);
+    case kFP8: return append_tokens_layout<kFP8, false>(sh, a, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -89,6 +89,9 @@ struct AppendTokensArgs {
   const float *k_scale_src, *v_scale_src;  // [n_nodes][Hkv] (fp8; read only for nodes that start a page)
   const int32_t *dst;                      // 2 ints per node: {page id, slot | (page is new) << 8}
   int32_t n_nodes;
+  // fp8 pools only: k_src / v_src hold bf16 values, which the kernel encodes with the scale of the
+  // page the token lands in (k_scale_src / v_scale_src for a page it starts)
+  bool quantise;
 };
 
 struct GatherArgs {

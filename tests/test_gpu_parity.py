@@ -550,3 +550,83 @@ def test_decode_loop_with_draft_masks_patches_lengths():
         assert_close(got, ref, "bf16", f"masked decode step {step}")
     assert states == {1, 2}
     tree.close()
+
+
+# ------------------------------------------------------------------ cache quantised on append
+@pytest.mark.parametrize("heads", [(10, 2, 128), (8, 8, 64), (4, 2, 96)])
+def test_quantising_append_gives_the_oracle_codes_and_attention(heads):
+    """spex_tree_append_tokens_quantize: bf16 tokens in, e4m3 codes in the pool.  The codes read
+    back are the oracle's byte for byte (also where values saturate), then attention matches."""
+    from oracle.adapters import OracleSink, queries_fp64
+    wl = sw.random_trace(91, heads=heads, kv_dtype="fp8_e4m3", n_ops=40, max_tokens=50, max_q_len=2)
+    _, _, alive = wl.node_tokens()
+    leaves = sorted(set(u for u in wl.leaves))
+    tree = build_gpu_tree(wl, extra_pages=4 * len(leaves) + 8)
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    grow = [u for u in leaves if tree.node_info(u)["n_live_children"] == 0]
+    H, D = wl.num_kv_heads, wl.head_dim
+    rng = np.random.default_rng(3)
+    start = {u: tree.node_info(u)["n_tokens"] for u in grow}
+    want_k = {u: [] for u in grow}
+    want_v = {u: [] for u in grow}
+    for step in range(37):                                     # crosses two page boundaries per node
+        boost = 40.0 if step % 5 == 4 else 1.0                 # every fifth token overflows its page's scale
+        k = (sw.normal_values(8, 1, 300 + step, torch.arange(len(grow)), H, D, 0.5, "cuda") * boost).to(torch.bfloat16)
+        v = (sw.normal_values(8, 2, 300 + step, torch.arange(len(grow)), H, D, 0.5, "cuda") * boost).to(torch.bfloat16)
+        if step == 7:
+            k[0, 0, :4] = torch.tensor([0.0, -0.0, 3e-9, -3e-9], dtype=torch.bfloat16)
+        ks = torch.from_numpy(rng.uniform(0.004, 0.02, size=(len(grow), H)).astype(np.float32)).cuda()
+        vs = torch.from_numpy(rng.uniform(0.004, 0.02, size=(len(grow), H)).astype(np.float32)).cuda()
+        new_page = [tree.node_info(u)["n_tokens"] % 16 == 0 for u in grow]
+        tree.append_tokens(grow, k, v, ks, vs, quantize=True)
+        for i, u in enumerate(grow):
+            sink.append_quantised(u, k[i:i + 1], v[i:i + 1], ks[i:i + 1] if new_page[i] else None,
+                                  vs[i:i + 1] if new_page[i] else None)
+            want_k[u].append(sink.tree.last_codes[0])
+            want_v[u].append(sink.tree.last_codes[1])
+    saturated = 0
+    for u in grow:
+        kc, vc, _, _ = tree.gather_kv(u, start[u], 37)
+        wk, wv = np.concatenate(want_k[u]), np.concatenate(want_v[u])
+        assert np.array_equal(kc.cpu().view(torch.uint8).numpy(), wk), u
+        assert np.array_equal(vc.cpu().view(torch.uint8).numpy(), wv), u
+        saturated += int(((wk & 0x7F) == 0x7E).sum())
+    assert saturated > 100
+    q = sw.gen_queries(wl, device="cuda")
+    out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+    ref = sink.tree.attention(wl.leaves, wl.q_lens, queries_fp64(q), wl.sm_scale)
+    got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+    # values up to 448 * 0.02 in V: the absolute bound scales with the value range (x 4)
+    assert np.max(np.abs(got[0] - ref[0])) <= 8e-3 and np.max(np.abs(got[1] - ref[1])) <= 2e-3
+    assert np.linalg.norm(got[0] - ref[0]) / np.linalg.norm(ref[0]) <= 1e-3
+    tree.close()
+
+
+def test_quantising_append_special_values_and_errors():
+    import paper_2605_10195_amd as spex
+    from oracle.tree_attention import decode_e4m3, encode_e4m3
+    t = spex.SpexTree(8, 2, 64, 16, "bf16", "fp8_e4m3", num_pages=4, device="cuda")
+    (r,) = t.fork(-1, 1)
+    grid = decode_e4m3(np.arange(0x7F, dtype=np.uint8))
+    mids = ((grid[:-1] + grid[1:]) / 2)[:126]                  # two heads x 64 dims hold 128 values
+    vals = np.concatenate([mids[:62], [np.inf, -np.inf], mids[62:124], [1e30, -1e-30]]).astype(np.float32)
+    x = torch.from_numpy(vals).to(torch.bfloat16).reshape(1, 2, 64).cuda()      # mid-points of small codes are exact in bf16
+    one = torch.ones((1, 2), dtype=torch.float32, device="cuda")
+    t.append_tokens([r], x, x.neg().contiguous(), one, one, quantize=True)
+    kc, vc, ks, _ = t.gather_kv(r, 0, 1)
+    xf = x.float().cpu().numpy().ravel()
+    assert np.array_equal(kc.cpu().view(torch.uint8).numpy().ravel(), encode_e4m3(xf))
+    assert np.array_equal(vc.cpu().view(torch.uint8).numpy().ravel(), encode_e4m3(-xf))
+    assert torch.all(ks == 1)
+    nan = torch.full((1, 2, 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+    t.append_tokens([r], nan, nan, None, None, quantize=True)                    # continues the page: no scales needed
+    kc, _, _, _ = t.gather_kv(r, 1, 1)
+    assert np.all(kc.cpu().view(torch.uint8).numpy() & 0x7F == 0x7F)
+    t.close()
+    b = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=4, device="cuda")
+    (r,) = b.fork(-1, 1)
+    with pytest.raises(spex.SpexError) as e:
+        b.append_tokens([r], x, x, one, one, quantize=True)
+    assert e.value.name == "UNSUPPORTED" and b.node_info(r)["n_tokens"] == 0
+    b.close()

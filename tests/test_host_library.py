@@ -499,3 +499,15 @@ def test_append_tokens_matches_single_appends_and_is_all_or_nothing():
     assert e.value.name == "OOM_PAGES" and small.stats() == (4, 1, 2)
     small.append_tokens(kids[:2], None, None)
     assert small.stats() == (4, 3, 0)
+
+
+def test_quantising_append_is_for_fp8_pools_only():
+    t = spex.SpexTree(4, 2, 96, 16, "bf16", "fp8_e4m3", num_pages=4, host_only=True)
+    (r,) = t.fork(-1, 1)
+    t.append_tokens([r], None, None, quantize=True)            # page table only
+    assert t.node_info(r)["n_tokens"] == 1
+    b = spex.SpexTree(4, 2, 64, 16, "bf16", "bf16", num_pages=4, host_only=True)
+    (r,) = b.fork(-1, 1)
+    with pytest.raises(spex.SpexError) as e:
+        b.append_tokens([r], None, None, quantize=True)
+    assert e.value.name == "UNSUPPORTED" and b.node_info(r)["n_tokens"] == 0
