@@ -83,6 +83,17 @@ EXPORTS = [
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
     "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens", "spex_tree_append_tokens_quantize",
 ]
+# spex_sched.h: host-side scheduling primitives
+SCHED_EXPORTS = [
+    "spex_sched_rebase_widths", "spex_sched_ucb_select", "spex_sched_dfs_speculate",
+    "spex_sched_allocate_budget", "spex_sched_early_termination", "spex_tree_path_kv_bytes",
+]
+
+
+class SearchTreeView(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("parent", C.POINTER(C.c_int32)), ("visits", C.POINTER(C.c_int64)),
+                ("value_sum", C.POINTER(C.c_double)), ("state", C.POINTER(C.c_int32)),
+                ("spec_reward", C.POINTER(C.c_double)), ("c", C.c_double)]
 
 
 def _load():
@@ -118,7 +129,14 @@ def _load():
     lib.spex_tree_set_profiling.argtypes = [vp, i32]
     lib.spex_tree_read_profile.argtypes = [vp, C.POINTER(f32), i32, _I32P]
     lib.spex_tree_last_launch_info.argtypes = [vp, C.POINTER(i64)]
-    for name in EXPORTS:
+    _F64P = C.POINTER(C.c_double)
+    lib.spex_sched_rebase_widths.argtypes = [_F64P, i32, i32, C.c_double, _I32P]
+    lib.spex_sched_ucb_select.argtypes = [C.POINTER(SearchTreeView), _I32P]
+    lib.spex_sched_dfs_speculate.argtypes = [C.POINTER(SearchTreeView), i32, _I32P, _I32P]
+    lib.spex_sched_allocate_budget.argtypes = [_I32P, _F64P, _F64P, i32, C.c_double, C.c_double, i32, _I32P, _F64P]
+    lib.spex_sched_early_termination.argtypes = [_I32P, _F64P, i32, i32, C.c_double, _I32P, _I32P]
+    lib.spex_tree_path_kv_bytes.argtypes = [vp, i32, _F64P]
+    for name in EXPORTS + SCHED_EXPORTS:
         fn = getattr(lib, name)
         if name not in ("spex_status_string", "spex_last_device_error", "spex_tree_destroy"):
             fn.restype = C.c_int
@@ -440,3 +458,69 @@ def spex_tree_decode_attention_masked(tree: SpexTree, leaves, q_lens, draft_mask
 
 def spex_tree_append_tokens_quantize(tree: SpexTree, nodes, k, v, k_scales, v_scales) -> None:
     tree.append_tokens(nodes, k, v, k_scales, v_scales, quantize=True)
+
+
+# ---- spex_sched.h: argument marshalling only ------------------------------------------------
+def _f64(seq) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(seq, dtype=np.float64))
+
+
+def _dptr(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def spex_sched_rebase_widths(rewards, budget: int, temperature: float) -> List[int]:
+    r = _f64(rewards)
+    w = np.zeros(len(r), dtype=np.int32)
+    _check(lib.spex_sched_rebase_widths(_dptr(r), len(r), int(budget), float(temperature), _ptr(w)))
+    return w.tolist()
+
+
+class SearchTree:
+    """Arrays of a DFS / MCTS search tree in the layout spex_search_tree_t points to."""
+
+    def __init__(self, parent, visits, value_sum, state=None, spec_reward=None, c: float = 1.0):
+        n = len(parent)
+        self.parent = _i32(parent)
+        self.visits = np.ascontiguousarray(np.asarray(visits, dtype=np.int64))
+        self.value_sum = _f64(value_sum)
+        self.state = _i32(state if state is not None else [0] * n)
+        self.spec_reward = _f64(spec_reward if spec_reward is not None else [0.0] * n)
+        self.view = SearchTreeView(n, _ptr(self.parent), self.visits.ctypes.data_as(C.POINTER(C.c_int64)),
+                                   _dptr(self.value_sum), _ptr(self.state), _dptr(self.spec_reward), float(c))
+
+
+def spex_sched_ucb_select(tree: SearchTree) -> int:
+    out = C.c_int32()
+    _check(lib.spex_sched_ucb_select(C.byref(tree.view), C.byref(out)))
+    return out.value
+
+
+def spex_sched_dfs_speculate(tree: SearchTree, k: int) -> List[int]:
+    sel = np.zeros(max(k, 1), dtype=np.int32)
+    n = C.c_int32()
+    _check(lib.spex_sched_dfs_speculate(C.byref(tree.view), int(k), _ptr(sel), C.byref(n)))
+    return sel[:n.value].tolist()
+
+
+def spex_sched_allocate_budget(capacity, hit_rate, kv_bytes, param_bytes: float, tau: float, k_total: int):
+    c, p, s = _i32(capacity), _f64(hit_rate), _f64(kv_bytes)
+    k = np.zeros(len(c), dtype=np.int32)
+    scores = np.zeros(len(c), dtype=np.float64)
+    _check(lib.spex_sched_allocate_budget(_ptr(c), _dptr(p), _dptr(s), len(c), float(param_bytes), float(tau),
+                                          int(k_total), _ptr(k), _dptr(scores)))
+    return k.tolist(), scores.tolist()
+
+
+def spex_sched_early_termination(answer_id, weight, t: int, alpha: float):
+    a, w = _i32(answer_id), _f64(weight)
+    term, best = C.c_int32(), C.c_int32()
+    _check(lib.spex_sched_early_termination(_ptr(a), _dptr(w), len(a), int(t), float(alpha), C.byref(term),
+                                            C.byref(best)))
+    return bool(term.value), best.value
+
+
+def spex_tree_path_kv_bytes(tree: SpexTree, node: int) -> float:
+    out = C.c_double()
+    _check(lib.spex_tree_path_kv_bytes(tree._h, int(node), C.byref(out)))
+    return out.value

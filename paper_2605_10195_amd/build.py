@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libspex_tree.so")
-SOURCES = ["api.cpp", "page_table.cpp", "planner.cpp", "kernels.hip"]
+SOURCES = ["api.cpp", "page_table.cpp", "planner.cpp", "sched.cpp", "kernels.hip"]
 
 
 def hipcc() -> str:

@@ -1,5 +1,6 @@
 // C ABI of the tree decode-attention library: argument checking, the host page table and
 // planner, device workspace management and kernel launches.  See include/spex_tree.h.
+#include "../../include/spex_sched.h"
 #include "../../include/spex_tree.h"
 
 #include <hip/hip_runtime.h>
@@ -761,6 +762,21 @@ spex_status_t spex_tree_free_pages(const spex_tree_t *t, int32_t *pages, int32_t
   *n = static_cast<int32_t>(fl.size());
   if (static_cast<int64_t>(fl.size()) > cap) return SPEX_ERR_CAPACITY;
   if (!fl.empty()) std::memcpy(pages, fl.data(), fl.size() * sizeof(int32_t));
+  return SPEX_OK;
+}
+
+spex_status_t spex_tree_path_kv_bytes(const spex_tree_t *t, spex_node_t node, double *bytes) {
+  if (!t || !bytes) return SPEX_ERR_INVALID_ARG;
+  if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
+  int64_t tokens = 0, pages = 0;
+  for (int32_t u = node; u != spex::kNoNode; u = t->pt->node(u).parent) {
+    tokens += t->pt->node(u).n_tokens;
+    pages += static_cast<int64_t>(t->pt->node(u).pages.size());
+  }
+  double b = static_cast<double>(tokens) * 2.0 * t->cfg.num_kv_heads * t->cfg.head_dim *
+             static_cast<double>(elem_size(t->cfg.kv_dtype));
+  if (t->cfg.kv_dtype == SPEX_FP8_E4M3) b += static_cast<double>(pages) * 8.0 * t->cfg.num_kv_heads;
+  *bytes = b;
   return SPEX_OK;
 }
 

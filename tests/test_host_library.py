@@ -17,12 +17,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "spex_tree.h")).read()
-    declared = set(re.findall(r"\b(spex_[a-z_]+)\s*\(", header))
-    assert declared == set(binding.EXPORTS)
     lib = ctypes.CDLL(binding.LIB_PATH)
-    for name in declared:
-        assert hasattr(lib, name), name
+    for fname, exports in (("spex_tree.h", binding.EXPORTS), ("spex_sched.h", binding.SCHED_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)             # declarations, not prose
+        declared = set(re.findall(r"\b(spex_[a-z0-9_]+)\s*\(", header))
+        assert declared == set(exports), fname
+        for name in declared:
+            assert hasattr(lib, name), name
     assert binding.lib.spex_status_string(4) == b"page pool exhausted"
 
 
