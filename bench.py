@@ -40,7 +40,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bfs_tot",
-                    choices=["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts"])
+                    choices=["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts",
+                             "dynamic_rebase"],
+                    help="dynamic_rebase: a breadth-first search that grows while it is served (REBASE "
+                         "widths, speculative children, prunes, early termination decided by the "
+                         "spex_sched_* primitives); --steps then counts decode iterations")
     ap.add_argument("--copies", type=int, default=0, help="rotating tree copies (0 = automatic)")
     ap.add_argument("--placement", default="random", choices=["random", "ascending"])
     ap.add_argument("--kv-pools", default="interleaved", choices=["interleaved", "separate"])
@@ -131,6 +135,97 @@ def decode_loop(tree, wl, q, out, lse, iters, dev):
                      "iterations may sit in the last-level cache")
 
 
+def run_dynamic(args):
+    """Decode iterations of a search whose trees change under it.  One iteration = one token for
+    every generating branch (spex_tree_append_tokens) + decode attention over those branches;
+    between iterations the scheduling primitives fork, speculate, verify, prune and terminate."""
+    import numpy as np
+    import torch
+
+    import paper_2605_10195_amd as spex
+    from paper_2605_10195_amd import binding as B
+    from spex_workloads.dynamic import (DynamicConfig, DynamicShape, DynamicValues, LibrarySink,
+                                        RebaseSpexDriver)
+
+    class Sched:
+        rebase_widths = staticmethod(B.spex_sched_rebase_widths)
+        allocate_budget = staticmethod(B.spex_sched_allocate_budget)
+        early_termination = staticmethod(B.spex_sched_early_termination)
+
+    dev = "cuda:0"
+    cfg = DynamicConfig(n_queries=32, prompt=(512, 2048), budget=16, max_depth=6, step=(16, 160),
+                        k_total=128, seed=11)
+    shape = DynamicShape(32, 8, 128, 16, "bf16")
+    n_pages = 65536
+    order = np.random.default_rng(1000).permutation(n_pages).tolist()
+    tree = spex.SpexTree(32, 8, 128, 16, "bf16", "bf16", num_pages=n_pages, device=dev, free_order=order,
+                         interleave_kv=True, kernel_mode=args.kernel_mode)
+    b_tok = 2.0 * 8 * 128 * 2
+    acc = dict(kv_tokens=0, peak_pages=0)
+
+    class Sink(LibrarySink):
+        def attend(self, nodes, iteration):
+            super().attend(nodes, iteration)
+            acc["kv_tokens"] += self.tree.last_launch_info()["kv_tokens"]
+            acc["peak_pages"] = max(acc["peak_pages"], self.tree.stats()[1])
+
+    sink = Sink(tree, shape, DynamicValues(shape, cfg.seed, dev), B.spex_tree_path_kv_bytes)
+    driver = RebaseSpexDriver(cfg, sink, Sched)
+    driver.start()
+    for _ in range(args.warmup):
+        driver.step()
+    torch.cuda.synchronize()
+    base = dict(driver.stats)
+    states0, kv0 = dict(sink.plan_states), acc["kv_tokens"]
+    tree.set_profiling(True)
+    prof_ms, done = 0.0, 0
+    t0 = time.perf_counter()
+    while done < args.steps and driver.step():
+        done += 1
+        if done % 128 == 0:                      # the library keeps the last 256 calls
+            prof_ms += float(tree.read_profile().sum())
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof_ms += float(tree.read_profile().sum())
+    tokens = driver.stats["tokens"] - base["tokens"]
+    kv_bytes = (acc["kv_tokens"] - kv0) * b_tok
+    # how scattered the pages of a path are after all the forking and pruning
+    live = [u for u, nd in driver.nodes.items() if nd.alive and not nd.children][:64]
+    adjacent = total = 0
+    for u in live:
+        pages, _ = tree.path_pages(u)
+        adjacent += sum(1 for a, b in zip(pages, pages[1:]) if b == a + 1)
+        total += max(len(pages) - 1, 0)
+    gbps = kv_bytes / (prof_ms * 1e-3) / 1e9 if prof_ms > 0 else 0.0
+    result = {
+        "metric": "tree decode-attn query-tokens/s + achieved HBM GB/s (unique KV bytes), 1 GPU",
+        "value": tokens / wall, "unit": "query-tokens/s", "n_gpus": 1, "steps": done, "warmup": args.warmup,
+        "ms_per_step": wall / max(done, 1) * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "dynamic_rebase", "queries": cfg.n_queries, "heads": [32, 8, 128],
+                   "budget": cfg.budget, "max_depth": cfg.max_depth, "prompt": list(cfg.prompt),
+                   "step_tokens": list(cfg.step), "k_total": cfg.k_total, "pool_pages": n_pages,
+                   "note": "a step is one decode iteration: append one token to every generating "
+                           "branch, attention for those tokens, then the scheduling decisions"},
+        "search": {k: (driver.stats[k] if k == "max_generating" else driver.stats[k] - base.get(k, 0))
+                   for k in driver.stats},
+        "plans": {"cached": sink.plan_states[0] - states0[0], "fresh": sink.plan_states[1] - states0[1],
+                  "patched": sink.plan_states[2] - states0[2]},
+        "mean_branches_per_iteration": tokens / max(done, 1),
+        "peak_pages_in_use": acc["peak_pages"],
+        "adjacent_page_fraction_on_live_paths": adjacent / total if total else None,
+        "roofline": {"bound": "hbm", "kernel": "spex_tree_walk_kernel", "achieved": gbps, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "bytes_per_launch": kv_bytes / max(done, 1), "ms_per_launch": prof_ms / max(done, 1),
+                     "note": "kernel time from HIP events around every attention launch; bytes = "
+                             "unique KV bytes of each launch's requested paths, summed"},
+        "kernel_ms_share_of_wall": prof_ms / (wall * 1e3),
+        "cpu_baseline": None,
+    }
+    print(json.dumps(result, default=float))
+    tree.close()
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -147,6 +242,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.workload == "dynamic_rebase":
+        run_dynamic(args)
+        return
     if args.token_trees:
         assert args.workload == "tot_with_drafts" and 1 <= args.token_trees <= 32
         wl = sw.tot_with_drafts(drafts=args.token_trees, token_trees=True)

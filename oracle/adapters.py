@@ -56,3 +56,66 @@ class OracleSink:
         ks = None if k_scales is None else raw_array(k_scales)
         vs = None if v_scales is None else raw_array(v_scales)
         self.tree.append_quantised(node, raw_array(k), raw_array(v), ks, vs)
+
+
+class OracleDynamicSink:
+    """The sink interface of the dynamic search driver (spex_workloads.dynamic) on top of an
+    OracleTree: same seeded values, the oracle's own quantiser for decode tokens, attention only
+    when `attend_every` says so (it is fp64 and slow), S_KV from its own token counts."""
+
+    def __init__(self, shape, values, attend_every=0, sm_scale=None):
+        self.shape, self.values = shape, values
+        self.tree = OracleTree(shape.num_q_heads, shape.num_kv_heads, shape.head_dim, shape.kv_dtype,
+                               scale_block=shape.page_size)
+        self.attend_every = attend_every
+        self.sm_scale = sm_scale if sm_scale is not None else shape.head_dim ** -0.5
+        self.results = {}                       # iteration -> (nodes, out, lse)
+        self._last_tok = None
+
+    def fork(self, parent, n):
+        return self.tree.fork(parent, n)
+
+    def prune(self, node):
+        self.tree.prune(node)
+
+    def path_kv_bytes(self, node):
+        esz = {"bf16": 2, "fp8_e4m3": 1, "f32": 4}[self.shape.kv_dtype]
+        tokens = pages = 0
+        for u in self.tree.path(node):
+            tokens += self.tree.n_tokens[u]
+            pages += -(-self.tree.n_tokens[u] // self.shape.page_size)
+        b = float(tokens) * 2.0 * self.shape.num_kv_heads * self.shape.head_dim * esz
+        if self.shape.kv_dtype == "fp8_e4m3":
+            b += float(pages) * 8.0 * self.shape.num_kv_heads
+        return b
+
+    def append_prompt(self, node, n, key):
+        from spex_workloads.quant import quantise_pages
+        k, v = self.values.kv_run(key, 0, n)
+        if self.shape.kv_dtype == "fp8_e4m3":
+            kc, ks = quantise_pages(k, 0, self.shape.page_size, None)
+            vc, vs = quantise_pages(v, 0, self.shape.page_size, None)
+            self.tree.append(node, raw_array(kc), raw_array(vc), raw_array(ks), raw_array(vs))
+        else:
+            self.tree.append(node, raw_array(k.to(torch.bfloat16)), raw_array(v.to(torch.bfloat16)))
+
+    def append_tokens(self, nodes, keys, tok):
+        k, v = self.values.kv_tokens(keys, tok)
+        P = self.shape.page_size
+        for i, u in enumerate(nodes):
+            if self.shape.kv_dtype == "fp8_e4m3":
+                s = None
+                if self.tree.n_tokens[u] % P == 0:
+                    s = np.full((1, self.shape.num_kv_heads), self.shape.fp8_scale, dtype=np.float32)
+                self.tree.append_quantised(u, raw_array(k[i:i + 1]), raw_array(v[i:i + 1]), s, s)
+            else:
+                self.tree.append(u, raw_array(k[i:i + 1]), raw_array(v[i:i + 1]))
+        self._last_tok = (list(keys), list(tok))
+
+    def attend(self, nodes, iteration):
+        if not self.attend_every or iteration % self.attend_every:
+            return
+        keys, tok = self._last_tok
+        q = queries_fp64(self.values.queries(keys, tok))
+        out, lse = self.tree.attention(list(nodes), None, q, self.sm_scale)
+        self.results[iteration] = (list(nodes), out, lse)

@@ -630,3 +630,57 @@ def test_quantising_append_special_values_and_errors():
         b.append_tokens([r], x, x, one, one, quantize=True)
     assert e.value.name == "UNSUPPORTED" and b.node_info(r)["n_tokens"] == 0
     b.close()
+
+
+# ------------------------------------------------------------------ a search that grows while it is served
+@pytest.mark.parametrize("kv_dtype,heads", [("bf16", (8, 2, 128)), ("fp8_e4m3", (16, 4, 128)), ("bf16", (8, 8, 64))])
+def test_dynamic_search_attention_matches_oracle_while_the_tree_changes(kv_dtype, heads):
+    """REBASE widths, speculative children, prunes and early termination (the C-ABI scheduling
+    primitives) reshape the tree every few iterations; the attention of sampled iterations is
+    compared with the oracle driven by its own primitives through the same seeded search."""
+    import paper_2605_10195_amd as spex
+    from paper_2605_10195_amd import binding as B
+    from oracle import scheduling as sch
+    from oracle.adapters import OracleDynamicSink
+    from spex_workloads.dynamic import DynamicConfig, DynamicShape, DynamicValues, LibrarySink, RebaseSpexDriver
+
+    class LibSched:
+        rebase_widths = staticmethod(B.spex_sched_rebase_widths)
+        allocate_budget = staticmethod(B.spex_sched_allocate_budget)
+        early_termination = staticmethod(B.spex_sched_early_termination)
+
+    class OracleSched:
+        rebase_widths = staticmethod(sch.rebase_widths)
+        allocate_budget = staticmethod(sch.allocate_budget)
+        early_termination = staticmethod(sch.early_termination)
+
+    cfg = DynamicConfig(n_queries=4, prompt=(40, 150), budget=6, max_depth=4, step=(4, 30), k_total=10, seed=31)
+    shape = DynamicShape(heads[0], heads[1], heads[2], 16, kv_dtype)
+    every = 7
+    ora = OracleDynamicSink(shape, DynamicValues(shape, cfg.seed, "cpu"), attend_every=every)
+    ref_driver = RebaseSpexDriver(cfg, ora, OracleSched)
+    ref_stats = ref_driver.run(400)
+    tree = spex.SpexTree(heads[0], heads[1], heads[2], 16, "bf16", kv_dtype, num_pages=4000, device="cuda",
+                         pool_fill=0xFF)
+
+    class Checked(LibrarySink):
+        checked = 0
+
+        def attend(self, nodes, iteration):
+            super().attend(nodes, iteration)
+            if iteration in ora.results:
+                ref_nodes, ref_out, ref_lse = ora.results[iteration]
+                assert ref_nodes == list(nodes)
+                _, _, out, lse = self.last
+                got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+                assert_close(got, (ref_out, ref_lse), kv_dtype, f"iteration {iteration}")
+                Checked.checked += 1
+
+    sink = Checked(tree, shape, DynamicValues(shape, cfg.seed, "cuda"), B.spex_tree_path_kv_bytes)
+    driver = RebaseSpexDriver(cfg, sink, LibSched)
+    stats = driver.run(400)
+    assert stats == ref_stats and driver.decisions == ref_driver.decisions
+    assert Checked.checked >= 5 and stats["spec_children"] > 0 and stats["prunes"] > 5
+    assert sink.plan_states[1] > 0 and sink.plan_states[2] > 0       # fresh plans and patched plans both occurred
+    assert tree.stats()[:2] == (0, 0)
+    tree.close()
