@@ -169,7 +169,7 @@ def run_dynamic(args):
             acc["kv_tokens"] += self.tree.last_launch_info()["kv_tokens"]
             acc["peak_pages"] = max(acc["peak_pages"], self.tree.stats()[1])
 
-    sink = Sink(tree, shape, DynamicValues(shape, cfg.seed, dev), B.spex_tree_path_kv_bytes)
+    sink = Sink(tree, shape, DynamicValues(shape, cfg.seed, dev, table_rows=8192), B.spex_tree_path_kv_bytes)
     driver = RebaseSpexDriver(cfg, sink, Sched)
     driver.start()
     for _ in range(args.warmup):

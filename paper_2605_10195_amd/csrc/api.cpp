@@ -61,10 +61,17 @@ struct spex_tree {
 
   void *d_plan = nullptr;
   size_t d_plan_cap = 0;
-  void *h_stage = nullptr;  // pinned
-  size_t h_stage_cap = 0;
-  hipEvent_t stage_event = nullptr;
-  bool stage_pending = false;
+  // Pinned staging for host -> device copies (plans, patches, append destinations).  Two slots
+  // used in turn: the host may fill one while the copy out of the other is still queued behind
+  // earlier kernels, so it can prepare the next call while the GPU runs the current one.
+  struct Stage {
+    void *h = nullptr;
+    size_t cap = 0;
+    hipEvent_t event = nullptr;
+    bool pending = false;
+  } stage[2];
+  int stage_cur = 0;
+  void *h_stage = nullptr;  // the slot reserved last (stage[stage_cur].h)
 
   float *d_part_o = nullptr, *d_part_ml = nullptr;
   int64_t part_cap_rows = 0;
@@ -182,26 +189,31 @@ constexpr int kPlanArrays = 15;
 constexpr int kPatchTarget[4] = {2 /*pg_rec*/, 3 /*qt_rec*/, 12 /*walk_blocks*/, 13 /*walk_qt*/};
 
 spex_status_t stage_reserve(spex_tree *t, size_t bytes) {
-  if (t->stage_pending) {
-    HIP_TRY(hipEventSynchronize(t->stage_event));
-    t->stage_pending = false;
+  t->stage_cur ^= 1;
+  spex_tree::Stage &st = t->stage[t->stage_cur];
+  t->h_stage = nullptr;
+  if (st.pending) {
+    HIP_TRY(hipEventSynchronize(st.event));
+    st.pending = false;
   }
-  if (bytes > t->h_stage_cap) {
-    if (t->h_stage) HIP_TRY(hipHostFree(t->h_stage));
-    t->h_stage = nullptr;
-    t->h_stage_cap = 0;
+  if (bytes > st.cap) {
+    if (st.h) HIP_TRY(hipHostFree(st.h));
+    st.h = nullptr;
+    st.cap = 0;
     const size_t cap = align_up(bytes + bytes / 2, 1 << 16);
-    HIP_TRY(hipHostMalloc(&t->h_stage, cap, hipHostMallocDefault));
-    t->h_stage_cap = cap;
+    HIP_TRY(hipHostMalloc(&st.h, cap, hipHostMallocDefault));
+    st.cap = cap;
   }
+  t->h_stage = st.h;
   return SPEX_OK;
 }
 
 spex_status_t stage_send(spex_tree *t, void *dst, size_t bytes, hipStream_t stream) {
-  HIP_TRY(hipMemcpyAsync(dst, t->h_stage, bytes, hipMemcpyHostToDevice, stream));
-  if (!t->stage_event) HIP_TRY(hipEventCreateWithFlags(&t->stage_event, hipEventDisableTiming));
-  HIP_TRY(hipEventRecord(t->stage_event, stream));
-  t->stage_pending = true;
+  spex_tree::Stage &st = t->stage[t->stage_cur];
+  HIP_TRY(hipMemcpyAsync(dst, st.h, bytes, hipMemcpyHostToDevice, stream));
+  if (!st.event) HIP_TRY(hipEventCreateWithFlags(&st.event, hipEventDisableTiming));
+  HIP_TRY(hipEventRecord(st.event, stream));
+  st.pending = true;
   return SPEX_OK;
 }
 
@@ -374,14 +386,16 @@ spex_status_t spex_tree_create(const spex_config_t *cfg, spex_tree_t **out) {
 
 void spex_tree_destroy(spex_tree_t *t) {
   if (!t) return;
-  const bool used_device = t->d_plan || t->d_part_o || t->h_stage || t->stage_event || !t->prof.empty();
+  const bool used_device = t->d_plan || t->d_part_o || t->stage[0].h || t->stage[1].h || !t->prof.empty();
   if (used_device) (void)hipDeviceSynchronize();
   if (t->d_plan) (void)hipFree(t->d_plan);
   if (t->d_patch) (void)hipFree(t->d_patch);
   if (t->d_part_o) (void)hipFree(t->d_part_o);
   if (t->d_part_ml) (void)hipFree(t->d_part_ml);
-  if (t->h_stage) (void)hipHostFree(t->h_stage);
-  if (t->stage_event) (void)hipEventDestroy(t->stage_event);
+  for (spex_tree::Stage &st : t->stage) {
+    if (st.h) (void)hipHostFree(st.h);
+    if (st.event) (void)hipEventDestroy(st.event);
+  }
   for (auto &slot : t->prof)
     for (hipEvent_t e : slot.ev)
       if (e) (void)hipEventDestroy(e);

@@ -89,10 +89,14 @@ class RebaseSpexDriver:
         self.stats = dict(iterations=0, tokens=0, forks=0, prunes=0, spec_children=0, spec_hits=0,
                           spec_misses=0, early_terminations=0, finished_queries=0, max_generating=0)
         self.decisions: List[tuple] = []               # every scheduling decision, for trace comparison
+        self._keys: Dict[int, int] = {}
 
     # ---- seeded properties of a node -----------------------------------------------------
     def _key(self, u: int) -> int:
-        return hash_key(self.cfg.seed, _TAG_NODE, u)
+        k = self._keys.get(u)
+        if k is None:
+            k = self._keys[u] = hash_key(self.cfg.seed, _TAG_NODE, u)
+        return k
 
     def _step_len(self, u: int) -> int:
         lo, hi = self.cfg.step
@@ -276,17 +280,31 @@ class DynamicValues:
     """Seeded K / V / Q of the dynamic search: token t of node u is keyed by (node key, t), so
     every sink receives the same bits whatever order it is driven in."""
 
-    def __init__(self, shape: DynamicShape, seed: int, device="cpu"):
+    def __init__(self, shape: DynamicShape, seed: int, device="cpu", table_rows: int = 0):
+        """table_rows > 0 (a power of two): decode tokens and queries are rows (key + token) mod
+        table_rows of tables drawn once -- one gather per tensor instead of a hash per element;
+        for timing runs, where only the cost of making the values matters."""
         import torch
         from .replay import TAG_K, TAG_Q, TAG_V
         self.shape, self.seed, self.device = shape, seed, torch.device(device)
         self._tags = (TAG_K, TAG_V, TAG_Q)
+        self._tables = None
+        if table_rows:
+            assert table_rows & (table_rows - 1) == 0
+            rows = torch.arange(table_rows, dtype=torch.int64, device=self.device)
+            zero = torch.zeros_like(rows)
+            self._tables = {tag: self._draw(tag, rows, zero, heads).to(torch.bfloat16)
+                            for tag, heads in ((TAG_K, shape.num_kv_heads), (TAG_V, shape.num_kv_heads),
+                                               (TAG_Q, shape.num_q_heads))}
+            self._mask = table_rows - 1
 
     def _draw(self, tag, keys, tok, heads):
         import torch
         from .rng import normal_values
         keys = torch.as_tensor(keys, dtype=torch.int64, device=self.device)
         tok = torch.as_tensor(tok, dtype=torch.int64, device=self.device)
+        if self._tables is not None and tag in self._tables:
+            return self._tables[tag][(keys + tok) & self._mask]
         return normal_values(self.seed, tag, keys, tok, heads, self.shape.head_dim, self.shape.value_scale,
                              self.device)
 
