@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bfs_tot",
                     choices=["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts",
-                             "dynamic_rebase"],
+                             "step_prefill", "dynamic_rebase"],
                     help="dynamic_rebase: a breadth-first search that grows while it is served (REBASE "
                          "widths, speculative children, prunes, early termination decided by the "
                          "spex_sched_* primitives); --steps then counts decode iterations")
@@ -395,7 +395,7 @@ def main():
     if not args.no_cpu_baseline:
         n_cpu = args.cpu_sample_leaves or {"tiny_tree": 4, "bfs_tot": 512, "mcts_skewed": 1105,
                                            "spec_at_scale": 512, "tot_with_drafts": 128,
-                                           "tot_with_drafts_token_trees": 128}[wl.name]
+                                           "tot_with_drafts_token_trees": 128, "step_prefill": 8}[wl.name]
         base, ref_out, leaves, q_lens = cpu_baseline(wl, n_cpu)
         got = sample_out[:ref_out.shape[0]].cpu().numpy().astype(np.float64)
         base["gpu_vs_oracle_max_abs"] = float(np.max(np.abs(got - ref_out)))
@@ -404,6 +404,19 @@ def main():
     else:
         result["cpu_baseline"] = None
 
+    if wl.name == "step_prefill":
+        # many queries per branch: the contraction, not the KV stream, bounds this workload.
+        # flops = 4 * D per (query token, query head, visible KV token): QK^T and PV, 2 each
+        visible = 0
+        for leaf, ql in zip(wl.leaves, wl.q_lens):
+            T = wl.path_tokens(leaf)
+            visible += ql * (T - ql) + ql * (ql + 1) // 2
+        flops = 4.0 * wl.head_dim * wl.num_q_heads * visible
+        tfs = flops / (dom["ms"] * 1e-3) / 1e12
+        result["roofline"] = {"bound": "mfma", "kernel": kernel_name, "achieved": tfs, "peak": 2500.0,
+                              "unit": "TFLOP/s", "frac": tfs / 2500.0, "traffic": None,
+                              "flops_per_launch": flops, "ms_per_launch": dom["ms"],
+                              "hbm_gbps_unique_kv": dom["gbps"]}
     print(json.dumps(result, default=float))
     for t in trees:
         t.close()

@@ -1011,6 +1011,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   constexpr int RK = FP8 ? NKI / 2 : NKI;  // of which K
   constexpr int PER = (RAW + NW - 1) / NW;  // global loads per wavefront and block in the shared phase
   constexpr bool kEven = RAW % NW == 0;     // else the last wavefronts have no piece to fetch
+  // When K and V each split evenly over the wavefronts, a wavefront's first KPER pieces are K and
+  // the others V whatever its index, so the widening code is chosen at compile time instead of
+  // being run for every piece and selected away.
+  constexpr bool kSplitKV = RK % NW == 0 && (RAW - RK) % NW == 0;
+  constexpr int KPER = kSplitKV ? RK / NW : 0;
   constexpr int kItemInts = NW == 4 ? 16 : 32;
   constexpr int kImgFloats = NI * 64 * 4;
   constexpr int kLdsFloats =
@@ -1112,10 +1117,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        const int idx = k * NW + w;  // wave-uniform
+        const bool is_k = kSplitKV ? k < KPER : k * NW + w < RK;
+        const int idx = kSplitKV ? (k < KPER ? k * NW + w : RK + (k - KPER) * NW + w) : k * NW + w;  // wave-uniform
         if (!kEven && idx >= RAW) continue;
-        const char *src = idx < RK ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
-                                   : vp + (idx - RK) * 512;
+        const char *src = is_k ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
+                               : vp + (idx - RK) * 512;
         rw.r[k] = (bm.flags & 2) ? *reinterpret_cast<const u32x4 *>(src) : load_kv(src);
       }
       rw.vs = jj < 2 ? bm.va : bm.vb;
@@ -1124,10 +1130,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       u32x4 *dst = img + buf * (NI * 64) + lane;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        const int idx = k * NW + w;
+        const bool is_k = kSplitKV ? k < KPER : k * NW + w < RK;
+        const int idx = kSplitKV ? (k < KPER ? k * NW + w : RK + (k - KPER) * NW + w) : k * NW + w;
         if (!kEven && idx >= RAW) continue;
         if (FP8) {
-          if (idx < RK) {
+          if (is_k) {
             dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][0], rw.r[k][1]));
             dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][2], rw.r[k][3]));
           } else {
@@ -1135,7 +1142,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
             dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(rw.r[k][2], rw.r[k][3], rw.vs);
           }
         } else {
-          dst[idx * 64] = idx < RK ? rw.r[k] : bf16x8_to_f16x8(rw.r[k]);
+          dst[idx * 64] = is_k ? rw.r[k] : bf16x8_to_f16x8(rw.r[k]);
         }
       }
     };

@@ -350,6 +350,19 @@ def tot_with_drafts(seed: int = 5, n_queries: int = 64, prompt: int = 1024, step
     return with_draft_trees(wl) if token_trees else wl
 
 
+def step_prefill(seed: int = 6, n_queries: int = 32, prompt: int = 512, step: int = 128, width: int = 16,
+                 keep: int = 4, depth: int = 5, heads=(32, 8, 128), kv_dtype: str = "bf16",
+                 q_dtype: str = "bf16") -> Workload:
+    """The tree of config 2 at the moment its newest steps are scored: a process reward model reads
+    every frontier node's whole step (Sec. 2.1: rewards come from a reward model; Sec. 6.1 runs one
+    next to the generator), i.e. q_len = step queries per leaf, causal among themselves, over the
+    shared root-to-parent prefix."""
+    wl = bfs_tot(seed, n_queries, prompt, step, width, keep, depth, heads, kv_dtype, q_dtype)
+    wl.name = "step_prefill"
+    wl.q_lens = [step] * len(wl.leaves)
+    return wl
+
+
 def draft_tree_masks(seed: int, key: int, n: int) -> List[int]:
     """A seeded draft token tree of n tokens (Sec. 6.5 verifies token trees of 4-16 drafts): draft
     0 is the root, the parent of draft j > 0 is drawn from the drafts before it; the mask of a
@@ -446,4 +459,5 @@ WORKLOADS = {
     "mcts_skewed": mcts_skewed,
     "spec_at_scale": spec_at_scale,
     "tot_with_drafts": tot_with_drafts,
+    "step_prefill": step_prefill,
 }
