@@ -182,6 +182,9 @@ REDUCED = [
     sw.spec_at_scale(n_queries=3, prompt=300, step=100, branches=12),
     sw.tot_with_drafts(n_queries=3, prompt=250, step=56),
     sw.bfs_tot(n_queries=2, prompt=64, step=32, kv_dtype="fp8_e4m3", heads=(16, 2, 64)),
+    sw.step_prefill(n_queries=2, prompt=90, step=44, width=8, keep=2, depth=3),           # q_len = 44: 176 rows per branch
+    sw.step_prefill(n_queries=1, prompt=50, step=70, width=4, keep=2, depth=2, kv_dtype="fp8_e4m3",
+                    heads=(10, 2, 128)),                                                   # 350 rows, G = 5
 ]
 
 
