@@ -25,10 +25,11 @@ HBM_PEAK_GBPS = 8000.0
 # a plain 1 GiB-in / 1 GiB-out kernel (--calibrate): FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB.  The
 # summaries are in profiles/<workload>_tree_walk.md.  Key: (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("bfs_tot", "spex_tree_walk_kernel"): 535151677,           # profiles/bfs_tot_tree_walk.md
-    ("mcts_skewed", "spex_tree_walk_kernel"): 609996247,       # profiles/mcts_skewed_tree_walk.md
-    ("spec_at_scale", "spex_tree_walk_kernel"): 13166198681,   # profiles/spec_at_scale_tree_walk.md
-    ("tot_with_drafts", "spex_tree_walk_kernel"): 497297500,   # profiles/tot_with_drafts_tree_walk.md
+    ("bfs_tot", "spex_tree_walk_kernel"): 535138528,           # profiles/bfs_tot_tree_walk.md
+    ("mcts_skewed", "spex_tree_walk_kernel"): 609959832,       # profiles/mcts_skewed_tree_walk.md
+    ("spec_at_scale", "spex_tree_walk_kernel"): 13311691808,   # profiles/spec_at_scale_tree_walk.md
+    ("tot_with_drafts", "spex_tree_walk_kernel"): 496820408,   # profiles/tot_with_drafts_tree_walk.md
+    ("step_prefill", "spex_tree_walk_kernel"): 2221897152,     # profiles/step_prefill_tree_walk.md
 }
 PAPER_CONTEXT = ("paper reports only end-to-end serving speedups (1.2-3x, up to 4.1x with MTP) on "
                  "NVIDIA A6000/A100; no attention-kernel number exists for this metric")
@@ -414,7 +415,8 @@ def main():
         flops = 4.0 * wl.head_dim * wl.num_q_heads * visible
         tfs = flops / (dom["ms"] * 1e-3) / 1e12
         result["roofline"] = {"bound": "mfma", "kernel": kernel_name, "achieved": tfs, "peak": 2500.0,
-                              "unit": "TFLOP/s", "frac": tfs / 2500.0, "traffic": None,
+                              "unit": "TFLOP/s", "frac": tfs / 2500.0,
+                              "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name)),
                               "flops_per_launch": flops, "ms_per_launch": dom["ms"],
                               "hbm_gbps_unique_kv": dom["gbps"]}
     print(json.dumps(result, default=float))
