@@ -146,8 +146,11 @@ spex_status_t spex_tree_append_step(spex_tree_t *tree, spex_node_t node, int32_t
  *           token starts a new page and ignored otherwise
  * All or nothing: if a node is unknown, repeated (SPEX_ERR_INVALID_ARG), has live children, or
  * the pool has too few free pages for all of them, nothing is changed.  Pages are taken in the
- * order of `nodes`.  Tokens that start no page leave the structure version of the tree unchanged,
- * so the next decode_attention patches its cached lists instead of planning afresh.
+ * order of `nodes`.  Tokens that start no page leave the structure of the cached launch lists
+ * intact: if the handle holds such lists on the device, the same launch that scatters the tokens
+ * also writes the new page lengths and query limits into them, and a decode_attention call that
+ * repeats the previous request then runs without planning, upload or patch launch (it reports
+ * plan state 2).  Both calls must be on the same stream, or ordered by the caller.
  */
 spex_status_t spex_tree_append_tokens(spex_tree_t *tree, const spex_node_t *nodes, int32_t n_nodes,
                                       const void *k, const void *v, const float *k_scales,

@@ -53,6 +53,7 @@ struct spex_tree {
   spex::Planner planner;
   spex::Plan plan;
   bool plan_on_device = false, device_has_split = false, device_has_walk = false;
+  bool plan_patched_by_append = false;  // the cached plan was brought up to date by an append call
   DevicePlan dplan;
   size_t blob_off[15] = {}, blob_ints[15] = {};  // byte offset and length of each list in the blob
   std::vector<int32_t> pending_patches;          // {array, index, value} not yet on the device
@@ -169,8 +170,13 @@ spex_status_t plan_status(spex_tree *t, spex::PlanError e) {
 spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_lens,
                         const uint32_t *masks, int32_t n, int *state) {
   *state = 0;
+  const bool by_append = t->plan_patched_by_append;
+  t->plan_patched_by_append = false;
   if (request_matches(t->plan, t, leaves, q_lens, masks, n)) {
-    if (t->plan.table_version == t->pt->version()) return SPEX_OK;
+    if (t->plan.table_version == t->pt->version()) {
+      if (by_append) *state = 2;  // patched already, by the append launch
+      return SPEX_OK;
+    }
     if (t->planner.patch_lengths(*t->pt, &t->plan, &t->pending_patches)) {
       *state = 2;
       return SPEX_OK;
@@ -498,16 +504,21 @@ static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes
   if (k && t->cfg.kv_dtype == SPEX_FP8_E4M3 && need > 0 && (!k_scales || !v_scales))
     return SPEX_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const size_t bytes = static_cast<size_t>(n_nodes) * 2 * sizeof(int32_t);
+  // Staging holds the destination list and, behind it, the length patches of the cached plan that
+  // this launch applies as well.  Room for 16 patches per node is reserved before anything
+  // changes; if a plan needs more, its patches wait for the next decode_attention call instead.
+  const size_t dst_ints = static_cast<size_t>(n_nodes) * 2;
+  const size_t patch_room = static_cast<size_t>(n_nodes) * 16;  // {index, value} pairs
+  const size_t bytes_max = (dst_ints + 2 * patch_room) * sizeof(int32_t);
   int32_t *h = nullptr;
   if (k) {
-    const spex_status_t rs = stage_reserve(t, bytes);
+    const spex_status_t rs = stage_reserve(t, bytes_max);
     if (rs != SPEX_OK) return rs;
-    if (bytes > t->d_patch_cap) {
+    if (bytes_max > t->d_patch_cap) {
       if (t->d_patch) HIP_TRY(hipFree(t->d_patch));
       t->d_patch = nullptr;
       t->d_patch_cap = 0;
-      const size_t cap = align_up(bytes + bytes / 2, 1 << 16);
+      const size_t cap = align_up(bytes_max + bytes_max / 2, 1 << 16);
       HIP_TRY(hipMalloc(&t->d_patch, cap));
       t->d_patch_cap = cap;
     }
@@ -526,6 +537,38 @@ static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes
     }
   }
   if (!k) return SPEX_OK;
+  // The cached plan, if its copy is on the device and nothing else is waiting for it, follows the
+  // append right here: same request next time means no planning and no separate patch launch.
+  size_t n_patch = 0;
+  if (t->plan.valid && t->plan_on_device && t->pending_patches.empty() &&
+      t->plan.table_version != t->pt->version()) {
+    std::vector<int32_t> &pp = t->pending_patches;
+    if (t->planner.patch_lengths(*t->pt, &t->plan, &pp)) {
+      int32_t *hp = h + dst_ints;
+      bool fits = true;
+      for (size_t i = 0; i < pp.size() / 3 && fits; ++i) {
+        const int arr = kPatchTarget[pp[3 * i]];
+        const size_t idx = static_cast<size_t>(pp[3 * i + 1]);
+        if (idx >= t->blob_ints[arr]) continue;  // that list is not on the device
+        if (n_patch == patch_room) {
+          fits = false;
+          break;
+        }
+        hp[2 * n_patch] = static_cast<int32_t>(t->blob_off[arr] / sizeof(int32_t) + idx);
+        hp[2 * n_patch + 1] = pp[3 * i + 2];
+        ++n_patch;
+      }
+      if (fits && n_patch <= static_cast<size_t>(n_nodes) * t->cfg.num_kv_heads * t->cfg.head_dim) {
+        pp.clear();
+        t->plan_patched_by_append = true;
+      } else {
+        n_patch = 0;  // too many for this launch: decode_attention sends them
+      }
+    } else {
+      pp.clear();  // the structure changed: the next call plans afresh
+    }
+  }
+  const size_t bytes = (dst_ints + 2 * n_patch) * sizeof(int32_t);
   const spex_status_t ss = stage_send(t, t->d_patch, bytes, stream);
   if (ss != SPEX_OK) return ss;
   spex::AppendTokensArgs a{};
@@ -540,6 +583,9 @@ static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes
   a.dst = static_cast<const int32_t *>(t->d_patch);
   a.n_nodes = n_nodes;
   a.quantise = quantise;
+  a.plan = static_cast<int32_t *>(t->d_plan);
+  a.patches = static_cast<const int32_t *>(t->d_patch) + dst_ints;
+  a.n_patches = static_cast<int32_t>(n_patch);
   HIP_TRY(spex::launch_append_tokens(t->shape, a, stream));
   return SPEX_OK;
 }

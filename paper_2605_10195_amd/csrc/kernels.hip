@@ -1511,7 +1511,8 @@ __device__ __forceinline__ uint32_t encode_e4m3(float y) {
 
 // One appended token per node: thread = (node, kv head, dim).  Writes the token's K and V element
 // into its slot; where the token starts a page it also zeroes the page's other slots (so that
-// nothing stale can be read from a partial page) and stores the page's fp8 scales.  QUANT (fp8
+// nothing stale can be read from a partial page) and stores the page's fp8 scales.  The first
+// n_patches threads also write one length patch each into the device copy of the cached plan.  QUANT (fp8
 // pools): the source holds bf16 values and the code is encode_e4m3(x * (1 / scale)), scale being
 // the one given for a page the token starts, else the one the page already has.
 template <int KV, int LAYOUT, bool QUANT>
@@ -1522,6 +1523,8 @@ __global__ __launch_bounds__(256) void spex_append_tokens_kernel(AppendTokensArg
   const int64_t total = static_cast<int64_t>(a.n_nodes) * H * D;
   const int64_t tid = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
   if (tid >= total) return;
+  // the cached launch lists follow the append in the same launch: new valid counts and limits
+  if (tid < a.n_patches) a.plan[a.patches[2 * tid]] = a.patches[2 * tid + 1];
   const int d = static_cast<int>(tid % D);
   const int g = static_cast<int>((tid / D) % H);
   const int node = static_cast<int>(tid / (static_cast<int64_t>(D) * H));

@@ -92,6 +92,11 @@ struct AppendTokensArgs {
   // fp8 pools only: k_src / v_src hold bf16 values, which the kernel encodes with the scale of the
   // page the token lands in (k_scale_src / v_scale_src for a page it starts)
   bool quantise;
+  // Length patches of the cached plan, applied by the same launch (thread i < n_patches stores
+  // patches[2 i + 1] into plan[patches[2 i]]); n_patches <= number of threads, 0 = none.
+  int32_t *plan;
+  const int32_t *patches;
+  int32_t n_patches;
 };
 
 struct GatherArgs {
