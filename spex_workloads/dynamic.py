@@ -336,8 +336,6 @@ class LibrarySink:
         self.tree, self.shape, self.values, self._path_bytes = tree, shape, values, path_bytes
         self.sm_scale = sm_scale if sm_scale is not None else shape.head_dim ** -0.5
         self.with_values = with_values
-        self.key_of: Dict[int, int] = {}
-        self.tok_of: Dict[int, int] = {}
         self.last = None                          # (nodes, q, out, lse) of the latest attention call
         self.plan_states = {0: 0, 1: 0, 2: 0}
 
@@ -351,8 +349,6 @@ class LibrarySink:
         return self._path_bytes(self.tree, node)
 
     def append_prompt(self, node, n, key):
-        self.key_of[node] = key
-        self.tok_of[node] = n
         if not self.with_values:
             self.tree.append_step(node, None, None, n_tokens=n)
             return
@@ -367,8 +363,6 @@ class LibrarySink:
             self.tree.append_step(node, k.to(torch.bfloat16).contiguous(), v.to(torch.bfloat16).contiguous())
 
     def append_tokens(self, nodes, keys, tok):
-        for u, key in zip(nodes, keys):
-            self.key_of[u] = key
         if not self.with_values:
             self.tree.append_tokens(nodes, None, None)
             return

@@ -687,3 +687,38 @@ def test_dynamic_search_attention_matches_oracle_while_the_tree_changes(kv_dtype
     assert sink.plan_states[1] > 0 and sink.plan_states[2] > 0       # fresh plans and patched plans both occurred
     assert tree.stats()[:2] == (0, 0)
     tree.close()
+
+
+def test_draft_masks_edge_cases():
+    """No prefix at all (T == q_len), drafts that straddle two nodes of which the first is shared,
+    a single query with an empty mask, and an empty request list."""
+    import paper_2605_10195_amd as spex
+    wl = sw.Workload("mask_edges", 8, 2, 128, 16, "bf16", "bf16", 0.5, 81)
+    b = sw.trees._Builder(wl)
+    (r1,) = b.fork(-1, 1)
+    b.append(r1, 5)
+    b.request(r1, 5)                               # the whole path is drafts
+    (r2,) = b.fork(-1, 1)
+    b.append(r2, 19)
+    c1, c2 = b.fork(r2, 2)
+    b.append(c1, 4)
+    b.append(c2, 2)
+    b.request(c1, 7)                               # 3 drafts in the shared root (partial page), 4 in the child
+    b.request(c2, 1)                               # mask 0: sees the 20 tokens before its own
+    b.request(c2, 2)                               # the same node again, two drafts
+    wl.draft_masks = [0b00001, 0b00011, 0b00101, 0b01001, 0b10101,
+                      0b0000001, 0b0000011, 0b0000101, 0b0001011, 0b0010011, 0b0100101, 0b1001011,
+                      0,
+                      0b01, 0b10]
+    ref = run_oracle(wl)
+    for mode in (0, 1, 3):
+        assert_close(run_gpu(wl, kernel_mode=mode), ref, "bf16", f"mask edges mode {mode}")
+    tree = build_gpu_tree(wl)
+    q = sw.gen_queries(wl, device="cuda")
+    out, lse = tree.decode_attention([], [], q[:0].contiguous(), wl.sm_scale, draft_masks=[])
+    assert out.shape[0] == 0
+    with pytest.raises(spex.SpexError) as e:       # the first query of r1 would see nothing
+        tree.decode_attention([r1], [5], q[:5].contiguous(), wl.sm_scale, draft_masks=[0, 1, 1, 1, 1])
+    assert e.value.name == "EMPTY_PATH"
+    tree.append_tokens([], None, None, quantize=False)      # nothing to do
+    tree.close()
