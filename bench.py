@@ -95,7 +95,13 @@ def cpu_baseline(wl, n_leaves):
         t0 = time.perf_counter()
         out, _ = sink.tree.attention(leaves, q_lens, q, wl.sm_scale, draft_masks=masks)
         dt = time.perf_counter() - t0
-    return dict(value=sum(q_lens) / dt, unit="query-tokens/s", cores=1, kind="oracle",
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
+    return dict(value=sum(q_lens) / dt, unit="query-tokens/s", cores=1, kind="oracle", cpu_model=cpu_model,
                 sample=f"first {len(leaves)} of {len(wl.leaves)} requested branches "
                        f"({sum(q_lens)} query tokens), materialise + fp64 attention, {dt:.2f} s",
                 seconds=dt), out, leaves, q_lens

@@ -722,3 +722,37 @@ def test_draft_masks_edge_cases():
     assert e.value.name == "EMPTY_PATH"
     tree.append_tokens([], None, None, quantize=False)      # nothing to do
     tree.close()
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3"])
+def test_causal_drafts_equal_single_queries_on_truncated_trees(kv_dtype):
+    """Draft i of a q_len = 6 request sees exactly what a single query sees on the same tree cut
+    off after draft i: both through the library, on two different trees."""
+    def tree_with(n_drafts, q_len):
+        wl = sw.Workload("drafts", 8, 2, 128, 16, "bf16", kv_dtype, 0.5, 83)
+        b = sw.trees._Builder(wl)
+        (root,) = b.fork(-1, 1)
+        b.append(root, 70)
+        a, c = b.fork(root, 2)
+        b.append(a, 21, key=1)
+        b.append(c, 33, key=2)
+        b.append(a, n_drafts, key=3)            # the drafts start a token run of their own
+        b.append(c, n_drafts, key=4)
+        b.request(a, q_len, key=5)
+        b.request(c, q_len, key=6)
+        return wl
+    full = tree_with(6, 6)
+    out6, lse6 = run_gpu(full, kernel_mode=0)
+    q6 = sw.gen_queries(full, device="cuda")
+    for i in range(6):
+        wl = tree_with(i + 1, 1)
+        tree = build_gpu_tree(wl)
+        q = torch.stack([q6[i], q6[6 + i]]).contiguous()        # the same query vectors
+        out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        want = np.stack([out6[i], out6[6 + i]])
+        assert np.max(np.abs(got - want)) <= 2e-3, i
+        assert np.max(np.abs(lse.cpu().numpy() - np.stack([lse6[i], lse6[6 + i]]))) <= 2e-3, i
+        tree.close()
+    assert_close((out6, lse6), run_oracle(full), kv_dtype, "six causal drafts")
