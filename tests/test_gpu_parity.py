@@ -756,3 +756,36 @@ def test_causal_drafts_equal_single_queries_on_truncated_trees(kv_dtype):
         assert np.max(np.abs(lse.cpu().numpy() - np.stack([lse6[i], lse6[6 + i]]))) <= 2e-3, i
         tree.close()
     assert_close((out6, lse6), run_oracle(full), kv_dtype, "six causal drafts")
+
+
+def test_flat_copies_of_every_branch_agree_with_the_shared_tree():
+    """Every requested branch stored privately (one root per branch holding a copy of its path's
+    tokens) gives what the prefix-sharing tree gives."""
+    shared = sw.bfs_tot(n_queries=2, prompt=70, step=27, width=8, keep=2, depth=3, heads=(8, 2, 128))
+    tokens, parent, _ = shared.node_tokens()
+    key_of = {}
+    for op in shared.ops:
+        if op.kind == "append":
+            assert op.tok0 == 0                     # one append per node in this generator
+            key_of[op.node] = op.key
+    flat = sw.Workload("flat", 8, 2, 128, 16, "bf16", "bf16", 0.5, shared.seed)
+    b = sw.trees._Builder(flat)
+    for leaf, ql, qk in zip(shared.leaves, shared.q_lens, shared.q_keys):
+        path = []
+        u = leaf
+        while u != -1:
+            path.append(u)
+            u = parent[u]
+        (r,) = b.fork(-1, 1)
+        for u in reversed(path):                    # the same token streams, laid end to end
+            flat.ops.append(sw.TreeOp("append", r, tokens[u], key_of[u], 0))
+            b.tokens[r] += tokens[u]
+        b.request(r, ql, key=qk)
+    assert flat.unique_kv_tokens() == shared.flat_kv_tokens() > 2 * shared.unique_kv_tokens()
+    ref = run_oracle(shared)
+    got_shared = run_gpu(shared)
+    got_flat = run_gpu(flat)
+    assert_close(got_shared, ref, "bf16", "shared")
+    assert_close(got_flat, ref, "bf16", "flat")
+    assert np.max(np.abs(got_shared[0] - got_flat[0])) <= 2e-3
+    assert_close(run_oracle(flat), ref, "bf16", "oracle flat vs shared")     # 1e-12 in fact
