@@ -1181,7 +1181,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     // LDS buffer after the computation, and the global loads of block c+PF are issued.  The loads
     // are unconditional (indices past the end repeat the last block) because a load issued on
     // one path only would make every later wait a wait for all outstanding loads.  (PF = 4 was
-    // measured for one row tile per wavefront, where the registers allow it: no gain.)
+    // measured for one row tile per wavefront and for fp8 with two, where the registers allow it:
+    // no gain.)
     constexpr int PF = 2;
     Raw x[PF];
     WalkBlock bmq[PF];
@@ -1196,12 +1197,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
 #pragma unroll
       for (int k = 0; k < PF; ++k) {
         const int c = b + k;             // block computed in this step; x[k] is free again
-        if (c >= n_shared) break;        // uniform over the workgroup
         const WalkBlock cur = bmq[k];
         bmq[k] = meta(c + PF);
         stage_load(x[k], bmq[k]);
-        compute(c, cur);
-        if (c + 1 < n_shared) stage_store(x[(k + 1) % PF], (c + 1) & 1);
+        // no early exit from the group of PF steps: a step past the end only moves (clamped)
+        // data, so that every path through the loop body issues and waits for the same loads
+        if (c < n_shared) compute(c, cur);
+        // Unconditional: after the last block this stores a copy of that block (the loads are
+        // clamped) into the buffer nobody reads any more.  A store skipped on one path would leave
+        // its loads unwaited there, and the compiler would then drain every outstanding load at
+        // the top of the loop -- the prefetch of the next block included.
+        stage_store(x[(k + 1) % PF], (c + 1) & 1);
         __syncthreads();
       }
     }
