@@ -42,10 +42,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bfs_tot",
                     choices=["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts",
-                             "step_prefill", "dynamic_rebase"],
-                    help="dynamic_rebase: a breadth-first search that grows while it is served (REBASE "
-                         "widths, speculative children, prunes, early termination decided by the "
-                         "spex_sched_* primitives); --steps then counts decode iterations")
+                             "step_prefill", "dynamic_rebase", "dynamic_mcts"],
+                    help="dynamic_rebase / dynamic_mcts: a breadth-first (REBASE widths, speculative "
+                         "children verified at the level barrier) or depth-first (UCB descents, Alg. 1 "
+                         "speculative expansions) search that grows while it is served, every decision "
+                         "by the spex_sched_* primitives; --steps then counts decode iterations")
     ap.add_argument("--copies", type=int, default=0, help="rotating tree copies (0 = automatic)")
     ap.add_argument("--placement", default="random", choices=["random", "ascending"])
     ap.add_argument("--kv-pools", default="interleaved", choices=["interleaved", "separate"])
@@ -152,16 +153,24 @@ def run_dynamic(args):
     import paper_2605_10195_amd as spex
     from paper_2605_10195_amd import binding as B
     from spex_workloads.dynamic import (DynamicConfig, DynamicShape, DynamicValues, LibrarySink,
-                                        RebaseSpexDriver)
+                                        MctsConfig, MctsSpexDriver, RebaseSpexDriver)
 
     class Sched:
         rebase_widths = staticmethod(B.spex_sched_rebase_widths)
         allocate_budget = staticmethod(B.spex_sched_allocate_budget)
         early_termination = staticmethod(B.spex_sched_early_termination)
+        ucb_select = staticmethod(B.spex_sched_ucb_select)
+        dfs_speculate = staticmethod(B.spex_sched_dfs_speculate)
+        make_tree = staticmethod(B.SearchTree)
 
     dev = "cuda:0"
-    cfg = DynamicConfig(n_queries=32, prompt=(512, 2048), budget=16, max_depth=6, step=(16, 160),
-                        k_total=128, seed=11)
+    mcts = args.workload == "dynamic_mcts"
+    if mcts:
+        cfg = MctsConfig(n_queries=32, prompt=(512, 2048), branch=3, rollouts=24, c=0.6, step=(16, 160),
+                         k_total=64, k_per_query=4, seed=17)
+    else:
+        cfg = DynamicConfig(n_queries=32, prompt=(512, 2048), budget=16, max_depth=6, step=(16, 160),
+                            k_total=128, seed=11)
     shape = DynamicShape(32, 8, 128, 16, "bf16")
     n_pages = 65536
     order = np.random.default_rng(1000).permutation(n_pages).tolist()
@@ -177,10 +186,8 @@ def run_dynamic(args):
             acc["peak_pages"] = max(acc["peak_pages"], self.tree.stats()[1])
 
     sink = Sink(tree, shape, DynamicValues(shape, cfg.seed, dev, table_rows=8192), B.spex_tree_path_kv_bytes)
-    driver = RebaseSpexDriver(cfg, sink, Sched)
-    driver.start()
-    for _ in range(args.warmup):
-        driver.step()
+    driver = (MctsSpexDriver if mcts else RebaseSpexDriver)(cfg, sink, Sched)
+    driver.run(args.warmup)               # starts the search and runs the warm-up iterations
     torch.cuda.synchronize()
     base = dict(driver.stats)
     states0, kv0 = dict(sink.plan_states), acc["kv_tokens"]
@@ -197,7 +204,8 @@ def run_dynamic(args):
     tokens = driver.stats["tokens"] - base["tokens"]
     kv_bytes = (acc["kv_tokens"] - kv0) * b_tok
     # how scattered the pages of a path are after all the forking and pruning
-    live = [u for u, nd in driver.nodes.items() if nd.alive and not nd.children][:64]
+    live = sorted(driver.gen)[:64] if mcts else \
+        [u for u, nd in driver.nodes.items() if nd.alive and not nd.children][:64]
     adjacent = total = 0
     for u in live:
         pages, _ = tree.path_pages(u)
@@ -209,12 +217,15 @@ def run_dynamic(args):
         "value": tokens / wall, "unit": "query-tokens/s", "n_gpus": 1, "steps": done, "warmup": args.warmup,
         "ms_per_step": wall / max(done, 1) * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "dynamic_rebase", "queries": cfg.n_queries, "heads": [32, 8, 128],
-                   "budget": cfg.budget, "max_depth": cfg.max_depth, "prompt": list(cfg.prompt),
+        "config": {"workload": args.workload, "queries": cfg.n_queries, "heads": [32, 8, 128],
+                   "search": ({"branch": cfg.branch, "rollouts": cfg.rollouts, "c": cfg.c,
+                               "k_per_query": cfg.k_per_query} if mcts else
+                              {"budget": cfg.budget, "max_depth": cfg.max_depth}),
+                   "prompt": list(cfg.prompt),
                    "step_tokens": list(cfg.step), "k_total": cfg.k_total, "pool_pages": n_pages,
                    "note": "a step is one decode iteration: append one token to every generating "
                            "branch, attention for those tokens, then the scheduling decisions"},
-        "search": {k: (driver.stats[k] if k == "max_generating" else driver.stats[k] - base.get(k, 0))
+        "search": {k: (driver.stats[k] if k.startswith("max_") else driver.stats[k] - base.get(k, 0))
                    for k in driver.stats},
         "plans": {"cached": sink.plan_states[0] - states0[0], "fresh": sink.plan_states[1] - states0[1],
                   "patched": sink.plan_states[2] - states0[2]},
@@ -249,7 +260,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda:0"
-    if args.workload == "dynamic_rebase":
+    if args.workload in ("dynamic_rebase", "dynamic_mcts"):
         run_dynamic(args)
         return
     if args.token_trees:

@@ -384,3 +384,215 @@ class LibrarySink:
         out, lse = self.tree.decode_attention(nodes, None, q, self.sm_scale)
         self.plan_states[self.tree.last_launch_info()["plan_rebuilt"]] += 1
         self.last = (list(nodes), q, out, lse)
+
+
+# ---- depth-first search (MCTS) with speculative expansion: Sec. 4.2, Alg. 1 ---------------------
+@dataclass
+class MctsConfig:
+    n_queries: int = 16
+    prompt: tuple = (256, 1024)
+    branch: int = 3                      # children created by one expansion
+    rollouts: int = 10                   # primary expansions per query (the paper runs 5 / 10)
+    c: float = 1.4                       # exploration constant of UCB
+    step: tuple = (8, 96)
+    p_terminal: float = 0.2              # a child of depth >= 3 ends in an answer
+    n_hypotheses: int = 4
+    t_min: int = 4
+    alpha: float = 0.5
+    tau: float = 2e-9
+    param_bytes: float = 1.6e10
+    k_total: int = 32                    # speculative expansions in flight, all queries together
+    k_per_query: int = 4                 # C_q: how far ahead one query is simulated
+    seed: int = 17
+
+
+class MctsSpexDriver:
+    """One search tree per query, kept as the parallel arrays spex_search_tree_t points to.  A
+    primary expansion takes the node a UCB descent ends at and generates `branch` children below
+    it; when they are finished their rewards are backed up.  Meanwhile the nodes the search is
+    predicted to select next (sched.dfs_speculate) are expanded speculatively: such a node is
+    ACTIVE while its children generate and SPEC_DONE afterwards, its children stay outside the
+    arrays.  When a later descent ends at a SPEC_DONE node its children are adopted at once (a
+    hit: no generation, no waiting); when it ends at an ACTIVE node the query waits for it.
+    Nothing is pruned before the query ends: an unused prediction stays a candidate (Sec. 4.2).
+
+    sched: ucb_select(tree) -> node, dfs_speculate(tree, k) -> [nodes], allocate_budget(...),
+    early_termination(...), where `tree` is built by sched.make_tree(parent, visits, value_sum,
+    state, spec_reward, c)."""
+
+    PLAIN, ACTIVE, SPEC_DONE = 0, 1, 2
+
+    def __init__(self, cfg: MctsConfig, sink, sched):
+        self.cfg, self.sink, self.sched = cfg, sink, sched
+        self.q: List[dict] = []
+        self.gen: Dict[int, dict] = {}            # KV node -> {query, remaining, tokens}
+        self.iteration = 0
+        self.stats = dict(iterations=0, tokens=0, expansions=0, spec_expansions=0, spec_hits=0, spec_waits=0,
+                          early_terminations=0, finished_queries=0, max_generating=0, max_depth=0)
+        self.decisions: List[tuple] = []
+        self._keys: Dict[int, int] = {}
+
+    def _key(self, u):
+        k = self._keys.get(u)
+        if k is None:
+            k = self._keys[u] = hash_key(self.cfg.seed, _TAG_NODE, u)
+        return k
+
+    def start(self):
+        cfg = self.cfg
+        roots = self.sink.fork(NO_NODE, cfg.n_queries)
+        for i, r in enumerate(roots):
+            n = cfg.prompt[0] + int((cfg.prompt[1] - cfg.prompt[0] + 1) * _uniform(cfg.seed, _TAG_PROMPT, i))
+            self.sink.append_prompt(r, n, self._key(r))
+            # search arrays; kv[s] = KV-tree node of search node s; pending[s] = children being generated
+            self.q.append(dict(root=r, parent=[-1], visits=[0], value=[0.0], state=[0], spec_reward=[0.0], kv=[r],
+                               depth=[0], pending={}, waiting=None, rollouts=0, answers=[], live=True,
+                               spec_made=0, spec_hit=0))
+
+    def _tree(self, st):
+        return self.sched.make_tree(st["parent"], st["visits"], st["value"], st["state"], st["spec_reward"],
+                                    self.cfg.c)
+
+    def _expand(self, qi, s, speculative):
+        """Fork `branch` children below search node s and start generating their steps."""
+        st = self.q[qi]
+        kids = self.sink.fork(st["kv"][s], self.cfg.branch)
+        lo, hi = self.cfg.step
+        for u in kids:
+            n = lo + int((hi - lo) * _uniform(self.cfg.seed, _TAG_LEN, u) ** 3)
+            self.gen[u] = dict(query=qi, remaining=n, tokens=0)
+        st["pending"][s] = dict(kids=list(kids), left=len(kids), speculative=speculative)
+        st["state"][s] = self.ACTIVE
+        self.stats["expansions" if not speculative else "spec_expansions"] += 1
+        if speculative:
+            st["spec_made"] += 1
+
+    def _adopt(self, qi, s):
+        """The children of s enter the arrays with their rewards backed up along the path."""
+        st = self.q[qi]
+        info = st["pending"].pop(s)
+        st["state"][s] = self.PLAIN
+        for u in info["kids"]:
+            d = st["depth"][s] + 1
+            r = 0.5 * (st["value"][s] / st["visits"][s] if st["visits"][s] else 0.5) \
+                + 0.5 * _uniform(self.cfg.seed, _TAG_REWARD, u)
+            c = len(st["parent"])
+            st["parent"].append(s)
+            st["visits"].append(1)
+            st["value"].append(r)
+            st["state"].append(self.PLAIN)
+            st["spec_reward"].append(0.0)
+            st["kv"].append(u)
+            st["depth"].append(d)
+            self.stats["max_depth"] = max(self.stats["max_depth"], d)
+            a = s
+            while a >= 0:
+                st["visits"][a] += 1
+                st["value"][a] += r
+                a = st["parent"][a]
+            if d >= 3 and _uniform(self.cfg.seed, _TAG_TERMINAL, u) < self.cfg.p_terminal:
+                hyp = 0 if r > 0.55 else 1 + int(_uniform(self.cfg.seed, _TAG_ANSWER, u) * (self.cfg.n_hypotheses - 1))
+                st["answers"].append((hyp, r))
+
+    def _finish(self, qi):
+        st = self.q[qi]
+        st["live"] = False
+        for u in [u for u, g in self.gen.items() if g["query"] == qi]:
+            del self.gen[u]
+        self.sink.prune(st["root"])
+        self.stats["finished_queries"] += 1
+
+    def _advance(self, qi):
+        """Primary search of query qi: select, adopt finished speculations, expand."""
+        st, cfg = self.q[qi], self.cfg
+        while st["live"] and st["waiting"] is None:
+            stop, _ = self.sched.early_termination([a for a, _ in st["answers"]], [w for _, w in st["answers"]],
+                                                   cfg.t_min, cfg.alpha)
+            if stop or st["rollouts"] >= cfg.rollouts:
+                self.decisions.append(("finish", self.iteration, qi, bool(stop)))
+                self.stats["early_terminations"] += int(bool(stop))
+                self._finish(qi)
+                return
+            s = self.sched.ucb_select(self._tree(st))
+            self.decisions.append(("select", self.iteration, qi, s, st["state"][s]))
+            st["rollouts"] += 1
+            if st["state"][s] == self.SPEC_DONE:          # predicted and already generated: a hit
+                self.stats["spec_hits"] += 1
+                st["spec_hit"] += 1
+                self._adopt(qi, s)
+                continue
+            if st["state"][s] == self.ACTIVE:             # being generated speculatively: wait for it
+                self.stats["spec_waits"] += 1
+                st["pending"][s]["speculative"] = False
+                st["waiting"] = s
+                return
+            self._expand(qi, s, False)
+            st["waiting"] = s
+
+    def _speculate(self):
+        cfg = self.cfg
+        live = [i for i, st in enumerate(self.q) if st["live"]]
+        in_flight = sum(1 for i in live for p in self.q[i]["pending"].values() if p["speculative"] and p["left"] > 0)
+        room = cfg.k_total - in_flight
+        if room <= 0 or not live:
+            return
+        capacity = [cfg.k_per_query] * len(live)
+        hit = [(self.q[i]["spec_hit"] + 1) / (self.q[i]["spec_made"] + 2) for i in live]
+        kv = [self.sink.path_kv_bytes(self.q[i]["kv"][self.q[i]["waiting"]] if self.q[i]["waiting"] is not None
+                                      else self.q[i]["root"]) for i in live]
+        k, _ = self.sched.allocate_budget(capacity, hit, kv, cfg.param_bytes, cfg.tau, room)
+        self.decisions.append(("budget", self.iteration, tuple(live), tuple(k)))
+        for qi, k_q in zip(live, k):
+            if k_q <= 0:
+                continue
+            picks = self.sched.dfs_speculate(self._tree(self.q[qi]), k_q)
+            self.decisions.append(("speculate", self.iteration, qi, tuple(picks)))
+            for s in picks:
+                self._expand(qi, s, True)
+
+    def step(self) -> bool:
+        if not any(st["live"] for st in self.q):
+            return False
+        generating = sorted(self.gen)
+        if generating:
+            self.sink.append_tokens(generating, [self._key(u) for u in generating],
+                                    [self.gen[u]["tokens"] for u in generating])
+            self.sink.attend(generating, self.iteration)
+            self.stats["tokens"] += len(generating)
+            self.stats["max_generating"] = max(self.stats["max_generating"], len(generating))
+            for u in generating:
+                g = self.gen[u]
+                g["tokens"] += 1
+                g["remaining"] -= 1
+                if g["remaining"] == 0:
+                    del self.gen[u]
+                    st = self.q[g["query"]]
+                    s = next(s for s, p in st["pending"].items() if u in p["kids"])
+                    p = st["pending"][s]
+                    p["left"] -= 1
+                    if p["left"] == 0:
+                        if p["speculative"]:
+                            st["state"][s] = self.SPEC_DONE
+                            st["spec_reward"][s] = sum(_uniform(self.cfg.seed, _TAG_REWARD, k) for k in p["kids"]) \
+                                / len(p["kids"])
+                        else:
+                            self._adopt(g["query"], s)
+                            if st["waiting"] == s:
+                                st["waiting"] = None
+        self.iteration += 1
+        self.stats["iterations"] = self.iteration
+        for qi, st in enumerate(self.q):
+            if st["live"] and st["waiting"] is None:
+                self._advance(qi)
+        self._speculate()
+        return True
+
+    def run(self, max_iterations: int) -> dict:
+        if not self.q:
+            self.start()
+            for qi in range(len(self.q)):
+                self._advance(qi)
+            self._speculate()
+        while self.iteration < max_iterations and self.step():
+            pass
+        return self.stats

@@ -93,3 +93,35 @@ def test_dynamic_search_terminates_early_when_answers_agree():
     st = d.run(5000)
     assert st["finished_queries"] == 6 and st["early_terminations"] >= 1
     assert any(x[0] == "terminate" and x[3] for x in d.decisions)
+
+
+# ------------------------------------------------------------------ depth-first search (Alg. 1)
+class LibSchedDfs(LibSched):
+    ucb_select = staticmethod(B.spex_sched_ucb_select)
+    dfs_speculate = staticmethod(B.spex_sched_dfs_speculate)
+    make_tree = staticmethod(B.SearchTree)
+
+
+class OracleSchedDfs(OracleSched):
+    ucb_select = staticmethod(sch.ucb_select)
+    dfs_speculate = staticmethod(sch.dfs_speculate)
+    make_tree = staticmethod(sch.SearchTree)
+
+
+@pytest.mark.parametrize("kv_dtype,seed", [("bf16", 17), ("fp8_e4m3", 18)])
+def test_mcts_library_and_oracle_drive_the_same_trace(kv_dtype, seed):
+    from spex_workloads.dynamic import MctsConfig, MctsSpexDriver
+    cfg = MctsConfig(n_queries=4, prompt=(40, 120), branch=3, rollouts=8, step=(3, 25), k_total=8,
+                     k_per_query=3, seed=seed)
+    shape = DynamicShape(8, 2, 64, 16, kv_dtype)
+    tree = spex.SpexTree(8, 2, 64, 16, "bf16", kv_dtype, num_pages=6000, host_only=True)
+    lib_sink = Recorder(LibrarySink(tree, shape, None, B.spex_tree_path_kv_bytes, with_values=False))
+    a = MctsSpexDriver(cfg, lib_sink, LibSchedDfs)
+    sa = a.run(3000)
+    ora_sink = Recorder(CountingOracleSink(shape, None))
+    b = MctsSpexDriver(cfg, ora_sink, OracleSchedDfs)
+    sb = b.run(3000)
+    assert sa == sb and a.decisions == b.decisions and lib_sink.ops == ora_sink.ops
+    assert sa["finished_queries"] == cfg.n_queries and sa["spec_expansions"] > 0
+    assert sa["spec_hits"] + sa["spec_waits"] > 0                 # predictions were used
+    assert sa["max_depth"] >= 3 and tree.stats()[:2] == (0, 0)

@@ -789,3 +789,57 @@ def test_flat_copies_of_every_branch_agree_with_the_shared_tree():
     assert_close(got_flat, ref, "bf16", "flat")
     assert np.max(np.abs(got_shared[0] - got_flat[0])) <= 2e-3
     assert_close(run_oracle(flat), ref, "bf16", "oracle flat vs shared")     # 1e-12 in fact
+
+
+@pytest.mark.parametrize("kv_dtype,heads", [("bf16", (8, 2, 128)), ("fp8_e4m3", (16, 4, 128))])
+def test_mcts_search_attention_matches_oracle_while_the_tree_changes(kv_dtype, heads):
+    """Depth-first search: UCB descents and Alg. 1 speculative expansions (C-ABI primitives) grow
+    deep trees; sampled iterations are compared with the oracle driven by its own primitives."""
+    import paper_2605_10195_amd as spex
+    from paper_2605_10195_amd import binding as B
+    from oracle import scheduling as sch
+    from oracle.adapters import OracleDynamicSink
+    from spex_workloads.dynamic import DynamicShape, DynamicValues, LibrarySink, MctsConfig, MctsSpexDriver
+
+    class LibSched:
+        allocate_budget = staticmethod(B.spex_sched_allocate_budget)
+        early_termination = staticmethod(B.spex_sched_early_termination)
+        ucb_select = staticmethod(B.spex_sched_ucb_select)
+        dfs_speculate = staticmethod(B.spex_sched_dfs_speculate)
+        make_tree = staticmethod(B.SearchTree)
+
+    class OracleSched:
+        allocate_budget = staticmethod(sch.allocate_budget)
+        early_termination = staticmethod(sch.early_termination)
+        ucb_select = staticmethod(sch.ucb_select)
+        dfs_speculate = staticmethod(sch.dfs_speculate)
+        make_tree = staticmethod(sch.SearchTree)
+
+    cfg = MctsConfig(n_queries=3, prompt=(40, 150), branch=3, rollouts=14, c=0.6, step=(4, 30), k_total=8,
+                     k_per_query=3, seed=37)
+    shape = DynamicShape(heads[0], heads[1], heads[2], 16, kv_dtype)
+    ora = OracleDynamicSink(shape, DynamicValues(shape, cfg.seed, "cpu"), attend_every=9)
+    ref_driver = MctsSpexDriver(cfg, ora, OracleSched)
+    ref_stats = ref_driver.run(600)
+    tree = spex.SpexTree(heads[0], heads[1], heads[2], 16, "bf16", kv_dtype, num_pages=6000, device="cuda",
+                         pool_fill=0xFF)
+    checked = []
+
+    class Checked(LibrarySink):
+        def attend(self, nodes, iteration):
+            super().attend(nodes, iteration)
+            if iteration in ora.results:
+                ref_nodes, ref_out, ref_lse = ora.results[iteration]
+                assert ref_nodes == list(nodes)
+                _, _, out, lse = self.last
+                got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+                assert_close(got, (ref_out, ref_lse), kv_dtype, f"iteration {iteration}")
+                checked.append(iteration)
+
+    sink = Checked(tree, shape, DynamicValues(shape, cfg.seed, "cuda"), B.spex_tree_path_kv_bytes)
+    driver = MctsSpexDriver(cfg, sink, LibSched)
+    stats = driver.run(600)
+    assert stats == ref_stats and driver.decisions == ref_driver.decisions
+    assert len(checked) >= 5 and stats["spec_expansions"] > 0 and stats["spec_hits"] > 0
+    assert tree.stats()[:2] == (0, 0)
+    tree.close()
