@@ -248,7 +248,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by tree or by KV head "
-              "without any exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "without any exchange between GPUs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
