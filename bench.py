@@ -25,11 +25,11 @@ HBM_PEAK_GBPS = 8000.0
 # a plain 1 GiB-in / 1 GiB-out kernel (--calibrate): FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB.  The
 # summaries are in profiles/<workload>_tree_walk.md.  Key: (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("bfs_tot", "spex_tree_walk_kernel"): 535138528,           # profiles/bfs_tot_tree_walk.md
-    ("mcts_skewed", "spex_tree_walk_kernel"): 609959832,       # profiles/mcts_skewed_tree_walk.md
-    ("spec_at_scale", "spex_tree_walk_kernel"): 13311691808,   # profiles/spec_at_scale_tree_walk.md
-    ("tot_with_drafts", "spex_tree_walk_kernel"): 496820408,   # profiles/tot_with_drafts_tree_walk.md
-    ("step_prefill", "spex_tree_walk_kernel"): 2221897152,     # profiles/step_prefill_tree_walk.md
+    ("bfs_tot", "spex_tree_walk_kernel"): 535127296,           # profiles/bfs_tot_tree_walk.md
+    ("mcts_skewed", "spex_tree_walk_kernel"): 610866520,       # profiles/mcts_skewed_tree_walk.md
+    ("spec_at_scale", "spex_tree_walk_kernel"): 13343266624,   # profiles/spec_at_scale_tree_walk.md
+    ("tot_with_drafts", "spex_tree_walk_kernel"): 496838488,   # profiles/tot_with_drafts_tree_walk.md
+    ("step_prefill", "spex_tree_walk_kernel"): 2224013696,     # profiles/step_prefill_tree_walk.md
 }
 PAPER_CONTEXT = ("paper reports only end-to-end serving speedups (1.2-3x, up to 4.1x with MTP) on "
                  "NVIDIA A6000/A100; no attention-kernel number exists for this metric")
@@ -64,6 +64,7 @@ def parse():
                     help="verify a seeded draft token tree of this many tokens per branch (4-16, "
                          "tot_with_drafts only; visibility masks through "
                          "spex_tree_decode_attention_masked); 0 = the workload's causal drafts")
+    ap.add_argument("--progress", action="store_true", help="print a line on stderr at every stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true",
@@ -277,6 +278,11 @@ def main():
     if unique_bytes > 4e9:
         copies = args.copies or 1
 
+    def progress(msg):
+        if args.progress:
+            print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+    progress(f"workload {wl.name}: building {copies} tree(s), {n_pages} pages each")
     t_build = time.perf_counter()
     trees = []
     for c in range(copies):
@@ -306,6 +312,7 @@ def main():
         trees[c].decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, outs[c], lses[c],
                                   draft_masks=wl.draft_masks)
 
+    progress("trees built; cold call")
     # cold call: plan build + upload + kernels
     t0 = time.perf_counter()
     step(0)
@@ -318,6 +325,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
+    progress("warm-up done; timed steps")
     # timed region: K steps, plan cached, no events
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -326,6 +334,7 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
 
+    progress("timed steps done; steps with per-kernel events")
     # same K steps again with HIP events around every kernel (on the launch stream)
     for t in trees:
         t.set_profiling(True)
@@ -399,6 +408,7 @@ def main():
     }
 
     sample_out = outs[0].clone()          # the decode loop below reuses outs[0] on a grown tree
+    progress("per-kernel steps done; decode loop / calibration / cpu baseline")
     if args.decode_iters > 0:
         result["decode_loop"] = decode_loop(trees[0], wl, q, outs[0], lses[0], args.decode_iters, dev)
 
@@ -436,6 +446,7 @@ def main():
                               "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name)),
                               "flops_per_launch": flops, "ms_per_launch": dom["ms"],
                               "hbm_gbps_unique_kv": dom["gbps"]}
+    progress("done")
     print(json.dumps(result, default=float))
     for t in trees:
         t.close()
