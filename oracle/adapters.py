@@ -51,11 +51,11 @@ class OracleSink:
         vs = None if v_scales is None else raw_array(v_scales)
         self.tree.append(node, raw_array(k), raw_array(v), ks, vs)
 
-    def append_quantised(self, node, k, v, k_scales=None, v_scales=None):
-        """bf16 tensors into an fp8 oracle tree (the library's quantising append)."""
+    def append_quantised(self, node, k, v, k_scales=None, v_scales=None, derive_scales=False):
+        """bf16 tensors into an fp8 oracle tree (the library's quantising appends)."""
         ks = None if k_scales is None else raw_array(k_scales)
         vs = None if v_scales is None else raw_array(v_scales)
-        self.tree.append_quantised(node, raw_array(k), raw_array(v), ks, vs)
+        self.tree.append_quantised(node, raw_array(k), raw_array(v), ks, vs, derive_scales=derive_scales)
 
 
 class OracleDynamicSink:

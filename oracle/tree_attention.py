@@ -160,27 +160,41 @@ class OracleTree:
         self.V[node].append(vd)
         self.n_tokens[node] += n
 
-    def append_quantised(self, node: int, k_bits, v_bits, k_scales=None, v_scales=None) -> None:
+    def append_quantised(self, node: int, k_bits, v_bits, k_scales=None, v_scales=None,
+                         derive_scales: bool = False) -> None:
         """fp8 cache filled from bf16 tokens (uint16 bit patterns [n, Hkv, D]): token j is encoded
-        with the scale of the block of scale_block tokens it falls in -- the next row of k_scales /
-        v_scales ([blocks this append starts, Hkv]) for a block it starts, else the scale the block
-        already has; a block is never requantised.  code = encode_e4m3(x * (1 / scale)) with the
-        reciprocal and the product rounded to fp32, the precision in which the cache is written."""
+        with the scale of the block of scale_block tokens it falls in.  A block this append starts
+        takes the next row of k_scales / v_scales ([blocks this append starts, Hkv]) or, with
+        derive_scales, max(amax / 448, 2^-40) where amax is the largest magnitude among the tokens
+        this append puts into the block (per kv head, K and V separately, division in fp32); a
+        block that already holds tokens keeps its scale and is never requantised.
+        code = encode_e4m3(x * (1 / scale)) with the reciprocal and the product rounded to fp32,
+        the precision in which the cache is written."""
         assert self.kv_dtype == "fp8_e4m3"
         self._check(node)
-        codes = []
+        B, start = self.scale_block, self.n_tokens[node]
+        codes, made = [], []
         for which, bits, new in ((0, k_bits, k_scales), (1, v_bits, v_scales)):
             x = decode_bf16(np.asarray(bits)).astype(np.float32)
+            blk = (start + np.arange(x.shape[0])) // B
             have = [r.astype(np.float32) for r in self._scales.get(node, ([], []))[which]]
+            if derive_scales:
+                assert new is None
+                rows = []
+                for b in range(len(have), int(blk.max()) + 1):          # the blocks this append starts
+                    amax = np.abs(x[blk == b]).max(axis=(0, 2)).astype(np.float32)      # [Hkv]
+                    rows.append(np.maximum(amax / np.float32(448.0), np.float32(2.0 ** -40)).astype(np.float32))
+                new = np.stack(rows) if rows else None
             if new is not None:
                 have += list(np.asarray(new, dtype=np.float32).reshape(-1, self.Hkv))
-            blk = (self.n_tokens[node] + np.arange(x.shape[0])) // self.scale_block
             assert blk.max() < len(have), "a started block needs a scale"
             sc = np.stack(have)[blk][:, :, None]                       # [n, Hkv, 1] fp32
             inv = (np.float32(1.0) / sc).astype(np.float32)
             codes.append(encode_e4m3((x * inv).astype(np.float32)))
-        self.append(node, codes[0], codes[1], k_scales, v_scales)
+            made.append(new)
+        self.append(node, codes[0], codes[1], made[0], made[1])
         self.last_codes = codes                                        # for byte-level comparison
+        self.last_scales = made
 
     def _dequant(self, node, x, new_scales, which):
         """Multiply codes by the scale of the block (of scale_block tokens of this node)

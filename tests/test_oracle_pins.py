@@ -500,3 +500,61 @@ def test_quantising_append_uses_the_scale_of_the_block_a_token_falls_in():
     got = decode_e4m3(t2.last_codes[0]) * float(s)
     step = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(xv) / float(s), 2.0 ** -6))) - 3), 2.0 ** -9) * float(s)
     assert np.all(np.abs(got - xv) <= step / 2 * (1 + 1e-6))
+
+
+def test_quantising_append_derives_block_scales_from_the_tokens_it_places():
+    from oracle.tree_attention import OracleTree, decode_e4m3
+
+    def bf16_bits(x):
+        return (np.asarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+    t = OracleTree(2, 1, 2, "fp8_e4m3", scale_block=4)
+    (r,) = t.fork(-1, 1)
+    # six tokens: block 0 gets four (K amax 7 -> scale 7 / 448 = 2^-6), block 1 two (K amax 3.5 -> 2^-7)
+    k = np.array([[[1.0, -7.0]], [[0.5, 0.25]], [[3.5, 0.0]], [[-1.75, 7.0]], [[3.5, 1.0]], [[-0.875, 0.4375]]])
+    v = k * 2
+    t.append_quantised(r, bf16_bits(k), bf16_bits(v), derive_scales=True)
+    assert t.last_scales[0].ravel().tolist() == [2.0 ** -6, 2.0 ** -7]
+    assert t.last_scales[1].ravel().tolist() == [2.0 ** -5, 2.0 ** -6]
+    assert t.last_codes[0][1].ravel().tolist() == [0x60, 0x58]            # 0.5 * 64 = 32, 0.25 * 64 = 16
+    assert t.last_codes[0][0, 0, 1] == 0xFE and t.last_codes[0][3, 0, 1] == 0x7E    # -7 and 7 sit at the end of the grid
+    assert np.array_equal(t.last_codes[0], t.last_codes[1])               # V = 2 K, scales doubled too
+    K, _ = t.materialise(r)
+    assert np.array_equal(K, k)                                            # every value is on its block's grid
+    # two more tokens continue block 1 (scale 2^-7, never requantised): 10 saturates at 448 * 2^-7 = 3.5
+    k2 = np.array([[[10.0, 0.4375]], [[-10.0, 1.0]]])
+    t.append_quantised(r, bf16_bits(k2), bf16_bits(k2), derive_scales=True)
+    assert t.last_scales == [None, None]
+    assert t.last_codes[0][:, 0, 0].tolist() == [0x7E, 0xFE]
+    K, _ = t.materialise(r)
+    assert K[6, 0, 0] == 3.5 and K[7, 0, 0] == -3.5 and K[6, 0, 1] == 0.4375
+    # an all-zero block takes the floor scale and stays zero
+    z = np.zeros((4, 1, 2))
+    t.append_quantised(r, bf16_bits(z), bf16_bits(z), derive_scales=True)
+    assert t.last_scales[0].ravel().tolist() == [2.0 ** -40] and not t.last_codes[0].any()
+
+
+def test_quantising_append_agrees_with_the_generators_quantiser():
+    """Two independent implementations of one recipe (the workload generator's, in torch integer
+    arithmetic, and the oracle's table search) give the same codes and scales."""
+    import spex_workloads as sw
+    from oracle.tree_attention import OracleTree
+    rng = np.random.default_rng(9)
+    t = OracleTree(4, 2, 64, "fp8_e4m3", scale_block=16)
+    (r,) = t.fork(-1, 1)
+    filled, prev = 0, None
+    for n in (5, 30, 1, 16, 43):
+        x = torch.from_numpy(rng.normal(size=(n, 2, 64)).astype(np.float32) * 0.7).to(torch.bfloat16)
+        bits = x.view(torch.int16).numpy().view(np.uint16)
+        pk = None if prev is None else prev[0]
+        pv = None if prev is None else prev[1]
+        kc, ks = sw.quantise_pages(x.float(), filled, 16, pk)
+        vc, vs = sw.quantise_pages(-x.float(), filled, 16, pv)
+        t.append_quantised(r, bits, (x.neg()).view(torch.int16).numpy().view(np.uint16), derive_scales=True)
+        assert np.array_equal(t.last_codes[0], kc.numpy()) and np.array_equal(t.last_codes[1], vc.numpy())
+        if ks.shape[0]:
+            assert np.array_equal(t.last_scales[0], ks.numpy()) and np.array_equal(t.last_scales[1], vs.numpy())
+            prev = (ks[-1], vs[-1])
+        filled += n
+        if filled % 16 == 0:
+            prev = None
