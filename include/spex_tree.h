@@ -137,6 +137,17 @@ spex_status_t spex_tree_append_step(spex_tree_t *tree, spex_node_t node, int32_t
                                     const void *k, const void *v, const float *k_scales,
                                     const float *v_scales, void *hip_stream);
 /*
+ * The same append with the cache quantised on the fly (fp8 pools only, else SPEX_ERR_UNSUPPORTED):
+ * k, v are DEVICE [n_tokens][num_kv_heads][head_dim] in bf16 with finite values.  For every page
+ * the append starts, the scatter kernel first takes amax = the largest magnitude among the tokens
+ * this append puts into that page, per kv head and separately for K and V, and sets the page's
+ * scale = max(amax / 448, 2^-40); tokens that continue a partially filled page use the scale the
+ * page already has (never requantised; they saturate).  code = e4m3fn(x * (1 / scale)), division,
+ * reciprocal and product in fp32, round to nearest even, saturating at +-448.
+ */
+spex_status_t spex_tree_append_step_quantize(spex_tree_t *tree, spex_node_t node, int32_t n_tokens,
+                                             const void *k, const void *v, void *hip_stream);
+/*
  * The decode iteration between two steps (Sec. 3.1: a step is tens to hundreds of tokens, generated
  * one at a time; Alg. 2: all live branches are generated concurrently): append ONE token to each
  * of n_nodes distinct nodes without live children, with one kernel launch.

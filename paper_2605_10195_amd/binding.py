@@ -81,7 +81,7 @@ EXPORTS = [
     "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_decode_attention_masked", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
-    "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens", "spex_tree_append_tokens_quantize",
+    "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens", "spex_tree_append_tokens_quantize", "spex_tree_append_step_quantize",
 ]
 # spex_sched.h: host-side scheduling primitives
 SCHED_EXPORTS = [
@@ -112,6 +112,7 @@ def _load():
     lib.spex_tree_destroy.restype = None
     lib.spex_tree_fork.argtypes = [vp, i32, i32, _I32P]
     lib.spex_tree_append_step.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.spex_tree_append_step_quantize.argtypes = [vp, i32, i32, vp, vp, vp]
     lib.spex_tree_append_new_pages.argtypes = [vp, i32, i32, _I32P]
     lib.spex_tree_append_tokens.argtypes = [vp, _I32P, i32, vp, vp, vp, vp, vp]
     lib.spex_tree_append_tokens_quantize.argtypes = [vp, _I32P, i32, vp, vp, vp, vp, vp]
@@ -246,9 +247,15 @@ class SpexTree:
 
     def append_step(self, node: int, k: Optional[torch.Tensor], v: Optional[torch.Tensor],
                     k_scales: Optional[torch.Tensor] = None, v_scales: Optional[torch.Tensor] = None,
-                    n_tokens: Optional[int] = None) -> None:
+                    n_tokens: Optional[int] = None, quantize: bool = False) -> None:
         if k is None:
             _check(lib.spex_tree_append_step(self._h, node, int(n_tokens), None, None, None, None, None))
+            return
+        if quantize:                     # bf16 in, e4m3 codes and page scales made by the library
+            assert k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16 and k_scales is None
+            assert k.is_contiguous() and v.is_contiguous() and k.device.type == self.device.type
+            assert tuple(k.shape) == (k.shape[0], self.Hkv, self.D) and tuple(v.shape) == tuple(k.shape)
+            _check(lib.spex_tree_append_step_quantize(self._h, node, k.shape[0], _dev(k), _dev(v), _stream()))
             return
         want = _TORCH_KV[self.kv_dtype]
         assert k.dtype == want and v.dtype == want, (k.dtype, want)

@@ -428,10 +428,11 @@ spex_status_t spex_tree_append_new_pages(const spex_tree_t *t, spex_node_t node,
   return SPEX_OK;
 }
 
-spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_tokens,
-                                    const void *k, const void *v, const float *k_scales,
-                                    const float *v_scales, void *hip_stream) {
+static spex_status_t append_step_impl(spex_tree_t *t, spex_node_t node, int32_t n_tokens, const void *k,
+                                      const void *v, const float *k_scales, const float *v_scales,
+                                      void *hip_stream, bool quantise) {
   if (!t || n_tokens < 0 || ((k == nullptr) != (v == nullptr))) return SPEX_ERR_INVALID_ARG;
+  if (quantise && t->cfg.kv_dtype != SPEX_FP8_E4M3) return SPEX_ERR_UNSUPPORTED;
   if (!t->pt->valid(node)) return SPEX_ERR_BAD_NODE;
   if (t->pt->node(node).n_live_children > 0) return SPEX_ERR_NOT_LEAF;
   if (k && !t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
@@ -440,7 +441,7 @@ spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_
   const int32_t old_tokens = t->pt->node(node).n_tokens;
   if (static_cast<int64_t>(old_tokens) + n_tokens > INT32_MAX / 2) return SPEX_ERR_UNSUPPORTED;
   const int32_t need = t->pt->new_pages_needed(node, n_tokens);
-  if (k && t->cfg.kv_dtype == SPEX_FP8_E4M3 && need > 0 && (!k_scales || !v_scales))
+  if (k && !quantise && t->cfg.kv_dtype == SPEX_FP8_E4M3 && need > 0 && (!k_scales || !v_scales))
     return SPEX_ERR_INVALID_ARG;
   int32_t first_new = 0;
   if (!t->pt->append(node, n_tokens, &first_new)) return SPEX_ERR_OOM_PAGES;
@@ -452,7 +453,7 @@ spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_
   const int32_t page_lo = old_tokens / P;  // first page written (continuing or new)
   const int32_t page_hi = (new_total + P - 1) / P;
   const size_t tok_bytes = static_cast<size_t>(t->cfg.num_kv_heads) * t->cfg.head_dim *
-                           elem_size(t->cfg.kv_dtype);
+                           (quantise ? sizeof(uint16_t) : elem_size(t->cfg.kv_dtype));
   for (int32_t pa = page_lo; pa < page_hi; pa += spex::kMaxPagesPerScatter) {
     const int32_t pb = pa + spex::kMaxPagesPerScatter < page_hi ? pa + spex::kMaxPagesPerScatter : page_hi;
     spex::ScatterArgs a{};
@@ -474,9 +475,21 @@ spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_
       a.v_scale_src = v_scales + static_cast<size_t>(first_new_in_launch - first_new) * t->cfg.num_kv_heads;
     }
     for (int32_t i = 0; i < a.n_pages; ++i) a.page_ids[i] = nd.pages[pa + i];
-    HIP_TRY(spex::launch_scatter(t->shape, a, stream));
+    HIP_TRY(quantise ? spex::launch_scatter_quantise(t->shape, a, stream)
+                     : spex::launch_scatter(t->shape, a, stream));
   }
   return SPEX_OK;
+}
+
+spex_status_t spex_tree_append_step(spex_tree_t *t, spex_node_t node, int32_t n_tokens,
+                                    const void *k, const void *v, const float *k_scales,
+                                    const float *v_scales, void *hip_stream) {
+  return append_step_impl(t, node, n_tokens, k, v, k_scales, v_scales, hip_stream, false);
+}
+
+spex_status_t spex_tree_append_step_quantize(spex_tree_t *t, spex_node_t node, int32_t n_tokens,
+                                             const void *k, const void *v, void *hip_stream) {
+  return append_step_impl(t, node, n_tokens, k, v, nullptr, nullptr, hip_stream, true);
 }
 
 static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes, int32_t n_nodes,

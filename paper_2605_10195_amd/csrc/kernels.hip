@@ -1515,6 +1515,71 @@ __device__ __forceinline__ uint32_t encode_e4m3(float y) {
   return code | sign;
 }
 
+// A run of bf16 tokens of one node into an fp8 pool, quantised on the way: one workgroup per
+// (page, kv head).  For a page this append starts, the workgroup first takes the largest magnitude
+// of the tokens it puts there, separately for K and V, and sets scale = max(amax / 448, 2^-40);
+// a page that was partially filled before keeps its scale.  Then code = e4m3(x * (1 / scale)).
+// Unused slots of a started page are zeroed.  Inputs must be finite.
+template <int LAYOUT>
+__global__ __launch_bounds__(256) void spex_scatter_quant_kernel(ScatterArgs a, Shape sh) {
+  const int D = sh.D, P = sh.P, H = sh.Hkv;
+  const int g = blockIdx.x % H, pi = blockIdx.x / H;
+  const bool is_new = pi > 0 || a.first_page_is_new;
+  const int page = a.page_ids[pi];
+  const int sidx = page * H + g;
+  const uint16_t *ksrc = static_cast<const uint16_t *>(a.k_src), *vsrc = static_cast<const uint16_t *>(a.v_src);
+  auto widen = [](uint16_t b) { return __builtin_bit_cast(float, static_cast<uint32_t>(b) << 16); };
+  __shared__ float red[2][4];
+  float ks, vs;
+  if (is_new) {  // uniform over the workgroup
+    float ka = 0.f, va = 0.f;
+    for (int e = threadIdx.x; e < P * D; e += 256) {
+      const int tok = pi * P + e / D - a.first_slot;
+      if (tok >= 0 && tok < a.n_tokens) {
+        const int64_t src = (static_cast<int64_t>(tok) * H + g) * D + e % D;
+        ka = fmaxf(ka, __builtin_fabsf(widen(ksrc[src])));
+        va = fmaxf(va, __builtin_fabsf(widen(vsrc[src])));
+      }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      ka = fmaxf(ka, __shfl_xor(ka, o));
+      va = fmaxf(va, __shfl_xor(va, o));
+    }
+    if ((threadIdx.x & 63) == 0) {
+      red[0][threadIdx.x >> 6] = ka;
+      red[1][threadIdx.x >> 6] = va;
+    }
+    __syncthreads();
+    ka = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+    va = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+    ks = fmaxf(ka / 448.0f, 0x1p-40f);
+    vs = fmaxf(va / 448.0f, 0x1p-40f);
+    if (threadIdx.x == 0) {
+      a.k_scale[sidx] = ks;
+      a.v_scale[sidx] = vs;
+    }
+  } else {
+    ks = a.k_scale[sidx];
+    vs = a.v_scale[sidx];
+  }
+  const float kinv = 1.0f / ks, vinv = 1.0f / vs;
+  const int64_t tile = (static_cast<int64_t>(page) * sh.page_tiles + g) * (static_cast<int64_t>(P) * D);
+  uint8_t *kp = static_cast<uint8_t *>(a.k_pool) + tile, *vp = static_cast<uint8_t *>(a.v_pool) + tile;
+  for (int e = threadIdx.x; e < P * D; e += 256) {
+    const int slot = e / D, d = e % D;
+    const int tok = pi * P + slot - a.first_slot;
+    if (tok >= 0 && tok < a.n_tokens) {
+      const int64_t src = (static_cast<int64_t>(tok) * H + g) * D + d;
+      kp[k_offset<kFP8, LAYOUT>(slot, d, D)] = static_cast<uint8_t>(encode_e4m3(widen(ksrc[src]) * kinv));
+      vp[v_offset<kFP8, LAYOUT>(slot, d, D)] = static_cast<uint8_t>(encode_e4m3(widen(vsrc[src]) * vinv));
+    } else if (tok >= a.n_tokens && is_new) {
+      kp[k_offset<kFP8, LAYOUT>(slot, d, D)] = 0;
+      vp[v_offset<kFP8, LAYOUT>(slot, d, D)] = 0;
+    }
+  }
+}
+
 // One appended token per node: thread = (node, kv head, dim).  Writes the token's K and V element
 // into its slot; where the token starts a page it also zeroes the page's other slots (so that
 // nothing stale can be read from a partial page) and stores the page's fp8 scales.  The first
@@ -1730,6 +1795,17 @@ static hipError_t scatter_layout(const Shape &sh, const ScatterArgs &a, hipStrea
     hipLaunchKernelGGL((spex_scatter_kv_kernel<KV, kMfmaTiled>), grid, block, 0, stream, a, sh);
   else
     hipLaunchKernelGGL((spex_scatter_kv_kernel<KV, kRowMajor>), grid, block, 0, stream, a, sh);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_quantise(const Shape &sh, const ScatterArgs &a, hipStream_t stream) {
+  if (a.n_pages <= 0) return hipSuccess;
+  if (sh.kv_dtype != kFP8) return hipErrorInvalidValue;
+  const dim3 grid(static_cast<unsigned>(a.n_pages * sh.Hkv)), block(256);
+  if (sh.layout == kMfmaTiled)
+    hipLaunchKernelGGL((spex_scatter_quant_kernel<kMfmaTiled>), grid, block, 0, stream, a, sh);
+  else
+    hipLaunchKernelGGL((spex_scatter_quant_kernel<kRowMajor>), grid, block, 0, stream, a, sh);
   return hipGetLastError();
 }
 

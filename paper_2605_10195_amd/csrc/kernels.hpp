@@ -114,6 +114,8 @@ hipError_t launch_attention(const Shape &sh, const AttnArgs &a, bool prefix, int
                             bool force_generic, hipStream_t stream);
 hipError_t launch_merge(const Shape &sh, const MergeArgs &a, hipStream_t stream);
 hipError_t launch_scatter(const Shape &sh, const ScatterArgs &a, hipStream_t stream);
+// fp8 pools: k_src / v_src hold bf16 values; page scales are computed (started pages) or reused.
+hipError_t launch_scatter_quantise(const Shape &sh, const ScatterArgs &a, hipStream_t stream);
 hipError_t launch_gather(const Shape &sh, const GatherArgs &a, hipStream_t stream);
 hipError_t launch_append_tokens(const Shape &sh, const AppendTokensArgs &a, hipStream_t stream);
 bool has_mfma_kernel(const Shape &sh);

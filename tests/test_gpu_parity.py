@@ -843,3 +843,60 @@ def test_mcts_search_attention_matches_oracle_while_the_tree_changes(kv_dtype, h
     assert len(checked) >= 5 and stats["spec_expansions"] > 0 and stats["spec_hits"] > 0
     assert tree.stats()[:2] == (0, 0)
     tree.close()
+
+
+@pytest.mark.parametrize("heads", [(10, 2, 128), (8, 8, 64), (4, 2, 96)])
+def test_quantising_step_append_gives_the_oracle_codes_scales_and_attention(heads):
+    """spex_tree_append_step_quantize: runs of bf16 tokens in, page scales and e4m3 codes made by
+    the scatter kernel.  Codes and scales read back equal the oracle's bit for bit, for appends
+    that start pages, continue partial ones, and span many pages in several launches."""
+    import paper_2605_10195_amd as spex
+    from oracle.adapters import OracleSink, queries_fp64
+    Hq, Hkv, D = heads
+    tree = spex.SpexTree(Hq, Hkv, D, 16, "bf16", "fp8_e4m3", num_pages=400, device="cuda", pool_fill=0xFF)
+    sink = OracleSink(Hq, Hkv, D, "fp8_e4m3", 16)
+    rng = np.random.default_rng(4)
+    (r,) = tree.fork(-1, 1)
+    sink.fork(-1, 1)
+    want_k, want_v, want_ks = [], [], []
+    lengths = [5, 30, 1, 16, 43, 11, 2200, 7]            # 2200 tokens: 138 pages, several scatter launches
+    for i, n in enumerate(lengths):
+        scale = [0.3, 2.0, 0.01, 1.0, 0.5, 40.0, 1.0, 1e-3][i]
+        x = sw.normal_values(9, 1, 1000 + i, torch.arange(n), Hkv, D, 1.0, "cuda") * scale
+        y = sw.normal_values(9, 2, 1000 + i, torch.arange(n), Hkv, D, 1.0, "cuda") * scale
+        k, v = x.to(torch.bfloat16).contiguous(), y.to(torch.bfloat16).contiguous()
+        tree.append_step(r, k, v, quantize=True)
+        sink.append_quantised(0, k, v, derive_scales=True)
+        want_k.append(sink.tree.last_codes[0])
+        want_v.append(sink.tree.last_codes[1])
+    total = sum(lengths)
+    kc, vc, ks, vs = tree.gather_kv(r, 0, total)
+    assert np.array_equal(kc.cpu().view(torch.uint8).numpy(), np.concatenate(want_k))
+    assert np.array_equal(vc.cpu().view(torch.uint8).numpy(), np.concatenate(want_v))
+    ref_ks = np.stack(sink.tree._scales[0][0]).astype(np.float32)            # [pages, Hkv]
+    ref_vs = np.stack(sink.tree._scales[0][1]).astype(np.float32)
+    assert np.array_equal(ks.cpu().numpy(), np.repeat(ref_ks, 16, axis=0)[:total])
+    assert np.array_equal(vs.cpu().numpy(), np.repeat(ref_vs, 16, axis=0)[:total])
+    # children forked below see it; decode tokens continue with the quantising token append
+    a, b = tree.fork(r, 2)
+    sink.fork(0, 2)
+    for u in (a, b):
+        x = (sw.normal_values(9, 1, 2000 + u, torch.arange(21), Hkv, D, 0.5, "cuda")).to(torch.bfloat16)
+        tree.append_step(u, x.contiguous(), x.neg().contiguous(), quantize=True)
+        sink.append_quantised(u, x, x.neg(), derive_scales=True)
+    q = sw.normal_values(9, 3, 77, torch.arange(5), Hq, D, 0.5, "cuda").to(torch.bfloat16).contiguous()
+    out, lse = tree.decode_attention([a, b], [2, 3], q, D ** -0.5)
+    ref = sink.tree.attention([a, b], [2, 3], queries_fp64(q), D ** -0.5)
+    got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+    # the absolute bound is stated for |V| <= 2.45 (P is rounded to 11 bits): scale it with this test's values
+    vmax = max(np.abs(sink.tree.materialise(u)[1]).max() for u in (a, b))
+    assert np.max(np.abs(got[0] - ref[0])) <= 2e-3 * vmax / 2.45 and np.max(np.abs(got[1] - ref[1])) <= 2e-3
+    assert np.linalg.norm(got[0] - ref[0]) / np.linalg.norm(ref[0]) <= 1e-3
+    tree.close()
+    bf = spex.SpexTree(8, 2, 64, 16, "bf16", "bf16", num_pages=4, device="cuda")
+    (r,) = bf.fork(-1, 1)
+    x = torch.zeros((3, 2, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(spex.SpexError) as e:
+        bf.append_step(r, x, x, quantize=True)
+    assert e.value.name == "UNSUPPORTED" and bf.node_info(r)["n_tokens"] == 0
+    bf.close()
