@@ -307,7 +307,10 @@ def test_walk_lists_random_traces(seed):
 
 @pytest.mark.parametrize("wl", [
     sw.bfs_tot(n_queries=3), sw.mcts_skewed(n_queries=6), sw.spec_at_scale(n_queries=4),
-    sw.tot_with_drafts(n_queries=3)], ids=lambda w: w.name)
+    sw.tot_with_drafts(n_queries=3),
+    sw.bfs_tot(n_queries=1, prompt=9000, step=1100, width=4, keep=2, depth=2, heads=(8, 2, 128)),   # few long paths
+    sw.mcts_skewed(n_queries=2, prompt=(3000, 6000), step=(300, 700), max_leaves=6)],
+    ids=lambda w: f"{w.name}_{w.n_trees}_{len(w.leaves)}")
 def test_walk_lists_config_shapes(wl):
     n_pages = wl.peak_pages()
     tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
