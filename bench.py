@@ -176,7 +176,8 @@ def run_dynamic(args):
     n_pages = 65536
     order = np.random.default_rng(1000).permutation(n_pages).tolist()
     tree = spex.SpexTree(32, 8, 128, 16, "bf16", "bf16", num_pages=n_pages, device=dev, free_order=order,
-                         interleave_kv=True, kernel_mode=args.kernel_mode)
+                         interleave_kv=True, kernel_mode=args.kernel_mode,
+                         walk_row_tiles=args.walk_row_tiles, walk_waves=args.walk_waves)
     b_tok = 2.0 * 8 * 128 * 2
     acc = dict(kv_tokens=0, peak_pages=0)
 

@@ -214,7 +214,8 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *     registers, only the output is written.  Needs MFMA-tiled pools and Hq / Hkv <= 64 (one
  *     query token's rows fit a wavefront; a requested node with more rows than a wavefront takes
  *     is cut into pieces of whole query tokens).  Chosen automatically when it yields >= 128
- *     workgroups or when no wavefront has more than 64 two-page blocks to walk;
+ *     workgroups, or when no wavefront has more two-page blocks to walk than 20 (up to 32
+ *     workgroups) rising to 87 (127 workgroups): 20 + (workgroups - 32) * 7 / 10;
  *   shared-prefix + suffix + merge: every shared node is read once for all rows below it, private
  *     suffixes are split for parallelism, partial softmax states go through memory.  Any shape.
  * Consecutive calls on one handle must use one stream or be separated by a synchronisation,

@@ -643,9 +643,12 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
   const spex_status_t st = make_plan(t, leaves, q_lens, draft_masks, n_leaves, &plan_state);
   if (st != SPEX_OK) return st;
   spex::Plan &pl = t->plan;
-  // Which kernels: the tree-walk kernel when its lists exist and fill the chip (or every work item
-  // is short anyway); else shared-prefix + suffix + merge, which can split long paths.  Only the
-  // lists of the chosen kernels are built.
+  // Which kernels: the tree-walk kernel when its lists exist and fill the chip, or when its
+  // longest workgroup is short; else shared-prefix + suffix + merge, which can split long paths.
+  // A tree-walk workgroup takes about 12 us + 0.8 us per two-page block on its path whatever else
+  // runs, the three split-path launches take 26-45 us for up to 32 work items of this size and
+  // grow with the item count: measured crossing points were 20 blocks at 8-32 items, 40 at 64
+  // and 65 at 96 (bf16, 32 / 8 heads of 128).  Only the lists of the chosen kernels are built.
   const bool want_walk = (t->kernel_mode == 0 || t->kernel_mode == 3) && spex::has_mfma_kernel(t->shape);
   if (want_walk) t->planner.ensure_walk(*t->pt, &pl);
   const bool tree_masks = draft_masks != nullptr;
@@ -654,8 +657,9 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
   const bool walk_possible = want_walk && pl.walk_ok && (!tree_masks || pl.walk_waves == 4);
   if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
   if (t->kernel_mode == 2 && tree_masks && spex::has_mfma_kernel(t->shape)) return SPEX_ERR_UNSUPPORTED;
+  const int32_t short_walk = pl.walk_real_items <= 32 ? 20 : 20 + (pl.walk_real_items - 32) * 7 / 10;
   const bool use_walk = walk_possible && (t->kernel_mode == 3 || tree_masks || pl.walk_real_items >= 128 ||
-                                          pl.walk_max_item_blocks <= 64);
+                                          pl.walk_max_item_blocks <= short_walk);
   if (!use_walk) {
     const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &pl));
     if (ss != SPEX_OK) return ss;
