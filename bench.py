@@ -192,7 +192,7 @@ def run_dynamic(args):
     driver.run(args.warmup)               # starts the search and runs the warm-up iterations
     torch.cuda.synchronize()
     base = dict(driver.stats)
-    states0, kv0 = dict(sink.plan_states), acc["kv_tokens"]
+    states0, kv0, calls0 = dict(sink.plan_states), acc["kv_tokens"], dict(sink.call_seconds)
     tree.set_profiling(True)
     prof_ms, done = 0.0, 0
     t0 = time.perf_counter()
@@ -240,6 +240,8 @@ def run_dynamic(args):
                      "note": "kernel time from HIP events around every attention launch; bytes = "
                              "unique KV bytes of each launch's requested paths, summed"},
         "kernel_ms_share_of_wall": prof_ms / (wall * 1e3),
+        "host_ms_per_step_in_library_calls": {k: (sink.call_seconds[k] - calls0[k]) / max(done, 1) * 1e3
+                                              for k in sink.call_seconds},
         "cpu_baseline": None,
     }
     print(json.dumps(result, default=float))

@@ -27,6 +27,7 @@ sink:   fork(parent, n) -> [ids];  prune(node);  append_prompt(node, n_tokens, k
 
 from __future__ import annotations
 
+import time
 from dataclasses import dataclass, field
 from typing import Dict, List
 
@@ -338,19 +339,29 @@ class LibrarySink:
         self.with_values = with_values
         self.last = None                          # (nodes, q, out, lse) of the latest attention call
         self.plan_states = {0: 0, 1: 0, 2: 0}
+        # host seconds spent inside the tree object's calls, by kind (what the harness itself
+        # costs -- drawing values, the search bookkeeping -- is the rest of the wall time)
+        self.call_seconds = {"fork_prune": 0.0, "append": 0.0, "attention": 0.0}
+
+    def _timed(self, kind, fn, *args, **kwargs):
+        t0 = time.perf_counter()
+        try:
+            return fn(*args, **kwargs)
+        finally:
+            self.call_seconds[kind] += time.perf_counter() - t0
 
     def fork(self, parent, n):
-        return self.tree.fork(parent, n)
+        return self._timed("fork_prune", self.tree.fork, parent, n)
 
     def prune(self, node):
-        self.tree.prune(node)
+        self._timed("fork_prune", self.tree.prune, node)
 
     def path_kv_bytes(self, node):
         return self._path_bytes(self.tree, node)
 
     def append_prompt(self, node, n, key):
         if not self.with_values:
-            self.tree.append_step(node, None, None, n_tokens=n)
+            self._timed("append", self.tree.append_step, node, None, None, n_tokens=n)
             return
         import torch
         from .quant import quantise_pages
@@ -358,22 +369,24 @@ class LibrarySink:
         if self.shape.kv_dtype == "fp8_e4m3":
             kc, ks = quantise_pages(k, 0, self.shape.page_size, None)
             vc, vs = quantise_pages(v, 0, self.shape.page_size, None)
-            self.tree.append_step(node, kc, vc, ks, vs)
+            self._timed("append", self.tree.append_step, node, kc, vc, ks, vs)
         else:
-            self.tree.append_step(node, k.to(torch.bfloat16).contiguous(), v.to(torch.bfloat16).contiguous())
+            self._timed("append", self.tree.append_step, node, k.to(torch.bfloat16).contiguous(),
+                        v.to(torch.bfloat16).contiguous())
 
     def append_tokens(self, nodes, keys, tok):
         if not self.with_values:
-            self.tree.append_tokens(nodes, None, None)
+            self._timed("append", self.tree.append_tokens, nodes, None, None)
             return
         import torch
         k, v = self.values.kv_tokens(keys, tok)
         if self.shape.kv_dtype == "fp8_e4m3":
             s = torch.full((len(nodes), self.shape.num_kv_heads), self.shape.fp8_scale, dtype=torch.float32,
                            device=k.device)
-            self.tree.append_tokens(nodes, k.contiguous(), v.contiguous(), s, s, quantize=True)
+            self._timed("append", self.tree.append_tokens, nodes, k.contiguous(), v.contiguous(), s, s,
+                        quantize=True)
         else:
-            self.tree.append_tokens(nodes, k.contiguous(), v.contiguous())
+            self._timed("append", self.tree.append_tokens, nodes, k.contiguous(), v.contiguous())
         self._last_tok = (list(keys), list(tok))
 
     def attend(self, nodes, iteration):
@@ -381,7 +394,7 @@ class LibrarySink:
             return
         keys, tok = self._last_tok
         q = self.values.queries(keys, tok)
-        out, lse = self.tree.decode_attention(nodes, None, q, self.sm_scale)
+        out, lse = self._timed("attention", self.tree.decode_attention, nodes, None, q, self.sm_scale)
         self.plan_states[self.tree.last_launch_info()["plan_rebuilt"]] += 1
         self.last = (list(nodes), q, out, lse)
 
