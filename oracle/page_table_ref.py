@@ -77,7 +77,12 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
     number of leading drafts that all of the request's queries see; a node whose
     range touches two wavefronts is shared, else private to wavefront lo // C;
   * blocks of a row block: shared nodes first, then the private nodes of
-    wavefront 0..NW-1, a node's pages two at a time; record (page a, pos_a << 7 |
+    wavefront 0..NW-1, each wavefront's blocks followed by room for blocks that
+    later appends start: two all-zero records per private node of the wavefront
+    that a request of the row block asks for and that has no live children; the
+    row block and the work items hold count | (count + room) << 16 per
+    wavefront (no lists if that exceeds 16 bits); a node's pages two at a time;
+    record (page a, pos_a << 7 |
     valid_a, page b or a again, pos_b << 7 | valid_b or 0, lo | hi << 16, flag, 0,
     0); flag bit 0 = a page partial or missing, or minlim < position after the
     block; flag bit 1 = the node lies on paths of more than one row block;
@@ -431,6 +436,8 @@ class PageTableRef:
                             ((pos_b << 7) | vb) if has_b else 0, lo | (hi << 16), int(masked) | multi, 0, 0])
             return out
 
+        overflow: List[int] = []
+
         def flush(root, placed, qt_first, qt_count):
             if not placed:
                 return
@@ -448,14 +455,21 @@ class PageTableRef:
             shared = [b for w, (lo, hi, ml) in nodes.items() if lo // C != (hi - 1) // C
                       for b in node_blocks(w, lo, hi, ml)]
             blocks.extend(shared)
-            n_priv = []
+            n_priv, packed = [], []
+            asked = {leaves[i] for i, _, _ in placed}
             for wv in range(NW):
-                mine = [b for w, (lo, hi, ml) in nodes.items()
-                        if lo // C == (hi - 1) // C and lo // C == wv for b in node_blocks(w, lo, hi, ml)]
+                own = [w for w, (lo, hi, ml) in nodes.items() if lo // C == (hi - 1) // C and lo // C == wv]
+                mine = [b for w in own for b in node_blocks(w, *nodes[w])]
+                # room for blocks that appends will start: two records per requested childless node
+                room = 2 * sum(1 for w in own if w in asked and not self.has_live_children(w))
+                if len(mine) + room > 0xffff:
+                    overflow.append(1)
                 blocks.extend(mine)
+                blocks.extend([[0] * 8 for _ in range(room)])
                 n_priv.append(len(mine))
+                packed.append(len(mine) | ((len(mine) + room) << 16))
             rbs_of_root[root].append(len(row_blocks))
-            row_blocks.append([root, first, len(shared)] + n_priv + qt_first + qt_count)
+            row_blocks.append([root, first, len(shared)] + packed + qt_first + qt_count)
             rb_total.append(len(shared) + sum(n_priv))
 
         cur_root, wave, used = None, 0, 0
@@ -480,6 +494,8 @@ class PageTableRef:
             placed.append((i, wave * C + used, n * G))
             used += n * G
         flush(cur_root, placed, qt_first, qt_count)
+        if overflow:
+            return dict(available=0, row_tiles=0, waves=0, row_blocks=[], blocks=[], qt=[], items=[])
 
         root_blocks = {r: sum(rb_total[b] for b in rbs_of_root[r]) for r in roots}
         root_order = sorted(roots, key=lambda r: -root_blocks[r])      # stable

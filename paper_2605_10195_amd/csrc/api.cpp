@@ -192,7 +192,7 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
 
 constexpr int kPlanArrays = 15;
 // Index, in the device blob's array list, of the arrays a length patch can touch.
-constexpr int kPatchTarget[4] = {2 /*pg_rec*/, 3 /*qt_rec*/, 12 /*walk_blocks*/, 13 /*walk_qt*/};
+constexpr int kPatchTarget[5] = {2 /*pg_rec*/, 3 /*qt_rec*/, 12 /*walk_blocks*/, 13 /*walk_qt*/, 11 /*walk_items*/};
 
 spex_status_t stage_reserve(spex_tree *t, size_t bytes) {
   t->stage_cur ^= 1;
@@ -518,10 +518,11 @@ static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes
     return SPEX_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   // Staging holds the destination list and, behind it, the length patches of the cached plan that
-  // this launch applies as well.  Room for 16 patches per node is reserved before anything
-  // changes; if a plan needs more, its patches wait for the next decode_attention call instead.
+  // this launch applies as well.  Room for 32 patches per node is reserved before anything
+  // changes (a block started in the tree-walk lists takes 8 + one per kv head, each query token
+  // one or two); if a plan needs more, its patches wait for the next decode_attention call instead.
   const size_t dst_ints = static_cast<size_t>(n_nodes) * 2;
-  const size_t patch_room = static_cast<size_t>(n_nodes) * 16;  // {index, value} pairs
+  const size_t patch_room = static_cast<size_t>(n_nodes) * 32;  // {index, value} pairs
   const size_t bytes_max = (dst_ints + 2 * patch_room) * sizeof(int32_t);
   int32_t *h = nullptr;
   if (k) {

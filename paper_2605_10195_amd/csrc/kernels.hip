@@ -1031,13 +1031,16 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   const int g = sload(p.items, ir + 0);
   const int blk_begin = sload(p.items, ir + 1);
   const int n_shared = sload(p.items, ir + 2);
+  // per wavefront: private blocks | room << 16; a wavefront's records are followed by the unused
+  // part of its room, so n_all spans records that no wavefront walks
   int n_all = n_shared, n_priv = 0, priv_begin = blk_begin + n_shared;
 #pragma unroll
   for (int v = 0; v < NW; ++v) {
-    const int npv = sload(p.items, ir + 3 + v);
-    n_all += npv;
+    const uint32_t packed = static_cast<uint32_t>(sload(p.items, ir + 3 + v));
+    const int npv = static_cast<int>(packed & 0xffffu), room = static_cast<int>(packed >> 16);
+    n_all += room;
     n_priv = v == w ? npv : n_priv;
-    priv_begin += v < w ? npv : 0;
+    priv_begin += v < w ? room : 0;
   }
   if (n_all == 0) return;  // padding item (whole workgroup)
   const bool rec_in_lds = n_all <= kWalkRecCap;  // uniform over the workgroup

@@ -23,6 +23,7 @@ int32_t PageTable::fork(int32_t parent, int32_t n) {
   live_nodes_ += n;
   ++version_;
   ++structure_version_;
+  ++topology_version_;
   return first;
 }
 
@@ -67,6 +68,7 @@ void PageTable::prune(int32_t u) {
   }
   ++version_;
   ++structure_version_;
+  ++topology_version_;
 }
 
 }  // namespace spex

@@ -36,6 +36,8 @@ class PageTable {
   // Bumped by fork, prune and every append that starts a new page; appends that only fill up a
   // node's last page leave it unchanged.
   uint64_t structure_version() const { return structure_version_; }
+  // Bumped by fork and prune only: which nodes exist and who their parents are.
+  uint64_t topology_version() const { return topology_version_; }
 
   // Creates n children under parent (kNoNode: roots); returns the first new id.
   int32_t fork(int32_t parent, int32_t n);
@@ -68,6 +70,7 @@ class PageTable {
   int64_t live_nodes_ = 0;
   uint64_t version_ = 1;       // bumped by every mutation; the planner's cache key
   uint64_t structure_version_ = 1;
+  uint64_t topology_version_ = 1;
 };
 
 }  // namespace spex

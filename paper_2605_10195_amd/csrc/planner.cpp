@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <limits>
 #include <numeric>
+#include <unordered_set>
 #include <utility>
 
 namespace spex {
@@ -37,6 +38,7 @@ PlanError Planner::begin(const PageTable &pt, const int32_t *leaves, const int32
   if (q_lens) pl.req_q_lens.assign(q_lens, q_lens + n_leaves);
   pl.table_version = pt.version();
   pl.structure_version = pt.structure_version();
+  pl.topology_version = pt.topology_version();
   pl.req_prefix_chunk = prefix_chunk_pages;
   pl.req_suffix_chunk = suffix_chunk_pages;
   pl.req_walk_row_tiles = walk_row_tiles;
@@ -426,8 +428,11 @@ PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
 //    does not see (T - q_len + 1 for the causal chain).  A node whose range touches two
 //    wavefronts is shared, else it is private to wavefront lo / C.
 //  * blocks of a row block: its shared nodes in encounter order, then the private nodes of
-//    wavefront 0, 1, ..; a node's pages two at a time (the last block of an odd run has no
-//    page b).  Flag bit 0: page a or b partial, or no page b, or minlim smaller than the path
+//    wavefront 0, 1, .., each wavefront's blocks followed by room for blocks that appends will
+//    start: two all-zero records for every private node of the wavefront that a request of the
+//    row block asks for and that has no live children; the row block and the work items hold
+//    count | (count + room) << 16 per wavefront.  A node's pages two at a time (the last block
+//    of an odd run has no page b).  Flag bit 0: page a or b partial, or no page b, or minlim smaller than the path
 //    position after the block's last token.  Flag bit 1: the node lies on paths of more than one
 //    row block (its pages are fetched again by another workgroup and are worth keeping cached).
 //  * launch order: roots by descending number of blocks in their row blocks (stable).  With
@@ -509,6 +514,11 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   }
   pl.walk_row_tiles = ntw;
   pl.req_walk_qt.assign(n_leaves, -1);
+  pl.req_walk_home.assign(n_leaves, -2);
+  pl.req_pages.resize(n_leaves);
+  for (int32_t i = 0; i < n_leaves; ++i)
+    pl.req_pages[i] = static_cast<int32_t>(pt.node(pl.req_leaves[i]).pages.size());
+  bool room_overflow = false;
   const int32_t C = 16 * ntw;
   // Measured on MI355X, two workgroups of 4 wavefronts per compute unit beat one of 8 on every
   // workload tried (the barrier of the shared phase then stalls only half of the unit), so 4 is
@@ -640,27 +650,41 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     }
     rb_rec[1] = static_cast<int32_t>(pl.walk_blocks.size() / Plan::kBlockInts);
     int64_t total = 0;
-    auto note_last = [&](const NodeRange &nr) {  // requests of this row block that asked for nr.node
+    const int32_t rb_index = static_cast<int32_t>(pl.walk_rb.size() / rb_ints);
+    // requests of this row block that asked for nr.node; home: the wavefront whose private list
+    // holds the node (-1: a shared node).  Returns whether any request asked for it.
+    auto note_last = [&](const NodeRange &nr, int32_t home) {
+      bool asked = false;
       for (const Placed &pc : cur)
-        if (pl.req_leaves[pc.req] == nr.node &&
-            (last_blks.empty() || last_blks.back() != std::make_pair(pc.req, last_blk_of_node)))
-          last_blks.emplace_back(pc.req, last_blk_of_node);
+        if (pl.req_leaves[pc.req] == nr.node) {
+          asked = true;
+          if (last_blks.empty() || last_blks.back() != std::make_pair(pc.req, last_blk_of_node)) {
+            last_blks.emplace_back(pc.req, last_blk_of_node);
+            int32_t &h = pl.req_walk_home[pc.req];
+            h = (h == -2 && home >= 0) ? rb_index * NW + home : -1;
+          }
+        }
+      return asked;
     };
     for (const NodeRange &nr : nodes)
       if (nr.lo / C != (nr.hi - 1) / C) {
         rb_rec[2] += emit_node(nr);
-        note_last(nr);
+        note_last(nr, -1);
       }
     total += rb_rec[2];
     int32_t longest_private = 0;
     for (int32_t w = 0; w < NW; ++w) {
+      int32_t count = 0, room = 0;
       for (const NodeRange &nr : nodes)
         if (nr.lo / C == (nr.hi - 1) / C && nr.lo / C == w) {
-          rb_rec[3 + w] += emit_node(nr);
-          note_last(nr);
+          count += emit_node(nr);
+          if (note_last(nr, w) && pt.node(nr.node).n_live_children == 0) room += 2;
         }
-      total += rb_rec[3 + w];
-      longest_private = std::max(longest_private, rb_rec[3 + w]);
+      pl.walk_blocks.resize(pl.walk_blocks.size() + static_cast<size_t>(room) * Plan::kBlockInts, 0);
+      if (count + room > 0xffff) room_overflow = true;
+      rb_rec[3 + w] = count | ((count + room) << 16);
+      total += count;
+      longest_private = std::max(longest_private, count);
     }
     rbs_of_root[root_slot].push_back(static_cast<int32_t>(pl.walk_rb.size() / rb_ints));
     pl.walk_rb.insert(pl.walk_rb.end(), rb_rec.begin(), rb_rec.end());
@@ -708,6 +732,10 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     for (const auto &rb : last_blks) pl.req_walk_blk[fill[rb.first]++] = rb.second;
   }
 
+  for (int32_t &h : pl.req_walk_home)
+    if (h == -2) h = -1;
+  if (room_overflow) return;  // a wavefront with more than 65535 private blocks: no tree-walk lists
+
   // ---- launch order
   const int32_t n_roots = static_cast<int32_t>(root_ids.size());
   std::vector<int64_t> root_blocks(n_roots, 0);
@@ -729,6 +757,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   }
   size_t rounds = 0;
   for (const auto &v : lane_rbs) rounds = std::max(rounds, v.size());
+  pl.rb_item0.assign(pl.walk_rb.size() / rb_ints, -1);
   for (size_t r = 0; r < rounds; ++r)
     for (int32_t l = 0; l < lanes; ++l) {
       const bool real = r < lane_rbs[l].size();
@@ -741,6 +770,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
           const int32_t rb = lane_rbs[l][r];
           for (int k = 1; k < rb_ints; ++k) rec[k] = pl.walk_rb[static_cast<size_t>(rb) * rb_ints + k];
           rec[item_ints - 1] = rb;
+          if (g == 0) pl.rb_item0[rb] = static_cast<int32_t>(pl.walk_items.size() / item_ints);
           ++pl.walk_real_items;
         }
         pl.walk_items.insert(pl.walk_items.end(), rec.begin(), rec.end());
@@ -749,15 +779,25 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   pl.walk_ok = true;
 }
 
-// Appends that only filled up last pages (same structure version): the lists stay as they are
-// except for the valid count of each grown node's last page and the limits of its query tokens.
-// Mask flags are left alone: a flag that a fresh plan would no longer set only costs the masked
-// code path, never correctness.
+// Appends to requested nodes since the plan was made (no fork, no prune): the lists stay as they
+// are except for
+//  * the valid count of each grown node's last page and the limits of its query tokens;
+//  * pages the appends started (tree-walk lists only, and only if the plan holds no other lists):
+//    an odd page of the node's run becomes page b of the node's last block, wherever that block
+//    is listed; an even one opens a new block in the room behind the private blocks of the
+//    wavefront that holds the node -- if the node is private to one wavefront of one row block,
+//    is asked for by one request and room is left; else the caller plans afresh.
+// A new block goes behind the wavefront's other blocks, not next to its node's; the kernel's
+// result does not depend on the order of a wavefront's blocks beyond rounding.  Mask flags are left
+// alone: a flag that a fresh plan would no longer set only costs the masked code path.
 bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t> *dev_patches) {
   Plan &pl = *plan;
-  if (!pl.valid || pl.structure_version != pt.structure_version()) return false;
+  if (!pl.valid || pl.topology_version != pt.topology_version()) return false;
+  const bool walk = pl.has_walk && pl.walk_ok;
+  const bool new_pages = pl.structure_version != pt.structure_version();
+  if (new_pages && (!walk || pl.has_split || pl.has_csr)) return false;
   const int32_t n_leaves = static_cast<int32_t>(pl.req_leaves.size());
-  const int32_t N = pt.num_nodes();
+  const int32_t N = pt.num_nodes(), P = pt.page_size();
   if (static_cast<int32_t>(stamp_.size()) < N) {
     stamp_.resize(N, 0);
     slot_.resize(N, 0);
@@ -767,12 +807,13 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
     stamp_next_ = 1;
   }
   const int32_t st = stamp_next_++;
+  const size_t first_patch = dev_patches->size();
   auto patch = [&](int32_t array, int64_t index, int32_t value) {
     dev_patches->push_back(array);
     dev_patches->push_back(static_cast<int32_t>(index));
     dev_patches->push_back(value);
   };
-  const bool walk = pl.has_walk && pl.walk_ok;
+  const int32_t NW = pl.walk_waves, rb_ints = pl.rb_ints();
   for (int32_t i = 0; i < n_leaves; ++i) {
     const int32_t u = pl.req_leaves[i];
     const Node &nd = pt.node(u);
@@ -780,7 +821,8 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
     if (delta == 0) continue;
     if (delta < 0 || nd.pages.empty()) return false;
     const int32_t ql = pl.req_q_lens.empty() ? 1 : pl.req_q_lens[i];
-    const int32_t new_valid = pt.page_valid(u, static_cast<int32_t>(nd.pages.size()) - 1);
+    const int32_t n_pages = static_cast<int32_t>(nd.pages.size());
+    const int32_t new_valid = pt.page_valid(u, n_pages - 1);
     const int32_t q0 = pl.qoff[i];
     if (pl.qt_limit[q0 + ql - 1] + delta >= (1 << 24)) return false;
     for (int32_t j = 0; j < ql; ++j) pl.qt_limit[q0 + j] += delta;
@@ -806,14 +848,60 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
         }
     }
     if (walk) {
-      if (pl.req_walk_blk_indptr[i] == pl.req_walk_blk_indptr[i + 1]) return false;
-      for (int32_t e = pl.req_walk_blk_indptr[i]; e < pl.req_walk_blk_indptr[i + 1]; ++e) {
-        const int32_t blk = pl.req_walk_blk[e];
-        int32_t *rec = &pl.walk_blocks[static_cast<size_t>(blk) * Plan::kBlockInts];
-        const int slot = rec[3] != 0 ? 3 : 1;  // the last page is page b if the block has one
-        rec[slot] = (rec[slot] & ~127) | new_valid;
-        patch(kPatchWalkBlocks, static_cast<int64_t>(blk) * Plan::kBlockInts + slot, rec[slot]);
+      const int32_t e0 = pl.req_walk_blk_indptr[i], e1 = pl.req_walk_blk_indptr[i + 1];
+      if (e0 == e1) return false;
+      const int32_t old_pages = pl.req_pages[i];
+      if (n_pages < old_pages || old_pages < 1) return false;
+      if (n_pages > old_pages && !first_visit) return false;  // the node is asked for twice
+      auto set_field = [&](int32_t blk, int slot, int32_t value) {
+        pl.walk_blocks[static_cast<size_t>(blk) * Plan::kBlockInts + slot] = value;
+        patch(kPatchWalkBlocks, static_cast<int64_t>(blk) * Plan::kBlockInts + slot, value);
+      };
+      // path position of the node's first token, from its last block: page a of that block is
+      // page (old_pages - 1) & ~1 of the run
+      const int32_t *last = &pl.walk_blocks[static_cast<size_t>(pl.req_walk_blk[e0]) * Plan::kBlockInts];
+      const int32_t pos0 = (last[1] >> 7) - ((old_pages - 1) & ~1) * P;
+      for (int32_t pi = old_pages - 1; pi < n_pages; ++pi) {
+        const int32_t valid = pt.page_valid(u, pi), pos = pos0 + pi * P;
+        if ((pi & 1) || pi == old_pages - 1) {
+          // the page is (or becomes) page a or b of the node's last block, in every list
+          for (int32_t e = e0; e < e1; ++e) {
+            const int32_t blk = pl.req_walk_blk[e];
+            if (pi & 1) {
+              set_field(blk, 2, nd.pages[pi]);
+              set_field(blk, 3, (pos << 7) | valid);
+            } else {
+              set_field(blk, 1, (pos << 7) | valid);
+            }
+          }
+          continue;
+        }
+        // a new block, in the room of the wavefront that holds the node
+        const int32_t home = pl.req_walk_home[i];
+        if (home < 0 || e1 - e0 != 1) return false;
+        const int32_t rb = home / NW, w = home % NW;
+        int32_t *rbr = &pl.walk_rb[static_cast<size_t>(rb) * rb_ints];
+        const int32_t count = rbr[3 + w] & 0xffff, room = static_cast<int32_t>(static_cast<uint32_t>(rbr[3 + w]) >> 16);
+        if (count >= room) return false;
+        int32_t at = rbr[1] + rbr[2] + count;
+        for (int32_t v = 0; v < w; ++v) at += static_cast<int32_t>(static_cast<uint32_t>(rbr[3 + v]) >> 16);
+        const int32_t old_blk = pl.req_walk_blk[e0];
+        const int32_t rows = pl.walk_blocks[static_cast<size_t>(old_blk) * Plan::kBlockInts + 4];
+        const int32_t flags = 1 | (pl.walk_blocks[static_cast<size_t>(old_blk) * Plan::kBlockInts + 5] & 2);
+        const int32_t rec[Plan::kBlockInts] = {nd.pages[pi], (pos << 7) | valid, nd.pages[pi], 0, rows, flags, 0, 0};
+        for (int k = 0; k < Plan::kBlockInts; ++k) set_field(at, k, rec[k]);
+        pl.req_walk_blk[e0] = at;
+        rbr[3 + w] = (count + 1) | (room << 16);
+        const int32_t item0 = pl.rb_item0[rb], item_ints = pl.item_ints();
+        for (int32_t g = 0; g < pl.num_kv_heads; ++g) {
+          const int64_t idx = static_cast<int64_t>(item0 + g) * item_ints + 3 + w;
+          pl.walk_items[idx] = rbr[3 + w];
+          patch(kPatchWalkItems, idx, rbr[3 + w]);
+        }
+        ++pl.walk_block_visits;
+        pl.walk_max_item_blocks = std::max(pl.walk_max_item_blocks, rbr[2] + count + 1);
       }
+      pl.req_pages[i] = n_pages;
       for (int32_t j = 0; j < ql; ++j) {
         const int64_t at = 2 * static_cast<int64_t>(pl.req_walk_qt[i] + j) + 1;
         pl.walk_qt[at] = pl.qt_limit[q0 + j];
@@ -822,7 +910,26 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
     }
     pl.req_tokens[i] = nd.n_tokens;
   }
+  if (new_pages) {
+    // The device applies a batch of patches in no particular order, so an index may appear only
+    // once: keep the last value written to each (a wavefront's block count rises once per block
+    // started, a block opened and then given its page b has two fields written twice).
+    std::vector<int32_t> &dp = *dev_patches;
+    std::unordered_set<int64_t> seen;
+    seen.reserve(dp.size() / 3 - first_patch / 3);
+    size_t keep = dp.size();
+    for (size_t k = dp.size(); k > first_patch; k -= 3) {
+      const int64_t key = (static_cast<int64_t>(dp[k - 3]) << 40) | static_cast<uint32_t>(dp[k - 2]);
+      if (!seen.insert(key).second) continue;
+      keep -= 3;
+      dp[keep] = dp[k - 3];
+      dp[keep + 1] = dp[k - 2];
+      dp[keep + 2] = dp[k - 1];
+    }
+    dp.erase(dp.begin() + static_cast<std::ptrdiff_t>(first_patch), dp.begin() + static_cast<std::ptrdiff_t>(keep));
+  }
   pl.table_version = pt.version();
+  pl.structure_version = pt.structure_version();
   return true;
 }
 

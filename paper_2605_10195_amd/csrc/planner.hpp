@@ -33,7 +33,7 @@ struct Plan {
   // ---- cache key
   std::vector<int32_t> req_leaves, req_q_lens;
   std::vector<uint32_t> req_masks;  // draft visibility masks per query token, or empty (causal chain)
-  uint64_t table_version = 0, structure_version = 0;
+  uint64_t table_version = 0, structure_version = 0, topology_version = 0;
   int32_t req_prefix_chunk = -1, req_suffix_chunk = -1;
   int32_t num_q_heads = 0, num_kv_heads = 0;
   bool valid = false;
@@ -53,6 +53,10 @@ struct Plan {
   // ---- where an append to a requested node shows up (see Planner::patch_lengths)
   std::vector<int32_t> req_split_pg, req_in_group, req_qtpos_indptr, req_qtpos;
   std::vector<int32_t> req_walk_blk_indptr, req_walk_blk, req_walk_qt;
+  std::vector<int32_t> req_pages;      // pages of each requested node when planned / patched
+  // row block * NW + wavefront whose private list alone holds the requested node's blocks, else -1
+  std::vector<int32_t> req_walk_home;
+  std::vector<int32_t> rb_item0;       // per row block: its work item for kv head 0 (the others follow)
 
   // ---- canonical arrays (see spex_plan_view_t)
   std::vector<int32_t> leaf_indptr, leaf_pages, leaf_valid, qt_limit, group_node;
@@ -81,8 +85,10 @@ struct Plan {
   int32_t walk_waves = 0;       // NW: wavefronts per row block = per workgroup (4 or 8)
   int32_t req_walk_row_tiles = -1, req_walk_waves = -1;
   // row blocks: 3 + 3 * NW ints each
-  //   {root node, first block, shared blocks, private blocks of wavefronts 0..NW-1,
-  //    first walk_qt entry of wavefronts 0..NW-1, walk_qt entries of wavefronts 0..NW-1}
+  //   {root node, first block, shared blocks, private blocks of wavefronts 0..NW-1 as
+  //    count | room << 16 (room >= count block records are set aside for the wavefront, the
+  //    unused ones zero), first walk_qt entry of wavefronts 0..NW-1, walk_qt entries of
+  //    wavefronts 0..NW-1}
   int rb_ints() const { return 3 + 3 * walk_waves; }
   std::vector<int32_t> walk_rb;
   // blocks: kBlockInts ints each {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b
@@ -104,7 +110,7 @@ struct Plan {
 enum class PlanError { kOk, kBadNode, kEmptyPath, kInvalid, kTooLarge };
 
 // Device arrays a length patch can touch; a patch is the triple {array, int index, new value}.
-enum PatchArray : int32_t { kPatchPgRec = 0, kPatchQtRec = 1, kPatchWalkBlocks = 2, kPatchWalkQt = 3 };
+enum PatchArray : int32_t { kPatchPgRec = 0, kPatchQtRec = 1, kPatchWalkBlocks = 2, kPatchWalkQt = 3, kPatchWalkItems = 4 };
 
 class Planner {
  public:
@@ -116,8 +122,11 @@ class Planner {
   void ensure_csr(const PageTable &pt, Plan *plan);
   PlanError ensure_split(const PageTable &pt, Plan *plan);
   void ensure_walk(const PageTable &pt, Plan *plan);
-  // Brings a plan up to date after appends that started no new page (same structure version).
-  // Returns false if that is not possible (the caller then plans afresh).
+  // Brings a plan up to date after appends to requested nodes (no fork or prune since it was
+  // made).  Tokens that fill up a last page change valid counts and limits; a newly started page
+  // becomes page b of the node's last block or, in tree-walk lists that are the plan's only
+  // lists, a new block in the room set aside behind its wavefront's private blocks.  Returns
+  // false if that is not possible (the caller then plans afresh; the plan may be half changed).
   bool patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t> *dev_patches);
 
  private:

@@ -274,7 +274,10 @@ def test_decode_loop_patches_or_replans_after_every_append(mode):
         state = tree.last_launch_info()["plan_rebuilt"]          # 1 planned afresh, 2 patched
         states.add(state)
         out2, _ = tree.decode_attention(wl.leaves, None, q, wl.sm_scale)
-        assert state == (1 if new_page else 2) and tree.last_launch_info()["plan_rebuilt"] == 0
+        # split lists cannot take a started page; tree-walk lists take it as a patch (page b of
+        # the last block, or a block in the wavefront's room) unless it is the first plan
+        want_state = 1 if (new_page and (mode == 2 or step == 0)) else 2
+        assert state == want_state and tree.last_launch_info()["plan_rebuilt"] == 0
         if step % 3 == 2 or new_page:
             ref = sink.tree.attention(wl.leaves, None, qd, wl.sm_scale)
             got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
@@ -350,6 +353,54 @@ def test_softmax_scale_must_be_positive():
             t.decode_attention([r], None, q, bad)
         assert e.value.name == "INVALID_ARG"
     t.close()
+
+
+# ------------------------------------------------------------------ started pages as patches
+@pytest.mark.parametrize("kv_dtype,heads", [("bf16", (28, 4, 128)), ("fp8_e4m3", (8, 2, 128)), ("bf16", (8, 8, 64))])
+def test_decode_loop_starts_pages_by_patches(kv_dtype, heads):
+    """Branches of different lengths: in almost every iteration some branch starts a page.  With the
+    tree-walk lists those pages are patched in (free half of the last block, else the room behind
+    the wavefront's private blocks) until some wavefront's room is used up; the attention must
+    match the oracle after every kind of step, and the patched device lists must give what a
+    fresh plan gives."""
+    from oracle.adapters import OracleSink, queries_fp64
+    wl = sw.mcts_skewed(n_queries=3, prompt=(30, 90), step=(5, 40), max_leaves=10, heads=heads, kv_dtype=kv_dtype)
+    nodes = sorted(set(wl.leaves))
+    tree = build_gpu_tree(wl, extra_pages=8 * len(nodes) + 8, kernel_mode=3)
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = sw.gen_queries(wl, device="cuda")
+    qd = queries_fp64(q)
+    H, D = heads[1], heads[2]
+    childless = [u for u in nodes if tree.node_info(u)["n_live_children"] == 0]
+    assert len(childless) >= 6
+    page_patches = fresh = 0
+    for step in range(76):
+        x_k = sw.normal_values(8, 1, 300 + step, torch.arange(len(childless)), H, D, 0.5, "cuda").to(torch.bfloat16)
+        x_v = sw.normal_values(8, 2, 300 + step, torch.arange(len(childless)), H, D, 0.5, "cuda").to(torch.bfloat16)
+        started = sum(tree.append_new_pages(u, 1) for u in childless)
+        if kv_dtype == "fp8_e4m3":
+            s = torch.full((len(childless), H), 2.0 ** -6, dtype=torch.float32, device="cuda")
+            tree.append_tokens(childless, x_k.contiguous(), x_v.contiguous(), s, s, quantize=True)
+            for i, u in enumerate(childless):
+                new = tree.node_info(u)["n_tokens"] % 16 == 1
+                sink.append_quantised(u, x_k[i:i + 1].cpu(), x_v[i:i + 1].cpu(), s[i:i + 1].cpu() if new else None,
+                                      s[i:i + 1].cpu() if new else None)
+        else:
+            tree.append_tokens(childless, x_k.contiguous(), x_v.contiguous())
+            for i, u in enumerate(childless):
+                sink.append(u, x_k[i:i + 1].cpu(), x_v[i:i + 1].cpu())
+        out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        state = tree.last_launch_info()["plan_rebuilt"]
+        assert state in (1, 2)
+        page_patches += state == 2 and started > 0
+        fresh += state == 1
+        if started or step % 6 == 0:
+            ref = sink.tree.attention(wl.leaves, wl.q_lens, qd, wl.sm_scale)
+            got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+            assert_close(got, ref, kv_dtype, f"{kv_dtype} step {step} state {state} started {started}")
+    assert page_patches >= 20 and fresh >= 2          # room ran out at least once after the first plan
+    tree.close()
 
 
 # ------------------------------------------------------------------ decode loop, one launch per append

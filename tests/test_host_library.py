@@ -201,6 +201,13 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
                          draft_masks=wl.draft_masks)
     for k in WALK_KEYS:
         assert got[k] == want[k], k
+    return check_walk_coverage(got, ref, wl, row_tiles, waves)
+
+
+def check_walk_coverage(got, ref, wl, row_tiles=0, waves=0, fresh=True):
+    """The model-independent part: what the lists of `got` make every row read.  fresh=False: a
+    plan that was patched after appends -- room may have been used up, and a block's flag bit 1
+    is not re-derived."""
     G = wl.num_q_heads // wl.num_kv_heads
     q_lens = wl.q_lens if wl.q_lens is not None else [1] * len(wl.leaves)
     masks = wl.draft_masks                                       # the chain if none are given
@@ -220,20 +227,36 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
     seen_tokens = []
     used_blocks = np.zeros(len(blocks), dtype=bool)
     rbs_of_page = {}                                              # page -> row blocks that list it
-    for bi, rb in enumerate(rbs):
-        for blk in blocks[rb[1]:rb[1] + rb[2] + rb[3:3 + NW].sum()]:
-            for pg in {int(blk[0]), int(blk[2])}:
-                rbs_of_page.setdefault(pg, set()).add(bi)
-    for blk in blocks:                                            # flag bit 1: shared between row blocks
-        assert bool(blk[5] & 2) == (len(rbs_of_page[int(blk[0])]) > 1)
-    for rb in rbs:
-        first, n_sh, n_pr = rb[1], rb[2], rb[3:3 + NW]
-        qt_first, qt_count = rb[3 + NW:3 + 2 * NW], rb[3 + 2 * NW:3 + 3 * NW]
-        spans = [(first, first + n_sh, None)]
+    def spans_of(rb):
+        """(first block, end, wavefront or None for the shared blocks), and the unused room"""
+        first, n_sh = rb[1], rb[2]
+        out, gaps = [(first, first + n_sh, None)], []
         b0 = first + n_sh
         for w in range(NW):
-            spans.append((b0, b0 + n_pr[w], w))
-            b0 += n_pr[w]
+            count, room = int(rb[3 + w]) & 0xffff, int(rb[3 + w]) >> 16
+            assert room >= count
+            out.append((b0, b0 + count, w))
+            gaps.append((b0 + count, b0 + room))
+            b0 += room
+        return out, gaps
+
+    childless = {u for u in set(wl.leaves) if not ref.has_live_children(u)}
+    for bi, rb in enumerate(rbs):
+        for a, b, _ in spans_of(rb)[0]:
+            for blk in blocks[a:b]:
+                for pg in {int(blk[0]), int(blk[2])}:
+                    rbs_of_page.setdefault(pg, set()).add(bi)
+    for rb in rbs:
+        spans, gaps = spans_of(rb)
+        for a, b in gaps:                                         # unused room: all-zero records
+            assert not blocks[a:b].any()
+            used_blocks[a:b] = True
+        if fresh:                                                 # flag bit 1: shared between row blocks
+            for a, b, _ in spans:
+                for blk in blocks[a:b]:
+                    assert bool(blk[5] & 2) == (len(rbs_of_page[int(blk[0])]) > 1)
+        first, n_sh = rb[1], rb[2]
+        qt_first, qt_count = rb[3 + NW:3 + 2 * NW], rb[3 + 2 * NW:3 + 3 * NW]
         # rows of the row block: row -> (query token, limit)
         row_tok = {}
         for w in range(NW):
@@ -246,6 +269,12 @@ def check_walk_lists(tree, ref, wl, row_tiles, waves=0):
                     row_tok[w * C + e * G + hh] = (t, hidden)
                 seen_tokens.append(t)
             assert qt_count[w] * G <= C
+        if fresh:        # room: two records per requested childless node that is private to the wavefront
+            for (a, b, w), (ga, gb) in zip(spans[1:], gaps):
+                own_pages = {int(blk[0]) for blk in blocks[a:b]}
+                nodes_here = {u for u in childless if ref.pages[u] and ref.pages[u][0] in own_pages
+                              and any(wl.leaves[tok_owner[qt[qt_first[w] + e][0]]] == u for e in range(qt_count[w]))}
+                assert gb - ga == 2 * len(nodes_here), (w, gb - ga, nodes_here)
         pages_of_row = {r: [] for r in row_tok}
         for a, b, wave in spans:
             for blk in blocks[a:b]:
@@ -408,20 +437,27 @@ def test_walk_lists_not_available_when_one_query_token_is_wider_than_a_wavefront
 
 
 # ------------------------------------------------------------------ length patches
-def grow_and_compare(wl, n_steps, seed):
-    """Append tokens to requested leaves step by step.  The library patches its cached lists when no
-    page is started; a second tree that replays everything and plans afresh must give the same
-    lists, except that a patched plan may keep mask flags a fresh plan no longer needs."""
-    n_pages = wl.peak_pages() + 2 * len(wl.leaves) + 8
+def grow_and_compare(wl, n_steps, seed, walk_only=False):
+    """Append tokens to requested leaves step by step.  The library patches its cached lists when
+    it can: always when no page is started; when pages are started, if the tree-walk lists are
+    the plan's only lists and the room behind the grown node's wavefront is not used up.  A second
+    tree that replays everything and plans afresh must give the same lists as a fresh plan, and as
+    a plan patched without page starts, except that a patched plan may keep mask flags a fresh
+    plan no longer needs; a plan patched with page starts is checked for what it makes every row
+    read (its new blocks sit in the room, not where a fresh plan puts them).
+    Returns (patches without page start, fresh plans, patches with page starts)."""
+    n_pages = wl.peak_pages() + 8 * len(wl.leaves) + 8
     tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
     replay_both(wl, tree, ref)
     rng = np.random.default_rng(seed)
     childless = [u for u in sorted(set(wl.leaves)) if not ref.has_live_children(u)]
     masks = wl.draft_masks          # with masks only the tree-walk lists are compared: the
-    if masks is None:               # split lists' dump takes no masks and would plan afresh
+    split = masks is None and not walk_only     # split lists' dump takes no masks and would plan afresh
+    if split:
         tree.plan_dump(wl.leaves, wl.q_lens)
     tree.walk_dump(wl.leaves, wl.q_lens, masks)
-    patched_seen = fresh_seen = 0
+    patched_seen = fresh_seen = page_patches = 0
+    moved = False                   # blocks were started by a patch since the last fresh plan
     for step in range(n_steps):
         grow = [u for u in childless if rng.random() < 0.7]
         started_page = False
@@ -431,15 +467,30 @@ def grow_and_compare(wl, n_steps, seed):
             tree.append_step(u, None, None, n_tokens=n)
             ref.append(u, n)
         got_walk = tree.walk_dump(wl.leaves, wl.q_lens, masks)
+        state = got_walk["plan_state"]
         if grow:
-            assert got_walk["plan_state"] == (1 if started_page else 2), step
+            if split or not got_walk["available"]:
+                assert state == (1 if started_page else 2), step
+            else:
+                assert state in ((1, 2) if started_page else (2,)), step
+        if grow:
+            patched_seen += state == 2 and not started_page
+            fresh_seen += state == 1
+        if state == 1:
+            moved = False
+        elif started_page and grow:
+            moved = True
+            page_patches += 1
+        if moved:
+            check_walk_coverage(got_walk, ref, wl, fresh=False)
+            continue
         want_walk = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, draft_masks=masks)
         got_split = want_split = {}
-        if masks is None:
+        if split:
             got_split = tree.plan_dump(wl.leaves, wl.q_lens)
             want_split = ref.plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads,
                                   got_split["prefix_chunk_pages"], got_split["suffix_chunk_pages"])
-        for k in (PLAN_KEYS if masks is None else []):
+        for k in (PLAN_KEYS if split else []):
             if k == "task_flags":
                 for a, b in zip(got_split[k], want_split[k]):
                     assert a & 2 == b & 2 and (a & 1) >= (b & 1)
@@ -452,22 +503,30 @@ def grow_and_compare(wl, n_steps, seed):
                 assert np.all((a[:, 5] & 1) >= (b[:, 5] & 1))
             else:
                 assert got_walk[k] == want_walk[k], (step, k)
-        if grow:
-            patched_seen += not started_page
-            fresh_seen += started_page
-    return patched_seen, fresh_seen
+    return patched_seen, fresh_seen, page_patches
 
 
-@pytest.mark.parametrize("wl", [
+GROW_WORKLOADS = [
     sw.bfs_tot(n_queries=2, prompt=40, step=19), sw.tot_with_drafts(n_queries=2, prompt=50, step=21),
     sw.mcts_skewed(n_queries=4, prompt=(30, 90), step=(5, 40), max_leaves=12),
     sw.random_trace(640, n_ops=60, max_tokens=40, max_q_len=3, heads=(8, 2, 64)),
     sw.with_draft_trees(sw.random_trace(641, n_ops=14, max_tokens=40, max_q_len=5, heads=(8, 2, 64))),
-    sw.random_trace(642, n_ops=16, max_tokens=40, max_q_len=9, heads=(16, 2, 64))],      # requests cut into pieces
-    ids=lambda w: w.name)
+    sw.random_trace(642, n_ops=16, max_tokens=40, max_q_len=9, heads=(16, 2, 64))]      # requests cut into pieces
+
+
+@pytest.mark.parametrize("wl", GROW_WORKLOADS, ids=lambda w: w.name)
 def test_length_patches_match_a_fresh_plan(wl):
-    patched, fresh = grow_and_compare(wl, 24, 5)
-    assert patched > 3 and fresh > 3          # both the patch path and the replan path were taken
+    patched, fresh, _ = grow_and_compare(wl, 24, 5)
+    assert patched > 3 and (fresh > 3 or wl.draft_masks is not None)    # both paths were taken
+
+
+@pytest.mark.parametrize("wl", GROW_WORKLOADS[:4] + [sw.random_trace(643, n_ops=40, max_tokens=50, max_q_len=1, heads=(28, 4, 128))],
+                         ids=lambda w: w.name)
+def test_patches_that_start_pages(wl):
+    """Tree-walk lists alone: started pages go into the last block's free half or into the room
+    of the node's wavefront, until the room is used up and the plan is made afresh."""
+    patched, fresh, page_patches = grow_and_compare(wl, 90, 9, walk_only=True)
+    assert page_patches > 10 and fresh > 0 and patched > 3
 
 
 # ------------------------------------------------------------------ one token per node
