@@ -157,11 +157,11 @@ spex_status_t spex_tree_append_step_quantize(spex_tree_t *tree, spex_node_t node
  *           token starts a new page and ignored otherwise
  * All or nothing: if a node is unknown, repeated (SPEX_ERR_INVALID_ARG), has live children, or
  * the pool has too few free pages for all of them, nothing is changed.  Pages are taken in the
- * order of `nodes`.  Tokens that start no page leave the structure of the cached launch lists
- * intact: if the handle holds such lists on the device, the same launch that scatters the tokens
- * also writes the new page lengths and query limits into them, and a decode_attention call that
- * repeats the previous request then runs without planning, upload or patch launch (it reports
- * plan state 2).  Both calls must be on the same stream, or ordered by the caller.
+ * order of `nodes`.  If the handle holds launch lists on the device that the appends can be
+ * patched into (see spex_tree_decode_attention), the same launch that scatters the tokens also
+ * writes the new page lengths, query limits and started pages into them, and a decode_attention
+ * call that repeats the previous request then runs without planning, upload or patch launch (it
+ * reports plan state 2).  Both calls must be on the same stream, or ordered by the caller.
  */
 spex_status_t spex_tree_append_tokens(spex_tree_t *tree, const spex_node_t *nodes, int32_t n_nodes,
                                       const void *k, const void *v, const float *k_scales,
@@ -204,10 +204,15 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *   sm_scale must be positive and finite.
  * The call flattens parent links into per-launch work lists, uploads them when the request or
  * the tree changed since the previous call, and enqueues the kernels on hip_stream without
- * waiting for them.  If the only change is that tokens were appended without starting a new page
- * (the usual decode iteration), the cached lists are patched instead: the valid count of each
- * grown page and the limits of its queries, on the host and -- with one small kernel -- in the
- * device copy.  Two kernel sets compute the same result:
+ * waiting for them.  If the only change is that tokens were appended to requested nodes (the
+ * usual decode iteration), the cached lists are patched instead, on the host and -- with one
+ * small kernel, or inside the spex_tree_append_tokens launch -- in the device copy: the valid
+ * count of each grown page and the limits of its queries; and, if the tree-walk lists are the
+ * only lists the cached plan holds, the pages the appends started: such a page becomes page b of
+ * its node's last block or a new block in the room kept behind the private blocks of the node's
+ * wavefront (two blocks per requested childless node when the plan is made; when a wavefront's
+ * room is used up, or a started page belongs to a node that several wavefronts or requests
+ * share, the call plans afresh).  Two kernel sets compute the same result:
  *   tree-walk: one workgroup carries a block of up to 16 * walk_row_tiles * walk_waves query rows (requested
  *     nodes that are neighbours in the tree) from the root to the requested nodes; pages shared
  *     by rows of several wavefronts are fetched once per workgroup, the softmax state stays in
@@ -325,15 +330,17 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *tree, int32_t prefix_chunk_pages
  *     (roots in order of first appearance) and sorted by path below a root, so that the requests
  *     below any node are consecutive.
  *   row_blocks[(3 + 3 * NW) * n_row_blocks]: {root node, first block, shared blocks, private
- *     blocks of wavefronts 0..NW-1, first qt entry of each wavefront, qt entries of each
- *     wavefront}.  Requests fill a wavefront while their q_len * G rows fit into C; wavefront NW
+ *     blocks of wavefronts 0..NW-1 as count | room << 16, first qt entry of each wavefront, qt
+ *     entries of each wavefront}.  room >= count records belong to the wavefront; those beyond
+ *     count are zero until an append starts a block there (a fresh plan leaves two per requested
+ *     node without live children that is private to the wavefront).  Requests fill a wavefront while their q_len * G rows fit into C; wavefront NW
  *     or a new root starts a new row block.  Row of a request: wavefront * C + rows before it in the wavefront.
  *   blocks[8 * n_blocks]: {page a, pos_a << 7 | valid_a, page b, pos_b << 7 | valid_b (0 = no page
  *     b), first row | (last row + 1) << 16, flags, 0, 0}: two consecutive pages of one node on the
  *     row block's paths, the path position and valid tokens of each, and the rows whose path
  *     holds the node.  A row block's blocks: first the nodes whose rows touch several
- *     wavefronts, then those of wavefront 0, 1, .. alone; every page of every row's path
- *     appears exactly once per row block.  Flag bit 0: a page is partial or missing, or some
+ *     wavefronts, then those of wavefront 0, 1, .. alone, each followed by its unused room; every
+ *     page of every row's path appears exactly once per row block.  Flag bit 0: a page is partial or missing, or some
  *     row in the range may not see every position the block holds (the block ends beyond the
  *     first position that some query of a request in the range does not see: T - q_len + 1 for
  *     the chain, T - q_len + the number of leading drafts all its queries see with draft_masks,
@@ -367,7 +374,7 @@ spex_status_t spex_tree_read_profile(spex_tree_t *tree, float *ms, int32_t cap, 
 
 /* Counts of the last decode_attention call, for the throughput metric:
  * info[0] distinct KV tokens on the requested paths, [6] 0 = the cached plan was used, 1 = planned
- * afresh, 2 = the cached plan was patched (tokens had been appended without starting a page),
+ * afresh, 2 = the cached plan was patched (tokens had been appended to requested nodes),
  * [7] 0 = shared-prefix + suffix + merge kernels ran ([1] tokens in shared-prefix tasks, [2] tokens in
  * suffix tasks, [3] prefix work items, [4] suffix work items, [5] partial rows), else the tree-walk
  * kernel ran with [7] = row tiles per wavefront + 256 * wavefronts per workgroup ([3] workgroups
