@@ -403,6 +403,41 @@ def test_decode_loop_starts_pages_by_patches(kv_dtype, heads):
     tree.close()
 
 
+def test_step_appends_that_start_several_pages_are_patched():
+    """Whole steps (runs of 5-45 tokens) appended to some branches between attention calls: the
+    tree-walk lists on the device take the started pages as one batch of patches in which no
+    index appears twice."""
+    from oracle.adapters import OracleSink, queries_fp64
+    wl = sw.mcts_skewed(n_queries=3, prompt=(30, 90), step=(5, 40), max_leaves=10, heads=(8, 2, 128))
+    nodes = sorted(set(wl.leaves))
+    tree = build_gpu_tree(wl, extra_pages=24 * len(nodes) + 8, kernel_mode=3)
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = sw.gen_queries(wl, device="cuda")
+    qd = queries_fp64(q)
+    childless = [u for u in nodes if tree.node_info(u)["n_live_children"] == 0]
+    rng = np.random.default_rng(21)
+    tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+    patched = fresh = 0
+    for step in range(14):
+        for i, u in enumerate(childless):
+            if rng.random() < 0.6:
+                n = int(rng.integers(5, 46))
+                k = sw.normal_values(9, 1, 1000 * step + i, torch.arange(n), 2, 128, 0.5, "cuda").to(torch.bfloat16)
+                v = sw.normal_values(9, 2, 1000 * step + i, torch.arange(n), 2, 128, 0.5, "cuda").to(torch.bfloat16)
+                tree.append_step(u, k.contiguous(), v.contiguous())
+                sink.append(u, k, v)
+        out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        state = tree.last_launch_info()["plan_rebuilt"]
+        patched += state == 2
+        fresh += state == 1
+        ref = sink.tree.attention(wl.leaves, wl.q_lens, qd, wl.sm_scale)
+        got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+        assert_close(got, ref, "bf16", f"step {step} state {state}")
+    assert patched >= 3 and fresh >= 1
+    tree.close()
+
+
 # ------------------------------------------------------------------ decode loop, one launch per append
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3", "f32"])
 def test_decode_loop_with_append_tokens(kv_dtype):

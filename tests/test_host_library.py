@@ -437,7 +437,7 @@ def test_walk_lists_not_available_when_one_query_token_is_wider_than_a_wavefront
 
 
 # ------------------------------------------------------------------ length patches
-def grow_and_compare(wl, n_steps, seed, walk_only=False):
+def grow_and_compare(wl, n_steps, seed, walk_only=False, max_run=3):
     """Append tokens to requested leaves step by step.  The library patches its cached lists when
     it can: always when no page is started; when pages are started, if the tree-walk lists are
     the plan's only lists and the room behind the grown node's wavefront is not used up.  A second
@@ -446,7 +446,7 @@ def grow_and_compare(wl, n_steps, seed, walk_only=False):
     plan no longer needs; a plan patched with page starts is checked for what it makes every row
     read (its new blocks sit in the room, not where a fresh plan puts them).
     Returns (patches without page start, fresh plans, patches with page starts)."""
-    n_pages = wl.peak_pages() + 8 * len(wl.leaves) + 8
+    n_pages = wl.peak_pages() + (8 + n_steps * max_run // 16) * len(wl.leaves) + 8
     tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
     replay_both(wl, tree, ref)
     rng = np.random.default_rng(seed)
@@ -462,7 +462,7 @@ def grow_and_compare(wl, n_steps, seed, walk_only=False):
         grow = [u for u in childless if rng.random() < 0.7]
         started_page = False
         for u in grow:
-            n = int(rng.integers(1, 4))
+            n = int(rng.integers(1, max_run + 1))
             started_page |= tree.append_new_pages(u, n) > 0
             tree.append_step(u, None, None, n_tokens=n)
             ref.append(u, n)
@@ -527,6 +527,14 @@ def test_patches_that_start_pages(wl):
     of the node's wavefront, until the room is used up and the plan is made afresh."""
     patched, fresh, page_patches = grow_and_compare(wl, 90, 9, walk_only=True)
     assert page_patches > 10 and fresh > 0 and patched > 3
+
+
+@pytest.mark.parametrize("wl", GROW_WORKLOADS[:3], ids=lambda w: w.name)
+def test_patches_that_start_several_pages_at_once(wl):
+    """Runs of up to 45 tokens: one append can fill the last block's free half, open a block in the
+    room and fill that block's second half as well."""
+    _, fresh, page_patches = grow_and_compare(wl, 30, 13, walk_only=True, max_run=45)
+    assert page_patches > 5 and fresh > 0
 
 
 # ------------------------------------------------------------------ one token per node
