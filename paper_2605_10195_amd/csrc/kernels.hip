@@ -887,14 +887,15 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const in
   for (int nt = 0; nt < NT; ++nt) {
     if (nt * 16 >= hi || nt * 16 + 16 <= lo) continue;  // wave-uniform
     const bool partial_tile = lo > nt * 16 || hi < nt * 16 + 16;
-    // Scores: with one scale for the whole path (bf16 KV) they stay raw, the running maximum is
-    // kept on raw scores and scale and subtraction fuse into one FMA per score; with a scale per
-    // page (fp8 KV) they are scaled here.  m is in units of raw score / of log2(e) accordingly.
+    // Scores stay raw; scale and subtraction of the reference fuse into one FMA per score.  With
+    // one scale for the whole path (bf16 KV) the reference m is kept on raw scores; with a scale
+    // per page (fp8 KV) it is kept in scaled units (log2 e folded in), and the largest scaled score
+    // of the lane is c * the largest raw one (c > 0, and rounding is monotonic).
     float x[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      x[i] = FP8 ? sa[nt][i] * c : sa[nt][i];
-      x[4 + i] = FP8 ? sb[nt][i] * c : sb[nt][i];
+      x[i] = sa[nt][i];
+      x[4 + i] = sb[nt][i];
     }
     if (tok_masked || partial_tile) {
       const int row = nt * 16 + m16;
@@ -921,8 +922,9 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const in
         for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
       }
     }
-    const float mx8 = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                            fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    const float mx8_raw = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
+                                fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+    const float mx8 = FP8 ? mx8_raw * c : mx8_raw;
     // Lazy reference: m is the value the row's weights are taken relative to, not its exact
     // running maximum.  It moves (and o and l are rescaled) only when a score of the row exceeds it
     // by more than `slack` (2^8 in weight); until then weights are at most 2^8, which fp16 and
@@ -940,8 +942,9 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const in
     }
     float pr[8];
     if (FP8) {
+      const float neg_m = -m[nt];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(x[i] - m[nt]);
+      for (int i = 0; i < 8; ++i) pr[i] = fast_exp2(__builtin_fmaf(x[i], c, neg_m));
     } else {
       const float mc = m[nt] * c;
 #pragma unroll
