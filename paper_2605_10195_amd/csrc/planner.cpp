@@ -807,7 +807,7 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
     stamp_next_ = 1;
   }
   const int32_t st = stamp_next_++;
-  const size_t first_patch = dev_patches->size();
+  const bool had_patches = !dev_patches->empty();
   auto patch = [&](int32_t array, int64_t index, int32_t value) {
     dev_patches->push_back(array);
     dev_patches->push_back(static_cast<int32_t>(index));
@@ -910,14 +910,16 @@ bool Planner::patch_lengths(const PageTable &pt, Plan *plan, std::vector<int32_t
     }
     pl.req_tokens[i] = nd.n_tokens;
   }
-  if (new_pages) {
+  if (new_pages || had_patches) {
     // The device applies a batch of patches in no particular order, so an index may appear only
     // once: keep the last value written to each (a wavefront's block count rises once per block
-    // started, a block opened and then given its page b has two fields written twice).
+    // started, a block opened and then given its page b has two fields written twice; patches
+    // that were already waiting in the list are older values of the same indices).
     std::vector<int32_t> &dp = *dev_patches;
     std::unordered_set<int64_t> seen;
-    seen.reserve(dp.size() / 3 - first_patch / 3);
+    seen.reserve(dp.size() / 3);
     size_t keep = dp.size();
+    const size_t first_patch = 0;  // the whole list is one batch
     for (size_t k = dp.size(); k > first_patch; k -= 3) {
       const int64_t key = (static_cast<int64_t>(dp[k - 3]) << 40) | static_cast<uint32_t>(dp[k - 2]);
       if (!seen.insert(key).second) continue;

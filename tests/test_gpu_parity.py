@@ -438,6 +438,35 @@ def test_step_appends_that_start_several_pages_are_patched():
     tree.close()
 
 
+def test_patches_left_waiting_are_merged_with_later_ones():
+    """Requests with 40 queries each: one appended token moves 41 list entries per branch, more
+    than an append launch takes along, so they wait for the next attention call.  A second append
+    before that call adds newer values for the same entries; the device must end up with the
+    newest of each."""
+    from oracle.adapters import OracleSink, queries_fp64
+    wl = sw.step_prefill(n_queries=2, prompt=64, step=40, heads=(8, 2, 128))
+    tree = build_gpu_tree(wl, extra_pages=4 * len(wl.leaves) + 4, kernel_mode=3)
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = sw.gen_queries(wl, device="cuda")
+    qd = queries_fp64(q)
+    tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+    L = len(wl.leaves)
+    for rnd in range(3):
+        for rep in range(2):                                  # two appends, no attention in between
+            k = sw.normal_values(7, 1, 50 + 2 * rnd + rep, torch.arange(L), 2, 128, 0.5, "cuda").to(torch.bfloat16)
+            v = sw.normal_values(7, 2, 50 + 2 * rnd + rep, torch.arange(L), 2, 128, 0.5, "cuda").to(torch.bfloat16)
+            tree.append_tokens(wl.leaves, k.contiguous(), v.contiguous())
+            for i, u in enumerate(wl.leaves):
+                sink.append(u, k[i:i + 1], v[i:i + 1])
+        out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        assert tree.last_launch_info()["plan_rebuilt"] == 2
+        ref = sink.tree.attention(wl.leaves, wl.q_lens, qd, wl.sm_scale)
+        got = (out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64))
+        assert_close(got, ref, "bf16", f"round {rnd}")
+    tree.close()
+
+
 # ------------------------------------------------------------------ decode loop, one launch per append
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3", "f32"])
 def test_decode_loop_with_append_tokens(kv_dtype):
