@@ -190,6 +190,43 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
                                          t->walk_row_tiles, t->walk_waves, &t->plan));
 }
 
+// Longest tree-walk workgroup (in two-page blocks) up to which a launch of `items` workgroups
+// (< 128) still goes to the tree-walk kernel.
+int32_t short_walk_blocks(int64_t items) {
+  return items <= 32 ? 20 : 20 + static_cast<int32_t>((items - 32) * 7 / 10);
+}
+
+// True if the automatic choice is certain to be the split path, judged from the request alone:
+// an upper bound on the tree-walk workgroups (no request has more rows than a 16-row wavefront,
+// so none is cut; every wavefront holds at least one request, so a root with r requests has at
+// most ceil(r / 4) row blocks) stays below 128, and a lower bound on
+// the longest workgroup (the longest path, two full pages per block) exceeds what that many
+// workgroups may walk.  Saves building the tree-walk lists just to discard them.
+bool obviously_split(const spex::Plan &pl) {
+  const size_t n = pl.req_leaves.size();
+  if (n == 0 || n > 512) return false;
+  const int32_t G = pl.num_q_heads / pl.num_kv_heads;
+  int32_t roots[512], counts[512], n_roots = 0;
+  int32_t longest = 0;
+  for (size_t i = 0; i < n; ++i) {
+    const int32_t r = pl.path_nodes[pl.path_indptr[i]];
+    int32_t k = 0;
+    while (k < n_roots && roots[k] != r) ++k;
+    if (k == n_roots) {
+      roots[n_roots] = r;
+      counts[n_roots++] = 0;
+    }
+    ++counts[k];
+    const int32_t ql = pl.req_q_lens.empty() ? 1 : pl.req_q_lens[i];
+    if (static_cast<int64_t>(ql) * G > 16) return false;  // may be cut into pieces: no simple bound
+    longest = std::max(longest, pl.qt_limit[pl.qoff[i] + ql - 1]);  // the path's tokens
+  }
+  int64_t items = 0;
+  for (int32_t k = 0; k < n_roots; ++k) items += (counts[k] + 3) / 4;
+  items *= pl.num_kv_heads;
+  return items < 128 && (longest + 31) / 32 > short_walk_blocks(items);
+}
+
 constexpr int kPlanArrays = 15;
 // Index, in the device blob's array list, of the arrays a length patch can touch.
 constexpr int kPatchTarget[5] = {2 /*pg_rec*/, 3 /*qt_rec*/, 12 /*walk_blocks*/, 13 /*walk_qt*/, 11 /*walk_items*/};
@@ -650,15 +687,17 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
   // runs, the three split-path launches take 26-45 us for up to 32 work items of this size and
   // grow with the item count: measured crossing points were 20 blocks at 8-32 items, 40 at 64
   // and 65 at 96 (bf16, 32 / 8 heads of 128).  Only the lists of the chosen kernels are built.
-  const bool want_walk = (t->kernel_mode == 0 || t->kernel_mode == 3) && spex::has_mfma_kernel(t->shape);
-  if (want_walk) t->planner.ensure_walk(*t->pt, &pl);
+  bool want_walk = (t->kernel_mode == 0 || t->kernel_mode == 3) && spex::has_mfma_kernel(t->shape);
   const bool tree_masks = draft_masks != nullptr;
+  if (want_walk && t->kernel_mode == 0 && !tree_masks && !pl.has_walk && obviously_split(pl))
+    want_walk = false;  // few requests with long paths: the split path without building the other lists
+  if (want_walk) t->planner.ensure_walk(*t->pt, &pl);
   // Draft-tree masks are understood by the tree-walk kernel (4 wavefronts per workgroup) and by
   // the generic kernels.
   const bool walk_possible = want_walk && pl.walk_ok && (!tree_masks || pl.walk_waves == 4);
   if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
   if (t->kernel_mode == 2 && tree_masks && spex::has_mfma_kernel(t->shape)) return SPEX_ERR_UNSUPPORTED;
-  const int32_t short_walk = pl.walk_real_items <= 32 ? 20 : 20 + (pl.walk_real_items - 32) * 7 / 10;
+  const int32_t short_walk = short_walk_blocks(pl.walk_real_items);
   const bool use_walk = walk_possible && (t->kernel_mode == 3 || tree_masks || pl.walk_real_items >= 128 ||
                                           pl.walk_max_item_blocks <= short_walk);
   if (!use_walk) {
