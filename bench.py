@@ -25,8 +25,8 @@ HBM_PEAK_GBPS = 8000.0
 # a plain 1 GiB-in / 1 GiB-out kernel (--calibrate): FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB.  The
 # summaries are in profiles/<workload>_tree_walk.md.  Key: (workload, kernel).
 MEASURED_TRAFFIC_BYTES = {
-    ("bfs_tot", "spex_tree_walk_kernel"): 535127296,           # profiles/bfs_tot_tree_walk.md
-    ("mcts_skewed", "spex_tree_walk_kernel"): 610866520,       # profiles/mcts_skewed_tree_walk.md
+    ("bfs_tot", "spex_tree_walk_kernel"): 535399424,           # profiles/bfs_tot_tree_walk.md
+    ("mcts_skewed", "spex_tree_walk_kernel"): 610967920,       # profiles/mcts_skewed_tree_walk.md
     ("spec_at_scale", "spex_tree_walk_kernel"): 13343266624,   # profiles/spec_at_scale_tree_walk.md
     ("tot_with_drafts", "spex_tree_walk_kernel"): 496838488,   # profiles/tot_with_drafts_tree_walk.md
     ("step_prefill", "spex_tree_walk_kernel"): 2224013696,     # profiles/step_prefill_tree_walk.md
