@@ -224,7 +224,10 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
  *   shared-prefix + suffix + merge: every shared node is read once for all rows below it, private
  *     suffixes are split for parallelism, partial softmax states go through memory.  Any shape.
  * Consecutive calls on one handle must use one stream or be separated by a synchronisation,
- * because they share the handle's workspace.
+ * because they share the handle's workspace.  A call that repeats the previous request on an
+ * unchanged tree (plan state 0, profiling off) only launches kernels -- no planning, allocation,
+ * copy or event -- and may therefore be recorded in a HIP graph; the recorded launches read the
+ * handle's device lists, so the graph is valid until a call plans afresh or the handle goes.
  */
 spex_status_t spex_tree_decode_attention(spex_tree_t *tree, const spex_node_t *leaves,
                                          const int32_t *q_lens, int32_t n_leaves, const void *q,

@@ -467,6 +467,42 @@ def test_patches_left_waiting_are_merged_with_later_ones():
     tree.close()
 
 
+# ------------------------------------------------------------------ capture in a HIP graph
+@pytest.mark.parametrize("mode", [2, 3])
+def test_attention_with_a_cached_plan_can_be_captured_in_a_graph(mode):
+    """A call that repeats the previous request on an unchanged tree only launches kernels (no
+    planning, upload, allocation or event), so a caller may record it in a HIP graph -- e.g. one
+    call per model layer.  Every replay, with eager work and synchronisation in between and new
+    query values in the same buffer, must give what the eager call gives."""
+    wl = sw.bfs_tot(n_queries=3, prompt=72, step=24)
+    tree = build_gpu_tree(wl, kernel_mode=mode)
+    q = sw.gen_queries(wl, device="cuda")
+    out = torch.empty((q.shape[0], wl.num_q_heads, wl.head_dim), dtype=torch.float32, device="cuda")
+    lse = torch.empty((q.shape[0], wl.num_q_heads), dtype=torch.float32, device="cuda")
+    tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse)      # plans, uploads, allocates
+    tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse)
+    assert tree.last_launch_info()["plan_rebuilt"] == 0
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, out, lse)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        q.copy_((q.float() * (0.5 + 0.25 * rep)).to(q.dtype))                  # new queries, same buffer
+        eager_out, eager_lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        out.fill_(7.0)
+        lse.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager_out) and torch.equal(lse, eager_lse), rep
+    del graph
+    tree.close()
+
+
 # ------------------------------------------------------------------ decode loop, one launch per append
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3", "f32"])
 def test_decode_loop_with_append_tokens(kv_dtype):
