@@ -33,7 +33,21 @@ PlanError Planner::begin(const PageTable &pt, const int32_t *leaves, const int32
   if (n_leaves < 0 || (n_leaves > 0 && !leaves)) return PlanError::kInvalid;
   const int32_t N = pt.num_nodes();
   Plan &pl = *plan;
-  pl = Plan();
+  {
+    // A fresh Plan, but the largest lists keep the memory of the previous plan: a request of
+    // thousands of branches has megabytes of block records, and growing those vectors from
+    // nothing each time costs more than filling them.
+    std::vector<int32_t> *big[] = {&pl.walk_blocks, &pl.walk_items, &pl.walk_qt,   &pl.walk_rb,  &pl.path_nodes,
+                                   &pl.path_indptr, &pl.qt_limit,   &pl.pg_rec,    &pl.qt_rec,   &pl.leaf_pages};
+    constexpr int kBig = sizeof(big) / sizeof(big[0]);
+    std::vector<int32_t> kept[kBig];
+    for (int i = 0; i < kBig; ++i) {
+      kept[i] = std::move(*big[i]);
+      kept[i].clear();
+    }
+    pl = Plan();
+    for (int i = 0; i < kBig; ++i) *big[i] = std::move(kept[i]);
+  }
   pl.req_leaves.assign(leaves, leaves + n_leaves);
   if (q_lens) pl.req_q_lens.assign(q_lens, q_lens + n_leaves);
   pl.table_version = pt.version();
