@@ -96,3 +96,55 @@ def test_full_config_5_with_draft_token_trees(drafts):
     ref = run_oracle(wl, leaves, q_lens, rows, draft_masks=[wl.draft_masks[r] for r in rows])
     max_abs, rel = assert_close((out[rows], lse[rows]), ref, wl.kv_dtype, wl.name)
     print(f"{wl.name} {drafts} drafts: max_abs={max_abs:.2e} rel_l2={rel:.2e}")
+
+
+def test_full_config_decode_loop_with_patched_plans():
+    """Config 3 at full size, 72 decode iterations: one token for every branch per iteration
+    (`spex_tree_append_tokens`), attention after each.  The 1 105 branches have unequal lengths, so
+    pages are started in every iteration; the plan is made afresh only when a wavefront's room for
+    started blocks is used up.  Sampled branches are checked against the oracle, which gets the
+    same appended tokens."""
+    import paper_2605_10195_amd as spex
+    from oracle.adapters import OracleSink, queries_fp64
+    wl = sw.WORKLOADS["mcts_skewed"]()
+    iters = 72
+    nodes = sorted(set(wl.leaves))
+    n_pages = wl.peak_pages()
+    extra = len(nodes) * (iters // 16 + 2)
+    order = np.random.default_rng(5).permutation(n_pages).tolist() + list(range(n_pages, n_pages + extra))
+    tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype, wl.kv_dtype,
+                         num_pages=n_pages + extra, device="cuda", free_order=order, interleave_kv=True)
+    sw.replay(wl, tree, device="cuda")
+    childless = [u for u in nodes if tree.node_info(u)["n_live_children"] == 0]
+    slot = {u: i for i, u in enumerate(childless)}
+    picks = list(range(0, len(wl.leaves), len(wl.leaves) // 40))[:40]
+    leaves, q_lens, rows = sample_rows(wl, picks)
+    _, parent, _ = wl.node_tokens()
+    only = set()
+    for u in leaves:
+        while u != -1 and u not in only:
+            only.add(u)
+            u = parent[u]
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink, device="cpu", only_nodes=only)
+    q = sw.gen_queries(wl, device="cuda")
+    rows_t = torch.as_tensor(rows, device="cuda")
+    qs = queries_fp64(q[rows_t])
+    plans = {0: 0, 1: 0, 2: 0}
+    for it in range(iters):
+        k = sw.normal_values(11, 1, 4000 + it, torch.arange(len(childless)), wl.num_kv_heads, wl.head_dim, 0.5,
+                             "cuda").to(torch.bfloat16)
+        v = sw.normal_values(11, 2, 4000 + it, torch.arange(len(childless)), wl.num_kv_heads, wl.head_dim, 0.5,
+                             "cuda").to(torch.bfloat16)
+        tree.append_tokens(childless, k.contiguous(), v.contiguous())
+        for u in set(leaves):
+            if u in slot:
+                sink.append(u, k[slot[u]:slot[u] + 1].cpu(), v[slot[u]:slot[u] + 1].cpu())
+        out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
+        plans[tree.last_launch_info()["plan_rebuilt"]] += 1
+        if it % 24 == 23:
+            ref = sink.tree.attention(leaves, q_lens, qs, wl.sm_scale)
+            got = (out[rows_t].cpu().numpy().astype(np.float64), lse[rows_t].cpu().numpy().astype(np.float64))
+            assert_close(got, ref, wl.kv_dtype, f"iteration {it}")
+    assert plans[1] <= 3 and plans[2] >= iters - 3, plans
+    tree.close()
