@@ -437,7 +437,7 @@ def test_walk_lists_not_available_when_one_query_token_is_wider_than_a_wavefront
 
 
 # ------------------------------------------------------------------ length patches
-def grow_and_compare(wl, n_steps, seed, walk_only=False, max_run=3):
+def grow_and_compare(wl, n_steps, seed, walk_only=False, max_run=3, row_tiles=0, waves=0):
     """Append tokens to requested leaves step by step.  The library patches its cached lists when
     it can: always when no page is started; when pages are started, if the tree-walk lists are
     the plan's only lists and the room behind the grown node's wavefront is not used up.  A second
@@ -453,6 +453,7 @@ def grow_and_compare(wl, n_steps, seed, walk_only=False, max_run=3):
     childless = [u for u in sorted(set(wl.leaves)) if not ref.has_live_children(u)]
     masks = wl.draft_masks          # with masks only the tree-walk lists are compared: the
     split = masks is None and not walk_only     # split lists' dump takes no masks and would plan afresh
+    tree.set_tuning(0, 0, 0, row_tiles, waves)
     if split:
         tree.plan_dump(wl.leaves, wl.q_lens)
     tree.walk_dump(wl.leaves, wl.q_lens, masks)
@@ -482,9 +483,10 @@ def grow_and_compare(wl, n_steps, seed, walk_only=False, max_run=3):
             moved = True
             page_patches += 1
         if moved:
-            check_walk_coverage(got_walk, ref, wl, fresh=False)
+            check_walk_coverage(got_walk, ref, wl, row_tiles, waves, fresh=False)
             continue
-        want_walk = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, draft_masks=masks)
+        want_walk = ref.walk_plan(wl.leaves, wl.q_lens, wl.num_q_heads, wl.num_kv_heads, row_tiles, waves,
+                                  draft_masks=masks)
         got_split = want_split = {}
         if split:
             got_split = tree.plan_dump(wl.leaves, wl.q_lens)
@@ -527,6 +529,45 @@ def test_patches_that_start_pages(wl):
     of the node's wavefront, until the room is used up and the plan is made afresh."""
     patched, fresh, page_patches = grow_and_compare(wl, 90, 9, walk_only=True)
     assert page_patches > 10 and fresh > 0 and patched > 3
+
+
+@pytest.mark.parametrize("row_tiles,waves", [(2, 4), (1, 8), (4, 8)])
+def test_patches_that_start_pages_other_row_block_shapes(row_tiles, waves):
+    wl = sw.mcts_skewed(n_queries=4, prompt=(30, 90), step=(5, 40), max_leaves=12)
+    patched, fresh, page_patches = grow_and_compare(wl, 90, 23, walk_only=True, row_tiles=row_tiles, waves=waves)
+    assert page_patches > 10 and fresh > 0 and patched > 3
+
+
+@pytest.mark.parametrize("wl", GROW_WORKLOADS[4:], ids=lambda w: w.name)
+def test_started_pages_of_nodes_that_several_wavefronts_share(wl):
+    """Draft token trees, and requests cut into pieces: a grown node whose rows lie in several
+    wavefronts sits among the shared blocks, which have no room -- its started page can still become
+    page b of its last block, otherwise the plan is made afresh.  Either way the lists must cover
+    every row's path."""
+    patched, fresh, page_patches = grow_and_compare(wl, 60, 17, walk_only=True)
+    assert patched > 3 and fresh > 0 and page_patches > 0
+
+
+def test_started_page_of_a_node_requested_twice_plans_afresh():
+    wl = sw.bfs_tot(n_queries=1, prompt=40, step=19)
+    n_pages = wl.peak_pages() + 16
+    tree, ref = host_tree(wl, n_pages), PageTableRef(n_pages, 16)
+    replay_both(wl, tree, ref)
+    leaves = list(wl.leaves) + [wl.leaves[0]]                  # the first branch asked for twice
+    assert tree.walk_dump(leaves, None)["plan_state"] == 1
+    u = wl.leaves[0]
+    seen = set()
+    for _ in range(40):
+        started = tree.append_new_pages(u, 1) > 0
+        tree.append_step(u, None, None, n_tokens=1)
+        ref.append(u, 1)
+        got = tree.walk_dump(leaves, None)
+        assert got["plan_state"] == (1 if started else 2)
+        seen.add(got["plan_state"])
+        want = ref.walk_plan(leaves, None, wl.num_q_heads, wl.num_kv_heads)
+        for k in ("row_blocks", "qt", "items"):
+            assert got[k] == want[k], k
+    assert seen == {1, 2}
 
 
 @pytest.mark.parametrize("wl", GROW_WORKLOADS[:3], ids=lambda w: w.name)
