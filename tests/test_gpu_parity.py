@@ -356,8 +356,10 @@ def test_softmax_scale_must_be_positive():
 
 
 # ------------------------------------------------------------------ started pages as patches
-@pytest.mark.parametrize("kv_dtype,heads", [("bf16", (28, 4, 128)), ("fp8_e4m3", (8, 2, 128)), ("bf16", (8, 8, 64))])
-def test_decode_loop_starts_pages_by_patches(kv_dtype, heads):
+@pytest.mark.parametrize("kv_dtype,heads,shape", [("bf16", (28, 4, 128), (0, 0)), ("fp8_e4m3", (8, 2, 128), (0, 0)),
+                                                  ("bf16", (8, 8, 64), (0, 0)), ("bf16", (8, 2, 128), (2, 8)),
+                                                  ("bf16", (8, 2, 64), (2, 4))])
+def test_decode_loop_starts_pages_by_patches(kv_dtype, heads, shape):
     """Branches of different lengths: in almost every iteration some branch starts a page.  With the
     tree-walk lists those pages are patched in (free half of the last block, else the room behind
     the wavefront's private blocks) until some wavefront's room is used up; the attention must
@@ -366,7 +368,8 @@ def test_decode_loop_starts_pages_by_patches(kv_dtype, heads):
     from oracle.adapters import OracleSink, queries_fp64
     wl = sw.mcts_skewed(n_queries=3, prompt=(30, 90), step=(5, 40), max_leaves=10, heads=heads, kv_dtype=kv_dtype)
     nodes = sorted(set(wl.leaves))
-    tree = build_gpu_tree(wl, extra_pages=8 * len(nodes) + 8, kernel_mode=3)
+    tree = build_gpu_tree(wl, extra_pages=8 * len(nodes) + 8, kernel_mode=3, walk_row_tiles=shape[0],
+                          walk_waves=shape[1])
     sink = OracleSink.for_workload(wl)
     sw.replay(wl, sink)
     q = sw.gen_queries(wl, device="cuda")
