@@ -144,7 +144,9 @@ def decode_loop(tree, wl, q, out, lse, iters, dev):
                 plans_patched=counts[2], plans_redone=counts[1],
                 note="append_tokens (fp8 pools: append_tokens_quantize, bf16 tokens encoded by the "
                      "append kernel) + decode_attention per iteration, one tree, KV of earlier "
-                     "iterations may sit in the last-level cache")
+                     "iterations may sit in the last-level cache; plans_patched counts iterations whose "
+                     "cached plan was brought up to date (grown and started pages) inside the append "
+                     "launch, plans_redone those that planned afresh")
 
 
 def run_dynamic(args):
