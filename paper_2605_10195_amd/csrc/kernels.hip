@@ -1318,8 +1318,10 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// One wavefront per work item; rows of the item one after the other.  Lane = token for the
-// scores, lane = dim (d, d+64, ..) for the weighted sum.
+// One wavefront per (work item, row): blockIdx.y strides over the item's rows.  Lane = token for
+// the scores, lane = dim (d, d+64, ..) for the weighted sum.  The loops over dims and tokens fetch
+// four elements before they use them (in the same order as one at a time), so that a lane does not
+// sit out a memory latency per element.
 template <int KV, int QT, int LAYOUT>
 __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape sh, int rows_per_item) {
   __shared__ float qs[256];
@@ -1339,7 +1341,7 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
   const int n_tok_slots = pg_count * P;
   const int r_end = min(rows, row0 + rows_per_item);
 
-  for (int r = row0; r < r_end; ++r) {
+  for (int r = row0 + static_cast<int>(blockIdx.y); r < r_end; r += static_cast<int>(gridDim.y)) {
     const int qt = p.qt_rec[2 * (qt_begin + r / G)];
     const int hh = r % G;
     const int limit = p.qt_rec[2 * (qt_begin + r / G) + 1];
@@ -1371,7 +1373,16 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
       if (ok) {
         const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e]) * sh.page_tiles + g);
         float dot = 0.f;
-        for (int d = 0; d < D; ++d)
+        int d = 0;
+        for (; d + 4 <= D; d += 4) {
+          float kv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            kv[u] = load_elem<KV>(p.k_pool, tile * tile_elems + k_offset<KV, LAYOUT>(slot, d + u, D));
+#pragma unroll
+          for (int u = 0; u < 4; ++u) dot += qs[d + u] * kv[u];
+        }
+        for (; d < D; ++d)
           dot += qs[d] * load_elem<KV>(p.k_pool, tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D));
         if (KV == kFP8) dot *= p.k_scale[p.pg_rec[2 * e] * sh.Hkv + g];
         s = dot * p.scale_log2;
@@ -1385,19 +1396,30 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
 #pragma unroll
       for (int c = 0; c < 4; ++c) acc[c] *= alpha;
       const int n_here = min(64, n_tok_slots - t0);
-      for (int t = 0; t < n_here; ++t) {
-        const float pt = __shfl(pw, t);
-        if (pt == 0.f) continue;
-        const int e2 = pg_begin + (t0 + t) / P;
-        const int slot2 = (t0 + t) % P;
-        const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e2]) * sh.page_tiles + g);
-        const float w = (KV == kFP8) ? pt * p.v_scale[p.pg_rec[2 * e2] * sh.Hkv + g] : pt;
+      for (int tb = 0; tb < n_here; tb += 4) {
+        float wt[4], vv[4][4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const int d = lane + 64 * c;
-          if (d < D)
-            acc[c] += w * load_elem<KV>(p.v_pool, tile * tile_elems + v_offset<KV, LAYOUT>(slot2, d, D));
+        for (int u = 0; u < 4; ++u) {
+          const int t = tb + u;
+          const float pt = t < n_here ? __shfl(pw, t & 63) : 0.f;
+          wt[u] = pt;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) vv[u][c] = 0.f;
+          if (pt == 0.f) continue;  // wave-uniform: pt is a broadcast value
+          const int e2 = pg_begin + (t0 + t) / P;
+          const int slot2 = (t0 + t) % P;
+          const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e2]) * sh.page_tiles + g);
+          if (KV == kFP8) wt[u] = pt * p.v_scale[p.pg_rec[2 * e2] * sh.Hkv + g];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int d = lane + 64 * c;
+            if (d < D) vv[u][c] = load_elem<KV>(p.v_pool, tile * tile_elems + v_offset<KV, LAYOUT>(slot2, d, D));
+          }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[c] += wt[u] * vv[u][c];
       }
     }
     const int64_t out_slot = static_cast<int64_t>(pbase) + static_cast<int64_t>(g) * rows + r;
@@ -1680,7 +1702,7 @@ hipError_t launch_mfma_nt(const Shape &sh, const AttnArgs &a, bool prefix, int n
 
 template <int KV, int QT>
 hipError_t launch_generic(const Shape &sh, const AttnArgs &a, int rows_per_item, hipStream_t stream) {
-  const dim3 grid(a.n_items), block(64);
+  const dim3 grid(a.n_items, rows_per_item), block(64);
   if (sh.layout == kMfmaTiled)
     hipLaunchKernelGGL((spex_generic_attn_kernel<KV, QT, kMfmaTiled>), grid, block, 0, stream, a, sh,
                        rows_per_item);
