@@ -1320,10 +1320,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // One wavefront per (work item, row): blockIdx.y strides over the item's rows.  Lane = token for
 // the scores, lane = dim (d, d+64, ..) for the weighted sum.  The loops over dims and tokens fetch
-// four elements before they use them (in the same order as one at a time), so that a lane does not
+// eight elements before they use them (in the same order as one at a time), so that a lane does not
 // sit out a memory latency per element.
 template <int KV, int QT, int LAYOUT>
 __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape sh, int rows_per_item) {
+  constexpr int kU = 8;  // elements fetched before they are used
   __shared__ float qs[256];
   const int lane = threadIdx.x;
   const int32_t *rec = p.items + static_cast<int64_t>(blockIdx.x) * 8;
@@ -1374,13 +1375,13 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
         const int64_t tile = (static_cast<int64_t>(p.pg_rec[2 * e]) * sh.page_tiles + g);
         float dot = 0.f;
         int d = 0;
-        for (; d + 4 <= D; d += 4) {
-          float kv[4];
+        for (; d + kU <= D; d += kU) {
+          float kv[kU];
 #pragma unroll
-          for (int u = 0; u < 4; ++u)
+          for (int u = 0; u < kU; ++u)
             kv[u] = load_elem<KV>(p.k_pool, tile * tile_elems + k_offset<KV, LAYOUT>(slot, d + u, D));
 #pragma unroll
-          for (int u = 0; u < 4; ++u) dot += qs[d + u] * kv[u];
+          for (int u = 0; u < kU; ++u) dot += qs[d + u] * kv[u];
         }
         for (; d < D; ++d)
           dot += qs[d] * load_elem<KV>(p.k_pool, tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D));
@@ -1396,10 +1397,10 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
 #pragma unroll
       for (int c = 0; c < 4; ++c) acc[c] *= alpha;
       const int n_here = min(64, n_tok_slots - t0);
-      for (int tb = 0; tb < n_here; tb += 4) {
-        float wt[4], vv[4][4];
+      for (int tb = 0; tb < n_here; tb += kU) {
+        float wt[kU], vv[kU][4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kU; ++u) {
           const int t = tb + u;
           const float pt = t < n_here ? __shfl(pw, t & 63) : 0.f;
           wt[u] = pt;
@@ -1417,7 +1418,7 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
           }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < kU; ++u)
 #pragma unroll
           for (int c = 0; c < 4; ++c) acc[c] += wt[u] * vv[u][c];
       }
