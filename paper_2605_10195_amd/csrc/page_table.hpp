@@ -7,6 +7,7 @@
 // a child's first token always starts a fresh page, so a page belongs to exactly one node.
 #pragma once
 
+#include <cstddef>
 #include <cstdint>
 #include <vector>
 
