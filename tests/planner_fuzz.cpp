@@ -101,6 +101,10 @@ int main(int argc, char **argv) {
       PlanError e = planner.begin(pt, leaves.data(), q_lens.data(), nullptr, static_cast<int>(leaves.size()), Hq, Hkv, 0, 0, ntw, nw, &plan);
       if (e != PlanError::kOk) return false;
       planner.ensure_walk(pt, &plan);
+      if (seed % 3 == 0) {                      // the split lists and the page CSR as well
+        planner.ensure_csr(pt, &plan);
+        if (planner.ensure_split(pt, &plan) != PlanError::kOk) return false;
+      }
       return plan.walk_ok;
     };
     if (!make()) continue;
