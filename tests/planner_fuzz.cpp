@@ -1,5 +1,5 @@
 // Host-only fuzz of the planner and page table, built with AddressSanitizer and UBSan by
-// test_planner_fuzz.py: random trees and requests, fresh tree-walk lists, then rounds of appends
+// test_host_sanitizers.py: random trees and requests, fresh tree-walk lists, then rounds of appends
 // that are patched into the lists (or planned afresh when that is not possible).  After every
 // round the lists must make every row read every page of its path exactly once, with the right
 // position and length; unused room must be zero; a batch of patches must not give one list entry

@@ -1,5 +1,5 @@
 // Host-only fuzz of the scheduling primitives (csrc/sched.cpp), built with AddressSanitizer and
-// UBSan by test_planner_fuzz.py: random search trees and parameters, including empty and
+// UBSan by test_host_sanitizers.py: random search trees and parameters, including empty and
 // degenerate inputs; every output must stay inside the ranges the header promises.
 #include <cmath>
 #include <cstdio>
