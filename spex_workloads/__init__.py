@@ -9,13 +9,13 @@ nor the oracle.
 
 from .rng import normal_values, hash_key
 from .quant import encode_e4m3, quantise_pages
-from .trees import (Workload, TreeOp, tiny_tree, bfs_tot, mcts_skewed,
+from .trees import (Workload, TreeOp, ValueProfile, tiny_tree, bfs_tot, mcts_skewed,
                     spec_at_scale, tot_with_drafts, step_prefill, random_trace, draft_tree_masks,
                     with_draft_trees, WORKLOADS)
 from .replay import replay, gen_queries
 
 __all__ = [
-    "normal_values", "hash_key", "encode_e4m3", "quantise_pages", "Workload", "TreeOp",
+    "normal_values", "hash_key", "encode_e4m3", "quantise_pages", "Workload", "TreeOp", "ValueProfile",
     "tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts", "step_prefill",
     "random_trace", "draft_tree_masks", "with_draft_trees", "WORKLOADS", "replay", "gen_queries",
 ]

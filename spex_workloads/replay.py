@@ -31,7 +31,7 @@ def _cast(x: torch.Tensor, dtype: str) -> torch.Tensor:
     raise ValueError(dtype)
 
 
-def _gen_batch(wl: Workload, ops, device):
+def _gen_batch(wl: Workload, ops, device, pos0=None):
     """K and V (fp32) for a list of append ops, generated in one vectorised call."""
     lens = torch.tensor([op.n for op in ops], dtype=torch.int64, device=device)
     keys = torch.tensor([op.key for op in ops], dtype=torch.int64, device=device)
@@ -45,6 +45,20 @@ def _gen_batch(wl: Workload, ops, device):
                       wl.value_scale, device)
     v = normal_values(wl.seed, TAG_V, node_keys, tok, wl.num_kv_heads, wl.head_dim,
                       wl.value_scale, device)
+    pf = wl.profile
+    if pf is not None:
+        if pf.k_ramp != 0.0 or pf.k_bias != 0.0:
+            first = torch.tensor([pos0[op.node] for op in ops], dtype=torch.int64, device=device)
+            pos = torch.repeat_interleave(first, lens) + tok
+            k[:, :, 0] += (pf.k_ramp * pos.to(torch.float32) + pf.k_bias)[:, None]
+        if pf.spikes:
+            st = starts.tolist()
+            for op, s0 in zip(ops, st):
+                for t, val in pf.spikes.get(op.node, ()):
+                    if op.tok0 <= t < op.tok0 + op.n:
+                        k[s0 + t - op.tok0, :, 0] += val
+        if pf.v_mult != 1.0:
+            v = v * pf.v_mult
     return k, v, starts.tolist()
 
 
@@ -66,6 +80,7 @@ def replay(wl: Workload, sink, device="cpu", batch_tokens: Optional[int] = None,
     last_scale: Dict[int, tuple] = {}
     ready: Dict[int, tuple] = {}
     ops = wl.ops
+    pos0 = wl.node_pos0() if wl.profile is not None else None
     for i, op in enumerate(ops):
         if op.kind == "fork":
             ids = sink.fork(op.node, op.n)
@@ -88,7 +103,7 @@ def replay(wl: Workload, sink, device="cpu", batch_tokens: Optional[int] = None,
                         batch.append(j)
                         tot += o.n
                     j += 1
-                kb, vb, starts = _gen_batch(wl, [ops[j] for j in batch], device)
+                kb, vb, starts = _gen_batch(wl, [ops[j] for j in batch], device, pos0)
                 for j, s in zip(batch, starts):
                     ready[j] = (kb[s:s + ops[j].n], vb[s:s + ops[j].n])
             k32, v32 = ready.pop(i)
@@ -116,4 +131,6 @@ def gen_queries(wl: Workload, device="cpu") -> torch.Tensor:
     tok = torch.arange(total, dtype=torch.int64, device=device) - torch.repeat_interleave(starts, lens)
     q = normal_values(wl.seed, TAG_Q, torch.repeat_interleave(keys, lens), tok,
                       wl.num_q_heads, wl.head_dim, wl.value_scale, device)
+    if wl.profile is not None and wl.profile.q0 is not None:
+        q[:, :, 0] = wl.profile.q0
     return _cast(q, wl.q_dtype).contiguous()

@@ -35,6 +35,23 @@ class TreeOp:
 
 
 @dataclass
+class ValueProfile:
+    """Structure laid over the i.i.d. values of a workload, so that tests can shape the scores
+    (inputs only -- which scores result is for the library and the oracle to work out):
+      q0      every query's dim 0 is set to this value (None: left as drawn);
+      k_ramp  added to dim 0 of every K token: k_ramp * (the token's position on its root path);
+      k_bias  added to dim 0 of every K token;
+      spikes  node -> [(token index inside the node, value added to dim 0 of that K token)];
+      v_mult  V is multiplied by this (a power of two keeps it exact).
+    With q0 = b, the score of a token moves by sm_scale * b * (what was added to its K)."""
+    q0: Optional[float] = None
+    k_ramp: float = 0.0
+    k_bias: float = 0.0
+    spikes: Optional[dict] = None
+    v_mult: float = 1.0
+
+
+@dataclass
 class Workload:
     name: str
     num_q_heads: int
@@ -54,6 +71,7 @@ class Workload:
     # visibility mask of every query token among its request's q_len drafts (bit k = draft k is
     # seen), or None for the causal chain
     draft_masks: Optional[List[int]] = None
+    profile: Optional[ValueProfile] = None
 
     def __post_init__(self):
         if self.sm_scale == 0.0:
@@ -83,6 +101,14 @@ class Workload:
                         alive[u] = False
                         stack.extend(children[u])
         return tokens, parent, alive
+
+    def node_pos0(self) -> List[int]:
+        """Path position of every node's first token (tokens of its ancestors)."""
+        tokens, parent, _ = self.node_tokens()
+        pos0 = [0] * len(tokens)
+        for u in range(len(tokens)):          # ids follow creation order: a parent precedes its children
+            pos0[u] = 0 if parent[u] == NO_NODE else pos0[parent[u]] + tokens[parent[u]]
+        return pos0
 
     def peak_pages(self) -> int:
         """Largest number of pages in use at any point of the trace."""

@@ -118,3 +118,34 @@ def test_replay_is_deterministic_and_batching_invariant():
         assert torch.equal(ka, kb) and torch.equal(va, vb)
     q1, q2 = sw.gen_queries(wl), sw.gen_queries(wl)
     assert torch.equal(q1, q2) and q1.dtype == torch.bfloat16
+
+
+def test_the_shaped_inputs_do_move_the_softmax_reference():
+    """The premise of the peaked-softmax GPU tests, checked on the inputs themselves (host
+    arithmetic on the seeded values, no kernel): along a 'rising' path the largest score seen so
+    far grows by more than 8 / log2(e) -- the distance at which the tree-walk kernel moves its
+    reference -- at least five times; with i.i.d. values it does so once."""
+    import numpy as np
+    from oracle.adapters import OracleSink, queries_fp64
+    from peaked_cases import make_workload, shaped
+    for kind, least, most in (("rising", 5, 10 ** 6), (None, 1, 1)):
+        wl = shaped("bfs_bf16", kind) if kind else make_workload("bfs_bf16")
+        sink = OracleSink.for_workload(wl)
+        sw.replay(wl, sink)
+        q = queries_fp64(sw.gen_queries(wl))
+        K, _ = sink.tree.materialise(wl.leaves[0])
+        s = wl.sm_scale * (K[:, 0, :] @ q[0, 0]) * 1.4426950408889634
+        moves, ref = 0, -1e30
+        for b in range(0, len(s), 32):
+            mx = s[b:b + 32].max()
+            if mx > ref + 8.0:
+                ref, moves = mx, moves + 1
+        assert least <= moves <= most, (kind, moves)
+    # a spike dominates: the weight of every other token is below e^-40
+    wl = shaped("bfs_bf16", "spike_root")
+    sink = OracleSink.for_workload(wl)
+    sw.replay(wl, sink)
+    q = queries_fp64(sw.gen_queries(wl))
+    K, _ = sink.tree.materialise(wl.leaves[0])
+    s = np.sort(wl.sm_scale * (K[:, 0, :] @ q[0, 0]))
+    assert s[-1] - s[-2] > 40.0
