@@ -20,19 +20,44 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this script (counters need runs of their own); scaled by the factors the same counters show for
-# a plain 1 GiB-in / 1 GiB-out kernel (--calibrate): FETCH_SIZE x 2 KiB, WRITE_SIZE x 1 KiB.  The
-# summaries are in profiles/<workload>_tree_walk.md.  Key: (workload, kernel).
-MEASURED_TRAFFIC_BYTES = {
-    ("bfs_tot", "spex_tree_walk_kernel"): 535399424,           # profiles/bfs_tot_tree_walk.md
-    ("mcts_skewed", "spex_tree_walk_kernel"): 610967920,       # profiles/mcts_skewed_tree_walk.md
-    ("spec_at_scale", "spex_tree_walk_kernel"): 13343266624,   # profiles/spec_at_scale_tree_walk.md
-    ("tot_with_drafts", "spex_tree_walk_kernel"): 496838488,   # profiles/tot_with_drafts_tree_walk.md
-    ("step_prefill", "spex_tree_walk_kernel"): 2224013696,     # profiles/step_prefill_tree_walk.md
-}
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 PAPER_CONTEXT = ("paper reports only end-to-end serving speedups (1.2-3x, up to 4.1x with MTP) on "
                  "NVIDIA A6000/A100; no attention-kernel number exists for this metric")
+# The five configs of the metric (config 1 is the fp32 parity case) and the many-query workload.
+PER_CONFIG = ["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts", "step_prefill"]
+
+
+def source_sha16():
+    """Hash of the sources that shape the kernels' memory traffic; a profile summary under
+    profiles/ names the hash it was measured at."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in ("paper_2605_10195_amd/csrc/kernels.hip", "paper_2605_10195_amd/csrc/planner.cpp"):
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def profiled_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the rocprofv3 --pmc summary profiles/<workload>_tree_walk.md
+    (FETCH_SIZE + WRITE_SIZE, collected in runs of their own and scaled as the summary says).  The
+    figure is reported only if the summary was made from the sources this run uses; else null."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_tree_walk.md")
+    fields = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("    ") and ":" in line:
+                    k, v = line.strip().split(":", 1)
+                    fields[k.strip()] = v.strip()
+    except OSError:
+        return None, "no summary under profiles/ for this workload"
+    if fields.get("kernel") != kernel or "traffic_bytes_per_launch" not in fields:
+        return None, "the summary holds no traffic figure for this kernel"
+    if fields.get("source_sha16") != source_sha16():
+        return None, ("profiles/%s_tree_walk.md was measured at source hash %s, this run is %s"
+                      % (workload, fields.get("source_sha16"), source_sha16()))
+    return int(fields["traffic_bytes_per_launch"]), "profiles/%s_tree_walk.md" % workload
 
 
 def parse():
@@ -40,7 +65,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="bfs_tot",
+    ap.add_argument("--workload", default="spec_at_scale",
                     choices=["tiny_tree", "bfs_tot", "mcts_skewed", "spec_at_scale", "tot_with_drafts",
                              "step_prefill", "dynamic_rebase", "dynamic_mcts"],
                     help="dynamic_rebase / dynamic_mcts: a breadth-first (REBASE widths, speculative "
@@ -66,6 +91,8 @@ def parse():
                          "spex_tree_decode_attention_masked); 0 = the workload's causal drafts")
     ap.add_argument("--progress", action="store_true", help="print a line on stderr at every stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short runs of the other configs that fill the per_config block")
     ap.add_argument("--cpu-sample-leaves", type=int, default=0)
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one elementwise kernel that reads 1 GiB and writes 1 GiB, as the "
@@ -73,12 +100,15 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, n_leaves):
-    """Time the oracle, as it stands, on the first n_leaves requested nodes (single thread)."""
+def cpu_baseline(wl, n_leaves, dev):
+    """Time the oracle (its C form, oracle/attention_ref.c: materialise each branch's contiguous
+    K/V, fp64 attention, requested nodes spread over the host's threads) on the first n_leaves
+    requested nodes.  The seeded inputs are generated on `dev` and decoded to fp64 on the host before
+    the clock starts."""
     import numpy as np
-    from threadpoolctl import threadpool_limits
 
     import spex_workloads as sw
+    from oracle import attention_c
     from oracle.adapters import OracleSink, queries_fp64
 
     leaves = wl.leaves[:n_leaves]
@@ -90,23 +120,29 @@ def cpu_baseline(wl, n_leaves):
             only.add(u)
             u = parent[u]
     sink = OracleSink.for_workload(wl)
-    sw.replay(wl, sink, device="cpu", only_nodes=only)
-    q = queries_fp64(sw.gen_queries(wl, device="cpu"))[:sum(q_lens)]
+    sw.replay(wl, sink, device=dev, only_nodes=only)
+    q = queries_fp64(sw.gen_queries(wl, device=dev)[:sum(q_lens)])
     masks = None if wl.draft_masks is None else [int(m) for m in wl.draft_masks[:sum(q_lens)]]
-    with threadpool_limits(limits=1):
-        t0 = time.perf_counter()
-        out, _ = sink.tree.attention(leaves, q_lens, q, wl.sm_scale, draft_masks=masks)
-        dt = time.perf_counter() - t0
+    threads = max(1, min(16, os.cpu_count() or 1))     # a one-GPU machine's share of the host
+    t0 = time.perf_counter()
+    out, _, info = attention_c.attention(sink.tree, leaves, q_lens, q, wl.sm_scale, draft_masks=masks,
+                                         threads=threads)
+    dt = time.perf_counter() - t0
     cpu_model = ""
     try:
         with open("/proc/cpuinfo") as f:
             cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
     except OSError:
         pass
-    return dict(value=sum(q_lens) / dt, unit="query-tokens/s", cores=1, kind="oracle", cpu_model=cpu_model,
+    busy = info["materialise_s"] + info["attention_s"]
+    return dict(value=sum(q_lens) / dt, unit="query-tokens/s", cores=info["threads"], kind="oracle",
+                cpu_model=cpu_model,
                 sample=f"first {len(leaves)} of {len(wl.leaves)} requested branches "
-                       f"({sum(q_lens)} query tokens), materialise + fp64 attention, {dt:.2f} s",
-                seconds=dt), out, leaves, q_lens
+                       f"({sum(q_lens)} query tokens): materialise each branch + fp64 attention in C, "
+                       f"{info['threads']} threads over the branches, {dt:.2f} s wall",
+                seconds=dt, materialise_share=info["materialise_s"] / busy if busy > 0 else 0.0,
+                materialise_thread_seconds=info["materialise_s"],
+                attention_thread_seconds=info["attention_s"]), out, leaves, q_lens
 
 
 def decode_loop(tree, wl, q, out, lse, iters, dev):
@@ -253,30 +289,22 @@ def run_dynamic(args):
     tree.close()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path shards by tree or by KV head "
-              "without any exchange between GPUs); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def measure(name, args, steps, warmup, decode_iters, cpu_sample, calibrate=False, progress=lambda m: None):
+    """Build the synthetic trees of workload `name`, time `steps` decode-attention calls (plan
+    cached, inputs resident in HBM), repeat them with HIP events around every kernel, and compare a
+    sample of the output with the oracle.  Returns the result dictionary of one workload."""
     import numpy as np
     import torch
 
     import paper_2605_10195_amd as spex
     import spex_workloads as sw
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
     dev = "cuda:0"
-    if args.workload in ("dynamic_rebase", "dynamic_mcts"):
-        run_dynamic(args)
-        return
-    if args.token_trees:
-        assert args.workload == "tot_with_drafts" and 1 <= args.token_trees <= 32
+    if args.token_trees and name == "tot_with_drafts":
+        assert 1 <= args.token_trees <= 32
         wl = sw.tot_with_drafts(drafts=args.token_trees, token_trees=True)
     else:
-        wl = sw.WORKLOADS[args.workload]()
+        wl = sw.WORKLOADS[name]()
     if wl.draft_masks is not None:
         wl.draft_masks = np.asarray(wl.draft_masks, dtype=np.uint32)   # marshalled once, not per step
     n_pages = wl.peak_pages()
@@ -286,10 +314,6 @@ def main():
     if unique_bytes > 4e9:
         copies = args.copies or 1
 
-    def progress(msg):
-        if args.progress:
-            print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
-
     progress(f"workload {wl.name}: building {copies} tree(s), {n_pages} pages each")
     t_build = time.perf_counter()
     trees = []
@@ -297,7 +321,7 @@ def main():
         order = None
         if args.placement == "random":
             order = np.random.default_rng(1000 + c).permutation(n_pages).tolist()
-        extra = len(set(wl.leaves)) * (args.decode_iters // wl.page_size + 2) if c == 0 else 0
+        extra = len(set(wl.leaves)) * (decode_iters // wl.page_size + 2) if c == 0 else 0
         if order is not None and extra:
             order = order + list(range(n_pages, n_pages + extra))
         tree = spex.SpexTree(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.q_dtype,
@@ -332,25 +356,25 @@ def main():
     info = trees[0].last_launch_info()
     for i in range(1, copies):
         step(i)
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
 
     progress("warm-up done; timed steps")
     # timed region: K steps, plan cached, no events
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = wall / args.steps * 1e3
+    ms_per_step = wall / steps * 1e3
 
     progress("timed steps done; steps with per-kernel events")
     # same K steps again with HIP events around every kernel (on the launch stream)
     for t in trees:
         t.set_profiling(True)
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     torch.cuda.synchronize()
     wall_prof = time.perf_counter() - t0
@@ -361,12 +385,12 @@ def main():
     b_tok = wl.kv_bytes_per_token()
     kernels = {}
     walked = info["walk_row_tiles"] > 0
-    for name, ms, toks in (("prefix", k_ms[0], 0 if walked else info["prefix_tokens"]),
-                           ("suffix", k_ms[1], 0 if walked else info["suffix_tokens"]),
-                           ("walk", k_ms[3], info["kv_tokens"] if walked else 0)):
+    for kname, ms, toks in (("prefix", k_ms[0], 0 if walked else info["prefix_tokens"]),
+                            ("suffix", k_ms[1], 0 if walked else info["suffix_tokens"]),
+                            ("walk", k_ms[3], info["kv_tokens"] if walked else 0)):
         gbps = toks * b_tok / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
-        kernels[name] = dict(ms=float(ms), kv_tokens=int(toks), kv_bytes=float(toks * b_tok),
-                             gbps=gbps, frac_hbm=gbps / HBM_PEAK_GBPS)
+        kernels[kname] = dict(ms=float(ms), kv_tokens=int(toks), kv_bytes=float(toks * b_tok),
+                              gbps=gbps, frac_hbm=gbps / HBM_PEAK_GBPS)
     part_bytes = 0 if walked else (info["partial_rows"] * (wl.head_dim + 2) * 4 +
                                    nq * wl.num_q_heads * (wl.head_dim + 1) * 4)
     kernels["merge"] = dict(ms=float(k_ms[2]), bytes=float(part_bytes),
@@ -375,14 +399,17 @@ def main():
     dom = kernels[dominant]
     kernel_name = {"suffix": "spex_suffix_attn_kernel", "prefix": "spex_prefix_attn_kernel",
                    "walk": "spex_tree_walk_kernel"}[dominant]
+    if wl.kv_dtype == "f32":
+        kernel_name = "spex_generic_attn_kernel"
+    traffic, traffic_source = profiled_traffic(wl.name, kernel_name)
 
     result = {
         "metric": "tree decode-attn query-tokens/s + achieved HBM GB/s (unique KV bytes), 1 GPU",
         "value": nq / (ms_per_step * 1e-3),
         "unit": "query-tokens/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
@@ -406,24 +433,23 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": kernel_name, "achieved": dom["gbps"], "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": dom["frac_hbm"],
-            "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name)),
+            "traffic": traffic, "traffic_source": traffic_source,
             "bytes_per_launch": dom["kv_bytes"], "ms_per_launch": dom["ms"],
         },
         "kernels": kernels,
         "kernels_ms_sum": float(sum(k_ms)),
-        "ms_per_step_profiled": wall_prof / args.steps * 1e3,
+        "ms_per_step_profiled": wall_prof / steps * 1e3,
         "cold_call_ms": cold_ms,
         "launch": {k: int(v) for k, v in info.items()},
         "build_seconds": t_build,
-        "paper_context": PAPER_CONTEXT,
     }
 
     sample_out = outs[0].clone()          # the decode loop below reuses outs[0] on a grown tree
     progress("per-kernel steps done; decode loop / calibration / cpu baseline")
-    if args.decode_iters > 0:
-        result["decode_loop"] = decode_loop(trees[0], wl, q, outs[0], lses[0], args.decode_iters, dev)
+    if decode_iters > 0:
+        result["decode_loop"] = decode_loop(trees[0], wl, q, outs[0], lses[0], decode_iters, dev)
 
-    if args.calibrate:
+    if calibrate:
         ref_in = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         ref_out = torch.empty_like(ref_in)
         torch.cuda.synchronize()
@@ -431,14 +457,20 @@ def main():
         torch.cuda.synchronize()
         del ref_in, ref_out
 
-    if not args.no_cpu_baseline:
-        n_cpu = args.cpu_sample_leaves or {"tiny_tree": 4, "bfs_tot": 512, "mcts_skewed": 1105,
-                                           "spec_at_scale": 512, "tot_with_drafts": 128,
-                                           "tot_with_drafts_token_trees": 128, "step_prefill": 8}[wl.name]
-        base, ref_out, leaves, q_lens = cpu_baseline(wl, n_cpu)
+    for t in trees:
+        t.close()
+    del trees, outs, lses
+    torch.cuda.empty_cache()
+
+    if cpu_sample > 0:
+        base, ref_out, leaves, q_lens = cpu_baseline(wl, cpu_sample, dev)
         got = sample_out[:ref_out.shape[0]].cpu().numpy().astype(np.float64)
-        base["gpu_vs_oracle_max_abs"] = float(np.max(np.abs(got - ref_out)))
-        base["gpu_vs_oracle_rel_l2"] = float(np.linalg.norm(got - ref_out) / np.linalg.norm(ref_out))
+        d = got - ref_out
+        base["gpu_vs_oracle_max_abs"] = float(np.max(np.abs(d)))
+        base["gpu_vs_oracle_rel_l2"] = float(np.linalg.norm(d) / np.linalg.norm(ref_out))
+        rows_d = np.linalg.norm(d.reshape(-1, d.shape[-1]), axis=1)
+        rows_r = np.linalg.norm(ref_out.reshape(-1, d.shape[-1]), axis=1)
+        base["gpu_vs_oracle_worst_row_rel_l2"] = float(np.max(rows_d / np.maximum(rows_r, 1e-300)))
         result["cpu_baseline"] = base
     else:
         result["cpu_baseline"] = None
@@ -452,15 +484,75 @@ def main():
             visible += ql * (T - ql) + ql * (ql + 1) // 2
         flops = 4.0 * wl.head_dim * wl.num_q_heads * visible
         tfs = flops / (dom["ms"] * 1e-3) / 1e12
-        result["roofline"] = {"bound": "mfma", "kernel": kernel_name, "achieved": tfs, "peak": 2500.0,
-                              "unit": "TFLOP/s", "frac": tfs / 2500.0,
-                              "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, kernel_name)),
+        result["roofline"] = {"bound": "mfma", "kernel": kernel_name, "achieved": tfs,
+                              "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tfs / MFMA_BF16_PEAK_TFLOPS,
+                              "traffic": traffic, "traffic_source": traffic_source,
                               "flops_per_launch": flops, "ms_per_launch": dom["ms"],
                               "hbm_gbps_unique_kv": dom["gbps"]}
+    return result
+
+
+# requested branches the oracle is timed on (about 10-30 s of host work each on 16 threads)
+CPU_SAMPLE = {"tiny_tree": 4, "bfs_tot": 512, "mcts_skewed": 1105, "spec_at_scale": 2048,
+              "tot_with_drafts": 512, "tot_with_drafts_token_trees": 512, "step_prefill": 64}
+# ... and on which the short per-config runs compare the GPU output with it
+PARITY_SAMPLE = {"tiny_tree": 4, "bfs_tot": 128, "mcts_skewed": 256, "spec_at_scale": 256,
+                 "tot_with_drafts": 64, "step_prefill": 8}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by tree or by KV head "
+              "without any exchange between GPUs); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    if args.workload in ("dynamic_rebase", "dynamic_mcts"):
+        run_dynamic(args)
+        return
+
+    def progress(msg):
+        if args.progress:
+            print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+    key = args.workload + ("_token_trees" if args.token_trees and args.workload == "tot_with_drafts" else "")
+    cpu_sample = 0 if args.no_cpu_baseline else (args.cpu_sample_leaves or CPU_SAMPLE[key])
+    result = measure(args.workload, args, args.steps, args.warmup, args.decode_iters, cpu_sample,
+                     calibrate=args.calibrate, progress=progress)
+    result["paper_context"] = PAPER_CONTEXT
+    result["source_sha16"] = source_sha16()
+
+    if not args.no_per_config:
+        # every config of the metric in the same line: short runs of the others, each with its
+        # roofline fraction and its error against the oracle on a sample of branches
+        per = {}
+        for name in PER_CONFIG:
+            if name == args.workload:
+                r = result
+            else:
+                progress(f"per-config run: {name}")
+                r = measure(name, args, min(args.steps, 50), min(args.warmup, 10), 0,
+                            0 if args.no_cpu_baseline else PARITY_SAMPLE[name], progress=progress)
+            rl, cb = r["roofline"], r["cpu_baseline"]
+            per[name] = {
+                "ms_per_step": r["ms_per_step"], "query_tokens_per_s": r["value"],
+                "kernel": rl["kernel"], "kernel_ms": rl["ms_per_launch"], "bound": rl["bound"],
+                "frac": rl["frac"], "achieved": rl["achieved"], "unit": rl["unit"],
+                "hbm_frac_unique_kv_wall": r["hbm_frac_unique_kv"],
+                "kernels": r["config"]["kernels"], "tree_copies_rotated": r["config"]["tree_copies_rotated"],
+                "steps": r["steps"],
+                "parity": None if cb is None else {
+                    "branches": cb["sample"].split(" requested")[0],
+                    "max_abs": cb["gpu_vs_oracle_max_abs"], "rel_l2": cb["gpu_vs_oracle_rel_l2"],
+                    "worst_row_rel_l2": cb["gpu_vs_oracle_worst_row_rel_l2"]},
+            }
+        result["per_config"] = per
     progress("done")
     print(json.dumps(result, default=float))
-    for t in trees:
-        t.close()
 
 
 if __name__ == "__main__":

@@ -69,6 +69,16 @@ typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
  *
  * fp8 (OCP e4m3fn): value = code * scale, one fp32 scale per (page, kv head), separately
  * for K and V, in the caller-owned DEVICE arrays k_scale / v_scale [num_pages][num_kv_heads].
+ * Scales must be finite and >= 0 (0: a page of zeros).
+ *
+ * Value range.  K, V and q must be finite.  The tree-walk and cooperative shared-prefix kernels
+ * (kernel_mode 0 / 3 on MFMA-tiled pools) multiply the softmax weights with V held in IEEE
+ * half precision, which is exact for every fp8 code and for bf16 magnitudes in [2^-14, 65504]:
+ *   - a bf16 V magnitude above 65504 is read as 65504 (saturation, never infinity);
+ *   - a bf16 V magnitude below 2^-14 is read with an absolute error below 2^-24;
+ *   - an fp8 v_scale above 146 (448 * 146 = 65408) is read as 146.
+ * Inside that range both kernel sets meet the same error bound; outside it only kernel_mode 2
+ * (weights split into two bf16 pieces) and the generic kernels reproduce V exactly.
  */
 typedef struct {
   int32_t num_q_heads;  /* multiple of num_kv_heads; query head h uses kv head h / (Hq/Hkv) */

@@ -181,6 +181,7 @@ spex_status_t make_plan(spex_tree *t, const int32_t *leaves, const int32_t *q_le
       *state = 2;
       return SPEX_OK;
     }
+    t->plan.valid = false;  // possibly half changed; replaced below
   }
   *state = 1;
   t->plan_on_device = false;
@@ -616,7 +617,11 @@ static spex_status_t append_tokens_impl(spex_tree_t *t, const spex_node_t *nodes
         n_patch = 0;  // too many for this launch: decode_attention sends them
       }
     } else {
-      pp.clear();  // the structure changed: the next call plans afresh
+      // The lists cannot follow this append (and may be half changed): drop the plan, so that the
+      // next call plans afresh instead of trying the same patch again on arrays already touched.
+      pp.clear();
+      t->plan.valid = false;
+      t->plan_on_device = false;
     }
   }
   const size_t bytes = (dst_ints + 2 * n_patch) * sizeof(int32_t);

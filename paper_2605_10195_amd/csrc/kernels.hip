@@ -621,17 +621,27 @@ __device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], c
   }
 }
 
-// Eight bf16 -> eight fp16 (exact for magnitudes in [2^-14, 65504]; smaller ones lose low bits).
+// Eight bf16 -> eight fp16.  Exact for magnitudes in [2^-14, 65504] (a bf16 has 8 significant bits,
+// an fp16 11).  The conversion rounds toward zero, so a finite magnitude above 65504 becomes
+// +-65504 instead of infinity (0 * inf in the PV product would poison a whole row), and one below
+// 2^-14 keeps the bits an fp16 subnormal has room for (absolute error below 2^-24).
 __device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
   u32x4 r;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float lo = __builtin_bit_cast(float, w[i] << 16);
     const float hi = __builtin_bit_cast(float, w[i] & 0xffff0000u);
-    r[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, f16x2));
+    r[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
   }
   return r;
 }
+
+// Largest V page scale the fp16 operand images can hold: 448 * 146 = 65408 <= 65504.  A larger
+// scale is read as this one (the page's values shrink together instead of turning into infinities).
+constexpr float kMaxVScaleF16 = 146.0f;
+// Smallest K page scale used in a product with a masked (-inf) score: a scale of 0 (an all-zero
+// page) would turn -inf into NaN; with this value the page's scores are 0 to within 1e-27.
+constexpr float kMinKScale = 1.0e-30f;
 
 // Eight e4m3 codes times a page scale -> eight fp16.
 __device__ __forceinline__ u32x4 fp8x8_to_f16x8(uint32_t w0, uint32_t w1, float scale) {
@@ -709,7 +719,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
                                  : vp + (idx - RK) * 512;
       rw.r[k] = load_kv(src);
     }
-    rw.vs = FP8 ? p.v_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g] : 1.f;
+    rw.vs = FP8 ? fminf(p.v_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g], kMaxVScaleF16) : 1.f;
   };
   auto stage_store = [&](const Raw &rw, int buf) {
     u32x4 *dst = img + buf * (NI * 64) + lane;
@@ -743,7 +753,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
     for (int dt = 0; dt < D / 16; ++dt) vh[dt] = __builtin_bit_cast(f16x8, src[(NKI + dt) * 64]);
     const int valid_a = bm.vp_a & 127, valid_b = bm.vp_b & 127;
     float c = p.scale_log2;
-    if (FP8) c *= p.k_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g];
+    if (FP8) c *= fmaxf(p.k_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g], kMinKScale);
     block_math_f16<FP8, D, NTW>(st.qf, st.limit, st.o, st.m, lacc, kf, vh,
                                 task_masked || valid_b == 0, jj < 2 ? valid_a : valid_b,
                                 jj < 2 ? (bm.vp_a >> 7) : (bm.vp_b >> 7), c);
@@ -823,10 +833,10 @@ __device__ __forceinline__ WalkBlock load_walk_block(const WalkArgs &p, int idx,
     b.flags = uniform(static_cast<int>(hi[1]));
     if (FP8) {
       const f32x4 sc = *reinterpret_cast<const f32x4 *>(scl + at * 4);
-      b.ka = sc[0];
-      b.kb = sc[1];
-      b.va = sc[2];
-      b.vb = sc[3];
+      b.ka = fmaxf(sc[0], kMinKScale);
+      b.kb = fmaxf(sc[1], kMinKScale);
+      b.va = fminf(sc[2], kMaxVScaleF16);
+      b.vb = fminf(sc[3], kMaxVScaleF16);
     } else {
       b.ka = b.kb = b.va = b.vb = 1.f;
     }
@@ -841,10 +851,10 @@ __device__ __forceinline__ WalkBlock load_walk_block(const WalkArgs &p, int idx,
   b.flags = sload(p.blocks, r + 5);
   if (FP8) {
     const int64_t ia = static_cast<int64_t>(b.pid_a) * Hkv + g, ib = static_cast<int64_t>(b.pid_b) * Hkv + g;
-    b.ka = sload_f(p.k_scale, ia);
-    b.kb = sload_f(p.k_scale, ib);
-    b.va = sload_f(p.v_scale, ia);
-    b.vb = sload_f(p.v_scale, ib);
+    b.ka = fmaxf(sload_f(p.k_scale, ia), kMinKScale);
+    b.kb = fmaxf(sload_f(p.k_scale, ib), kMinKScale);
+    b.va = fminf(sload_f(p.v_scale, ia), kMaxVScaleF16);
+    b.vb = fminf(sload_f(p.v_scale, ib), kMaxVScaleF16);
   } else {
     b.ka = b.kb = b.va = b.vb = 1.f;
   }

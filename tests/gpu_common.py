@@ -54,6 +54,44 @@ def run_oracle(wl, leaves=None, q_lens=None, q_rows=None, draft_masks=None):
     return sink.tree.attention(leaves, q_lens, q[q_rows], wl.sm_scale, draft_masks=draft_masks)
 
 
+def run_oracle_c(wl, leaves=None, q_lens=None, q_rows=None, draft_masks=None, device="cpu", threads=0):
+    """As run_oracle, through the C form of the oracle (oracle/attention_ref.c), which spreads the
+    requested nodes over threads.  device: where the seeded input generator runs (its values are
+    bit-identical on CPU and GPU); the oracle itself always computes on the host."""
+    from oracle import attention_c
+    sink = OracleSink.for_workload(wl)
+    only = None
+    if leaves is not None:
+        _, parent, _ = wl.node_tokens()
+        only = set()
+        for u in leaves:
+            while u != -1 and u not in only:
+                only.add(u)
+                u = parent[u]
+    sw.replay(wl, sink, device=device, only_nodes=only)
+    qt = sw.gen_queries(wl, device=device)
+    if leaves is None:
+        leaves, q_lens, draft_masks = wl.leaves, wl.q_lens, wl.draft_masks
+    else:
+        qt = qt[torch.as_tensor(np.asarray(q_rows), device=qt.device)]
+    q = queries_fp64(qt)
+    out, lse, _ = attention_c.attention(sink.tree, leaves, q_lens, q, wl.sm_scale, draft_masks=draft_masks,
+                                        threads=threads)
+    return out, lse
+
+
+def error_report(got_o, ref_o):
+    """max abs error, relative L2 over the whole tensor, and the worst relative L2 of a single
+    query row (one query token and head)."""
+    d = got_o - ref_o
+    max_abs = float(np.max(np.abs(d))) if d.size else 0.0
+    rel = float(np.linalg.norm(d) / max(np.linalg.norm(ref_o), 1e-300))
+    rows_d = np.linalg.norm(d.reshape(-1, d.shape[-1]), axis=1)
+    rows_r = np.linalg.norm(ref_o.reshape(-1, d.shape[-1]), axis=1)
+    worst = float(np.max(rows_d / np.maximum(rows_r, 1e-300))) if d.size else 0.0
+    return dict(max_abs=max_abs, rel_l2=rel, worst_row_rel_l2=worst)
+
+
 def assert_close(got, ref, kv_dtype, what=""):
     max_abs_tol, rel_tol = TOL[kv_dtype]
     got_o, got_l = got

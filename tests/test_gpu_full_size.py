@@ -1,15 +1,21 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times
 (automatic chunking, seeded random page placement, interleaved K/V pool).
 
-Configs 2 and 3 are checked on every output; configs 4 and 5 on a sample of requested branches
-spread over the trees (the oracle holds values only for the nodes on the sampled paths)."""
+Every output row of every config is compared with the oracle, in both kernel sets.  Configs 2 and
+3 take one oracle pass; config 4 (8 192 branches, 3.4e11 fp64 multiply-adds), config 5 and the
+many-query workload go through the C form of the oracle in chunks of whole trees, so that the
+host never holds more than a few GB of fp64 K/V.  Each chunk is held to the stated tolerance by
+itself; the last test of a config adds the chunks' sums up to the error over the whole output
+tensor and reports max abs, relative L2 and the worst single row."""
+
+import functools
 
 import numpy as np
 import pytest
 import torch
 
 import spex_workloads as sw
-from gpu_common import assert_close, run_oracle
+from gpu_common import TOL, assert_close, error_report, run_oracle, run_oracle_c
 
 pytestmark = pytest.mark.gpu
 
@@ -26,7 +32,7 @@ def run_full(wl, mode):
     out, lse = tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale)
     torch.cuda.synchronize()
     info = tree.last_launch_info()
-    res = out.cpu().numpy().astype(np.float64), lse.cpu().numpy().astype(np.float64)
+    res = out.cpu().numpy(), lse.cpu().numpy()
     tree.close()
     return res, info
 
@@ -45,31 +51,103 @@ MODES = [0, 2]      # automatic (the tree-walk kernel at these sizes) and shared
 def test_full_config_every_output(name, mode):
     wl = sw.WORKLOADS[name]()
     (out, lse), info = run_full(wl, mode)
+    out, lse = out.astype(np.float64), lse.astype(np.float64)
     assert (info["walk_row_tiles"] > 0) == (mode == 0)
     assert info["kv_tokens"] == wl.unique_kv_tokens()          # every shared page planned once
-    max_abs, rel = assert_close((out, lse), run_oracle(wl), wl.kv_dtype, name)
-    print(f"{name} mode {mode}: max_abs={max_abs:.2e} rel_l2={rel:.2e}")
+    ref = run_oracle(wl)
+    max_abs, rel = assert_close((out, lse), ref, wl.kv_dtype, name)
+    print(f"{name} mode {mode}: {error_report(out, ref[0])}")
 
 
-@pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("name,n_sample", [("spec_at_scale", 96), ("tot_with_drafts", 48), ("step_prefill", 6)])
-def test_full_config_sampled_outputs(name, n_sample, mode):
-    if name == "step_prefill" and mode != 0:
-        pytest.skip("the many-query workload is measured on the tree-walk kernel only")
-    wl = sw.WORKLOADS[name]()
-    (out, lse), info = run_full(wl, mode)
-    assert (info["walk_row_tiles"] > 0) == (mode == 0)
-    assert info["kv_tokens"] == wl.unique_kv_tokens()
-    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
-    picks = np.sort(np.random.default_rng(7).choice(len(wl.leaves), size=n_sample, replace=False)).tolist()
+# ---- configs whose oracle pass is taken in chunks of whole trees
+CHUNKED = {"spec_at_scale": 8, "tot_with_drafts": 2, "step_prefill": 8}
+_totals = {}
+
+
+@functools.lru_cache(maxsize=None)
+def workload(name):
+    return sw.WORKLOADS[name]()
+
+
+@functools.lru_cache(maxsize=2)
+def gpu_outputs(name):
+    """(out, lse) in fp32 as the library wrote them, per kernel mode."""
+    wl = workload(name)
+    res = {}
+    for mode in MODES:
+        (out, lse), info = run_full(wl, mode)
+        assert (info["walk_row_tiles"] > 0) == (mode == 0), (name, mode, info)
+        assert info["kv_tokens"] == wl.unique_kv_tokens()
+        assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+        res[mode] = (out, lse)
+    return res
+
+
+def tree_chunks(wl, n_chunks):
+    """Indices (into wl.leaves) of the requested nodes of each chunk of whole trees."""
+    _, parent, _ = wl.node_tokens()
+    root_of = {}
+
+    def root(u):
+        chain = []
+        while u not in root_of and parent[u] != -1:
+            chain.append(u)
+            u = parent[u]
+        r = root_of.get(u, u)
+        for c in chain + [u]:
+            root_of[c] = r
+        return r
+
+    roots = sorted({root(u) for u in wl.leaves})
+    slot = {r: i * n_chunks // len(roots) for i, r in enumerate(roots)}
+    chunks = [[] for _ in range(n_chunks)]
+    for i, u in enumerate(wl.leaves):
+        chunks[slot[root(u)]].append(i)
+    return chunks
+
+
+CHUNK_CASES = [(name, c) for name, n in CHUNKED.items() for c in range(n)]
+
+
+@pytest.mark.parametrize("name,chunk", CHUNK_CASES, ids=lambda v: str(v))
+def test_full_config_every_output_in_chunks(name, chunk):
+    wl = workload(name)
+    got = gpu_outputs(name)
+    picks = tree_chunks(wl, CHUNKED[name])[chunk]
+    assert picks
     leaves, q_lens, rows = sample_rows(wl, picks)
-    ref = run_oracle(wl, leaves, q_lens, rows)
-    max_abs, rel = assert_close((out[rows], lse[rows]), ref, wl.kv_dtype, name)
-    print(f"{name} mode {mode}: {n_sample} branches sampled, max_abs={max_abs:.2e} rel_l2={rel:.2e}")
-    # a property that holds at any size: rows of one requested node differ only through their
-    # queries, so identical query vectors would give identical rows; here: outputs stay inside the
-    # value range of the inputs (a convex combination of V rows with |v| <= 0.5 * 4.9)
-    assert np.max(np.abs(out)) <= 0.5 * 4.9 + 1e-3
+    ref_o, ref_l = run_oracle_c(wl, leaves, q_lens, rows, device="cuda")
+    tol_abs, tol_rel = TOL[wl.kv_dtype]
+    for mode in MODES:
+        out = got[mode][0][rows].astype(np.float64)
+        lse = got[mode][1][rows].astype(np.float64)
+        rep = error_report(out, ref_o)
+        lse_err = float(np.max(np.abs(lse - ref_l)))
+        print(f"{name} chunk {chunk} mode {mode}: {len(picks)} branches, {rep} lse_max_abs={lse_err:.2e}")
+        assert rep["max_abs"] <= tol_abs and rep["rel_l2"] <= tol_rel and lse_err <= tol_abs, (name, chunk, mode, rep)
+        t = _totals.setdefault((name, mode), dict(rows=0, err2=0.0, ref2=0.0, max_abs=0.0, worst=0.0))
+        t["rows"] += len(rows)
+        t["err2"] += float(np.sum((out - ref_o) ** 2))
+        t["ref2"] += float(np.sum(ref_o ** 2))
+        t["max_abs"] = max(t["max_abs"], rep["max_abs"])
+        t["worst"] = max(t["worst"], rep["worst_row_rel_l2"])
+
+
+@pytest.mark.parametrize("name", list(CHUNKED))
+def test_full_config_whole_tensor_error(name):
+    """Runs after the chunks of `name`: every output row was compared, and the error over the
+    whole tensor meets the bound."""
+    wl = workload(name)
+    tol_abs, tol_rel = TOL[wl.kv_dtype]
+    for mode in MODES:
+        t = _totals.get((name, mode))
+        if t is None:
+            pytest.skip("the chunk tests of this config were not run in this session")
+        assert t["rows"] == sum(wl.q_lens), (t["rows"], sum(wl.q_lens))
+        rel = (t["err2"] / t["ref2"]) ** 0.5
+        print(f"{name} mode {mode}: all {t['rows']} query tokens, max_abs={t['max_abs']:.3e} "
+              f"rel_l2={rel:.3e} worst_row_rel_l2={t['worst']:.3e}")
+        assert t["max_abs"] <= tol_abs and rel <= tol_rel
 
 
 @pytest.mark.parametrize("drafts", [6, 16])
