@@ -77,8 +77,10 @@ typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
  *   - a bf16 V magnitude above 65504 is read as 65504 (saturation, never infinity);
  *   - a bf16 V magnitude below 2^-14 is read with an absolute error below 2^-24;
  *   - an fp8 v_scale above 146 (448 * 146 = 65408) is read as 146.
- * Inside that range both kernel sets meet the same error bound; outside it only kernel_mode 2
- * (weights split into two bf16 pieces) and the generic kernels reproduce V exactly.
+ * The same holds for an fp8 V value (code * v_scale) of magnitude below 2^-14.  Inside the range
+ * every kernel meets the same error bound; outside it only the generic kernels (kernel_mode 1)
+ * reproduce V exactly (kernel_mode 2 runs the cooperative kernel for nodes shared by more than 16
+ * query rows).
  */
 typedef struct {
   int32_t num_q_heads;  /* multiple of num_kv_heads; query head h uses kv head h / (Hq/Hkv) */
@@ -242,6 +244,26 @@ spex_status_t spex_tree_prune(spex_tree_t *tree, spex_node_t node);
 spex_status_t spex_tree_decode_attention(spex_tree_t *tree, const spex_node_t *leaves,
                                          const int32_t *q_lens, int32_t n_leaves, const void *q,
                                          float *out, float *lse, float sm_scale, void *hip_stream);
+
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture set-up, tight
+ * serving loops, harnesses that forbid hipMalloc): spex_tree_decode_attention with the same
+ * arguments, result and kernels, except that the call allocates nothing -- no hipMalloc, hipFree,
+ * pinned host memory or event.  The launch lists and the partial softmax states of the
+ * shared-prefix / suffix kernels go into a 64 MiB array that the library holds statically on every
+ * GPU it runs on, from the load of its code object until the process ends (16 MiB for the lists,
+ * 48 MiB for partial states), instead of the handle's grow-only workspace; the lists are copied
+ * there from pageable host memory on every call, so nothing stays cached on the device between
+ * calls and no plan state is shared with spex_tree_decode_attention's device copy (the host side
+ * of the plan -- planning afresh, patching after appends -- is shared).  A request whose lists or
+ * partial states exceed the array fails with SPEX_ERR_CAPACITY before anything is launched.
+ * Per-kernel profiling is not recorded for these calls.  All calls on one GPU share the array,
+ * whichever handle they use: calls that overlap in time on one GPU (different streams, threads or
+ * handles) race; calls in stream order do not, each call rewrites what it reads.
+ */
+spex_status_t spex_tree_decode_attention_static(spex_tree_t *tree, const spex_node_t *leaves,
+                                                const int32_t *q_lens, int32_t n_leaves, const void *q,
+                                                float *out, float *lse, float sm_scale, void *hip_stream);
 
 /*
  * Sec. 6.5 (composition with token-level speculative decoding): the draft tokens a branch

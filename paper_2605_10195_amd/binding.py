@@ -78,7 +78,8 @@ class WalkView(C.Structure):
 EXPORTS = [
     "spex_pool_bytes", "spex_status_string", "spex_last_device_error", "spex_tree_create",
     "spex_tree_destroy", "spex_tree_fork", "spex_tree_append_step", "spex_tree_append_new_pages",
-    "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_decode_attention_masked", "spex_tree_node_info", "spex_tree_path_pages",
+    "spex_tree_prune", "spex_tree_decode_attention", "spex_tree_decode_attention_masked",
+    "spex_tree_decode_attention_static", "spex_tree_node_info", "spex_tree_path_pages",
     "spex_tree_free_pages", "spex_tree_stats", "spex_tree_plan_dump", "spex_tree_gather_kv",
     "spex_tree_set_tuning", "spex_tree_set_profiling", "spex_tree_read_profile",
     "spex_tree_last_launch_info", "spex_tree_walk_dump", "spex_tree_append_tokens", "spex_tree_append_tokens_quantize", "spex_tree_append_step_quantize",
@@ -119,6 +120,7 @@ def _load():
     lib.spex_tree_prune.argtypes = [vp, i32]
     lib.spex_tree_decode_attention.argtypes = [vp, _I32P, _I32P, i32, vp, vp, vp, f32, vp]
     lib.spex_tree_decode_attention_masked.argtypes = [vp, _I32P, _I32P, _U32P, i32, vp, vp, vp, f32, vp]
+    lib.spex_tree_decode_attention_static.argtypes = [vp, _I32P, _I32P, i32, vp, vp, vp, f32, vp]
     lib.spex_tree_node_info.argtypes = [vp, i32, C.POINTER(NodeInfo)]
     lib.spex_tree_path_pages.argtypes = [vp, i32, _I32P, _I32P, i32, _I32P]
     lib.spex_tree_free_pages.argtypes = [vp, _I32P, i32, _I32P]
@@ -292,7 +294,9 @@ class SpexTree:
     def decode_attention(self, leaves: Sequence[int], q_lens: Optional[Sequence[int]],
                          q: torch.Tensor, sm_scale: float, out: Optional[torch.Tensor] = None,
                          lse: Optional[torch.Tensor] = None, want_lse: bool = True,
-                         draft_masks: Optional[Sequence[int]] = None):
+                         draft_masks: Optional[Sequence[int]] = None, static_scratch: bool = False):
+        """static_scratch: go through spex_tree_decode_attention_static (the entry point that
+        allocates nothing; out and lse must then be given)."""
         la = _i32(leaves)
         qa = None if q_lens is None else _i32(q_lens)
         nq = len(la) if qa is None else int(qa.sum())
@@ -304,7 +308,11 @@ class SpexTree:
             out = torch.empty((nq, self.Hq, self.D), dtype=torch.float32, device=q.device)
         if lse is None and want_lse:
             lse = torch.empty((nq, self.Hq), dtype=torch.float32, device=q.device)
-        if ma is None:
+        if static_scratch:
+            assert ma is None, "the static entry point takes no draft masks"
+            _check(lib.spex_tree_decode_attention_static(self._h, _ptr(la), _ptr(qa), len(la), _dev(q),
+                                                         _dev(out), _dev(lse), float(sm_scale), _stream()))
+        elif ma is None:
             _check(lib.spex_tree_decode_attention(self._h, _ptr(la), _ptr(qa), len(la), _dev(q),
                                                   _dev(out), _dev(lse), float(sm_scale), _stream()))
         else:
@@ -456,6 +464,11 @@ def spex_tree_prune(tree: SpexTree, node: int) -> None:
 
 def spex_tree_decode_attention(tree: SpexTree, leaves, q_lens, q, sm_scale, out=None, lse=None):
     return tree.decode_attention(leaves, q_lens, q, sm_scale, out, lse)
+
+
+def spex_tree_decode_attention_static(tree: SpexTree, leaves, q_lens, q, sm_scale, out, lse=None):
+    return tree.decode_attention(leaves, q_lens, q, sm_scale, out, lse, want_lse=lse is not None,
+                                 static_scratch=True)
 
 
 def spex_tree_decode_attention_masked(tree: SpexTree, leaves, q_lens, draft_masks, q, sm_scale, out=None,

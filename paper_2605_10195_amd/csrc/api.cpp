@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -76,6 +77,7 @@ struct spex_tree {
 
   float *d_part_o = nullptr, *d_part_ml = nullptr;
   int64_t part_cap_rows = 0;
+  std::vector<char> static_stage;  // host image of the lists for the entry point that allocates nothing
 
   int32_t prefix_chunk = 0, suffix_chunk = 0, kernel_mode = 0, walk_row_tiles = 0, walk_waves = 0;
   // Profiling: a ring of event sets, one per decode_attention call since it was enabled.
@@ -359,6 +361,80 @@ spex_status_t ensure_partials(spex_tree *t, int64_t rows) {
                     static_cast<size_t>(cap) * t->cfg.head_dim * sizeof(float)));
   HIP_TRY(hipMalloc(reinterpret_cast<void **>(&t->d_part_ml), static_cast<size_t>(cap) * 2 * sizeof(float)));
   t->part_cap_rows = cap;
+  return SPEX_OK;
+}
+
+// ---- device scratch of the entry point that allocates nothing ----------------------------------
+// One array per GPU, held from the moment the library's code object is loaded on that GPU until
+// the process ends.  Layout: the launch lists of the current call (kStaticPlanBytes), then the
+// partial softmax states of the shared-prefix / suffix kernels.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels get the address that call returns for the
+// current device.
+constexpr size_t kStaticPlanBytes = size_t(16) << 20;
+constexpr size_t kStaticPartBytes = size_t(48) << 20;
+constexpr size_t kStaticScratchBytes = kStaticPlanBytes + kStaticPartBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of the scratch array (looked up once per device).
+spex_status_t static_scratch(unsigned char **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) {
+    g_last_error = "device index beyond the static scratch table";
+    return SPEX_ERR_DEVICE;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) {
+      g_last_error = "hipGetSymbolAddress returned no address for the static scratch";
+      return SPEX_ERR_DEVICE;
+    }
+    g_scratch_ptr[dev] = static_cast<unsigned char *>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return SPEX_OK;
+}
+
+// Copies the lists of the current plan into the plan region of the static scratch (through a
+// pageable host buffer of the handle: no pinned allocation) and fills dp with their addresses.
+spex_status_t upload_plan_static(spex_tree *t, unsigned char *base, DevicePlan *dp, hipStream_t stream) {
+  const spex::Plan &pl = t->plan;
+  const std::vector<int32_t> *arrays[kPlanArrays] = {
+      &pl.prefix_items, &pl.suffix_items, &pl.pg_rec, &pl.qt_rec,
+      &pl.part_indptr, &pl.part_base,    &pl.part_hstride, &pl.merge_qt,
+      &pl.coop_items[0], &pl.coop_items[1], &pl.coop_items[2],
+      &pl.walk_items, &pl.walk_blocks, &pl.walk_qt, &pl.qt_mask};
+  size_t off[kPlanArrays], total = 0;
+  for (int i = 0; i < kPlanArrays; ++i) {
+    off[i] = total;
+    total += align_up(arrays[i]->size() * sizeof(int32_t) + 16, 256);
+  }
+  if (total > kStaticPlanBytes) return SPEX_ERR_CAPACITY;
+  std::vector<char> &h = t->static_stage;
+  if (h.size() < total) h.resize(total);
+  for (int i = 0; i < kPlanArrays; ++i)
+    if (!arrays[i]->empty()) std::memcpy(h.data() + off[i], arrays[i]->data(), arrays[i]->size() * sizeof(int32_t));
+  HIP_TRY(hipMemcpyAsync(base, h.data(), total, hipMemcpyHostToDevice, stream));
+  auto at = [&](int i) { return reinterpret_cast<const int32_t *>(base + off[i]); };
+  dp->prefix_items = at(0);
+  dp->suffix_items = at(1);
+  dp->pg_rec = at(2);
+  dp->qt_rec = at(3);
+  dp->part_indptr = at(4);
+  dp->part_base = at(5);
+  dp->part_hstride = at(6);
+  dp->merge_qt = at(7);
+  for (int c = 0; c < 3; ++c) dp->coop_items[c] = at(8 + c);
+  dp->walk_items = at(11);
+  dp->walk_blocks = at(12);
+  dp->walk_qt = at(13);
+  dp->qt_mask = pl.qt_mask.empty() ? nullptr : at(14);
   return SPEX_OK;
 }
 
@@ -665,6 +741,11 @@ spex_status_t spex_tree_prune(spex_tree_t *t, spex_node_t node) {
   return SPEX_OK;
 }
 
+static spex_status_t decode_attention_impl(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
+                                           const uint32_t *draft_masks, int32_t n_leaves, const void *q,
+                                           float *out, float *lse, float sm_scale, void *hip_stream,
+                                           bool use_static);
+
 spex_status_t spex_tree_decode_attention(spex_tree_t *t, const spex_node_t *leaves,
                                          const int32_t *q_lens, int32_t n_leaves, const void *q,
                                          float *out, float *lse, float sm_scale, void *hip_stream) {
@@ -676,6 +757,20 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
                                                 const int32_t *q_lens, const uint32_t *draft_masks,
                                                 int32_t n_leaves, const void *q, float *out, float *lse,
                                                 float sm_scale, void *hip_stream) {
+  return decode_attention_impl(t, leaves, q_lens, draft_masks, n_leaves, q, out, lse, sm_scale, hip_stream,
+                               false);
+}
+
+spex_status_t spex_tree_decode_attention_static(spex_tree_t *t, const spex_node_t *leaves,
+                                                const int32_t *q_lens, int32_t n_leaves, const void *q,
+                                                float *out, float *lse, float sm_scale, void *hip_stream) {
+  return decode_attention_impl(t, leaves, q_lens, nullptr, n_leaves, q, out, lse, sm_scale, hip_stream, true);
+}
+
+static spex_status_t decode_attention_impl(spex_tree_t *t, const spex_node_t *leaves, const int32_t *q_lens,
+                                           const uint32_t *draft_masks, int32_t n_leaves, const void *q,
+                                           float *out, float *lse, float sm_scale, void *hip_stream,
+                                           bool use_static) {
   if (!t || n_leaves < 0 || (n_leaves > 0 && (!leaves || !q || !out))) return SPEX_ERR_INVALID_ARG;
   if (!t->cfg.k_pool) return SPEX_ERR_INVALID_ARG;
   if (!(sm_scale > 0.f) || std::isinf(sm_scale)) return SPEX_ERR_INVALID_ARG;
@@ -709,17 +804,32 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
     const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &pl));
     if (ss != SPEX_OK) return ss;
   }
-  if (!t->plan_on_device || (use_walk ? !t->device_has_walk : !t->device_has_split)) {
+  unsigned char *sbase = nullptr;
+  DevicePlan static_dp;
+  if (use_static) {
+    // Nothing is allocated on this path: the lists go into the per-device static array (all of them,
+    // every call: another handle's call may have overwritten it), partial results follow them
+    // there, and no events are made.  The handle's own device copy, if any, and the patches that
+    // wait for it are left as they are.
+    if (!use_walk && align_up(static_cast<size_t>(pl.n_partial_rows) * t->cfg.head_dim * 4, 256) +
+                             static_cast<size_t>(pl.n_partial_rows) * 8 > kStaticPartBytes)
+      return SPEX_ERR_CAPACITY;
+    const spex_status_t gs = static_scratch(&sbase);
+    if (gs != SPEX_OK) return gs;
+    const spex_status_t us = upload_plan_static(t, sbase, &static_dp, stream);
+    if (us != SPEX_OK) return us;
+    if (!t->plan_on_device) t->pending_patches.clear();  // no device copy is waiting for them
+  } else if (!t->plan_on_device || (use_walk ? !t->device_has_walk : !t->device_has_split)) {
     const spex_status_t us = upload_plan(t, stream);
     if (us != SPEX_OK) return us;
   } else if (!t->pending_patches.empty()) {
     const spex_status_t us = send_patches(t, stream);
     if (us != SPEX_OK) return us;
   }
-  const DevicePlan &dp = t->dplan;
+  const DevicePlan &dp = use_static ? static_dp : t->dplan;
 
   spex_tree::ProfSlot *slot = nullptr;
-  if (t->profiling) {
+  if (t->profiling && !use_static) {
     if (t->prof.empty()) t->prof.resize(spex_tree::kProfSlots);
     slot = &t->prof[t->prof_calls % spex_tree::kProfSlots];
     ++t->prof_calls;
@@ -762,8 +872,17 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
     return SPEX_OK;
   }
 
-  const spex_status_t ps = ensure_partials(t, pl.n_partial_rows);
-  if (ps != SPEX_OK) return ps;
+  float *part_o = nullptr, *part_ml = nullptr;
+  if (use_static) {
+    part_o = reinterpret_cast<float *>(sbase + kStaticPlanBytes);
+    part_ml = reinterpret_cast<float *>(
+        sbase + kStaticPlanBytes + align_up(static_cast<size_t>(pl.n_partial_rows) * t->cfg.head_dim * 4, 256));
+  } else {
+    const spex_status_t ps = ensure_partials(t, pl.n_partial_rows);
+    if (ps != SPEX_OK) return ps;
+    part_o = t->d_part_o;
+    part_ml = t->d_part_ml;
+  }
 
   spex::AttnArgs a{};
   a.k_pool = t->cfg.k_pool;
@@ -773,8 +892,8 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
   a.q = q;
   a.pg_rec = dp.pg_rec;
   a.qt_rec = dp.qt_rec;
-  a.part_o = t->d_part_o;
-  a.part_ml = t->d_part_ml;
+  a.part_o = part_o;
+  a.part_ml = part_ml;
   a.part_indptr = dp.part_indptr;
   a.part_base = dp.part_base;
   a.part_hstride = dp.part_hstride;
@@ -818,8 +937,8 @@ spex_status_t spex_tree_decode_attention_masked(spex_tree_t *t, const spex_node_
   m.part_indptr = dp.part_indptr;
   m.part_base = dp.part_base;
   m.part_hstride = dp.part_hstride;
-  m.part_o = t->d_part_o;
-  m.part_ml = t->d_part_ml;
+  m.part_o = part_o;
+  m.part_ml = part_ml;
   m.out = out;
   m.lse = lse;
   // The MFMA suffix kernel finishes the rows of single-chunk suffixes itself; the generic kernels
