@@ -106,7 +106,9 @@ typedef struct {
                                 v_pool = k_pool + num_kv_heads tiles interleaves K and V of a page
                                 in one buffer, so that a page's K and V share a 64 KiB region. */
   int32_t walk_row_tiles; /* tree-walk kernel: 16-row tiles per wavefront, 1 / 2 / 4; 0 = automatic */
-  int32_t walk_waves;     /* tree-walk kernel: wavefronts per workgroup, 4 / 8; 0 = 4 */
+  int32_t walk_waves;     /* tree-walk kernel: wavefronts of query rows per workgroup, 2 / 4 / 8; 0 = 4.
+                             2: four wavefronts run, two on each set of rows, and split the rows' path
+                             between them (walk_row_tiles 1 or 2, no draft masks) */
 } spex_config_t;
 
 /* Bytes each of k_pool and v_pool must hold for this config. */
@@ -279,7 +281,7 @@ spex_status_t spex_tree_decode_attention_static(spex_tree_t *tree, const spex_no
  * (SPEX_ERR_INVALID_ARG); a query that sees no position at all is SPEX_ERR_EMPTY_PATH.  Nothing is
  * launched when an error is returned.  The tree-walk kernel (4 wavefronts per workgroup) and the
  * generic kernels evaluate masks; kernel_mode 2 with MFMA-tiled pools, or kernel_mode 3 where the
- * tree-walk kernel cannot take the request or walk_waves is 8, is SPEX_ERR_UNSUPPORTED.
+ * tree-walk kernel cannot take the request or walk_waves is 2 or 8, is SPEX_ERR_UNSUPPORTED.
  * Length patches work as for decode_attention: the masks are part of the cached request.
  */
 spex_status_t spex_tree_decode_attention_masked(spex_tree_t *tree, const spex_node_t *leaves,

@@ -63,7 +63,7 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
     ceil(q_len / cap) pieces of consecutive query tokens, the first
     q_len mod pieces of them one token longer than the rest; "request" below
     means such a piece;
-  * a row block has NW wavefronts: the value asked for (4, 8), 4 if 0;
+  * a row block has NW wavefronts of rows: the value asked for (2, 4, 8), 4 if 0;
   * a request joins the current wavefront while its rows fit, else starts the
     next; wavefront NW or a new root starts a new row block; `qt` lists
     (query token, limit) of the requests in this order; the row of a request in
@@ -381,6 +381,8 @@ class PageTableRef:
                 row_tiles = 4 if G > 32 else 2
         elif G > 16 * row_tiles:
             return dict(none, row_tiles=0)
+        if waves == 2 and row_tiles == 4:
+            return none
         C = 16 * row_tiles
         NW = waves if waves else 4
         pos0: Dict[int, int] = {}
@@ -513,7 +515,7 @@ class PageTableRef:
                 if not real and lanes == 1:
                     continue
                 for g in range(num_kv_heads):
-                    stride = 16 if NW == 4 else 32
+                    stride = 16 if NW <= 4 else 32
                     if real:
                         rb = lane_rbs[l][r]
                         body = [g] + row_blocks[rb][1:]

@@ -416,7 +416,7 @@ class SpexTree:
         return dict(available=v.available, row_tiles=v.row_tiles, waves=nw, plan_state=v.plan_state,
                     row_blocks=arr("row_blocks", (3 + 3 * nw) * v.n_row_blocks),
                     blocks=arr("blocks", 8 * v.n_blocks), qt=arr("qt", 2 * v.n_qt),
-                    items=arr("items", (16 if nw == 4 else 32) * v.n_items))
+                    items=arr("items", (16 if nw <= 4 else 32) * v.n_items))
 
     def set_profiling(self, enabled: bool):
         _check(lib.spex_tree_set_profiling(self._h, int(enabled)))

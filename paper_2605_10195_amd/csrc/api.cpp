@@ -107,7 +107,7 @@ spex_status_t check_config(const spex_config_t *c) {
   if (c->kernel_mode < 0 || c->kernel_mode > 3) return SPEX_ERR_INVALID_ARG;
   if (c->walk_row_tiles != 0 && c->walk_row_tiles != 1 && c->walk_row_tiles != 2 && c->walk_row_tiles != 4)
     return SPEX_ERR_INVALID_ARG;
-  if (c->walk_waves != 0 && c->walk_waves != 4 && c->walk_waves != 8) return SPEX_ERR_INVALID_ARG;
+  if (c->walk_waves != 0 && c->walk_waves != 2 && c->walk_waves != 4 && c->walk_waves != 8) return SPEX_ERR_INVALID_ARG;
   const bool ok = (c->q_dtype == SPEX_F32 && c->kv_dtype == SPEX_F32) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_BF16) ||
                   (c->q_dtype == SPEX_BF16 && c->kv_dtype == SPEX_FP8_E4M3);
@@ -1118,7 +1118,7 @@ spex_status_t spex_tree_set_tuning(spex_tree_t *t, int32_t prefix_chunk_pages,
                                    int32_t walk_row_tiles, int32_t walk_waves) {
   if (!t || prefix_chunk_pages < 0 || suffix_chunk_pages < 0 || kernel_mode < 0 || kernel_mode > 3 ||
       (walk_row_tiles != 0 && walk_row_tiles != 1 && walk_row_tiles != 2 && walk_row_tiles != 4) ||
-      (walk_waves != 0 && walk_waves != 4 && walk_waves != 8))
+      (walk_waves != 0 && walk_waves != 2 && walk_waves != 4 && walk_waves != 8))
     return SPEX_ERR_INVALID_ARG;
   t->prefix_chunk = prefix_chunk_pages;
   t->suffix_chunk = suffix_chunk_pages;

@@ -707,7 +707,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
     u32x4 r[PER];
     float vs;
   };
-  auto stage_load = [&](Raw &rw, const BlockMeta &bm) {
+  auto stage_load = [&](Raw &raw, const BlockMeta &bm) {
     const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
     const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
     const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
@@ -717,25 +717,25 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
       const int idx = k * 4 + w;  // wave-uniform
       const char *src = idx < RK ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
                                  : vp + (idx - RK) * 512;
-      rw.r[k] = load_kv(src);
+      raw.r[k] = load_kv(src);
     }
-    rw.vs = FP8 ? fminf(p.v_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g], kMaxVScaleF16) : 1.f;
+    raw.vs = FP8 ? fminf(p.v_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g], kMaxVScaleF16) : 1.f;
   };
-  auto stage_store = [&](const Raw &rw, int buf) {
+  auto stage_store = [&](const Raw &raw, int buf) {
     u32x4 *dst = img + buf * (NI * 64) + lane;
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
       const int idx = k * 4 + w;
       if (FP8) {
         if (idx < RK) {
-          dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][0], rw.r[k][1]));
-          dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][2], rw.r[k][3]));
+          dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(raw.r[k][0], raw.r[k][1]));
+          dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(raw.r[k][2], raw.r[k][3]));
         } else {
-          dst[(2 * idx) * 64] = fp8x8_to_f16x8(rw.r[k][0], rw.r[k][1], rw.vs);
-          dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(rw.r[k][2], rw.r[k][3], rw.vs);
+          dst[(2 * idx) * 64] = fp8x8_to_f16x8(raw.r[k][0], raw.r[k][1], raw.vs);
+          dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(raw.r[k][2], raw.r[k][3], raw.vs);
         }
       } else {
-        dst[idx * 64] = idx < RK ? rw.r[k] : bf16x8_to_f16x8(rw.r[k]);
+        dst[idx * 64] = idx < RK ? raw.r[k] : bf16x8_to_f16x8(raw.r[k]);
       }
     }
   };
@@ -1012,7 +1012,14 @@ __device__ __forceinline__ void walk_write_rows(float *out, float *lse, const Sh
   }
 }
 
-template <int KV, int D, int NTW, int NW, bool TREE>
+// KS = 1: wavefront w holds rows w * C .. of the row block.  KS = 2 (NW = 4): the lists are made
+// for LW = 2 wavefronts of rows; wavefronts w and w + 2 hold the same rows and split the row
+// block's path between them -- shared blocks alternate between the two halves of the workgroup
+// (two blocks per barrier, each staged by the pair that computes on it), a list wavefront's private
+// blocks alternate likewise -- and at the end the upper pair hands its softmax state to the lower
+// one through LDS.  Per block a wavefront then works on twice the rows, so half as many operand
+// images cross the LDS per row, and a row block's longest path takes half as many steps.
+template <int KV, int D, int NTW, int NW, bool TREE, int KS = 1>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_tree_walk_kernel(WalkArgs p, Shape sh) {
   constexpr bool FP8 = KV == kFP8;
   constexpr int ESZ = FP8 ? 1 : 2;
@@ -1022,17 +1029,22 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   constexpr int NI = NKI + D / 16;         // all operand images per block (1 KiB each)
   constexpr int RAW = FP8 ? NI / 2 : NI;   // 1 KiB global loads per block
   constexpr int RK = FP8 ? NKI / 2 : NKI;  // of which K
-  constexpr int PER = (RAW + NW - 1) / NW;  // global loads per wavefront and block in the shared phase
-  constexpr bool kEven = RAW % NW == 0;     // else the last wavefronts have no piece to fetch
+  static_assert(KS == 1 || (KS == 2 && NW == 4), "the path is split between the two halves of four wavefronts");
+  constexpr int LW = NW / KS;               // wavefronts the lists were made for (each holds C rows)
+  constexpr int PER = (RAW + LW - 1) / LW;  // global loads per wavefront and block in the shared phase
+  constexpr bool kEven = RAW % LW == 0;     // else the last wavefronts have no piece to fetch
   // When K and V each split evenly over the wavefronts, a wavefront's first KPER pieces are K and
   // the others V whatever its index, so the widening code is chosen at compile time instead of
   // being run for every piece and selected away.
-  constexpr bool kSplitKV = RK % NW == 0 && (RAW - RK) % NW == 0;
-  constexpr int KPER = kSplitKV ? RK / NW : 0;
-  constexpr int kItemInts = NW == 4 ? 16 : 32;
+  constexpr bool kSplitKV = RK % LW == 0 && (RAW - RK) % LW == 0;
+  constexpr int KPER = kSplitKV ? RK / LW : 0;
+  constexpr int kItemInts = LW <= 4 ? 16 : 32;
   constexpr int kImgFloats = NI * 64 * 4;
-  constexpr int kLdsFloats =
-      2 * kImgFloats > NW * stage_floats<D>() ? 2 * kImgFloats : NW * stage_floats<D>();
+  // KS = 2: what a wavefront of the upper pair hands over at the end: o, l (as accumulator) and m
+  constexpr int kFoldWaveFloats = NTW * (D / 16) * 256 + NTW * 256 + NTW * 64;
+  // output staging of the wavefronts that write rows (all, or the lower pair), then the hand-over area
+  constexpr int kTailFloats = LW * stage_floats<D>() + (KS == 2 ? LW * kFoldWaveFloats : 0);
+  constexpr int kLdsFloats = 2 * KS * kImgFloats > kTailFloats ? 2 * KS * kImgFloats : kTailFloats;
   __shared__ __attribute__((aligned(16))) float lds[kLdsFloats];
   __shared__ __attribute__((aligned(16))) int32_t rec_lds[kWalkRecCap * 8];
   __shared__ __attribute__((aligned(16))) float scl_lds[FP8 ? kWalkRecCap * 4 : 4];
@@ -1046,16 +1058,19 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   const int n_shared = sload(p.items, ir + 2);
   // per wavefront: private blocks | room << 16; a wavefront's records are followed by the unused
   // part of its room, so n_all spans records that no wavefront walks
+  const int rw = KS == 1 ? w : w % LW;  // the list wavefront whose rows this wavefront holds
+  const int ks = KS == 1 ? 0 : w / LW;  // which part of the path it walks
   int n_all = n_shared, n_priv = 0, priv_begin = blk_begin + n_shared;
 #pragma unroll
-  for (int v = 0; v < NW; ++v) {
+  for (int v = 0; v < LW; ++v) {
     const uint32_t packed = static_cast<uint32_t>(sload(p.items, ir + 3 + v));
     const int npv = static_cast<int>(packed & 0xffffu), room = static_cast<int>(packed >> 16);
     n_all += room;
-    n_priv = v == w ? npv : n_priv;
-    priv_begin += v < w ? room : 0;
+    n_priv = v == rw ? npv : n_priv;
+    priv_begin += v < rw ? room : 0;
   }
   if (n_all == 0) return;  // padding item (whole workgroup)
+  if (KS == 2) n_priv = (n_priv + 1 - ks) >> 1;  // private blocks ks, ks + 2, .. of the list wavefront
   const bool rec_in_lds = n_all <= kWalkRecCap;  // uniform over the workgroup
   if (rec_in_lds) {
     const u32x4 *src = reinterpret_cast<const u32x4 *>(p.blocks + static_cast<int64_t>(blk_begin) * 8);
@@ -1069,8 +1084,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     }
     __syncthreads();
   }
-  const int qt_begin = sload(p.items, ir + 3 + NW + w);
-  const int qt_count = sload(p.items, ir + 3 + 2 * NW + w);
+  const int qt_begin = sload(p.items, ir + 3 + LW + rw);
+  const int qt_count = sload(p.items, ir + 3 + 2 * LW + rw);
   const int rows = qt_count * sh.G;
   const bool has_rows = rows > 0;
   const char *kpool = static_cast<const char *>(p.k_pool);
@@ -1126,46 +1141,46 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     // A block that another row block reads too (flag bit 1) is loaded with the ordinary cache
     // policy, so that the second reader finds it in the L2 of the XCD both run on; everything
     // else is streamed.
-    auto stage_load = [&](Raw &rw, const WalkBlock &bm) {
+    auto stage_load = [&](Raw &raw, const WalkBlock &bm) {
       const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
       const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
       const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
       const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        const bool is_k = kSplitKV ? k < KPER : k * NW + w < RK;
-        const int idx = kSplitKV ? (k < KPER ? k * NW + w : RK + (k - KPER) * NW + w) : k * NW + w;  // wave-uniform
+        const bool is_k = kSplitKV ? k < KPER : k * LW + rw < RK;
+        const int idx = kSplitKV ? (k < KPER ? k * LW + rw : RK + (k - KPER) * LW + rw) : k * LW + rw;  // wave-uniform
         if (!kEven && idx >= RAW) continue;
         const char *src = is_k ? kp + (idx / (RK / 2)) * (TILE_BYTES / 2) + (idx % (RK / 2)) * 512
                                : vp + (idx - RK) * 512;
-        rw.r[k] = (bm.flags & 2) ? *reinterpret_cast<const u32x4 *>(src) : load_kv(src);
+        raw.r[k] = (bm.flags & 2) ? *reinterpret_cast<const u32x4 *>(src) : load_kv(src);
       }
-      rw.vs = jj < 2 ? bm.va : bm.vb;
+      raw.vs = jj < 2 ? bm.va : bm.vb;
     };
-    auto stage_store = [&](const Raw &rw, int buf) {
-      u32x4 *dst = img + buf * (NI * 64) + lane;
+    auto stage_store = [&](const Raw &raw, int buf) {
+      u32x4 *dst = img + (buf * KS + ks) * (NI * 64) + lane;
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
-        const bool is_k = kSplitKV ? k < KPER : k * NW + w < RK;
-        const int idx = kSplitKV ? (k < KPER ? k * NW + w : RK + (k - KPER) * NW + w) : k * NW + w;
+        const bool is_k = kSplitKV ? k < KPER : k * LW + rw < RK;
+        const int idx = kSplitKV ? (k < KPER ? k * LW + rw : RK + (k - KPER) * LW + rw) : k * LW + rw;
         if (!kEven && idx >= RAW) continue;
         if (FP8) {
           if (is_k) {
-            dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][0], rw.r[k][1]));
-            dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(rw.r[k][2], rw.r[k][3]));
+            dst[(2 * idx) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(raw.r[k][0], raw.r[k][1]));
+            dst[(2 * idx + 1) * 64] = __builtin_bit_cast(u32x4, fp8x8_to_bf16x8(raw.r[k][2], raw.r[k][3]));
           } else {
-            dst[(2 * idx) * 64] = fp8x8_to_f16x8(rw.r[k][0], rw.r[k][1], rw.vs);
-            dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(rw.r[k][2], rw.r[k][3], rw.vs);
+            dst[(2 * idx) * 64] = fp8x8_to_f16x8(raw.r[k][0], raw.r[k][1], raw.vs);
+            dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(raw.r[k][2], raw.r[k][3], raw.vs);
           }
         } else {
-          dst[idx * 64] = is_k ? rw.r[k] : bf16x8_to_f16x8(rw.r[k]);
+          dst[idx * 64] = is_k ? raw.r[k] : bf16x8_to_f16x8(raw.r[k]);
         }
       }
     };
     auto compute = [&](int b, const WalkBlock &bm) {
-      const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
+      const int lo = (bm.rows & 0xffff) - rw * C, hi = (bm.rows >> 16) - rw * C;
       if (!has_rows || hi <= 0 || lo >= C) return;  // wave-uniform: none of this wavefront's rows
-      const u32x4 *src = img + (b & 1) * (NI * 64) + lane;
+      const u32x4 *src = img + ((b & 1) * KS + ks) * (NI * 64) + lane;
       const float c = p.scale_log2 * (jj < 2 ? bm.ka : bm.kb);
       f32x4 sa[NTW], sb[NTW];
       {
@@ -1199,17 +1214,39 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     // one path only would make every later wait a wait for all outstanding loads.  (PF = 4 was
     // measured for one row tile per wavefront and for fp8 with two, where the registers allow it:
     // no gain.)
+    if (KS == 2) {
+      // Two blocks per barrier: step s holds blocks 2 s (lower pair of wavefronts) and 2 s + 1
+      // (upper pair); each pair stages and computes its own.  The loads of step s + 1 are in
+      // flight while step s is computed.  With an odd number of blocks the upper pair's last
+      // step only moves a copy of the last block.
+      const int n_steps = (n_shared + 1) >> 1;
+      Raw x;
+      WalkBlock cur = meta(ks);
+      stage_load(x, cur);
+      stage_store(x, 0);
+      __syncthreads();
+      for (int st = 0; st < n_steps; ++st) {
+        const WalkBlock nxt = meta(2 * (st + 1) + ks);
+        stage_load(x, nxt);
+        if (2 * st + ks < n_shared) compute(st, cur);
+        stage_store(x, (st + 1) & 1);
+        cur = nxt;
+        __syncthreads();
+      }
+    }
     constexpr int PF = 2;
     Raw x[PF];
     WalkBlock bmq[PF];
+    if (KS == 1) {
 #pragma unroll
-    for (int k = 0; k < PF; ++k) {
-      bmq[k] = meta(k);
-      stage_load(x[k], bmq[k]);
+      for (int k = 0; k < PF; ++k) {
+        bmq[k] = meta(k);
+        stage_load(x[k], bmq[k]);
+      }
+      stage_store(x[0], 0);
+      __syncthreads();
     }
-    stage_store(x[0], 0);
-    __syncthreads();
-    for (int b = 0; b < n_shared; b += PF) {
+    for (int b = 0; KS == 1 && b < n_shared; b += PF) {
 #pragma unroll
       for (int k = 0; k < PF; ++k) {
         const int c = b + k;             // block computed in this step; x[k] is free again
@@ -1233,8 +1270,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   if (has_rows && n_priv > 0) {
     constexpr int NK = FP8 ? D / 64 : D / 32;  // 128-bit loads per K half-tile
     constexpr int NV = FP8 ? D / 32 : D / 16;
-    u32x4 kr[2][NK], vr[NV];
-    auto issue_k = [&](const WalkBlock &bm) {
+    auto issue_k = [&](u32x4 (&kr)[2][NK], const WalkBlock &bm) {
       const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
       const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
       const char *kp = kpool + (m16 < 8 ? tile_a : tile_b) * TILE_BYTES + k_lane_off;
@@ -1243,17 +1279,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
 #pragma unroll
         for (int s = 0; s < NK; ++s) kr[t][s] = load_kv(kp + t * (TILE_BYTES / 2) + s * 512);
     };
-    auto issue_v = [&](const WalkBlock &bm) {
+    auto issue_v = [&](u32x4 (&vr)[NV], const WalkBlock &bm) {
       const int64_t tile_a = (static_cast<int64_t>(bm.pid_a) * sh.page_tiles + g);
       const int64_t tile_b = (static_cast<int64_t>(bm.pid_b) * sh.page_tiles + g);
       const char *vp = vpool + (jj < 2 ? tile_a : tile_b) * TILE_BYTES + v_lane_off;
 #pragma unroll
       for (int s = 0; s < NV; ++s) vr[s] = load_kv(vp + s * 512);
     };
-    // One block: scores from the K registers, which are then refilled with the next block's K
-    // while the softmax runs; the V registers are refilled after the PV product.
-    auto step = [&](const WalkBlock &bm, const WalkBlock &nxt, bool more) {
-      const int lo = (bm.rows & 0xffff) - w * C, hi = (bm.rows >> 16) - w * C;
+    // One block: scores from the K registers, which are then refilled (with the block `refill`,
+    // if `more`) while the softmax runs; the V registers are refilled as soon as they are widened.
+    auto step = [&](u32x4 (&kr)[2][NK], u32x4 (&vr)[NV], const WalkBlock &bm, const WalkBlock &refill, bool more) {
+      const int lo = (bm.rows & 0xffff) - rw * C, hi = (bm.rows >> 16) - rw * C;
       const float c = p.scale_log2 * (jj < 2 ? bm.ka : bm.kb), vs = jj < 2 ? bm.va : bm.vb;
       bf16x8 kf[2][D / 32];
       if (FP8) {
@@ -1272,7 +1308,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       }
       f32x4 sa[NTW], sb[NTW];
       walk_scores<D, NTW>(qf, kf, lo, hi, sa, sb);
-      if (more) issue_k(nxt);
+      if (more) issue_k(kr, refill);
       f16x8 vh[D / 16];
       if (FP8) {
 #pragma unroll
@@ -1284,31 +1320,69 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) vh[s] = __builtin_bit_cast(f16x8, bf16x8_to_f16x8(vr[s]));
       }
-      if (more) issue_v(nxt);
+      if (more) issue_v(vr, refill);
       walk_softmax_pv<FP8, TREE, D, NTW>(limit, qidx, dmask, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
                                    (jj < 2 ? bm.vp_a : bm.vp_b) & 127, (jj < 2 ? bm.vp_a : bm.vp_b) >> 7,
                                    c, slack, lo, hi);
     };
-    const int priv_last = priv_begin + n_priv - 1;
-    auto rec_at = [&](int idx) {
-      return load_walk_block<FP8>(p, idx, g, sh.Hkv, rec_in_lds, rec_lds, scl_lds, blk_begin);
+    // the j-th private block of this wavefront (past the end: the last one)
+    auto rec_at = [&](int j) {
+      const int jc = j < n_priv ? j : n_priv - 1;
+      return load_walk_block<FP8>(p, priv_begin + ks + KS * jc, g, sh.Hkv, rec_in_lds, rec_lds, scl_lds, blk_begin);
     };
-    WalkBlock cur = rec_at(priv_begin);
-    WalkBlock nxt = rec_at(priv_begin + 1 < priv_last ? priv_begin + 1 : priv_last);
-    issue_k(cur);
-    issue_v(cur);
-    for (int i = 0; i + 1 < n_priv; ++i) {
-      const int i2 = priv_begin + i + 2;
-      const WalkBlock nxt2 = rec_at(i2 < priv_last ? i2 : priv_last);
-      step(cur, nxt, true);
-      cur = nxt;
-      nxt = nxt2;
+    {
+      u32x4 kr[2][NK], vr[NV];
+      WalkBlock cur = rec_at(0);
+      WalkBlock nxt = rec_at(1);
+      issue_k(kr, cur);
+      issue_v(vr, cur);
+      for (int i = 0; i + 1 < n_priv; ++i) {
+        const WalkBlock nxt2 = rec_at(i + 2);
+        step(kr, vr, cur, nxt, true);
+        cur = nxt;
+        nxt = nxt2;
+      }
+      step(kr, vr, cur, cur, false);
     }
-    step(cur, cur, false);
+  }
+
+  // ---- KS = 2: the upper pair hands its state to the lower pair, which folds it into its own
+  // (log-sum-exp rule on the two references).  The LDS images are dead after the last barrier of
+  // phase 1, and phase 2 does not touch LDS, so the hand-over area may lie behind the output staging.
+  if (KS == 2) {
+    float *fold = lds + LW * stage_floats<D>() + rw * kFoldWaveFloats;
+    f32x4 *fo = reinterpret_cast<f32x4 *>(fold) + lane;                               // [nt][dt][lane]
+    f32x4 *fl = reinterpret_cast<f32x4 *>(fold + NTW * (D / 16) * 256) + lane;         // [nt][lane]
+    float *fm = fold + NTW * (D / 16) * 256 + NTW * 256 + lane;                        // [nt][lane]
+    if (has_rows && ks == 1) {
+#pragma unroll
+      for (int nt = 0; nt < NTW; ++nt) {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) fo[(nt * (D / 16) + dt) * 64] = o[nt][dt];
+        fl[nt * 64] = lacc[nt];
+        fm[nt * 64] = m[nt];
+      }
+    }
+    __syncthreads();
+    if (has_rows && ks == 0) {
+#pragma unroll
+      for (int nt = 0; nt < NTW; ++nt) {
+        const float m1 = fm[nt * 64];
+        const float mn = fmaxf(m[nt], m1);
+        // a side that saw nothing still has the (finite) start value of m: its factor is 0, or 1
+        // where neither saw anything (rows past the end of the wavefront's rows)
+        const float a0 = fast_exp2(FP8 ? m[nt] - mn : (m[nt] - mn) * p.scale_log2);
+        const float a1 = fast_exp2(FP8 ? m1 - mn : (m1 - mn) * p.scale_log2);
+        m[nt] = mn;
+        lacc[nt] = lacc[nt] * a0 + fl[nt * 64] * a1;
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) o[nt][dt] = o[nt][dt] * a0 + fo[(nt * (D / 16) + dt) * 64] * a1;
+      }
+    }
   }
 
   // ---- output.  The LDS images are dead after the last barrier of phase 1.
-  if (has_rows) {
+  if (has_rows && ks == 0) {
     float m_log2[NTW];
 #pragma unroll
     for (int nt = 0; nt < NTW; ++nt) m_log2[nt] = FP8 ? m[nt] : m[nt] * p.scale_log2;
@@ -1785,13 +1859,23 @@ template <int KV, int D>
 static hipError_t launch_walk_nw(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {
   if (a.qt_mask)  // draft-tree masks: 4 wavefronts per workgroup only
     return waves == 4 ? launch_walk_ntw<KV, D, 4, true>(sh, a, ntw, stream) : hipErrorInvalidValue;
+  if (waves == 2) {  // lists for two wavefronts of rows, walked by four: the path is split in two
+    const dim3 grid(a.n_items), block(256);
+    if (ntw == 1)
+      hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 1, 4, false, 2>), grid, block, 0, stream, a, sh);
+    else if (ntw == 2)
+      hipLaunchKernelGGL((spex_tree_walk_kernel<KV, D, 2, 4, false, 2>), grid, block, 0, stream, a, sh);
+    else
+      return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
   return waves == 4 ? launch_walk_ntw<KV, D, 4, false>(sh, a, ntw, stream)
                     : launch_walk_ntw<KV, D, 8, false>(sh, a, ntw, stream);
 }
 
 hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {
   if (a.n_items <= 0) return hipSuccess;
-  if (!has_mfma_kernel(sh) || (ntw != 1 && ntw != 2 && ntw != 4) || (waves != 4 && waves != 8))
+  if (!has_mfma_kernel(sh) || (ntw != 1 && ntw != 2 && ntw != 4) || (waves != 2 && waves != 4 && waves != 8))
     return hipErrorInvalidValue;
   if (sh.kv_dtype == kBF16)
     return sh.D == 64 ? launch_walk_nw<kBF16, 64>(sh, a, ntw, waves, stream)

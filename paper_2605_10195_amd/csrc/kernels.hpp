@@ -46,7 +46,7 @@ struct WalkArgs {
   const void *k_pool, *v_pool;
   const float *k_scale, *v_scale;
   const void *q;
-  const int32_t *items;   // 16 (4 wavefronts per workgroup) or 32 (8) ints per workgroup: {kv head,
+  const int32_t *items;   // 16 (2 or 4 wavefronts of rows per row block) or 32 (8) ints per workgroup: {kv head,
                           //   first block, shared blocks, private blocks of wavefronts 0..NW-1,
                           //   first qt_rec entry of each wavefront, qt_rec entries of each
                           //   wavefront, zeros.., row block}; no blocks = padding
@@ -124,8 +124,9 @@ hipError_t launch_patch(int32_t *blob, const int32_t *pairs, int32_t n, hipStrea
 // Cooperative shared-prefix kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront (64 * ntw rows
 // per workgroup).  One work item per workgroup.  Only for shapes with has_mfma_kernel().
 hipError_t launch_prefix_coop(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream);
-// Tree-walk kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront and waves in {4, 8} = wavefronts
-// per workgroup the lists were built for.
+// Tree-walk kernel; ntw in {1, 2, 4} = 16-row tiles per wavefront and waves in {2, 4, 8} = wavefronts
+// of rows per row block the lists were built for (2: run by four wavefronts, two on each set of
+// rows, which split the path between them; ntw 1 or 2, no draft masks).
 hipError_t launch_tree_walk(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream);
 
 }  // namespace spex

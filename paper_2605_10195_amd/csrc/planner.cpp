@@ -422,14 +422,15 @@ PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
 //    for (1, 2 or 4) or, if 0: 1 if no request has more than 16 rows (raised to 2 when some root
 //    has more than 64 rows below it and sum over roots of ceil(rows / 128), times Hkv, is at least
 //    512), 2 if none has more than 32, else 2 (4 if G > 32).  No lists (walk_ok = false) if
-//    G > 16 * NTW, i.e. if one query token does not fit a wavefront.
+//    G > 16 * NTW, i.e. if one query token does not fit a wavefront, or if NW = 2 is asked for and NTW is 4.
 //  * roots in order of first appearance in the request list; the requests of a root sorted by
 //    path (node ids root first, lexicographic, a proper prefix first), ties in request order;
 //    so the requests below any node are consecutive.
 //  * a request with more than cap = C / G query tokens is cut into ceil(q_len / cap) pieces of
 //    consecutive query tokens, the first (q_len mod pieces) of them one token longer than the
 //    others; "request" in the rules below means such a piece.
-//  * a row block has NW wavefronts: the value asked for (4 or 8), 4 if 0.
+//  * a row block has NW wavefronts of rows: the value asked for (2, 4 or 8), 4 if 0.  (With 2 the
+//    kernel still runs four wavefronts: two per wavefront of rows, which split the path between them.)
 //  * packing: a request joins the current wavefront if its rows still fit, else it starts the
 //    next one; wavefront NW, or a new root, starts a new row block.  walk_qt lists
 //    {query token, limit} of the requests in this order.  Wavefronts without requests have
@@ -526,6 +527,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   } else if (G > 16 * ntw) {
     return;
   }
+  if (walk_waves == 2 && ntw == 4) return;  // the kernel that splits the path holds at most two row tiles
   pl.walk_row_tiles = ntw;
   pl.req_walk_qt.assign(n_leaves, -1);
   pl.req_walk_home.assign(n_leaves, -2);
@@ -539,7 +541,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   // the default even for roots with more rows than one 4-wavefront row block takes.
   const int32_t NW = walk_waves == 0 ? 4 : walk_waves;
   pl.walk_waves = NW;
-  const int32_t rb_ints = 3 + 3 * NW, item_ints = NW == 4 ? 16 : 32;
+  const int32_t rb_ints = 3 + 3 * NW, item_ints = NW <= 4 ? 16 : 32;
 
   std::vector<int32_t> order(n_leaves);
   std::iota(order.begin(), order.end(), 0);

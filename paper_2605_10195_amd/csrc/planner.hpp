@@ -82,7 +82,7 @@ struct Plan {
   // ---- tree-walk lists (see the rules above build_walk in planner.cpp)
   bool walk_ok = false;         // every requested node's rows fit one wavefront
   int32_t walk_row_tiles = 0;   // 16-row tiles per wavefront (1, 2 or 4)
-  int32_t walk_waves = 0;       // NW: wavefronts per row block = per workgroup (4 or 8)
+  int32_t walk_waves = 0;       // NW: wavefronts of rows per row block (2, 4 or 8; with 2 the kernel runs two wavefronts on each)
   int32_t req_walk_row_tiles = -1, req_walk_waves = -1;
   // row blocks: 3 + 3 * NW ints each
   //   {root node, first block, shared blocks, private blocks of wavefronts 0..NW-1 as
@@ -97,10 +97,10 @@ struct Plan {
   static constexpr int kBlockInts = 8;
   std::vector<int32_t> walk_blocks;
   std::vector<int32_t> walk_qt;     // {query token, limit} in row order
-  // launch order: item_ints() = 16 (NW = 4) or 32 (NW = 8) ints per workgroup {kv head, first
+  // launch order: item_ints() = 16 (NW <= 4) or 32 (NW = 8) ints per workgroup {kv head, first
   //   block, shared blocks, private blocks[NW], walk_qt first[NW], walk_qt count[NW], zeros..,
   //   row block index in the last int}; a padding item has row block index -1 and no blocks
-  int item_ints() const { return walk_waves == 4 ? 16 : 32; }
+  int item_ints() const { return walk_waves <= 4 ? 16 : 32; }
   std::vector<int32_t> walk_items;
   int32_t walk_real_items = 0;       // workgroups with work
   int32_t walk_max_item_blocks = 0;  // longest workgroup: shared blocks + most private blocks of a wavefront

@@ -114,7 +114,7 @@ def walk_applies(wl, row_tiles=0):
 
 
 @pytest.mark.parametrize("case", RANDOM_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")
-@pytest.mark.parametrize("row_tiles,waves", [(0, 0), (1, 4), (2, 4), (4, 4), (1, 8), (2, 8), (4, 8)])
+@pytest.mark.parametrize("row_tiles,waves", [(0, 0), (1, 4), (2, 4), (4, 4), (1, 8), (2, 8), (4, 8), (1, 2), (2, 2)])
 def test_random_trees_tree_walk_kernel(case, row_tiles, waves):
     import paper_2605_10195_amd as spex
     wl = sw.random_trace(case["seed"], heads=case["heads"], kv_dtype=case["kv_dtype"],
@@ -130,17 +130,18 @@ def test_random_trees_tree_walk_kernel(case, row_tiles, waves):
     info = tree.last_launch_info()
     tree.close()
     assert info["walk_row_tiles"] == (row_tiles or info["walk_row_tiles"]) and info["walk_row_tiles"] > 0
-    assert info["walk_waves"] == (waves or info["walk_waves"]) and info["walk_waves"] in (4, 8)
+    assert info["walk_waves"] == (waves or info["walk_waves"]) and info["walk_waves"] in (2, 4, 8)
     assert_close(got, run_oracle(wl), case["kv_dtype"], wl.name)
 
 
+@pytest.mark.parametrize("waves", [0, 2])
 @pytest.mark.parametrize("kv_dtype", ["bf16", "fp8_e4m3"])
-def test_tree_walk_kernel_with_more_blocks_than_its_lds_copy_holds(kv_dtype):
+def test_tree_walk_kernel_with_more_blocks_than_its_lds_copy_holds(kv_dtype, waves):
     # 9 000-token prompt + 1 100-token steps: > 256 two-page blocks per row block, so the kernel
     # reads its block records through the scalar path instead of from LDS
     wl = sw.bfs_tot(n_queries=1, prompt=9000, step=1100, width=4, keep=2, depth=2, heads=(8, 2, 128),
                     kv_dtype=kv_dtype)
-    tree = build_gpu_tree(wl, kernel_mode=3)
+    tree = build_gpu_tree(wl, kernel_mode=3, walk_waves=waves)
     got = run_gpu(wl, tree=tree)
     dump = tree.walk_dump(wl.leaves, wl.q_lens)
     tree.close()
@@ -189,7 +190,7 @@ REDUCED = [
 
 
 @pytest.mark.parametrize("wl", REDUCED, ids=lambda w: w.name + "_" + w.kv_dtype)
-@pytest.mark.parametrize("mode,waves", [(2, 0), (3, 4), (3, 8)])
+@pytest.mark.parametrize("mode,waves", [(2, 0), (3, 4), (3, 8), (3, 2)])
 def test_reduced_config_shapes_match_oracle(wl, mode, waves):
     assert_close(run_gpu(wl, kernel_mode=mode, walk_waves=waves), run_oracle(wl), wl.kv_dtype,
                  f"{wl.name} mode {mode} waves {waves}")

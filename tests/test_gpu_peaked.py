@@ -57,7 +57,7 @@ def run(wl, mode, row_tiles, waves, **kw):
 SHAPES = ["bfs_bf16", "spec_bf16", "mcts_bf16", "drafts_fp8"]
 KINDS = ["rising", "falling", "negative", "spike_root", "spike_mid", "spike_last", "rising_spike",
          "scale_x8", "scale_div8"]
-LAUNCHES = [(2, 0, 0), (3, 0, 0), (3, 2, 8)]
+LAUNCHES = [(2, 0, 0), (3, 0, 0), (3, 2, 8), (3, 2, 2)]
 
 
 @pytest.mark.parametrize("launch", LAUNCHES, ids=lambda l: "mode%d_t%d_w%d" % l)
@@ -69,7 +69,7 @@ def test_peaked_softmax_matches_oracle(shape, kind, launch):
     check(wl, got, reference(shape, kind), f"{shape} {kind} {launch}")
 
 
-@pytest.mark.parametrize("launch", [(3, 1, 4), (3, 2, 4), (3, 4, 4), (3, 1, 8), (3, 4, 8)],
+@pytest.mark.parametrize("launch", [(3, 1, 4), (3, 2, 4), (3, 4, 4), (3, 1, 8), (3, 4, 8), (3, 1, 2)],
                          ids=lambda l: "mode%d_t%d_w%d" % l)
 @pytest.mark.parametrize("kind", ["rising", "spike_last", "rising_spike"])
 @pytest.mark.parametrize("shape", SHAPES)
