@@ -63,7 +63,9 @@ q_len_i * G rows and C = 16 * row_tiles rows fit one wavefront:
     ceil(q_len / cap) pieces of consecutive query tokens, the first
     q_len mod pieces of them one token longer than the rest; "request" below
     means such a piece;
-  * a row block has NW wavefronts of rows: the value asked for (2, 4, 8), 4 if 0;
+  * a row block has NW wavefronts of rows: the value asked for (2, 4, 8); if 0: 8 if there are no
+    draft masks, NTW <= 2, no request has more than C rows, some root has more than 4 C rows and
+    sum over roots of ceil(rows / (8 C)), times Hkv, is at least 1024; else 4;
   * a request joins the current wavefront while its rows fit, else starts the
     next; wavefront NW or a new root starts a new row block; `qt` lists
     (query token, limit) of the requests in this order; the row of a request in
@@ -385,6 +387,10 @@ class PageTableRef:
             return none
         C = 16 * row_tiles
         NW = waves if waves else 4
+        if waves == 0 and draft_masks is None and row_tiles <= 2 and max(rows) <= C \
+                and max(root_rows.values()) > 4 * C \
+                and sum(-(-r // (8 * C)) for r in root_rows.values()) * num_kv_heads >= 1024:
+            NW = 8
         pos0: Dict[int, int] = {}
         for path in paths:
             t = 0
