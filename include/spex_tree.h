@@ -279,9 +279,10 @@ spex_status_t spex_tree_decode_attention_static(spex_tree_t *tree, const spex_no
  *     decode_attention's result.  NULL = that chain.
  * With masks, q_lens must be given and q_lens[i] <= 32; bits at or above q_lens[i] must be clear
  * (SPEX_ERR_INVALID_ARG); a query that sees no position at all is SPEX_ERR_EMPTY_PATH.  Nothing is
- * launched when an error is returned.  The tree-walk kernel (4 wavefronts per workgroup) and the
- * generic kernels evaluate masks; kernel_mode 2 with MFMA-tiled pools, or kernel_mode 3 where the
- * tree-walk kernel cannot take the request or walk_waves is 2 or 8, is SPEX_ERR_UNSUPPORTED.
+ * launched when an error is returned.  Every kernel set evaluates masks (the automatic choice
+ * between them is the one of decode_attention), except the tree-walk kernel that splits the path:
+ * kernel_mode 3 where the tree-walk kernel cannot take the request, or with walk_waves 2, is
+ * SPEX_ERR_UNSUPPORTED.
  * Length patches work as for decode_attention: the masks are part of the cached request.
  */
 spex_status_t spex_tree_decode_attention_masked(spex_tree_t *tree, const spex_node_t *leaves,

@@ -789,16 +789,15 @@ static spex_status_t decode_attention_impl(spex_tree_t *t, const spex_node_t *le
   // and 65 at 96 (bf16, 32 / 8 heads of 128).  Only the lists of the chosen kernels are built.
   bool want_walk = (t->kernel_mode == 0 || t->kernel_mode == 3) && spex::has_mfma_kernel(t->shape);
   const bool tree_masks = draft_masks != nullptr;
-  if (want_walk && t->kernel_mode == 0 && !tree_masks && !pl.has_walk && obviously_split(pl))
+  if (want_walk && t->kernel_mode == 0 && !pl.has_walk && obviously_split(pl))
     want_walk = false;  // few requests with long paths: the split path without building the other lists
   if (want_walk) t->planner.ensure_walk(*t->pt, &pl);
-  // Draft-tree masks are understood by the tree-walk kernel (4 wavefronts per workgroup) and by
-  // the generic kernels.
-  const bool walk_possible = want_walk && pl.walk_ok && (!tree_masks || pl.walk_waves == 4);
+  // Draft-tree masks are understood by every kernel but the tree-walk kernel that splits the path
+  // (walk_waves 2).
+  const bool walk_possible = want_walk && pl.walk_ok && (!tree_masks || pl.walk_waves != 2);
   if (t->kernel_mode == 3 && !walk_possible) return SPEX_ERR_UNSUPPORTED;
-  if (t->kernel_mode == 2 && tree_masks && spex::has_mfma_kernel(t->shape)) return SPEX_ERR_UNSUPPORTED;
   const int32_t short_walk = short_walk_blocks(pl.walk_real_items);
-  const bool use_walk = walk_possible && (t->kernel_mode == 3 || tree_masks || pl.walk_real_items >= 128 ||
+  const bool use_walk = walk_possible && (t->kernel_mode == 3 || pl.walk_real_items >= 128 ||
                                           pl.walk_max_item_blocks <= short_walk);
   if (!use_walk) {
     const spex_status_t ss = plan_status(t, t->planner.ensure_split(*t->pt, &pl));
@@ -901,7 +900,7 @@ static spex_status_t decode_attention_impl(spex_tree_t *t, const spex_node_t *le
   a.lse = lse;
   a.scale_log2 = sm_scale * 1.4426950408889634f;
   a.qt_mask = dp.qt_mask;
-  const bool generic = t->kernel_mode == 1 || tree_masks;
+  const bool generic = t->kernel_mode == 1;
 
   const int32_t n_prefix_items = static_cast<int32_t>(pl.prefix_items.size() / spex::Plan::kItemInts);
   const int32_t n_suffix_items = static_cast<int32_t>(pl.suffix_items.size() / spex::Plan::kItemInts);

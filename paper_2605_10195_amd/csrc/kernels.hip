@@ -180,9 +180,40 @@ template <int D, int NT>
 struct RowState {
   bf16x8 qf[NT][D / 32];  // query operand: dims s*32 + 8*jj .. +7
   int limit[NT], qtok[NT];
+  int qidx[NT];           // draft token trees: index of the row's query in its request
+  uint32_t dmask[NT];     //   and its visibility mask among the request's drafts
   f32x4 o[NT][D / 16];
   float m[NT], l[NT];     // l is this lane's share; summed over the four jj at the end
 };
+
+// Scores of the lane's 8 tokens that the row does not see become -inf.  Chain: the first
+// limit - pos positions of the page are visible.  Draft token tree: positions below
+// base = limit - 1 - qidx are visible, position base + k iff bit k of the row's mask is set; shifting
+// {mask, 32 ones} right by (first position of the lane's tokens - base + 32) puts the visibility of
+// the lane's 8 tokens into the low 8 bits.
+template <bool TREE>
+__device__ __forceinline__ void mask_scores(float (&x)[8], int limit, int qidx, uint32_t dmask, int valid_l,
+                                            int pos_l, bool row_in) {
+  const int jj = (threadIdx.x & 63) >> 4;
+  const int first = 8 * (jj & 1);
+  if (TREE) {
+    const int base = limit - 1 - qidx;
+    const int sh = pos_l + first - base + 32;
+    const uint64_t bits = (static_cast<uint64_t>(dmask) << 32) | 0xffffffffull;
+    uint32_t vm = sh <= 0 ? 0xffu : (sh >= 64 ? 0u : static_cast<uint32_t>(bits >> sh) & 0xffu);
+    const int have = valid_l - first;  // tokens of the lane's 8 that exist
+    vm = row_in ? vm : 0u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (i < have && ((vm >> i) & 1u)) ? x[i] : kNegInf;
+  } else {
+    int vis = limit - pos_l;
+    vis = vis < valid_l ? vis : valid_l;
+    vis -= first;
+    vis = row_in ? vis : 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
+  }
+}
 
 template <int D, int NT>
 __device__ __forceinline__ void load_rows(const AttnArgs &p, const Shape &sh, const Item &cur,
@@ -194,6 +225,8 @@ __device__ __forceinline__ void load_rows(const AttnArgs &p, const Shape &sh, co
     const int r = row_base + nt * 16 + m16;
     st.limit[nt] = INT_MAX;
     st.qtok[nt] = 0;
+    st.qidx[nt] = 0;
+    st.dmask[nt] = 0;
     st.m[nt] = kNegInf;
     st.l[nt] = 0.f;
 #pragma unroll
@@ -202,6 +235,11 @@ __device__ __forceinline__ void load_rows(const AttnArgs &p, const Shape &sh, co
       const int2 qr = *reinterpret_cast<const int2 *>(p.qt_rec + 2 * (cur.qt_begin + r / G));
       st.limit[nt] = qr.y;
       st.qtok[nt] = qr.x;
+      if (p.qt_mask) {
+        const int2 dm = *reinterpret_cast<const int2 *>(p.qt_mask + 2 * qr.x);
+        st.qidx[nt] = dm.x;
+        st.dmask[nt] = static_cast<uint32_t>(dm.y);
+      }
       const uint16_t *qp = static_cast<const uint16_t *>(p.q) +
                            (static_cast<int64_t>(qr.x) * sh.Hq + cur.g * G + r % G) * D + jj * 8;
 #pragma unroll
@@ -219,7 +257,7 @@ __device__ __forceinline__ void load_rows(const AttnArgs &p, const Shape &sh, co
 // tile come from page A, rows 8-15 from page B.  vf[dt]: V^T, dims dt*16.., tokens 8*(jj&1)..+7 of
 // page jj/2.  After the two score tiles this lane holds the scores of exactly those 8 tokens, i.e.
 // the operand layout of the PV product, so P never leaves the registers.
-template <int D, int NT>
+template <bool TREE, int D, int NT>
 __device__ __forceinline__ void block_math(RowState<D, NT> &st, const bf16x8 (&kf)[2][D / 32],
                                            const bf16x8 (&vf)[D / 16], bool masked, int valid_l,
                                            int pos_l, float c, float vs) {
@@ -238,13 +276,7 @@ __device__ __forceinline__ void block_math(RowState<D, NT> &st, const bf16x8 (&k
       x[i] = sa[i] * c;
       x[4 + i] = sb[i] * c;
     }
-    if (masked) {
-      int vis = st.limit[nt] - pos_l;
-      vis = vis < valid_l ? vis : valid_l;
-      vis -= 8 * (jj & 1);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
-    }
+    if (masked) mask_scores<TREE>(x, st.limit[nt], st.qidx[nt], st.dmask[nt], valid_l, pos_l, true);
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                      fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -421,7 +453,7 @@ struct RawBlock {
 // free of conditional loads on purpose: the vector-memory completion counter is in-order, and a
 // load that is issued on one path only would force the compiler to wait for everything
 // outstanding at the join.
-template <int KV, int D, int NT, bool SUFFIX>
+template <int KV, int D, int NT, bool SUFFIX, bool TREE>
 __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   constexpr int ESZ = (KV == kFP8) ? 1 : 2;
   constexpr int TILE_BYTES = 16 * D * ESZ;
@@ -502,7 +534,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
       for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
     }
     // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
-    block_math<D, NT>(st, kf, vf, task_masked || rb.valid_b == 0, jj < 2 ? rb.valid_a : rb.valid_b,
+    block_math<TREE, D, NT>(st, kf, vf, task_masked || rb.valid_b == 0, jj < 2 ? rb.valid_a : rb.valid_b,
                       jj < 2 ? rb.pos_a : rb.pos_b, p.scale_log2 * rb.ks, rb.vs);
   };
 
@@ -536,14 +568,14 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
   finish_rows<D, NT, SUFFIX>(p, sh, cur, cur.row0, st.o, st.m, l_tot, st.qtok, stage[threadIdx.x >> 6]);
 }
 
-template <int KV, int D, int NT>
+template <int KV, int D, int NT, bool TREE>
 __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_prefix_attn_kernel(AttnArgs p, Shape sh) {
-  attn_wave<KV, D, NT, false>(p, sh);
+  attn_wave<KV, D, NT, false, TREE>(p, sh);
 }
 
-template <int KV, int D, int NT>
+template <int KV, int D, int NT, bool TREE>
 __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_suffix_attn_kernel(AttnArgs p, Shape sh) {
-  attn_wave<KV, D, NT, true>(p, sh);
+  attn_wave<KV, D, NT, true, TREE>(p, sh);
 }
 
 // Block step of the cooperative kernel.  Same contraction as block_math, tuned for many row
@@ -556,8 +588,9 @@ __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_suffix_attn_kernel(
 //  * with a page-independent scale (bf16 KV) the running maximum is kept on the raw scores and
 //    scale and subtraction fuse into one FMA per score.
 // m is in units of raw score for bf16 KV and of scaled score for fp8 KV (c differs per page).
-template <bool FP8, int D, int NT>
+template <bool FP8, bool TREE, int D, int NT>
 __device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], const int (&limit)[NT],
+                                               const int (&qidx)[NT], const uint32_t (&dmask)[NT],
                                                f32x4 (&o)[NT][D / 16], float (&m)[NT],
                                                f32x4 (&lacc)[NT], const bf16x8 (&kf)[2][D / 32],
                                                const f16x8 (&vh)[D / 16], bool masked, int valid_l,
@@ -579,13 +612,7 @@ __device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], c
       x[i] = FP8 ? sa[i] * c : sa[i];
       x[4 + i] = FP8 ? sb[i] * c : sb[i];
     }
-    if (masked) {
-      int vis = limit[nt] - pos_l;
-      vis = vis < valid_l ? vis : valid_l;
-      vis -= 8 * (jj & 1);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = i < vis ? x[i] : kNegInf;
-    }
+    if (masked) mask_scores<TREE>(x, limit[nt], qidx[nt], dmask[nt], valid_l, pos_l, true);
     float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
                      fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -664,7 +691,7 @@ __device__ __forceinline__ u32x4 fp8x8_to_f16x8(uint32_t w0, uint32_t w1, float 
 // ready-made MFMA operand images (K as bf16, V^T as fp16, fp8 widened on the way and V multiplied
 // by its page scale) that all four wavefronts read (lane * 16 B, conflict free).  Two LDS buffers
 // and one barrier per block.
-template <int KV, int D, int NTW>
+template <int KV, int D, int NTW, bool TREE>
 __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel(AttnArgs p, Shape sh) {
   constexpr bool FP8 = KV == kFP8;
   constexpr int ESZ = FP8 ? 1 : 2;
@@ -754,7 +781,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
     const int valid_a = bm.vp_a & 127, valid_b = bm.vp_b & 127;
     float c = p.scale_log2;
     if (FP8) c *= fmaxf(p.k_scale[(jj < 2 ? bm.pid_a : bm.pid_b) * sh.Hkv + g], kMinKScale);
-    block_math_f16<FP8, D, NTW>(st.qf, st.limit, st.o, st.m, lacc, kf, vh,
+    block_math_f16<FP8, TREE, D, NTW>(st.qf, st.limit, st.qidx, st.dmask, st.o, st.m, lacc, kf, vh,
                                 task_masked || valid_b == 0, jj < 2 ? valid_a : valid_b,
                                 jj < 2 ? (bm.vp_a >> 7) : (bm.vp_b >> 7), c);
   };
@@ -1773,10 +1800,16 @@ __global__ __launch_bounds__(256) void spex_gather_kv_kernel(GatherArgs a, Shape
 template <int KV, int D, int NT>
 hipError_t launch_mfma(const Shape &sh, const AttnArgs &a, bool prefix, hipStream_t stream) {
   const dim3 grid((a.n_items + 3) / 4), block(256);
-  if (prefix)
-    hipLaunchKernelGGL((spex_prefix_attn_kernel<KV, D, NT>), grid, block, 0, stream, a, sh);
-  else
-    hipLaunchKernelGGL((spex_suffix_attn_kernel<KV, D, NT>), grid, block, 0, stream, a, sh);
+  if (a.qt_mask) {  // draft token trees: visibility masks per query
+    if (prefix)
+      hipLaunchKernelGGL((spex_prefix_attn_kernel<KV, D, NT, true>), grid, block, 0, stream, a, sh);
+    else
+      hipLaunchKernelGGL((spex_suffix_attn_kernel<KV, D, NT, true>), grid, block, 0, stream, a, sh);
+  } else if (prefix) {
+    hipLaunchKernelGGL((spex_prefix_attn_kernel<KV, D, NT, false>), grid, block, 0, stream, a, sh);
+  } else {
+    hipLaunchKernelGGL((spex_suffix_attn_kernel<KV, D, NT, false>), grid, block, 0, stream, a, sh);
+  }
   return hipGetLastError();
 }
 
@@ -1824,12 +1857,20 @@ hipError_t launch_attention(const Shape &sh, const AttnArgs &a, bool prefix, int
 template <int KV, int D>
 static hipError_t launch_coop_ntw(const Shape &sh, const AttnArgs &a, int ntw, hipStream_t stream) {
   const dim3 grid(a.n_items), block(256);
-  if (ntw == 1)
-    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 1>), grid, block, 0, stream, a, sh);
-  else if (ntw == 2)
-    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 2>), grid, block, 0, stream, a, sh);
-  else
-    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 4>), grid, block, 0, stream, a, sh);
+  if (a.qt_mask) {
+    if (ntw == 1)
+      hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 1, true>), grid, block, 0, stream, a, sh);
+    else if (ntw == 2)
+      hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 2, true>), grid, block, 0, stream, a, sh);
+    else
+      hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 4, true>), grid, block, 0, stream, a, sh);
+  } else if (ntw == 1) {
+    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 1, false>), grid, block, 0, stream, a, sh);
+  } else if (ntw == 2) {
+    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 2, false>), grid, block, 0, stream, a, sh);
+  } else {
+    hipLaunchKernelGGL((spex_prefix_coop_kernel<KV, D, 4, false>), grid, block, 0, stream, a, sh);
+  }
   return hipGetLastError();
 }
 
@@ -1857,8 +1898,10 @@ static hipError_t launch_walk_ntw(const Shape &sh, const WalkArgs &a, int ntw, h
 
 template <int KV, int D>
 static hipError_t launch_walk_nw(const Shape &sh, const WalkArgs &a, int ntw, int waves, hipStream_t stream) {
-  if (a.qt_mask)  // draft-tree masks: 4 wavefronts per workgroup only
-    return waves == 4 ? launch_walk_ntw<KV, D, 4, true>(sh, a, ntw, stream) : hipErrorInvalidValue;
+  if (a.qt_mask)  // draft-tree masks: not in the kernel that splits the path
+    return waves == 4   ? launch_walk_ntw<KV, D, 4, true>(sh, a, ntw, stream)
+           : waves == 8 ? launch_walk_ntw<KV, D, 8, true>(sh, a, ntw, stream)
+                        : hipErrorInvalidValue;
   if (waves == 2) {  // lists for two wavefronts of rows, walked by four: the path is split in two
     const dim3 grid(a.n_items), block(256);
     if (ntw == 1)

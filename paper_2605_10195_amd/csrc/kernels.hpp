@@ -37,7 +37,7 @@ struct AttnArgs {
   float scale_log2;
   // Draft-tree visibility, or null for the causal chain: 2 ints per query token {index i of the
   // query in its request, mask}; with base = limit - 1 - i the query sees path positions below base
-  // and position base + k iff bit k of the mask is set.  Only the generic kernel reads it.
+  // and position base + k iff bit k of the mask is set.
   const int32_t *qt_mask;
 };
 

@@ -259,15 +259,26 @@ PlanError Planner::ensure_split(const PageTable &pt, Plan *plan) {
                               : clamp32((suffix_pages * num_kv_heads + 2047) / 2048, 8, 64);
 
   // ---- tasks
+  std::vector<int32_t> qt_req;  // with draft masks: the request of every query token
+  if (!pl.qt_mask.empty()) {
+    qt_req.resize(NQ);
+    for (int32_t i = 0; i < n_leaves; ++i)
+      for (int32_t j = 0; j < (q_lens ? q_lens[i] : 1); ++j) qt_req[qoff[i] + j] = i;
+  }
   std::vector<std::vector<std::pair<int32_t, int32_t>>> parts(NQ);
   int64_t pbase = 0;
   bool overflow = false;
   auto emit = [&](const Segment &s, int32_t chunk_pages, int64_t *tokens, bool suffix) -> bool {
     const int32_t n = static_cast<int32_t>(s.ids.size());
     const int32_t rows = s.qt_count * G;
+    // first path position that some row of the task does not see: the smallest limit for the
+    // causal chain; with draft masks a query may miss drafts below its own position, and the
+    // request's first position not seen by all its queries takes the limit's place
     int32_t min_limit = std::numeric_limits<int32_t>::max();
-    for (int32_t r = 0; r < s.qt_count; ++r)
-      min_limit = std::min(min_limit, pl.qt_limit[pl.qt_list[s.qt_begin + r]]);
+    for (int32_t r = 0; r < s.qt_count; ++r) {
+      const int32_t qt = pl.qt_list[s.qt_begin + r];
+      min_limit = std::min(min_limit, qt_req.empty() ? pl.qt_limit[qt] : pl.req_minlim[qt_req[qt]]);
+    }
     const int32_t c = (n + chunk_pages - 1) / chunk_pages;
     const bool final = suffix && c == 1;
     for (int32_t j = 0; j < c; ++j) {

@@ -606,7 +606,7 @@ def token_tree_workload(case, arbitrary=False):
 
 
 @pytest.mark.parametrize("case", TOKEN_TREE_CASES, ids=lambda c: f"{c['kv_dtype']}-{c['heads']}-q{c['max_q_len']}")
-@pytest.mark.parametrize("mode,row_tiles", [(0, 0), (1, 0), (3, 0), (3, 2), (3, 4)])
+@pytest.mark.parametrize("mode,row_tiles", [(0, 0), (1, 0), (2, 0), (3, 0), (3, 2), (3, 4)])
 @pytest.mark.parametrize("arbitrary", [False, True], ids=["ancestors", "any_bits"])
 def test_draft_token_trees_match_oracle(case, mode, row_tiles, arbitrary):
     import paper_2605_10195_amd as spex
@@ -621,10 +621,10 @@ def test_draft_token_trees_match_oracle(case, mode, row_tiles, arbitrary):
     got = run_gpu(wl, tree=tree)
     info = tree.last_launch_info()
     tree.close()
-    if mode == 3 or (mode == 0 and walk_applies(wl)):
+    if mode == 3:
         assert info["walk_row_tiles"] > 0 and info["walk_waves"] == 4
-    else:
-        assert info["walk_row_tiles"] == 0
+    elif mode in (1, 2):
+        assert info["walk_row_tiles"] == 0          # mode 0: the library's choice, as without masks
     assert_close(got, run_oracle(wl), case["kv_dtype"], wl.name)
 
 
@@ -643,22 +643,25 @@ def test_chain_masks_give_the_bits_of_the_call_without_masks(case):
         tree.close()
 
 
-def test_draft_masks_where_no_kernel_takes_them():
+def test_draft_masks_in_every_kernel_set():
+    """Masks in the shared-prefix / suffix / merge kernels (kernel_mode 2) and in the tree-walk kernel
+    with 8 wavefronts; only the kernel that splits the path (walk_waves 2) refuses them."""
     import paper_2605_10195_amd as spex
     wl = token_tree_workload(TOKEN_TREE_CASES[0])
     q = sw.gen_queries(wl, device="cuda")
-    for kw in (dict(kernel_mode=2), dict(kernel_mode=3, walk_waves=8)):
+    ref = run_oracle(wl)
+    for kw in (dict(kernel_mode=2), dict(kernel_mode=2, prefix_chunk_pages=1, suffix_chunk_pages=1),
+               dict(kernel_mode=3, walk_waves=8), dict(kernel_mode=0, walk_waves=8)):
         tree = build_gpu_tree(wl, **kw)
-        with pytest.raises(spex.SpexError) as e:
-            tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
-        assert e.value.name == "UNSUPPORTED"
+        got = run_gpu(wl, tree=tree)
+        assert (tree.last_launch_info()["walk_row_tiles"] > 0) == (kw["kernel_mode"] == 3)
         tree.close()
-    # automatic mode with 8 wavefronts asked for: the generic kernels take the request
-    tree = build_gpu_tree(wl, kernel_mode=0, walk_waves=8)
-    got = run_gpu(wl, tree=tree)
-    assert tree.last_launch_info()["walk_row_tiles"] == 0
+        assert_close(got, ref, "bf16", f"{wl.name} {kw}")
+    tree = build_gpu_tree(wl, kernel_mode=3, walk_waves=2)
+    with pytest.raises(spex.SpexError) as e:
+        tree.decode_attention(wl.leaves, wl.q_lens, q, wl.sm_scale, draft_masks=wl.draft_masks)
+    assert e.value.name == "UNSUPPORTED"
     tree.close()
-    assert_close(got, run_oracle(wl), "bf16", wl.name)
 
 
 TOKEN_TREE_SHAPES = [
@@ -672,12 +675,13 @@ TOKEN_TREE_SHAPES = [
 
 
 @pytest.mark.parametrize("wl", TOKEN_TREE_SHAPES, ids=lambda w: f"{w.name}_{w.kv_dtype}_{w.num_q_heads}_{w.q_lens[0]}")
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
 def test_token_tree_sizes_of_the_paper_match_oracle(wl, mode):
     # Sec. 6.5 verifies token trees of 16, 8 and 4 drafts per branch
     tree = build_gpu_tree(wl, kernel_mode=mode)
     got = run_gpu(wl, tree=tree)
-    assert (tree.last_launch_info()["walk_row_tiles"] > 0) == (mode == 0)
+    if mode != 0:
+        assert (tree.last_launch_info()["walk_row_tiles"] > 0) == (mode == 3)
     tree.close()
     assert_close(got, run_oracle(wl), wl.kv_dtype, wl.name)
 
