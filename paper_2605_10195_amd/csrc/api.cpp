@@ -283,7 +283,9 @@ spex_status_t upload_plan(spex_tree *t, hipStream_t stream) {
     if (t->d_plan) HIP_TRY(hipFree(t->d_plan));
     t->d_plan = nullptr;
     t->d_plan_cap = 0;
-    const size_t cap = align_up(total + total / 2, 1 << 16);
+    // Freeing and allocating device memory synchronises the device, so the workspace grows in
+    // large steps: at least 1 MiB, and twice what is needed now.
+    const size_t cap = align_up(std::max<size_t>(2 * total, size_t(1) << 20), 1 << 16);
     HIP_TRY(hipMalloc(&t->d_plan, cap));
     t->d_plan_cap = cap;
   }
@@ -356,7 +358,7 @@ spex_status_t ensure_partials(spex_tree *t, int64_t rows) {
   if (t->d_part_ml) HIP_TRY(hipFree(t->d_part_ml));
   t->d_part_o = t->d_part_ml = nullptr;
   t->part_cap_rows = 0;
-  const int64_t cap = rows + rows / 4 + 1024;
+  const int64_t cap = 2 * rows + 1024;  // grows in large steps: a reallocation synchronises the device
   HIP_TRY(hipMalloc(reinterpret_cast<void **>(&t->d_part_o),
                     static_cast<size_t>(cap) * t->cfg.head_dim * sizeof(float)));
   HIP_TRY(hipMalloc(reinterpret_cast<void **>(&t->d_part_ml), static_cast<size_t>(cap) * 2 * sizeof(float)));

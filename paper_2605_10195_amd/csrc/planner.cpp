@@ -569,16 +569,49 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
   pl.walk_waves = NW;
   const int32_t rb_ints = 3 + 3 * NW, item_ints = NW <= 4 ? 16 : 32;
 
+  // Order of the requests: by root, then by path (node ids root first, lexicographic, a proper
+  // prefix first), ties in request order.  Comparing paths pairwise costs a walk over the common
+  // prefix per comparison; instead every node on a requested path gets its rank in the pre-order
+  // traversal of the requested part of the forest that visits roots in order of first appearance
+  // and children in ascending id -- the same order -- and the requests are sorted by the rank of
+  // their node.
   std::vector<int32_t> order(n_leaves);
-  std::iota(order.begin(), order.end(), 0);
-  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-    if (root_of[a] != root_of[b]) return root_of[a] < root_of[b];
-    const int32_t la = path_indptr[a + 1] - path_indptr[a], lb = path_indptr[b + 1] - path_indptr[b];
-    const int32_t *pa = path_nodes.data() + path_indptr[a], *pb = path_nodes.data() + path_indptr[b];
-    for (int32_t k = 0; k < la && k < lb; ++k)
-      if (pa[k] != pb[k]) return pa[k] < pb[k];
-    return la < lb;
-  });
+  {
+    if (static_cast<int32_t>(rank_.size()) < N) {
+      rank_.resize(N, 0);
+      child_lo_.resize(N, 0);
+      child_n_.resize(N, 0);
+    }
+    const int32_t st_seen = fresh();
+    edges_.clear();
+    for (int32_t i = 0; i < n_leaves; ++i)
+      for (int32_t k = path_indptr[i + 1] - 1; k >= path_indptr[i]; --k) {
+        const int32_t u = path_nodes[k];
+        if (stamp_[u] == st_seen) break;  // the rest of the path is known already
+        stamp_[u] = st_seen;
+        child_n_[u] = 0;
+        if (k > path_indptr[i]) edges_.emplace_back(path_nodes[k - 1], u);
+      }
+    std::sort(edges_.begin(), edges_.end());
+    for (size_t e = 0; e < edges_.size(); ++e) {
+      const int32_t par = edges_[e].first;
+      if (child_n_[par]++ == 0) child_lo_[par] = static_cast<int32_t>(e);
+    }
+    int32_t next_rank = 0;
+    dfs_.clear();
+    for (int32_t r = static_cast<int32_t>(root_ids.size()) - 1; r >= 0; --r) dfs_.push_back(root_ids[r]);
+    while (!dfs_.empty()) {
+      const int32_t u = dfs_.back();
+      dfs_.pop_back();
+      rank_[u] = next_rank++;
+      for (int32_t c = child_n_[u] - 1; c >= 0; --c) dfs_.push_back(edges_[child_lo_[u] + c].second);
+    }
+    keyed_.resize(n_leaves);
+    for (int32_t i = 0; i < n_leaves; ++i)
+      keyed_[i] = (static_cast<int64_t>(rank_[path_nodes[path_indptr[i + 1] - 1]]) << 32) | static_cast<uint32_t>(i);
+    std::sort(keyed_.begin(), keyed_.end());
+    for (int32_t i = 0; i < n_leaves; ++i) order[i] = static_cast<int32_t>(keyed_[i] & 0xffffffff);
+  }
 
   // A request with more query tokens than a wavefront holds is cut into pieces of consecutive
   // query tokens of (almost) equal size; the packing below places pieces.
@@ -631,6 +664,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     }
   }
 
+  const int32_t c_shift = ntw == 1 ? 4 : (ntw == 2 ? 5 : 6);  // C = 16 * ntw = 1 << c_shift
   struct Placed { int32_t req, row0, rows; };
   std::vector<std::pair<int32_t, int32_t>> last_blks;  // (request, block with its node's last page)
   struct NodeRange { int32_t node, lo, hi, minlim; };
@@ -649,25 +683,32 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     const Node &nd = pt.node(nr.node);
     last_blk_of_node = -1;
     const int32_t n = static_cast<int32_t>(nd.pages.size());
-    int32_t made = 0;
-    for (int32_t k = 0; k < n; k += 2, ++made) {
+    const int32_t made = (n + 1) >> 1;
+    if (made == 0) return 0;
+    const size_t first = pl.walk_blocks.size();
+    pl.walk_blocks.resize(first + static_cast<size_t>(made) * Plan::kBlockInts);
+    int32_t *rec = &pl.walk_blocks[first];
+    const int32_t *pages = nd.pages.data();
+    const int32_t rows = nr.lo | (nr.hi << 16), multi = multi_[nr.node] == st_multi ? 2 : 0;
+    const int32_t last_valid = nd.n_tokens - (n - 1) * P;  // every page but the last is full
+    int32_t pos_a = pos0_[nr.node];
+    for (int32_t k = 0; k < n; k += 2, rec += Plan::kBlockInts, pos_a += 2 * P) {
       const bool has_b = k + 1 < n;
-      const int32_t va = pt.page_valid(nr.node, k);
-      const int32_t vb = has_b ? pt.page_valid(nr.node, k + 1) : 0;
-      const int32_t pos_a = pos0_[nr.node] + k * P, pos_b = pos_a + P;
+      const int32_t va = k == n - 1 ? last_valid : P;
+      const int32_t vb = has_b ? (k + 1 == n - 1 ? last_valid : P) : 0;
+      const int32_t pos_b = pos_a + P;
       const int32_t end = has_b ? pos_b + vb : pos_a + va;
       const bool masked = va != P || !has_b || vb != P || nr.minlim < end;
-      if (k + 2 >= n) last_blk_of_node = static_cast<int32_t>(pl.walk_blocks.size() / Plan::kBlockInts);
-      const int32_t rec[Plan::kBlockInts] = {nd.pages[k],
-                                             (pos_a << 7) | va,
-                                             has_b ? nd.pages[k + 1] : nd.pages[k],
-                                             has_b ? ((pos_b << 7) | vb) : 0,
-                                             nr.lo | (nr.hi << 16),
-                                             (masked ? 1 : 0) | (multi_[nr.node] == st_multi ? 2 : 0),
-                                             0,
-                                             0};
-      pl.walk_blocks.insert(pl.walk_blocks.end(), rec, rec + Plan::kBlockInts);
+      rec[0] = pages[k];
+      rec[1] = (pos_a << 7) | va;
+      rec[2] = has_b ? pages[k + 1] : pages[k];
+      rec[3] = has_b ? ((pos_b << 7) | vb) : 0;
+      rec[4] = rows;
+      rec[5] = (masked ? 1 : 0) | multi;
+      rec[6] = 0;
+      rec[7] = 0;
     }
+    last_blk_of_node = static_cast<int32_t>(first / Plan::kBlockInts) + made - 1;
     return made;
   };
   auto flush = [&](int32_t root_slot) {
@@ -695,21 +736,33 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     const int32_t rb_index = static_cast<int32_t>(pl.walk_rb.size() / rb_ints);
     // requests of this row block that asked for nr.node; home: the wavefront whose private list
     // holds the node (-1: a shared node).  Returns whether any request asked for it.
+    // The placed requests that ask for one node follow each other (the requests are in path
+    // order): first index and count per asked node, in the per-node scratch of the ordering step.
+    for (int32_t ci = 0; ci < static_cast<int32_t>(cur.size()); ++ci) {
+      const int32_t u = pl.req_leaves[cur[ci].req];
+      if (rank_[u] != -st) {
+        rank_[u] = -st;  // ranks are >= 0 and no longer needed: a negative stamp marks "asked in this row block"
+        child_lo_[u] = ci;
+        child_n_[u] = 0;
+      }
+      ++child_n_[u];
+    }
     auto note_last = [&](const NodeRange &nr, int32_t home) {
-      bool asked = false;
-      for (const Placed &pc : cur)
-        if (pl.req_leaves[pc.req] == nr.node) {
-          asked = true;
-          if (last_blks.empty() || last_blks.back() != std::make_pair(pc.req, last_blk_of_node)) {
-            last_blks.emplace_back(pc.req, last_blk_of_node);
-            int32_t &h = pl.req_walk_home[pc.req];
-            h = (h == -2 && home >= 0) ? rb_index * NW + home : -1;
-          }
+      if (rank_[nr.node] != -st) return false;
+      for (int32_t ci = child_lo_[nr.node]; ci < child_lo_[nr.node] + child_n_[nr.node]; ++ci) {
+        const Placed &pc = cur[ci];
+        if (last_blks.empty() || last_blks.back() != std::make_pair(pc.req, last_blk_of_node)) {
+          last_blks.emplace_back(pc.req, last_blk_of_node);
+          int32_t &h = pl.req_walk_home[pc.req];
+          h = (h == -2 && home >= 0) ? rb_index * NW + home : -1;
         }
-      return asked;
+      }
+      return true;
     };
+    // wavefront that holds all rows of a node, or -1 if they touch several (C is a power of two)
+    auto home_of = [&](const NodeRange &nr) { return (nr.lo >> c_shift) == ((nr.hi - 1) >> c_shift) ? (nr.lo >> c_shift) : -1; };
     for (const NodeRange &nr : nodes)
-      if (nr.lo / C != (nr.hi - 1) / C) {
+      if (home_of(nr) < 0) {
         rb_rec[2] += emit_node(nr);
         note_last(nr, -1);
       }
@@ -718,7 +771,7 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     for (int32_t w = 0; w < NW; ++w) {
       int32_t count = 0, room = 0;
       for (const NodeRange &nr : nodes)
-        if (nr.lo / C == (nr.hi - 1) / C && nr.lo / C == w) {
+        if (home_of(nr) == w) {
           count += emit_node(nr);
           if (note_last(nr, w) && pt.node(nr.node).n_live_children == 0) room += 2;
         }
@@ -805,17 +858,18 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
       const bool real = r < lane_rbs[l].size();
       if (!real && lanes == 1) continue;
       for (int32_t g = 0; g < num_kv_heads; ++g) {
-        std::vector<int32_t> rec(item_ints, 0);
+        const size_t at = pl.walk_items.size();
+        pl.walk_items.resize(at + item_ints, 0);
+        int32_t *rec = &pl.walk_items[at];
         rec[0] = g;
         rec[item_ints - 1] = -1;
         if (real) {
           const int32_t rb = lane_rbs[l][r];
           for (int k = 1; k < rb_ints; ++k) rec[k] = pl.walk_rb[static_cast<size_t>(rb) * rb_ints + k];
           rec[item_ints - 1] = rb;
-          if (g == 0) pl.rb_item0[rb] = static_cast<int32_t>(pl.walk_items.size() / item_ints);
+          if (g == 0) pl.rb_item0[rb] = static_cast<int32_t>(at / item_ints);
           ++pl.walk_real_items;
         }
-        pl.walk_items.insert(pl.walk_items.end(), rec.begin(), rec.end());
       }
     }
   pl.walk_ok = true;

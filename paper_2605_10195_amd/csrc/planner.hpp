@@ -23,6 +23,7 @@
 #pragma once
 
 #include <cstdint>
+#include <utility>
 #include <vector>
 
 #include "page_table.hpp"
@@ -132,6 +133,11 @@ class Planner {
  private:
   std::vector<int32_t> multi_, last_pg_;
   std::vector<int32_t> stamp_, slot_;  // per-node scratch of build_walk, valid where stamp_ == current stamp
+  // scratch of the request ordering in ensure_walk: pre-order rank and child ranges per node,
+  // (parent, child) edges of the requested paths, traversal stack, (rank, request) keys
+  std::vector<int32_t> rank_, child_lo_, child_n_, dfs_;
+  std::vector<std::pair<int32_t, int32_t>> edges_;
+  std::vector<int64_t> keyed_;
   int32_t stamp_next_ = 1;
   // dense per-node scratch, reset through touched_
   std::vector<int32_t> live_, pos0_, gindex_, touched_;
