@@ -90,12 +90,11 @@ class OracleDynamicSink:
         return b
 
     def append_prompt(self, node, n, key):
-        from spex_workloads.quant import quantise_pages
         k, v = self.values.kv_run(key, 0, n)
         if self.shape.kv_dtype == "fp8_e4m3":
-            kc, ks = quantise_pages(k, 0, self.shape.page_size, None)
-            vc, vs = quantise_pages(v, 0, self.shape.page_size, None)
-            self.tree.append(node, raw_array(kc), raw_array(vc), raw_array(ks), raw_array(vs))
+            # the oracle's own quantiser: page scales from the tokens, codes by its table search
+            self.tree.append_quantised(node, raw_array(k.to(torch.bfloat16)), raw_array(v.to(torch.bfloat16)),
+                                       derive_scales=True)
         else:
             self.tree.append(node, raw_array(k.to(torch.bfloat16)), raw_array(v.to(torch.bfloat16)))
 

@@ -364,12 +364,11 @@ class LibrarySink:
             self._timed("append", self.tree.append_step, node, None, None, n_tokens=n)
             return
         import torch
-        from .quant import quantise_pages
         k, v = self.values.kv_run(key, 0, n)
         if self.shape.kv_dtype == "fp8_e4m3":
-            kc, ks = quantise_pages(k, 0, self.shape.page_size, None)
-            vc, vs = quantise_pages(v, 0, self.shape.page_size, None)
-            self._timed("append", self.tree.append_step, node, kc, vc, ks, vs)
+            # bf16 tokens in; the library's scatter kernel derives the page scales and encodes
+            self._timed("append", self.tree.append_step, node, k.to(torch.bfloat16).contiguous(),
+                        v.to(torch.bfloat16).contiguous(), quantize=True)
         else:
             self._timed("append", self.tree.append_step, node, k.to(torch.bfloat16).contiguous(),
                         v.to(torch.bfloat16).contiguous())
