@@ -62,7 +62,9 @@ typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
  *     every 128-bit load instruction of the attention kernels reads contiguous memory
  *     and lands directly in operand registers.
  *     K, bf16:  ((t>>2)&1) * 8*head_dim + (d/32)*256 + ((d%32)/8)*64 + (4*(t>>3) + (t&3))*8 + d%8
- *     V, bf16:  (d/16)*256 + (t/8)*128 + (d%16)*8 + t%8              (token-minor: V transposed)
+ *     V, bf16:  (d/16)*256 + (t/8)*128 + (d%16)*8 + t%8              (token-minor: V transposed;
+ *               the 16-bit element is the IEEE half-precision image of the bf16 value, written by
+ *               the append calls and turned back into bf16 by spex_tree_gather_kv -- see Value range)
  *     K, fp8 :  ((t>>2)&1) * 8*head_dim + (d/64)*512 + ((d%32)/8)*128 + (4*(t>>3) + (t&3))*16 + ((d/32)&1)*8 + d%8
  *     V, fp8 :  (d/32)*512 + (t/8)*256 + (d%16)*16 + ((d/16)&1)*8 + t%8
  *  Use spex_tree_gather_kv to read tokens back in logical order.
@@ -71,16 +73,22 @@ typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
  * for K and V, in the caller-owned DEVICE arrays k_scale / v_scale [num_pages][num_kv_heads].
  * Scales must be finite and >= 0 (0: a page of zeros).
  *
- * Value range.  K, V and q must be finite.  The tree-walk and cooperative shared-prefix kernels
- * (kernel_mode 0 / 3 on MFMA-tiled pools) multiply the softmax weights with V held in IEEE
- * half precision, which is exact for every fp8 code and for bf16 magnitudes in [2^-14, 65504]:
- *   - a bf16 V magnitude above 65504 is read as 65504 (saturation, never infinity);
- *   - a bf16 V magnitude below 2^-14 is read with an absolute error below 2^-24;
- *   - an fp8 v_scale above 146 (448 * 146 = 65408) is read as 146.
- * The same holds for an fp8 V value (code * v_scale) of magnitude below 2^-14.  Inside the range
- * every kernel meets the same error bound; outside it only the generic kernels (kernel_mode 1)
- * reproduce V exactly (kernel_mode 2 runs the cooperative kernel for nodes shared by more than 16
- * query rows).
+ * Value range.  K, V and q must be finite.  On MFMA-tiled pools the product of the softmax weights
+ * with V runs in IEEE half precision.  For a bf16 pool the append calls store V in that format
+ * (rounding toward zero), which is exact for zero and every bf16 magnitude in [2^-17, 65504]:
+ *   - a bf16 V magnitude above 65504 is stored as 65504 (saturation, never infinity;
+ *     spex_tree_gather_kv returns 65280, the bf16 below it);
+ *   - a bf16 V magnitude below 2^-17 is stored as the multiple of 2^-24 below it (absolute error
+ *     below 2^-24);
+ * every kernel on such a pool, the generic one included, sees the stored values.  For an fp8 pool
+ * the codes are stored as given and widened when read by the tree-walk and cooperative kernels
+ * (kernel_mode 0 / 3, and 2 for nodes shared by more than 16 query rows):
+ *   - an fp8 v_scale above 146 (448 * 146 = 65408) is read as 146;
+ *   - an fp8 V value (code * v_scale) of magnitude below 2^-14 is read with an absolute error
+ *     below 2^-24;
+ * the other kernels of an fp8 pool reproduce code * v_scale exactly.  Row-major pools (fp32, other
+ * page sizes and head dims) hold and return V as given.  Inside the range every kernel meets the
+ * same error bound.
  */
 typedef struct {
   int32_t num_q_heads;  /* multiple of num_kv_heads; query head h uses kv head h / (Hq/Hkv) */

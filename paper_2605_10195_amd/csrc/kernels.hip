@@ -112,6 +112,32 @@ __device__ __forceinline__ float load_elem(const void *base, int64_t idx) {
   return e4m3_to_float(static_cast<const uint8_t *>(base)[idx]);
 }
 
+// V of a bf16 pool in the MFMA-tiled layout is stored as IEEE half precision, so that a tile is an
+// fp16 operand image of the PV product as it lies in memory.  The append kernels convert once,
+// rounding toward zero: exact for magnitudes in [2^-17, 65504] (a bf16 has 8 significant bits, an
+// fp16 11, and subnormal fp16 still resolve 2^-24); a finite magnitude above 65504 becomes +-65504
+// instead of infinity (0 * inf in the PV product would poison a whole row), one below 2^-17 keeps
+// the multiples of 2^-24 it contains.  K stays bf16.
+template <int KV, int LAYOUT>
+__device__ __forceinline__ constexpr bool v_is_f16() {
+  return KV == kBF16 && LAYOUT == kMfmaTiled;
+}
+__device__ __forceinline__ uint16_t bf16_bits_to_f16_bits(uint16_t b) {
+  const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_bits_to_float(b), 0.f));
+  return static_cast<uint16_t>(w & 0xffffu);
+}
+// Back to bf16 by truncation: exact for everything bf16_bits_to_f16_bits produced.
+__device__ __forceinline__ uint16_t f16_bits_to_bf16_bits(uint16_t h) {
+  const float f = static_cast<float>(__builtin_bit_cast(_Float16, h));
+  return static_cast<uint16_t>(__builtin_bit_cast(uint32_t, f) >> 16);
+}
+template <int KV, int LAYOUT>
+__device__ __forceinline__ float load_v_elem(const void *base, int64_t idx) {
+  if (v_is_f16<KV, LAYOUT>())
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<const uint16_t *>(base)[idx]));
+  return load_elem<KV>(base, idx);
+}
+
 template <int KV>
 __device__ __forceinline__ constexpr int elem_size() {
   return KV == kF32 ? 4 : (KV == kBF16 ? 2 : 1);
@@ -257,11 +283,11 @@ __device__ __forceinline__ void load_rows(const AttnArgs &p, const Shape &sh, co
 // tile come from page A, rows 8-15 from page B.  vf[dt]: V^T, dims dt*16.., tokens 8*(jj&1)..+7 of
 // page jj/2.  After the two score tiles this lane holds the scores of exactly those 8 tokens, i.e.
 // the operand layout of the PV product, so P never leaves the registers.
-template <bool TREE, int D, int NT>
+// VF16: vf holds fp16 (V of a bf16 pool as stored), else bf16 (widened fp8 codes).
+template <bool TREE, bool VF16, int D, int NT>
 __device__ __forceinline__ void block_math(RowState<D, NT> &st, const bf16x8 (&kf)[2][D / 32],
                                            const bf16x8 (&vf)[D / 16], bool masked, int valid_l,
                                            int pos_l, float c, float vs) {
-  const int jj = (threadIdx.x & 63) >> 4;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
@@ -297,22 +323,41 @@ __device__ __forceinline__ void block_math(RowState<D, NT> &st, const bf16x8 (&k
 #pragma unroll
       for (int dt = 0; dt < D / 16; ++dt) st.o[nt][dt] *= alpha;
     }
-    // P as two bf16 pieces (hi + lo) so that the product keeps ~16 bits of each weight.
+    // P as two pieces (hi + lo, each rounded toward zero, lo from the exact fp32 remainder) so that
+    // the product keeps ~16 (bf16 pieces) or ~22 (fp16 pieces) bits of each weight.
     u32x4 phi, plo;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float a0 = pr[2 * i] * vs, a1 = pr[2 * i + 1] * vs;
-      const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
-      const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
-      phi[i] = pack_hi16(h0, h1);
-      plo[i] = pack_hi16(a0 - h0, a1 - h1);
+      if (VF16) {  // weights are at most 1 here: no overflow
+        const auto h = __builtin_amdgcn_cvt_pkrtz(a0, a1);
+        phi[i] = __builtin_bit_cast(uint32_t, h);
+        plo[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a0 - static_cast<float>(h[0]),
+                                                                         a1 - static_cast<float>(h[1])));
+      } else {
+        const float h0 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a0) & 0xffff0000u);
+        const float h1 = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, a1) & 0xffff0000u);
+        phi[i] = pack_hi16(h0, h1);
+        plo[i] = pack_hi16(a0 - h0, a1 - h1);
+      }
     }
-    const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
-    const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
+    if (VF16) {
+      const f16x8 ph = __builtin_bit_cast(f16x8, phi);
+      const f16x8 pl = __builtin_bit_cast(f16x8, plo);
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) {
-      st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, st.o[nt][dt], 0, 0, 0);
-      st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, st.o[nt][dt], 0, 0, 0);
+      for (int dt = 0; dt < D / 16; ++dt) {
+        const f16x8 vh = __builtin_bit_cast(f16x8, vf[dt]);
+        st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, ph, st.o[nt][dt], 0, 0, 0);
+        st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl, st.o[nt][dt], 0, 0, 0);
+      }
+    } else {
+      const bf16x8 ph = __builtin_bit_cast(bf16x8, phi);
+      const bf16x8 pl = __builtin_bit_cast(bf16x8, plo);
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) {
+        st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], ph, st.o[nt][dt], 0, 0, 0);
+        st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pl, st.o[nt][dt], 0, 0, 0);
+      }
     }
   }
 }
@@ -534,7 +579,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs &p, const Shape &sh) {
       for (int s = 0; s < D / 16; ++s) vf[s] = __builtin_bit_cast(bf16x8, rb.v[s]);
     }
     // This lane's score registers cover tokens 8*(jj&1) .. +7 of page A (jj < 2) or B.
-    block_math<TREE, D, NT>(st, kf, vf, task_masked || rb.valid_b == 0, jj < 2 ? rb.valid_a : rb.valid_b,
+    block_math<TREE, KV == kBF16, D, NT>(st, kf, vf, task_masked || rb.valid_b == 0, jj < 2 ? rb.valid_a : rb.valid_b,
                       jj < 2 ? rb.pos_a : rb.pos_b, p.scale_log2 * rb.ks, rb.vs);
   };
 
@@ -595,7 +640,6 @@ __device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], c
                                                f32x4 (&lacc)[NT], const bf16x8 (&kf)[2][D / 32],
                                                const f16x8 (&vh)[D / 16], bool masked, int valid_l,
                                                int pos_l, float c) {
-  const int jj = (threadIdx.x & 63) >> 4;
   const _Float16 one = static_cast<_Float16>(1.0f);
   const f16x8 ones = {one, one, one, one, one, one, one, one};
 #pragma unroll
@@ -646,21 +690,6 @@ __device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], c
     for (int dt = 0; dt < D / 16; ++dt)
       o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh[dt], ph, o[nt][dt], 0, 0, 0);
   }
-}
-
-// Eight bf16 -> eight fp16.  Exact for magnitudes in [2^-14, 65504] (a bf16 has 8 significant bits,
-// an fp16 11).  The conversion rounds toward zero, so a finite magnitude above 65504 becomes
-// +-65504 instead of infinity (0 * inf in the PV product would poison a whole row), and one below
-// 2^-14 keeps the bits an fp16 subnormal has room for (absolute error below 2^-24).
-__device__ __forceinline__ u32x4 bf16x8_to_f16x8(u32x4 w) {
-  u32x4 r;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float lo = __builtin_bit_cast(float, w[i] << 16);
-    const float hi = __builtin_bit_cast(float, w[i] & 0xffff0000u);
-    r[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
-  }
-  return r;
 }
 
 // Largest V page scale the fp16 operand images can hold: 448 * 146 = 65408 <= 65504.  A larger
@@ -762,7 +791,7 @@ __global__ __launch_bounds__(256, NTW <= 2 ? 2 : 1) void spex_prefix_coop_kernel
           dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(raw.r[k][2], raw.r[k][3], raw.vs);
         }
       } else {
-        dst[idx * 64] = idx < RK ? raw.r[k] : bf16x8_to_f16x8(raw.r[k]);
+        dst[idx * 64] = raw.r[k];  // bf16 pool: K is a bf16 and V an fp16 operand image as stored
       }
     }
   };
@@ -1200,7 +1229,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
             dst[(2 * idx + 1) * 64] = fp8x8_to_f16x8(raw.r[k][2], raw.r[k][3], raw.vs);
           }
         } else {
-          dst[idx * 64] = is_k ? raw.r[k] : bf16x8_to_f16x8(raw.r[k]);
+          dst[idx * 64] = raw.r[k];  // bf16 pool: K is a bf16 and V an fp16 operand image as stored
         }
       }
     };
@@ -1345,7 +1374,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
         }
       } else {
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) vh[s] = __builtin_bit_cast(f16x8, bf16x8_to_f16x8(vr[s]));
+        for (int s = 0; s < D / 16; ++s) vh[s] = __builtin_bit_cast(f16x8, vr[s]);
       }
       if (more) issue_v(vr, refill);
       walk_softmax_pv<FP8, TREE, D, NTW>(limit, qidx, dmask, o, m, lacc, sa, sb, vh, (bm.flags & 1) != 0,
@@ -1525,7 +1554,7 @@ __global__ __launch_bounds__(64) void spex_generic_attn_kernel(AttnArgs p, Shape
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int d = lane + 64 * c;
-            if (d < D) vv[u][c] = load_elem<KV>(p.v_pool, tile * tile_elems + v_offset<KV, LAYOUT>(slot2, d, D));
+            if (d < D) vv[u][c] = load_v_elem<KV, LAYOUT>(p.v_pool, tile * tile_elems + v_offset<KV, LAYOUT>(slot2, d, D));
           }
         }
 #pragma unroll
@@ -1621,7 +1650,8 @@ __global__ __launch_bounds__(256) void spex_scatter_kv_kernel(ScatterArgs a, Sha
   if (tok >= 0 && tok < a.n_tokens) {
     const int64_t src = (static_cast<int64_t>(tok) * H + g) * D + d;
     *kp = static_cast<const T *>(a.k_src)[src];
-    *vp = static_cast<const T *>(a.v_src)[src];
+    const T vx = static_cast<const T *>(a.v_src)[src];
+    *vp = v_is_f16<KV, LAYOUT>() ? static_cast<T>(bf16_bits_to_f16_bits(static_cast<uint16_t>(vx))) : vx;
   } else if (tok >= a.n_tokens && is_new) {
     *kp = T(0);
     *vp = T(0);
@@ -1755,6 +1785,7 @@ __global__ __launch_bounds__(256) void spex_append_tokens_kernel(AppendTokensArg
   } else {
     kx = static_cast<const T *>(a.k_src)[tid];
     vx = static_cast<const T *>(a.v_src)[tid];
+    if (v_is_f16<KV, LAYOUT>()) vx = static_cast<T>(bf16_bits_to_f16_bits(static_cast<uint16_t>(vx)));
   }
   kp[k_offset<KV, LAYOUT>(slot, d, D)] = kx;
   vp[v_offset<KV, LAYOUT>(slot, d, D)] = vx;
@@ -1789,8 +1820,9 @@ __global__ __launch_bounds__(256) void spex_gather_kv_kernel(GatherArgs a, Shape
   const int64_t tile_elems = static_cast<int64_t>(P) * D;
   static_cast<T *>(a.k_out)[tid] =
       static_cast<const T *>(a.k_pool)[tile * tile_elems + k_offset<KV, LAYOUT>(slot, d, D)];
+  const T vx = static_cast<const T *>(a.v_pool)[tile * tile_elems + v_offset<KV, LAYOUT>(slot, d, D)];
   static_cast<T *>(a.v_out)[tid] =
-      static_cast<const T *>(a.v_pool)[tile * tile_elems + v_offset<KV, LAYOUT>(slot, d, D)];
+      v_is_f16<KV, LAYOUT>() ? static_cast<T>(f16_bits_to_bf16_bits(static_cast<uint16_t>(vx))) : vx;
   if (KV == kFP8 && d == 0) {
     if (a.k_scale_out) a.k_scale_out[static_cast<int64_t>(tok) * H + g] = a.k_scale[sidx];
     if (a.v_scale_out) a.v_scale_out[static_cast<int64_t>(tok) * H + g] = a.v_scale[sidx];

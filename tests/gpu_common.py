@@ -80,6 +80,21 @@ def run_oracle_c(wl, leaves=None, q_lens=None, q_rows=None, draft_masks=None, de
     return out, lse
 
 
+def assert_v_round_trip(got_v, want_v, what=""):
+    """V read back with gather_kv against what was appended.  In an MFMA-tiled bf16 pool V is held
+    in IEEE half precision (converted toward zero when it is appended): every bf16 of magnitude in
+    [2^-17, 65504], and zero, comes back bit for bit; a smaller one comes back as the multiple of
+    2^-24 below it.  Other pools (fp32, fp8 codes, row-major bf16) return V bit for bit."""
+    got_v, want_v = got_v.cpu(), want_v.cpu()
+    if want_v.dtype != torch.bfloat16:
+        assert torch.equal(got_v.view(want_v.dtype), want_v), what
+        return
+    g, w = got_v.view(torch.bfloat16).float(), want_v.float()
+    small = (w.abs() < 2.0 ** -17) & (w != 0)
+    assert torch.equal(g[~small], w[~small]), what
+    assert torch.all((g[small] - w[small]).abs() < 2.0 ** -24) and torch.all(g[small].abs() <= w[small].abs()), what
+
+
 def error_report(got_o, ref_o):
     """max abs error, relative L2 over the whole tensor, and the worst relative L2 of a single
     query row (one query token and head)."""

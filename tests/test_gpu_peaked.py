@@ -154,9 +154,10 @@ def test_v_magnitudes_inside_the_half_precision_range(shape, log2_mult, launch):
 
 @pytest.mark.parametrize("launch", [(3, 0, 0), (3, 2, 8)], ids=lambda l: "mode%d_t%d_w%d" % l)
 def test_v_beyond_the_half_precision_range_saturates(launch):
-    """bf16 V of magnitude up to 3 * 10^5: the tree-walk kernel reads magnitudes above 65504 as
-    65504 (never as infinity), i.e. it matches the oracle on the clipped values; the generic
-    kernels (kernel_mode 1) reproduce the unclipped ones."""
+    """bf16 V of magnitude up to 3 * 10^5: an MFMA-tiled bf16 pool holds V in half precision, and the
+    append stores a magnitude above 65504 as 65504 (never as infinity), so every kernel on that
+    pool -- the generic one included -- matches the oracle on the clipped values, not on the
+    unclipped ones."""
     from oracle.adapters import OracleSink, queries_fp64
     from oracle import attention_c
     wl = make_workload("bfs_bf16")
@@ -179,8 +180,34 @@ def test_v_beyond_the_half_precision_range_saturates(launch):
     print(f"saturating V {launch}: {rep}")
     assert rep["max_abs"] <= 2e-3 * mult and rep["rel_l2"] <= 1e-3, rep
     got1 = run(wl, 1, 0, 0)
-    rep1 = error_report(got1[0], exact[0])
+    rep1 = error_report(got1[0], ref[0])
     assert rep1["max_abs"] <= 2e-3 * mult and rep1["rel_l2"] <= 1e-3, rep1
+    assert error_report(got1[0], exact[0])["rel_l2"] > 1e-2      # the clipping is visible
+
+
+def test_gather_returns_v_as_the_pool_holds_it():
+    """Round trip of chosen bf16 V values through an MFMA-tiled pool (half precision, toward zero)
+    and through a row-major one (bf16 as given)."""
+    import paper_2605_10195_amd as spex
+    vals = torch.tensor([0.0, 1.0, -2.5, 65280.0, 65536.0, -3.0e5, 2.0 ** -14, 2.0 ** -17, -1.5 * 2.0 ** -17,
+                         (1 + 2.0 ** -7) * 2.0 ** -18, 1.5 * 2.0 ** -24, 2.0 ** -25, -2.0 ** -30, 448.0], dtype=torch.float32)
+    want = torch.tensor([0.0, 1.0, -2.5, 65280.0, 65504.0, -65504.0, 2.0 ** -14, 2.0 ** -17, -1.5 * 2.0 ** -17,
+                         2.0 ** -18, 2.0 ** -24, 0.0, -0.0, 448.0], dtype=torch.float32)
+    for D, tiled in ((128, True), (96, False)):
+        tree = spex.SpexTree(4, 2, D, 16, "bf16", "bf16", num_pages=8, device="cuda")
+        (r,) = tree.fork(-1, 1)
+        n = 20
+        v = vals.repeat((n * 2 * D + len(vals) - 1) // len(vals))[:n * 2 * D].reshape(n, 2, D).to(torch.bfloat16).cuda()
+        k = v.flip(0).contiguous()
+        tree.append(r, k, v.contiguous())
+        gk, gv, _, _ = tree.gather_kv(r, 0, n)
+        assert torch.equal(gk, k)
+        exp = want if tiled else vals
+        exp = exp.repeat((n * 2 * D + len(vals) - 1) // len(vals))[:n * 2 * D].reshape(n, 2, D).to(torch.bfloat16)
+        if tiled:  # 65504 is not a bf16: what comes back is the bf16 below it
+            exp = torch.where(exp.float().abs() > 65504.0, torch.sign(exp.float()) * 65280.0, exp.float()).to(torch.bfloat16)
+        assert torch.equal(gv.cpu().view(torch.int16), exp.view(torch.int16)), (D, gv.cpu().float().flatten()[:14], exp.float().flatten()[:14])
+        tree.close()
 
 
 @pytest.mark.parametrize("launch", LAUNCHES, ids=lambda l: "mode%d_t%d_w%d" % l)
