@@ -84,8 +84,9 @@ typedef enum { SPEX_F32 = 0, SPEX_BF16 = 1, SPEX_FP8_E4M3 = 2 } spex_dtype_t;
  * the codes are stored as given and widened when read by the tree-walk and cooperative kernels
  * (kernel_mode 0 / 3, and 2 for nodes shared by more than 16 query rows):
  *   - an fp8 v_scale above 146 (448 * 146 = 65408) is read as 146;
- *   - an fp8 V value (code * v_scale) of magnitude below 2^-14 is read with an absolute error
- *     below 2^-24;
+ *   - code * v_scale is formed in half precision in two steps (the power of two of the scale,
+ *     then its mantissa rounded to 11 bits): relative error at most 2^-10, and for a magnitude
+ *     below 2^-14 an absolute error below 2^-23;
  * the other kernels of an fp8 pool reproduce code * v_scale exactly.  Row-major pools (fp32, other
  * page sizes and head dims) hold and return V as given.  Inside the range every kernel meets the
  * same error bound.

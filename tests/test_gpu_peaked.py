@@ -135,7 +135,7 @@ def test_v_magnitudes_inside_the_half_precision_range(shape, log2_mult, launch):
     """|V| up to 2.45 * 2^11 = 5 * 10^3, 2.45 * 2^14 = 4 * 10^4 and 2.45 * 2^-20.  The absolute
     bound scales with the value range (it is stated for values of magnitude 0.5 * N(0,1)); the
     relative bound is unchanged, except below 2^-14 where half precision is subnormal and the
-    header promises an absolute error below 2^-24 per element instead."""
+    header promises an absolute error below 2^-24 (bf16 pools) or 2^-23 (fp8 pools) per element instead."""
     wl = make_workload(shape)
     mult = 2.0 ** log2_mult
     wl.profile = sw.ValueProfile(v_mult=mult)
@@ -147,8 +147,8 @@ def test_v_magnitudes_inside_the_half_precision_range(shape, log2_mult, launch):
     tol_abs, tol_rel = TOL[wl.kv_dtype]
     if log2_mult >= 0:
         assert rep["max_abs"] <= tol_abs * mult and rep["rel_l2"] <= tol_rel, rep
-    else:
-        assert rep["max_abs"] <= 2.0 ** -24, rep
+    else:   # bf16: stored toward zero in half precision; fp8: code * scale formed in two half-precision steps
+        assert rep["max_abs"] <= (2.0 ** -24 if wl.kv_dtype == "bf16" else 2.0 ** -23), rep
     assert np.max(np.abs(got[1] - ref[1])) <= tol_abs
 
 
