@@ -624,8 +624,10 @@ __global__ __launch_bounds__(256, NT == 1 ? 2 : 1) void spex_suffix_attn_kernel(
 // Block step of the cooperative kernel.  Same contraction as block_math, tuned for many row
 // tiles per wavefront, where the vector ALU work of the softmax -- not the matrix cores -- sets
 // the pace:
-//  * P is rounded once to fp16 (11 significant bits; round to nearest) and V^T arrives as fp16
-//    operand images, so PV is one MFMA per tile instead of a hi and a lo one;
+//  * P is rounded once to fp16 (11 significant bits; toward zero, one instruction per pair: the
+//    row sum is taken from the same rounded weights, so the mean shortfall cancels in o / l and
+//    what remains has the spread of round-to-nearest) and V^T arrives as fp16 operand images, so
+//    PV is one MFMA per tile instead of a hi and a lo one;
 //  * the row sums come from one more MFMA against a tile of ones, which also adds up the four
 //    lane groups and uses the same rounded weights as the numerator;
 //  * with a page-independent scale (bf16 KV) the running maximum is kept on the raw scores and
@@ -681,7 +683,7 @@ __device__ __forceinline__ void block_math_f16(const bf16x8 (&qf)[NT][D / 32], c
     u32x4 pw;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pr[2 * i], pr[2 * i + 1]}, f16x2));
+      pw[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(pr[2 * i], pr[2 * i + 1]));
     const f16x8 ph = __builtin_bit_cast(f16x8, pw);
     lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, ph, lacc[nt], 0, 0, 0);
 #pragma unroll
@@ -1022,7 +1024,7 @@ __device__ __forceinline__ void walk_softmax_pv(const int (&limit)[NT], const in
     u32x4 pw;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{pr[2 * i], pr[2 * i + 1]}, f16x2));
+      pw[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(pr[2 * i], pr[2 * i + 1]));
     const f16x8 ph = __builtin_bit_cast(f16x8, pw);
     lacc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, ph, lacc[nt], 0, 0, 0);
 #pragma unroll
