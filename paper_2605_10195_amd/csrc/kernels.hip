@@ -1193,8 +1193,20 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
     }
   }
 
+  // The two phases run in either order (the online softmax does not care).  The shared phase is
+  // bound by the matrix cores and LDS, the private phase by memory; workgroups that start together
+  // would all be in the same phase at the same time, so every other workgroup -- by its place on
+  // the XCD (workgroup n runs on XCD n % 8) and by its round of 256 -- takes its private blocks
+  // first: the loop below then runs twice, one phase per turn.  Only with one row tile per
+  // wavefront; with more, the compiler does not fit the second order into the registers.
+  constexpr bool kStagger = NTW <= 2 && KS == 1;
+  const bool private_first = kStagger && (((blockIdx.x >> 3) ^ (blockIdx.x >> 8)) & 1) != 0;
+#pragma nounroll
+  for (int ph = 0; ph < (kStagger ? 2 : 1); ++ph) {
+  const bool run_shared = !kStagger || (ph == 0) != private_first;
+  const bool run_private = !kStagger || (ph == 0) == private_first;
   // ---- phase 1: blocks shared by several wavefronts, through LDS
-  if (n_shared > 0) {
+  if (run_shared && n_shared > 0) {
     struct Raw {
       u32x4 r[PER];
       float vs;
@@ -1328,7 +1340,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
   }
 
   // ---- phase 2: blocks of this wavefront alone, straight into registers
-  if (has_rows && n_priv > 0) {
+  if (run_private && has_rows && n_priv > 0) {
     constexpr int NK = FP8 ? D / 64 : D / 32;  // 128-bit loads per K half-tile
     constexpr int NV = FP8 ? D / 32 : D / 16;
     auto issue_k = [&](u32x4 (&kr)[2][NK], const WalkBlock &bm) {
@@ -1406,6 +1418,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
       step(kr, vr, cur, cur, false);
     }
   }
+  }  // phases
 
   // ---- KS = 2: the upper pair hands its state to the lower pair, which folds it into its own
   // (log-sum-exp rule on the two references).  The LDS images are dead after the last barrier of
