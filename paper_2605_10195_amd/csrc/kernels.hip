@@ -1195,12 +1195,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && NTW <= 2) ? 2 : 1) void spex_t
 
   // The two phases run in either order (the online softmax does not care).  The shared phase is
   // bound by the matrix cores and LDS, the private phase by memory; workgroups that start together
-  // would all be in the same phase at the same time, so every other workgroup -- by its place on
-  // the XCD (workgroup n runs on XCD n % 8) and by its round of 256 -- takes its private blocks
-  // first: the loop below then runs twice, one phase per turn.  Only with one row tile per
-  // wavefront; with more, the compiler does not fit the second order into the registers.
+  // would all be in the same phase at the same time, so every other pair of workgroups of an XCD
+  // (workgroup n runs on XCD n % 8; the pair n, n + 8 are row blocks of one root and kv head when
+  // a root has several, and stay in step so that one finds the other's shared blocks in L2),
+  // alternating again with every round of 256, takes its private blocks first: the loop below
+  // then runs twice, one phase per turn.  Not with four row tiles per wavefront (registers).
   constexpr bool kStagger = NTW <= 2 && KS == 1;
-  const bool private_first = kStagger && (((blockIdx.x >> 3) ^ (blockIdx.x >> 8)) & 1) != 0;
+  const bool private_first = kStagger && (((blockIdx.x >> 4) ^ (blockIdx.x >> 8)) & 1) != 0;
 #pragma nounroll
   for (int ph = 0; ph < (kStagger ? 2 : 1); ++ph) {
   const bool run_shared = !kStagger || (ph == 0) != private_first;
