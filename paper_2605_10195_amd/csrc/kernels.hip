@@ -1,5 +1,14 @@
 // HIP kernels for tree decode attention on gfx950 (CDNA4, 64-lane wavefronts).
 //
+//   spex_tree_walk_kernel  (the default path)
+//       One workgroup per (row block, kv head) carries up to 16 * NTW * NW query rows from the root
+//       to their requested nodes in one launch: blocks whose rows span several wavefronts are
+//       fetched once per workgroup and staged in LDS as MFMA operand images, blocks of one
+//       wavefront stream straight into its operand registers, and the online-softmax state stays
+//       in registers until the finished rows are written -- no partial results, no merge.
+//   spex_prefix_coop_kernel
+//       The shared-prefix step of the split path for nodes with many stacked rows: one workgroup
+//       per (task, kv head, span of rows), operand images in LDS as in the tree-walk kernel.
 //   spex_prefix_attn_kernel / spex_suffix_attn_kernel
 //       One wavefront per work item = (task, kv head, row tile).  A task is a run of KV pages
 //       (a chunk of a shared-prefix group or of a private suffix) and a set of query rows; the
@@ -12,8 +21,11 @@
 //       Same contract without matrix cores, for fp32 KV and shapes the MFMA kernels do not cover.
 //   spex_lse_merge_kernel
 //       Combines the partial states of every query row (log-sum-exp rule) and normalises.
-//   spex_scatter_kv_kernel / spex_gather_kv_kernel
-//       Write appended tokens into / read tokens out of the paged pool.
+//   spex_scatter_kv_kernel / spex_scatter_quant_kernel / spex_append_tokens_kernel / spex_gather_kv_kernel
+//       Write appended tokens into (a run for one node, the same quantised to e4m3 on the way, one
+//       token for each of many nodes) / read tokens out of the paged pool.
+//   spex_patch_plan_kernel
+//       Applies {index, value} patches to the device copy of the cached launch lists.
 #include "kernels.hpp"
 
 #include <climits>

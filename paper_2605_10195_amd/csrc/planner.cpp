@@ -549,15 +549,18 @@ void Planner::ensure_walk(const PageTable &pt, Plan *plan) {
     pl.req_pages[i] = static_cast<int32_t>(pt.node(pl.req_leaves[i]).pages.size());
   bool room_overflow = false;
   const int32_t C = 16 * ntw;
-  // Measured on MI355X, two workgroups of 4 wavefronts per compute unit beat one of 8 on every
-  // workload tried (the barrier of the shared phase then stalls only half of the unit), so 4 is
-  // the default even for roots with more rows than one 4-wavefront row block takes.
+  // Measured on MI355X, two workgroups of 4 wavefronts per compute unit beat one of 8 wherever a
+  // root's rows fit one 4-wavefront row block (the barrier of the shared phase then stalls only
+  // half of the unit), so 4 is the default.
   int32_t NW = walk_waves == 0 ? 4 : walk_waves;
   if (walk_waves == 0 && plan->req_masks.empty() && ntw <= 2 && max_rows <= C) {
     // Eight wavefronts: a root whose rows overflow one row block of four wavefronts gets row blocks
-    // twice as large, so its shared pages are fetched by half as many workgroups (config 4: once
-    // instead of twice -- measured 1.04 instead of 1.17 times the unique bytes, for 1.5 % more
-    // time).  Only when no request is cut into pieces and at least 1024 such workgroups remain.
+    // twice as large, so its shared pages are fetched by half as many workgroups (256 queries of
+    // 32 branches and 8 rows each: once instead of twice, 1.04 instead of 1.16 times the unique
+    // bytes), and since workgroups alternate in which kind of block they take first, the two
+    // halves of such a root need not be in the same phase at the same time to share its prompt
+    // in L2 (1.91 against 2.09 ms).  Only when no request is cut into pieces and at least 1024
+    // such workgroups remain.
     bool wide = false;
     int64_t n8 = 0;
     for (int64_t r : root_rows) {
